@@ -1,0 +1,222 @@
+"""ctypes wrapper around the fp64 CPU oracle (test infrastructure).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import
+this.  It never imports the HIP package.  The C source beside this file is
+compiled with gcc on first use if no built library is present.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mosaic_oracle.c")
+_LIB = os.path.join(_HERE, "libmosaic_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, strict IEEE: no fast-math, no FMA
+    contraction) and return the library path."""
+    if force or not os.path.exists(_LIB) or \
+            os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+class _Decision(C.Structure):
+    _fields_ = [("winner", C.c_int), ("runner_up", C.c_int),
+                ("gap", C.c_double), ("sim", C.c_double)]
+
+
+@dataclass
+class Decision:
+    winner: int
+    runner_up: int
+    gap: float
+    sim: float
+
+
+_lib = None
+_dp = C.POINTER(C.c_double)
+_ip = C.POINTER(C.c_int)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        L.orc_unit_new.restype = C.c_void_p
+        L.orc_unit_new.argtypes = [C.c_int] * 8
+        L.orc_unit_free.argtypes = [C.c_void_p]
+        L.orc_unit_reset.argtypes = [C.c_void_p]
+        L.orc_summary.argtypes = [_dp, C.c_int, C.c_int, _dp]
+        L.orc_unit_peek.argtypes = [C.c_void_p, _dp, C.POINTER(_Decision)]
+        L.orc_unit_ingest.restype = C.c_int
+        L.orc_unit_ingest.argtypes = [C.c_void_p, _dp, C.c_int, C.POINTER(_Decision)]
+        L.orc_mean_query.argtypes = [_dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _dp]
+        L.orc_unit_score.argtypes = [C.c_void_p, _dp, _dp]
+        L.orc_select.restype = C.c_int
+        L.orc_select.argtypes = [_dp, _ip, C.c_int, C.c_int, _ip, _dp]
+        L.orc_unit_gather.restype = C.c_int
+        L.orc_unit_gather.argtypes = [C.c_void_p, _ip, C.c_int, _ip]
+        L.orc_attend.argtypes = [_dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                 _dp, _dp, _ip, C.c_int, _dp, _dp]
+        for name, rt in (("orc_unit_n_frames", C.c_int), ("orc_unit_ready", C.c_int),
+                         ("orc_unit_n_lloyd_runs", C.c_int),
+                         ("orc_unit_lloyd_min_gap", C.c_double),
+                         ("orc_unit_centroids", _dp), ("orc_unit_sizes", _ip),
+                         ("orc_unit_assign", _ip), ("orc_unit_summaries", _dp)):
+            fn = getattr(L, name)
+            fn.restype = rt
+            fn.argtypes = [C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _d(a: np.ndarray):
+    assert a.dtype == np.float64 and a.flags.c_contiguous
+    return a.ctypes.data_as(_dp)
+
+
+def _i(a: np.ndarray):
+    assert a.dtype == np.int32 and a.flags.c_contiguous
+    return a.ctypes.data_as(_ip)
+
+
+def f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def summary(k_frame: np.ndarray) -> np.ndarray:
+    k_frame = f64(k_frame)
+    T, D = k_frame.shape
+    s = np.empty(D, dtype=np.float64)
+    lib().orc_summary(_d(k_frame), T, D, _d(s))
+    return s
+
+
+def mean_query(q: np.ndarray, h: int, G: int) -> np.ndarray:
+    q = f64(q)
+    Tq, Hq, D = q.shape
+    out = np.empty(D, dtype=np.float64)
+    lib().orc_mean_query(_d(q), Tq, Hq, D, h, G, _d(out))
+    return out
+
+
+def select(score: np.ndarray, sizes: np.ndarray, k: int):
+    """-> (ids kept, relative gap between last kept and first dropped)."""
+    score = f64(score)
+    sizes = np.ascontiguousarray(sizes, dtype=np.int32)
+    Cn = score.shape[0]
+    ids = np.empty(max(k, 1), dtype=np.int32)
+    gap = C.c_double()
+    m = lib().orc_select(_d(score), _i(sizes), Cn, k, _i(ids), C.byref(gap))
+    return ids[:m].copy(), gap.value
+
+
+def attend(q: np.ndarray, K: np.ndarray, V: np.ndarray, tok_idx: np.ndarray,
+           h: int, G: int):
+    """q [Tq][Hq][D], K/V [N][D] -> (out [Tq][G][D], lse [Tq][G])."""
+    q, K, V = f64(q), f64(K), f64(V)
+    tok_idx = np.ascontiguousarray(tok_idx, dtype=np.int32)
+    Tq, Hq, D = q.shape
+    out = np.empty((Tq, G, D), dtype=np.float64)
+    lse = np.empty((Tq, G), dtype=np.float64)
+    lib().orc_attend(_d(q), Tq, Hq, D, h, G, _d(K), _d(V), _i(tok_idx),
+                     int(tok_idx.shape[0]), _d(out), _d(lse))
+    return out, lse
+
+
+class OracleUnit:
+    """Clustering state of one (layer, KV head)."""
+
+    def __init__(self, n_clusters: int, head_dim: int, tokens_per_frame: int,
+                 max_frames: int, warmup_frames: int = 0, lloyd_iters: int = 8,
+                 recluster_every: int = 0, score_mode: int = 0):
+        self.C, self.D, self.T = n_clusters, head_dim, tokens_per_frame
+        self.max_frames = max_frames
+        self._L = lib()
+        self._u = self._L.orc_unit_new(n_clusters, head_dim, tokens_per_frame,
+                                       max_frames, warmup_frames, lloyd_iters,
+                                       recluster_every, score_mode)
+
+    def __del__(self):
+        if getattr(self, "_u", None):
+            self._L.orc_unit_free(self._u)
+            self._u = None
+
+    def reset(self):
+        self._L.orc_unit_reset(self._u)
+
+    def peek(self, k_frame: np.ndarray) -> Decision:
+        k_frame = f64(k_frame)
+        d = _Decision()
+        self._L.orc_unit_peek(self._u, _d(k_frame), C.byref(d))
+        return Decision(d.winner, d.runner_up, d.gap, d.sim)
+
+    def ingest(self, k_frame: np.ndarray, force: int = -1) -> Decision:
+        k_frame = f64(k_frame)
+        assert k_frame.shape == (self.T, self.D)
+        d = _Decision()
+        rc = self._L.orc_unit_ingest(self._u, _d(k_frame), force, C.byref(d))
+        if rc != 0:
+            raise RuntimeError("oracle unit is full")
+        return Decision(d.winner, d.runner_up, d.gap, d.sim)
+
+    @property
+    def n_frames(self) -> int:
+        return self._L.orc_unit_n_frames(self._u)
+
+    @property
+    def ready(self) -> bool:
+        return bool(self._L.orc_unit_ready(self._u))
+
+    @property
+    def n_lloyd_runs(self) -> int:
+        return self._L.orc_unit_n_lloyd_runs(self._u)
+
+    @property
+    def lloyd_min_gap(self) -> float:
+        return self._L.orc_unit_lloyd_min_gap(self._u)
+
+    def centroids(self) -> np.ndarray:
+        p = self._L.orc_unit_centroids(self._u)
+        return np.ctypeslib.as_array(p, shape=(self.C, self.D)).copy()
+
+    def sizes(self) -> np.ndarray:
+        p = self._L.orc_unit_sizes(self._u)
+        return np.ctypeslib.as_array(p, shape=(self.C,)).copy()
+
+    def assignments(self) -> np.ndarray:
+        p = self._L.orc_unit_assign(self._u)
+        return np.ctypeslib.as_array(p, shape=(self.max_frames,))[: self.n_frames].copy()
+
+    def summaries(self) -> np.ndarray:
+        p = self._L.orc_unit_summaries(self._u)
+        return np.ctypeslib.as_array(p, shape=(self.max_frames, self.D))[: self.n_frames].copy()
+
+    def score(self, qbar: np.ndarray) -> np.ndarray:
+        qbar = f64(qbar)
+        out = np.empty(self.C, dtype=np.float64)
+        self._L.orc_unit_score(self._u, _d(qbar), _d(out))
+        return out
+
+    def gather(self, ids: np.ndarray) -> np.ndarray:
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        out = np.empty(max(self.n_frames * self.T, 1), dtype=np.int32)
+        m = self._L.orc_unit_gather(self._u, _i(ids), int(ids.shape[0]), _i(out))
+        return out[:m].copy()
+
+    # -- the whole query side for this unit --------------------------------
+    def retrieve(self, q: np.ndarray, h: int, G: int, top_k: int):
+        """q [Tq][Hq][D] -> (ids, scores, tok_idx, gap_k)."""
+        qbar = mean_query(q, h, G)
+        sc = self.score(qbar)
+        ids, gap = select(sc, self.sizes(), top_k)
+        return ids, sc, self.gather(ids), gap

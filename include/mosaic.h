@@ -1,0 +1,174 @@
+/*
+ * libmosaic -- cluster-driven KV-cache management for streaming long-video
+ * VLM inference on one MI355X (gfx950): C ABI.
+ *
+ * The calls mirror the two-stage workflow of the paper's problem statement
+ * (Sec. V-A "Setup"): Frame Encoding = mosaic_ingest_frame (update the
+ * layer-wise KV cache and its cluster structure as frames arrive), Query
+ * Retrieval = mosaic_retrieve + mosaic_attend (select the relevant clusters
+ * and run attention over them only).
+ *
+ * Vocabulary.  L layers, Hq query heads, Hkv KV heads, G = Hq/Hkv, D head_dim,
+ * T tokens per frame, C clusters, k = top_k.  A "unit" is one (layer, KV head)
+ * pair, index u = layer*Hkv + head; units never interact.  The thing that is
+ * clustered is the frame: its state is the mean of its T key vectors, and all
+ * T tokens (keys and values) follow the frame into its cluster.
+ *
+ * Conventions.
+ *  - Every function returns a mosaic_status; nothing throws or aborts across
+ *    the boundary.  mosaic_last_error() gives the text of the last failure.
+ *  - "device pointer" = HIP device memory of the GPU current at mosaic_create;
+ *    "host pointer" = ordinary host memory.  Stated per argument.
+ *  - All device work is enqueued on config.stream (a hipStream_t passed as
+ *    void*).  ingest / retrieve / attend / reset do not synchronise; the
+ *    mosaic_get_* observers do (they copy to host memory).
+ *  - The library allocates no device memory: the caller provides one arena
+ *    (size from mosaic_workspace_size) which is borrowed until
+ *    mosaic_destroy.  Input buffers passed to a call must stay valid until
+ *    the stream has passed that call.
+ *  - A handle is not thread-safe; distinct handles are independent.
+ *  - Decision arithmetic (frame summaries, cosine similarities, representative
+ *    updates, query scores, top-k) is fp64 on the device; attention
+ *    accumulates in fp32.
+ */
+#ifndef MOSAIC_H
+#define MOSAIC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mosaic_ctx mosaic_ctx; /* one per video stream */
+
+typedef enum {
+    MOSAIC_OK = 0,
+    MOSAIC_EINVAL = -1,    /* bad argument or unsupported shape */
+    MOSAIC_ENOMEM = -2,    /* arena too small */
+    MOSAIC_ECAPACITY = -3, /* more than max_frames frames, or an output buffer too small */
+    MOSAIC_ENOTREADY = -4, /* retrieve before the initial clustering, or attend before retrieve */
+    MOSAIC_EHIP = -5       /* a HIP call failed (text in mosaic_last_error) */
+} mosaic_status;
+
+enum { MOSAIC_FP32 = 0, MOSAIC_BF16 = 1 };
+enum { MOSAIC_ATTEND_AUTO = 0, /* bf16 -> MFMA kernel, fp32 -> vector-ALU kernel */
+       MOSAIC_ATTEND_VALU = 1, /* vector-ALU kernel for either dtype */
+       MOSAIC_ATTEND_MFMA = 2  /* MFMA kernel (bf16 only) */ };
+
+typedef struct {
+    int32_t n_layers, n_q_heads, n_kv_heads;
+    int32_t head_dim;         /* 64 or 128 */
+    int32_t tokens_per_frame; /* T >= 1 */
+    int32_t max_frames;       /* capacity of the stream */
+    int32_t n_clusters;       /* C, 1..1024, fixed */
+    int32_t top_k;            /* 1..C */
+    int32_t kv_dtype;         /* MOSAIC_FP32 | MOSAIC_BF16: dtype of K, V, q and the attention output */
+    int32_t warmup_frames;    /* W; 0 -> 2*C.  The first W frames are buffered, then the initial clustering runs */
+    int32_t lloyd_iters;      /* rounds of the cosine K-means used at init and re-clustering; 0 -> 8 */
+    int32_t recluster_every;  /* 0 = never; else a warm-started full re-clustering whenever the frame
+                                 count reaches a multiple of it beyond the warm-up */
+    int32_t score_mode;       /* 0 cosine (paper Sec. V-B criterion), 1 plain dot product */
+    int32_t max_q_tokens;     /* largest n_q_tokens retrieve/attend will be given; 0 -> 256 */
+    int32_t attend_impl;      /* MOSAIC_ATTEND_* */
+    int32_t reserved0;
+    void *dev_arena;          /* device pointer, 256-byte aligned, borrowed */
+    size_t dev_arena_bytes;
+    void *stream;             /* hipStream_t, borrowed; NULL = the null stream */
+} mosaic_config;
+
+typedef struct {
+    int64_t frames_ingested;
+    int64_t lloyd_runs;        /* initial clustering + re-clusterings */
+    int64_t retrieve_calls, attend_calls;
+    int64_t kv_bytes_stored;   /* K+V bytes written into the arena so far */
+    int32_t ready;             /* 1 once the initial clustering has run */
+    int32_t attend_impl;       /* the kernel family in use (MOSAIC_ATTEND_VALU or _MFMA) */
+    int32_t last_n_splits;     /* KV splits used by the latest attend */
+    int32_t reserved;
+} mosaic_stats;
+
+/* Bytes of device arena a context with this configuration needs (dev_arena
+ * fields of cfg are ignored).  dev_bytes: host pointer. */
+int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes);
+
+/* Validate cfg, carve the arena, enqueue nothing.  out: host pointer. */
+int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out);
+int32_t mosaic_destroy(mosaic_ctx *ctx);
+
+/* Forget all frames and clusters; keep the arena and configuration. */
+int32_t mosaic_reset(mosaic_ctx *ctx);
+
+/* Frame Encoding (Sec. V-A (1); Sec. VI-A greedy assignment and Eq. 3; Sec. VII-A
+ * batched matching when n_frames > 1).
+ * k_dev, v_dev: device pointers, [n_frames][L][Hkv][T][D] in kv_dtype, the
+ * keys and values of the next n_frames frames in stream order.  For every
+ * frame and unit: the K and V pages are copied into the arena, the frame's
+ * key summary is formed, and -- once W frames are in -- the frame is assigned
+ * to the non-empty cluster with the most similar representative (cosine; ties
+ * to the lowest id) whose representative is then updated by Eq. 3.  The result
+ * is identical to n_frames calls with one frame each.
+ * Errors: EINVAL (NULL, n_frames < 1), ECAPACITY (max_frames exceeded; nothing
+ * is ingested). */
+int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_dev,
+                            int32_t n_frames);
+
+/* Query Retrieval, selection part (Sec. V-C "Cluster Indexing" / second stage
+ * of "Two-Stage Retrieval"; top-K of Sec. VII-B).
+ * layer >= 0: that layer only, q_dev is [Tq][Hq][D]; layer == -1: all layers,
+ * q_dev is [L][Tq][Hq][D].  q_dev: device pointer, kv_dtype.
+ * Per unit: mean query over the Tq tokens and the unit's G query heads;
+ * score_j = (mean query . r_j)/|r_j| for non-empty clusters; the top_k best by
+ * (score descending, id ascending); then the page list of those clusters
+ * (clusters in selection order, member frames ascending).  The selection stays
+ * in the context until the next retrieve for that layer or the next ingest.
+ * Errors: ENOTREADY before W frames are in; EINVAL (layer, n_q_tokens out of
+ * range, NULL). */
+int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
+                        int32_t n_q_tokens);
+
+/* Query Retrieval, attention part (Sec. V-A (2)): softmax(q K^T/sqrt(D)) V over
+ * the tokens of the clusters chosen by the latest mosaic_retrieve for `layer`
+ * (same `layer` convention), query head hq reading KV head hq / G, no mask.
+ * q_dev as in mosaic_retrieve; out_dev [.][Tq][Hq][D] in kv_dtype and lse_dev
+ * [.][Tq][Hq] fp32 (natural-log sum of exponentials of the scaled logits; may
+ * be NULL) are device pointers.
+ * Errors: ENOTREADY if no selection is current for the layer; EINVAL. */
+int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
+                      int32_t n_q_tokens, void *out_dev, float *lse_dev);
+
+/* Observers for parity checks.  All outputs are HOST pointers, caller-allocated;
+ * each call synchronises the stream.  NULL outputs are skipped. */
+
+/* frame_to_cluster [L*Hkv][n_frames_ingested] (row stride = frames ingested);
+ * -1 for frames still buffered before the initial clustering. */
+int32_t mosaic_get_assignments(mosaic_ctx *ctx, int32_t *frame_to_cluster);
+/* r [L*Hkv][C][D] fp64 representatives, n [L*Hkv][C] cluster sizes in frames. */
+int32_t mosaic_get_centroids(mosaic_ctx *ctx, double *r, int32_t *n);
+/* summaries [L*Hkv][n_frames_ingested][D] fp64 per-frame key summaries. */
+int32_t mosaic_get_summaries(mosaic_ctx *ctx, double *summaries);
+/* Latest selection of one layer (layer >= 0): ids [Hkv][top_k] (-1 padded),
+ * n_ids [Hkv], scores [Hkv][C] fp64 (-inf for empty clusters), tok_idx
+ * [Hkv][tok_cap] global token indices f*T+t in gather order, n_tok [Hkv].
+ * ECAPACITY if a unit retrieved more than tok_cap tokens. */
+int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32_t *n_ids,
+                             double *scores, int32_t *tok_idx, int64_t tok_cap,
+                             int32_t *n_tok);
+int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats);
+
+/* Kernel timing for benchmarks: when enabled, the split-KV attention kernel of
+ * every mosaic_attend is bracketed by HIP events on the context's stream.
+ * mosaic_profile_read synchronises and returns the summed kernel time and the
+ * number of launches since the last read (host pointers), then clears them. */
+int32_t mosaic_profile_enable(mosaic_ctx *ctx, int32_t on);
+int32_t mosaic_profile_read(mosaic_ctx *ctx, double *attend_kernel_ms, int64_t *launches);
+
+/* Text of the last error on this handle (never NULL).  ctx may be NULL: then
+ * the text of the last failed mosaic_create / mosaic_workspace_size. */
+const char *mosaic_last_error(const mosaic_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOSAIC_H */

@@ -1,0 +1,208 @@
+// Attention over the retrieved KV (paper Sec. V-A (2)): vector-ALU split-KV
+// kernel (fp32 or bf16 pages, values stored [T][D]) and the combine kernel that
+// merges the per-split partials of either kernel family.
+//
+// Work decomposition shared by both families:
+//   rows     the unit's G*Tq query rows, row r = t*G + g, in tiles of 16
+//   chunks   32 tokens inside one page; a unit has n_sel * ceil(T/32) chunks
+//   splits   contiguous chunk ranges; one workgroup per (split, row tile, unit)
+// Each workgroup keeps an online softmax in the log2 domain (logits are
+// multiplied by log2(e)/sqrt(D) once) and writes (max, sum, unnormalised O).
+#include "mosaic_internal.h"
+
+namespace mosaic {
+
+namespace {
+
+template <typename E> __device__ __forceinline__ float to_f32(E v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<unsigned short>(unsigned short v) {
+    return bf16_to_f32(v);
+}
+template <typename E> __device__ __forceinline__ void load8f(const E *p, float (&v)[8]);
+template <> __device__ __forceinline__ void load8f<float>(const float *p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <> __device__ __forceinline__ void load8f<unsigned short>(const unsigned short *p,
+                                                                   float (&v)[8]) {
+    const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    const unsigned int w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+template <typename E> __device__ __forceinline__ void store_out(E *p, float v);
+template <> __device__ __forceinline__ void store_out<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_out<unsigned short>(unsigned short *p, float v) {
+    *p = f32_to_bf16_rne(v);
+}
+
+__device__ __forceinline__ float group16_max(float x) {
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 16));
+    return x;
+}
+__device__ __forceinline__ float group16_sumf(float x) {
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) x += __shfl_xor(x, o, 16);
+    return x;
+}
+
+// grid (n_splits, NT, n_units), 256 threads: thread (row = tid/16, tl = tid%16)
+template <typename E, int D>
+__global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, const E *q, int Tq,
+                                                        int n_splits) {
+    constexpr int DPT = D / 16;   // output channels per thread
+    constexpr int CG = D / 8;     // 8-element groups per token row
+    const int split = blockIdx.x, tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc;
+    const int NT = gridDim.y, tid = threadIdx.x, row = tid / 16, tl = tid % 16;
+    const int G = dv.G, Hq = dv.Hq, T = dv.T;
+    const int lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
+    __shared__ float q_sh[kRowTile][D];
+    __shared__ float k_sh[kChunk][D + 1];
+    __shared__ float v_sh[kChunk][D];
+    __shared__ float p_sh[kRowTile][kChunk];
+
+    const float sl2 = 1.4426950408889634f / sqrtf((float)D);
+    for (int idx = tid; idx < kRowTile * D; idx += kBlock) {
+        const int rr = idx / D, d = idx % D, gr = tile * kRowTile + rr;
+        float v = 0.f;
+        if (gr < R) {
+            const int t = gr / G, g = gr % G;
+            v = to_f32<E>(q[(((size_t)lc * Tq + t) * Hq + (size_t)h * G + g) * D + d]) * sl2;
+        }
+        q_sh[rr][d] = v;
+    }
+    const int cpp = dv.chunks_per_page;
+    const int NC = dv.n_sel[u] * cpp;
+    const int cps = (NC + n_splits - 1) / n_splits;
+    const int c0 = split * cps, c1 = min(NC, c0 + cps);
+    const int *sel = dv.sel_pages + (size_t)u * dv.F;
+
+    float m = -INFINITY, l = 0.f, acc[DPT];
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) acc[i] = 0.f;
+    __syncthreads();
+
+    for (int c = c0; c < c1; ++c) {
+        const int page = sel[c / cpp], t0 = (c % cpp) * kChunk, nt = min(kChunk, T - t0);
+        const E *kp = reinterpret_cast<const E *>(dv.k_store) + (((size_t)u * dv.F + page) * T + t0) * D;
+        const E *vp = reinterpret_cast<const E *>(dv.v_store) + (((size_t)u * dv.F + page) * T + t0) * D;
+        for (int item = tid; item < kChunk * CG; item += kBlock) {
+            const int tok = item / CG, cg = item % CG;
+            float kv[8], vv[8];
+            if (tok < nt) {
+                load8f<E>(kp + (size_t)tok * D + cg * 8, kv);
+                load8f<E>(vp + (size_t)tok * D + cg * 8, vv);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { kv[i] = 0.f; vv[i] = 0.f; }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { k_sh[tok][cg * 8 + i] = kv[i]; v_sh[tok][cg * 8 + i] = vv[i]; }
+        }
+        __syncthreads();
+        float s0 = 0.f, s1 = 0.f;
+        for (int d = 0; d < D; ++d) {
+            const float qv = q_sh[row][d];
+            s0 += qv * k_sh[tl][d];
+            s1 += qv * k_sh[tl + 16][d];
+        }
+        if (tl >= nt) s0 = -INFINITY;
+        if (tl + 16 >= nt) s1 = -INFINITY;
+        const float mnew = fmaxf(m, group16_max(fmaxf(s0, s1)));
+        const float alpha = exp2f(m - mnew);
+        const float p0 = exp2f(s0 - mnew), p1 = exp2f(s1 - mnew);
+        l = l * alpha + group16_sumf(p0 + p1);
+        m = mnew;
+        p_sh[row][tl] = p0;
+        p_sh[row][tl + 16] = p1;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < DPT; ++i) acc[i] *= alpha;
+        for (int t = 0; t < kChunk; ++t) {
+            const float p = p_sh[row][t];
+#pragma unroll
+            for (int i = 0; i < DPT; ++i) acc[i] += p * v_sh[t][tl + 16 * i];
+        }
+        __syncthreads();
+    }
+    const size_t entry = ((size_t)uc * NT + tile) * n_splits + split;
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) dv.part_o[(entry * kRowTile + row) * D + tl + 16 * i] = acc[i];
+    if (tl == 0) {
+        dv.part_ml[entry * 2 * kRowTile + row] = m;
+        dv.part_ml[entry * 2 * kRowTile + kRowTile + row] = l;
+    }
+}
+
+// grid (NT, n_units), 256 threads: thread (row = tid/16, dl = tid%16)
+template <typename E, int D>
+__global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0, int Tq,
+                                                           int n_splits, E *out, float *lse) {
+    constexpr int DPT = D / 16;
+    const int tile = blockIdx.x, uc = blockIdx.y, u = u0 + uc, NT = gridDim.x;
+    const int tid = threadIdx.x, row = tid / 16, dl = tid % 16;
+    const int G = dv.G, Hq = dv.Hq, lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
+    const int gr = tile * kRowTile + row;
+    if (gr >= R) return;
+    const size_t e0 = ((size_t)uc * NT + tile) * n_splits;
+    float M = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, dv.part_ml[(e0 + s) * 2 * kRowTile + row]);
+    float L = 0.f, o[DPT];
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) o[i] = 0.f;
+    if (M > -INFINITY) {
+        for (int s = 0; s < n_splits; ++s) {
+            const float w = exp2f(dv.part_ml[(e0 + s) * 2 * kRowTile + row] - M);
+            L += w * dv.part_ml[(e0 + s) * 2 * kRowTile + kRowTile + row];
+#pragma unroll
+            for (int i = 0; i < DPT; ++i)
+                o[i] += w * dv.part_o[((e0 + s) * kRowTile + row) * D + dl + 16 * i];
+        }
+    }
+    const int t = gr / G, g = gr % G;
+    const size_t orow = ((size_t)lc * Tq + t) * Hq + (size_t)h * G + g;
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) store_out<E>(out + orow * D + dl + 16 * i, o[i] * inv);
+    if (dl == 0 && lse != nullptr)
+        lse[orow] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+}
+
+} // namespace
+
+hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
+                              int n_splits, hipStream_t s) {
+    const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
+    dim3 grid(n_splits, NT, n_units);
+    if (dv.esize == 4) {
+        if (dv.D == 64) k_attend_valu<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_splits);
+        else k_attend_valu<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_splits);
+    } else {
+        if (dv.D == 64) k_attend_valu<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_splits);
+        else k_attend_valu<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_splits);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
+                                 void *out, float *lse, hipStream_t s) {
+    const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
+    dim3 grid(NT, n_units);
+    if (dv.esize == 4) {
+        if (dv.D == 64) k_attend_combine<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (float *)out, lse);
+        else k_attend_combine<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (float *)out, lse);
+    } else {
+        if (dv.D == 64) k_attend_combine<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (unsigned short *)out, lse);
+        else k_attend_combine<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (unsigned short *)out, lse);
+    }
+    return hipGetLastError();
+}
+
+} // namespace mosaic

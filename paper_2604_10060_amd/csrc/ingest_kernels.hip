@@ -1,0 +1,424 @@
+// Frame Encoding kernels (paper Sec. V-A (1), Sec. VI-A, Sec. V-B):
+//   k_store_summary  copy a frame's K/V pages into the arena and form the
+//                    frame's key summary (mean of its T keys) in fp64
+//   k_assign_update  greedy cosine assignment + running-mean update (Eq. 3),
+//                    sequential over the frames of a batch, one workgroup per unit
+//   k_lloyd_*        cosine K-means rounds for the initial clustering and the
+//                    periodic warm-started re-clustering
+// All decision arithmetic is fp64: on CDNA4 the fp64 vector rate equals the
+// non-packed fp32 rate, so exact-to-rounding decisions cost only table bytes.
+#include "mosaic_internal.h"
+
+namespace mosaic {
+
+namespace {
+
+template <typename E> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ void load8(const float *p, float (&v)[8]) {
+        const float4 a = *reinterpret_cast<const float4 *>(p);
+        const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    static __device__ __forceinline__ void copy8(const float *src, float *dst) {
+        *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
+        *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + 4);
+    }
+};
+template <> struct Elem<unsigned short> {
+    static __device__ __forceinline__ void load8(const unsigned short *p, float (&v)[8]) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(p);
+        const unsigned int w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void copy8(const unsigned short *src, unsigned short *dst) {
+        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+    }
+};
+
+__device__ __forceinline__ double group16_sum(double x) {
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) x += __shfl_xor(x, o, 16);
+    return x;
+}
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+// (value, id) ordered by value descending then id ascending
+__device__ __forceinline__ bool better(double v, int i, double bv, int bi) {
+    return v > bv || (v == bv && i < bi);
+}
+
+// ---------------------------------------------------------------------------
+// Page store + key summary.  grid (U, n_frames, 2): z = 0 keys, z = 1 values.
+// ---------------------------------------------------------------------------
+template <typename E, int D>
+__global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E *k_in,
+                                                          const E *v_in, int f0) {
+    constexpr int LPR = D / 8;          // lanes per row, 8 elements each
+    constexpr int RP = kBlock / LPR;    // rows per pass
+    const int u = blockIdx.x, fl = blockIdx.y, f = f0 + fl;
+    const int tid = threadIdx.x, cg = tid % LPR, r0 = tid / LPR;
+    const int T = dv.T;
+    const size_t in_page = ((size_t)fl * dv.U + u) * (size_t)T * D;
+    const size_t page = (size_t)u * dv.F + f;
+
+    if (blockIdx.z == 0) {
+        __shared__ double red[RP][D];
+        const E *src = k_in + in_page;
+        E *dst = reinterpret_cast<E *>(dv.k_store) + page * (size_t)T * D;
+        double acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+        for (int t = r0; t < T; t += RP) {
+            float v[8];
+            Elem<E>::load8(src + (size_t)t * D + cg * 8, v);
+            Elem<E>::copy8(src + (size_t)t * D + cg * 8, dst + (size_t)t * D + cg * 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] += (double)v[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) red[r0][cg * 8 + i] = acc[i];
+        __syncthreads();
+        if (tid < D) {
+            double s = 0.0;
+            for (int rr = 0; rr < RP; ++rr) s += red[rr][tid];
+            dv.summ[page * D + tid] = s / (double)T;
+        }
+        return;
+    }
+
+    const E *src = v_in + in_page;
+    if (!dv.v_transposed) {
+        E *dst = reinterpret_cast<E *>(dv.v_store) + page * (size_t)T * D;
+        for (int t = r0; t < T; t += RP)
+            Elem<E>::copy8(src + (size_t)t * D + cg * 8, dst + (size_t)t * D + cg * 8);
+        return;
+    }
+    // Transposed value page [D][Tp] (2-byte elements only): 8 consecutive
+    // tokens of one channel become one 16-byte operand of the PV contraction.
+    if constexpr (sizeof(E) == 2) {
+        constexpr int TC = 64;                       // tokens per LDS tile
+        __shared__ unsigned short tile[TC][D + 2];
+        const int Tp = dv.Tp;
+        unsigned short *dst = reinterpret_cast<unsigned short *>(dv.v_store) + page * (size_t)D * Tp;
+        for (int tc0 = 0; tc0 < Tp; tc0 += TC) {
+            for (int t = r0; t < TC; t += RP) {
+                const int tok = tc0 + t;
+                uint4 w = make_uint4(0u, 0u, 0u, 0u);
+                if (tok < T) w = *reinterpret_cast<const uint4 *>(src + (size_t)tok * D + cg * 8);
+                unsigned int *row = reinterpret_cast<unsigned int *>(&tile[t][cg * 8]);
+                row[0] = w.x; row[1] = w.y; row[2] = w.z; row[3] = w.w;
+            }
+            __syncthreads();
+            const int ntg = (min(TC, Tp - tc0)) / 8;  // token groups of 8 in this tile
+            for (int id = tid; id < D * ntg; id += kBlock) {
+                const int d = id / ntg, tg = id % ntg;
+                unsigned int w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    w[j] = (unsigned int)tile[tg * 8 + 2 * j][d] |
+                           ((unsigned int)tile[tg * 8 + 2 * j + 1][d] << 16);
+                *reinterpret_cast<uint4 *>(dst + (size_t)d * Tp + tc0 + tg * 8) =
+                    make_uint4(w[0], w[1], w[2], w[3]);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Online assignment + Eq. 3, frames f0..f1-1 in order.  grid (U), 256 threads.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0, int f1) {
+    constexpr int EPL = D / 16;  // elements per lane in a 16-lane row group
+    const int u = blockIdx.x, tid = threadIdx.x, C = dv.C;
+    const int lr = tid % 16, row0 = tid / 16, wave = tid / 64, lane = tid % 64;
+    __shared__ double s_sh[D];
+    __shared__ double dot_sh[1024];
+    __shared__ double red_v[4];
+    __shared__ int red_i[4];
+    __shared__ double snorm_sh, nsum_sh[2];
+    __shared__ int win_sh;
+    double *r = dv.r + (size_t)u * C * D;
+    double *rn = dv.rnorm + (size_t)u * C;
+    int *n = dv.n + (size_t)u * C;
+
+    for (int f = f0; f < f1; ++f) {
+        if (tid < D) s_sh[tid] = dv.summ[((size_t)u * dv.F + f) * D + tid];
+        __syncthreads();
+        if (wave == 0) {
+            double x = 0.0;
+            for (int d = lane; d < D; d += 64) x += s_sh[d] * s_sh[d];
+            x = wave_sum(x);
+            if (lane == 0) snorm_sh = sqrt(x);
+        }
+        for (int j = row0; j < C; j += 16) {
+            double p = 0.0;
+            if (n[j] > 0) {
+                const double *rj = r + (size_t)j * D + lr * EPL;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) p += s_sh[lr * EPL + i] * rj[i];
+            }
+            p = group16_sum(p);
+            if (lr == 0) dot_sh[j] = p;
+        }
+        __syncthreads();
+        // argmax of the cosine over non-empty clusters, ties to the lowest id
+        double bv = -INFINITY;
+        int bi = 0x7fffffff;
+        const double sn = snorm_sh;
+        for (int j = tid; j < C; j += kBlock) {
+            if (n[j] <= 0) continue;
+            const double den = sn * rn[j];
+            const double c = (sn == 0.0 || rn[j] == 0.0) ? 0.0 : dot_sh[j] / den;
+            if (better(c, j, bv, bi)) { bv = c; bi = j; }
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+            const double ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < 4; ++w)
+                if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
+            win_sh = bi == 0x7fffffff ? 0 : bi;
+        }
+        __syncthreads();
+        const int a = win_sh;
+        const int na_i = n[a];
+        const double na = (double)na_i;
+        double sq = 0.0;
+        if (tid < D) {
+            // Eq. 3 with each operation rounded separately (no contraction)
+            const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, r[(size_t)a * D + tid]), s_sh[tid]),
+                                        na + 1.0);
+            r[(size_t)a * D + tid] = rv;
+            sq = rv * rv;
+        }
+        if (wave < 2) {
+            sq = wave_sum(sq);
+            if (lane == 0) nsum_sh[wave] = sq;
+        }
+        __syncthreads();   // all threads have read n[a] and written r before the scalars change
+        if (tid == 0) {
+            rn[a] = sqrt(D > 64 ? nsum_sh[0] + nsum_sh[1] : nsum_sh[0]);
+            n[a] = na_i + 1;
+            dv.assign[(size_t)u * dv.F + f] = a;
+            dv.pos[(size_t)u * dv.F + f] = na_i;
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Lloyd: seeds from the warm-up buffer.  grid (U), 256 threads.
+// r_j = summary of frame floor(j*W/C); every cluster counts as non-empty for
+// the first assignment round (n_j = 1 as a placeholder).
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_lloyd_seed(DeviceView dv, int W) {
+    constexpr int EPL = D / 16;
+    const int u = blockIdx.x, tid = threadIdx.x, C = dv.C;
+    const int lr = tid % 16, row0 = tid / 16;
+    for (int j = row0; j < C; j += 16) {
+        const int src = (int)(((long long)j * W) / C);
+        const double *s = dv.summ + ((size_t)u * dv.F + src) * D + lr * EPL;
+        double *rj = dv.r + ((size_t)u * C + j) * D + lr * EPL;
+        double sq = 0.0;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) { rj[i] = s[i]; sq += s[i] * s[i]; }
+        sq = group16_sum(sq);
+        if (lr == 0) { dv.rnorm[(size_t)u * C + j] = sqrt(sq); dv.n[(size_t)u * C + j] = 1; }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Lloyd assignment round.  grid (U, ceil(F/32)), 256 threads.
+// Thread (fi = tid%32, cq = tid/32): frame ft0+fi against 4 centroids at a time.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_frames) {
+    constexpr int FT = 32, LDP = D + 2;
+    const int u = blockIdx.x, ft0 = blockIdx.y * FT, tid = threadIdx.x, C = dv.C;
+    const int fi = tid % FT, cq = tid / FT;
+    __shared__ double s_sh[FT][LDP];
+    __shared__ double bv_sh[8][FT];
+    __shared__ int bi_sh[8][FT];
+    for (int idx = tid; idx < FT * D; idx += kBlock) {
+        const int ff = idx / D, d = idx % D;
+        s_sh[ff][d] = (ft0 + ff < n_frames) ? dv.summ[((size_t)u * dv.F + ft0 + ff) * D + d] : 0.0;
+    }
+    __syncthreads();
+    double sn = 0.0;
+#pragma unroll 4
+    for (int d = 0; d < D; ++d) sn += s_sh[fi][d] * s_sh[fi][d];
+    sn = sqrt(sn);
+    const double *r = dv.r + (size_t)u * C * D;
+    const double *rn = dv.rnorm + (size_t)u * C;
+    const int *n = dv.n + (size_t)u * C;
+    double bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int jb = cq * 4; jb < C; jb += 32) {
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        const double *rj[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) rj[q] = r + (size_t)min(jb + q, C - 1) * D;
+#pragma unroll 4
+        for (int d = 0; d < D; d += 2) {
+            const double s0 = s_sh[fi][d], s1 = s_sh[fi][d + 1];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const double2 rv = *reinterpret_cast<const double2 *>(rj[q] + d);
+                acc[q] += s0 * rv.x;
+                acc[q] += s1 * rv.y;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int j = jb + q;
+            if (j < C && n[j] > 0) {
+                const double c = (sn == 0.0 || rn[j] == 0.0) ? 0.0 : acc[q] / (sn * rn[j]);
+                if (better(c, j, bv, bi)) { bv = c; bi = j; }
+            }
+        }
+    }
+    bv_sh[cq][fi] = bv;
+    bi_sh[cq][fi] = bi;
+    __syncthreads();
+    if (tid < FT && ft0 + tid < n_frames) {
+        bv = bv_sh[0][tid]; bi = bi_sh[0][tid];
+        for (int q = 1; q < 8; ++q)
+            if (better(bv_sh[q][tid], bi_sh[q][tid], bv, bi)) { bv = bv_sh[q][tid]; bi = bi_sh[q][tid]; }
+        dv.assign[(size_t)u * dv.F + ft0 + tid] = bi == 0x7fffffff ? 0 : bi;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Lloyd update round.  grid (U, C), 128 threads (thread d owns channel d).
+// Members are found by an order-preserving compaction of the assignment array
+// (2048 frames at a time) and summed in ascending frame order, so the mean is
+// the same sequence of additions a sequential loop would perform.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frames) {
+    constexpr int CH = 2048, NT = 128;
+    const int u = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, C = dv.C;
+    const int wave = tid / 64, lane = tid % 64;
+    __shared__ int mem[CH];
+    __shared__ int wcnt[2];
+    __shared__ double nsum_sh[2];
+    const int *assign = dv.assign + (size_t)u * dv.F;
+    int *pos = dv.pos + (size_t)u * dv.F;
+    double acc = 0.0;
+    int count = 0;
+    for (int c0 = 0; c0 < n_frames; c0 += CH) {
+        int filled = 0;  // members found in this chunk so far (same in every thread)
+        const int cend = min(n_frames, c0 + CH);
+        for (int b = c0; b < cend; b += NT) {
+            const int f = b + tid;
+            const bool is = f < cend && assign[f] == j;
+            const unsigned long long bal = __ballot(is);
+            const int before = __popcll(bal & ((1ull << lane) - 1ull));
+            if (lane == 0) wcnt[wave] = __popcll(bal);
+            __syncthreads();
+            const int w0 = wcnt[0], w1 = wcnt[1];
+            if (is) {
+                const int slot = filled + (wave == 1 ? w0 : 0) + before;
+                mem[slot] = f;
+                pos[f] = count + slot;
+            }
+            filled += w0 + w1;
+            __syncthreads();
+        }
+        if (tid < D)
+            for (int m = 0; m < filled; ++m)
+                acc += dv.summ[((size_t)u * dv.F + mem[m]) * D + tid];
+        count += filled;
+        __syncthreads();
+    }
+    if (count == 0) {                      // keeps its representative, skipped from now on
+        if (tid == 0) dv.n[(size_t)u * C + j] = 0;
+        return;
+    }
+    double sq = 0.0;
+    if (tid < D) {
+        const double rv = acc / (double)count;
+        dv.r[((size_t)u * C + j) * D + tid] = rv;
+        sq = rv * rv;
+    }
+    sq = wave_sum(sq);
+    if (lane == 0) nsum_sh[wave] = sq;
+    __syncthreads();
+    if (tid == 0) {
+        dv.rnorm[(size_t)u * C + j] = sqrt(nsum_sh[0] + nsum_sh[1]);
+        dv.n[(size_t)u * C + j] = count;
+    }
+}
+
+template <typename F> hipError_t checked(F &&launch) {
+    launch();
+    return hipGetLastError();
+}
+
+} // namespace
+
+hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const void *v_in, int f0,
+                                int n_frames, hipStream_t s) {
+    dim3 grid(dv.U, n_frames, 2);
+    return checked([&] {
+        if (dv.esize == 4) {
+            if (dv.D == 64) k_store_summary<float, 64><<<grid, kBlock, 0, s>>>(dv, (const float *)k_in, (const float *)v_in, f0);
+            else k_store_summary<float, 128><<<grid, kBlock, 0, s>>>(dv, (const float *)k_in, (const float *)v_in, f0);
+        } else {
+            if (dv.D == 64) k_store_summary<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f0);
+            else k_store_summary<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f0);
+        }
+    });
+}
+
+hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s) {
+    return checked([&] {
+        if (dv.D == 64) k_assign_update<64><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
+        else k_assign_update<128><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
+    });
+}
+
+hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed_from_warmup,
+                        hipStream_t s) {
+    hipError_t e = hipSuccess;
+    if (seed_from_warmup) {
+        e = checked([&] {
+            if (dv.D == 64) k_lloyd_seed<64><<<dv.U, kBlock, 0, s>>>(dv, n_frames);
+            else k_lloyd_seed<128><<<dv.U, kBlock, 0, s>>>(dv, n_frames);
+        });
+        if (e != hipSuccess) return e;
+    }
+    dim3 ga(dv.U, (n_frames + 31) / 32), gu(dv.U, dv.C);
+    for (int it = 0; it < iters; ++it) {
+        e = checked([&] {
+            if (dv.D == 64) k_lloyd_assign<64><<<ga, kBlock, 0, s>>>(dv, n_frames);
+            else k_lloyd_assign<128><<<ga, kBlock, 0, s>>>(dv, n_frames);
+        });
+        if (e != hipSuccess) return e;
+        e = checked([&] {
+            if (dv.D == 64) k_lloyd_update<64><<<gu, 128, 0, s>>>(dv, n_frames);
+            else k_lloyd_update<128><<<gu, 128, 0, s>>>(dv, n_frames);
+        });
+        if (e != hipSuccess) return e;
+    }
+    return e;
+}
+
+} // namespace mosaic

@@ -1,0 +1,95 @@
+// Internal declarations shared by the HIP sources of libmosaic (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/mosaic.h"
+
+namespace mosaic {
+
+constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts of 64)
+constexpr int kRowTile = 16;      // query rows per attention tile
+constexpr int kChunk = 32;        // tokens per attention step, always inside one page
+constexpr int kMaxSplits = 64;    // KV splits per (unit, row tile)
+
+// Device-side view of one context: plain pointers into the caller's arena.
+struct DeviceView {
+    // geometry
+    int L, Hq, Hkv, G, D, T, Tp, F, C, k, U;
+    int esize;        // bytes per KV element
+    int v_transposed; // 1: V pages stored [D][Tp] (MFMA path); 0: [T][D]
+    int chunks_per_page;
+    // KV store, pages in arrival order: page (u, f) at index u*F + f
+    char *k_store;    // [U][F][T][D] elements
+    char *v_store;    // [U][F][T][D] or [U][F][D][Tp] elements
+    // clustering state (decision arithmetic in fp64)
+    double *summ;     // [U][F][D]   per-frame key summaries
+    double *r;        // [U][C][D]   representatives
+    double *rnorm;    // [U][C]      |r_j|
+    int *n;           // [U][C]      sizes in frames
+    int *assign;      // [U][F]      frame -> cluster
+    int *pos;         // [U][F]      rank of the frame among its cluster's members (ascending frame order)
+    // latest selection per unit
+    double *scores;   // [U][C]
+    int *ids;         // [U][k]
+    int *n_ids;       // [U]
+    int *sel_pages;   // [U][F]      frames of the selected clusters, gather order
+    int *n_sel;       // [U]         number of selected frames
+    int *tok_scratch; // [Hkv][F*T]  token-index expansion for the observer
+    // attention partials: entry e = ((uc*NT + tile)*S + split)
+    float *part_o;    // [entries][16][D]
+    float *part_ml;   // [entries][2][16]  running max (log2 domain) and sum
+    long long part_entries;
+};
+
+struct Ctx {
+    mosaic_config cfg;
+    DeviceView dv;
+    hipStream_t stream;
+    int device;
+    int W;               // warm-up frames
+    int iters;
+    int impl;            // MOSAIC_ATTEND_VALU | MOSAIC_ATTEND_MFMA
+    long long n_frames;  // ingested so far (host-side count)
+    std::vector<long long> sel_epoch; // per layer: epoch at which the selection was made
+    std::vector<int> sel_tq;
+    long long epoch;     // bumped by ingest and reset
+    mosaic_stats stats;
+    std::string err;
+    // profiling
+    bool profile;
+    std::vector<hipEvent_t> ev;      // pairs
+    size_t ev_used;
+};
+
+// ---- launchers (each checks its own launch; returns hipError_t) ----
+hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const void *v_in,
+                                int f0, int n_frames, hipStream_t s);
+hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s);
+hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed_from_warmup,
+                        hipStream_t s);
+hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
+                           int n_frames, int score_mode, hipStream_t s);
+hipError_t launch_expand_tok_idx(const DeviceView &dv, int u0, int n_units, hipStream_t s);
+// n_splits chosen by the caller; partial entries needed = n_units * NT * n_splits
+hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
+                              int n_splits, hipStream_t s);
+hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
+                              int n_splits, hipStream_t s);
+hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
+                                 void *out, float *lse, hipStream_t s);
+
+// ---- small device helpers ----
+__device__ __forceinline__ float bf16_to_f32(unsigned short h) {
+    return __uint_as_float(((unsigned int)h) << 16);
+}
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40); // NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+} // namespace mosaic

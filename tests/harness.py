@@ -1,0 +1,195 @@
+"""Parity harness: runs the HIP library and the CPU oracle on the same seeded
+stream and compares them element by element.  Used by the GPU tests, the smoke
+check and the benchmark's spot checks.
+
+Bars (from the benchmark definition):
+  * cluster assignments, selected cluster ids, gathered token indices: exact,
+    except at documented near-ties (relative similarity/score gap < 1e-5),
+    where the oracle adopts the library's choice and every such case is counted;
+  * attention output: max-abs error <= 1e-4 (fp32 KV) / 2e-2 (bf16 KV) against
+    the fp64 oracle;
+  * centroids / scores / summaries (fp64 on both sides): rtol 1e-9.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+from oracle import mosaic_oracle as orc
+from paper_2604_10060_amd import binding, inputs
+
+NEAR_TIE = 1e-5
+OUT_TOL = {"fp32": 1e-4, "bf16": 2e-2}
+LSE_TOL = {"fp32": 1e-4, "bf16": 2e-3}
+
+
+@dataclass
+class Report:
+    online_decisions: int = 0
+    forced_near_ties: int = 0
+    lloyd_runs: int = 0
+    topk_near_ties: int = 0
+    max_out_err: float = 0.0
+    max_lse_err: float = 0.0
+    max_centroid_rel: float = 0.0
+    notes: list = field(default_factory=list)
+
+
+def segment_bounds(wl, F):
+    """Frame counts at which a Lloyd run happens (init, re-clusterings), plus F."""
+    W = wl.warmup
+    b = [W] if W <= F else []
+    if wl.recluster_every > 0:
+        b += [x for x in range(wl.recluster_every, F + 1, wl.recluster_every) if x > W]
+    if not b or b[-1] != F:
+        b.append(F)
+    return b
+
+
+def ingest_with_parity(m: binding.Mosaic, wl, K: torch.Tensor, V: torch.Tensor, units,
+                       rep: Report, batch_pattern=(1, 3, 8, 2)):
+    """Ingest K, V ([F][L][Hkv][T][D], on the library's device) into `m`, replaying
+    the units in `units` (list of (layer, head)) through the oracle.  Library
+    calls never straddle a Lloyd run so that online decisions stay observable."""
+    F = K.shape[0]
+    oracles = {}
+    Kcpu = {}
+    for (l, h) in units:
+        oracles[(l, h)] = orc.OracleUnit(wl.n_clusters, wl.head_dim, wl.tokens_per_frame, F,
+                                         wl.warmup_frames, wl.lloyd_iters, wl.recluster_every)
+        Kcpu[(l, h)] = inputs.unit_pages(K, l, h)
+    f = 0
+    bi = 0
+    for end in segment_bounds(wl, F):
+        seg0 = f
+        while f < end:
+            nb = min(batch_pattern[bi % len(batch_pattern)], end - f)
+            bi += 1
+            m.ingest_frame(K[f:f + nb].contiguous(), V[f:f + nb].contiguous())
+            f += nb
+        A = m.assignments()
+        R, N = m.centroids()
+        for (l, h), o in oracles.items():
+            u = l * wl.n_kv_heads + h
+            for ff in range(seg0, end):
+                will_lloyd = (not o.ready and ff + 1 == wl.warmup) or \
+                    (o.ready and wl.recluster_every > 0 and (ff + 1) % wl.recluster_every == 0)
+                if o.ready:
+                    # online decision: the library's choice is only visible if no
+                    # Lloyd run overwrote it, i.e. for all frames of this segment
+                    # when the segment does not end in a Lloyd run
+                    seg_ends_in_lloyd = end == wl.warmup or \
+                        (wl.recluster_every > 0 and end % wl.recluster_every == 0 and end > wl.warmup)
+                    force = -1
+                    if not seg_ends_in_lloyd:
+                        dec = o.peek(Kcpu[(l, h)][ff])
+                        got = int(A[u, ff])
+                        rep.online_decisions += 1
+                        if got != dec.winner:
+                            assert dec.gap < NEAR_TIE and got == dec.runner_up, (
+                                f"unit {(l, h)} frame {ff}: library chose {got}, oracle {dec.winner} "
+                                f"(runner-up {dec.runner_up}, gap {dec.gap:.3e})")
+                            rep.forced_near_ties += 1
+                            force = got
+                    o.ingest(Kcpu[(l, h)][ff], force)
+                else:
+                    o.ingest(Kcpu[(l, h)][ff])
+                if will_lloyd:
+                    rep.lloyd_runs += 1
+            if o.ready:
+                a_or = o.assignments()
+                got = A[u, : len(a_or)]
+                if not np.array_equal(got, a_or):
+                    bad = np.nonzero(got != a_or)[0]
+                    raise AssertionError(
+                        f"unit {(l, h)} after {end} frames: {len(bad)} assignments differ "
+                        f"(first frame {bad[0]}: library {got[bad[0]]}, oracle {a_or[bad[0]]}); "
+                        f"smallest Lloyd gap {o.lloyd_min_gap:.3e}")
+                np.testing.assert_array_equal(N[u], o.sizes())
+                live = o.sizes() > 0
+                Ro = o.centroids()
+                rel = np.abs(R[u][live] - Ro[live]).max() / max(np.abs(Ro[live]).max(), 1e-30)
+                rep.max_centroid_rel = max(rep.max_centroid_rel, float(rel))
+                assert rel < 1e-9, f"unit {(l, h)}: centroid rel err {rel:.3e}"
+    return oracles
+
+
+def query_with_parity(m: binding.Mosaic, wl, q: torch.Tensor, oracles, K, V, rep: Report,
+                      layer_mode="per_layer", check_attention=True):
+    """q [L][Tq][Hq][D] on the device.  Retrieve + attend through the library
+    (per layer, or all layers in one call) and compare with the oracle for the
+    units in `oracles`.  Returns (out, lse) tensors [L][Tq][Hq][D], [L][Tq][Hq]."""
+    L = wl.n_layers
+    G = wl.group
+    if layer_mode == "all":
+        m.retrieve(-1, q)
+        out, lse = m.attend(-1, q)
+    else:
+        outs, lses = [], []
+        for l in range(L):
+            m.retrieve(l, q[l].contiguous())
+            o_, l_ = m.attend(l, q[l].contiguous())
+            outs.append(o_); lses.append(l_)
+        out, lse = torch.stack(outs), torch.stack(lses)
+    torch.cuda.synchronize()
+    out_h = out.float().cpu().numpy().astype(np.float64)
+    lse_h = lse.cpu().numpy().astype(np.float64)
+    q_h = q.float().cpu().numpy().astype(np.float64)
+    sel_cache = {}
+    for (l, h), o in oracles.items():
+        if l not in sel_cache:
+            sel_cache[l] = m.selection(l)
+        ids, n_ids, scores, toks = sel_cache[l]
+        ids_o, sc_o, tok_o, gap = o.retrieve(q_h[l], h, G, wl.top_k)
+        live = o.sizes() > 0
+        np.testing.assert_allclose(scores[h][live], sc_o[live], rtol=1e-9, atol=1e-12)
+        assert np.all(np.isneginf(scores[h][~live]))
+        got_ids = ids[h, : n_ids[h]]
+        assert n_ids[h] == len(ids_o)
+        assert np.all(ids[h, n_ids[h]:] == -1)
+        if not np.array_equal(got_ids, ids_o):
+            # acceptable only at a documented near-tie in the ranking
+            srt = np.sort(sc_o[live])[::-1]
+            gaps = np.abs(np.diff(srt)) / np.maximum(np.maximum(np.abs(srt[1:]), np.abs(srt[:-1])), 1e-30)
+            assert gaps.min() < NEAR_TIE, (
+                f"unit {(l, h)}: ids {got_ids} != oracle {ids_o} with no near-tie (min gap {gaps.min():.3e})")
+            rep.topk_near_ties += 1
+            tok_o = o.gather(got_ids)
+        np.testing.assert_array_equal(toks[h], tok_o)
+        if check_attention:
+            Ku = inputs.unit_pages(K, l, h).reshape(-1, wl.head_dim)
+            Vu = inputs.unit_pages(V, l, h).reshape(-1, wl.head_dim)
+            want, want_lse = orc.attend(q_h[l], Ku, Vu, tok_o, h, G)
+            err = np.abs(out_h[l][:, h * G:(h + 1) * G, :] - want).max()
+            lerr = np.abs(lse_h[l][:, h * G:(h + 1) * G] - want_lse).max()
+            rep.max_out_err = max(rep.max_out_err, float(err))
+            rep.max_lse_err = max(rep.max_lse_err, float(lerr))
+            assert err <= OUT_TOL[wl.kv_dtype], f"unit {(l, h)}: attention max-abs err {err:.3e}"
+            assert lerr <= LSE_TOL[wl.kv_dtype], f"unit {(l, h)}: lse max-abs err {lerr:.3e}"
+    return out, lse
+
+
+def run_workload(wl, units=None, device="cuda:0", n_questions=1, decode_steps=0,
+                 layer_mode="per_layer", **cfg_overrides):
+    """Whole hot path on workload `wl` with parity on `units` (default: all)."""
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    Kd, Vd = K.to(device), V.to(device)
+    m = binding.Mosaic(binding.config_for(wl, **cfg_overrides), device=device)
+    rep = Report()
+    if units is None:
+        units = [(l, h) for l in range(wl.n_layers) for h in range(wl.n_kv_heads)]
+    oracles = ingest_with_parity(m, wl, Kd, Vd, units, rep)
+    tag = 0
+    for _ in range(n_questions):
+        q = st.question(st.draw_scene(), wl.question_tokens, tag).to(device)
+        tag += 1
+        query_with_parity(m, wl, q, oracles, K, V, rep, layer_mode)
+    for _ in range(decode_steps):
+        q = st.question(st.draw_scene(), 1, tag).to(device)
+        tag += 1
+        query_with_parity(m, wl, q, oracles, K, V, rep, layer_mode)
+    m.close()
+    return rep

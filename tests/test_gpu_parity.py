@@ -1,0 +1,192 @@
+"""GPU parity tests: the HIP library, called through its C ABI, against the
+fp64 CPU oracle on the same seeded streams.  Bars are stated in tests/harness.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_10060_amd import binding, inputs
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _small(**kw):
+    """A reduced single-layer bf16 workload with the realistic head shape."""
+    base = dict(name="small_bf16", n_frames=160, n_scenes=8, n_clusters=12, top_k=4,
+                question_tokens=4)
+    base.update(kw)
+    return inputs.CONFIGS[1].scaled(**base)
+
+
+def _report(rep):
+    print(f"  decisions {rep.online_decisions} forced {rep.forced_near_ties} lloyd {rep.lloyd_runs} "
+          f"topk-ties {rep.topk_near_ties} out {rep.max_out_err:.2e} lse {rep.max_lse_err:.2e} "
+          f"centroid {rep.max_centroid_rel:.1e}", flush=True)
+
+
+def test_cfg0_fp32_full():
+    rep = harness.run_workload(inputs.CONFIGS[0])
+    _report(rep)
+    assert rep.max_out_err <= 1e-4
+
+
+def test_small_bf16_mfma_prefill_and_decode():
+    rep = harness.run_workload(_small(), decode_steps=3)
+    _report(rep)
+    assert rep.max_out_err <= 2e-2
+
+
+def test_small_bf16_valu_kernel():
+    rep = harness.run_workload(_small(), decode_steps=2, attend_impl=binding.ATTEND_VALU)
+    _report(rep)
+
+
+def test_all_layers_in_one_call():
+    wl = _small(n_layers=3, n_frames=96, n_clusters=8, top_k=3)
+    rep = harness.run_workload(wl, decode_steps=2, layer_mode="all")
+    _report(rep)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(tokens_per_frame=5, n_clusters=7, top_k=7),            # ragged page, k = C (dense attention)
+    dict(tokens_per_frame=13, top_k=1),                         # k = 1
+    dict(tokens_per_frame=196, n_frames=64, n_clusters=6, top_k=2, n_scenes=4),   # 7 chunks per page, last ragged
+    dict(tokens_per_frame=40, question_tokens=3),               # 21 query rows: two row tiles
+    dict(n_q_heads=4, n_kv_heads=4, question_tokens=5),         # G = 1
+    dict(n_q_heads=8, n_kv_heads=4, head_dim=64, question_tokens=9),   # G = 2, D = 64, 18 rows
+    dict(n_q_heads=32, n_kv_heads=2, question_tokens=1),        # G = 16: exactly one full tile
+])
+def test_shapes_bf16(kw):
+    rep = harness.run_workload(_small(**kw), decode_steps=1)
+    _report(rep)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(tokens_per_frame=3, n_clusters=5, top_k=5),
+    dict(tokens_per_frame=33, head_dim=128, n_q_heads=6, n_kv_heads=2, question_tokens=7),
+])
+def test_shapes_fp32(kw):
+    wl = inputs.CONFIGS[0].scaled(name="odd_fp32", **kw)
+    rep = harness.run_workload(wl, decode_steps=1)
+    _report(rep)
+
+
+def test_recluster_parity():
+    wl = _small(n_frames=200, recluster_every=48, n_clusters=10, warmup_frames=24, lloyd_iters=3)
+    rep = harness.run_workload(wl, decode_steps=1)
+    _report(rep)
+    assert rep.lloyd_runs >= 4 * 4      # init + 4 re-clusterings (48..192, 96 etc.), per unit
+
+
+def test_low_coherence_stream():
+    wl = inputs.cfg4_stream(5).scaled(n_frames=192, n_clusters=16, top_k=5, question_tokens=8)
+    rep = harness.run_workload(wl)
+    _report(rep)
+
+
+def _ingest_all(wl, K, V, pattern, **over):
+    m = binding.Mosaic(binding.config_for(wl, **over), device=DEV)
+    f = 0
+    i = 0
+    while f < wl.n_frames:
+        nb = min(pattern[i % len(pattern)], wl.n_frames - f)
+        i += 1
+        m.ingest_frame(K[f:f + nb].contiguous(), V[f:f + nb].contiguous())
+        f += nb
+    return m
+
+
+def test_batched_ingest_equals_single_frame_calls_bitwise():
+    # batches that straddle the warm-up boundary and re-clustering points
+    wl = _small(n_frames=150, recluster_every=40, warmup_frames=24, lloyd_iters=2)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    q = st.question(0, 2, 0).to(DEV)
+    res = []
+    for pattern in ((1,), (37, 5, 64), (150,)):
+        m = _ingest_all(wl, K, V, pattern)
+        m.retrieve(0, q[0].contiguous())
+        out, lse = m.attend(0, q[0].contiguous())
+        r, n = m.centroids()
+        res.append((m.assignments(), r, n, out.float().cpu().numpy(), lse.cpu().numpy()))
+        assert m.stats().lloyd_runs == 1 + 3
+        m.close()
+    for other in res[1:]:
+        for a, b in zip(res[0], other):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_reset_and_rerun_is_deterministic():
+    wl = _small(n_frames=80, n_clusters=6, top_k=2)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    q = st.question(1, 1, 0).to(DEV)[0].contiguous()
+    m = _ingest_all(wl, K, V, (16,))
+    m.retrieve(0, q)
+    o1, l1 = m.attend(0, q)
+    a1 = m.assignments()
+    m.reset()
+    assert m.stats().frames_ingested == 0
+    with pytest.raises(binding.MosaicError) as e:
+        m.retrieve(0, q)
+    assert e.value.code == binding.ENOTREADY
+    for f in range(0, wl.n_frames, 16):
+        m.ingest_frame(K[f:f + 16].contiguous(), V[f:f + 16].contiguous())
+    m.retrieve(0, q)
+    o2, l2 = m.attend(0, q)
+    np.testing.assert_array_equal(a1, m.assignments())
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+    m.close()
+
+
+def test_error_paths():
+    wl = _small(n_frames=40, n_clusters=8, top_k=2)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    q = st.question(0, 1, 0).to(DEV)[0].contiguous()
+    m = binding.Mosaic(binding.config_for(wl), device=DEV)
+    m.ingest_frame(K[:10].contiguous(), V[:10].contiguous())
+    assert (m.assignments() == -1).all()                       # still buffered
+    with pytest.raises(binding.MosaicError) as e:               # before the initial clustering
+        m.retrieve(0, q)
+    assert e.value.code == binding.ENOTREADY
+    m.ingest_frame(K[10:30].contiguous(), V[10:30].contiguous())
+    with pytest.raises(binding.MosaicError) as e:               # attend without a selection
+        m.attend(0, q)
+    assert e.value.code == binding.ENOTREADY
+    m.retrieve(0, q)
+    m.attend(0, q)
+    m.ingest_frame(K[30:31].contiguous(), V[30:31].contiguous())
+    with pytest.raises(binding.MosaicError) as e:               # selection is stale after an ingest
+        m.attend(0, q)
+    assert e.value.code == binding.ENOTREADY
+    with pytest.raises(binding.MosaicError) as e:               # capacity
+        m.ingest_frame(K[:10].contiguous(), V[:10].contiguous())
+    assert e.value.code == binding.ECAPACITY
+    assert m.stats().frames_ingested == 31                      # nothing was ingested by the failed call
+    L = binding.load_library()
+    assert L.mosaic_retrieve(m._h, 3, q.data_ptr(), 1) == binding.EINVAL      # layer out of range
+    assert L.mosaic_retrieve(m._h, 0, q.data_ptr(), 0) == binding.EINVAL      # no query tokens
+    assert L.mosaic_retrieve(m._h, 0, q.data_ptr(), 10 ** 6) == binding.EINVAL
+    assert L.mosaic_ingest_frame(m._h, None, None, 1) == binding.EINVAL
+    assert b"NULL" in L.mosaic_last_error(m._h)
+    m.close()
+    # arena too small
+    cfg = binding.config_for(wl)
+    need = binding.workspace_size(cfg)
+    buf = torch.empty(need // 2, dtype=torch.uint8, device=DEV)
+    cfg.dev_arena = (buf.data_ptr() + 255) // 256 * 256
+    cfg.dev_arena_bytes = need // 2 - 256
+    import ctypes as C
+    h = C.c_void_p()
+    assert L.mosaic_create(C.byref(cfg), C.byref(h)) == binding.ENOMEM
+
+
+def test_cfg1_full_size():
+    """Single-layer realistic workload at full size in the launch configuration
+    the benchmark times: 32-token question, then decode steps."""
+    rep = harness.run_workload(inputs.CONFIGS[1], decode_steps=4)
+    _report(rep)
+    assert rep.max_out_err <= 2e-2

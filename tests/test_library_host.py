@@ -1,0 +1,75 @@
+"""Host-side checks that need no GPU: the built library loads, exports every
+symbol the public header declares, validates configurations and sizes arenas."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_10060_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "mosaic.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mosaic_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = binding.load_library()
+    names = _declared_functions()
+    assert "mosaic_ingest_frame" in names and "mosaic_retrieve" in names
+    assert "mosaic_attend" in names and "mosaic_reset" in names
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in mosaic.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_struct_layout_matches_header():
+    # 16 int32 fields, then pointer, size_t, pointer
+    assert C.sizeof(binding.Config) == 16 * 4 + 3 * 8
+    assert C.sizeof(binding.Stats) == 5 * 8 + 4 * 4
+
+
+def _cfg(**kw):
+    base = dict(n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=64, tokens_per_frame=16,
+                max_frames=128, n_clusters=16, top_k=4, kv_dtype="fp32")
+    base.update(kw)
+    return binding.make_config(**base)
+
+
+def test_workspace_size_grows_with_the_stream():
+    a = binding.workspace_size(_cfg())
+    b = binding.workspace_size(_cfg(max_frames=256))
+    assert b > a > 2 * 2 * 128 * 16 * 64 * 4          # at least the K and V pages
+    # bf16 pages are half the bytes of fp32 pages
+    kv32 = 2 * 2 * 4096 * 64 * 128 * 4
+    d = binding.workspace_size(_cfg(head_dim=128, tokens_per_frame=64, max_frames=4096)) - \
+        binding.workspace_size(_cfg(head_dim=128, tokens_per_frame=64, max_frames=4096, kv_dtype="bf16"))
+    assert d == kv32 // 2
+
+
+@pytest.mark.parametrize("bad", [
+    dict(head_dim=96), dict(n_q_heads=5), dict(top_k=0), dict(top_k=17), dict(n_clusters=0),
+    dict(n_clusters=2000, top_k=4), dict(kv_dtype=7), dict(tokens_per_frame=0),
+    dict(warmup_frames=8), dict(score_mode=2), dict(attend_impl=binding.ATTEND_MFMA),
+    dict(max_frames=1 << 30, tokens_per_frame=64), dict(attend_impl=9),
+])
+def test_bad_configurations_are_rejected(bad):
+    with pytest.raises(binding.MosaicError) as e:
+        binding.workspace_size(_cfg(**bad))
+    assert e.value.code == binding.EINVAL
+    assert len(str(e.value)) > 10
+
+
+def test_null_arguments_do_not_crash():
+    lib = binding.load_library()
+    assert lib.mosaic_workspace_size(None, None) == binding.EINVAL
+    assert lib.mosaic_reset(None) == binding.EINVAL
+    assert lib.mosaic_ingest_frame(None, None, None, 1) == binding.EINVAL
+    assert lib.mosaic_retrieve(None, 0, None, 1) == binding.EINVAL
+    assert lib.mosaic_attend(None, 0, None, 1, None, None) == binding.EINVAL
+    assert lib.mosaic_destroy(None) == binding.EINVAL
+    assert isinstance(lib.mosaic_last_error(None), bytes)

@@ -204,6 +204,17 @@ class Mosaic:
         self._check(self._L.mosaic_attend(self._h, layer, _ptr(q), tq, _ptr(out), _ptr(lse)))
         return out, lse
 
+    # -- unchecked variants for timed loops: raw device addresses, same C calls --
+    def retrieve_raw(self, layer: int, q_ptr: int, n_q_tokens: int):
+        rc = self._L.mosaic_retrieve(self._h, layer, q_ptr, n_q_tokens)
+        if rc != OK:
+            self._check(rc)
+
+    def attend_raw(self, layer: int, q_ptr: int, n_q_tokens: int, out_ptr: int, lse_ptr: int):
+        rc = self._L.mosaic_attend(self._h, layer, q_ptr, n_q_tokens, out_ptr, lse_ptr)
+        if rc != OK:
+            self._check(rc)
+
     # -- observers -------------------------------------------------------------
     def stats(self) -> Stats:
         s = Stats()

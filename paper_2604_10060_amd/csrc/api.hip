@@ -62,7 +62,7 @@ Layout make_layout(const mosaic_config &c) {
                  ? (c.kv_dtype == MOSAIC_BF16 ? MOSAIC_ATTEND_MFMA : MOSAIC_ATTEND_VALU)
                  : c.attend_impl;
     L.v_transposed = L.impl == MOSAIC_ATTEND_MFMA;
-    L.Tp = (int)((T + 7) / 8 * 8);
+    L.Tp = (int)((T + kChunk - 1) / kChunk * kChunk);   // value pages are padded to whole 32-token chunks
     const int G = c.n_q_heads / c.n_kv_heads;
     const int maxq = c.max_q_tokens > 0 ? c.max_q_tokens : 256;
     const long long nt_max = ((long long)maxq * G + kRowTile - 1) / kRowTile;

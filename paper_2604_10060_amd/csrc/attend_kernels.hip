@@ -141,38 +141,102 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, c
     }
 }
 
-// grid (NT, n_units), 256 threads: thread (row = tid/16, dl = tid%16)
+// Merge of the per-split partials (log-sum-exp weights), normalisation, output.
+// grid (D/32, NT, n_units), 256 threads.  A workgroup owns 32 output channels of
+// one row tile; its 8 groups of 32 threads share the splits, so the partial
+// buffer is read with many independent 128-byte loads in flight.
 template <typename E, int D>
 __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0, int Tq,
                                                            int n_splits, E *out, float *lse) {
-    constexpr int DPT = D / 16;
-    const int tile = blockIdx.x, uc = blockIdx.y, u = u0 + uc, NT = gridDim.x;
-    const int tid = threadIdx.x, row = tid / 16, dl = tid % 16;
+    const int dg = blockIdx.x, tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc, NT = gridDim.y;
+    const int tid = threadIdx.x;
     const int G = dv.G, Hq = dv.Hq, lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
-    const int gr = tile * kRowTile + row;
-    if (gr >= R) return;
+    const int rows = min(kRowTile, R - tile * kRowTile);
     const size_t e0 = ((size_t)uc * NT + tile) * n_splits;
-    float M = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, dv.part_ml[(e0 + s) * 2 * kRowTile + row]);
-    float L = 0.f, o[DPT];
+    __shared__ float w_sh[kMaxSplits][kRowTile];
+    __shared__ float pm[16][kRowTile], pl[16][kRowTile];
+    __shared__ float M_sh[kRowTile], L_sh[kRowTile];
+    __shared__ float red[8][kRowTile][33];
+    {   // per-row maximum and normaliser over the splits
+        const int row = tid % 16, part = tid / 16;
+        float mr[kMaxSplits / 16], lr[kMaxSplits / 16];
+        float mx = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < DPT; ++i) o[i] = 0.f;
-    if (M > -INFINITY) {
-        for (int s = 0; s < n_splits; ++s) {
-            const float w = exp2f(dv.part_ml[(e0 + s) * 2 * kRowTile + row] - M);
-            L += w * dv.part_ml[(e0 + s) * 2 * kRowTile + kRowTile + row];
+        for (int i = 0; i < kMaxSplits / 16; ++i) {
+            const int s = part + 16 * i;
+            mr[i] = -INFINITY; lr[i] = 0.f;
+            if (s < n_splits) {
+                mr[i] = dv.part_ml[(e0 + s) * 2 * kRowTile + row];
+                lr[i] = dv.part_ml[(e0 + s) * 2 * kRowTile + kRowTile + row];
+            }
+            mx = fmaxf(mx, mr[i]);
+        }
+        pm[part][row] = mx;
+        __syncthreads();
+        float M = -INFINITY;
 #pragma unroll
-            for (int i = 0; i < DPT; ++i)
-                o[i] += w * dv.part_o[((e0 + s) * kRowTile + row) * D + dl + 16 * i];
+        for (int p = 0; p < 16; ++p) M = fmaxf(M, pm[p][row]);
+        float ls = 0.f;
+#pragma unroll
+        for (int i = 0; i < kMaxSplits / 16; ++i) {
+            const int s = part + 16 * i;
+            if (s < n_splits) {
+                const float w = M > -INFINITY ? exp2f(mr[i] - M) : 0.f;
+                w_sh[s][row] = w;
+                ls += w * lr[i];
+            }
+        }
+        pl[part][row] = ls;
+        __syncthreads();
+        if (part == 0) {
+            float Ls = 0.f;
+#pragma unroll
+            for (int p = 0; p < 16; ++p) Ls += pl[p][row];
+            M_sh[row] = M;
+            L_sh[row] = Ls;
         }
     }
-    const int t = gr / G, g = gr % G;
-    const size_t orow = ((size_t)lc * Tq + t) * Hq + (size_t)h * G + g;
-    const float inv = L > 0.f ? 1.f / L : 0.f;
+    const int sg = tid / 32, col = tid % 32;
+    float acc[kRowTile];
 #pragma unroll
-    for (int i = 0; i < DPT; ++i) store_out<E>(out + orow * D + dl + 16 * i, o[i] * inv);
-    if (dl == 0 && lse != nullptr)
-        lse[orow] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+    for (int r = 0; r < kRowTile; ++r) acc[r] = 0.f;
+    {   // all loads of this thread are issued before the first use: the partials were
+        // written by other compute units, so every load is a full memory round trip
+        float v[kMaxSplits / 8][kRowTile];
+#pragma unroll
+        for (int i = 0; i < kMaxSplits / 8; ++i) {
+            const int s = sg + 8 * i;
+            const float *po = dv.part_o + (e0 + s) * kRowTile * D + dg * 32 + col;
+#pragma unroll
+            for (int r = 0; r < kRowTile; ++r)
+                v[i][r] = (s < n_splits && r < rows) ? po[(size_t)r * D] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < kMaxSplits / 8; ++i) {
+            const int s = sg + 8 * i;
+            if (s < n_splits) {
+#pragma unroll
+                for (int r = 0; r < kRowTile; ++r) acc[r] += w_sh[s][r] * v[i][r];
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kRowTile; ++r) red[sg][r][col] = acc[r];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = sg + 8 * j;
+        if (r >= rows) continue;
+        float o = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) o += red[q][r][col];
+        const float Lr = L_sh[r];
+        const int gr = tile * kRowTile + r, t = gr / G, g = gr % G;
+        const size_t orow = ((size_t)lc * Tq + t) * Hq + (size_t)h * G + g;
+        store_out<E>(out + orow * D + dg * 32 + col, Lr > 0.f ? o / Lr : 0.f);
+        if (dg == 0 && col == 0 && lse != nullptr)
+            lse[orow] = Lr > 0.f ? (M_sh[r] + log2f(Lr)) * 0.6931471805599453f : -INFINITY;
+    }
 }
 
 } // namespace
@@ -194,7 +258,7 @@ hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const v
 hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
                                  void *out, float *lse, hipStream_t s) {
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
-    dim3 grid(NT, n_units);
+    dim3 grid(dv.D / 32, NT, n_units);
     if (dv.esize == 4) {
         if (dv.D == 64) k_attend_combine<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (float *)out, lse);
         else k_attend_combine<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (float *)out, lse);

@@ -102,10 +102,12 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
             Elem<E>::copy8(src + (size_t)t * D + cg * 8, dst + (size_t)t * D + cg * 8);
         return;
     }
-    // Transposed value page [D][Tp] (2-byte elements only): 8 consecutive
-    // tokens of one channel become one 16-byte operand of the PV contraction.
+    // Transposed, chunk-blocked value page [Tp/32][D][32] (2-byte elements only):
+    // 8 consecutive tokens of one channel form one 16-byte operand of the PV
+    // contraction, and the 16 channels x 32 tokens a wavefront loads at once
+    // are one contiguous KiB.  Tokens T..Tp-1 are written as zeros.
     if constexpr (sizeof(E) == 2) {
-        constexpr int TC = 64;                       // tokens per LDS tile
+        constexpr int TC = 64;                       // tokens per LDS tile (two chunks)
         __shared__ unsigned short tile[TC][D + 2];
         const int Tp = dv.Tp;
         unsigned short *dst = reinterpret_cast<unsigned short *>(dv.v_store) + page * (size_t)D * Tp;
@@ -126,7 +128,8 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
                 for (int j = 0; j < 4; ++j)
                     w[j] = (unsigned int)tile[tg * 8 + 2 * j][d] |
                            ((unsigned int)tile[tg * 8 + 2 * j + 1][d] << 16);
-                *reinterpret_cast<uint4 *>(dst + (size_t)d * Tp + tc0 + tg * 8) =
+                const int tok = tc0 + tg * 8;         // first of the 8 tokens
+                *reinterpret_cast<uint4 *>(dst + ((size_t)(tok / kChunk) * D + d) * kChunk + tok % kChunk) =
                     make_uint4(w[0], w[1], w[2], w[3]);
             }
             __syncthreads();

@@ -19,11 +19,11 @@ struct DeviceView {
     // geometry
     int L, Hq, Hkv, G, D, T, Tp, F, C, k, U;
     int esize;        // bytes per KV element
-    int v_transposed; // 1: V pages stored [D][Tp] (MFMA path); 0: [T][D]
+    int v_transposed; // 1: V pages stored [Tp/32][D][32] (MFMA path, Tp = T rounded up to 32); 0: [T][D]
     int chunks_per_page;
     // KV store, pages in arrival order: page (u, f) at index u*F + f
     char *k_store;    // [U][F][T][D] elements
-    char *v_store;    // [U][F][T][D] or [U][F][D][Tp] elements
+    char *v_store;    // [U][F][T][D] or [U][F][Tp/32][D][32] elements
     // clustering state (decision arithmetic in fp64)
     double *summ;     // [U][F][D]   per-frame key summaries
     double *r;        // [U][C][D]   representatives

@@ -21,84 +21,153 @@ template <> __device__ __forceinline__ double to_f64<unsigned short>(unsigned sh
 }
 
 // grid (n_units), 256 threads.  u0 is a multiple of Hkv.
+// A single workgroup per unit is latency-bound, so every global load whose
+// address does not depend on an earlier result (query rows, sizes, norms, the
+// representative rows, and the first frames' assignment/position entries) is
+// issued up front, unconditionally; what follows runs out of LDS and registers.
 template <typename E, int D>
 __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, const E *q, int Tq,
                                                      int n_frames, int score_mode) {
-    constexpr int EPL = D / 16;
+    constexpr int EPL = D / 16;   // doubles per lane in a 16-lane row group
+    constexpr int FPT = 8;        // frames per thread prefetched for the page-list scatter
+    constexpr int RPF = 4;        // passes of 16 representative rows prefetched into registers
     const int uc = blockIdx.x, u = u0 + uc, tid = threadIdx.x;
     const int C = dv.C, G = dv.G, Hq = dv.Hq, k = dv.k;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv;
     const int lr = tid % 16, row0 = tid / 16;
     __shared__ double qbar[D];
+    __shared__ double qpart[2][D];
     __shared__ double sc_sh[1024];
+    __shared__ int n_sh[1024];
+    __shared__ double rn_sh[1024];
     __shared__ int rank_sh[1024];   // selection rank of cluster j, or -1
+    __shared__ int cnt_sh[1024];
     __shared__ int ids_sh[1024];
     __shared__ int off_sh[1025];
     __shared__ int n_live_sh;
     const double *r = dv.r + (size_t)u * C * D;
     const double *rn = dv.rnorm + (size_t)u * C;
     const int *n = dv.n + (size_t)u * C;
-
+    const int *assign = dv.assign + (size_t)u * dv.F;
+    const int *pos = dv.pos + (size_t)u * dv.F;
+    // ---- independent loads ----
+    int fa[FPT], fp[FPT];
+#pragma unroll
+    for (int i = 0; i < FPT; ++i) {
+        const int f = tid + kBlock * i;
+        fa[i] = f < n_frames ? assign[f] : -1;
+        fp[i] = f < n_frames ? pos[f] : 0;
+    }
+    for (int j = tid; j < C; j += kBlock) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; }
     if (tid == 0) n_live_sh = 0;
-    // mean query over the Tq tokens and the G query heads of this KV head
-    if (tid < D) {
+    // representative rows of the first RPF passes (row index clamped, loads unconditional)
+    double rpre[RPF][EPL];
+#pragma unroll
+    for (int i = 0; i < RPF; ++i) {
+        const double *rj = r + (size_t)min(row0 + 16 * i, C - 1) * D + lr * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
+    }
+    // mean query over the Tq tokens and the G query heads of this KV head: thread
+    // (d, half) sums its half of the tokens in (t, g) order
+    {
+        const int d = tid % D, half = tid / D;          // D = 64: 4 parts, D = 128: 2 parts
+        constexpr int PARTS = kBlock / D;
         const E *qb = q + (size_t)lc * Tq * Hq * D;
         double acc = 0.0;
-        for (int t = 0; t < Tq; ++t)
+        for (int t = half; t < Tq; t += PARTS)
             for (int g = 0; g < G; ++g)
-                acc += to_f64<E>(qb[((size_t)t * Hq + (size_t)h * G + g) * D + tid]);
-        qbar[tid] = acc / (double)(Tq * G);
+                acc += to_f64<E>(qb[((size_t)t * Hq + (size_t)h * G + g) * D + d]);
+        if (PARTS == 2) qpart[half][d] = acc;
+        else {                                          // 4 parts: fold pairs through LDS
+            if (half >= 2) qpart[half - 2][d] = acc;
+            __syncthreads();
+            if (half < 2) qpart[half][d] += acc;
+        }
     }
     __syncthreads();
-    // score_j = (qbar . r_j) / |r_j|   (plain dot product in score_mode 1)
-    for (int j = row0; j < C; j += 16) {
-        double p = 0.0;
-        const bool live = n[j] > 0;
-        if (live) {
-            const double *rj = r + (size_t)j * D + lr * EPL;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) p += qbar[lr * EPL + i] * rj[i];
-        }
+    if (tid < D) qbar[tid] = (qpart[0][tid] + qpart[1][tid]) / (double)(Tq * G);
+    __syncthreads();
+    auto finish_row = [&](int j, double p) {
         p = group16_sum(p);
         if (lr == 0) {
             double sc = -INFINITY;
-            if (live) sc = score_mode == 1 ? p : (rn[j] == 0.0 ? 0.0 : p / rn[j]);
+            if (n_sh[j] > 0) {
+                const double nr = rn_sh[j];
+                sc = score_mode == 1 ? p : (nr == 0.0 ? 0.0 : p / nr);
+            }
             sc_sh[j] = sc;
             dv.scores[(size_t)u * C + j] = sc;
         }
+    };
+#pragma unroll
+    for (int i = 0; i < RPF; ++i) {
+        const int j = row0 + 16 * i;
+        if (j < C) {
+            double p = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rpre[i][e];
+            finish_row(j, p);
+        }
+    }
+    for (int j = row0 + 16 * RPF; j < C; j += 16) {
+        const double *rj = r + (size_t)j * D + lr * EPL;
+        double p = 0.0;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rj[e];
+        finish_row(j, p);
     }
     __syncthreads();
-    // rank among non-empty clusters by (score descending, id ascending)
-    for (int j = tid; j < C; j += kBlock) {
-        int rk = -1;
-        if (n[j] > 0) {
+    // rank among non-empty clusters by (score descending, id ascending).  Empty
+    // clusters carry -inf and so never outrank a live one.  With few clusters the
+    // comparison range of a cluster is shared by several threads.
+    {
+        const int P = C <= 64 ? 4 : (C <= 128 ? 2 : 1);
+        for (int j = tid; j < C; j += kBlock) cnt_sh[j] = 0;
+        __syncthreads();
+        for (int item = tid; item < C * P; item += kBlock) {
+            const int j = item % C, part = item / C;
+            if (n_sh[j] <= 0) continue;
             const double sj = sc_sh[j];
-            rk = 0;
-            for (int i = 0; i < C; ++i) {
+            const int i0 = (C * part) / P, i1 = (C * (part + 1)) / P;
+            int c = 0;
+#pragma unroll 8
+            for (int i = i0; i < i1; ++i) {
                 const double si = sc_sh[i];
-                rk += (n[i] > 0) && (si > sj || (si == sj && i < j));
+                c += (si > sj) || (si == sj && i < j);
             }
-            atomicAdd(&n_live_sh, 1);
-            if (rk < k) ids_sh[rk] = j; else rk = -1;
+            atomicAdd(&cnt_sh[j], c);
         }
-        rank_sh[j] = rk;
+        __syncthreads();
+        for (int j = tid; j < C; j += kBlock) {
+            int rk = -1;
+            if (n_sh[j] > 0) {
+                rk = cnt_sh[j];
+                atomicAdd(&n_live_sh, 1);
+                if (rk < k) ids_sh[rk] = j; else rk = -1;
+            }
+            rank_sh[j] = rk;
+        }
     }
     __syncthreads();
     const int n_ids = min(k, n_live_sh);
     if (tid == 0) {
         int o = 0;
         off_sh[0] = 0;
-        for (int i = 0; i < n_ids; ++i) { o += n[ids_sh[i]]; off_sh[i + 1] = o; }
+        for (int i = 0; i < n_ids; ++i) { o += n_sh[ids_sh[i]]; off_sh[i + 1] = o; }
         dv.n_ids[u] = n_ids;
         dv.n_sel[u] = o;
     }
     for (int i = tid; i < k; i += kBlock) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
     __syncthreads();
-    // page list: clusters in selection order, member frames ascending
-    const int *assign = dv.assign + (size_t)u * dv.F;
-    const int *pos = dv.pos + (size_t)u * dv.F;
     int *sel = dv.sel_pages + (size_t)u * dv.F;
-    for (int f = tid; f < n_frames; f += kBlock) {
+#pragma unroll
+    for (int i = 0; i < FPT; ++i) {
+        if (fa[i] < 0) continue;
+        const int rk = rank_sh[fa[i]];
+        if (rk >= 0) sel[off_sh[rk] + fp[i]] = tid + kBlock * i;
+    }
+    for (int f = tid + kBlock * FPT; f < n_frames; f += kBlock) {
         const int c = assign[f];
         if (c < 0) continue;
         const int rk = rank_sh[c];
@@ -136,3 +205,4 @@ hipError_t launch_expand_tok_idx(const DeviceView &dv, int u0, int n_units, hipS
 }
 
 } // namespace mosaic
+

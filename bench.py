@@ -5,14 +5,21 @@ A timed "step" is one autoregressive decode step of the workload: for every
 layer, mosaic_retrieve (mean query, scores, top-k, page list) followed by
 mosaic_attend (split-KV attention over the retrieved pages + combine), chained
 on one stream.  The stream is ingested beforehand through mosaic_ingest_frame
-(timed separately: frames/s), and a multi-token question is prefilled once.
+(timed separately: frames/s), and the multi-token question is prefilled once.
 All inputs are resident in HBM before any timed region starts.
 
-Prints ONE JSON line (see the keys at the bottom).  `roofline` refers to the
-split-KV attention kernel (the dominant kernel): algorithmic bytes = K and V of
-the retrieved tokens read once, divided by that kernel's mean duration measured
-with HIP events on the library's stream.  `cpu_baseline` is the fp64 CPU oracle
-timed on this host on a bounded sample of the same decode steps.
+Prints ONE JSON line.  The headline numbers are those of the single-layer
+realistic workload (config 1 of the benchmark definition); `extra` repeats the
+measurement on the full 28-layer stack (config 2, ~15 GB of KV streamed from
+HBM), once with per-layer calls and once with all layers in one call.
+
+`roofline` refers to the split-KV attention kernel (the dominant kernel):
+algorithmic bytes = K and V of the retrieved tokens read once, divided by that
+kernel's mean duration.  The duration is measured with HIP events recorded on
+the library's stream around every launch; the mean cost of an empty event pair
+on the same stream is measured too and subtracted (both are reported).
+`cpu_baseline` is the fp64 CPU oracle timed on this host on a bounded sample of
+the same decode steps.
 """
 from __future__ import annotations
 
@@ -29,9 +36,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
-# HBM bytes per attention-kernel launch from rocprofv3 --pmc runs (FETCH_SIZE +
-# WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {"cfg1_single_layer_hbm": None, "cfg2_full_stack_hbm": None}
+# HBM bytes per launch of the decode attention kernel from rocprofv3 --pmc runs
+# (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter read on
+# k_calibration_copy, a 256 MiB copy): see profiles/.  Keyed by (workload, calls).
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
 
 
 def parse():
@@ -40,36 +52,55 @@ def parse():
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2"])
-    ap.add_argument("--layers", type=int, default=0, help="override the layer count (cfg2)")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count")
     ap.add_argument("--all-layers-call", action="store_true",
                     help="one retrieve/attend call for all layers instead of per-layer calls")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the config-2 legs reported under `extra`")
+    ap.add_argument("--extra-steps", type=int, default=32)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (counter calibration for rocprofv3 --pmc)")
     ap.add_argument("--check-units", type=int, default=2,
                     help="units spot-checked against the oracle before timing (0 = none)")
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (units are independent; "
-              "no collective path exists); --gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+def n_tok_all(m, L):
+    """Selected token count of every unit (one small D2H per layer)."""
+    H = m.cfg.n_kv_heads
+    out = []
+    buf = np.empty(H, dtype=np.int32)
+    for l in range(L):
+        rc = m._L.mosaic_get_selection(m._h, l, None, None, None, None, 0, buf.ctypes.data)
+        if rc != 0:
+            m._check(rc)
+        out.extend(buf.tolist())
+    return out
+
+
+def event_pair_overhead_us(torch, n=200):
+    """Mean elapsed time of an empty HIP event pair on the current stream."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    x = torch.zeros(1024, device="cuda:0")
+    for a, b in evs:
+        x.add_(1.0)            # keep the stream busy like a preceding kernel would
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
+
+
+def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrate=False):
     import torch
     from paper_2604_10060_amd import binding, inputs
 
     dev = "cuda:0"
-    wl = inputs.CONFIGS[int(args.workload[-1])]
-    if args.layers:
-        wl = wl.scaled(n_layers=args.layers)
-    if args.frames:
-        wl = wl.scaled(n_frames=args.frames)
     L, Hq, D, T, F = wl.n_layers, wl.n_q_heads, wl.head_dim, wl.tokens_per_frame, wl.n_frames
     esz = 4 if wl.kv_dtype == "fp32" else 2
-    K_steps, W_steps = args.steps, args.warmup
-    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    mode = "all_layers" if all_layers else "per_layer"
 
     # ---- synthetic stream, generated on the device ---------------------------------
     t0 = time.time()
@@ -80,11 +111,21 @@ def main():
     for f in range(F):
         K_all[f], V_all[f] = st.frame(f)
     torch.cuda.synchronize()
-    log(f"[bench] {wl.name}: stream of {F} frames generated in {time.time() - t0:.1f}s "
+    log(f"[bench] {wl.name}/{mode}: {F} frames generated in {time.time() - t0:.1f}s "
         f"({2 * K_all.numel() * esz / 1e9:.2f} GB KV)")
 
+    if calibrate:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        lib_ = binding.load_library()   # k_calibration_copy: reads 256 MiB, writes 256 MiB
+        assert lib_.mosaic_calibration_copy(b.data_ptr(), a.data_ptr(), a.numel(),
+                                            torch.cuda.current_stream().cuda_stream) == 0
+        torch.cuda.synchronize()
+        del a, b
+
     m = binding.Mosaic(binding.config_for(wl), device=dev)
-    frame_elems = L * wl.n_kv_heads * T * D
+    frame_bytes = L * wl.n_kv_heads * T * D * esz
     kp, vp = K_all.data_ptr(), V_all.data_ptr()
     lib, h = m._L, m._h
 
@@ -95,21 +136,21 @@ def main():
         f = 0
         while f < F:
             nb = min(batch, F - f)
-            rc = lib.mosaic_ingest_frame(h, kp + f * frame_elems * esz, vp + f * frame_elems * esz, nb)
+            rc = lib.mosaic_ingest_frame(h, kp + f * frame_bytes, vp + f * frame_bytes, nb)
             if rc != 0:
                 m._check(rc)
             f += nb
         torch.cuda.synchronize()
         return F / (time.perf_counter() - t)
 
-    ingest(16)                              # warm-up pass (code objects, caches)
+    ingest(16)                              # warm-up pass
     fps_b16 = ingest(16)
     fps_b1 = ingest(1)                      # the stream the queries run against
     log(f"[bench] ingest: {fps_b1:.0f} frames/s (1 frame per call), {fps_b16:.0f} frames/s (16 per call)")
 
     # ---- questions ------------------------------------------------------------------
-    q_question = st.question(st.draw_scene(), wl.question_tokens, 0)
-    n_q = W_steps + K_steps
+    q_question = st.question(st.draw_scene(), wl.question_tokens, 0).contiguous()
+    n_q = warmup + steps
     q_dec = torch.stack([st.question(st.draw_scene(), 1, 1 + i) for i in range(n_q)])  # [n][L][1][Hq][D]
     out = torch.empty((L, 1, Hq, D), dtype=wl.torch_dtype, device=dev)
     lse = torch.empty((L, 1, Hq), dtype=torch.float32, device=dev)
@@ -118,12 +159,12 @@ def main():
 
     # ---- parity spot check in the timed launch configuration ------------------------
     checked = None
-    if args.check_units > 0:
+    if check_units > 0:
         from tests import harness
         from oracle import mosaic_oracle as orc
         rng = np.random.Generator(np.random.PCG64(7))
         all_units = [(l, hh) for l in range(L) for hh in range(wl.n_kv_heads)]
-        pick = [all_units[i] for i in rng.choice(len(all_units), min(args.check_units, len(all_units)),
+        pick = [all_units[i] for i in rng.choice(len(all_units), min(check_units, len(all_units)),
                                                  replace=False)]
         t0 = time.time()
         oracles = {}
@@ -137,26 +178,24 @@ def main():
             assert np.array_equal(A[u], o.assignments()), f"unit {(l, hh)}: assignments differ from the oracle"
             oracles[(l, hh)] = o
         rep = harness.Report()
-        harness.query_with_parity(m, wl, q_question.to(dev), oracles, K_all, V_all, rep,
-                                  "all" if args.all_layers_call else "per_layer")
-        harness.query_with_parity(m, wl, q_dec[0], oracles, K_all, V_all, rep,
-                                  "all" if args.all_layers_call else "per_layer")
+        lm = "all" if all_layers else "per_layer"
+        harness.query_with_parity(m, wl, q_question, oracles, K_all, V_all, rep, lm)
+        harness.query_with_parity(m, wl, q_dec[0], oracles, K_all, V_all, rep, lm)
         checked = {"units": [list(p) for p in pick], "max_out_err": rep.max_out_err,
                    "max_lse_err": rep.max_lse_err, "topk_near_ties": rep.topk_near_ties}
         log(f"[bench] parity spot check on units {pick}: out err {rep.max_out_err:.2e} "
             f"({time.time() - t0:.1f}s)")
 
     # ---- question prefill (once, timed) ---------------------------------------------
-    qq = q_question.to(dev).contiguous()
-    oq = torch.empty_like(qq)
-    lq = torch.empty(qq.shape[:-1], dtype=torch.float32, device=dev)
+    oq = torch.empty_like(q_question)
+    lq = torch.empty(q_question.shape[:-1], dtype=torch.float32, device=dev)
 
     def run_question():
-        if args.all_layers_call:
-            m.retrieve(-1, qq); m.attend(-1, qq, oq, lq)
+        if all_layers:
+            m.retrieve(-1, q_question); m.attend(-1, q_question, oq, lq)
         else:
             for l in range(L):
-                m.retrieve(l, qq[l]); m.attend(l, qq[l], oq[l], lq[l])
+                m.retrieve(l, q_question[l]); m.attend(l, q_question[l], oq[l], lq[l])
     run_question()
     torch.cuda.synchronize()
     t = time.perf_counter()
@@ -166,13 +205,21 @@ def main():
 
     # ---- decode steps ---------------------------------------------------------------
     qbase = q_dec.data_ptr()
-    step_bytes_q = L * layer_q_bytes
+    step_q_bytes = L * layer_q_bytes
     op, lp = out.data_ptr(), lse.data_ptr()
     out_layer, lse_layer = Hq * D * esz, Hq * 4
 
+    def retrieve_step(i):
+        qp = qbase + i * step_q_bytes
+        if all_layers:
+            m.retrieve_raw(-1, qp, 1)
+        else:
+            for l in range(L):
+                m.retrieve_raw(l, qp + l * layer_q_bytes, 1)
+
     def step(i):
-        qp = qbase + i * step_bytes_q
-        if args.all_layers_call:
+        qp = qbase + i * step_q_bytes
+        if all_layers:
             m.retrieve_raw(-1, qp, 1)
             m.attend_raw(-1, qp, 1, op, lp)
         else:
@@ -180,66 +227,55 @@ def main():
                 m.retrieve_raw(l, qp + l * layer_q_bytes, 1)
                 m.attend_raw(l, qp + l * layer_q_bytes, 1, op + l * out_layer, lp + l * lse_layer)
 
-    for i in range(W_steps):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t = time.perf_counter()
-    for i in range(W_steps, n_q):
+    for i in range(warmup, n_q):
         step(i)
     torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t
-    us_per_step = elapsed / K_steps * 1e6
+    us_per_step = (time.perf_counter() - t) / steps * 1e6
 
     # kernel-only time of the attention kernel, HIP events on the library's stream
+    ev_overhead = event_pair_overhead_us(torch)
     m.profile_enable(True)
-    for i in range(W_steps, n_q):
+    for i in range(warmup, n_q):
         step(i)
     kern_ms, launches = m.profile_read()
     m.profile_enable(False)
     # algorithmic bytes: K and V of the retrieved tokens, read once
     tok_total = 0
-    for i in range(W_steps, n_q):
-        qp = qbase + i * step_bytes_q
-        if args.all_layers_call:
-            m.retrieve_raw(-1, qp, 1)
-        else:
-            for l in range(L):
-                m.retrieve_raw(l, qp + l * layer_q_bytes, 1)
-        tok_total += sum(_n_tok_all(m, L))      # selected tokens of every unit for this step
+    for i in range(warmup, n_q):
+        retrieve_step(i)
+        tok_total += sum(n_tok_all(m, L))
     bytes_total = tok_total * 2 * D * esz
     bytes_per_launch = bytes_total / max(launches, 1)
-    kern_us = kern_ms * 1e3 / max(launches, 1)
-    achieved = bytes_per_launch / (kern_us * 1e-6) / 1e9 if kern_us > 0 else 0.0
-    step_gbps = (bytes_total / K_steps) / (us_per_step * 1e-6) / 1e9
+    kern_us_raw = kern_ms * 1e3 / max(launches, 1)
+    kern_us = max(kern_us_raw - ev_overhead, 1e-3)
+    achieved = bytes_per_launch / (kern_us * 1e-6) / 1e9
+    step_gbps = (bytes_total / steps) / (us_per_step * 1e-6) / 1e9
     stats = m.stats()
+    kernel = ("k_attend_decode_mfma" if stats.attend_impl == binding.ATTEND_MFMA else "k_attend_valu")
 
-    # ---- CPU oracle on the same decode steps (bounded sample) -----------------------
     cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(wl, K_all, V_all, q_dec[W_steps:], args.cpu_seconds, log)
+    if cpu_seconds > 0:
+        cpu = cpu_baseline(wl, K_all, V_all, q_dec[warmup:], cpu_seconds)
 
-    result = {
-        "metric": "decode_step_retrieve_attend_latency_us",
-        "value": round(us_per_step, 3),
-        "unit": "us",
-        "n_gpus": 1,
-        "steps": K_steps,
-        "warmup": W_steps,
-        "ms_per_step": round(us_per_step / 1e3, 6),
-        "higher_is_better": False,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": wl.kv_dtype,
-        "data": "synthetic",
+    m.close()
+    del K_all, V_all, m
+    torch.cuda.empty_cache()
+    return {
+        "us_per_step": us_per_step,
         "config": {"workload": wl.name, "layers": L, "q_heads": Hq, "kv_heads": wl.n_kv_heads,
                    "head_dim": D, "frames": F, "tokens_per_frame": T, "clusters": wl.n_clusters,
-                   "top_k": wl.top_k, "calls": "all_layers" if args.all_layers_call else "per_layer",
-                   "kv_splits": stats.last_n_splits},
+                   "top_k": wl.top_k, "calls": mode, "kv_splits": stats.last_n_splits},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
-                     "kernel": "k_attend_mfma" if stats.attend_impl == binding.ATTEND_MFMA else "k_attend_valu",
-                     "kernel_us": round(kern_us, 3), "bytes_per_launch": round(bytes_per_launch)},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode)),
+                     "kernel": kernel, "kernel_us": round(kern_us, 3),
+                     "kernel_us_with_event_pair": round(kern_us_raw, 3),
+                     "event_pair_us": round(ev_overhead, 3),
+                     "launches": int(launches), "bytes_per_launch": round(bytes_per_launch)},
         "cpu_baseline": cpu,
         "step_hbm_gbps": round(step_gbps, 1),
         "step_hbm_frac": round(step_gbps / HBM_PEAK_GBPS, 4),
@@ -249,24 +285,9 @@ def main():
         "question_ms": round(question_ms, 4),
         "parity_spot_check": checked,
     }
-    print(json.dumps(result))
 
 
-def _n_tok_all(m, L):
-    """Selected token count of every unit (one small D2H per layer)."""
-    import ctypes as C
-    H = m.cfg.n_kv_heads
-    out = []
-    buf = np.empty(H, dtype=np.int32)
-    for l in range(L):
-        rc = m._L.mosaic_get_selection(m._h, l, None, None, None, None, 0, buf.ctypes.data)
-        if rc != 0:
-            m._check(rc)
-        out.extend(buf.tolist())
-    return out
-
-
-def cpu_baseline(wl, K_all, V_all, q_steps, budget_s, log):
+def cpu_baseline(wl, K_all, V_all, q_steps, budget_s):
     """The oracle as it stands, on this host: clustering of the sampled units'
     streams (untimed here), then timed decode steps (retrieve + attend), units
     in parallel threads (the C code releases the GIL)."""
@@ -280,20 +301,14 @@ def cpu_baseline(wl, K_all, V_all, q_steps, budget_s, log):
     threads = min(len(sample), 16, os.cpu_count() or 1)
     t0 = time.time()
     state = {}
-
-    def prepare(lh):
-        l, h = lh
+    for (l, h) in sample:                       # sequential: bounds host memory
         Ku = inputs.unit_pages(K_all, l, h)
         Vu = inputs.unit_pages(V_all, l, h)
         o = orc.OracleUnit(wl.n_clusters, D, T, F, wl.warmup_frames, wl.lloyd_iters, wl.recluster_every)
         ti = time.perf_counter()
         for f in range(F):
             o.ingest(Ku[f])
-        return lh, (o, Ku.reshape(-1, D), Vu.reshape(-1, D), time.perf_counter() - ti)
-
-    for lh in sample:                           # sequential: bounds host memory
-        k, v = prepare(lh)
-        state[k] = v
+        state[(l, h)] = (o, Ku.reshape(-1, D), Vu.reshape(-1, D), time.perf_counter() - ti)
     ingest_s = sum(v[3] for v in state.values()) / len(state)     # per unit, one thread
     log(f"[bench] oracle: {len(sample)} unit streams clustered in {time.time() - t0:.1f}s "
         f"({F / ingest_s:.0f} frames/s per unit-thread)")
@@ -318,6 +333,56 @@ def cpu_baseline(wl, K_all, V_all, q_steps, budget_s, log):
             "sample": f"{done} decode steps x {len(sample)} of {len(units)} units "
                       f"(time scaled to all units), {threads} threads",
             "ingest_frames_per_s_per_thread": round(F / ingest_s, 1)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (units are independent; "
+              "no collective path exists); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    from paper_2604_10060_amd import inputs
+
+    wl = inputs.CONFIGS[int(args.workload[-1])]
+    if args.layers:
+        wl = wl.scaled(n_layers=args.layers)
+    if args.frames:
+        wl = wl.scaled(n_frames=args.frames)
+    main_leg = run_leg(wl, steps=args.steps, warmup=args.warmup, all_layers=args.all_layers_call,
+                       check_units=args.check_units,
+                       cpu_seconds=0 if args.no_cpu_baseline else args.cpu_seconds,
+                       calibrate=args.calibrate_copy)
+    extra = None
+    if not args.no_extra and args.workload == "cfg1" and not (args.layers or args.frames):
+        extra = {}
+        for all_layers in (False, True):
+            leg = run_leg(inputs.CONFIGS[2], steps=args.extra_steps, warmup=4, all_layers=all_layers,
+                          check_units=1 if all_layers else 0, cpu_seconds=0)
+            extra["cfg2_" + leg["config"]["calls"]] = {
+                "decode_step_us": round(leg["us_per_step"], 2), "config": leg["config"],
+                "roofline": leg["roofline"], "step_hbm_gbps": leg["step_hbm_gbps"],
+                "step_hbm_frac": leg["step_hbm_frac"],
+                "ingest_frames_per_s": leg["ingest_frames_per_s"],
+                "ingest_frames_per_s_batch16": leg["ingest_frames_per_s_batch16"],
+                "question_ms": leg["question_ms"], "parity_spot_check": leg["parity_spot_check"]}
+    us = main_leg.pop("us_per_step")
+    result = {
+        "metric": "decode_step_retrieve_attend_latency_us",
+        "value": round(us, 3),
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(us / 1e3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.kv_dtype,
+        "data": "synthetic",
+    }
+    result.update(main_leg)
+    result["extra"] = extra
+    print(json.dumps(result))
 
 
 if __name__ == "__main__":

@@ -164,6 +164,12 @@ int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats);
 int32_t mosaic_profile_enable(mosaic_ctx *ctx, int32_t on);
 int32_t mosaic_profile_read(mosaic_ctx *ctx, double *attend_kernel_ms, int64_t *launches);
 
+/* Counter calibration for profilers: a plain grid-stride copy of `bytes` bytes
+ * (multiple of 16; both device pointers 16-byte aligned) on `stream` (hipStream_t
+ * as void*).  It reads and writes exactly `bytes` bytes, so a hardware byte
+ * counter read for this kernel gives the counter's scale.  Not part of the path. */
+int32_t mosaic_calibration_copy(void *dst_dev, const void *src_dev, size_t bytes, void *stream);
+
 /* Text of the last error on this handle (never NULL).  ctx may be NULL: then
  * the text of the last failed mosaic_create / mosaic_workspace_size. */
 const char *mosaic_last_error(const mosaic_ctx *ctx);

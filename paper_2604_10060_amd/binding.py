@@ -26,7 +26,7 @@ EXPORTS = (
     "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_attend",
     "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries",
     "mosaic_get_selection", "mosaic_get_stats", "mosaic_profile_enable",
-    "mosaic_profile_read", "mosaic_last_error",
+    "mosaic_profile_read", "mosaic_calibration_copy", "mosaic_last_error",
 )
 
 
@@ -85,6 +85,7 @@ def load_library():
     L.mosaic_get_stats.argtypes = [vp, C.POINTER(Stats)]
     L.mosaic_profile_enable.argtypes = [vp, i32]
     L.mosaic_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    L.mosaic_calibration_copy.argtypes = [vp, vp, sz, vp]
     L.mosaic_last_error.argtypes = [vp]
     L.mosaic_last_error.restype = C.c_char_p
     for name in EXPORTS:

@@ -106,9 +106,25 @@ int choose_splits(const mosaic_ctx *ctx, int n_units, int Tq) {
     return (int)std::max<long long>(1, s);
 }
 
+__global__ __launch_bounds__(256) void k_calibration_copy(uint4 *dst, const uint4 *src, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+         i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
 } // namespace
 
 extern "C" {
+
+int32_t mosaic_calibration_copy(void *dst_dev, const void *src_dev, size_t bytes, void *stream) {
+    if (!dst_dev || !src_dev || bytes % 16 || ((uintptr_t)dst_dev | (uintptr_t)src_dev) % 16)
+        return fail(nullptr, MOSAIC_EINVAL, "calibration copy needs 16-byte aligned pointers and size");
+    if (bytes == 0) return MOSAIC_OK;
+    k_calibration_copy<<<2048, 256, 0, (hipStream_t)stream>>>((uint4 *)dst_dev, (const uint4 *)src_dev, bytes / 16);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(nullptr, e, "calibration copy launch");
+    return MOSAIC_OK;
+}
 
 int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes) {
     std::string why;

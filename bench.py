@@ -15,9 +15,8 @@ HBM), once with per-layer calls and once with all layers in one call.
 
 `roofline` refers to the split-KV attention kernel (the dominant kernel):
 algorithmic bytes = K and V of the retrieved tokens read once, divided by that
-kernel's mean duration.  The duration is measured with HIP events recorded on
-the library's stream around every launch; the mean cost of an empty event pair
-on the same stream is measured too and subtracted (both are reported).
+kernel's mean duration, measured with a HIP start/stop event pair attached to
+every launch on the library's stream (the kernel's own begin/end timestamps).
 `cpu_baseline` is the fp64 CPU oracle timed on this host on a bounded sample of
 the same decode steps.
 """
@@ -39,7 +38,11 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 # HBM bytes per launch of the decode attention kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter read on
 # k_calibration_copy, a 256 MiB copy): see profiles/.  Keyed by (workload, calls).
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg1_single_layer_hbm", "per_layer"): 27_330_000,     # 26.40 MB read + 0.93 MB written
+    ("cfg2_full_stack_hbm", "per_layer"): 118_050_000,      # 117.12 MB + 0.93 MB
+    ("cfg2_full_stack_hbm", "all_layers"): 3_281_480_000,   # 3273.71 MB + 7.77 MB
+}
 
 
 def log(*a):
@@ -79,18 +82,6 @@ def n_tok_all(m, L):
             m._check(rc)
         out.extend(buf.tolist())
     return out
-
-
-def event_pair_overhead_us(torch, n=200):
-    """Mean elapsed time of an empty HIP event pair on the current stream."""
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-    x = torch.zeros(1024, device="cuda:0")
-    for a, b in evs:
-        x.add_(1.0)            # keep the stream busy like a preceding kernel would
-        a.record()
-        b.record()
-    torch.cuda.synchronize()
-    return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
 
 
 def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrate=False):
@@ -236,8 +227,7 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
     torch.cuda.synchronize()
     us_per_step = (time.perf_counter() - t) / steps * 1e6
 
-    # kernel-only time of the attention kernel, HIP events on the library's stream
-    ev_overhead = event_pair_overhead_us(torch)
+    # kernel-only time of the attention kernel: HIP start/stop events attached to each launch
     m.profile_enable(True)
     for i in range(warmup, n_q):
         step(i)
@@ -250,8 +240,7 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
         tok_total += sum(n_tok_all(m, L))
     bytes_total = tok_total * 2 * D * esz
     bytes_per_launch = bytes_total / max(launches, 1)
-    kern_us_raw = kern_ms * 1e3 / max(launches, 1)
-    kern_us = max(kern_us_raw - ev_overhead, 1e-3)
+    kern_us = kern_ms * 1e3 / max(launches, 1)
     achieved = bytes_per_launch / (kern_us * 1e-6) / 1e9
     step_gbps = (bytes_total / steps) / (us_per_step * 1e-6) / 1e9
     stats = m.stats()
@@ -273,8 +262,6 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode)),
                      "kernel": kernel, "kernel_us": round(kern_us, 3),
-                     "kernel_us_with_event_pair": round(kern_us_raw, 3),
-                     "event_pair_us": round(ev_overhead, 3),
                      "launches": int(launches), "bytes_per_launch": round(bytes_per_launch)},
         "cpu_baseline": cpu,
         "step_hbm_gbps": round(step_gbps, 1),

@@ -158,7 +158,8 @@ int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32
 int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats);
 
 /* Kernel timing for benchmarks: when enabled, the split-KV attention kernel of
- * every mosaic_attend is bracketed by HIP events on the context's stream.
+ * every mosaic_attend is launched with a HIP start/stop event pair that receives
+ * the kernel's own begin and end timestamps on the context's stream.
  * mosaic_profile_read synchronises and returns the summed kernel time and the
  * number of launches since the last read (host pointers), then clears them. */
 int32_t mosaic_profile_enable(mosaic_ctx *ctx, int32_t on);

@@ -306,12 +306,10 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t
         }
         ev0 = ctx->ev[ctx->ev_used]; ev1 = ctx->ev[ctx->ev_used + 1];
         ctx->ev_used += 2;
-        (void)hipEventRecord(ev0, ctx->stream);
     }
     e = ctx->impl == MOSAIC_ATTEND_MFMA
-            ? launch_attend_mfma(ctx->dv, u0, nu, q_dev, n_q_tokens, S, ctx->stream)
-            : launch_attend_valu(ctx->dv, u0, nu, q_dev, n_q_tokens, S, ctx->stream);
-    if (ev1) (void)hipEventRecord(ev1, ctx->stream);
+            ? launch_attend_mfma(ctx->dv, u0, nu, q_dev, n_q_tokens, S, ctx->stream, ev0, ev1)
+            : launch_attend_valu(ctx->dv, u0, nu, q_dev, n_q_tokens, S, ctx->stream, ev0, ev1);
     if (e != hipSuccess) return fail_hip(ctx, e, "attend launch");
     e = launch_attend_combine(ctx->dv, u0, nu, n_q_tokens, S, out_dev, lse_dev, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "combine launch");

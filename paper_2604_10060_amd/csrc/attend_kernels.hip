@@ -242,15 +242,15 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
 } // namespace
 
 hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
-                              int n_splits, hipStream_t s) {
+                              int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
-    dim3 grid(n_splits, NT, n_units);
+    const dim3 grid(n_splits, NT, n_units), block(kBlock);
     if (dv.esize == 4) {
-        if (dv.D == 64) k_attend_valu<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_splits);
-        else k_attend_valu<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_splits);
+        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<float, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, (const float *)q, Tq, n_splits);
+        else hipExtLaunchKernelGGL((k_attend_valu<float, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, (const float *)q, Tq, n_splits);
     } else {
-        if (dv.D == 64) k_attend_valu<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_splits);
-        else k_attend_valu<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_splits);
+        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, (const unsigned short *)q, Tq, n_splits);
+        else hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, (const unsigned short *)q, Tq, n_splits);
     }
     return hipGetLastError();
 }

@@ -292,17 +292,18 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
 } // namespace
 
 hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
-                              int n_splits, hipStream_t s) {
+                              int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
     const unsigned short *qq = (const unsigned short *)q;
+    const dim3 block(kBlock);
     if (NT == 1) {
-        dim3 grid(n_splits, 1, n_units);
-        if (dv.D == 64) k_attend_decode_mfma<64><<<grid, kBlock, 0, s>>>(dv, u0, qq, Tq, n_splits);
-        else k_attend_decode_mfma<128><<<grid, kBlock, 0, s>>>(dv, u0, qq, Tq, n_splits);
+        const dim3 grid(n_splits, 1, n_units);
+        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_decode_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits);
+        else hipExtLaunchKernelGGL(k_attend_decode_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits);
     } else {
-        dim3 grid(n_splits, (NT + 3) / 4, n_units);
-        if (dv.D == 64) k_attend_prefill_mfma<64><<<grid, kBlock, 0, s>>>(dv, u0, qq, Tq, n_splits, NT);
-        else k_attend_prefill_mfma<128><<<grid, kBlock, 0, s>>>(dv, u0, qq, Tq, n_splits, NT);
+        const dim3 grid(n_splits, (NT + 3) / 4, n_units);
+        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_prefill_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, NT);
+        else hipExtLaunchKernelGGL(k_attend_prefill_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, NT);
     }
     return hipGetLastError();
 }

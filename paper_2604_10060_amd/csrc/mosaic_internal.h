@@ -1,6 +1,7 @@
 // Internal declarations shared by the HIP sources of libmosaic (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string>
 #include <vector>
@@ -74,10 +75,11 @@ hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void
                            int n_frames, int score_mode, hipStream_t s);
 hipError_t launch_expand_tok_idx(const DeviceView &dv, int u0, int n_units, hipStream_t s);
 // n_splits chosen by the caller; partial entries needed = n_units * NT * n_splits
+// ev0/ev1 (may be null) receive the kernel's own start/stop timestamps
 hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
-                              int n_splits, hipStream_t s);
+                              int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
-                              int n_splits, hipStream_t s);
+                              int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
                                  void *out, float *lse, hipStream_t s);
 

@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg4"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count")
     ap.add_argument("--all-layers-call", action="store_true",
@@ -274,6 +274,88 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
     }
 
 
+def run_prefill_leg(n_streams=8, check=True):
+    """Config 4: `n_streams` independent video streams, each with its own context
+    on its own HIP stream; one 256-token question chunk per stream is prefilled
+    against the retrieved KV (the MFMA path).  Reports the MFMA roofline of
+    k_attend_prefill_mfma and the aggregate question latency."""
+    import torch
+    from paper_2604_10060_amd import binding, inputs
+    dev = "cuda:0"
+    ctxs = []
+    for sid in range(n_streams):
+        wl = inputs.cfg4_stream(sid)
+        st = inputs.SceneStream(wl, device=dev)
+        K, V = st.frames(0, wl.n_frames)
+        stream = torch.cuda.Stream(device=dev)
+        with torch.cuda.stream(stream):
+            m = binding.Mosaic(binding.config_for(wl), device=dev, stream=stream)
+            for f in range(0, wl.n_frames, 64):
+                m.ingest_frame(K[f:f + 64], V[f:f + 64])
+            q = st.question(st.draw_scene(), wl.question_tokens, 0)[0].contiguous()
+            out = torch.empty_like(q)
+            lse = torch.empty(q.shape[:-1], dtype=torch.float32, device=dev)
+        ctxs.append((wl, st, K, V, m, q, out, lse, stream))
+    torch.cuda.synchronize()
+    wl0 = ctxs[0][0]
+    Tq, Hq, D, G = wl0.question_tokens, wl0.n_q_heads, wl0.head_dim, wl0.group
+
+    def issue():
+        for (wl, st, K, V, m, q, out, lse, stream) in ctxs:
+            m.retrieve_raw(0, q.data_ptr(), Tq)
+            m.attend_raw(0, q.data_ptr(), Tq, out.data_ptr(), lse.data_ptr())
+    issue()
+    torch.cuda.synchronize()
+    reps = 5
+    t = time.perf_counter()
+    for _ in range(reps):
+        issue()
+    torch.cuda.synchronize()
+    wall_us = (time.perf_counter() - t) / reps * 1e6
+    # kernel time and flops of the prefill attention kernel, one stream at a time
+    kern_us_total, flops_total, tok_total = 0.0, 0.0, 0
+    for (wl, st, K, V, m, q, out, lse, stream) in ctxs:
+        m.profile_enable(True)
+        for _ in range(reps):
+            m.retrieve_raw(0, q.data_ptr(), Tq)
+            m.attend_raw(0, q.data_ptr(), Tq, out.data_ptr(), lse.data_ptr())
+        ms, n = m.profile_read()
+        m.profile_enable(False)
+        ntok = sum(n_tok_all(m, 1))                     # retrieved tokens, all KV heads
+        kern_us_total += ms * 1e3 / n
+        flops_total += 4.0 * Tq * G * ntok * D          # QK^T and PV, all query heads
+        tok_total += ntok
+    checked = None
+    if check:
+        from tests import harness
+        from oracle import mosaic_oracle as orc
+        wl, st, K, V, m, q, out, lse, stream = ctxs[5]   # a low-coherence stream
+        o = orc.OracleUnit(wl.n_clusters, D, wl.tokens_per_frame, wl.n_frames, wl.warmup_frames,
+                           wl.lloyd_iters, wl.recluster_every)
+        Ku = inputs.unit_pages(K, 0, 1)
+        for f in range(wl.n_frames):
+            o.ingest(Ku[f])
+        rep = harness.Report()
+        with torch.cuda.stream(stream):
+            harness.query_with_parity(m, wl, q[None], {(0, 1): o}, K, V, rep)
+        checked = {"stream": 5, "unit": [0, 1], "max_out_err": rep.max_out_err, "max_lse_err": rep.max_lse_err}
+    tflops = flops_total / (kern_us_total * 1e-6) / 1e12
+    for c in ctxs:
+        c[4].close()
+    del ctxs
+    torch.cuda.empty_cache()
+    return {"config": {"workload": "cfg4_prefill_stream x%d" % n_streams, "question_tokens": Tq,
+                       "frames": wl0.n_frames, "clusters": wl0.n_clusters, "top_k": wl0.top_k},
+            "question_us_all_streams_concurrent": round(wall_us, 1),
+            "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                         "frac": round(tflops / 2500.0, 4), "traffic": None,
+                         "kernel": "k_attend_prefill_mfma",
+                         "kernel_us": round(kern_us_total / n_streams, 2),
+                         "flop_per_launch": round(flops_total / n_streams)},
+            "retrieved_tokens_per_stream": tok_total // n_streams,
+            "parity_spot_check": checked}
+
+
 def cpu_baseline(wl, K_all, V_all, q_steps, budget_s):
     """The oracle as it stands, on this host: clustering of the sampled units'
     streams (untimed here), then timed decode steps (retrieve + attend), units
@@ -330,6 +412,9 @@ def main():
         sys.exit(2)
     from paper_2604_10060_amd import inputs
 
+    if args.workload == "cfg4":
+        print(json.dumps(run_prefill_leg(check=args.check_units > 0)))
+        return
     wl = inputs.CONFIGS[int(args.workload[-1])]
     if args.layers:
         wl = wl.scaled(n_layers=args.layers)
@@ -352,6 +437,7 @@ def main():
                 "ingest_frames_per_s": leg["ingest_frames_per_s"],
                 "ingest_frames_per_s_batch16": leg["ingest_frames_per_s_batch16"],
                 "question_ms": leg["question_ms"], "parity_spot_check": leg["parity_spot_check"]}
+        extra["cfg4_prefill_8_streams"] = run_prefill_leg()
     us = main_leg.pop("us_per_step")
     result = {
         "metric": "decode_step_retrieve_attend_latency_us",

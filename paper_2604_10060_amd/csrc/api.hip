@@ -89,18 +89,29 @@ Layout make_layout(const mosaic_config &c) {
     return L;
 }
 
-// KV splits for one attend call: enough workgroups to cover the chip a few
-// times over, at least 4 chunks (one per wavefront) per workgroup, bounded by
-// the partial-buffer capacity.
+// KV splits for one attend call, bounded by the partial-buffer capacity.
 int choose_splits(const mosaic_ctx *ctx, int n_units, int Tq) {
     const DeviceView &dv = ctx->dv;
     const long long NT = ((long long)Tq * dv.G + kRowTile - 1) / kRowTile;
-    const long long row_blocks = NT == 1 ? 1 : (ctx->impl == MOSAIC_ATTEND_MFMA ? (NT + 3) / 4 : NT);
+    const bool mfma = ctx->impl == MOSAIC_ATTEND_MFMA;
+    const long long row_blocks = NT == 1 ? 1 : (mfma ? (NT + 15) / 16 : NT);
     const long long est_pages = std::max<long long>(1, (ctx->n_frames * dv.k + dv.C - 1) / dv.C);
     const long long est_chunks = est_pages * dv.chunks_per_page;
-    const long long target = 2048;
-    long long s = (target + n_units * row_blocks - 1) / (n_units * row_blocks);
-    s = std::min(s, std::max<long long>(1, est_chunks / 4));
+    long long s;
+    if (NT > 1 && mfma) {
+        // MFMA-bound multi-tile launches: every split re-writes 16 x D partial rows per
+        // tile, so only as many splits as needed to cover the chip once, each with at
+        // least 8 chunks; a multiple of 8 keeps the workgroups that share a
+        // (unit, split) on one XCD (workgroup ids congruent mod 8)
+        s = (256 + n_units * row_blocks - 1) / (n_units * row_blocks);
+        s = std::min(s, std::max<long long>(1, est_chunks / 8));
+        if (s >= 8) s = s / 8 * 8;
+    } else {
+        // bandwidth/latency-bound: cover the chip several times over, at least 4
+        // chunks (one per wavefront) per workgroup
+        s = (2048 + n_units * row_blocks - 1) / (n_units * row_blocks);
+        s = std::min(s, std::max<long long>(1, est_chunks / 4));
+    }
     s = std::min<long long>(s, kMaxSplits);
     s = std::min(s, std::max<long long>(1, dv.part_entries / (n_units * NT)));
     return (int)std::max<long long>(1, s);

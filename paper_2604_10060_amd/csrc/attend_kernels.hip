@@ -53,13 +53,15 @@ __device__ __forceinline__ float group16_sumf(float x) {
     return x;
 }
 
-// grid (n_splits, NT, n_units), 256 threads: thread (row = tid/16, tl = tid%16)
+// grid (n_units * n_splits, NT), 256 threads: thread (row = tid/16, tl = tid%16)
 template <typename E, int D>
-__global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, const E *q, int Tq,
-                                                        int n_splits) {
+__global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, int n_units, const E *q,
+                                                        int Tq) {
     constexpr int DPT = D / 16;   // output channels per thread
     constexpr int CG = D / 8;     // 8-element groups per token row
-    const int split = blockIdx.x, tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc;
+    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, gridDim.x, blockIdx.x);
+    if (slot.uc < 0) return;      // block-uniform: no barrier reached yet
+    const int split = slot.split, n_splits = slot.S, tile = blockIdx.y, uc = slot.uc, u = u0 + uc;
     const int NT = gridDim.y, tid = threadIdx.x, row = tid / 16, tl = tid % 16;
     const int G = dv.G, Hq = dv.Hq, T = dv.T;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, c
         }
         __syncthreads();
     }
-    const size_t entry = ((size_t)uc * NT + tile) * n_splits + split;
+    const size_t entry = (size_t)slot.base * NT + (size_t)tile * n_splits + split;
 #pragma unroll
     for (int i = 0; i < DPT; ++i) dv.part_o[(entry * kRowTile + row) * D + tl + 16 * i] = acc[i];
     if (tl == 0) {
@@ -146,13 +148,15 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, c
 // one row tile; its 8 groups of 32 threads share the splits, so the partial
 // buffer is read with many independent 128-byte loads in flight.
 template <typename E, int D>
-__global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0, int Tq,
-                                                           int n_splits, E *out, float *lse) {
+__global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0, int n_units, int Tq,
+                                                           int B, E *out, float *lse) {
     const int dg = blockIdx.x, tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc, NT = gridDim.y;
     const int tid = threadIdx.x;
     const int G = dv.G, Hq = dv.Hq, lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
     const int rows = min(kRowTile, R - tile * kRowTile);
-    const size_t e0 = ((size_t)uc * NT + tile) * n_splits;
+    const SplitSlot slot = split_slot<true>(dv.n_sel + u0, n_units, B, uc);
+    const int n_splits = slot.S;                 // 0 if the unit retrieved nothing
+    const size_t e0 = (size_t)slot.base * NT + (size_t)tile * n_splits;
     __shared__ float w_sh[kMaxSplits][kRowTile];
     __shared__ float pm[16][kRowTile], pl[16][kRowTile];
     __shared__ float M_sh[kRowTile], L_sh[kRowTile];
@@ -244,13 +248,13 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
 hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                               int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
-    const dim3 grid(n_splits, NT, n_units), block(kBlock);
+    const dim3 grid(n_units * n_splits, NT), block(kBlock);
     if (dv.esize == 4) {
-        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<float, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, (const float *)q, Tq, n_splits);
-        else hipExtLaunchKernelGGL((k_attend_valu<float, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, (const float *)q, Tq, n_splits);
+        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<float, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const float *)q, Tq);
+        else hipExtLaunchKernelGGL((k_attend_valu<float, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const float *)q, Tq);
     } else {
-        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, (const unsigned short *)q, Tq, n_splits);
-        else hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, (const unsigned short *)q, Tq, n_splits);
+        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const unsigned short *)q, Tq);
+        else hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const unsigned short *)q, Tq);
     }
     return hipGetLastError();
 }
@@ -258,13 +262,14 @@ hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const v
 hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
                                  void *out, float *lse, hipStream_t s) {
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
+    const int B = n_units * n_splits;
     dim3 grid(dv.D / 32, NT, n_units);
     if (dv.esize == 4) {
-        if (dv.D == 64) k_attend_combine<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (float *)out, lse);
-        else k_attend_combine<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (float *)out, lse);
+        if (dv.D == 64) k_attend_combine<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, (float *)out, lse);
+        else k_attend_combine<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, (float *)out, lse);
     } else {
-        if (dv.D == 64) k_attend_combine<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (unsigned short *)out, lse);
-        else k_attend_combine<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, u0, Tq, n_splits, (unsigned short *)out, lse);
+        if (dv.D == 64) k_attend_combine<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, (unsigned short *)out, lse);
+        else k_attend_combine<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, (unsigned short *)out, lse);
     }
     return hipGetLastError();
 }

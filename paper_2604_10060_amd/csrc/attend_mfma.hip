@@ -42,49 +42,88 @@ __device__ __forceinline__ unsigned int pack_bf16(float a, float b) {
 __device__ __forceinline__ float bf16_lo(unsigned int w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned int w) { return __uint_as_float(w & 0xffff0000u); }
 
-// One 32-token step of the online softmax for the 16 query rows of a tile.
-// kf: 2 key tiles x KK k-steps; vf: DB channel blocks.  n_valid = tokens of the
-// chunk that exist (the rest are clamped re-reads and get weight 0).
+// Online softmax with a lazily updated reference: the running reference m of a
+// row (log2 domain) is only raised -- and the accumulators only rescaled -- when
+// some logit exceeds it by more than kLazy; until then weights are
+// exp2(s - m) <= 2^kLazy, exact in fp32/bf16 range, and (m, sum, O) stay a
+// consistent triple for the later log-sum-exp merge.  The cross-lane maximum and
+// the rescale therefore leave the common path.
+constexpr float kLazy = 8.0f;
+
+// R row tiles of 16 query rows share one chunk's operands (kf: 2 key tiles x KK
+// k-steps; vf: DB channel blocks).  n_valid = tokens of the chunk that exist
+// (the rest are clamped re-reads and get weight 0).  Three phases -- all logit
+// MFMAs, all softmax arithmetic, all output MFMAs -- so the independent chains
+// of the tiles overlap.
+template <int D, int R>
+__device__ __forceinline__ void chunk_step_multi(const bf16x8 (&kf)[2 * (D / 32)], const bf16x8 (&vf)[D / 16],
+                                                 const bf16x8 (&qf)[R][D / 32], int n_valid, int g,
+                                                 float sl2, f32x4 (&acc)[R][D / 16], float (&m)[R],
+                                                 float (&l)[R]) {
+    constexpr int KK = D / 32, DB = D / 16;
+    f32x4 s[R][2];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int tau = 0; tau < 2; ++tau) {
+            s[r][tau] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+                s[r][tau] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tau * KK + kk], qf[r][kk], s[r][tau], 0, 0, 0);
+        }
+    if (n_valid < kChunk) {             // ragged last chunk of a page (wave-uniform)
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (8 * g + j >= n_valid) s[r][j / 4][j % 4] = -INFINITY;
+    }
+    bf16x8 pf[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float c0 = fmaxf(fmaxf(s[r][0][0], s[r][0][1]), fmaxf(s[r][0][2], s[r][0][3]));
+        const float c1 = fmaxf(fmaxf(s[r][1][0], s[r][1][1]), fmaxf(s[r][1][2], s[r][1][3]));
+        float cm = fmaxf(c0, c1) * sl2;
+        if (__builtin_amdgcn_ballot_w64(cm > m[r] + kLazy)) {   // rare, wave-uniform
+            cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
+            cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
+            const float mnew = fmaxf(m[r], cm);
+            const float alpha = __builtin_amdgcn_exp2f(m[r] - mnew);
+            l[r] *= alpha;
+            m[r] = mnew;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) acc[r][db] = acc[r][db] * alpha;
+        }
+        const float nm = -m[r];
+        unsigned int pw[4];
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r][(2 * j) / 4][(2 * j) % 4], sl2, nm));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r][(2 * j + 1) / 4][(2 * j + 1) % 4], sl2, nm));
+            pw[j] = pack_bf16(p0, p1);
+            psum += bf16_lo(pw[j]) + bf16_hi(pw[j]);   // the normaliser uses the rounded weights
+        }
+        l[r] += psum;
+        pf[r] = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            acc[r][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf[r], acc[r][db], 0, 0, 0);
+}
+
+// Single-tile form used by the decode kernel.
 template <int D>
 __device__ __forceinline__ void chunk_step(const bf16x8 (&kf)[2 * (D / 32)], const bf16x8 (&vf)[D / 16],
                                            const bf16x8 (&qf)[D / 32], int n_valid, int g, float sl2,
                                            f32x4 (&acc)[D / 16], float &m, float &l) {
-    constexpr int KK = D / 32, DB = D / 16;
-    f32x4 s[2];
-#pragma unroll
-    for (int tau = 0; tau < 2; ++tau) {
-        s[tau] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-            s[tau] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tau * KK + kk], qf[kk], s[tau], 0, 0, 0);
-    }
-    float sv[8];
-    float cmax = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        sv[j] = (8 * g + j) < n_valid ? s[j / 4][j % 4] * sl2 : -INFINITY;
-        cmax = fmaxf(cmax, sv[j]);
-    }
-    cmax = fmaxf(cmax, __shfl_xor(cmax, 16, 64));
-    cmax = fmaxf(cmax, __shfl_xor(cmax, 32, 64));
-    const float mnew = fmaxf(m, cmax);
-    const float alpha = __builtin_amdgcn_exp2f(m - mnew);
-    unsigned int pw[4];
-    float psum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        pw[j] = pack_bf16(__builtin_amdgcn_exp2f(sv[2 * j] - mnew),
-                          __builtin_amdgcn_exp2f(sv[2 * j + 1] - mnew));
-        psum += bf16_lo(pw[j]) + bf16_hi(pw[j]);   // the normaliser uses the rounded weights
-    }
-    l = l * alpha + psum;
-    m = mnew;
-    const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-        acc[db] = acc[db] * alpha;
-        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, acc[db], 0, 0, 0);
-    }
+    const bf16x8 (&q1)[1][D / 32] = reinterpret_cast<const bf16x8 (&)[1][D / 32]>(qf);
+    f32x4 (&a1)[1][D / 16] = reinterpret_cast<f32x4 (&)[1][D / 16]>(acc);
+    float (&m1)[1] = reinterpret_cast<float (&)[1]>(m);
+    float (&l1)[1] = reinterpret_cast<float (&)[1]>(l);
+    chunk_step_multi<D, 1>(kf, vf, q1, n_valid, g, sl2, a1, m1, l1);
 }
 
 // Issue the 16-byte operand loads of one chunk.  Tokens beyond the page's T are
@@ -125,25 +164,26 @@ __device__ __forceinline__ void load_q(const DeviceView &dv, const unsigned shor
 
 // ---------------------------------------------------------------------------
 // Decode shape: at most 16 query rows per unit (one row tile).
-// grid (n_splits, 1, n_units), 4 waves.  Chunks are dealt round-robin:
-// wave w of split s takes chunks s + S*(w + 4*i), so chunk indices (and the
-// page ids behind them) are known before the selection size has arrived, and
-// the next chunk's operands are in flight while the current one is reduced.
+// grid (n_units * n_splits), 4 waves; split_slot() shares the workgroups out
+// over the units by retrieved size.  Inside a unit chunks are dealt round-robin:
+// wave w of split s takes chunks s + S*(w + 4*i); the next chunk's operands are
+// in flight while the current one is reduced.
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv, int u0,
-                                                                  const unsigned short *q, int Tq,
-                                                                  int n_splits) {
+__global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv, int u0, int n_units,
+                                                                  const unsigned short *q, int Tq) {
     constexpr int KK = D / 32, DB = D / 16;
-    const int split = blockIdx.x, uc = blockIdx.z, u = u0 + uc;
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
+    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, gridDim.x, blockIdx.x);
+    if (slot.uc < 0) return;                       // block-uniform: no barrier reached yet
+    const int uc = slot.uc, u = u0 + uc, split = slot.split, S = slot.S;
     const int T = dv.T, F = dv.F, cpp = dv.chunks_per_page;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * dv.G;
     const int *sel = dv.sel_pages + (size_t)u * F;
-    const int stride = 4 * n_splits, first = split + n_splits * wave;
+    const int stride = 4 * S, first = split + S * wave;
 
     const int nsel = dv.n_sel[u];
-    // page ids of this wave's first 64 chunks, one per lane, loaded speculatively
+    // page ids of this wave's first 64 chunks, one per lane
     int pgs = sel[min((first + stride * lane) / cpp, F - 1)];
     bf16x8 qf[KK];
     load_q<D>(dv, q, lc, h, Tq, n, g, qf);
@@ -207,7 +247,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
         wgt[w] = M > -INFINITY ? __builtin_amdgcn_exp2f(m_sh[w][row] - M) : 0.f;
         Lsum += wgt[w] * l_sh[w][row];
     }
-    const size_t entry = (size_t)uc * n_splits + split;   // one row tile
+    const size_t entry = (size_t)slot.base + split;        // one row tile
     float *po = dv.part_o + (entry * kRowTile + row) * D;
 #pragma unroll
     for (int d = dl; d < D; d += 16) {
@@ -223,26 +263,43 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
 }
 
 // ---------------------------------------------------------------------------
-// Multi-token questions: wave w owns row tile 4*blockIdx.y + w and walks the
-// contiguous chunk range of its split, next chunk prefetched.
-// grid (n_splits, ceil(NT/4), n_units).  With n_splits a multiple of 8 the
-// workgroups that re-read the same keys/values land on the same XCD (ids
-// congruent mod 8), so the re-reads hit that XCD's L2.
+// Multi-token questions (MFMA-bound).  A workgroup owns 256 query rows: wave w
+// holds kPrefillTiles row tiles of 16 in registers and all four waves walk the
+// same chunk range, so each 32-token K/V chunk is fetched from memory once per
+// workgroup, staged in LDS (double-buffered, next chunk's global loads in flight
+// during the current chunk's MFMAs) and read as MFMA operands by every wave.
+// LDS rows are padded (K: +16 B, V: +16 B) and the K rows are stored in MFMA
+// slot order so that the 16-byte operand reads are bank-conflict free.
+// grid (n_units * n_splits, ceil(NT / 16)); split_slot() shares the split
+// workgroups out over the units by retrieved size.  With the x extent a multiple
+// of 8 the workgroups sharing a (unit, split) have ids congruent mod 8, i.e. land
+// on the same XCD, and their K/V re-reads hit that XCD's L2.
 // ---------------------------------------------------------------------------
+constexpr int kPrefillTiles = 4;   // row tiles per wave
+
 template <int D>
-__global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv, int u0,
+__global__ __launch_bounds__(kBlock, 1) void k_attend_prefill_mfma(DeviceView dv, int u0, int n_units,
                                                                    const unsigned short *q, int Tq,
-                                                                   int n_splits, int NT) {
-    constexpr int KK = D / 32, DB = D / 16;
-    const int split = blockIdx.x, uc = blockIdx.z, u = u0 + uc;
+                                                                   int NT) {
+    constexpr int KK = D / 32, DB = D / 16, RTW = kPrefillTiles;
+    constexpr int KROW = D + 8, VROW = kChunk + 8;       // LDS row strides in elements
+    constexpr int KPIECES = kChunk * D / 8, VPIECES = D * kChunk / 8;   // 16-byte pieces per chunk
+    constexpr int KPT = KPIECES / kBlock, VPT = VPIECES / kBlock;       // pieces per thread
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
-    const int tile = (int)blockIdx.y * 4 + wave;
-    if (tile >= NT) return;   // no barriers in this kernel
+    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, gridDim.x, blockIdx.x);
+    if (slot.uc < 0) return;                       // block-uniform: no barrier reached yet
+    const int uc = slot.uc, u = u0 + uc, split = slot.split, n_splits = slot.S;
     const int T = dv.T, F = dv.F, cpp = dv.chunks_per_page;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv;
+    const int tile0 = ((int)blockIdx.y * 4 + wave) * RTW;
+    __shared__ __attribute__((aligned(16))) unsigned short k_lds[2][kChunk][KROW];
+    __shared__ __attribute__((aligned(16))) unsigned short v_lds[2][D][VROW];
+
+    bf16x8 qf[RTW][KK];
+#pragma unroll
+    for (int r = 0; r < RTW; ++r) load_q<D>(dv, q, lc, h, Tq, (tile0 + r) * kRowTile + n, g, qf[r]);
+
     const int *sel = dv.sel_pages + (size_t)u * F;
-    bf16x8 qf[KK];
-    load_q<D>(dv, q, lc, h, Tq, tile * kRowTile + n, g, qf);
     const int NC = dv.n_sel[u] * cpp;
     const int cps = (NC + n_splits - 1) / n_splits;
     const int c0 = split * cps, c1 = min(NC, c0 + cps);
@@ -251,41 +308,107 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
     const size_t kpage_elems = (size_t)T * D, vpage_elems = (size_t)D * dv.Tp;
     const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 
-    f32x4 acc[DB];
+    f32x4 acc[RTW][DB];
+    float m[RTW], l[RTW];
 #pragma unroll
-    for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, l = 0.f;
-    bf16x8 kA[2 * KK], vA[DB], kB[2 * KK], vB[DB];
-    auto issue = [&](int c, bf16x8 (&kf)[2 * KK], bf16x8 (&vf)[DB]) {
-        const int page = sel[c / cpp], cc = c % cpp;
-        issue_chunk<D>(kbase + (size_t)page * kpage_elems,
-                       vbase + (size_t)page * vpage_elems + (size_t)cc * D * 32, cc * kChunk, T, g, n,
-                       kf, vf);
+    for (int r = 0; r < RTW; ++r) {
+        m[r] = -INFINITY; l[r] = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[r][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // page ids of this split's chunks, one per lane (64 at a time), so that a chunk's
+    // operand addresses never wait on a dependent load
+    int pgs = 0;
+    auto load_pages = [&](int c) { pgs = sel[min((c + lane) / cpp, F - 1)]; };
+    uint4 kregA[KPT], vregA[VPT], kregB[KPT], vregB[VPT];
+    auto fetch = [&](int c, uint4 (&kreg)[KPT], uint4 (&vreg)[VPT]) {   // global -> registers
+        if (((c - c0) & 63) == 0) load_pages(c);
+        const int page = __builtin_amdgcn_readlane(pgs, (c - c0) & 63);
+        const int cc = c % cpp, t0 = cc * kChunk;
+        const unsigned short *kp = kbase + (size_t)page * kpage_elems;
+        const unsigned short *vp = vbase + (size_t)page * vpage_elems + (size_t)cc * D * kChunk;
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);
+            kreg[i] = *reinterpret_cast<const uint4 *>(kp + (size_t)min(t0 + t, T - 1) * D + seg * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int p = tid + kBlock * i;
+            vreg[i] = *reinterpret_cast<const uint4 *>(vp + (size_t)p * 8);   // chunk block is contiguous
+        }
     };
-    auto valid = [&](int c) { return min(kChunk, T - (c % cpp) * kChunk); };
+    auto stage = [&](int buf, const uint4 (&kreg)[KPT], const uint4 (&vreg)[VPT]) {   // registers -> LDS
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);
+            const int row = 16 * ((t / 4) % 2) + 4 * (t / 8) + t % 4;   // MFMA slot order
+            *reinterpret_cast<uint4 *>(&k_lds[buf][row][seg * 8]) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int p = tid + kBlock * i, d = p / (kChunk / 8), seg = p % (kChunk / 8);
+            *reinterpret_cast<uint4 *>(&v_lds[buf][d][seg * 8]) = vreg[i];
+        }
+    };
+    auto compute = [&](int c, int buf) {
+        bf16x8 kf[2 * KK], vf[DB];
+#pragma unroll
+        for (int tau = 0; tau < 2; ++tau)
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+                kf[tau * KK + kk] = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const uint4 *>(&k_lds[buf][16 * tau + n][32 * kk + 8 * g]));
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            vf[db] = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const uint4 *>(&v_lds[buf][16 * db + n][8 * g]));
+        const int n_valid = min(kChunk, T - (c % cpp) * kChunk);
+        chunk_step_multi<D, RTW>(kf, vf, qf, n_valid, g, sl2, acc, m, l);
+    };
+
+    // Pipeline: chunk c is computed from LDS buffer (c-c0)&1 while chunk c+1 sits in one
+    // register set and chunk c+2 is in flight in the other (two chunks of memory latency
+    // hidden behind every chunk of arithmetic).
     if (c0 < c1) {
+        fetch(c0, kregA, vregA);
+        if (c0 + 1 < c1) fetch(c0 + 1, kregB, vregB);
+        stage(0, kregA, vregA);
+        __syncthreads();
         int c = c0;
-        issue(c, kA, vA);
         while (true) {
-            if (c + 1 < c1) issue(c + 1, kB, vB);
-            chunk_step<D>(kA, vA, qf, valid(c), g, sl2, acc, m, l);
+            // here: LDS[(c-c0)&1] holds c, regs B hold c+1
+            if (c + 2 < c1) fetch(c + 2, kregA, vregA);
+            compute(c, (c - c0) & 1);
+            if (c + 1 < c1) stage(((c - c0) & 1) ^ 1, kregB, vregB);
+            __syncthreads();
             if (++c >= c1) break;
-            if (c + 1 < c1) issue(c + 1, kA, vA);
-            chunk_step<D>(kB, vB, qf, valid(c), g, sl2, acc, m, l);
+            // here: LDS[(c-c0)&1] holds c, regs A hold c+1
+            if (c + 2 < c1) fetch(c + 2, kregB, vregB);
+            compute(c, (c - c0) & 1);
+            if (c + 1 < c1) stage(((c - c0) & 1) ^ 1, kregA, vregA);
+            __syncthreads();
             if (++c >= c1) break;
         }
     }
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-    const size_t entry = ((size_t)uc * NT + tile) * n_splits + split;
-    float *po = dv.part_o + (entry * kRowTile + n) * D;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-        *reinterpret_cast<float4 *>(po + 16 * db + 4 * g) =
-            make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
-    if (g == 0) {
-        dv.part_ml[entry * 2 * kRowTile + n] = m;
-        dv.part_ml[entry * 2 * kRowTile + kRowTile + n] = l;
+    for (int r = 0; r < RTW; ++r) {
+        const int tile = tile0 + r;
+        if (tile >= NT) break;
+        float lr = l[r];
+        lr += __shfl_xor(lr, 16, 64);
+        lr += __shfl_xor(lr, 32, 64);
+        const size_t entry = (size_t)slot.base * NT + (size_t)tile * n_splits + split;
+        float *po = dv.part_o + (entry * kRowTile + n) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            *reinterpret_cast<float4 *>(po + 16 * db + 4 * g) =
+                make_float4(acc[r][db][0], acc[r][db][1], acc[r][db][2], acc[r][db][3]);
+        if (g == 0) {
+            dv.part_ml[entry * 2 * kRowTile + n] = m[r];
+            dv.part_ml[entry * 2 * kRowTile + kRowTile + n] = lr;
+        }
     }
 }
 
@@ -297,13 +420,13 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
     const unsigned short *qq = (const unsigned short *)q;
     const dim3 block(kBlock);
     if (NT == 1) {
-        const dim3 grid(n_splits, 1, n_units);
-        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_decode_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits);
-        else hipExtLaunchKernelGGL(k_attend_decode_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits);
+        const dim3 grid(n_units * n_splits);
+        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_decode_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq);
+        else hipExtLaunchKernelGGL(k_attend_decode_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq);
     } else {
-        const dim3 grid(n_splits, (NT + 3) / 4, n_units);
-        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_prefill_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, NT);
-        else hipExtLaunchKernelGGL(k_attend_prefill_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, NT);
+        const dim3 grid(n_units * n_splits, (NT + 4 * kPrefillTiles - 1) / (4 * kPrefillTiles));
+        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_prefill_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT);
+        else hipExtLaunchKernelGGL(k_attend_prefill_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT);
     }
     return hipGetLastError();
 }

@@ -39,7 +39,7 @@ struct DeviceView {
     int *sel_pages;   // [U][F]      frames of the selected clusters, gather order
     int *n_sel;       // [U]         number of selected frames
     int *tok_scratch; // [Hkv][F*T]  token-index expansion for the observer
-    // attention partials: entry e = ((uc*NT + tile)*S + split)
+    // attention partials: entry e = base_slot(unit)*NT + tile*S(unit) + split, see split_slot()
     float *part_o;    // [entries][16][D]
     float *part_ml;   // [entries][2][16]  running max (log2 domain) and sum
     long long part_entries;
@@ -74,7 +74,8 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
 hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                            int n_frames, int score_mode, hipStream_t s);
 hipError_t launch_expand_tok_idx(const DeviceView &dv, int u0, int n_units, hipStream_t s);
-// n_splits chosen by the caller; partial entries needed = n_units * NT * n_splits
+// n_splits = average splits per unit chosen by the caller (B = n_units * n_splits split
+// workgroups are shared out by split_slot); partial entries needed = B * NT
 // ev0/ev1 (may be null) receive the kernel's own start/stop timestamps
 hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                               int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
@@ -92,6 +93,62 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
     if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40); // NaN
     u += 0x7fffu + ((u >> 16) & 1u);
     return (unsigned short)(u >> 16);
+}
+
+
+// ---------------------------------------------------------------------------
+// Load-balanced KV splits.  An attend launch has B split workgroups (per row
+// block) for the n_units units of the call.  Units retrieve different numbers
+// of tokens, so the splits are shared out in proportion to the selected page
+// counts: unit i gets (n_sel_i > 0) + floor((B - n_units) * n_sel_i / total),
+// capped at kMaxSplits, contiguous workgroup ids, in unit order.  The attention
+// kernels (by workgroup id) and the combine kernel (by unit) evaluate the same
+// function of the same device-resident sizes, so they agree without any
+// host round trip.  Every lane of the calling wavefront gets the result.
+// ---------------------------------------------------------------------------
+struct SplitSlot {
+    int uc;      // unit within the call, -1: this workgroup has no work
+    int split;   // split index within the unit
+    int S;       // number of splits of the unit
+    int base;    // first split slot of the unit (partials are indexed by slot)
+};
+
+template <bool BY_UNIT>
+__device__ __forceinline__ SplitSlot split_slot(const int *n_sel_call, int n_units, int B, int key) {
+    const int lane = threadIdx.x % 64;
+    long long total = 0;
+    for (int i = lane; i < n_units; i += 64) total += n_sel_call[i];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) total += __shfl_xor(total, o, 64);
+    SplitSlot r{-1, 0, 0, 0};
+    int run = 0;
+    for (int i0 = 0; i0 < n_units; i0 += 64) {
+        const int i = i0 + lane;
+        const int ns = i < n_units ? n_sel_call[i] : 0;
+        int want = 0;
+        if (i < n_units && ns > 0) {
+            want = 1 + (int)(((long long)(B - n_units) * ns) / (total > 0 ? total : 1));
+            want = min(want, kMaxSplits);
+        }
+        int incl = want;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        const int excl = run + incl - want;
+        const bool hit = BY_UNIT ? (i == key) : (key >= excl && key < excl + want);
+        const unsigned long long mask = __ballot(hit);
+        if (mask) {
+            const int src = __ffsll((long long)mask) - 1;
+            r.uc = i0 + src;
+            r.S = __shfl(want, src, 64);
+            r.base = __shfl(excl, src, 64);
+            r.split = BY_UNIT ? 0 : key - r.base;
+        }
+        run += __shfl(incl, 63, 64);
+    }
+    return r;
 }
 
 } // namespace mosaic

@@ -73,6 +73,16 @@ def test_shapes_fp32(kw):
     _report(rep)
 
 
+@pytest.mark.parametrize("tq,kw", [
+    (256, dict(n_frames=128, n_clusters=8, top_k=3)),          # 1792 rows: 7 full 256-row workgroups
+    (41, dict(tokens_per_frame=50, n_frames=96)),              # 287 rows: 18 tiles, ragged last workgroup and tile
+    (19, dict(n_q_heads=8, n_kv_heads=4, head_dim=64)),        # G = 2, D = 64, 38 rows
+])
+def test_long_question_prefill_bf16(tq, kw):
+    rep = harness.run_workload(_small(question_tokens=tq, **kw))
+    _report(rep)
+
+
 def test_recluster_parity():
     wl = _small(n_frames=200, recluster_every=48, n_clusters=10, warmup_frames=24, lloyd_iters=3)
     rep = harness.run_workload(wl, decode_steps=1)

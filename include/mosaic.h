@@ -53,6 +53,7 @@ typedef enum {
 } mosaic_status;
 
 enum { MOSAIC_FP32 = 0, MOSAIC_BF16 = 1 };
+enum { MOSAIC_TIER_HBM = 0, MOSAIC_TIER_HOST = 1 };
 enum { MOSAIC_ATTEND_AUTO = 0, /* bf16 -> MFMA kernel, fp32 -> vector-ALU kernel */
        MOSAIC_ATTEND_VALU = 1, /* vector-ALU kernel for either dtype */
        MOSAIC_ATTEND_MFMA = 2  /* MFMA kernel (bf16 only) */ };
@@ -72,10 +73,25 @@ typedef struct {
     int32_t score_mode;       /* 0 cosine (paper Sec. V-B criterion), 1 plain dot product */
     int32_t max_q_tokens;     /* largest n_q_tokens retrieve/attend will be given; 0 -> 256 */
     int32_t attend_impl;      /* MOSAIC_ATTEND_* */
-    int32_t reserved0;
+    int32_t tier;             /* MOSAIC_TIER_HBM: all K/V pages stay in the device arena;
+                                 MOSAIC_TIER_HOST: pages are offloaded to pinned host memory in
+                                 cluster-contiguous slabs and fetched cluster by cluster into a GPU
+                                 cluster cache (paper Sec. V-A, V-C: clusters live in CPU memory and
+                                 are the retrieval units) */
     void *dev_arena;          /* device pointer, 256-byte aligned, borrowed */
     size_t dev_arena_bytes;
     void *stream;             /* hipStream_t, borrowed; NULL = the null stream */
+    /* host tier only (ignored for MOSAIC_TIER_HBM) */
+    int32_t slab_frames;          /* frames per host slab = unit of one host-to-device copy; 0 -> 8 */
+    int32_t cache_pages_per_unit; /* GPU cluster-cache capacity per unit, in frame pages (rounded up to
+                                     whole slabs); 0 -> 3 * max(cache_fraction, top_k/C) * (max_frames +
+                                     C * slab_frames) + top_k * slab_frames, at most the whole stream */
+    float cache_fraction;         /* at most floor(cache_fraction * C) clusters (but at least top_k) are
+                                     cached per unit, least recently used evicted first; 0 -> 0.10 */
+    int32_t reserved1;
+    void *host_arena;             /* HOST pointer to pinned (hipHostMalloc) memory, 256-byte aligned,
+                                     borrowed; size from mosaic_workspace_size */
+    size_t host_arena_bytes;
 } mosaic_config;
 
 typedef struct {
@@ -85,13 +101,20 @@ typedef struct {
     int64_t kv_bytes_stored;   /* K+V bytes written into the arena so far */
     int32_t ready;             /* 1 once the initial clustering has run */
     int32_t attend_impl;       /* the kernel family in use (MOSAIC_ATTEND_VALU or _MFMA) */
-    int32_t last_n_splits;     /* KV splits used by the latest attend */
+    int32_t last_n_splits;     /* average KV splits per unit used by the latest attend */
     int32_t reserved;
+    /* host tier */
+    int64_t cache_hits, cache_misses;   /* selected clusters found in / missing from the GPU cache */
+    int64_t h2d_bytes, h2d_copies;      /* cluster fetches: bytes and hipMemcpyAsync calls */
+    double h2d_busy_ms;                 /* time the copy stream spent on those fetches (event pairs
+                                           around each retrieve's copies; filled by mosaic_get_stats,
+                                           which synchronises) */
 } mosaic_stats;
 
-/* Bytes of device arena a context with this configuration needs (dev_arena
- * fields of cfg are ignored).  dev_bytes: host pointer. */
-int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes);
+/* Bytes of device arena and of pinned host arena (0 for MOSAIC_TIER_HBM) a
+ * context with this configuration needs (the arena fields of cfg are
+ * ignored).  dev_bytes, host_bytes: host pointers; host_bytes may be NULL. */
+int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes, size_t *host_bytes);
 
 /* Validate cfg, carve the arena, enqueue nothing.  out: host pointer. */
 int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out);
@@ -110,7 +133,11 @@ int32_t mosaic_reset(mosaic_ctx *ctx);
  * to the lowest id) whose representative is then updated by Eq. 3.  The result
  * is identical to n_frames calls with one frame each.
  * Errors: EINVAL (NULL, n_frames < 1), ECAPACITY (max_frames exceeded; nothing
- * is ingested). */
+ * is ingested).
+ * Host tier: the pages are written to a device staging ring, the batch's
+ * assignments are read back (this call then synchronises the stream once), and
+ * a kernel stores each page into its cluster's slab in the pinned host arena.
+ * Re-clustering (recluster_every > 0) is not available in the host tier. */
 int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_dev,
                             int32_t n_frames);
 
@@ -124,7 +151,13 @@ int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_de
  * (clusters in selection order, member frames ascending).  The selection stays
  * in the context until the next retrieve for that layer or the next ingest.
  * Errors: ENOTREADY before W frames are in; EINVAL (layer, n_q_tokens out of
- * range, NULL). */
+ * range, NULL).
+ * Host tier (layer >= 0 only): scoring and top-k run on an internal selection
+ * stream, the ids are read back (the call waits for that small copy only), and
+ * every selected cluster missing from the unit's GPU cache is fetched with one
+ * asynchronous copy per slab (K and V) on an internal copy stream, so that the
+ * fetch for layer l+1 overlaps mosaic_attend of layer l when retrieve(l+1) is
+ * issued before attend(l).  ECAPACITY if the selection does not fit the cache. */
 int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
                         int32_t n_q_tokens);
 
@@ -134,7 +167,8 @@ int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
  * q_dev as in mosaic_retrieve; out_dev [.][Tq][Hq][D] in kv_dtype and lse_dev
  * [.][Tq][Hq] fp32 (natural-log sum of exponentials of the scaled logits; may
  * be NULL) are device pointers.
- * Errors: ENOTREADY if no selection is current for the layer; EINVAL. */
+ * Errors: ENOTREADY if no selection is current for the layer; EINVAL.
+ * Host tier: the stream first waits (on the device) for the layer's fetches. */
 int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
                       int32_t n_q_tokens, void *out_dev, float *lse_dev);
 

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmosaic.so")
 
 OK, EINVAL, ENOMEM, ECAPACITY, ENOTREADY, EHIP = 0, -1, -2, -3, -4, -5
 FP32, BF16 = 0, 1
+TIER_HBM, TIER_HOST = 0, 1
 ATTEND_AUTO, ATTEND_VALU, ATTEND_MFMA = 0, 1, 2
 _STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ECAPACITY", -4: "ENOTREADY", -5: "EHIP"}
 
@@ -43,8 +44,11 @@ class Config(C.Structure):
         ("n_clusters", C.c_int32), ("top_k", C.c_int32), ("kv_dtype", C.c_int32),
         ("warmup_frames", C.c_int32), ("lloyd_iters", C.c_int32),
         ("recluster_every", C.c_int32), ("score_mode", C.c_int32),
-        ("max_q_tokens", C.c_int32), ("attend_impl", C.c_int32), ("reserved0", C.c_int32),
+        ("max_q_tokens", C.c_int32), ("attend_impl", C.c_int32), ("tier", C.c_int32),
         ("dev_arena", C.c_void_p), ("dev_arena_bytes", C.c_size_t), ("stream", C.c_void_p),
+        ("slab_frames", C.c_int32), ("cache_pages_per_unit", C.c_int32),
+        ("cache_fraction", C.c_float), ("reserved1", C.c_int32),
+        ("host_arena", C.c_void_p), ("host_arena_bytes", C.c_size_t),
     ]
 
 
@@ -54,6 +58,8 @@ class Stats(C.Structure):
         ("retrieve_calls", C.c_int64), ("attend_calls", C.c_int64),
         ("kv_bytes_stored", C.c_int64), ("ready", C.c_int32), ("attend_impl", C.c_int32),
         ("last_n_splits", C.c_int32), ("reserved", C.c_int32),
+        ("cache_hits", C.c_int64), ("cache_misses", C.c_int64),
+        ("h2d_bytes", C.c_int64), ("h2d_copies", C.c_int64), ("h2d_busy_ms", C.c_double),
     ]
 
 
@@ -71,7 +77,7 @@ def load_library():
             "(hipcc, gfx950).  There is no fallback path.")
     L = C.CDLL(LIB_PATH)
     vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
-    L.mosaic_workspace_size.argtypes = [C.POINTER(Config), C.POINTER(sz)]
+    L.mosaic_workspace_size.argtypes = [C.POINTER(Config), C.POINTER(sz), C.POINTER(sz)]
     L.mosaic_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
     L.mosaic_destroy.argtypes = [vp]
     L.mosaic_reset.argtypes = [vp]
@@ -97,7 +103,8 @@ def load_library():
 
 def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, max_frames,
                 n_clusters, top_k, kv_dtype, warmup_frames=0, lloyd_iters=0, recluster_every=0,
-                score_mode=0, max_q_tokens=0, attend_impl=ATTEND_AUTO) -> Config:
+                score_mode=0, max_q_tokens=0, attend_impl=ATTEND_AUTO, tier=TIER_HBM,
+                slab_frames=0, cache_pages_per_unit=0, cache_fraction=0.0) -> Config:
     c = Config()
     c.n_layers, c.n_q_heads, c.n_kv_heads = n_layers, n_q_heads, n_kv_heads
     c.head_dim, c.tokens_per_frame, c.max_frames = head_dim, tokens_per_frame, max_frames
@@ -105,16 +112,23 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
     c.kv_dtype = {"fp32": FP32, "bf16": BF16}.get(kv_dtype, kv_dtype)
     c.warmup_frames, c.lloyd_iters, c.recluster_every = warmup_frames, lloyd_iters, recluster_every
     c.score_mode, c.max_q_tokens, c.attend_impl = score_mode, max_q_tokens, attend_impl
+    c.tier, c.slab_frames, c.cache_pages_per_unit = tier, slab_frames, cache_pages_per_unit
+    c.cache_fraction = cache_fraction
     return c
 
 
-def workspace_size(cfg: Config) -> int:
+def workspace_sizes(cfg: Config):
+    """-> (device arena bytes, pinned host arena bytes)"""
     L = load_library()
-    n = C.c_size_t()
-    rc = L.mosaic_workspace_size(C.byref(cfg), C.byref(n))
+    n, h = C.c_size_t(), C.c_size_t()
+    rc = L.mosaic_workspace_size(C.byref(cfg), C.byref(n), C.byref(h))
     if rc != OK:
         raise MosaicError(rc, L.mosaic_last_error(None).decode())
-    return n.value
+    return n.value, h.value
+
+
+def workspace_size(cfg: Config) -> int:
+    return workspace_sizes(cfg)[0]
 
 
 def _ptr(t) -> int:
@@ -132,12 +146,18 @@ class Mosaic:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.cfg = cfg
-        nbytes = workspace_size(cfg)
+        nbytes, hbytes = workspace_sizes(cfg)
         # the arena: uninitialised device memory owned here, borrowed by the library
         self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
         base = (self.arena.data_ptr() + 255) // 256 * 256
         cfg.dev_arena = base
         cfg.dev_arena_bytes = nbytes
+        self.host_arena = None
+        if hbytes:
+            # pinned (hipHostMalloc) host memory for the host tier's cluster slabs
+            self.host_arena = torch.empty(hbytes + 256, dtype=torch.uint8, pin_memory=True)
+            cfg.host_arena = (self.host_arena.data_ptr() + 255) // 256 * 256
+            cfg.host_arena_bytes = hbytes
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         cfg.stream = self.stream.cuda_stream
         h = C.c_void_p()

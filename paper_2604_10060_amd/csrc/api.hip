@@ -8,6 +8,7 @@
 #include <new>
 
 #include "mosaic_internal.h"
+#include "host_tier.h"
 
 using namespace mosaic;
 
@@ -29,9 +30,13 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 
 struct Layout {
     size_t k_store, v_store, summ, r, rnorm, n, assign, pos, scores, ids, n_ids, sel_pages, n_sel,
-        tok_scratch, part_o, part_ml, total;
+        tok_scratch, part_o, part_ml, stage_k, stage_v, dest, total;
+    size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_total;   // offsets into the pinned host arena
     long long part_entries;
     int Tp, impl, v_transposed;
+    // host tier geometry
+    int SF, slabs_per_unit, HP, cache_blocks, PU, SN, max_clusters;
+    size_t kpage, vpage;
 };
 
 int check_config(const mosaic_config *c, std::string &why) {
@@ -50,6 +55,12 @@ int check_config(const mosaic_config *c, std::string &why) {
     if (c->attend_impl < MOSAIC_ATTEND_AUTO || c->attend_impl > MOSAIC_ATTEND_MFMA) { why = "attend_impl out of range"; return MOSAIC_EINVAL; }
     if (c->attend_impl == MOSAIC_ATTEND_MFMA && c->kv_dtype != MOSAIC_BF16) { why = "the MFMA attention kernel needs bf16 KV"; return MOSAIC_EINVAL; }
     if ((long long)c->max_frames * c->tokens_per_frame > 0x7fffffffLL) { why = "max_frames * tokens_per_frame must fit in int32"; return MOSAIC_EINVAL; }
+    if (c->tier != MOSAIC_TIER_HBM && c->tier != MOSAIC_TIER_HOST) { why = "tier must be MOSAIC_TIER_HBM or MOSAIC_TIER_HOST"; return MOSAIC_EINVAL; }
+    if (c->tier == MOSAIC_TIER_HOST) {
+        if (c->recluster_every != 0) { why = "re-clustering is not available in the host tier (pages would have to move between slabs)"; return MOSAIC_EINVAL; }
+        if (c->slab_frames < 0 || c->cache_pages_per_unit < 0) { why = "negative host-tier size"; return MOSAIC_EINVAL; }
+        if (c->cache_fraction < 0.f || c->cache_fraction > 1.f) { why = "cache_fraction must be in 0..1"; return MOSAIC_EINVAL; }
+    }
     return MOSAIC_OK;
 }
 
@@ -67,10 +78,34 @@ Layout make_layout(const mosaic_config &c) {
     const int maxq = c.max_q_tokens > 0 ? c.max_q_tokens : 256;
     const long long nt_max = ((long long)maxq * G + kRowTile - 1) / kRowTile;
     L.part_entries = std::max<long long>(4096, (long long)U * nt_max * 2);
+    L.kpage = T * D * e;
+    L.vpage = D * (L.v_transposed ? (size_t)L.Tp : T) * e;
+    const bool host = c.tier == MOSAIC_TIER_HOST;
+    L.PU = (int)F; L.SN = 1;
+    if (host) {
+        const int W = c.warmup_frames > 0 ? c.warmup_frames : 2 * c.n_clusters;
+        L.SF = c.slab_frames > 0 ? c.slab_frames : 8;
+        L.slabs_per_unit = (int)((F + L.SF - 1) / L.SF + C);
+        L.HP = L.slabs_per_unit * L.SF;
+        const float frac = c.cache_fraction > 0.f ? c.cache_fraction : 0.10f;
+        L.max_clusters = std::max<int>((int)k, (int)(frac * (float)C));
+        // default capacity: three times the average footprint of the clusters that may be resident
+        const double share = std::max((double)frac, (double)k / (double)C);
+        long long cp = c.cache_pages_per_unit > 0
+                           ? c.cache_pages_per_unit
+                           : std::min<long long>((long long)(3.0 * share * (double)(F + C * (size_t)L.SF)) + (long long)k * L.SF,
+                                                 (long long)(F + C * (size_t)L.SF));
+        L.cache_blocks = (int)((cp + L.SF - 1) / L.SF);
+        L.PU = L.cache_blocks * L.SF;
+        L.SN = std::max(W, 64);                 // staging ring: the warm-up plus one batch
+    }
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-    L.k_store = take(U * F * T * D * e);
-    L.v_store = take(U * F * D * (L.v_transposed ? (size_t)L.Tp : T) * e);
+    L.k_store = take(U * (size_t)L.PU * L.kpage);
+    L.v_store = take(U * (size_t)L.PU * L.vpage);
+    L.stage_k = take(host ? (size_t)L.SN * U * L.kpage : 0);
+    L.stage_v = take(host ? (size_t)L.SN * U * L.vpage : 0);
+    L.dest = take(host ? U * (size_t)L.SN * 4 : 0);
     L.summ = take(U * F * D * 8);
     L.r = take(U * C * D * 8);
     L.rnorm = take(U * C * 8);
@@ -86,6 +121,19 @@ Layout make_layout(const mosaic_config &c) {
     L.part_o = take((size_t)L.part_entries * kRowTile * D * 4);
     L.part_ml = take((size_t)L.part_entries * 2 * kRowTile * 4);
     L.total = off;
+    L.host_k = 0;
+    L.host_v = align_up(host ? U * (size_t)L.HP * L.kpage : 0);
+    if (host) {
+        size_t ho = L.host_v + align_up(U * (size_t)L.HP * L.vpage);
+        auto htake = [&](size_t bytes) { size_t o = ho; ho = align_up(ho + bytes); return o; };
+        L.host_sel = htake(U * F * 4);      // page lists on their way to the device
+        L.host_nsel = htake(U * 4);
+        L.host_ids = htake(U * k * 4);      // selections on their way back
+        L.host_nids = htake(U * 4);
+        L.host_total = ho;
+    } else {
+        L.host_total = 0;
+    }
     return L;
 }
 
@@ -137,12 +185,14 @@ int32_t mosaic_calibration_copy(void *dst_dev, const void *src_dev, size_t bytes
     return MOSAIC_OK;
 }
 
-int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes) {
+int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes, size_t *host_bytes) {
     std::string why;
     int rc = check_config(cfg, why);
     if (rc != MOSAIC_OK) return fail(nullptr, rc, why);
     if (!dev_bytes) return fail(nullptr, MOSAIC_EINVAL, "dev_bytes is NULL");
-    *dev_bytes = make_layout(*cfg).total;
+    const Layout L = make_layout(*cfg);
+    *dev_bytes = L.total;
+    if (host_bytes) *host_bytes = L.host_total;
     return MOSAIC_OK;
 }
 
@@ -193,6 +243,51 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.n_sel = (int *)(base + L.n_sel); dv.tok_scratch = (int *)(base + L.tok_scratch);
     dv.part_o = (float *)(base + L.part_o); dv.part_ml = (float *)(base + L.part_ml);
     dv.part_entries = L.part_entries;
+    dv.tier = cfg->tier; dv.PU = L.PU; dv.SN = L.SN; dv.HP = L.HP;
+    dv.stage_k = base + L.stage_k; dv.stage_v = base + L.stage_v; dv.dest = (int *)(base + L.dest);
+    dv.host_k = dv.host_v = nullptr;
+    ctx->host = nullptr;
+    if (cfg->tier == MOSAIC_TIER_HOST) {
+        auto bail = [&](int code, const std::string &msg) {
+            delete ctx->host; delete ctx;
+            return fail(nullptr, code, msg);
+        };
+        if (!cfg->host_arena) return bail(MOSAIC_EINVAL, "host_arena is NULL");
+        if ((uintptr_t)cfg->host_arena % 256) return bail(MOSAIC_EINVAL, "host_arena must be 256-byte aligned");
+        if (cfg->host_arena_bytes < L.host_total) {
+            char b[128];
+            snprintf(b, sizeof b, "host_arena has %zu bytes, %zu needed", cfg->host_arena_bytes, L.host_total);
+            return bail(MOSAIC_ENOMEM, b);
+        }
+        void *dptr = nullptr;
+        e = hipHostGetDevicePointer(&dptr, cfg->host_arena, 0);
+        if (e != hipSuccess || !dptr)
+            return bail(MOSAIC_EINVAL, "host_arena must be pinned, device-mapped host memory (hipHostMalloc)");
+        dv.host_k = (char *)dptr + L.host_k;
+        dv.host_v = (char *)dptr + L.host_v;
+        ctx->h_sel = (int *)((char *)cfg->host_arena + L.host_sel);
+        ctx->h_nsel = (int *)((char *)cfg->host_arena + L.host_nsel);
+        ctx->h_ids = (int *)((char *)cfg->host_arena + L.host_ids);
+        ctx->h_nids = (int *)((char *)cfg->host_arena + L.host_nids);
+        ctx->h_k = (char *)cfg->host_arena + L.host_k;
+        ctx->h_v = (char *)cfg->host_arena + L.host_v;
+        HostTier *ht = new (std::nothrow) HostTier();
+        if (!ht) return bail(MOSAIC_ENOMEM, "host allocation failed");
+        ctx->host = ht;
+        ht->init(dv.U, dv.C, L.SF, L.slabs_per_unit, L.cache_blocks, L.max_clusters, L.kpage, L.vpage);
+        ht->last_ids.assign(dv.U, {});
+        // default-priority streams for selection and for the fetches
+        if ((e = hipStreamCreateWithFlags(&ht->sel_stream, hipStreamNonBlocking)) != hipSuccess ||
+            (e = hipStreamCreateWithFlags(&ht->copy_stream, hipStreamNonBlocking)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&ht->main_mark, hipEventDisableTiming)) != hipSuccess)
+            return bail(MOSAIC_EHIP, std::string("host tier stream/event creation: ") + hipGetErrorString(e));
+        ht->ready.resize(dv.L); ht->attend_done.resize(dv.L);
+        ht->attend_recorded.assign(dv.L, 0); ht->ready_recorded.assign(dv.L, 0);
+        for (int l = 0; l < dv.L; ++l)
+            if ((e = hipEventCreateWithFlags(&ht->ready[l], hipEventDisableTiming)) != hipSuccess ||
+                (e = hipEventCreateWithFlags(&ht->attend_done[l], hipEventDisableTiming)) != hipSuccess)
+                return bail(MOSAIC_EHIP, std::string("host tier event creation: ") + hipGetErrorString(e));
+    }
     *out = ctx;
     return MOSAIC_OK;
 }
@@ -200,6 +295,15 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
 int32_t mosaic_destroy(mosaic_ctx *ctx) {
     if (!ctx) return MOSAIC_EINVAL;
     (void)hipStreamSynchronize(ctx->stream);
+    if (HostTier *ht = ctx->host) {
+        if (ht->sel_stream) { (void)hipStreamSynchronize(ht->sel_stream); (void)hipStreamDestroy(ht->sel_stream); }
+        if (ht->copy_stream) { (void)hipStreamSynchronize(ht->copy_stream); (void)hipStreamDestroy(ht->copy_stream); }
+        if (ht->main_mark) (void)hipEventDestroy(ht->main_mark);
+        for (hipEvent_t e : ht->ready) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ht->attend_done) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ht->busy_ev) (void)hipEventDestroy(e);
+        delete ht;
+    }
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     delete ctx;
     return MOSAIC_OK;
@@ -209,9 +313,85 @@ int32_t mosaic_reset(mosaic_ctx *ctx) {
     if (!ctx) return MOSAIC_EINVAL;
     ctx->n_frames = 0;
     ctx->epoch += 1;
+    if (HostTier *ht = ctx->host) {
+        // nothing may still be reading the cache or the staging ring
+        (void)hipStreamSynchronize(ctx->stream);
+        (void)hipStreamSynchronize(ht->sel_stream);
+        (void)hipStreamSynchronize(ht->copy_stream);
+        ht->reset();
+        ht->hits = ht->misses = ht->evictions = ht->h2d_bytes = ht->h2d_copies = 0;
+        ht->busy_ms = 0.0;
+        for (hipEvent_t e : ht->busy_ev) (void)hipEventDestroy(e);
+        ht->busy_ev.clear();
+        std::fill(ht->attend_recorded.begin(), ht->attend_recorded.end(), 0);
+        std::fill(ht->ready_recorded.begin(), ht->ready_recorded.end(), 0);
+    }
     const int attend_impl = ctx->stats.attend_impl;
     memset(&ctx->stats, 0, sizeof ctx->stats);
     ctx->stats.attend_impl = attend_impl;
+    return MOSAIC_OK;
+}
+
+// Host tier: read back the assignments of staged frames f0..f1-1, give every
+// page its slab position, and store the pages into pinned host memory.
+static int offload_range(mosaic_ctx *ctx, int f0, int f1) {
+    const DeviceView &dv = ctx->dv;
+    HostTier *ht = ctx->host;
+    const int n = f1 - f0;
+    std::vector<int> a((size_t)dv.U * n), dest((size_t)dv.U * dv.SN, 0);
+    hipError_t e = hipMemcpy2DAsync(a.data(), (size_t)n * 4, dv.assign + f0, (size_t)dv.F * 4, (size_t)n * 4,
+                                    dv.U, hipMemcpyDeviceToHost, ctx->stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "assignment read-back");
+    if ((e = hipStreamSynchronize(ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+    for (int fl = 0; fl < n; ++fl)
+        for (int u = 0; u < dv.U; ++u) {
+            const int c = a[(size_t)u * n + fl];
+            if (c < 0 || c >= dv.C) return fail(ctx, MOSAIC_EHIP, "assignment read-back returned an invalid cluster id");
+            const int hp = ht->append(u, f0 + fl, c);
+            if (hp < 0) return fail(ctx, MOSAIC_ECAPACITY, "host slab pool exhausted");
+            dest[(size_t)u * dv.SN + fl] = hp;
+        }
+    // pageable source: the runtime stages it before returning, so `dest` may go out of scope
+    e = hipMemcpyAsync(dv.dest, dest.data(), dest.size() * 4, hipMemcpyHostToDevice, ctx->stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "slab table upload");
+    if ((e = launch_offload(dv, f0, n, ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "offload launch");
+    return MOSAIC_OK;
+}
+
+static int ingest_host(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, int n_frames) {
+    const DeviceView &dv = ctx->dv;
+    HostTier *ht = ctx->host;
+    const size_t frame_bytes = (size_t)dv.U * dv.T * dv.D * dv.esize;
+    long long f = ctx->n_frames;
+    const long long end = f + n_frames, W = ctx->W;
+    size_t done = 0;
+    hipError_t e;
+    int rc;
+    while (f < end) {
+        // warm-up frames stay in the staging ring (SN >= W); afterwards batches of <= 64
+        const int nb = (int)(f < W ? std::min(end, W) - f : std::min<long long>(end - f, 64));
+        e = launch_store_summary(dv, (const char *)k_dev + done * frame_bytes,
+                                 (const char *)v_dev + done * frame_bytes, (int)f, nb, ctx->stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "store_summary launch");
+        if (f < W) {
+            f += nb;
+            if (f == W) {
+                if ((e = launch_lloyd(dv, (int)W, ctx->iters, true, ctx->stream)) != hipSuccess)
+                    return fail_hip(ctx, e, "initial clustering launch");
+                ctx->stats.lloyd_runs += 1;
+                if ((rc = offload_range(ctx, 0, (int)W)) != MOSAIC_OK) return rc;
+            }
+        } else {
+            if ((e = launch_assign_update(dv, (int)f, (int)f + nb, ctx->stream)) != hipSuccess)
+                return fail_hip(ctx, e, "assign_update launch");
+            if ((rc = offload_range(ctx, (int)f, (int)f + nb)) != MOSAIC_OK) return rc;
+            f += nb;
+        }
+        done += nb;
+        // a failure above leaves the frames before this batch ingested
+        ctx->n_frames = f;
+    }
+    (void)ht;
     return MOSAIC_OK;
 }
 
@@ -222,6 +402,15 @@ int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_de
     if (n_frames < 1) return fail(ctx, MOSAIC_EINVAL, "n_frames must be >= 1");
     const DeviceView &dv = ctx->dv;
     if (ctx->n_frames + n_frames > dv.F) return fail(ctx, MOSAIC_ECAPACITY, "max_frames exceeded");
+    if (ctx->host) {
+        const long long before = ctx->n_frames;
+        const int rc = ingest_host(ctx, k_dev, v_dev, n_frames);
+        ctx->epoch += 1;
+        ctx->stats.frames_ingested = ctx->n_frames;
+        ctx->stats.kv_bytes_stored += (int64_t)(ctx->n_frames - before) * dv.U * dv.T * dv.D * dv.esize * 2;
+        ctx->stats.ready = ctx->n_frames >= ctx->W;
+        return rc;
+    }
     hipError_t e;
     // pages + summaries of the whole batch (independent across frames); the grid's
     // y dimension is limited to 65535 frames per launch
@@ -277,14 +466,78 @@ static int check_query_args(mosaic_ctx *ctx, int32_t layer, const void *q_dev, i
     return MOSAIC_OK;
 }
 
+// Host tier: selection on the selection stream, LRU + fetches on the copy stream.
+static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq) {
+    const DeviceView &dv = ctx->dv;
+    HostTier *ht = ctx->host;
+    const int u0 = layer * dv.Hkv, nu = dv.Hkv, k = dv.k;
+    hipError_t e;
+    // the query was produced by work already enqueued on the caller's stream
+    // (and the representatives by the last ingest): mark the stream, wait for the mark
+    if ((e = hipEventRecord(ht->main_mark, ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    if ((e = hipStreamWaitEvent(ht->sel_stream, ht->main_mark, 0)) != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
+    if ((e = launch_retrieve(dv, u0, nu, q_dev, Tq, (int)ctx->n_frames, ctx->cfg.score_mode, false,
+                             ht->sel_stream)) != hipSuccess) return fail_hip(ctx, e, "retrieve launch");
+    int *ids = ctx->h_ids + (size_t)u0 * k, *nids = ctx->h_nids + u0;
+    if ((e = hipMemcpyAsync(ids, dv.ids + (size_t)u0 * k, (size_t)nu * k * 4, hipMemcpyDeviceToHost, ht->sel_stream)) != hipSuccess ||
+        (e = hipMemcpyAsync(nids, dv.n_ids + u0, (size_t)nu * 4, hipMemcpyDeviceToHost, ht->sel_stream)) != hipSuccess)
+        return fail_hip(ctx, e, "selection read-back");
+    if ((e = hipStreamSynchronize(ht->sel_stream)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+    // the pinned page-list staging of this layer must not be in flight any more
+    if (ht->ready_recorded[layer] && (e = hipEventSynchronize(ht->ready[layer])) != hipSuccess)
+        return fail_hip(ctx, e, "hipEventSynchronize");
+    // cache blocks of this layer may still be read by its previous attend
+    if (ht->attend_recorded[layer] &&
+        (e = hipStreamWaitEvent(ht->copy_stream, ht->attend_done[layer], 0)) != hipSuccess)
+        return fail_hip(ctx, e, "hipStreamWaitEvent");
+    hipEvent_t b0 = nullptr, b1 = nullptr;
+    if (ctx->profile) {            // time the copy stream's work for this retrieve
+        if ((e = hipEventCreate(&b0)) != hipSuccess || (e = hipEventCreate(&b1)) != hipSuccess)
+            return fail_hip(ctx, e, "hipEventCreate");
+        ht->busy_ev.push_back(b0); ht->busy_ev.push_back(b1);
+        (void)hipEventRecord(b0, ht->copy_stream);
+    }
+    std::vector<int> pages;
+    for (int i = 0; i < nu; ++i) {
+        const int u = u0 + i;
+        pages.clear();
+        hipError_t he;
+        const int rc = ht->fetch(u, ids + (size_t)i * k, nids[i], ctx->h_k, ctx->h_v, dv.HP, dv.k_store,
+                                 dv.v_store, dv.PU, ht->copy_stream, pages, &he);
+        if (rc == MOSAIC_EHIP) return fail_hip(ctx, he, "cluster fetch");
+        if (rc != MOSAIC_OK) return fail(ctx, rc, "the selected clusters do not fit the GPU cluster cache (raise cache_pages_per_unit / cache_fraction)");
+        ht->last_ids[u].assign(ids + (size_t)i * k, ids + (size_t)i * k + nids[i]);
+        int *hs = ctx->h_sel + (size_t)u * dv.F;
+        std::copy(pages.begin(), pages.end(), hs);
+        ctx->h_nsel[u] = (int)pages.size();
+        if (!pages.empty() &&
+            (e = hipMemcpyAsync(dv.sel_pages + (size_t)u * dv.F, hs, pages.size() * 4, hipMemcpyHostToDevice,
+                                ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "page list upload");
+    }
+    if ((e = hipMemcpyAsync(dv.n_sel + u0, ctx->h_nsel + u0, (size_t)nu * 4, hipMemcpyHostToDevice,
+                            ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "page count upload");
+    if (b1) (void)hipEventRecord(b1, ht->copy_stream);
+    if ((e = hipEventRecord(ht->ready[layer], ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    ht->ready_recorded[layer] = 1;
+    return MOSAIC_OK;
+}
+
 int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens) {
     if (!ctx) return MOSAIC_EINVAL;
     int u0, nu;
     int rc = check_query_args(ctx, layer, q_dev, n_q_tokens, &u0, &nu);
     if (rc != MOSAIC_OK) return rc;
     if (ctx->n_frames < ctx->W) return fail(ctx, MOSAIC_ENOTREADY, "initial clustering has not run yet (fewer than warmup_frames frames ingested)");
+    if (ctx->host) {
+        if (layer < 0) return fail(ctx, MOSAIC_EINVAL, "the host tier retrieves one layer per call");
+        rc = retrieve_host(ctx, layer, q_dev, n_q_tokens);
+        if (rc != MOSAIC_OK) return rc;
+        ctx->sel_epoch[layer] = ctx->epoch; ctx->sel_tq[layer] = n_q_tokens;
+        ctx->stats.retrieve_calls += 1;
+        return MOSAIC_OK;
+    }
     hipError_t e = launch_retrieve(ctx->dv, u0, nu, q_dev, n_q_tokens, (int)ctx->n_frames,
-                                   ctx->cfg.score_mode, ctx->stream);
+                                   ctx->cfg.score_mode, true, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "retrieve launch");
     const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? ctx->dv.L : layer + 1;
     for (int l = l0; l < l1; ++l) { ctx->sel_epoch[l] = ctx->epoch; ctx->sel_tq[l] = n_q_tokens; }
@@ -305,6 +558,11 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t
             return fail(ctx, MOSAIC_ENOTREADY, "no current selection for this layer: call mosaic_retrieve after the last ingest");
     const int S = choose_splits(ctx, nu, n_q_tokens);
     hipError_t e;
+    if (ctx->host) {
+        if (layer < 0) return fail(ctx, MOSAIC_EINVAL, "the host tier attends one layer per call");
+        if ((e = hipStreamWaitEvent(ctx->stream, ctx->host->ready[layer], 0)) != hipSuccess)
+            return fail_hip(ctx, e, "hipStreamWaitEvent");
+    }
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (ctx->profile) {
         if (ctx->ev_used + 2 > ctx->ev.size()) {
@@ -324,6 +582,11 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t
     if (e != hipSuccess) return fail_hip(ctx, e, "attend launch");
     e = launch_attend_combine(ctx->dv, u0, nu, n_q_tokens, S, out_dev, lse_dev, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "combine launch");
+    if (ctx->host) {
+        if ((e = hipEventRecord(ctx->host->attend_done[layer], ctx->stream)) != hipSuccess)
+            return fail_hip(ctx, e, "hipEventRecord");
+        ctx->host->attend_recorded[layer] = 1;
+    }
     ctx->stats.attend_calls += 1;
     ctx->stats.last_n_splits = S;
     return MOSAIC_OK;
@@ -391,6 +654,29 @@ int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32
     if (ctx->sel_epoch[layer] != ctx->epoch) return fail(ctx, MOSAIC_ENOTREADY, "no current selection for this layer");
     const int u0 = layer * dv.Hkv, H = dv.Hkv;
     int rc;
+    if (HostTier *ht = ctx->host) {
+        // ids and scores were produced on the selection stream; the token list comes from
+        // the host-side cluster membership (frames of each selected cluster, ascending)
+        hipError_t he = hipStreamSynchronize(ht->sel_stream);
+        if (he != hipSuccess) return fail_hip(ctx, he, "hipStreamSynchronize");
+        if (ids && (rc = d2h(ctx, ids, dv.ids + (size_t)u0 * dv.k, (size_t)H * dv.k * 4)) != MOSAIC_OK) return rc;
+        if (n_ids && (rc = d2h(ctx, n_ids, dv.n_ids + u0, (size_t)H * 4)) != MOSAIC_OK) return rc;
+        if (scores && (rc = d2h(ctx, scores, dv.scores + (size_t)u0 * dv.C, (size_t)H * dv.C * 8)) != MOSAIC_OK) return rc;
+        if ((rc = sync(ctx)) != MOSAIC_OK) return rc;
+        for (int h = 0; h < H; ++h) {
+            const HostTier::Unit &un = ht->units[u0 + h];
+            int64_t m = 0;
+            for (int c : ht->last_ids[u0 + h]) m += (int64_t)un.frames[c].size() * dv.T;
+            if (n_tok) n_tok[h] = (int32_t)m;
+            if (!tok_idx) continue;
+            if (m > tok_cap) return fail(ctx, MOSAIC_ECAPACITY, "tok_cap too small for the retrieved token list");
+            int32_t *o = tok_idx + (size_t)h * tok_cap;
+            for (int c : ht->last_ids[u0 + h])
+                for (int f : un.frames[c])
+                    for (int t = 0; t < dv.T; ++t) *o++ = f * dv.T + t;
+        }
+        return MOSAIC_OK;
+    }
     if (ids && (rc = d2h(ctx, ids, dv.ids + (size_t)u0 * dv.k, (size_t)H * dv.k * 4)) != MOSAIC_OK) return rc;
     if (n_ids && (rc = d2h(ctx, n_ids, dv.n_ids + u0, (size_t)H * 4)) != MOSAIC_OK) return rc;
     if (scores && (rc = d2h(ctx, scores, dv.scores + (size_t)u0 * dv.C, (size_t)H * dv.C * 8)) != MOSAIC_OK) return rc;
@@ -413,6 +699,22 @@ int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32
 
 int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats) {
     if (!ctx || !stats) return MOSAIC_EINVAL;
+    if (HostTier *ht = ctx->host) {
+        if (!ht->busy_ev.empty()) {
+            hipError_t e = hipStreamSynchronize(ht->copy_stream);
+            if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+            for (size_t i = 0; i + 1 < ht->busy_ev.size(); i += 2) {
+                float ms = 0.f;
+                if (hipEventElapsedTime(&ms, ht->busy_ev[i], ht->busy_ev[i + 1]) == hipSuccess) ht->busy_ms += ms;
+                (void)hipEventDestroy(ht->busy_ev[i]);
+                (void)hipEventDestroy(ht->busy_ev[i + 1]);
+            }
+            ht->busy_ev.clear();
+        }
+        ctx->stats.cache_hits = ht->hits; ctx->stats.cache_misses = ht->misses;
+        ctx->stats.h2d_bytes = ht->h2d_bytes; ctx->stats.h2d_copies = ht->h2d_copies;
+        ctx->stats.h2d_busy_ms = ht->busy_ms;
+    }
     *stats = ctx->stats;
     return MOSAIC_OK;
 }

@@ -188,8 +188,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
     bf16x8 qf[KK];
     load_q<D>(dv, q, lc, h, Tq, n, g, qf);
 
-    const unsigned short *kbase = reinterpret_cast<const unsigned short *>(dv.k_store) + (size_t)u * F * T * D;
-    const unsigned short *vbase = reinterpret_cast<const unsigned short *>(dv.v_store) + (size_t)u * F * D * dv.Tp;
+    const unsigned short *kbase = reinterpret_cast<const unsigned short *>(dv.k_store) + (size_t)u * dv.PU * T * D;
+    const unsigned short *vbase = reinterpret_cast<const unsigned short *>(dv.v_store) + (size_t)u * dv.PU * D * dv.Tp;
     const size_t kpage_elems = (size_t)T * D, vpage_elems = (size_t)D * dv.Tp;
     const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 
@@ -303,8 +303,8 @@ __global__ __launch_bounds__(kBlock, 1) void k_attend_prefill_mfma(DeviceView dv
     const int NC = dv.n_sel[u] * cpp;
     const int cps = (NC + n_splits - 1) / n_splits;
     const int c0 = split * cps, c1 = min(NC, c0 + cps);
-    const unsigned short *kbase = reinterpret_cast<const unsigned short *>(dv.k_store) + (size_t)u * F * T * D;
-    const unsigned short *vbase = reinterpret_cast<const unsigned short *>(dv.v_store) + (size_t)u * F * D * dv.Tp;
+    const unsigned short *kbase = reinterpret_cast<const unsigned short *>(dv.k_store) + (size_t)u * dv.PU * T * D;
+    const unsigned short *vbase = reinterpret_cast<const unsigned short *>(dv.v_store) + (size_t)u * dv.PU * D * dv.Tp;
     const size_t kpage_elems = (size_t)T * D, vpage_elems = (size_t)D * dv.Tp;
     const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 

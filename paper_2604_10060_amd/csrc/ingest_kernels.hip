@@ -68,12 +68,17 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
     const int tid = threadIdx.x, cg = tid % LPR, r0 = tid / LPR;
     const int T = dv.T;
     const size_t in_page = ((size_t)fl * dv.U + u) * (size_t)T * D;
-    const size_t page = (size_t)u * dv.F + f;
+    const size_t page = (size_t)u * dv.F + f;          // summary slot
+    // where the pages go: the arena's store (HBM tier) or the staging ring (host tier)
+    const bool host = dv.tier == MOSAIC_TIER_HOST;
+    const size_t spage = host ? (size_t)(f % dv.SN) * dv.U + u : (size_t)u * dv.PU + f;
+    char *kdst_base = host ? dv.stage_k : dv.k_store;
+    char *vdst_base = host ? dv.stage_v : dv.v_store;
 
     if (blockIdx.z == 0) {
         __shared__ double red[RP][D];
         const E *src = k_in + in_page;
-        E *dst = reinterpret_cast<E *>(dv.k_store) + page * (size_t)T * D;
+        E *dst = reinterpret_cast<E *>(kdst_base) + spage * (size_t)T * D;
         double acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.0;
@@ -97,7 +102,7 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
 
     const E *src = v_in + in_page;
     if (!dv.v_transposed) {
-        E *dst = reinterpret_cast<E *>(dv.v_store) + page * (size_t)T * D;
+        E *dst = reinterpret_cast<E *>(vdst_base) + spage * (size_t)T * D;
         for (int t = r0; t < T; t += RP)
             Elem<E>::copy8(src + (size_t)t * D + cg * 8, dst + (size_t)t * D + cg * 8);
         return;
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
         constexpr int TC = 64;                       // tokens per LDS tile (two chunks)
         __shared__ unsigned short tile[TC][D + 2];
         const int Tp = dv.Tp;
-        unsigned short *dst = reinterpret_cast<unsigned short *>(dv.v_store) + page * (size_t)D * Tp;
+        unsigned short *dst = reinterpret_cast<unsigned short *>(vdst_base) + spage * (size_t)D * Tp;
         for (int tc0 = 0; tc0 < Tp; tc0 += TC) {
             for (int t = r0; t < TC; t += RP) {
                 const int tok = tc0 + t;
@@ -370,6 +375,23 @@ __global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frame
     }
 }
 
+// ---------------------------------------------------------------------------
+// Host tier: store staged pages into their cluster's slab in pinned host memory
+// (device stores over PCIe, 16 bytes per lane, whole pages contiguous).
+// grid (U, n, 2): z = 0 keys, z = 1 values.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_offload(DeviceView dv, int f0) {
+    const int u = blockIdx.x, fl = blockIdx.y, f = f0 + fl;
+    const size_t kpage = (size_t)dv.T * dv.D * dv.esize;
+    const size_t vpage = (size_t)dv.D * (dv.v_transposed ? dv.Tp : dv.T) * dv.esize;
+    const size_t bytes = blockIdx.z == 0 ? kpage : vpage;
+    const size_t spage = (size_t)(f % dv.SN) * dv.U + u;
+    const size_t hpage = (size_t)u * dv.HP + dv.dest[(size_t)u * dv.SN + fl];
+    const uint4 *src = reinterpret_cast<const uint4 *>((blockIdx.z == 0 ? dv.stage_k : dv.stage_v) + spage * bytes);
+    uint4 *dst = reinterpret_cast<uint4 *>((blockIdx.z == 0 ? dv.host_k : dv.host_v) + hpage * bytes);
+    for (size_t i = threadIdx.x; i < bytes / 16; i += kBlock) dst[i] = src[i];
+}
+
 template <typename F> hipError_t checked(F &&launch) {
     launch();
     return hipGetLastError();
@@ -389,6 +411,10 @@ hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const vo
             else k_store_summary<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f0);
         }
     });
+}
+
+hipError_t launch_offload(const DeviceView &dv, int f0, int n, hipStream_t s) {
+    return checked([&] { k_offload<<<dim3(dv.U, n, 2), kBlock, 0, s>>>(dv, f0); });
 }
 
 hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s) {

@@ -22,9 +22,19 @@ struct DeviceView {
     int esize;        // bytes per KV element
     int v_transposed; // 1: V pages stored [Tp/32][D][32] (MFMA path, Tp = T rounded up to 32); 0: [T][D]
     int chunks_per_page;
-    // KV store, pages in arrival order: page (u, f) at index u*F + f
-    char *k_store;    // [U][F][T][D] elements
-    char *v_store;    // [U][F][T][D] or [U][F][Tp/32][D][32] elements
+    int tier;         // MOSAIC_TIER_*
+    int PU;           // pages per unit in k_store / v_store: F (HBM tier) or the cluster-cache capacity (host tier)
+    int SN;           // host tier: frames in the staging ring
+    // KV pages the attention kernels read: page (u, p) at index u*PU + p.
+    // HBM tier: p = frame id (arrival order).  Host tier: p = slot of the unit's cluster cache.
+    char *k_store;    // [U][PU][T][D] elements
+    char *v_store;    // [U][PU][T][D] or [U][PU][Tp/32][D][32] elements
+    // host tier: staging ring the ingest kernel writes (frame f at slot f % SN), and the
+    // device-visible address of the pinned host pools the offload kernel writes
+    char *stage_k, *stage_v;   // [SN][U][page]
+    char *host_k, *host_v;     // [U][HP][page]
+    int HP;                    // host pages per unit
+    int *dest;                 // [U][SN] host page of each staged frame of the current batch
     // clustering state (decision arithmetic in fp64)
     double *summ;     // [U][F][D]   per-frame key summaries
     double *r;        // [U][C][D]   representatives
@@ -45,6 +55,8 @@ struct DeviceView {
     long long part_entries;
 };
 
+struct HostTier;   // host_tier.hip
+
 struct Ctx {
     mosaic_config cfg;
     DeviceView dv;
@@ -59,6 +71,11 @@ struct Ctx {
     long long epoch;     // bumped by ingest and reset
     mosaic_stats stats;
     std::string err;
+    HostTier *host;      // non-null in the host tier
+    // host tier: host-side views of the pinned arena
+    char *h_k, *h_v;     // slab pools
+    int *h_sel, *h_nsel; // page lists / counts staged for upload, [U][F] / [U]
+    int *h_ids, *h_nids; // selections read back, [U][k] / [U]
     // profiling
     bool profile;
     std::vector<hipEvent_t> ev;      // pairs
@@ -71,8 +88,11 @@ hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const vo
 hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s);
 hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed_from_warmup,
                         hipStream_t s);
+// write_pages = false (host tier): only scores and ids; the page list comes from the host
 hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
-                           int n_frames, int score_mode, hipStream_t s);
+                           int n_frames, int score_mode, bool write_pages, hipStream_t s);
+// host tier: copy staged frames f0..f0+n-1 of every unit to host page dest[u][f - f0]
+hipError_t launch_offload(const DeviceView &dv, int f0, int n, hipStream_t s);
 hipError_t launch_expand_tok_idx(const DeviceView &dv, int u0, int n_units, hipStream_t s);
 // n_splits = average splits per unit chosen by the caller (B = n_units * n_splits split
 // workgroups are shared out by split_slot); partial entries needed = B * NT

@@ -27,7 +27,7 @@ template <> __device__ __forceinline__ double to_f64<unsigned short>(unsigned sh
 // issued up front, unconditionally; what follows runs out of LDS and registers.
 template <typename E, int D>
 __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, const E *q, int Tq,
-                                                     int n_frames, int score_mode) {
+                                                     int n_frames, int score_mode, bool write_pages) {
     constexpr int EPL = D / 16;   // doubles per lane in a 16-lane row group
     constexpr int FPT = 8;        // frames per thread prefetched for the page-list scatter
     constexpr int RPF = 4;        // passes of 16 representative rows prefetched into registers
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, cons
         off_sh[0] = 0;
         for (int i = 0; i < n_ids; ++i) { o += n_sh[ids_sh[i]]; off_sh[i + 1] = o; }
         dv.n_ids[u] = n_ids;
-        dv.n_sel[u] = o;
+        if (write_pages) dv.n_sel[u] = o;
     }
     for (int i = tid; i < k; i += kBlock) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
     __syncthreads();
@@ -188,13 +188,13 @@ __global__ __launch_bounds__(kBlock) void k_expand_tok_idx(DeviceView dv, int u0
 } // namespace
 
 hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
-                           int n_frames, int score_mode, hipStream_t s) {
+                           int n_frames, int score_mode, bool write_pages, hipStream_t s) {
     if (dv.esize == 4) {
-        if (dv.D == 64) k_retrieve<float, 64><<<n_units, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode);
-        else k_retrieve<float, 128><<<n_units, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode);
+        if (dv.D == 64) k_retrieve<float, 64><<<n_units, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
+        else k_retrieve<float, 128><<<n_units, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
     } else {
-        if (dv.D == 64) k_retrieve<unsigned short, 64><<<n_units, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode);
-        else k_retrieve<unsigned short, 128><<<n_units, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode);
+        if (dv.D == 64) k_retrieve<unsigned short, 64><<<n_units, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
+        else k_retrieve<unsigned short, 128><<<n_units, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
     }
     return hipGetLastError();
 }

@@ -200,3 +200,117 @@ def test_cfg1_full_size():
     rep = harness.run_workload(inputs.CONFIGS[1], decode_steps=4)
     _report(rep)
     assert rep.max_out_err <= 2e-2
+
+
+# --------------------------------------------------------------------------
+# host tier: pinned-host cluster slabs + GPU cluster cache
+# --------------------------------------------------------------------------
+HOST = dict(tier=binding.TIER_HOST, slab_frames=4)
+
+
+def test_host_tier_parity():
+    rep = harness.run_workload(_small(n_frames=200), decode_steps=3, **HOST)
+    _report(rep)
+
+
+def test_host_tier_parity_ragged_pages_two_layers():
+    wl = _small(n_layers=2, tokens_per_frame=50, n_frames=120, n_clusters=9, top_k=3, question_tokens=3)
+    rep = harness.run_workload(wl, decode_steps=2, slab_frames=3, tier=binding.TIER_HOST)
+    _report(rep)
+
+
+def test_host_tier_matches_hbm_tier_bitwise_and_overlaps_layers():
+    wl = _small(n_layers=3, n_frames=144, n_clusters=10, top_k=3)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    qs = [st.question(st.draw_scene(), 1, i).to(DEV) for i in range(4)]
+    outs = {}
+    for name, over in (("hbm", {}), ("host", HOST)):
+        m = _ingest_all(wl, K, V, (16,), **over)
+        res = []
+        for q in qs:
+            o = torch.empty_like(q)
+            l = torch.empty(q.shape[:-1], dtype=torch.float32, device=DEV)
+            # software pipeline: the selection/fetch of layer l+1 is issued before attend(l)
+            m.retrieve(0, q[0].contiguous())
+            for layer in range(wl.n_layers):
+                if layer + 1 < wl.n_layers:
+                    m.retrieve(layer + 1, q[layer + 1].contiguous())
+                m.attend(layer, q[layer].contiguous(), o[layer], l[layer])
+            torch.cuda.synchronize()
+            res.append((o.clone(), l.clone()))
+        outs[name] = res
+        if name == "host":
+            s = m.stats()
+            assert s.cache_misses > 0 and s.h2d_bytes > 0 and s.h2d_copies >= 2 * s.cache_misses
+        m.close()
+    for (o1, l1), (o2, l2) in zip(outs["hbm"], outs["host"]):
+        assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+def _lru_sim(seq_ids, sizes_at, max_clusters, blocks, SF):
+    """Reference LRU at cluster granularity: returns (hits, misses)."""
+    present, stamp, used, clock, hits, misses = {}, {}, 0, 0, 0, 0
+    for ids, sizes in zip(seq_ids, sizes_at):
+        for c in ids:
+            need = -(-int(sizes[c]) // SF)
+            if c in present and present[c][1] == sizes[c]:
+                hits += 1
+            else:
+                misses += 1
+            have_blocks = present[c][0] if c in present else 0
+            while blocks - used < need - have_blocks or (c not in present and len(present) >= max_clusters):
+                victim = min((j for j in present if j not in ids), key=lambda j: stamp[j])
+                used -= present.pop(victim)[0]
+            used += need - have_blocks
+            present[c] = (need, int(sizes[c]))
+            clock += 1
+            stamp[c] = clock
+    return hits, misses
+
+
+def test_host_tier_cache_follows_lru_and_grows_with_the_stream():
+    wl = _small(n_kv_heads=1, n_q_heads=7, n_frames=240, n_clusters=12, top_k=3, n_scenes=10)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    SF, pages = 4, 55 * 4
+    m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=SF,
+                                          cache_pages_per_unit=pages, cache_fraction=5 / 12), device=DEV)
+    m.ingest_frame(K[:160].contiguous(), V[:160].contiguous())
+    seq, sizes_at = [], []
+    f = 160
+    for i in range(24):
+        if i % 6 == 5 and f < wl.n_frames:          # the stream keeps growing between questions
+            m.ingest_frame(K[f:f + 20].contiguous(), V[f:f + 20].contiguous())
+            f += 20
+        q = st.question(st.draw_scene(), 1, i).to(DEV)[0].contiguous()
+        m.retrieve(0, q)
+        out, _ = m.attend(0, q)
+        ids, n_ids, _, toks = m.selection(0)
+        _, n = m.centroids()
+        seq.append([int(c) for c in ids[0, : n_ids[0]]])
+        sizes_at.append(n[0].copy())
+        assert len(toks[0]) == wl.tokens_per_frame * n[0][ids[0, : n_ids[0]]].sum()
+        assert torch.isfinite(out.float()).all()
+    s = m.stats()
+    hits, misses = _lru_sim(seq, sizes_at, max_clusters=5, blocks=pages // SF, SF=SF)
+    assert (s.cache_hits, s.cache_misses) == (hits, misses)
+    assert s.cache_hits > 0 and s.cache_misses > 0
+    m.close()
+
+
+def test_host_tier_cache_too_small_is_an_error():
+    wl = _small(n_frames=120, n_clusters=6, top_k=4)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=4,
+                                          cache_pages_per_unit=8), device=DEV)
+    m.ingest_frame(K, V)
+    q = st.question(0, 1, 0).to(DEV)[0].contiguous()
+    with pytest.raises(binding.MosaicError) as e:
+        m.retrieve(0, q)
+    assert e.value.code == binding.ECAPACITY
+    with pytest.raises(binding.MosaicError) as e:     # all-layers calls are not part of the host tier
+        m.retrieve(-1, q[None].contiguous())
+    assert e.value.code == binding.EINVAL
+    m.close()

@@ -28,9 +28,9 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    # 16 int32 fields, then pointer, size_t, pointer
-    assert C.sizeof(binding.Config) == 16 * 4 + 3 * 8
-    assert C.sizeof(binding.Stats) == 5 * 8 + 4 * 4
+    # 16 int32 fields; pointer, size_t, pointer; 2 int32, float, int32; pointer, size_t
+    assert C.sizeof(binding.Config) == 16 * 4 + 3 * 8 + 4 * 4 + 2 * 8
+    assert C.sizeof(binding.Stats) == 5 * 8 + 4 * 4 + 5 * 8
 
 
 def _cfg(**kw):
@@ -55,7 +55,8 @@ def test_workspace_size_grows_with_the_stream():
     dict(head_dim=96), dict(n_q_heads=5), dict(top_k=0), dict(top_k=17), dict(n_clusters=0),
     dict(n_clusters=2000, top_k=4), dict(kv_dtype=7), dict(tokens_per_frame=0),
     dict(warmup_frames=8), dict(score_mode=2), dict(attend_impl=binding.ATTEND_MFMA),
-    dict(max_frames=1 << 30, tokens_per_frame=64), dict(attend_impl=9),
+    dict(max_frames=1 << 30, tokens_per_frame=64), dict(attend_impl=9), dict(tier=2),
+    dict(tier=1, recluster_every=16), dict(tier=1, cache_fraction=1.5),
 ])
 def test_bad_configurations_are_rejected(bad):
     with pytest.raises(binding.MosaicError) as e:
@@ -64,9 +65,21 @@ def test_bad_configurations_are_rejected(bad):
     assert len(str(e.value)) > 10
 
 
+def test_host_tier_sizes():
+    hbm = binding.workspace_sizes(_cfg(kv_dtype="bf16", head_dim=128, tokens_per_frame=64, max_frames=4096))
+    assert hbm[1] == 0
+    cfg = _cfg(kv_dtype="bf16", head_dim=128, tokens_per_frame=64, max_frames=4096, tier=binding.TIER_HOST,
+               slab_frames=8, cache_fraction=0.1)
+    dev, host = binding.workspace_sizes(cfg)
+    # host pool: (4096/8 + 16) slabs of 8 pages per unit, K and V pages of 16 KiB each, 2 units
+    assert host >= 2 * (4096 // 8 + 16) * 8 * 2 * 64 * 128 * 2
+    # the device side only holds the cache and the staging ring, not the whole stream
+    assert dev < hbm[0]
+
+
 def test_null_arguments_do_not_crash():
     lib = binding.load_library()
-    assert lib.mosaic_workspace_size(None, None) == binding.EINVAL
+    assert lib.mosaic_workspace_size(None, None, None) == binding.EINVAL
     assert lib.mosaic_reset(None) == binding.EINVAL
     assert lib.mosaic_ingest_frame(None, None, None, 1) == binding.EINVAL
     assert lib.mosaic_retrieve(None, 0, None, 1) == binding.EINVAL

@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg4"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count")
     ap.add_argument("--all-layers-call", action="store_true",
@@ -356,6 +356,123 @@ def run_prefill_leg(n_streams=8, check=True):
             "parity_spot_check": checked}
 
 
+def run_host_leg(layers=4, steps=128, check=True):
+    """Config 3 (host-offload tier) with the layer count scaled to `layers` (the
+    full 28 layers need 184 GB of pinned host memory; the per-layer shape is
+    kept): clusters live in pinned host memory in slabs of 16 frames, the GPU
+    caches at most 10 % of a unit's clusters (LRU), the fetch for layer l+1 is
+    issued before attention of layer l.  4 question topics, steps/4 consecutive
+    decode steps each (a topic switch means cold misses)."""
+    import torch
+    from paper_2604_10060_amd import binding, inputs
+    dev = "cuda:0"
+    wl = inputs.CONFIGS[3].scaled(n_layers=layers)
+    L, Hq, D, T, F, H = wl.n_layers, wl.n_q_heads, wl.head_dim, wl.tokens_per_frame, wl.n_frames, wl.n_kv_heads
+    # measured pinned host-to-device rate of this box: one 1 GiB copy
+    src = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+    dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst.copy_(src, non_blocking=True)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); dst.copy_(src, non_blocking=True); e1.record()
+    torch.cuda.synchronize()
+    pcie_gbps = (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    st = inputs.SceneStream(wl, device=dev)
+    # resident clusters capped at 10 % (51 of 512), least recently used evicted first.  The block pool
+    # is sized for the worst case (any 51 clusters): with a fixed number of clusters and no splitting a
+    # few clusters grow very large (here up to ~1500 of 16384 frames) and top-32 can cover half the stream.
+    m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
+                                          cache_pages_per_unit=F + 52 * 16), device=dev)
+    cu = (layers - 1, 2)                             # unit checked against the oracle
+    keepK, keepV = [], []
+    t0 = time.perf_counter()
+    gen_s = 0.0
+    for f0 in range(0, F, 256):
+        tg = time.perf_counter()
+        K, V = st.frames(f0, min(F, f0 + 256))
+        torch.cuda.synchronize()
+        gen_s += time.perf_counter() - tg
+        if check:
+            keepK.append(K[:, cu[0], cu[1]].cpu()); keepV.append(V[:, cu[0], cu[1]].cpu())
+        for b in range(0, K.shape[0], 64):
+            m.ingest_frame(K[b:b + 64], V[b:b + 64])
+    torch.cuda.synchronize()
+    ingest_fps = F / (time.perf_counter() - t0 - gen_s)
+    log(f"[bench] {wl.name} x{layers} layers: host-tier ingest {ingest_fps:.0f} frames/s, "
+        f"pinned H2D {pcie_gbps:.1f} GB/s")
+    _, sizes = m.centroids()
+    log(f"[bench] cluster sizes (frames): max {sizes.max()}, mean {sizes[sizes > 0].mean():.1f}, "
+        f"non-empty {int((sizes > 0).sum() / sizes.shape[0])} of {wl.n_clusters} per unit")
+    topics = [st.draw_scene() for _ in range(4)]
+    per_topic = steps // 4
+    qs = torch.stack([st.question(topics[i // per_topic], 1, 1 + i) for i in range(steps)])   # [n][L][1][Hq][D]
+    out = torch.empty((L, 1, Hq, D), dtype=wl.torch_dtype, device=dev)
+    lse = torch.empty((L, 1, Hq), dtype=torch.float32, device=dev)
+    esz = 2
+    lq = Hq * D * esz
+    m.profile_enable(True)                           # times the copy stream's fetches
+
+    def step(i):
+        qp = qs.data_ptr() + i * L * lq
+        m.retrieve_raw(0, qp, 1)
+        for l in range(L):
+            if l + 1 < L:
+                m.retrieve_raw(l + 1, qp + (l + 1) * lq, 1)
+            m.attend_raw(l, qp + l * lq, 1, out.data_ptr() + l * lq, lse.data_ptr() + l * Hq * 4)
+
+    lat = []
+    for i in range(steps):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        step(i)
+        torch.cuda.synchronize()
+        lat.append((time.perf_counter() - t) * 1e6)
+    s = m.stats()
+    lat = np.array(lat)
+    cold = lat[::per_topic]
+    warm = np.delete(lat, np.arange(0, steps, per_topic))
+    h2d_gbps = s.h2d_bytes / (s.h2d_busy_ms * 1e-3) / 1e9 if s.h2d_busy_ms > 0 else 0.0
+    checked = None
+    if check:
+        from oracle import mosaic_oracle as orc
+        Ku = torch.cat(keepK).float().numpy().astype(np.float64)
+        Vu = torch.cat(keepV).float().numpy().astype(np.float64)
+        o = orc.OracleUnit(wl.n_clusters, D, T, F, wl.warmup_frames, wl.lloyd_iters, 0)
+        for f in range(F):
+            o.ingest(Ku[f])
+        u = cu[0] * H + cu[1]
+        assert np.array_equal(m.assignments()[u], o.assignments()), "host tier: assignments differ from the oracle"
+        q_last = qs[steps - 1]
+        step(steps - 1)
+        torch.cuda.synchronize()
+        ids, n_ids, sc, toks = m.selection(cu[0])
+        qh = q_last[cu[0]].float().cpu().numpy().astype(np.float64)
+        ids_o, sc_o, tok_o, gap = o.retrieve(qh, cu[1], wl.group, wl.top_k)
+        assert np.array_equal(ids[cu[1], : n_ids[cu[1]]], ids_o) and np.array_equal(toks[cu[1]], tok_o)
+        want, _ = orc.attend(qh, Ku.reshape(-1, D), Vu.reshape(-1, D), tok_o, cu[1], wl.group)
+        got = out[cu[0], :, cu[1] * wl.group:(cu[1] + 1) * wl.group].float().cpu().numpy()
+        err = float(np.abs(got - want).max())
+        assert err <= 2e-2, f"host tier attention err {err}"
+        checked = {"unit": list(cu), "max_out_err": err}
+    m.close()
+    del m
+    torch.cuda.empty_cache()
+    return {"config": {"workload": wl.name, "layers": layers, "layers_of_full_config": 28,
+                       "frames": F, "tokens_per_frame": T, "clusters": wl.n_clusters, "top_k": wl.top_k,
+                       "slab_frames": 16, "cache_fraction": 0.10},
+            "decode_step_us_warm_median": round(float(np.median(warm)), 1),
+            "decode_step_us_topic_switch_mean": round(float(cold.mean()), 1),
+            "ingest_frames_per_s": round(ingest_fps, 1),
+            "roofline": {"bound": "pcie", "achieved": round(h2d_gbps, 2), "peak": round(pcie_gbps, 2),
+                         "unit": "GB/s", "frac": round(h2d_gbps / pcie_gbps, 4) if pcie_gbps else None,
+                         "peak_kind": "measured: one 1 GiB pinned hipMemcpyAsync on this box",
+                         "bytes": int(s.h2d_bytes), "copies": int(s.h2d_copies),
+                         "busy_ms": round(s.h2d_busy_ms, 3)},
+            "cache": {"hits": int(s.cache_hits), "misses": int(s.cache_misses)},
+            "parity_spot_check": checked}
+
+
 def cpu_baseline(wl, K_all, V_all, q_steps, budget_s):
     """The oracle as it stands, on this host: clustering of the sampled units'
     streams (untimed here), then timed decode steps (retrieve + attend), units
@@ -415,6 +532,9 @@ def main():
     if args.workload == "cfg4":
         print(json.dumps(run_prefill_leg(check=args.check_units > 0)))
         return
+    if args.workload == "cfg3":
+        print(json.dumps(run_host_leg(layers=args.layers or 4, check=args.check_units > 0)))
+        return
     wl = inputs.CONFIGS[int(args.workload[-1])]
     if args.layers:
         wl = wl.scaled(n_layers=args.layers)
@@ -438,6 +558,7 @@ def main():
                 "ingest_frames_per_s_batch16": leg["ingest_frames_per_s_batch16"],
                 "question_ms": leg["question_ms"], "parity_spot_check": leg["parity_spot_check"]}
         extra["cfg4_prefill_8_streams"] = run_prefill_leg()
+        extra["cfg3_host_offload"] = run_host_leg()
     us = main_leg.pop("us_per_step")
     result = {
         "metric": "decode_step_retrieve_attend_latency_us",

@@ -82,7 +82,8 @@ typedef struct {
     size_t dev_arena_bytes;
     void *stream;             /* hipStream_t, borrowed; NULL = the null stream */
     /* host tier only (ignored for MOSAIC_TIER_HBM) */
-    int32_t slab_frames;          /* frames per host slab = unit of one host-to-device copy; 0 -> 8 */
+    int32_t slab_frames;          /* frames per host slab (a cluster's pages are contiguous in runs of
+                                     this many frames, keys then values); 0 -> 8 */
     int32_t cache_pages_per_unit; /* GPU cluster-cache capacity per unit, in frame pages (rounded up to
                                      whole slabs); 0 -> 3 * max(cache_fraction, top_k/C) * (max_frames +
                                      C * slab_frames) + top_k * slab_frames, at most the whole stream */
@@ -105,10 +106,10 @@ typedef struct {
     int32_t reserved;
     /* host tier */
     int64_t cache_hits, cache_misses;   /* selected clusters found in / missing from the GPU cache */
-    int64_t h2d_bytes, h2d_copies;      /* cluster fetches: bytes and hipMemcpyAsync calls */
-    double h2d_busy_ms;                 /* time the copy stream spent on those fetches (event pairs
-                                           around each retrieve's copies; filled by mosaic_get_stats,
-                                           which synchronises) */
+    int64_t h2d_bytes, h2d_copies;      /* cluster fetches: bytes moved host-to-device and fetch-kernel launches */
+    double h2d_busy_ms;                 /* time of those fetch kernels (event pairs around each launch while
+                                           mosaic_profile_enable is on; filled by mosaic_get_stats, which
+                                           synchronises) */
 } mosaic_stats;
 
 /* Bytes of device arena and of pinned host arena (0 for MOSAIC_TIER_HBM) a
@@ -154,10 +155,11 @@ int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_de
  * range, NULL).
  * Host tier (layer >= 0 only): scoring and top-k run on an internal selection
  * stream, the ids are read back (the call waits for that small copy only), and
- * every selected cluster missing from the unit's GPU cache is fetched with one
- * asynchronous copy per slab (K and V) on an internal copy stream, so that the
- * fetch for layer l+1 overlaps mosaic_attend of layer l when retrieve(l+1) is
- * issued before attend(l).  ECAPACITY if the selection does not fit the cache. */
+ * every page of a selected cluster that is missing from the unit's GPU cache is
+ * moved by one fetch kernel per call on an internal copy stream (the kernel
+ * reads the pinned slabs over PCIe), so that the fetch for layer l+1 overlaps
+ * mosaic_attend of layer l when retrieve(l+1) is issued before attend(l).
+ * ECAPACITY if the selection does not fit the cache. */
 int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
                         int32_t n_q_tokens);
 

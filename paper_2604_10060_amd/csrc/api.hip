@@ -31,7 +31,7 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 struct Layout {
     size_t k_store, v_store, summ, r, rnorm, n, assign, pos, scores, ids, n_ids, sel_pages, n_sel,
         tok_scratch, part_o, part_ml, stage_k, stage_v, dest, total;
-    size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_total;   // offsets into the pinned host arena
+    size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_moves, host_nmoves, host_total;   // offsets into the pinned host arena
     long long part_entries;
     int Tp, impl, v_transposed;
     // host tier geometry
@@ -101,8 +101,13 @@ Layout make_layout(const mosaic_config &c) {
     }
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-    L.k_store = take(U * (size_t)L.PU * L.kpage);
-    L.v_store = take(U * (size_t)L.PU * L.vpage);
+    if (host) {       // one pool of blocks [SF K pages][SF V pages] per unit
+        L.k_store = take(U * (size_t)L.PU * (L.kpage + L.vpage));
+        L.v_store = L.k_store + (size_t)L.SF * L.kpage;
+    } else {
+        L.k_store = take(U * (size_t)L.PU * L.kpage);
+        L.v_store = take(U * (size_t)L.PU * L.vpage);
+    }
     L.stage_k = take(host ? (size_t)L.SN * U * L.kpage : 0);
     L.stage_v = take(host ? (size_t)L.SN * U * L.vpage : 0);
     L.dest = take(host ? U * (size_t)L.SN * 4 : 0);
@@ -122,14 +127,16 @@ Layout make_layout(const mosaic_config &c) {
     L.part_ml = take((size_t)L.part_entries * 2 * kRowTile * 4);
     L.total = off;
     L.host_k = 0;
-    L.host_v = align_up(host ? U * (size_t)L.HP * L.kpage : 0);
+    L.host_v = host ? (size_t)L.SF * L.kpage : 0;     // inside the first slab: [SF K pages][SF V pages]
     if (host) {
-        size_t ho = L.host_v + align_up(U * (size_t)L.HP * L.vpage);
+        size_t ho = align_up(U * (size_t)L.HP * (L.kpage + L.vpage));
         auto htake = [&](size_t bytes) { size_t o = ho; ho = align_up(ho + bytes); return o; };
         L.host_sel = htake(U * F * 4);      // page lists on their way to the device
         L.host_nsel = htake(U * 4);
         L.host_ids = htake(U * k * 4);      // selections on their way back
         L.host_nids = htake(U * 4);
+        L.host_moves = htake(U * F * 2 * 4);   // fetch work lists, read by the fetch kernel
+        L.host_nmoves = htake(U * 4);
         L.host_total = ho;
     } else {
         L.host_total = 0;
@@ -244,6 +251,19 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.part_o = (float *)(base + L.part_o); dv.part_ml = (float *)(base + L.part_ml);
     dv.part_entries = L.part_entries;
     dv.tier = cfg->tier; dv.PU = L.PU; dv.SN = L.SN; dv.HP = L.HP;
+    dv.kpage = L.kpage; dv.vpage = L.vpage;
+    if (cfg->tier == MOSAIC_TIER_HOST) {
+        dv.SFd = L.SF;
+        dv.k_bstride = dv.v_bstride = (size_t)L.SF * (L.kpage + L.vpage);
+        dv.k_ustride = dv.v_ustride = (size_t)L.cache_blocks * dv.k_bstride;
+        dv.h_bstride = dv.k_bstride;
+        dv.h_ustride = (size_t)L.slabs_per_unit * dv.h_bstride;
+    } else {
+        dv.SFd = 1;
+        dv.k_bstride = L.kpage; dv.k_ustride = (size_t)L.PU * L.kpage;
+        dv.v_bstride = L.vpage; dv.v_ustride = (size_t)L.PU * L.vpage;
+        dv.h_bstride = dv.h_ustride = 0;
+    }
     dv.stage_k = base + L.stage_k; dv.stage_v = base + L.stage_v; dv.dest = (int *)(base + L.dest);
     dv.host_k = dv.host_v = nullptr;
     ctx->host = nullptr;
@@ -271,12 +291,17 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
         ctx->h_nids = (int *)((char *)cfg->host_arena + L.host_nids);
         ctx->h_k = (char *)cfg->host_arena + L.host_k;
         ctx->h_v = (char *)cfg->host_arena + L.host_v;
+        ctx->h_moves = (int *)((char *)cfg->host_arena + L.host_moves);
+        ctx->h_nmoves = (int *)((char *)cfg->host_arena + L.host_nmoves);
+        dv.moves = (const int *)((char *)dptr + L.host_moves);
+        dv.n_moves = (const int *)((char *)dptr + L.host_nmoves);
         HostTier *ht = new (std::nothrow) HostTier();
         if (!ht) return bail(MOSAIC_ENOMEM, "host allocation failed");
         ctx->host = ht;
         ht->init(dv.U, dv.C, L.SF, L.slabs_per_unit, L.cache_blocks, L.max_clusters, L.kpage, L.vpage);
         ht->last_ids.assign(dv.U, {});
         // default-priority streams for selection and for the fetches
+        // two internal streams only: selection (+ value fetches) and key fetches
         if ((e = hipStreamCreateWithFlags(&ht->sel_stream, hipStreamNonBlocking)) != hipSuccess ||
             (e = hipStreamCreateWithFlags(&ht->copy_stream, hipStreamNonBlocking)) != hipSuccess ||
             (e = hipEventCreateWithFlags(&ht->main_mark, hipEventDisableTiming)) != hipSuccess)
@@ -495,18 +520,25 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq) 
         if ((e = hipEventCreate(&b0)) != hipSuccess || (e = hipEventCreate(&b1)) != hipSuccess)
             return fail_hip(ctx, e, "hipEventCreate");
         ht->busy_ev.push_back(b0); ht->busy_ev.push_back(b1);
-        (void)hipEventRecord(b0, ht->copy_stream);
     }
-    std::vector<int> pages;
+    std::vector<int> pages, moves;
+    int max_moves = 0;
     for (int i = 0; i < nu; ++i) {
         const int u = u0 + i;
-        pages.clear();
-        hipError_t he;
-        const int rc = ht->fetch(u, ids + (size_t)i * k, nids[i], ctx->h_k, ctx->h_v, dv.HP, dv.k_store,
-                                 dv.v_store, dv.PU, ht->copy_stream, pages, &he);
-        if (rc == MOSAIC_EHIP) return fail_hip(ctx, he, "cluster fetch");
-        if (rc != MOSAIC_OK) return fail(ctx, rc, "the selected clusters do not fit the GPU cluster cache (raise cache_pages_per_unit / cache_fraction)");
+        pages.clear(); moves.clear();
+        const int rc = ht->fetch(u, ids + (size_t)i * k, nids[i], moves, pages);
+        if (rc != MOSAIC_OK) {
+            char b[256];
+            snprintf(b, sizeof b, "the selected clusters do not fit the GPU cluster cache: unit %d selects %d pages "
+                     "(cache %d pages), a cluster needs %d blocks with %d free and %d clusters resident, none evictable "
+                     "(raise cache_pages_per_unit / cache_fraction)", u, ht->fail_sel_pages, dv.PU, ht->fail_need,
+                     ht->fail_free, ht->fail_cached);
+            return fail(ctx, rc, b);
+        }
         ht->last_ids[u].assign(ids + (size_t)i * k, ids + (size_t)i * k + nids[i]);
+        std::copy(moves.begin(), moves.end(), ctx->h_moves + (size_t)u * dv.F * 2);
+        ctx->h_nmoves[u] = (int)moves.size() / 2;
+        max_moves = std::max(max_moves, (int)moves.size() / 2);
         int *hs = ctx->h_sel + (size_t)u * dv.F;
         std::copy(pages.begin(), pages.end(), hs);
         ctx->h_nsel[u] = (int)pages.size();
@@ -516,6 +548,10 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq) 
     }
     if ((e = hipMemcpyAsync(dv.n_sel + u0, ctx->h_nsel + u0, (size_t)nu * 4, hipMemcpyHostToDevice,
                             ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "page count upload");
+    // one kernel moves every missing page of this layer (timed when profiling is on)
+    if (b0) (void)hipEventRecord(b0, ht->copy_stream);
+    if ((e = launch_fetch(dv, u0, nu, max_moves, ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "fetch launch");
+    if (max_moves > 0) ht->h2d_copies += 1;
     if (b1) (void)hipEventRecord(b1, ht->copy_stream);
     if ((e = hipEventRecord(ht->ready[layer], ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     ht->ready_recorded[layer] = 1;

@@ -93,8 +93,8 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, i
 
     for (int c = c0; c < c1; ++c) {
         const int page = sel[c / cpp], t0 = (c % cpp) * kChunk, nt = min(kChunk, T - t0);
-        const E *kp = reinterpret_cast<const E *>(dv.k_store) + (((size_t)u * dv.PU + page) * T + t0) * D;
-        const E *vp = reinterpret_cast<const E *>(dv.v_store) + (((size_t)u * dv.PU + page) * T + t0) * D;
+        const E *kp = reinterpret_cast<const E *>(k_page(dv, u, page)) + (size_t)t0 * D;
+        const E *vp = reinterpret_cast<const E *>(v_page(dv, u, page)) + (size_t)t0 * D;
         for (int item = tid; item < kChunk * CG; item += kBlock) {
             const int tok = item / CG, cg = item % CG;
             float kv[8], vv[8];

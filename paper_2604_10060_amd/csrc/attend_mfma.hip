@@ -188,9 +188,6 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
     bf16x8 qf[KK];
     load_q<D>(dv, q, lc, h, Tq, n, g, qf);
 
-    const unsigned short *kbase = reinterpret_cast<const unsigned short *>(dv.k_store) + (size_t)u * dv.PU * T * D;
-    const unsigned short *vbase = reinterpret_cast<const unsigned short *>(dv.v_store) + (size_t)u * dv.PU * D * dv.Tp;
-    const size_t kpage_elems = (size_t)T * D, vpage_elems = (size_t)D * dv.Tp;
     const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 
     f32x4 acc[DB];
@@ -206,8 +203,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
         if ((i & 63) == 0 && i > 0) pgs = sel[min((first + stride * (i + lane)) / cpp, F - 1)];
         const int ci = first + stride * i, cc = ci % cpp;
         const int page = __builtin_amdgcn_readlane(pgs, i & 63);
-        issue_chunk<D>(kbase + (size_t)page * kpage_elems,
-                       vbase + (size_t)page * vpage_elems + (size_t)cc * D * 32, cc * kChunk, T, g, n,
+        issue_chunk<D>(reinterpret_cast<const unsigned short *>(k_page(dv, u, page)),
+                       reinterpret_cast<const unsigned short *>(v_page(dv, u, page)) + (size_t)cc * D * 32,
+                       cc * kChunk, T, g, n,
                        kf, vf);
     };
     auto valid = [&](int i) { return min(kChunk, T - ((first + stride * i) % cpp) * kChunk); };
@@ -303,9 +301,6 @@ __global__ __launch_bounds__(kBlock, 1) void k_attend_prefill_mfma(DeviceView dv
     const int NC = dv.n_sel[u] * cpp;
     const int cps = (NC + n_splits - 1) / n_splits;
     const int c0 = split * cps, c1 = min(NC, c0 + cps);
-    const unsigned short *kbase = reinterpret_cast<const unsigned short *>(dv.k_store) + (size_t)u * dv.PU * T * D;
-    const unsigned short *vbase = reinterpret_cast<const unsigned short *>(dv.v_store) + (size_t)u * dv.PU * D * dv.Tp;
-    const size_t kpage_elems = (size_t)T * D, vpage_elems = (size_t)D * dv.Tp;
     const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 
     f32x4 acc[RTW][DB];
@@ -326,8 +321,8 @@ __global__ __launch_bounds__(kBlock, 1) void k_attend_prefill_mfma(DeviceView dv
         if (((c - c0) & 63) == 0) load_pages(c);
         const int page = __builtin_amdgcn_readlane(pgs, (c - c0) & 63);
         const int cc = c % cpp, t0 = cc * kChunk;
-        const unsigned short *kp = kbase + (size_t)page * kpage_elems;
-        const unsigned short *vp = vbase + (size_t)page * vpage_elems + (size_t)cc * D * kChunk;
+        const unsigned short *kp = reinterpret_cast<const unsigned short *>(k_page(dv, u, page));
+        const unsigned short *vp = reinterpret_cast<const unsigned short *>(v_page(dv, u, page)) + (size_t)cc * D * kChunk;
 #pragma unroll
         for (int i = 0; i < KPT; ++i) {
             const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);

@@ -26,9 +26,11 @@ struct HostTier {
     size_t kpage = 0, vpage = 0;                // bytes of one K / V page
     std::vector<Unit> units;
     long long clock = 0;
+    int fail_need = 0, fail_free = 0, fail_cached = 0, fail_sel_pages = 0;   // context of the last ECAPACITY
     long long hits = 0, misses = 0, evictions = 0, h2d_bytes = 0, h2d_copies = 0;
     // streams and events owned by the context
-    hipStream_t sel_stream = nullptr, copy_stream = nullptr;
+    hipStream_t sel_stream = nullptr;    // selection kernel + read-back of the ids
+    hipStream_t copy_stream = nullptr;   // fetch kernel, page-list upload, `ready` events
     hipEvent_t main_mark = nullptr;                 // marks the caller's stream at each retrieve
     std::vector<hipEvent_t> ready, attend_done;     // per layer
     std::vector<char> attend_recorded, ready_recorded;
@@ -41,8 +43,7 @@ struct HostTier {
               size_t kpage, size_t vpage);
     void reset();
     int append(int u, int f, int c);
-    int fetch(int u, const int *ids, int n_ids, char *host_k, char *host_v, int HP, char *cache_k,
-              char *cache_v, int CP, hipStream_t copy, std::vector<int> &pages, hipError_t *hip_err);
+    int fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, std::vector<int> &pages);
 };
 
 } // namespace mosaic

@@ -2,17 +2,17 @@
 // fetched on demand as retrieval units; Sec. VII-B: transfers overlap compute).
 //
 // Pinned host memory holds, per unit, a pool of slabs of `SF` frame pages.  A
-// cluster owns a chain of slabs, so its pages are contiguous in runs of SF and
-// one fetch is a few large copies (one per slab for K, one for V) instead of one
-// per frame.  The GPU side keeps, per unit, a cache of slab-sized blocks with
+// cluster owns a chain of slabs, so its pages are contiguous in runs of SF
+// ([SF K pages][SF V pages]) and a fetch streams a few large contiguous regions.  The GPU side keeps, per unit, a cache of slab-sized blocks with
 // least-recently-used replacement at cluster granularity; the attention kernels
 // read cache slots through the same page list they use in the HBM tier.
 //
 // All bookkeeping (slab chains, cache directory, LRU) is plain host code; the
-// data moves by device stores (ingest) and hipMemcpyAsync (fetch).
+// data moves by device stores into pinned memory (ingest, k_offload) and by
+// device loads from pinned memory (fetch, k_fetch).
 #include <algorithm>
 
-#include "mosaic_internal.h"
+#include "../../include/mosaic.h"
 #include "host_tier.h"
 
 namespace mosaic {
@@ -53,14 +53,15 @@ int HostTier::append(int u, int f, int c) {
     return un.slabs[c].back() * SF + slot;
 }
 
-// Make clusters ids[0..n_ids) of unit u resident, issuing the copies for what is
-// missing on `copy`; appends the cache pages of the selection, in gather order,
-// to `pages`.  Returns MOSAIC_OK or MOSAIC_ECAPACITY.
-int HostTier::fetch(int u, const int *ids, int n_ids, char *host_k, char *host_v, int HP,
-                    char *cache_k, char *cache_v, int CP, hipStream_t copy, std::vector<int> &pages,
-                    hipError_t *hip_err) {
+// Make clusters ids[0..n_ids) of unit u resident: decide what must move (LRU at
+// cluster granularity), append the moves as (host page, cache page) pairs to
+// `moves`, and append the cache pages of the selection, in gather order, to
+// `pages`.  The data itself is moved afterwards by ONE fetch kernel per retrieve
+// that reads the pinned slabs directly over PCIe (measured at the rate of a
+// large DMA copy, without a per-copy API cost).  Returns MOSAIC_OK or
+// MOSAIC_ECAPACITY.
+int HostTier::fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, std::vector<int> &pages) {
     Unit &un = units[u];
-    *hip_err = hipSuccess;
     std::vector<char> pinned(C, 0);
     for (int i = 0; i < n_ids; ++i) pinned[ids[i]] = 1;
     for (int i = 0; i < n_ids; ++i) {
@@ -77,7 +78,12 @@ int HostTier::fetch(int u, const int *ids, int n_ids, char *host_k, char *host_v
             for (int j = 0; j < C; ++j)
                 if (un.cache[j].present && !pinned[j] &&
                     (victim < 0 || un.cache[j].stamp < un.cache[victim].stamp)) victim = j;
-            if (victim < 0) return MOSAIC_ECAPACITY;
+            if (victim < 0) {
+                fail_need = need_blocks; fail_free = (int)un.free_blocks.size(); fail_cached = un.n_cached;
+                fail_sel_pages = 0;
+                for (int q = 0; q < n_ids; ++q) fail_sel_pages += un.n[ids[q]];
+                return MOSAIC_ECAPACITY;
+            }
             Entry &v = un.cache[victim];
             for (int b : v.blocks) un.free_blocks.push_back(b);
             v.blocks.clear(); v.pages = 0; v.present = false;
@@ -89,22 +95,11 @@ int HostTier::fetch(int u, const int *ids, int n_ids, char *host_k, char *host_v
             e.blocks.push_back(un.free_blocks.back());
             un.free_blocks.pop_back();
         }
-        // copy pages [have, want): per slab one copy for K and one for V
-        for (int p0 = have; p0 < want;) {
-            const int si = p0 / SF, j0 = p0 % SF;
-            const int cnt = std::min(SF - j0, want - p0);
-            const size_t hsrc = (size_t)u * HP + (size_t)un.slabs[c][si] * SF + j0;
-            const size_t ddst = (size_t)u * CP + (size_t)e.blocks[si] * SF + j0;
-            hipError_t he = hipMemcpyAsync(cache_k + ddst * kpage, host_k + hsrc * kpage, cnt * kpage,
-                                           hipMemcpyHostToDevice, copy);
-            if (he == hipSuccess)
-                he = hipMemcpyAsync(cache_v + ddst * vpage, host_v + hsrc * vpage, cnt * vpage,
-                                    hipMemcpyHostToDevice, copy);
-            if (he != hipSuccess) { *hip_err = he; return MOSAIC_EHIP; }
-            h2d_bytes += (long long)cnt * (kpage + vpage);
-            h2d_copies += 2;
-            p0 += cnt;
+        for (int p = have; p < want; ++p) {          // pages still in host memory only
+            moves.push_back(un.slabs[c][p / SF] * SF + p % SF);
+            moves.push_back(e.blocks[p / SF] * SF + p % SF);
         }
+        h2d_bytes += (long long)(want - have) * (kpage + vpage);
         e.pages = want;
         e.stamp = ++clock;
         for (int p = 0; p < want; ++p) pages.push_back(e.blocks[p / SF] * SF + p % SF);

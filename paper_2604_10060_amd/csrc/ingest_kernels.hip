@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
     const size_t page = (size_t)u * dv.F + f;          // summary slot
     // where the pages go: the arena's store (HBM tier) or the staging ring (host tier)
     const bool host = dv.tier == MOSAIC_TIER_HOST;
-    const size_t spage = host ? (size_t)(f % dv.SN) * dv.U + u : (size_t)u * dv.PU + f;
+    const size_t spage = host ? (size_t)(f % dv.SN) * dv.U + u : (size_t)u * dv.PU + f;   // HBM tier: SFd = 1
     char *kdst_base = host ? dv.stage_k : dv.k_store;
     char *vdst_base = host ? dv.stage_v : dv.v_store;
 
@@ -382,14 +382,36 @@ __global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frame
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_offload(DeviceView dv, int f0) {
     const int u = blockIdx.x, fl = blockIdx.y, f = f0 + fl;
-    const size_t kpage = (size_t)dv.T * dv.D * dv.esize;
-    const size_t vpage = (size_t)dv.D * (dv.v_transposed ? dv.Tp : dv.T) * dv.esize;
-    const size_t bytes = blockIdx.z == 0 ? kpage : vpage;
+    const size_t bytes = blockIdx.z == 0 ? dv.kpage : dv.vpage;
     const size_t spage = (size_t)(f % dv.SN) * dv.U + u;
-    const size_t hpage = (size_t)u * dv.HP + dv.dest[(size_t)u * dv.SN + fl];
+    const int hp = dv.dest[(size_t)u * dv.SN + fl];        // page within the unit's host pool
+    const size_t hoff = (size_t)u * dv.h_ustride + (size_t)(hp / dv.SFd) * dv.h_bstride + (size_t)(hp % dv.SFd) * bytes;
     const uint4 *src = reinterpret_cast<const uint4 *>((blockIdx.z == 0 ? dv.stage_k : dv.stage_v) + spage * bytes);
-    uint4 *dst = reinterpret_cast<uint4 *>((blockIdx.z == 0 ? dv.host_k : dv.host_v) + hpage * bytes);
+    uint4 *dst = reinterpret_cast<uint4 *>((blockIdx.z == 0 ? dv.host_k : dv.host_v) + hoff);
     for (size_t i = threadIdx.x; i < bytes / 16; i += kBlock) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------
+// Host tier: cluster fetch.  One launch moves every missing page of a layer's
+// selection from the pinned slabs into the GPU cluster cache: the kernel loads
+// straight from host memory over PCIe (16 bytes per lane, a page per workgroup
+// and operand), which streams at the rate of a large DMA copy and costs one
+// launch instead of one runtime call per slab.
+// grid (max moves per unit, 2, n_units): y = 0 keys, y = 1 values.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_fetch(DeviceView dv, int u0) {
+    const int u = u0 + blockIdx.z, i = blockIdx.x;
+    if (i >= dv.n_moves[u]) return;
+    const int hp = dv.moves[((size_t)u * dv.F + i) * 2], cp = dv.moves[((size_t)u * dv.F + i) * 2 + 1];
+    const bool val = blockIdx.y == 1;
+    const size_t bytes = val ? dv.vpage : dv.kpage;
+    const char *src = (val ? dv.host_v : dv.host_k) + (size_t)u * dv.h_ustride +
+                      (size_t)(hp / dv.SFd) * dv.h_bstride + (size_t)(hp % dv.SFd) * bytes;
+    char *dst = (val ? dv.v_store : dv.k_store) + (size_t)u * dv.k_ustride +
+                (size_t)(cp / dv.SFd) * dv.k_bstride + (size_t)(cp % dv.SFd) * bytes;
+    const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
+    uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+    for (size_t j = threadIdx.x; j < bytes / 16; j += kBlock) d4[j] = s4[j];
 }
 
 template <typename F> hipError_t checked(F &&launch) {
@@ -415,6 +437,11 @@ hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const vo
 
 hipError_t launch_offload(const DeviceView &dv, int f0, int n, hipStream_t s) {
     return checked([&] { k_offload<<<dim3(dv.U, n, 2), kBlock, 0, s>>>(dv, f0); });
+}
+
+hipError_t launch_fetch(const DeviceView &dv, int u0, int n_units, int max_moves, hipStream_t s) {
+    if (max_moves <= 0) return hipSuccess;
+    return checked([&] { k_fetch<<<dim3(max_moves, 2, n_units), kBlock, 0, s>>>(dv, u0); });
 }
 
 hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s) {

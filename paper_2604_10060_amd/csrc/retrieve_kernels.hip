@@ -20,26 +20,32 @@ template <> __device__ __forceinline__ double to_f64<unsigned short>(unsigned sh
     return (double)bf16_to_f32(v);
 }
 
-// grid (n_units), 256 threads.  u0 is a multiple of Hkv.
-// A single workgroup per unit is latency-bound, so every global load whose
-// address does not depend on an earlier result (query rows, sizes, norms, the
-// representative rows, and the first frames' assignment/position entries) is
-// issued up front, unconditionally; what follows runs out of LDS and registers.
+// grid (n_units), kRetrBlock threads.  u0 is a multiple of Hkv.
+// A single workgroup per unit is latency-bound, so it is wide (1024 threads) and
+// every global load whose address does not depend on an earlier result (query
+// rows, sizes, norms, the representative rows, and the first frames'
+// assignment/position entries) is issued up front, unconditionally; what
+// follows runs out of LDS and registers.
+constexpr int kRetrBlock = 1024;
+
 template <typename E, int D>
-__global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, const E *q, int Tq,
-                                                     int n_frames, int score_mode, bool write_pages) {
-    constexpr int EPL = D / 16;   // doubles per lane in a 16-lane row group
-    constexpr int FPT = 8;        // frames per thread prefetched for the page-list scatter
-    constexpr int RPF = 4;        // passes of 16 representative rows prefetched into registers
+__global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, const E *q, int Tq,
+                                                         int n_frames, int score_mode, bool write_pages) {
+    constexpr int BLK = kRetrBlock;
+    constexpr int EPL = D / 16;        // doubles per lane in a 16-lane row group
+    constexpr int RPP = BLK / 16;      // representative rows per pass
+    constexpr int FPT = 4;             // frames per thread prefetched for the page-list scatter
+    constexpr int RPF = 2;             // passes of representative rows prefetched into registers
+    constexpr int PARTS = BLK / D;     // threads sharing one channel of the mean query
     const int uc = blockIdx.x, u = u0 + uc, tid = threadIdx.x;
     const int C = dv.C, G = dv.G, Hq = dv.Hq, k = dv.k;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv;
     const int lr = tid % 16, row0 = tid / 16;
     __shared__ double qbar[D];
-    __shared__ double qpart[2][D];
+    __shared__ double qpart[PARTS][D];
     __shared__ double sc_sh[1024];
-    __shared__ int n_sh[1024];
     __shared__ double rn_sh[1024];
+    __shared__ int n_sh[1024];
     __shared__ int rank_sh[1024];   // selection rank of cluster j, or -1
     __shared__ int cnt_sh[1024];
     __shared__ int ids_sh[1024];
@@ -50,44 +56,46 @@ __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, cons
     const int *n = dv.n + (size_t)u * C;
     const int *assign = dv.assign + (size_t)u * dv.F;
     const int *pos = dv.pos + (size_t)u * dv.F;
+
     // ---- independent loads ----
     int fa[FPT], fp[FPT];
 #pragma unroll
     for (int i = 0; i < FPT; ++i) {
-        const int f = tid + kBlock * i;
-        fa[i] = f < n_frames ? assign[f] : -1;
-        fp[i] = f < n_frames ? pos[f] : 0;
+        const int f = tid + BLK * i;
+        const bool in = write_pages && f < n_frames;
+        fa[i] = in ? assign[f] : -1;
+        fp[i] = in ? pos[f] : 0;
     }
-    for (int j = tid; j < C; j += kBlock) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; }
+    for (int j = tid; j < C; j += BLK) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; cnt_sh[j] = 0; }
     if (tid == 0) n_live_sh = 0;
     // representative rows of the first RPF passes (row index clamped, loads unconditional)
     double rpre[RPF][EPL];
 #pragma unroll
     for (int i = 0; i < RPF; ++i) {
-        const double *rj = r + (size_t)min(row0 + 16 * i, C - 1) * D + lr * EPL;
+        const double *rj = r + (size_t)min(row0 + RPP * i, C - 1) * D + lr * EPL;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
     }
-    // mean query over the Tq tokens and the G query heads of this KV head: thread
-    // (d, half) sums its half of the tokens in (t, g) order
+    // mean query over the Tq tokens and the G query heads of this KV head: PARTS
+    // threads per channel, each over a strided share of the tokens, folded in order
     {
-        const int d = tid % D, half = tid / D;          // D = 64: 4 parts, D = 128: 2 parts
-        constexpr int PARTS = kBlock / D;
+        const int d = tid % D, part = tid / D;
         const E *qb = q + (size_t)lc * Tq * Hq * D;
         double acc = 0.0;
-        for (int t = half; t < Tq; t += PARTS)
+        for (int t = part; t < Tq; t += PARTS)
             for (int g = 0; g < G; ++g)
                 acc += to_f64<E>(qb[((size_t)t * Hq + (size_t)h * G + g) * D + d]);
-        if (PARTS == 2) qpart[half][d] = acc;
-        else {                                          // 4 parts: fold pairs through LDS
-            if (half >= 2) qpart[half - 2][d] = acc;
-            __syncthreads();
-            if (half < 2) qpart[half][d] += acc;
-        }
+        qpart[part][d] = acc;
     }
     __syncthreads();
-    if (tid < D) qbar[tid] = (qpart[0][tid] + qpart[1][tid]) / (double)(Tq * G);
+    if (tid < D) {
+        double acc = 0.0;
+#pragma unroll
+        for (int p = 0; p < PARTS; ++p) acc += qpart[p][tid];
+        qbar[tid] = acc / (double)(Tq * G);
+    }
     __syncthreads();
+    // score_j = (qbar . r_j) / |r_j|   (plain dot product in score_mode 1)
     auto finish_row = [&](int j, double p) {
         p = group16_sum(p);
         if (lr == 0) {
@@ -102,7 +110,7 @@ __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, cons
     };
 #pragma unroll
     for (int i = 0; i < RPF; ++i) {
-        const int j = row0 + 16 * i;
+        const int j = row0 + RPP * i;
         if (j < C) {
             double p = 0.0;
 #pragma unroll
@@ -110,7 +118,7 @@ __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, cons
             finish_row(j, p);
         }
     }
-    for (int j = row0 + 16 * RPF; j < C; j += 16) {
+    for (int j = row0 + RPP * RPF; j < C; j += RPP) {
         const double *rj = r + (size_t)j * D + lr * EPL;
         double p = 0.0;
 #pragma unroll
@@ -119,13 +127,11 @@ __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, cons
     }
     __syncthreads();
     // rank among non-empty clusters by (score descending, id ascending).  Empty
-    // clusters carry -inf and so never outrank a live one.  With few clusters the
-    // comparison range of a cluster is shared by several threads.
+    // clusters carry -inf and so never outrank a live one.  The comparison range of
+    // a cluster is shared by P threads.
     {
-        const int P = C <= 64 ? 4 : (C <= 128 ? 2 : 1);
-        for (int j = tid; j < C; j += kBlock) cnt_sh[j] = 0;
-        __syncthreads();
-        for (int item = tid; item < C * P; item += kBlock) {
+        const int P = C <= 64 ? 16 : (C <= 128 ? 8 : (C <= 256 ? 4 : (C <= 512 ? 2 : 1)));
+        for (int item = tid; item < C * P; item += BLK) {
             const int j = item % C, part = item / C;
             if (n_sh[j] <= 0) continue;
             const double sj = sc_sh[j];
@@ -139,7 +145,7 @@ __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, cons
             atomicAdd(&cnt_sh[j], c);
         }
         __syncthreads();
-        for (int j = tid; j < C; j += kBlock) {
+        for (int j = tid; j < C; j += BLK) {
             int rk = -1;
             if (n_sh[j] > 0) {
                 rk = cnt_sh[j];
@@ -158,16 +164,18 @@ __global__ __launch_bounds__(kBlock) void k_retrieve(DeviceView dv, int u0, cons
         dv.n_ids[u] = n_ids;
         if (write_pages) dv.n_sel[u] = o;
     }
-    for (int i = tid; i < k; i += kBlock) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
+    for (int i = tid; i < k; i += BLK) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
     __syncthreads();
+    if (!write_pages) return;     // host tier: the host maps clusters to cache slots
+    // page list: clusters in selection order, member frames ascending
     int *sel = dv.sel_pages + (size_t)u * dv.F;
 #pragma unroll
     for (int i = 0; i < FPT; ++i) {
         if (fa[i] < 0) continue;
         const int rk = rank_sh[fa[i]];
-        if (rk >= 0) sel[off_sh[rk] + fp[i]] = tid + kBlock * i;
+        if (rk >= 0) sel[off_sh[rk] + fp[i]] = tid + BLK * i;
     }
-    for (int f = tid + kBlock * FPT; f < n_frames; f += kBlock) {
+    for (int f = tid + BLK * FPT; f < n_frames; f += BLK) {
         const int c = assign[f];
         if (c < 0) continue;
         const int rk = rank_sh[c];
@@ -190,11 +198,11 @@ __global__ __launch_bounds__(kBlock) void k_expand_tok_idx(DeviceView dv, int u0
 hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                            int n_frames, int score_mode, bool write_pages, hipStream_t s) {
     if (dv.esize == 4) {
-        if (dv.D == 64) k_retrieve<float, 64><<<n_units, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
-        else k_retrieve<float, 128><<<n_units, kBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
+        if (dv.D == 64) k_retrieve<float, 64><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
+        else k_retrieve<float, 128><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
     } else {
-        if (dv.D == 64) k_retrieve<unsigned short, 64><<<n_units, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
-        else k_retrieve<unsigned short, 128><<<n_units, kBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
+        if (dv.D == 64) k_retrieve<unsigned short, 64><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
+        else k_retrieve<unsigned short, 128><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
     }
     return hipGetLastError();
 }

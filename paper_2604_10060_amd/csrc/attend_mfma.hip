@@ -26,6 +26,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 ld_frag(const unsigned short *p) {
     const uint4 w = *reinterpret_cast<const uint4 *>(p);
@@ -55,12 +56,17 @@ constexpr float kLazy = 8.0f;
 // (the rest are clamped re-reads and get weight 0).  Three phases -- all logit
 // MFMAs, all softmax arithmetic, all output MFMAs -- so the independent chains
 // of the tiles overlap.
-template <int D, int R>
+// The normaliser l is either a per-lane float (sum of this lane's 8 weights; the caller
+// adds the four lane groups at the end) or an f32x4 accumulator fed by one more MFMA
+// whose A operand is all ones: every element of it is then the row's full sum over
+// the 32 tokens, and the 8 adds per tile leave the vector ALU.
+template <int D, int R, typename LT>
 __device__ __forceinline__ void chunk_step_multi(const bf16x8 (&kf)[2 * (D / 32)], const bf16x8 (&vf)[D / 16],
                                                  const bf16x8 (&qf)[R][D / 32], int n_valid, int g,
                                                  float sl2, f32x4 (&acc)[R][D / 16], float (&m)[R],
-                                                 float (&l)[R]) {
+                                                 LT (&l)[R]) {
     constexpr int KK = D / 32, DB = D / 16;
+    constexpr bool kSumByMfma = sizeof(LT) == sizeof(f32x4);
     f32x4 s[R][2];
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -89,23 +95,31 @@ __device__ __forceinline__ void chunk_step_multi(const bf16x8 (&kf)[2 * (D / 32)
             cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
             const float mnew = fmaxf(m[r], cm);
             const float alpha = __builtin_amdgcn_exp2f(m[r] - mnew);
-            l[r] *= alpha;
+            l[r] = l[r] * alpha;
             m[r] = mnew;
 #pragma unroll
             for (int db = 0; db < DB; ++db) acc[r][db] = acc[r][db] * alpha;
         }
         const float nm = -m[r];
         unsigned int pw[4];
-        float psum = 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r][(2 * j) / 4][(2 * j) % 4], sl2, nm));
             const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r][(2 * j + 1) / 4][(2 * j + 1) % 4], sl2, nm));
             pw[j] = pack_bf16(p0, p1);
-            psum += bf16_lo(pw[j]) + bf16_hi(pw[j]);   // the normaliser uses the rounded weights
         }
-        l[r] += psum;
         pf[r] = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+        if constexpr (!kSumByMfma) {               // the normaliser uses the rounded weights
+            float psum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) psum += bf16_lo(pw[j]) + bf16_hi(pw[j]);
+            l[r] += psum;
+        }
+    }
+    if constexpr (kSumByMfma) {
+        const bf16x8 ones = __builtin_bit_cast(bf16x8, make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u));
+#pragma unroll
+        for (int r = 0; r < R; ++r) l[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf[r], l[r], 0, 0, 0);
     }
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -123,7 +137,7 @@ __device__ __forceinline__ void chunk_step(const bf16x8 (&kf)[2 * (D / 32)], con
     f32x4 (&a1)[1][D / 16] = reinterpret_cast<f32x4 (&)[1][D / 16]>(acc);
     float (&m1)[1] = reinterpret_cast<float (&)[1]>(m);
     float (&l1)[1] = reinterpret_cast<float (&)[1]>(l);
-    chunk_step_multi<D, 1>(kf, vf, q1, n_valid, g, sl2, a1, m1, l1);
+    chunk_step_multi<D, 1, float>(kf, vf, q1, n_valid, g, sl2, a1, m1, l1);
 }
 
 // Issue the 16-byte operand loads of one chunk.  Tokens beyond the page's T are
@@ -261,22 +275,22 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
 }
 
 // ---------------------------------------------------------------------------
-// Multi-token questions (MFMA-bound).  A workgroup owns 256 query rows: wave w
-// holds kPrefillTiles row tiles of 16 in registers and all four waves walk the
-// same chunk range, so each 32-token K/V chunk is fetched from memory once per
-// workgroup, staged in LDS (double-buffered, next chunk's global loads in flight
-// during the current chunk's MFMAs) and read as MFMA operands by every wave.
+// Multi-token questions (MFMA-bound).  A workgroup owns 64 * kPrefillTiles query
+// rows: wave w holds kPrefillTiles row tiles of 16 in registers and all four waves
+// walk the same chunk range, so each 32-token K/V chunk is fetched from memory once
+// per workgroup, staged in LDS (double-buffered; the loads of the next two chunks
+// are in flight, in two register sets, during the current chunk's MFMAs) and read
+// as MFMA operands by every wave.  Two workgroups share a CU, so one's barriers and
+// softmax arithmetic overlap the other's MFMAs.
 // LDS rows are padded (K: +16 B, V: +16 B) and the K rows are stored in MFMA
 // slot order so that the 16-byte operand reads are bank-conflict free.
-// grid (n_units * n_splits, ceil(NT / 16)); split_slot() shares the split
+// grid (n_units * n_splits, ceil(NT / (4 * kPrefillTiles))); split_slot() shares the split
 // workgroups out over the units by retrieved size.  With the x extent a multiple
 // of 8 the workgroups sharing a (unit, split) have ids congruent mod 8, i.e. land
 // on the same XCD, and their K/V re-reads hit that XCD's L2.
 // ---------------------------------------------------------------------------
-constexpr int kPrefillTiles = 4;   // row tiles per wave
-
 template <int D>
-__global__ __launch_bounds__(kBlock, 1) void k_attend_prefill_mfma(DeviceView dv, int u0, int n_units,
+__global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv, int u0, int n_units,
                                                                    const unsigned short *q, int Tq,
                                                                    int NT) {
     constexpr int KK = D / 32, DB = D / 16, RTW = kPrefillTiles;
@@ -298,56 +312,87 @@ __global__ __launch_bounds__(kBlock, 1) void k_attend_prefill_mfma(DeviceView dv
     for (int r = 0; r < RTW; ++r) load_q<D>(dv, q, lc, h, Tq, (tile0 + r) * kRowTile + n, g, qf[r]);
 
     const int *sel = dv.sel_pages + (size_t)u * F;
-    const int NC = dv.n_sel[u] * cpp;
+    const int NC = __builtin_amdgcn_readfirstlane(dv.n_sel[u]) * cpp;
     const int cps = (NC + n_splits - 1) / n_splits;
-    const int c0 = split * cps, c1 = min(NC, c0 + cps);
+    const int c0 = __builtin_amdgcn_readfirstlane(split * cps);
+    const int c1 = __builtin_amdgcn_readfirstlane(min(NC, c0 + cps));
     const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 
-    f32x4 acc[RTW][DB];
-    float m[RTW], l[RTW];
+    f32x4 acc[RTW][DB], l[RTW];                    // l: row sums, kept by an all-ones MFMA
+    float m[RTW];
 #pragma unroll
     for (int r = 0; r < RTW; ++r) {
-        m[r] = -INFINITY; l[r] = 0.f;
+        m[r] = -INFINITY; l[r] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int db = 0; db < DB; ++db) acc[r][db] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // page ids of this split's chunks, one per lane (64 at a time), so that a chunk's
-    // operand addresses never wait on a dependent load
-    int pgs = 0;
-    auto load_pages = [&](int c) { pgs = sel[min((c + lane) / cpp, F - 1)]; };
-    uint4 kregA[KPT], vregA[VPT], kregB[KPT], vregB[VPT];
-    auto fetch = [&](int c, uint4 (&kreg)[KPT], uint4 (&vreg)[VPT]) {   // global -> registers
-        if (((c - c0) & 63) == 0) load_pages(c);
-        const int page = __builtin_amdgcn_readlane(pgs, (c - c0) & 63);
-        const int cc = c % cpp, t0 = cc * kChunk;
-        const unsigned short *kp = reinterpret_cast<const unsigned short *>(k_page(dv, u, page));
-        const unsigned short *vp = reinterpret_cast<const unsigned short *>(v_page(dv, u, page)) + (size_t)cc * D * kChunk;
-#pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);
-            kreg[i] = *reinterpret_cast<const uint4 *>(kp + (size_t)min(t0 + t, T - 1) * D + seg * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int p = tid + kBlock * i;
-            vreg[i] = *reinterpret_cast<const uint4 *>(vp + (size_t)p * 8);   // chunk block is contiguous
-        }
+    // Chunks are fetched in order.  The fetch cursor (chunk nf = chunk f_cc of the
+    // f_pi-th selected page) advances by increments, page addresses are worked out once
+    // per page, and the id of the page after the current one is read (a wave-uniform
+    // load) a whole page ahead, so no fetch waits on a dependent load or divides.
+    const int cl = c1 - 1, n_pages = NC / cpp;
+    const char *const kbase = dv.k_store + (size_t)u * dv.k_ustride;
+    const char *const vbase = dv.v_store + (size_t)u * dv.v_ustride;
+    int nf = c0, f_pi = c0 / cpp, f_cc = c0 - f_pi * cpp;
+    const unsigned short *f_kp = nullptr, *f_vp = nullptr;
+    auto set_page = [&](int page) {
+        const int b = dv.SFd == 1 ? page : page / dv.SFd, r = dv.SFd == 1 ? 0 : page - b * dv.SFd;
+        f_kp = reinterpret_cast<const unsigned short *>(kbase + (size_t)b * dv.k_bstride + (size_t)r * dv.kpage);
+        f_vp = reinterpret_cast<const unsigned short *>(vbase + (size_t)b * dv.v_bstride + (size_t)r * dv.vpage);
     };
-    auto stage = [&](int buf, const uint4 (&kreg)[KPT], const uint4 (&vreg)[VPT]) {   // registers -> LDS
-#pragma unroll
-        for (int i = 0; i < KPT; ++i) {
+    int pg_next = 0;
+    if (c0 < c1) {
+        set_page(sel[f_pi]);
+        pg_next = sel[min(f_pi + 1, n_pages - 1)];
+    }
+    int c_cc = f_cc;                                  // compute cursor: chunk inside its page
+    // One chunk's worth of 16-byte pieces per thread (KPT, VPT <= 2), held in named
+    // members so that both register sets stay in VGPRs.
+    static_assert(KPT >= 1 && KPT <= 2 && VPT >= 1 && VPT <= 2, "piece count per thread");
+    struct Regs { u32x4 k0, k1, v0, v1; };
+    Regs ra, rb;
+    auto fetch = [&]() -> Regs {   // global -> registers; past the end re-reads the last chunk
+        const int t0 = f_cc * kChunk;
+        const unsigned short *kp = f_kp, *vp = f_vp + (size_t)f_cc * D * kChunk;
+        auto kpiece = [&](int i) {
+            const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);
+            return *reinterpret_cast<const u32x4 *>(kp + (size_t)min(t0 + t, T - 1) * D + seg * 8);
+        };
+        auto vpiece = [&](int i) {   // chunk block is contiguous
+            return *reinterpret_cast<const u32x4 *>(vp + (size_t)(tid + kBlock * i) * 8);
+        };
+        Regs r;
+        r.k0 = kpiece(0);
+        r.k1 = KPT > 1 ? kpiece(KPT - 1) : r.k0;
+        r.v0 = vpiece(0);
+        r.v1 = VPT > 1 ? vpiece(VPT - 1) : r.v0;
+        if (nf < cl) {                                // wave-uniform
+            ++nf;
+            if (++f_cc == cpp) {
+                f_cc = 0; ++f_pi;
+                set_page(pg_next);
+                pg_next = sel[min(f_pi + 1, n_pages - 1)];
+            }
+        }
+        return r;
+    };
+    auto stage = [&](int buf, const Regs &r) {   // registers -> LDS
+        auto kput = [&](int i, u32x4 x) {
             const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);
             const int row = 16 * ((t / 4) % 2) + 4 * (t / 8) + t % 4;   // MFMA slot order
-            *reinterpret_cast<uint4 *>(&k_lds[buf][row][seg * 8]) = kreg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
+            *reinterpret_cast<u32x4 *>(&k_lds[buf][row][seg * 8]) = x;
+        };
+        auto vput = [&](int i, u32x4 x) {
             const int p = tid + kBlock * i, d = p / (kChunk / 8), seg = p % (kChunk / 8);
-            *reinterpret_cast<uint4 *>(&v_lds[buf][d][seg * 8]) = vreg[i];
-        }
+            *reinterpret_cast<u32x4 *>(&v_lds[buf][d][seg * 8]) = x;
+        };
+        kput(0, r.k0);
+        if (KPT > 1) kput(1, r.k1);
+        vput(0, r.v0);
+        if (VPT > 1) vput(1, r.v1);
     };
-    auto compute = [&](int c, int buf) {
+    auto compute = [&](int buf) {
         bf16x8 kf[2 * KK], vf[DB];
 #pragma unroll
         for (int tau = 0; tau < 2; ++tau)
@@ -359,41 +404,41 @@ __global__ __launch_bounds__(kBlock, 1) void k_attend_prefill_mfma(DeviceView dv
         for (int db = 0; db < DB; ++db)
             vf[db] = __builtin_bit_cast(
                 bf16x8, *reinterpret_cast<const uint4 *>(&v_lds[buf][16 * db + n][8 * g]));
-        const int n_valid = min(kChunk, T - (c % cpp) * kChunk);
-        chunk_step_multi<D, RTW>(kf, vf, qf, n_valid, g, sl2, acc, m, l);
+        const int n_valid = min(kChunk, T - c_cc * kChunk);
+        c_cc = c_cc + 1 == cpp ? 0 : c_cc + 1;
+        chunk_step_multi<D, RTW, f32x4>(kf, vf, qf, n_valid, g, sl2, acc, m, l);
     };
 
     // Pipeline: chunk c is computed from LDS buffer (c-c0)&1 while chunk c+1 sits in one
     // register set and chunk c+2 is in flight in the other (two chunks of memory latency
-    // hidden behind every chunk of arithmetic).
+    // hidden behind every chunk of arithmetic).  Fetches past the end re-read the last
+    // chunk instead of being skipped, so the register sets are written unconditionally
+    // and stay in registers.
     if (c0 < c1) {
-        fetch(c0, kregA, vregA);
-        if (c0 + 1 < c1) fetch(c0 + 1, kregB, vregB);
-        stage(0, kregA, vregA);
+        ra = fetch();
+        rb = fetch();
+        stage(0, ra);
         __syncthreads();
         int c = c0;
-        while (true) {
-            // here: LDS[(c-c0)&1] holds c, regs B hold c+1
-            if (c + 2 < c1) fetch(c + 2, kregA, vregA);
-            compute(c, (c - c0) & 1);
-            if (c + 1 < c1) stage(((c - c0) & 1) ^ 1, kregB, vregB);
+        for (; c + 1 < c1; c += 2) {
+            // LDS[0] holds c, regs B hold c+1
+            ra = fetch();
+            compute(0);
+            stage(1, rb);
             __syncthreads();
-            if (++c >= c1) break;
-            // here: LDS[(c-c0)&1] holds c, regs A hold c+1
-            if (c + 2 < c1) fetch(c + 2, kregB, vregB);
-            compute(c, (c - c0) & 1);
-            if (c + 1 < c1) stage(((c - c0) & 1) ^ 1, kregA, vregA);
+            // LDS[1] holds c+1, regs A hold c+2
+            rb = fetch();
+            compute(1);
+            stage(0, ra);
             __syncthreads();
-            if (++c >= c1) break;
         }
+        if (c < c1) compute(0);
     }
 #pragma unroll
     for (int r = 0; r < RTW; ++r) {
         const int tile = tile0 + r;
         if (tile >= NT) break;
-        float lr = l[r];
-        lr += __shfl_xor(lr, 16, 64);
-        lr += __shfl_xor(lr, 32, 64);
+        const float lr = l[r][0];
         const size_t entry = (size_t)slot.base * NT + (size_t)tile * n_splits + split;
         float *po = dv.part_o + (entry * kRowTile + n) * D;
 #pragma unroll

@@ -14,6 +14,7 @@ constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts of 64)
 constexpr int kRowTile = 16;      // query rows per attention tile
 constexpr int kChunk = 32;        // tokens per attention step, always inside one page
 constexpr int kMaxSplits = 64;    // KV splits per (unit, row tile)
+constexpr int kPrefillTiles = 2;  // row tiles per wavefront in the multi-tile MFMA kernel
 
 // Device-side view of one context: plain pointers into the caller's arena.
 struct DeviceView {

@@ -194,11 +194,10 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
     const int T = dv.T, F = dv.F, cpp = dv.chunks_per_page;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * dv.G;
     const int *sel = dv.sel_pages + (size_t)u * F;
-    const int stride = 4 * S, first = split + S * wave;
+    // wave-uniform chunk walk: wave w of split s takes chunks first + stride * i
+    const int stride = __builtin_amdgcn_readfirstlane(4 * S);
+    const int first = __builtin_amdgcn_readfirstlane(split + S * wave);
 
-    const int nsel = dv.n_sel[u];
-    // page ids of this wave's first 64 chunks, one per lane
-    int pgs = sel[min((first + stride * lane) / cpp, F - 1)];
     bf16x8 qf[KK];
     load_q<D>(dv, q, lc, h, Tq, n, g, qf);
 
@@ -209,31 +208,61 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
     for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m = -INFINITY, l = 0.f;
 
-    const int NC = nsel * cpp;
-    const int n_my = first < NC ? (NC - first + stride - 1) / stride : 0;
+    const int NC = __builtin_amdgcn_readfirstlane(dv.n_sel[u]) * cpp;
+    const int n_my = __builtin_amdgcn_readfirstlane(first < NC ? (NC - first + stride - 1) / stride : 0);
 
+    // The page id of a chunk is read (a wave-uniform scalar load) one step before the
+    // chunk's operand loads are issued, the cursor that walks the selection advances by
+    // increments (no division in the loop), and inside the steady-state loop every load
+    // is issued unconditionally, so the operand loads of chunk i+1 stay in flight across
+    // the whole reduction of chunk i.
     bf16x8 kA[2 * KK], vA[DB], kB[2 * KK], vB[DB];
-    auto issue = [&](int i, bf16x8 (&kf)[2 * KK], bf16x8 (&vf)[DB]) {
-        if ((i & 63) == 0 && i > 0) pgs = sel[min((first + stride * (i + lane)) / cpp, F - 1)];
-        const int ci = first + stride * i, cc = ci % cpp;
-        const int page = __builtin_amdgcn_readlane(pgs, i & 63);
-        issue_chunk<D>(reinterpret_cast<const unsigned short *>(k_page(dv, u, page)),
-                       reinterpret_cast<const unsigned short *>(v_page(dv, u, page)) + (size_t)cc * D * 32,
-                       cc * kChunk, T, g, n,
-                       kf, vf);
+    int ccA = 0, ccB = 0;                             // chunk index inside its page
+    const int sq = __builtin_amdgcn_readfirstlane(stride / cpp), sr = __builtin_amdgcn_readfirstlane(stride % cpp);
+    int lq = __builtin_amdgcn_readfirstlane(first / cpp), lr = __builtin_amdgcn_readfirstlane(first % cpp), lj = 0;
+    auto lookup = [&](int &page, int &cc) {           // page and in-page chunk of the cursor's chunk
+        page = sel[lq]; cc = lr;
+        if (lj + 1 < n_my) {                          // advance, stopping at the wave's last chunk
+            ++lj; lq += sq; lr += sr;
+            if (lr >= cpp) { lr -= cpp; ++lq; }
+        }
     };
-    auto valid = [&](int i) { return min(kChunk, T - ((first + stride * i) % cpp) * kChunk); };
+    auto issue = [&](int page, int cc_in, bf16x8 (&kf)[2 * KK], bf16x8 (&vf)[DB], int &cc) {
+        cc = cc_in;
+        const int b = dv.SFd == 1 ? page : page / dv.SFd, r = dv.SFd == 1 ? 0 : page - b * dv.SFd;
+        const char *kp = dv.k_store + (size_t)u * dv.k_ustride + (size_t)b * dv.k_bstride + (size_t)r * dv.kpage;
+        const char *vp = dv.v_store + (size_t)u * dv.v_ustride + (size_t)b * dv.v_bstride + (size_t)r * dv.vpage;
+        issue_chunk<D>(reinterpret_cast<const unsigned short *>(kp),
+                       reinterpret_cast<const unsigned short *>(vp) + (size_t)cc * D * 32,
+                       cc * kChunk, T, g, n, kf, vf);
+    };
+    auto step = [&](const bf16x8 (&kf)[2 * KK], const bf16x8 (&vf)[DB], int cc) {
+        chunk_step<D>(kf, vf, qf, min(kChunk, T - cc * kChunk), g, sl2, acc, m, l);
+    };
 
     if (n_my > 0) {
+        int pg, cc, pg_n, cc_n;
+        lookup(pg, cc);
+        lookup(pg_n, cc_n);
+        issue(pg, cc, kA, vA, ccA);
         int i = 0;
-        issue(0, kA, vA);
-        while (true) {
-            if (i + 1 < n_my) issue(i + 1, kB, vB);
-            chunk_step<D>(kA, vA, qf, valid(i), g, sl2, acc, m, l);
-            if (++i >= n_my) break;
-            if (i + 1 < n_my) issue(i + 1, kA, vA);
-            chunk_step<D>(kB, vB, qf, valid(i), g, sl2, acc, m, l);
-            if (++i >= n_my) break;
+        for (; i + 2 < n_my; i += 2) {                // A holds chunk i; (pg_n, cc_n) is chunk i+1
+            issue(pg_n, cc_n, kB, vB, ccB);
+            lookup(pg_n, cc_n);
+            __builtin_amdgcn_sched_barrier(0);        // keep the loads ahead of the arithmetic
+            step(kA, vA, ccA);
+            issue(pg_n, cc_n, kA, vA, ccA);
+            lookup(pg_n, cc_n);
+            __builtin_amdgcn_sched_barrier(0);
+            step(kB, vB, ccB);
+        }
+        if (i + 2 == n_my) {
+            issue(pg_n, cc_n, kB, vB, ccB);
+            __builtin_amdgcn_sched_barrier(0);
+            step(kA, vA, ccA);
+            step(kB, vB, ccB);
+        } else {
+            step(kA, vA, ccA);
         }
     }
     l += __shfl_xor(l, 16, 64);

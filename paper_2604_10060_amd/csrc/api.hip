@@ -154,12 +154,13 @@ int choose_splits(const mosaic_ctx *ctx, int n_units, int Tq) {
     const long long est_chunks = est_pages * dv.chunks_per_page;
     long long s;
     if (NT > 1 && mfma) {
-        // MFMA-bound multi-tile launches: every split re-writes 16 x D partial rows per
-        // tile, so only as many splits as needed to give every CU's two resident
-        // workgroups two rounds of work (measured best on config 4), each with at
-        // least 8 chunks; a multiple of 8 keeps the workgroups that share a
-        // (unit, split) on one XCD (workgroup ids congruent mod 8)
-        s = (1024 + n_units * row_blocks - 1) / (n_units * row_blocks);
+        // MFMA-bound multi-tile launches: every split writes 16 x D partial rows per
+        // tile that the combine kernel reads back, so only as many splits as fill the
+        // chip's two resident workgroups per CU once (more splits raise the attention
+        // kernel's rate a little but cost more in the combine; measured on config 4),
+        // each with at least 8 chunks; a multiple of 8 keeps the workgroups that share
+        // a (unit, split) on one XCD (workgroup ids congruent mod 8)
+        s = (512 + n_units * row_blocks - 1) / (n_units * row_blocks);
         s = std::min(s, std::max<long long>(1, est_chunks / 8));
         if (s >= 8) s = s / 8 * 8;
     } else {

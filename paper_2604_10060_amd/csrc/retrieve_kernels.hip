@@ -77,15 +77,24 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
     }
     // mean query over the Tq tokens and the G query heads of this KV head: PARTS
-    // threads per channel, each over a strided share of the tokens, folded in order
+    // threads per channel, each over a strided share of the Tq * G query rows, eight
+    // rows' loads in flight at a time (row index clamped, loads unconditional)
     {
-        const int d = tid % D, part = tid / D;
-        const E *qb = q + (size_t)lc * Tq * Hq * D;
-        double acc = 0.0;
-        for (int t = part; t < Tq; t += PARTS)
-            for (int g = 0; g < G; ++g)
-                acc += to_f64<E>(qb[((size_t)t * Hq + (size_t)h * G + g) * D + d]);
-        qpart[part][d] = acc;
+        const int d = tid % D, part = tid / D, R = Tq * G;
+        const E *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + d;
+        double a[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+        for (int r0 = part; r0 < R; r0 += 8 * PARTS) {
+            E v[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int rr = min(r0 + x * PARTS, R - 1), t = rr / G, g = rr - t * G;
+                v[x] = qb[((size_t)t * Hq + g) * D];
+            }
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+                if (r0 + x * PARTS < R) a[x] += to_f64<E>(v[x]);
+        }
+        qpart[part][d] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     }
     __syncthreads();
     if (tid < D) {

@@ -313,26 +313,34 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
 // softmax arithmetic overlap the other's MFMAs.
 // LDS rows are padded (K: +16 B, V: +16 B) and the K rows are stored in MFMA
 // slot order so that the 16-byte operand reads are bank-conflict free.
-// grid (n_units * n_splits, ceil(NT / (4 * kPrefillTiles))); split_slot() shares the split
-// workgroups out over the units by retrieved size.  With the x extent a multiple
-// of 8 the workgroups sharing a (unit, split) have ids congruent mod 8, i.e. land
-// on the same XCD, and their K/V re-reads hit that XCD's L2.
+// A group is one (unit, split) slot -- split_slot() shares the slots out over the
+// units by retrieved size -- and its n_row_blocks workgroups read the same K/V range.
+// Workgroups go to the 8 XCDs round-robin by id and are dispatched in id order, so
+// the 1-D grid is laid out as id = 8 * (row block + n_row_blocks * (group / 8)) +
+// group % 8: a group's workgroups share one XCD (one L2) and have neighbouring
+// dispatch slots there, which keeps them together in time -- also when the grid
+// exceeds the chip or several streams' kernels interleave -- so the group's K/V is
+// fetched from memory once and found in L2 by the rest.
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv, int u0, int n_units,
                                                                    const unsigned short *q, int Tq,
-                                                                   int NT) {
+                                                                   int NT, int n_groups, int n_row_blocks) {
     constexpr int KK = D / 32, DB = D / 16, RTW = kPrefillTiles;
     constexpr int KROW = D + 8, VROW = kChunk + 8;       // LDS row strides in elements
     constexpr int KPIECES = kChunk * D / 8, VPIECES = D * kChunk / 8;   // 16-byte pieces per chunk
     constexpr int KPT = KPIECES / kBlock, VPT = VPIECES / kBlock;       // pieces per thread
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
-    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, gridDim.x, blockIdx.x);
-    if (slot.uc < 0) return;                       // block-uniform: no barrier reached yet
+    // workgroup id -> (group = (unit, split) slot, row block): see the mapping above
+    const int xcd = (int)blockIdx.x % 8, seq = (int)blockIdx.x / 8;
+    const int grp = (seq / n_row_blocks) * 8 + xcd, yb = seq % n_row_blocks;
+    if (grp >= n_groups) return;                   // block-uniform: no barrier reached yet
+    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, n_groups, grp);
+    if (slot.uc < 0) return;
     const int uc = slot.uc, u = u0 + uc, split = slot.split, n_splits = slot.S;
     const int T = dv.T, F = dv.F, cpp = dv.chunks_per_page;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv;
-    const int tile0 = ((int)blockIdx.y * 4 + wave) * RTW;
+    const int tile0 = (yb * 4 + wave) * RTW;
     __shared__ __attribute__((aligned(16))) unsigned short k_lds[2][kChunk][KROW];
     __shared__ __attribute__((aligned(16))) unsigned short v_lds[2][D][VROW];
 
@@ -493,9 +501,10 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
         if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_decode_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq);
         else hipExtLaunchKernelGGL(k_attend_decode_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq);
     } else {
-        const dim3 grid(n_units * n_splits, (NT + 4 * kPrefillTiles - 1) / (4 * kPrefillTiles));
-        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_prefill_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT);
-        else hipExtLaunchKernelGGL(k_attend_prefill_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT);
+        const int n_groups = n_units * n_splits, rb = (NT + 4 * kPrefillTiles - 1) / (4 * kPrefillTiles);
+        const dim3 grid((n_groups + 7) / 8 * 8 * rb);
+        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_prefill_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb);
+        else hipExtLaunchKernelGGL(k_attend_prefill_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb);
     }
     return hipGetLastError();
 }

@@ -31,7 +31,7 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 struct Layout {
     size_t k_store, v_store, summ, r, rnorm, n, assign, pos, scores, ids, n_ids, sel_pages, n_sel,
         tok_scratch, part_o, part_ml, stage_k, stage_v, dest, total;
-    size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_moves, host_nmoves, host_total;   // offsets into the pinned host arena
+    size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_moves, host_nmoves, host_assign, host_dest, host_total;   // offsets into the pinned host arena
     long long part_entries;
     int Tp, impl, v_transposed;
     // host tier geometry
@@ -137,6 +137,8 @@ Layout make_layout(const mosaic_config &c) {
         L.host_nids = htake(U * 4);
         L.host_moves = htake(U * F * 2 * 4);   // fetch work lists, read by the fetch kernel
         L.host_nmoves = htake(U * 4);
+        L.host_assign = htake(U * (size_t)L.SN * 4);  // assignments of a staged batch on their way back
+        L.host_dest = htake(U * (size_t)L.SN * 4);    // their slab positions on their way to the device
         L.host_total = ho;
     } else {
         L.host_total = 0;
@@ -295,6 +297,8 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
         ctx->h_v = (char *)cfg->host_arena + L.host_v;
         ctx->h_moves = (int *)((char *)cfg->host_arena + L.host_moves);
         ctx->h_nmoves = (int *)((char *)cfg->host_arena + L.host_nmoves);
+        ctx->h_assign = (int *)((char *)cfg->host_arena + L.host_assign);
+        ctx->h_dest = (int *)((char *)cfg->host_arena + L.host_dest);
         dv.moves = (const int *)((char *)dptr + L.host_moves);
         dv.n_moves = (const int *)((char *)dptr + L.host_nmoves);
         HostTier *ht = new (std::nothrow) HostTier();
@@ -365,9 +369,16 @@ static int offload_range(mosaic_ctx *ctx, int f0, int f1) {
     const DeviceView &dv = ctx->dv;
     HostTier *ht = ctx->host;
     const int n = f1 - f0;
-    std::vector<int> a((size_t)dv.U * n), dest((size_t)dv.U * dv.SN, 0);
-    hipError_t e = hipMemcpy2DAsync(a.data(), (size_t)n * 4, dv.assign + f0, (size_t)dv.F * 4, (size_t)n * 4,
-                                    dv.U, hipMemcpyDeviceToHost, ctx->stream);
+    // both directions go through pinned memory of the host arena: an asynchronous copy to
+    // or from pageable memory is only complete (or its source only free) when the runtime
+    // says so, which a stream synchronisation does not promise
+    int *a = ctx->h_assign, *dest = ctx->h_dest;
+    hipError_t e = hipSuccess;
+    // the previous batch's slab table must have left `dest`, and its assignments are final
+    if ((e = hipStreamSynchronize(ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+    for (int u = 0; u < dv.U && e == hipSuccess; ++u)
+        e = hipMemcpyAsync(a + (size_t)u * n, dv.assign + (size_t)u * dv.F + f0, (size_t)n * 4,
+                           hipMemcpyDeviceToHost, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "assignment read-back");
     if ((e = hipStreamSynchronize(ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
     for (int fl = 0; fl < n; ++fl)
@@ -378,8 +389,7 @@ static int offload_range(mosaic_ctx *ctx, int f0, int f1) {
             if (hp < 0) return fail(ctx, MOSAIC_ECAPACITY, "host slab pool exhausted");
             dest[(size_t)u * dv.SN + fl] = hp;
         }
-    // pageable source: the runtime stages it before returning, so `dest` may go out of scope
-    e = hipMemcpyAsync(dv.dest, dest.data(), dest.size() * 4, hipMemcpyHostToDevice, ctx->stream);
+    e = hipMemcpyAsync(dv.dest, dest, (size_t)dv.U * dv.SN * 4, hipMemcpyHostToDevice, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "slab table upload");
     if ((e = launch_offload(dv, f0, n, ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "offload launch");
     return MOSAIC_OK;

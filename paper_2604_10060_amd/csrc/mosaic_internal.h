@@ -91,6 +91,7 @@ struct Ctx {
     int *h_sel, *h_nsel; // page lists / counts staged for upload, [U][F] / [U]
     int *h_moves, *h_nmoves; // fetch work lists, [U][F][2] / [U]
     int *h_ids, *h_nids; // selections read back, [U][k] / [U]
+    int *h_assign, *h_dest; // staged batch: assignments read back / slab positions, [U][SN]
     // profiling
     bool profile;
     std::vector<hipEvent_t> ev;      // pairs

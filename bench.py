@@ -39,9 +39,9 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 # (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter read on
 # k_calibration_copy, a 256 MiB copy): see profiles/.  Keyed by (workload, calls).
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg1_single_layer_hbm", "per_layer"): 27_330_000,     # 26.40 MB read + 0.93 MB written
-    ("cfg2_full_stack_hbm", "per_layer"): 118_050_000,      # 117.12 MB + 0.93 MB
-    ("cfg2_full_stack_hbm", "all_layers"): 3_281_480_000,   # 3273.71 MB + 7.77 MB
+    ("cfg1_single_layer_hbm", "per_layer"): 27_150_000,     # 26.41 MB read + 0.74 MB written
+    ("cfg2_full_stack_hbm", "per_layer"): 117_650_000,      # 116.94 MB + 0.71 MB
+    ("cfg2_full_stack_hbm", "all_layers"): 3_279_920_000,   # 3272.38 MB + 7.54 MB
 }
 
 
@@ -227,6 +227,31 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
     torch.cuda.synchronize()
     us_per_step = (time.perf_counter() - t) / steps * 1e6
 
+    # per-step latencies of the same steps: one event between consecutive steps on the
+    # library's stream (the binding runs on torch's current stream), read after the pass
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    for j, i in enumerate(range(warmup, n_q)):
+        evs[j].record()
+        step(i)
+    evs[steps].record()
+    torch.cuda.synchronize()
+    per_step = np.array([evs[j].elapsed_time(evs[j + 1]) * 1e3 for j in range(steps)])
+
+    # a plain streaming kernel on the same box (256 MiB read + 256 MiB written) as the
+    # achievable-bandwidth reference next to the published peak
+    ca = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    cb = torch.empty_like(ca)
+    cs = torch.cuda.current_stream().cuda_stream
+    lib.mosaic_calibration_copy(cb.data_ptr(), ca.data_ptr(), ca.numel(), cs)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(4):
+        lib.mosaic_calibration_copy(cb.data_ptr(), ca.data_ptr(), ca.numel(), cs)
+    c1.record()
+    torch.cuda.synchronize()
+    stream_gbps = 4 * 2 * ca.numel() / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del ca, cb
+
     # kernel-only time of the attention kernel: HIP start/stop events attached to each launch
     m.profile_enable(True)
     for i in range(warmup, n_q):
@@ -264,8 +289,12 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
                      "kernel": kernel, "kernel_us": round(kern_us, 3),
                      "launches": int(launches), "bytes_per_launch": round(bytes_per_launch)},
         "cpu_baseline": cpu,
+        "step_us_median": round(float(np.median(per_step)), 3),
+        "step_us_p95": round(float(np.percentile(per_step, 95)), 3),
         "step_hbm_gbps": round(step_gbps, 1),
         "step_hbm_frac": round(step_gbps / HBM_PEAK_GBPS, 4),
+        "stream_kernel_gbps": round(stream_gbps, 1),
+        "frac_of_stream_kernel": round(achieved / stream_gbps, 4),
         "ingest_frames_per_s": round(fps_b1, 1),
         "ingest_frames_per_s_batch16": round(fps_b16, 1),
         "question_tokens": wl.question_tokens,
@@ -556,8 +585,10 @@ def main():
                 continue
             extra["cfg2_" + leg["config"]["calls"]] = {
                 "decode_step_us": round(leg["us_per_step"], 2), "config": leg["config"],
+                "step_us_median": leg["step_us_median"], "step_us_p95": leg["step_us_p95"],
                 "roofline": leg["roofline"], "step_hbm_gbps": leg["step_hbm_gbps"],
-                "step_hbm_frac": leg["step_hbm_frac"],
+                "step_hbm_frac": leg["step_hbm_frac"], "stream_kernel_gbps": leg["stream_kernel_gbps"],
+                "frac_of_stream_kernel": leg["frac_of_stream_kernel"],
                 "ingest_frames_per_s": leg["ingest_frames_per_s"],
                 "ingest_frames_per_s_batch16": leg["ingest_frames_per_s_batch16"],
                 "question_ms": leg["question_ms"], "parity_spot_check": leg["parity_spot_check"]}

@@ -13,6 +13,11 @@
  * vs the batch mean of Eq. 1; assignment and Lloyd steps vs exhaustive search;
  * selection vs a full lexicographic sort; gather invariants (whole clusters,
  * partition); attention vs dense softmax attention when k covers all clusters.
+ * The self-adaptive maintainer (Sec. VI) is pinned by a hand-worked Eq. 3/4
+ * fixture, closed forms of Eq. 5, Eq. 2 against numpy, Split against a numpy
+ * two-means, equality with the plain online rule when the threshold is out of
+ * reach, and the state transitions of Alg. 1 (buffered singletons, their
+ * visibility to retrieval, materialization on retrieval, conservation).
  * End-to-end retrieval *quality* has no value in the paper to pin it to:
  * parity unpinned for that quantity only (it is reported, never gated).
  */
@@ -32,7 +37,27 @@ typedef struct {
     double lloyd_min_gap;  /* smallest winner/runner-up relative gap seen in
                               the latest Lloyd run (diagnostic only) */
     int n_lloyd_runs;
+    /* self-adaptive maintenance (Sec. VI); maint_mode 0 = off */
+    int warmup_arg;        /* warm-up length as passed (0 = default) */
+    int n_slots;           /* cluster ids in use: [0, n_slots); C when off */
+    int c_init;            /* clusters the initial K-means builds (maintenance on) */
+    int maint_mode;        /* 1 = split at once, 2 = deferred split (Alg. 1) */
+    double tau_min, tau_max, n0;   /* Eq. 5 */
+    int split_iters, buf_max;
+    double *var;           /* [C] running intra-cluster variance (Eq. 2 / Eq. 4) */
+    int *lazy;             /* [C] lazy-split flag */
+    int *resident;         /* [C] 1 = the cluster's contents are on the GPU */
+    int *buf_frame, *buf_owner;    /* GPU-side buffer of singletons: frame, owning cluster */
+    int n_buf;
+    long n_split_now, n_split_deferred, n_deferred, n_forced_absorb;
+    int last_action;       /* what the latest online insertion did (ORC_ACT_*) */
+    double last_var, last_tau;     /* the two sides of its threshold test */
+    double split_min_gap;  /* smallest relative gap of any comparison inside the
+                              latest Split (diagnostic only) */
 } orc_unit;
+
+enum { ORC_ACT_NONE = 0, ORC_ACT_ABSORB = 1, ORC_ACT_SPLIT = 2, ORC_ACT_DEFER = 3,
+       ORC_ACT_FORCED_ABSORB = 4 };
 
 typedef struct {
     int winner;     /* chosen cluster */
@@ -40,6 +65,9 @@ typedef struct {
     double gap;     /* |a-b| / max(|a|,|b|,1e-30) of their similarities */
     double sim;     /* similarity of the winner */
 } orc_decision;
+
+void orc_unit_score(const orc_unit *u, const double *qbar, double *score);
+int orc_select(const double *score, const int *n, int C, int k, int *ids, double *gap_k);
 
 static double rel_gap(double a, double b)
 {
@@ -69,6 +97,7 @@ orc_unit *orc_unit_new(int C, int D, int T, int max_frames, int warmup,
     orc_unit *u = (orc_unit *)calloc(1, sizeof(orc_unit));
     u->C = C; u->D = D; u->T = T; u->max_frames = max_frames;
     u->warmup = warmup > 0 ? warmup : 2 * C;
+    u->warmup_arg = warmup; u->n_slots = C; u->split_min_gap = INFINITY;
     u->lloyd_iters = lloyd_iters; u->recluster_every = recluster_every;
     u->score_mode = score_mode;
     u->summ = (double *)calloc((size_t)max_frames * D, sizeof(double));
@@ -83,7 +112,9 @@ orc_unit *orc_unit_new(int C, int D, int T, int max_frames, int warmup,
 void orc_unit_free(orc_unit *u)
 {
     if (!u) return;
-    free(u->summ); free(u->r); free(u->n); free(u->assign); free(u);
+    free(u->summ); free(u->r); free(u->n); free(u->assign);
+    free(u->var); free(u->lazy); free(u->resident); free(u->buf_frame); free(u->buf_owner);
+    free(u);
 }
 
 void orc_unit_reset(orc_unit *u)
@@ -93,6 +124,14 @@ void orc_unit_reset(orc_unit *u)
     memset(u->r, 0, (size_t)u->C * u->D * sizeof(double));
     memset(u->n, 0, (size_t)u->C * sizeof(int));
     for (int f = 0; f < u->max_frames; ++f) u->assign[f] = -1;
+    if (u->maint_mode) {
+        memset(u->var, 0, (size_t)u->C * sizeof(double));
+        memset(u->lazy, 0, (size_t)u->C * sizeof(int));
+        memset(u->resident, 0, (size_t)u->C * sizeof(int));
+        u->n_buf = 0; u->n_slots = u->c_init;
+        u->n_split_now = u->n_split_deferred = u->n_deferred = u->n_forced_absorb = 0;
+        u->last_action = ORC_ACT_NONE; u->split_min_gap = INFINITY;
+    }
 }
 
 /* The unit that is clustered is the frame: its "KV state" (Sec. VI-A) is the
@@ -115,7 +154,7 @@ static void nearest(const orc_unit *u, const double *s, int all_live,
 {
     int best = -1, second = -1;
     double bs = -INFINITY, ss = -INFINITY;
-    for (int j = 0; j < u->C; ++j) {
+    for (int j = 0; j < u->n_slots; ++j) {
         if (!all_live && u->n[j] == 0) continue;
         double c = cosine(s, u->r + (size_t)j * u->D, u->D);
         if (best < 0 || c > bs) { second = best; ss = bs; best = j; bs = c; }
@@ -133,7 +172,7 @@ static void nearest(const orc_unit *u, const double *s, int all_live,
  * ascending frame order. */
 static void lloyd(orc_unit *u, int first_all_live)
 {
-    const int F = u->n_frames, C = u->C, D = u->D;
+    const int F = u->n_frames, C = u->n_slots, D = u->D;
     u->lloyd_min_gap = INFINITY;
     for (int it = 0; it < u->lloyd_iters; ++it) {
         int all_live = first_all_live && it == 0;
@@ -158,6 +197,247 @@ static void lloyd(orc_unit *u, int first_all_live)
         }
     }
     u->n_lloyd_runs += 1;
+}
+
+/* ------------------------------------------------------------------------
+ * Self-Adaptive Maintainer (Sec. VI).
+ * ------------------------------------------------------------------------ */
+
+/* Switch the maintainer on; call before the first frame.  c_init clusters are
+ * built by the initial K-means (default warm-up 2*c_init frames) and splits
+ * add clusters up to the table size C.  mode 1 treats every cluster as GPU
+ * resident (every invalid cluster is split at once); mode 2 follows Alg. 1
+ * with "resident" = selected by the unit's latest retrieval.  The paper gives
+ * no values for tau_min, tau_max, N0: they are parameters.  Periodic full
+ * re-clustering and the maintainer exclude each other.  Returns 0 or -1. */
+int orc_unit_set_maintainer(orc_unit *u, int mode, int c_init, double tau_min,
+                            double tau_max, double n0, int split_iters,
+                            int buf_max)
+{
+    if (u->n_frames != 0 || u->recluster_every != 0) return -1;
+    if (mode < 1 || mode > 2 || c_init < 1 || c_init > u->C || !(n0 > 0.0) ||
+        split_iters < 1 || buf_max < 0) return -1;
+    u->maint_mode = mode; u->c_init = c_init; u->n_slots = c_init;
+    u->tau_min = tau_min; u->tau_max = tau_max; u->n0 = n0;
+    u->split_iters = split_iters; u->buf_max = buf_max;
+    u->warmup = u->warmup_arg > 0 ? u->warmup_arg : 2 * c_init;
+    u->var = (double *)calloc((size_t)u->C, sizeof(double));
+    u->lazy = (int *)calloc((size_t)u->C, sizeof(int));
+    u->resident = (int *)calloc((size_t)u->C, sizeof(int));
+    u->buf_frame = (int *)calloc((size_t)(buf_max > 0 ? buf_max : 1), sizeof(int));
+    u->buf_owner = (int *)calloc((size_t)(buf_max > 0 ? buf_max : 1), sizeof(int));
+    u->n_buf = 0;
+    return 0;
+}
+
+/* Size-adaptive threshold, Eq. 5. */
+double orc_tau(double tau_min, double tau_max, double n0, double N)
+{
+    return tau_min + (tau_max - tau_min) * exp(-N / n0);
+}
+
+static double sqdist(const double *a, const double *b, int D)
+{
+    double s = 0.0;
+    for (int d = 0; d < D; ++d) { double t = a[d] - b[d]; s += t * t; }
+    return s;
+}
+
+/* Size, representative (Eq. 1) and variance (Eq. 2) of cluster j from its
+ * member list, members in ascending frame order. */
+static void exact_stats(orc_unit *u, int j)
+{
+    const int D = u->D, F = u->n_frames;
+    double *rj = u->r + (size_t)j * D;
+    int cnt = 0;
+    for (int f = 0; f < F; ++f) cnt += (u->assign[f] == j);
+    u->n[j] = cnt;
+    if (cnt == 0) { u->var[j] = 0.0; return; }
+    for (int d = 0; d < D; ++d) {
+        double acc = 0.0;
+        for (int f = 0; f < F; ++f)
+            if (u->assign[f] == j) acc += u->summ[(size_t)f * D + d];
+        rj[d] = acc / (double)cnt;
+    }
+    double acc = 0.0;
+    for (int f = 0; f < F; ++f)
+        if (u->assign[f] == j) acc += sqdist(u->summ + (size_t)f * D, rj, D);
+    u->var[j] = acc / (double)cnt;
+}
+
+/* Split (Alg. 1, lines 5 and 14) -- the paper does not define it.  Reading:
+ * two-means under the clustering criterion of Sec. V-B.  Seeds are the two
+ * members with the lowest mutual cosine (first such pair in (i, i') order);
+ * then split_iters rounds of (each member to the seed representative it is
+ * more similar to, equal goes to the first; representatives = means of their
+ * sides, a side left empty keeps its representative).  mem[0..m) ascending
+ * frames; side[i] = 0 stays, 1 leaves.  Returns the size of side 1 (0 or m
+ * means the split is degenerate). */
+static int split_members(orc_unit *u, const int *mem, int m, int *side)
+{
+    const int D = u->D;
+    u->split_min_gap = INFINITY;
+    if (m < 2) { for (int i = 0; i < m; ++i) side[i] = 0; return 0; }
+    int si = 0, sj = 1;
+    double best = INFINITY, second = INFINITY;
+    for (int i = 0; i < m; ++i)
+        for (int k = i + 1; k < m; ++k) {
+            double c = cosine(u->summ + (size_t)mem[i] * D, u->summ + (size_t)mem[k] * D, D);
+            if (c < best) { second = best; best = c; si = i; sj = k; }
+            else if (c < second) second = c;
+        }
+    if (second < INFINITY) u->split_min_gap = rel_gap(best, second);
+    double *ca = (double *)malloc((size_t)D * sizeof(double));
+    double *cb = (double *)malloc((size_t)D * sizeof(double));
+    memcpy(ca, u->summ + (size_t)mem[si] * D, (size_t)D * sizeof(double));
+    memcpy(cb, u->summ + (size_t)mem[sj] * D, (size_t)D * sizeof(double));
+    int nb = 0;
+    for (int it = 0; it < u->split_iters; ++it) {
+        nb = 0;
+        for (int i = 0; i < m; ++i) {
+            const double *s = u->summ + (size_t)mem[i] * D;
+            double a = cosine(s, ca, D), b = cosine(s, cb, D);
+            side[i] = b > a;
+            nb += side[i];
+            double g = rel_gap(a, b);
+            if (g < u->split_min_gap) u->split_min_gap = g;
+        }
+        for (int which = 0; which < 2; ++which) {
+            int cnt = which ? nb : m - nb;
+            if (cnt == 0) continue;
+            double *c = which ? cb : ca;
+            for (int d = 0; d < D; ++d) {
+                double acc = 0.0;
+                for (int i = 0; i < m; ++i)
+                    if (side[i] == which) acc += u->summ[(size_t)mem[i] * D + d];
+                c[d] = acc / (double)cnt;
+            }
+        }
+    }
+    free(ca); free(cb);
+    return nb;
+}
+
+/* Split cluster a into a (the side of the first seed) and a new cluster id.
+ * Returns the new id, or -1 if nothing was split (no free id, fewer than two
+ * members, or one side empty); statistics of the touched clusters are then
+ * exact (Eq. 1, Eq. 2) when `refresh` is set. */
+static int split_cluster(orc_unit *u, int a, int refresh)
+{
+    const int F = u->n_frames;
+    int m = 0, fresh = -1;
+    for (int f = 0; f < F; ++f) m += (u->assign[f] == a);
+    if (u->n_slots < u->C && m >= 2) {
+        int *mem = (int *)malloc((size_t)m * sizeof(int));
+        int *side = (int *)malloc((size_t)m * sizeof(int));
+        int k = 0;
+        for (int f = 0; f < F; ++f) if (u->assign[f] == a) mem[k++] = f;
+        int nb = split_members(u, mem, m, side);
+        if (nb > 0 && nb < m) {
+            fresh = u->n_slots++;
+            for (int i = 0; i < m; ++i) if (side[i]) u->assign[mem[i]] = fresh;
+            exact_stats(u, a);
+            exact_stats(u, fresh);
+            u->lazy[a] = u->lazy[fresh] = 0;
+            u->resident[fresh] = u->resident[a];
+        }
+        free(mem); free(side);
+    }
+    if (fresh < 0 && refresh) exact_stats(u, a);
+    return fresh;
+}
+
+/* Insertion procedure of Alg. 1 for frame f (summary s) given its cluster a. */
+static void maintain_insert(orc_unit *u, int f, const double *s, int a)
+{
+    const int D = u->D;
+    double *ra = u->r + (size_t)a * D;
+    const double na = (double)u->n[a];
+    for (int d = 0; d < D; ++d)                        /* Eq. 3 */
+        ra[d] = (na * ra[d] + s[d]) / (na + 1.0);
+    const double var_new = (na * u->var[a] + sqdist(s, ra, D)) / (na + 1.0);   /* Eq. 4 */
+    const double tau = orc_tau(u->tau_min, u->tau_max, u->n0, na);  /* size before the insertion (line 2) */
+    u->var[a] = var_new;                               /* line 1: statistics always move */
+    u->last_var = var_new; u->last_tau = tau;
+    const int on_gpu = u->maint_mode == 1 || u->resident[a];
+    if (var_new <= tau) {                              /* lines 2-3 */
+        u->assign[f] = a; u->n[a] += 1;
+        u->last_action = ORC_ACT_ABSORB;
+    } else if (on_gpu) {                               /* lines 4-6 */
+        u->assign[f] = a; u->n[a] += 1;
+        if (split_cluster(u, a, 0) >= 0) { u->n_split_now += 1; u->last_action = ORC_ACT_SPLIT; }
+        else { u->n_forced_absorb += 1; u->last_action = ORC_ACT_FORCED_ABSORB; }
+    } else if (u->n_buf < u->buf_max) {                /* lines 7-10 */
+        u->lazy[a] = 1;
+        u->buf_frame[u->n_buf] = f; u->buf_owner[u->n_buf] = a; u->n_buf += 1;
+        u->assign[f] = -2 - a;                         /* held in the buffer on behalf of a */
+        u->n_deferred += 1; u->last_action = ORC_ACT_DEFER;
+    } else {                                           /* buffer full: the paper is silent; absorb */
+        u->lazy[a] = 1;
+        u->assign[f] = a; u->n[a] += 1;
+        u->n_forced_absorb += 1; u->last_action = ORC_ACT_FORCED_ABSORB;
+    }
+}
+
+/* Retrieval procedure of Alg. 1 (lines 12-17) for one selected cluster: merge
+ * its buffered entries, split, refresh the representatives, clear the flag. */
+static void materialize(orc_unit *u, int j)
+{
+    if (!u->lazy[j]) return;
+    int w = 0;
+    for (int b = 0; b < u->n_buf; ++b) {
+        if (u->buf_owner[b] == j) { u->assign[u->buf_frame[b]] = j; continue; }
+        u->buf_frame[w] = u->buf_frame[b]; u->buf_owner[w] = u->buf_owner[b]; ++w;
+    }
+    u->n_buf = w;
+    u->lazy[j] = 0;
+    if (split_cluster(u, j, 1) >= 0) u->n_split_deferred += 1;
+}
+
+/* Query Retrieval with the maintainer on (mode 2): the representative set is
+ * the non-empty clusters plus the buffered singletons (a singleton's
+ * representative is its own summary, Alg. 1 line 10).  score [C + buf_max];
+ * selected ids: cluster j -> j, buffer entry b -> C + b; sorted by (score
+ * descending, id ascending); tokens as in the plain gather, a singleton
+ * contributing its one frame.  Afterwards the selected clusters count as GPU
+ * resident, all others as not, and every selected cluster with a lazy flag
+ * has its deferred split materialized (in selection order).  Returns the
+ * number of ids; *n_tok tokens are written to tok_idx. */
+int orc_unit_retrieve_maintained(orc_unit *u, const double *qbar, int k, int *ids,
+                                 double *score, int *tok_idx, int *n_tok,
+                                 double *gap_k)
+{
+    const int C = u->C, D = u->D, R = C + u->n_buf;
+    orc_unit_score(u, qbar, score);
+    int *live = (int *)calloc((size_t)R, sizeof(int));
+    for (int j = 0; j < C; ++j) live[j] = u->n[j];
+    for (int b = 0; b < u->n_buf; ++b) {
+        const double *sb = u->summ + (size_t)u->buf_frame[b] * D;
+        double dp = dot(qbar, sb, D);
+        if (u->score_mode == 1) score[C + b] = dp;
+        else { double nr = sqrt(dot(sb, sb, D)); score[C + b] = nr == 0.0 ? 0.0 : dp / nr; }
+        live[C + b] = 1;
+    }
+    int kept = orc_select(score, live, R, k, ids, gap_k);
+    free(live);
+    int m = 0;
+    for (int i = 0; i < kept; ++i) {
+        if (ids[i] >= C) {
+            int f = u->buf_frame[ids[i] - C];
+            for (int t = 0; t < u->T; ++t) tok_idx[m++] = f * u->T + t;
+        } else {
+            for (int f = 0; f < u->n_frames; ++f)
+                if (u->assign[f] == ids[i])
+                    for (int t = 0; t < u->T; ++t) tok_idx[m++] = f * u->T + t;
+        }
+    }
+    *n_tok = m;
+    if (u->maint_mode == 2) {
+        memset(u->resident, 0, (size_t)C * sizeof(int));
+        for (int i = 0; i < kept; ++i) if (ids[i] < C) u->resident[ids[i]] = 1;
+        for (int i = 0; i < kept; ++i) if (ids[i] < C) materialize(u, ids[i]);
+    }
+    return kept;
 }
 
 /* What the greedy rule would decide for a frame, without changing state.
@@ -195,15 +475,21 @@ int orc_unit_ingest(orc_unit *u, const double *k_frame, int force,
         u->n_frames = f + 1;
         if (u->n_frames == u->warmup) {
             const int W = u->warmup;
-            for (int j = 0; j < u->C; ++j) {
-                int src = (int)(((long long)j * W) / u->C);
+            for (int j = 0; j < u->n_slots; ++j) {
+                int src = (int)(((long long)j * W) / u->n_slots);
                 memcpy(u->r + (size_t)j * D, u->summ + (size_t)src * D,
                        (size_t)D * sizeof(double));
                 u->n[j] = 0;
             }
             lloyd(u, 1);
+            if (u->maint_mode)                          /* Eq. 2 from the members */
+                for (int j = 0; j < u->n_slots; ++j) exact_stats(u, j);
             u->ready = 1;
         }
+    } else if (u->maint_mode) {
+        nearest(u, s, 0, &local);
+        u->n_frames = f + 1;                            /* the new state is part of what a split sees */
+        maintain_insert(u, f, s, force >= 0 ? force : local.winner);
     } else {
         nearest(u, s, 0, &local);
         int a = force >= 0 ? force : local.winner;
@@ -344,3 +630,18 @@ const double *orc_unit_centroids(const orc_unit *u) { return u->r; }
 const int *orc_unit_sizes(const orc_unit *u) { return u->n; }
 const int *orc_unit_assign(const orc_unit *u) { return u->assign; }
 const double *orc_unit_summaries(const orc_unit *u) { return u->summ; }
+int orc_unit_n_slots(const orc_unit *u) { return u->n_slots; }
+int orc_unit_n_buf(const orc_unit *u) { return u->n_buf; }
+int orc_unit_last_action(const orc_unit *u) { return u->last_action; }
+double orc_unit_last_var(const orc_unit *u) { return u->last_var; }
+double orc_unit_last_tau(const orc_unit *u) { return u->last_tau; }
+double orc_unit_split_min_gap(const orc_unit *u) { return u->split_min_gap; }
+long orc_unit_n_split_now(const orc_unit *u) { return u->n_split_now; }
+long orc_unit_n_split_deferred(const orc_unit *u) { return u->n_split_deferred; }
+long orc_unit_n_deferred(const orc_unit *u) { return u->n_deferred; }
+long orc_unit_n_forced_absorb(const orc_unit *u) { return u->n_forced_absorb; }
+const double *orc_unit_var(const orc_unit *u) { return u->var; }
+const int *orc_unit_lazy(const orc_unit *u) { return u->lazy; }
+const int *orc_unit_resident(const orc_unit *u) { return u->resident; }
+const int *orc_unit_buf_frame(const orc_unit *u) { return u->buf_frame; }
+const int *orc_unit_buf_owner(const orc_unit *u) { return u->buf_owner; }

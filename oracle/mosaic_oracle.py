@@ -67,6 +67,23 @@ def lib():
         L.orc_unit_gather.argtypes = [C.c_void_p, _ip, C.c_int, _ip]
         L.orc_attend.argtypes = [_dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                  _dp, _dp, _ip, C.c_int, _dp, _dp]
+        L.orc_unit_set_maintainer.restype = C.c_int
+        L.orc_unit_set_maintainer.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_double,
+                                              C.c_double, C.c_int, C.c_int]
+        L.orc_tau.restype = C.c_double
+        L.orc_tau.argtypes = [C.c_double] * 4
+        L.orc_unit_retrieve_maintained.restype = C.c_int
+        L.orc_unit_retrieve_maintained.argtypes = [C.c_void_p, _dp, C.c_int, _ip, _dp, _ip, _ip, _dp]
+        for name, rt in (("orc_unit_n_slots", C.c_int), ("orc_unit_n_buf", C.c_int),
+                         ("orc_unit_last_action", C.c_int), ("orc_unit_last_var", C.c_double),
+                         ("orc_unit_last_tau", C.c_double), ("orc_unit_split_min_gap", C.c_double),
+                         ("orc_unit_n_split_now", C.c_long), ("orc_unit_n_split_deferred", C.c_long),
+                         ("orc_unit_n_deferred", C.c_long), ("orc_unit_n_forced_absorb", C.c_long),
+                         ("orc_unit_var", _dp), ("orc_unit_lazy", _ip), ("orc_unit_resident", _ip),
+                         ("orc_unit_buf_frame", _ip), ("orc_unit_buf_owner", _ip)):
+            fn = getattr(L, name)
+            fn.restype = rt
+            fn.argtypes = [C.c_void_p]
         for name, rt in (("orc_unit_n_frames", C.c_int), ("orc_unit_ready", C.c_int),
                          ("orc_unit_n_lloyd_runs", C.c_int),
                          ("orc_unit_lloyd_min_gap", C.c_double),
@@ -133,18 +150,41 @@ def attend(q: np.ndarray, K: np.ndarray, V: np.ndarray, tok_idx: np.ndarray,
     return out, lse
 
 
+ACT_NONE, ACT_ABSORB, ACT_SPLIT, ACT_DEFER, ACT_FORCED_ABSORB = range(5)
+
+
+def tau(tau_min: float, tau_max: float, n0: float, size: float) -> float:
+    """Size-adaptive threshold (Eq. 5)."""
+    return lib().orc_tau(tau_min, tau_max, n0, size)
+
+
 class OracleUnit:
-    """Clustering state of one (layer, KV head)."""
+    """Clustering state of one (layer, KV head).
+
+    maintainer = dict(mode=1|2, c_init=.., tau_min=.., tau_max=.., n0=..,
+    split_iters=.., buf_max=..) switches the self-adaptive maintainer on
+    (Sec. VI): n_clusters is then the size of the cluster table, c_init the
+    number of clusters the initial K-means builds."""
 
     def __init__(self, n_clusters: int, head_dim: int, tokens_per_frame: int,
                  max_frames: int, warmup_frames: int = 0, lloyd_iters: int = 8,
-                 recluster_every: int = 0, score_mode: int = 0):
+                 recluster_every: int = 0, score_mode: int = 0, maintainer: dict | None = None):
         self.C, self.D, self.T = n_clusters, head_dim, tokens_per_frame
         self.max_frames = max_frames
         self._L = lib()
         self._u = self._L.orc_unit_new(n_clusters, head_dim, tokens_per_frame,
                                        max_frames, warmup_frames, lloyd_iters,
                                        recluster_every, score_mode)
+        self.maintainer = maintainer
+        self.buf_max = 0
+        if maintainer:
+            m = maintainer
+            self.buf_max = int(m.get("buf_max", 0))
+            rc = self._L.orc_unit_set_maintainer(self._u, int(m["mode"]), int(m["c_init"]),
+                                                 float(m["tau_min"]), float(m["tau_max"]), float(m["n0"]),
+                                                 int(m.get("split_iters", 4)), self.buf_max)
+            if rc != 0:
+                raise ValueError("bad maintainer parameters")
 
     def __del__(self):
         if getattr(self, "_u", None):
@@ -212,6 +252,66 @@ class OracleUnit:
         out = np.empty(max(self.n_frames * self.T, 1), dtype=np.int32)
         m = self._L.orc_unit_gather(self._u, _i(ids), int(ids.shape[0]), _i(out))
         return out[:m].copy()
+
+    # -- self-adaptive maintainer ------------------------------------------
+    @property
+    def n_slots(self) -> int:
+        return self._L.orc_unit_n_slots(self._u)
+
+    @property
+    def n_buf(self) -> int:
+        return self._L.orc_unit_n_buf(self._u)
+
+    @property
+    def last_action(self) -> int:
+        return self._L.orc_unit_last_action(self._u)
+
+    @property
+    def last_threshold_test(self):
+        """(variance after the update, threshold it was compared with)"""
+        return self._L.orc_unit_last_var(self._u), self._L.orc_unit_last_tau(self._u)
+
+    @property
+    def split_min_gap(self) -> float:
+        return self._L.orc_unit_split_min_gap(self._u)
+
+    def counters(self) -> dict:
+        L, u = self._L, self._u
+        return {"split_now": L.orc_unit_n_split_now(u), "split_deferred": L.orc_unit_n_split_deferred(u),
+                "deferred": L.orc_unit_n_deferred(u), "forced_absorb": L.orc_unit_n_forced_absorb(u)}
+
+    def variances(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._L.orc_unit_var(self._u), shape=(self.C,)).copy()
+
+    def lazy_flags(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._L.orc_unit_lazy(self._u), shape=(self.C,)).copy()
+
+    def resident_flags(self) -> np.ndarray:
+        return np.ctypeslib.as_array(self._L.orc_unit_resident(self._u), shape=(self.C,)).copy()
+
+    def buffer(self):
+        """-> (frames, owning clusters) of the buffered singletons"""
+        nb = self.n_buf
+        if nb == 0:
+            return np.empty(0, np.int32), np.empty(0, np.int32)
+        fr = np.ctypeslib.as_array(self._L.orc_unit_buf_frame(self._u), shape=(max(self.buf_max, 1),))
+        ow = np.ctypeslib.as_array(self._L.orc_unit_buf_owner(self._u), shape=(max(self.buf_max, 1),))
+        return fr[:nb].copy(), ow[:nb].copy()
+
+    def retrieve_maintained(self, q: np.ndarray, h: int, G: int, top_k: int):
+        """Retrieval with singletons visible and deferred splits materialized
+        (Alg. 1): q [Tq][Hq][D] -> (ids, scores [C + n_buf], tok_idx, gap_k).
+        Changes the unit's state in mode 2."""
+        qbar = mean_query(q, h, G)
+        nb = self.n_buf
+        sc = np.full(self.C + max(self.buf_max, 1), -np.inf, dtype=np.float64)
+        ids = np.empty(max(top_k, 1), dtype=np.int32)
+        tok = np.empty(max(self.n_frames * self.T, 1), dtype=np.int32)
+        n_tok = C.c_int()
+        gap = C.c_double()
+        m = self._L.orc_unit_retrieve_maintained(self._u, _d(qbar), top_k, _i(ids), _d(sc), _i(tok),
+                                                 C.byref(n_tok), C.byref(gap))
+        return ids[:m].copy(), sc[: self.C + nb].copy(), tok[: n_tok.value].copy(), gap.value
 
     # -- the whole query side for this unit --------------------------------
     def retrieve(self, q: np.ndarray, h: int, G: int, top_k: int):

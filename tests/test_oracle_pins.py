@@ -422,3 +422,212 @@ def test_cfg0_pipeline_invariants():
         # attention output is a convex combination of the retrieved values
         Vs = V.reshape(-1, wl.head_dim)[tok]
         assert (out <= Vs.max(axis=0) + 1e-12).all() and (out >= Vs.min(axis=0) - 1e-12).all()
+
+
+# --------------------------------------------------------------------------
+# Self-adaptive maintainer (Sec. VI): Eq. 2, Eq. 4, Eq. 5, Split, Alg. 1
+# --------------------------------------------------------------------------
+BIG = 1e300
+
+
+def _maint(mode=1, c_init=1, tau_min=BIG, tau_max=BIG, n0=8.0, split_iters=4, buf_max=8):
+    return dict(mode=mode, c_init=c_init, tau_min=tau_min, tau_max=tau_max, n0=n0,
+                split_iters=split_iters, buf_max=buf_max)
+
+
+def test_eq4_hand_worked_fixture():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "eq4_running_variance.txt"))
+            if l.strip() and not l.startswith("#")]
+    u = orc.OracleUnit(2, 1, 1, 16, warmup_frames=2, lloyd_iters=2, maintainer=_maint())
+    u.ingest(np.array([[1.0]]))
+    u.ingest(np.array([[3.0]]))
+    assert u.ready and u.sizes()[0] == 2
+    np.testing.assert_allclose(u.centroids()[0], [2.0], atol=1e-15)
+    np.testing.assert_allclose(u.variances()[0], 1.0, atol=1e-15)          # Eq. 2
+    for x, r, var, n in rows:
+        u.ingest(np.array([[float(x)]]))
+        np.testing.assert_allclose(u.centroids()[0], [float(r)], rtol=1e-15)
+        np.testing.assert_allclose(u.variances()[0], float(var), rtol=1e-14)
+        assert u.sizes()[0] == int(n) and u.last_action == orc.ACT_ABSORB
+
+
+def test_eq5_threshold_closed_forms():
+    lo, hi, n0 = 0.7, 5.2, 12.0
+    assert orc.tau(lo, hi, n0, 0.0) == hi                                   # empty cluster: tau_max
+    np.testing.assert_allclose(orc.tau(lo, hi, n0, n0), lo + (hi - lo) / np.e, rtol=1e-15)
+    np.testing.assert_allclose(orc.tau(lo, hi, n0, 2 * n0), lo + (hi - lo) / np.e ** 2, rtol=1e-15)
+    assert abs(orc.tau(lo, hi, n0, 1e6) - lo) < 1e-300 or orc.tau(lo, hi, n0, 1e6) == lo
+    vals = [orc.tau(lo, hi, n0, n) for n in range(0, 200)]
+    assert all(a > b for a, b in zip(vals, vals[1:]))                       # relaxes towards tau_min as N grows
+    # halving the distance to tau_min takes n0 * ln 2 members
+    np.testing.assert_allclose(orc.tau(lo, hi, n0, n0 * np.log(2.0)) - lo, (hi - lo) / 2, rtol=1e-14)
+
+
+def test_maintainer_with_unreachable_threshold_is_the_plain_online_rule():
+    """With tau = 1e300 nothing is ever invalid: assignments, sizes and representatives must be
+    those of the plain greedy rule with C = c_init (Sec. VI-A without refinement)."""
+    K, _ = _stream(160, 3, 8, 5, seed=21)
+    a = orc.OracleUnit(12, 8, 3, 160, lloyd_iters=4, maintainer=_maint(c_init=5))
+    b = orc.OracleUnit(5, 8, 3, 160, lloyd_iters=4)
+    for f in range(160):
+        a.ingest(K[f]); b.ingest(K[f])
+    assert a.n_slots == 5 and a.counters() == {"split_now": 0, "split_deferred": 0, "deferred": 0, "forced_absorb": 0}
+    np.testing.assert_array_equal(a.assignments(), b.assignments())
+    np.testing.assert_array_equal(a.sizes()[:5], b.sizes())
+    np.testing.assert_array_equal(a.centroids()[:5], b.centroids())
+    assert np.all(a.sizes()[5:] == 0)
+
+
+def test_eq2_exact_variance_after_initial_clustering():
+    K, _ = _stream(24, 4, 6, 3, seed=22)
+    u = orc.OracleUnit(8, 6, 4, 24, warmup_frames=24, lloyd_iters=5, maintainer=_maint(c_init=3))
+    for f in range(24):
+        u.ingest(K[f])
+    S, A, R = u.summaries(), u.assignments(), u.centroids()
+    for j in range(3):
+        mem = S[A == j]
+        assert len(mem) == u.sizes()[j] > 0
+        np.testing.assert_allclose(u.variances()[j], ((mem - R[j]) ** 2).sum(axis=1).mean(), rtol=1e-13)
+
+
+def _split_brute_force(S, iters):
+    """Two-means with cosine, seeds = the pair with the lowest mutual cosine (numpy)."""
+    Cm = _cos_matrix(S, S)
+    iu = np.triu_indices(len(S), 1)
+    p = np.argmin(Cm[iu])                       # first minimum in (i, i') order
+    ca, cb = S[iu[0][p]].copy(), S[iu[1][p]].copy()
+    for _ in range(iters):
+        side = (_cos_matrix(S, cb[None])[:, 0] > _cos_matrix(S, ca[None])[:, 0]).astype(int)
+        if (side == 0).any():
+            ca = S[side == 0].mean(axis=0)
+        if (side == 1).any():
+            cb = S[side == 1].mean(axis=0)
+    return side
+
+
+def test_split_matches_brute_force_two_means():
+    """One cluster, the threshold trips on the first frame after warm-up: the members are then
+    split; compare sides, sizes, Eq. 1 and Eq. 2 of both halves with numpy."""
+    r = _rng(23)
+    D, T, W = 6, 2, 14
+    cent = r.normal(size=(2, D)) * 2.0
+    K = cent[r.integers(0, 2, size=W + 1)][:, None, :] + 0.4 * r.normal(size=(W + 1, T, D))
+    u = orc.OracleUnit(4, D, T, 32, warmup_frames=W, lloyd_iters=2,
+                       maintainer=_maint(c_init=1, tau_min=1e-9, tau_max=1e-9, split_iters=3))
+    for f in range(W + 1):
+        u.ingest(K[f])
+    assert u.last_action == orc.ACT_SPLIT and u.n_slots == 2 and u.counters()["split_now"] == 1
+    S = u.summaries()
+    side = _split_brute_force(S, 3)
+    assert 0 < side.sum() < len(S)
+    np.testing.assert_array_equal(u.assignments(), side)       # first seed's side keeps id 0
+    for j in (0, 1):
+        mem = S[side == j]
+        assert u.sizes()[j] == len(mem)
+        np.testing.assert_allclose(u.centroids()[j], mem.mean(axis=0), rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(u.variances()[j], ((mem - mem.mean(axis=0)) ** 2).sum(axis=1).mean(), rtol=1e-12)
+    assert u.split_min_gap > 1e-6
+
+
+def test_split_separates_two_scenes_and_followers_join_their_scene():
+    r = _rng(24)
+    D, T = 8, 3
+    ca, cb = r.normal(size=D) * 3, r.normal(size=D) * 3
+    frames = [ca] * 12 + [cb] * 10 + [ca] * 5
+    K = np.stack(frames)[:, None, :] + 0.2 * r.normal(size=(len(frames), T, D))
+    u = orc.OracleUnit(6, D, T, 64, warmup_frames=8, lloyd_iters=2,
+                       maintainer=_maint(c_init=1, tau_min=2.0, tau_max=2.0))
+    for f in range(len(frames)):
+        u.ingest(K[f])
+    A = u.assignments()
+    assert u.n_slots == 2 and u.counters()["split_now"] == 1
+    assert len(set(A[:12])) == 1 and len(set(A[12:22])) == 1 and A[0] != A[12]
+    np.testing.assert_array_equal(A[22:], A[0])                # scene A returns: old cluster
+    assert u.sizes()[A[0]] == 17 and u.sizes()[A[12]] == 10
+
+
+def test_full_cluster_table_forces_absorption():
+    K, _ = _stream(80, 2, 6, 8, seed=25, noise=0.5)
+    u = orc.OracleUnit(3, 6, 2, 80, warmup_frames=4, lloyd_iters=2,
+                       maintainer=_maint(c_init=2, tau_min=1e-9, tau_max=1e-9))
+    for f in range(80):
+        u.ingest(K[f])
+    c = u.counters()
+    assert u.n_slots == 3 and c["split_now"] == 1 and c["forced_absorb"] > 0
+    A = u.assignments()
+    assert A.min() >= 0 and A.max() <= 2 and u.sizes().sum() == 80
+
+
+def _deferred_unit(r, n_a=10, n_b=4, buf_max=8, k_table=6):
+    D, T = 8, 2
+    ca, cb = r.normal(size=D) * 3, r.normal(size=D) * 3
+    K = np.stack([ca] * n_a + [cb] * n_b)[:, None, :] + 0.2 * r.normal(size=(n_a + n_b, T, D))
+    u = orc.OracleUnit(k_table, D, T, 64, warmup_frames=6, lloyd_iters=2,
+                       maintainer=_maint(mode=2, c_init=1, tau_min=2.0, tau_max=2.0, buf_max=buf_max))
+    for f in range(n_a + n_b):
+        u.ingest(K[f])
+    return u, K, ca, cb
+
+
+def test_deferred_split_buffers_singletons_until_the_cluster_is_retrieved():
+    """Alg. 1: nothing is resident before the first retrieval, so invalid insertions are buffered
+    (lines 7-10), stay visible to retrieval as singletons, and the split happens when the flagged
+    cluster is retrieved (lines 12-17)."""
+    r = _rng(26)
+    u, K, ca, cb = _deferred_unit(r)
+    c = u.counters()
+    assert c["split_now"] == 0 and c["split_deferred"] == 0 and c["deferred"] == 4 and u.n_buf == 4
+    A = u.assignments()
+    np.testing.assert_array_equal(A[:10], 0)
+    np.testing.assert_array_equal(A[10:], -2)                  # -2 - owner: buffered on behalf of cluster 0
+    assert u.lazy_flags()[0] == 1 and u.sizes()[0] == 10 and u.sizes()[0] + u.n_buf == 14
+    fr, ow = u.buffer()
+    np.testing.assert_array_equal(fr, [10, 11, 12, 13]); np.testing.assert_array_equal(ow, 0)
+    # a query along a buffered state ranks that singleton first; k = 1 returns just its frame
+    T, D, C = 2, 8, 6
+    q = u.summaries()[11][None, None, :]
+    ids, sc, tok, _ = u.retrieve_maintained(q, 0, 1, 1)
+    np.testing.assert_array_equal(ids, [C + 1]); np.testing.assert_array_equal(tok, [11 * T, 11 * T + 1])
+    assert u.n_buf == 4 and u.lazy_flags()[0] == 1              # owner not retrieved: still deferred
+    # retrieving the flagged cluster materializes the split
+    q = ca[None, None, :]
+    ids, sc, tok, _ = u.retrieve_maintained(q, 0, 1, 1)
+    np.testing.assert_array_equal(ids, [0])
+    np.testing.assert_array_equal(tok, np.arange(10 * T))       # the query sees the cluster as it was
+    assert u.n_buf == 0 and u.lazy_flags()[0] == 0 and u.counters()["split_deferred"] == 1 and u.n_slots == 2
+    A = u.assignments()
+    np.testing.assert_array_equal(A[:10], 0); np.testing.assert_array_equal(A[10:], 1)
+    S = u.summaries()
+    np.testing.assert_allclose(u.centroids()[1], S[10:].mean(axis=0), rtol=1e-13)
+    np.testing.assert_allclose(u.variances()[1], ((S[10:] - S[10:].mean(axis=0)) ** 2).sum(axis=1).mean(), rtol=1e-12)
+    # both halves are now resident: the next invalid insertion splits at once
+    assert u.resident_flags()[0] == 1 and u.resident_flags()[1] == 1
+    cc = r.normal(size=8) * 3
+    for i in range(3):
+        u.ingest(cc[None, :] + 0.2 * r.normal(size=(2, 8)))
+    assert u.counters()["split_now"] == 1 and u.n_slots == 3
+
+
+def test_deferred_buffer_overflow_is_absorbed():
+    u, K, ca, cb = _deferred_unit(_rng(27), n_a=10, n_b=6, buf_max=2)
+    c = u.counters()
+    assert u.n_buf == 2 and c["deferred"] == 2 and c["forced_absorb"] == 4
+    assert u.sizes()[0] == 14 and u.sizes()[0] + u.n_buf == 16
+
+
+def test_maintainer_conserves_frames():
+    K, _ = _stream(300, 2, 8, 9, seed=28, noise=0.4)
+    for mode in (1, 2):
+        u = orc.OracleUnit(24, 8, 2, 300, lloyd_iters=3,
+                           maintainer=_maint(mode=mode, c_init=3, tau_min=1.5, tau_max=4.0, n0=10.0, buf_max=16))
+        r = _rng(29)
+        for f in range(300):
+            u.ingest(K[f])
+            if mode == 2 and f >= 6 and f % 37 == 0:
+                u.retrieve_maintained(r.normal(size=(1, 1, 8)), 0, 1, 4)
+            if u.ready:
+                A = u.assignments()
+                assert np.array_equal(np.bincount(A[A >= 0], minlength=24), u.sizes())
+                assert (A < 0).sum() == u.n_buf and u.sizes().sum() + u.n_buf == f + 1
+                assert np.all(u.sizes()[u.n_slots:] == 0)
+        assert u.n_slots > 3

@@ -93,7 +93,30 @@ typedef struct {
     void *host_arena;             /* HOST pointer to pinned (hipHostMalloc) memory, 256-byte aligned,
                                      borrowed; size from mosaic_workspace_size */
     size_t host_arena_bytes;
+    /* Self-adaptive maintainer (paper Sec. VI); MOSAIC_TIER_HBM only, excludes recluster_every.
+     * Every insertion updates the cluster's running variance (Eq. 4) next to its representative
+     * (Eq. 3); a cluster whose variance exceeds the size-adaptive threshold (Eq. 5, evaluated at
+     * its size before the insertion) is refined by a two-way Split (two-means under the cosine
+     * criterion, seeds = the two members with the lowest mutual cosine).  n_clusters is then the
+     * capacity of the cluster table: the initial K-means builds init_clusters clusters and every
+     * split adds one (no free id left: the state is absorbed without refinement). */
+    int32_t maint_mode;           /* MOSAIC_MAINT_OFF | _EAGER | _DEFERRED */
+    int32_t init_clusters;        /* 1..n_clusters; 0 -> max(1, n_clusters / 2); warmup_frames 0 -> 2 * init_clusters */
+    int32_t split_iters;          /* two-means rounds of Split; 0 -> 4 */
+    int32_t buffer_max;           /* _DEFERRED: capacity of the per-unit buffer of singletons (Alg. 1, B);
+                                     0 -> 32; n_clusters + buffer_max <= 1024.  A full buffer: absorbed */
+    double tau_min, tau_max;      /* Eq. 5: threshold for large / for small clusters (squared distance) */
+    double tau_n0;                /* Eq. 5: transition rate N0 > 0 */
 } mosaic_config;
+
+/* maint_mode.  _EAGER: every cluster counts as GPU resident, an invalid cluster is split at once
+ * (Alg. 1 lines 4-6).  _DEFERRED: Alg. 1 in full with "GPU resident" = selected by the unit's
+ * latest mosaic_retrieve (the working set a GPU cluster cache would hold): an invalid cluster that
+ * is not resident gets a lazy-split flag and the new state is kept in the buffer as a singleton
+ * cluster that retrieval can select (id n_clusters + buffer slot); the split is carried out when
+ * mosaic_retrieve next selects the flagged cluster (lines 12-17), after that query's page list
+ * has been built. */
+enum { MOSAIC_MAINT_OFF = 0, MOSAIC_MAINT_EAGER = 1, MOSAIC_MAINT_DEFERRED = 2 };
 
 typedef struct {
     int64_t frames_ingested;
@@ -110,6 +133,11 @@ typedef struct {
     double h2d_busy_ms;                 /* time of those fetch kernels (event pairs around each launch while
                                            mosaic_profile_enable is on; filled by mosaic_get_stats, which
                                            synchronises) */
+    /* maintainer, summed over the units (filled by mosaic_get_stats, which synchronises) */
+    int64_t splits_immediate;           /* invalid clusters split on insertion */
+    int64_t splits_deferred;            /* deferred splits carried out at retrieval */
+    int64_t deferred_inserts;           /* states put into the singleton buffer */
+    int64_t forced_absorbs;             /* invalid, but absorbed: no free cluster id, degenerate split, or full buffer */
 } mosaic_stats;
 
 /* Bytes of device arena and of pinned host arena (0 for MOSAIC_TIER_HBM) a
@@ -184,6 +212,15 @@ int32_t mosaic_get_assignments(mosaic_ctx *ctx, int32_t *frame_to_cluster);
 int32_t mosaic_get_centroids(mosaic_ctx *ctx, double *r, int32_t *n);
 /* summaries [L*Hkv][n_frames_ingested][D] fp64 per-frame key summaries. */
 int32_t mosaic_get_summaries(mosaic_ctx *ctx, double *summaries);
+
+/* Maintainer state (paper Sec. VI), maint_mode != MOSAIC_MAINT_OFF only.  All arguments are
+ * HOST pointers, any may be NULL: var [L*Hkv][C] running variances (Eq. 2 after a K-means run or
+ * a split, Eq. 4 after an insertion); lazy, resident [L*Hkv][C] flags of Alg. 1; n_slots [L*Hkv]
+ * cluster ids in use; n_buf [L*Hkv] and buf_frame, buf_owner [L*Hkv][buffer_max] the buffered
+ * singletons (frame, cluster it was assigned to).  mosaic_get_assignments reports a buffered
+ * frame as -2 - owner.  Synchronises the stream. */
+int32_t mosaic_get_maintainer(mosaic_ctx *ctx, double *var, int32_t *lazy, int32_t *resident,
+                              int32_t *n_slots, int32_t *n_buf, int32_t *buf_frame, int32_t *buf_owner);
 /* Latest selection of one layer (layer >= 0): ids [Hkv][top_k] (-1 padded),
  * n_ids [Hkv], scores [Hkv][C] fp64 (-inf for empty clusters), tok_idx
  * [Hkv][tok_cap] global token indices f*T+t in gather order, n_tok [Hkv].

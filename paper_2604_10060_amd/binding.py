@@ -20,12 +20,13 @@ OK, EINVAL, ENOMEM, ECAPACITY, ENOTREADY, EHIP = 0, -1, -2, -3, -4, -5
 FP32, BF16 = 0, 1
 TIER_HBM, TIER_HOST = 0, 1
 ATTEND_AUTO, ATTEND_VALU, ATTEND_MFMA = 0, 1, 2
+MAINT_OFF, MAINT_EAGER, MAINT_DEFERRED = 0, 1, 2
 _STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ECAPACITY", -4: "ENOTREADY", -5: "EHIP"}
 
 EXPORTS = (
     "mosaic_workspace_size", "mosaic_create", "mosaic_destroy", "mosaic_reset",
     "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_attend",
-    "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries",
+    "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries", "mosaic_get_maintainer",
     "mosaic_get_selection", "mosaic_get_stats", "mosaic_profile_enable",
     "mosaic_profile_read", "mosaic_calibration_copy", "mosaic_last_error",
 )
@@ -49,6 +50,9 @@ class Config(C.Structure):
         ("slab_frames", C.c_int32), ("cache_pages_per_unit", C.c_int32),
         ("cache_fraction", C.c_float), ("reserved1", C.c_int32),
         ("host_arena", C.c_void_p), ("host_arena_bytes", C.c_size_t),
+        ("maint_mode", C.c_int32), ("init_clusters", C.c_int32), ("split_iters", C.c_int32),
+        ("buffer_max", C.c_int32), ("tau_min", C.c_double), ("tau_max", C.c_double),
+        ("tau_n0", C.c_double),
     ]
 
 
@@ -60,6 +64,8 @@ class Stats(C.Structure):
         ("last_n_splits", C.c_int32), ("reserved", C.c_int32),
         ("cache_hits", C.c_int64), ("cache_misses", C.c_int64),
         ("h2d_bytes", C.c_int64), ("h2d_copies", C.c_int64), ("h2d_busy_ms", C.c_double),
+        ("splits_immediate", C.c_int64), ("splits_deferred", C.c_int64),
+        ("deferred_inserts", C.c_int64), ("forced_absorbs", C.c_int64),
     ]
 
 
@@ -87,6 +93,7 @@ def load_library():
     L.mosaic_get_assignments.argtypes = [vp, vp]
     L.mosaic_get_centroids.argtypes = [vp, vp, vp]
     L.mosaic_get_summaries.argtypes = [vp, vp]
+    L.mosaic_get_maintainer.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.mosaic_get_selection.argtypes = [vp, i32, vp, vp, vp, vp, C.c_int64, vp]
     L.mosaic_get_stats.argtypes = [vp, C.POINTER(Stats)]
     L.mosaic_profile_enable.argtypes = [vp, i32]
@@ -104,7 +111,9 @@ def load_library():
 def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, max_frames,
                 n_clusters, top_k, kv_dtype, warmup_frames=0, lloyd_iters=0, recluster_every=0,
                 score_mode=0, max_q_tokens=0, attend_impl=ATTEND_AUTO, tier=TIER_HBM,
-                slab_frames=0, cache_pages_per_unit=0, cache_fraction=0.0) -> Config:
+                slab_frames=0, cache_pages_per_unit=0, cache_fraction=0.0,
+                maint_mode=MAINT_OFF, init_clusters=0, split_iters=0, buffer_max=0,
+                tau_min=0.0, tau_max=0.0, tau_n0=1.0) -> Config:
     c = Config()
     c.n_layers, c.n_q_heads, c.n_kv_heads = n_layers, n_q_heads, n_kv_heads
     c.head_dim, c.tokens_per_frame, c.max_frames = head_dim, tokens_per_frame, max_frames
@@ -114,6 +123,8 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
     c.score_mode, c.max_q_tokens, c.attend_impl = score_mode, max_q_tokens, attend_impl
     c.tier, c.slab_frames, c.cache_pages_per_unit = tier, slab_frames, cache_pages_per_unit
     c.cache_fraction = cache_fraction
+    c.maint_mode, c.init_clusters, c.split_iters, c.buffer_max = maint_mode, init_clusters, split_iters, buffer_max
+    c.tau_min, c.tau_max, c.tau_n0 = tau_min, tau_max, tau_n0
     return c
 
 
@@ -167,6 +178,8 @@ class Mosaic:
         self._h = h
         self.U = cfg.n_layers * cfg.n_kv_heads
         self.dtype = torch.float32 if cfg.kv_dtype == FP32 else torch.bfloat16
+        # score columns beyond n_clusters: the buffered singletons of the deferred-split maintainer
+        self.buffer_max = (cfg.buffer_max or 32) if cfg.maint_mode == MAINT_DEFERRED else 0
 
     def close(self):
         if getattr(self, "_h", None):
@@ -267,7 +280,7 @@ class Mosaic:
         H = c.n_kv_heads
         ids = np.empty((H, c.top_k), dtype=np.int32)
         n_ids = np.empty(H, dtype=np.int32)
-        scores = np.empty((H, c.n_clusters), dtype=np.float64)
+        scores = np.empty((H, c.n_clusters + self.buffer_max), dtype=np.float64)
         n_tok = np.empty(H, dtype=np.int32)
         self._check(self._L.mosaic_get_selection(self._h, layer, ids.ctypes.data, n_ids.ctypes.data,
                                                  scores.ctypes.data, None, 0, n_tok.ctypes.data))
@@ -279,6 +292,21 @@ class Mosaic:
                                                      buf.ctypes.data, cap, None))
             toks = [buf[h, : n_tok[h]].copy() for h in range(H)]
         return ids, n_ids, scores, toks
+
+    def maintainer(self) -> dict:
+        """State of the self-adaptive maintainer: var, lazy, resident [U][C]; n_slots, n_buf [U];
+        buf_frame, buf_owner [U][buffer_max]."""
+        c = self.cfg
+        U, Cn, B = c.n_layers * c.n_kv_heads, c.n_clusters, self.buffer_max
+        out = {"var": np.empty((U, Cn), np.float64), "lazy": np.empty((U, Cn), np.int32),
+               "resident": np.empty((U, Cn), np.int32), "n_slots": np.empty(U, np.int32),
+               "n_buf": np.empty(U, np.int32), "buf_frame": np.zeros((U, max(B, 1)), np.int32),
+               "buf_owner": np.zeros((U, max(B, 1)), np.int32)}
+        self._check(self._L.mosaic_get_maintainer(
+            self._h, out["var"].ctypes.data, out["lazy"].ctypes.data, out["resident"].ctypes.data,
+            out["n_slots"].ctypes.data, out["n_buf"].ctypes.data,
+            out["buf_frame"].ctypes.data if B else None, out["buf_owner"].ctypes.data if B else None))
+        return out
 
     def profile_enable(self, on: bool = True):
         self._check(self._L.mosaic_profile_enable(self._h, 1 if on else 0))

@@ -30,14 +30,29 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 
 struct Layout {
     size_t k_store, v_store, summ, r, rnorm, n, assign, pos, scores, ids, n_ids, sel_pages, n_sel,
-        tok_scratch, part_o, part_ml, stage_k, stage_v, dest, total;
+        tok_scratch, part_o, part_ml, stage_k, stage_v, dest, var, lazy, resident, n_slots, buf_frame,
+        buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, total;
     size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_moves, host_nmoves, host_assign, host_dest, host_total;   // offsets into the pinned host arena
     long long part_entries;
     int Tp, impl, v_transposed;
+    int c_init, split_iters, buf_max, W;   // maintainer (c_init = C, buf_max = 0 when off); warm-up frames
     // host tier geometry
     int SF, slabs_per_unit, HP, cache_blocks, PU, SN, max_clusters;
     size_t kpage, vpage;
 };
+
+// resolved defaults of the maintainer fields and of the warm-up length
+int init_clusters_of(const mosaic_config &c) {
+    if (c.maint_mode == MOSAIC_MAINT_OFF) return c.n_clusters;
+    return c.init_clusters > 0 ? c.init_clusters : std::max(1, c.n_clusters / 2);
+}
+int buffer_max_of(const mosaic_config &c) {
+    if (c.maint_mode != MOSAIC_MAINT_DEFERRED) return 0;
+    return c.buffer_max > 0 ? c.buffer_max : 32;
+}
+int warmup_of(const mosaic_config &c) {
+    return c.warmup_frames > 0 ? c.warmup_frames : 2 * init_clusters_of(c);
+}
 
 int check_config(const mosaic_config *c, std::string &why) {
     if (!c) { why = "config is NULL"; return MOSAIC_EINVAL; }
@@ -49,8 +64,18 @@ int check_config(const mosaic_config *c, std::string &why) {
     if (c->top_k < 1 || c->top_k > c->n_clusters) { why = "top_k must be in 1..n_clusters"; return MOSAIC_EINVAL; }
     if (c->kv_dtype != MOSAIC_FP32 && c->kv_dtype != MOSAIC_BF16) { why = "kv_dtype must be MOSAIC_FP32 or MOSAIC_BF16"; return MOSAIC_EINVAL; }
     if (c->warmup_frames < 0 || c->lloyd_iters < 0 || c->recluster_every < 0 || c->max_q_tokens < 0) { why = "negative count"; return MOSAIC_EINVAL; }
-    const int W = c->warmup_frames > 0 ? c->warmup_frames : 2 * c->n_clusters;
-    if (W < c->n_clusters) { why = "warmup_frames must be at least n_clusters (one seed per cluster)"; return MOSAIC_EINVAL; }
+    if (c->maint_mode < MOSAIC_MAINT_OFF || c->maint_mode > MOSAIC_MAINT_DEFERRED) { why = "maint_mode out of range"; return MOSAIC_EINVAL; }
+    if (c->maint_mode != MOSAIC_MAINT_OFF) {
+        if (c->tier != MOSAIC_TIER_HBM) { why = "the maintainer is available in the HBM tier only"; return MOSAIC_EINVAL; }
+        if (c->recluster_every != 0) { why = "the maintainer and periodic re-clustering exclude each other"; return MOSAIC_EINVAL; }
+        if (c->init_clusters < 0 || c->init_clusters > c->n_clusters) { why = "init_clusters must be in 0..n_clusters"; return MOSAIC_EINVAL; }
+        if (c->split_iters < 0 || c->buffer_max < 0) { why = "negative maintainer count"; return MOSAIC_EINVAL; }
+        if (!(c->tau_n0 > 0.0)) { why = "tau_n0 must be positive"; return MOSAIC_EINVAL; }
+        if (!(c->tau_min == c->tau_min) || !(c->tau_max == c->tau_max)) { why = "tau_min / tau_max is NaN"; return MOSAIC_EINVAL; }
+        if (c->n_clusters + buffer_max_of(*c) > 1024) { why = "n_clusters + buffer_max must not exceed 1024"; return MOSAIC_EINVAL; }
+    }
+    const int W = warmup_of(*c);
+    if (W < init_clusters_of(*c)) { why = "warmup_frames must be at least the number of initial clusters (one seed per cluster)"; return MOSAIC_EINVAL; }
     if (c->score_mode != 0 && c->score_mode != 1) { why = "score_mode must be 0 or 1"; return MOSAIC_EINVAL; }
     if (c->attend_impl < MOSAIC_ATTEND_AUTO || c->attend_impl > MOSAIC_ATTEND_MFMA) { why = "attend_impl out of range"; return MOSAIC_EINVAL; }
     if (c->attend_impl == MOSAIC_ATTEND_MFMA && c->kv_dtype != MOSAIC_BF16) { why = "the MFMA attention kernel needs bf16 KV"; return MOSAIC_EINVAL; }
@@ -83,7 +108,7 @@ Layout make_layout(const mosaic_config &c) {
     const bool host = c.tier == MOSAIC_TIER_HOST;
     L.PU = (int)F; L.SN = 1;
     if (host) {
-        const int W = c.warmup_frames > 0 ? c.warmup_frames : 2 * c.n_clusters;
+        const int W = warmup_of(c);
         L.SF = c.slab_frames > 0 ? c.slab_frames : 8;
         L.slabs_per_unit = (int)((F + L.SF - 1) / L.SF + C);
         L.HP = L.slabs_per_unit * L.SF;
@@ -117,7 +142,22 @@ Layout make_layout(const mosaic_config &c) {
     L.n = take(U * C * 4);
     L.assign = take(U * F * 4);
     L.pos = take(U * F * 4);
-    L.scores = take(U * C * 8);
+    L.c_init = init_clusters_of(c); L.buf_max = buffer_max_of(c); L.W = warmup_of(c);
+    L.split_iters = c.split_iters > 0 ? c.split_iters : 4;
+    const bool mt = c.maint_mode != MOSAIC_MAINT_OFF;
+    const size_t B = (size_t)L.buf_max;
+    L.var = take(mt ? U * C * 8 : 0);
+    L.lazy = take(mt ? U * C * 4 : 0);
+    L.resident = take(mt ? U * C * 4 : 0);
+    L.n_slots = take(mt ? U * 4 : 0);
+    L.buf_frame = take(mt ? U * B * 4 : 0);
+    L.buf_owner = take(mt ? U * B * 4 : 0);
+    L.n_buf = take(mt ? U * 4 : 0);
+    L.mt_cnt = take(mt ? U * 4 * 8 : 0);
+    L.mt_mem = take(mt ? U * F * 4 : 0);
+    L.mt_side = take(mt ? U * F * 4 : 0);
+    L.mt_nrm = take(mt ? U * F * 8 : 0);
+    L.scores = take(U * (C + B) * 8);
     L.ids = take(U * k * 4);
     L.n_ids = take(U * 4);
     L.sel_pages = take(U * F * 4);
@@ -207,6 +247,8 @@ int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes, size_
     return MOSAIC_OK;
 }
 
+static hipError_t clear_maintainer(mosaic_ctx *ctx);
+
 int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     std::string why;
     int rc = check_config(cfg, why);
@@ -226,7 +268,7 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     hipError_t e = hipGetDevice(&ctx->device);
     if (e != hipSuccess) { delete ctx; return fail_hip(nullptr, e, "hipGetDevice"); }
     ctx->stream = (hipStream_t)cfg->stream;
-    ctx->W = cfg->warmup_frames > 0 ? cfg->warmup_frames : 2 * cfg->n_clusters;
+    ctx->W = L.W;
     ctx->iters = cfg->lloyd_iters > 0 ? cfg->lloyd_iters : 8;
     ctx->impl = L.impl;
     ctx->n_frames = 0;
@@ -250,6 +292,15 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.rnorm = (double *)(base + L.rnorm); dv.n = (int *)(base + L.n);
     dv.assign = (int *)(base + L.assign); dv.pos = (int *)(base + L.pos);
     dv.scores = (double *)(base + L.scores); dv.ids = (int *)(base + L.ids);
+    dv.maint_mode = cfg->maint_mode; dv.c_init = L.c_init; dv.split_iters = L.split_iters;
+    dv.buf_max = L.buf_max; dv.SC = dv.C + L.buf_max;
+    dv.tau_min = cfg->tau_min; dv.tau_max = cfg->tau_max; dv.tau_n0 = cfg->tau_n0;
+    dv.var = (double *)(base + L.var); dv.lazy = (int *)(base + L.lazy);
+    dv.resident = (int *)(base + L.resident); dv.n_slots = (int *)(base + L.n_slots);
+    dv.buf_frame = (int *)(base + L.buf_frame); dv.buf_owner = (int *)(base + L.buf_owner);
+    dv.n_buf = (int *)(base + L.n_buf); dv.mt_cnt = (long long *)(base + L.mt_cnt);
+    dv.mt_mem = (int *)(base + L.mt_mem); dv.mt_side = (int *)(base + L.mt_side);
+    dv.mt_nrm = (double *)(base + L.mt_nrm);
     dv.n_ids = (int *)(base + L.n_ids); dv.sel_pages = (int *)(base + L.sel_pages);
     dv.n_sel = (int *)(base + L.n_sel); dv.tok_scratch = (int *)(base + L.tok_scratch);
     dv.part_o = (float *)(base + L.part_o); dv.part_ml = (float *)(base + L.part_ml);
@@ -319,6 +370,13 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
                 (e = hipEventCreateWithFlags(&ht->attend_done[l], hipEventDisableTiming)) != hipSuccess)
                 return bail(MOSAIC_EHIP, std::string("host tier event creation: ") + hipGetErrorString(e));
     }
+    if (hipError_t e = clear_maintainer(ctx); e != hipSuccess) {
+        const std::string msg = std::string("hipMemsetAsync: ") + hipGetErrorString(e);
+        delete ctx;
+        *out = nullptr;
+        (void)msg;
+        return MOSAIC_EHIP;
+    }
     *out = ctx;
     return MOSAIC_OK;
 }
@@ -338,6 +396,19 @@ int32_t mosaic_destroy(mosaic_ctx *ctx) {
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     delete ctx;
     return MOSAIC_OK;
+}
+
+// Maintainer state that must read as empty before the initial clustering has run.
+static hipError_t clear_maintainer(mosaic_ctx *ctx) {
+    const DeviceView &dv = ctx->dv;
+    if (!dv.maint_mode) return hipSuccess;
+    hipError_t e;
+    if ((e = hipMemsetAsync(dv.n_buf, 0, (size_t)dv.U * 4, ctx->stream)) != hipSuccess) return e;
+    if ((e = hipMemsetAsync(dv.n_slots, 0, (size_t)dv.U * 4, ctx->stream)) != hipSuccess) return e;
+    if ((e = hipMemsetAsync(dv.mt_cnt, 0, (size_t)dv.U * 4 * 8, ctx->stream)) != hipSuccess) return e;
+    if ((e = hipMemsetAsync(dv.var, 0, (size_t)dv.U * dv.C * 8, ctx->stream)) != hipSuccess) return e;
+    if ((e = hipMemsetAsync(dv.lazy, 0, (size_t)dv.U * dv.C * 4, ctx->stream)) != hipSuccess) return e;
+    return hipMemsetAsync(dv.resident, 0, (size_t)dv.U * dv.C * 4, ctx->stream);
 }
 
 int32_t mosaic_reset(mosaic_ctx *ctx) {
@@ -360,6 +431,8 @@ int32_t mosaic_reset(mosaic_ctx *ctx) {
     const int attend_impl = ctx->stats.attend_impl;
     memset(&ctx->stats, 0, sizeof ctx->stats);
     ctx->stats.attend_impl = attend_impl;
+    hipError_t e = clear_maintainer(ctx);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipMemsetAsync");
     return MOSAIC_OK;
 }
 
@@ -694,6 +767,23 @@ int32_t mosaic_get_summaries(mosaic_ctx *ctx, double *summaries) {
     return sync(ctx);
 }
 
+int32_t mosaic_get_maintainer(mosaic_ctx *ctx, double *var, int32_t *lazy, int32_t *resident,
+                              int32_t *n_slots, int32_t *n_buf, int32_t *buf_frame, int32_t *buf_owner) {
+    if (!ctx) return MOSAIC_EINVAL;
+    const DeviceView &dv = ctx->dv;
+    if (!dv.maint_mode) return fail(ctx, MOSAIC_EINVAL, "the maintainer is off (maint_mode = MOSAIC_MAINT_OFF)");
+    const size_t UC = (size_t)dv.U * dv.C, UB = (size_t)dv.U * dv.buf_max;
+    int rc;
+    if (var && (rc = d2h(ctx, var, dv.var, UC * 8)) != MOSAIC_OK) return rc;
+    if (lazy && (rc = d2h(ctx, lazy, dv.lazy, UC * 4)) != MOSAIC_OK) return rc;
+    if (resident && (rc = d2h(ctx, resident, dv.resident, UC * 4)) != MOSAIC_OK) return rc;
+    if (n_slots && (rc = d2h(ctx, n_slots, dv.n_slots, (size_t)dv.U * 4)) != MOSAIC_OK) return rc;
+    if (n_buf && (rc = d2h(ctx, n_buf, dv.n_buf, (size_t)dv.U * 4)) != MOSAIC_OK) return rc;
+    if (buf_frame && UB && (rc = d2h(ctx, buf_frame, dv.buf_frame, UB * 4)) != MOSAIC_OK) return rc;
+    if (buf_owner && UB && (rc = d2h(ctx, buf_owner, dv.buf_owner, UB * 4)) != MOSAIC_OK) return rc;
+    return sync(ctx);
+}
+
 int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32_t *n_ids,
                              double *scores, int32_t *tok_idx, int64_t tok_cap, int32_t *n_tok) {
     if (!ctx) return MOSAIC_EINVAL;
@@ -709,7 +799,7 @@ int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32
         if (he != hipSuccess) return fail_hip(ctx, he, "hipStreamSynchronize");
         if (ids && (rc = d2h(ctx, ids, dv.ids + (size_t)u0 * dv.k, (size_t)H * dv.k * 4)) != MOSAIC_OK) return rc;
         if (n_ids && (rc = d2h(ctx, n_ids, dv.n_ids + u0, (size_t)H * 4)) != MOSAIC_OK) return rc;
-        if (scores && (rc = d2h(ctx, scores, dv.scores + (size_t)u0 * dv.C, (size_t)H * dv.C * 8)) != MOSAIC_OK) return rc;
+        if (scores && (rc = d2h(ctx, scores, dv.scores + (size_t)u0 * dv.SC, (size_t)H * dv.SC * 8)) != MOSAIC_OK) return rc;
         if ((rc = sync(ctx)) != MOSAIC_OK) return rc;
         for (int h = 0; h < H; ++h) {
             const HostTier::Unit &un = ht->units[u0 + h];
@@ -727,7 +817,7 @@ int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32
     }
     if (ids && (rc = d2h(ctx, ids, dv.ids + (size_t)u0 * dv.k, (size_t)H * dv.k * 4)) != MOSAIC_OK) return rc;
     if (n_ids && (rc = d2h(ctx, n_ids, dv.n_ids + u0, (size_t)H * 4)) != MOSAIC_OK) return rc;
-    if (scores && (rc = d2h(ctx, scores, dv.scores + (size_t)u0 * dv.C, (size_t)H * dv.C * 8)) != MOSAIC_OK) return rc;
+    if (scores && (rc = d2h(ctx, scores, dv.scores + (size_t)u0 * dv.SC, (size_t)H * dv.SC * 8)) != MOSAIC_OK) return rc;
     std::vector<int32_t> nsel(H);
     if ((rc = d2h(ctx, nsel.data(), dv.n_sel + u0, (size_t)H * 4)) != MOSAIC_OK) return rc;
     if ((rc = sync(ctx)) != MOSAIC_OK) return rc;
@@ -762,6 +852,17 @@ int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats) {
         ctx->stats.cache_hits = ht->hits; ctx->stats.cache_misses = ht->misses;
         ctx->stats.h2d_bytes = ht->h2d_bytes; ctx->stats.h2d_copies = ht->h2d_copies;
         ctx->stats.h2d_busy_ms = ht->busy_ms;
+    }
+    if (ctx->dv.maint_mode) {
+        const DeviceView &dv = ctx->dv;
+        std::vector<long long> cnt((size_t)dv.U * 4);
+        int rc = d2h(ctx, cnt.data(), dv.mt_cnt, cnt.size() * 8);
+        if (rc != MOSAIC_OK || (rc = sync(ctx)) != MOSAIC_OK) return rc;
+        long long tot[4] = {0, 0, 0, 0};
+        for (int u = 0; u < dv.U; ++u)
+            for (int i = 0; i < 4; ++i) tot[i] += cnt[(size_t)u * 4 + i];
+        ctx->stats.splits_immediate = tot[0]; ctx->stats.splits_deferred = tot[1];
+        ctx->stats.deferred_inserts = tot[2]; ctx->stats.forced_absorbs = tot[3];
     }
     *stats = ctx->stats;
     return MOSAIC_OK;

@@ -8,6 +8,7 @@
 // All decision arithmetic is fp64: on CDNA4 the fp64 vector rate equals the
 // non-packed fp32 rate, so exact-to-rounding decisions cost only table bytes.
 #include "mosaic_internal.h"
+#include "maintain_device.h"
 
 namespace mosaic {
 
@@ -145,7 +146,12 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
 // ---------------------------------------------------------------------------
 // Online assignment + Eq. 3, frames f0..f1-1 in order.  grid (U), 256 threads.
 // ---------------------------------------------------------------------------
-template <int D>
+// With MAINT the insertion procedure of the self-adaptive maintainer (Sec. VI,
+// Alg. 1 lines 1-10) follows the update: running variance (Eq. 4), threshold
+// (Eq. 5) at the size before the insertion, then absorb / split / defer.
+enum { kActAbsorb = 1, kActSplit = 2, kActDefer = 3, kActForced = 4 };
+
+template <int D, bool MAINT>
 __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0, int f1) {
     constexpr int EPL = D / 16;  // elements per lane in a 16-lane row group
     const int u = blockIdx.x, tid = threadIdx.x, C = dv.C;
@@ -154,8 +160,9 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
     __shared__ double dot_sh[1024];
     __shared__ double red_v[4];
     __shared__ int red_i[4];
-    __shared__ double snorm_sh, nsum_sh[2];
-    __shared__ int win_sh;
+    __shared__ double snorm_sh, nsum_sh[2], dsum_sh[2];
+    __shared__ int win_sh, act_sh;
+    __shared__ SplitShared<MAINT ? D : 16> split_sh;   // (small placeholder when the maintainer is off)
     double *r = dv.r + (size_t)u * C * D;
     double *rn = dv.rnorm + (size_t)u * C;
     int *n = dv.n + (size_t)u * C;
@@ -207,26 +214,64 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
         const int a = win_sh;
         const int na_i = n[a];
         const double na = (double)na_i;
-        double sq = 0.0;
+        double sq = 0.0, dq = 0.0;
         if (tid < D) {
             // Eq. 3 with each operation rounded separately (no contraction)
             const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, r[(size_t)a * D + tid]), s_sh[tid]),
                                         na + 1.0);
             r[(size_t)a * D + tid] = rv;
             sq = rv * rv;
+            const double t = s_sh[tid] - rv;
+            dq = t * t;
         }
         if (wave < 2) {
             sq = wave_sum(sq);
-            if (lane == 0) nsum_sh[wave] = sq;
+            if (MAINT) dq = wave_sum(dq);
+            if (lane == 0) { nsum_sh[wave] = sq; dsum_sh[wave] = dq; }
         }
         __syncthreads();   // all threads have read n[a] and written r before the scalars change
         if (tid == 0) {
             rn[a] = sqrt(D > 64 ? nsum_sh[0] + nsum_sh[1] : nsum_sh[0]);
-            n[a] = na_i + 1;
-            dv.assign[(size_t)u * dv.F + f] = a;
-            dv.pos[(size_t)u * dv.F + f] = na_i;
+            int act = kActAbsorb;
+            if (MAINT) {
+                const double dist2 = D > 64 ? dsum_sh[0] + dsum_sh[1] : dsum_sh[0];
+                double *var = dv.var + (size_t)u * C;
+                const double var_new = (na * var[a] + dist2) / (na + 1.0);                          // Eq. 4
+                const double tau = dv.tau_min + (dv.tau_max - dv.tau_min) * exp(-na / dv.tau_n0);   // Eq. 5
+                var[a] = var_new;
+                const bool on_gpu = dv.maint_mode == MOSAIC_MAINT_EAGER || dv.resident[(size_t)u * C + a] != 0;
+                if (var_new <= tau) act = kActAbsorb;
+                else if (on_gpu) act = kActSplit;
+                else if (dv.n_buf[u] < dv.buf_max) act = kActDefer;
+                else act = kActForced;
+                if (act == kActDefer || act == kActForced) dv.lazy[(size_t)u * C + a] = 1;
+                if (act == kActDefer) {
+                    const int b = dv.n_buf[u];
+                    dv.buf_frame[(size_t)u * dv.buf_max + b] = f;
+                    dv.buf_owner[(size_t)u * dv.buf_max + b] = a;
+                    dv.n_buf[u] = b + 1;
+                    dv.mt_cnt[(size_t)u * 4 + 2] += 1;
+                }
+                if (act == kActForced) dv.mt_cnt[(size_t)u * 4 + 3] += 1;
+                act_sh = act;
+            }
+            if (act == kActDefer) {                     // held in the buffer on behalf of cluster a
+                dv.assign[(size_t)u * dv.F + f] = -2 - a;
+                dv.pos[(size_t)u * dv.F + f] = 0;
+            } else {
+                n[a] = na_i + 1;
+                dv.assign[(size_t)u * dv.F + f] = a;
+                dv.pos[(size_t)u * dv.F + f] = na_i;
+            }
         }
         __syncthreads();
+        if constexpr (MAINT) {
+            if (act_sh == kActSplit) {                  // workgroup-uniform
+                const int fresh = mt_split_cluster<D>(dv, u, a, f + 1, false, split_sh);
+                if (tid == 0) dv.mt_cnt[(size_t)u * 4 + (fresh >= 0 ? 0 : 3)] += 1;
+            }
+            __syncthreads();
+        }
     }
 }
 
@@ -235,20 +280,73 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
 // r_j = summary of frame floor(j*W/C); every cluster counts as non-empty for
 // the first assignment round (n_j = 1 as a placeholder).
 // ---------------------------------------------------------------------------
+// With the maintainer on only the first c_init ids are seeded (the rest of the
+// table is empty until splits fill it) and the maintainer's state is cleared.
 template <int D>
 __global__ __launch_bounds__(kBlock) void k_lloyd_seed(DeviceView dv, int W) {
     constexpr int EPL = D / 16;
     const int u = blockIdx.x, tid = threadIdx.x, C = dv.C;
+    const int Cl = dv.maint_mode ? dv.c_init : C;
     const int lr = tid % 16, row0 = tid / 16;
     for (int j = row0; j < C; j += 16) {
-        const int src = (int)(((long long)j * W) / C);
-        const double *s = dv.summ + ((size_t)u * dv.F + src) * D + lr * EPL;
         double *rj = dv.r + ((size_t)u * C + j) * D + lr * EPL;
+        if (j >= Cl) {
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) rj[i] = 0.0;
+            if (lr == 0) { dv.rnorm[(size_t)u * C + j] = 0.0; dv.n[(size_t)u * C + j] = 0; }
+            continue;
+        }
+        const int src = (int)(((long long)j * W) / Cl);
+        const double *s = dv.summ + ((size_t)u * dv.F + src) * D + lr * EPL;
         double sq = 0.0;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) { rj[i] = s[i]; sq += s[i] * s[i]; }
         sq = group16_sum(sq);
         if (lr == 0) { dv.rnorm[(size_t)u * C + j] = sqrt(sq); dv.n[(size_t)u * C + j] = 1; }
+    }
+    if (dv.maint_mode) {
+        for (int j = tid; j < C; j += kBlock) {
+            dv.var[(size_t)u * C + j] = 0.0;
+            dv.lazy[(size_t)u * C + j] = 0;
+            dv.resident[(size_t)u * C + j] = 0;
+        }
+        if (tid == 0) { dv.n_slots[u] = Cl; dv.n_buf[u] = 0; }
+        if (tid < 4) dv.mt_cnt[(size_t)u * 4 + tid] = 0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Intra-cluster variance from the member lists (Eq. 2), after a K-means run.
+// grid (U, clusters), 256 threads: 16-lane groups take members in turn, the
+// group partials are added in a fixed order.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_exact_var(DeviceView dv, int n_frames) {
+    constexpr int EPL = D / 16, NG = kBlock / 16;
+    const int u = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, C = dv.C;
+    const int lr = tid % 16, grp = tid / 16;
+    __shared__ double part[NG];
+    const int *assign = dv.assign + (size_t)u * dv.F;
+    const double *rj = dv.r + ((size_t)u * C + j) * D + lr * EPL;
+    double rv[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) rv[i] = rj[i];
+    double acc = 0.0;
+    for (int f = grp; f < n_frames; f += NG) {
+        if (assign[f] != j) continue;                    // uniform within the 16-lane group
+        const double *s = dv.summ + ((size_t)u * dv.F + f) * D + lr * EPL;
+        double p = 0.0;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) { const double t = s[i] - rv[i]; p += t * t; }
+        acc += group16_sum(p);
+    }
+    if (lr == 0) part[grp] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        double tot = 0.0;
+        for (int g = 0; g < NG; ++g) tot += part[g];
+        const int cnt = dv.n[(size_t)u * C + j];
+        dv.var[(size_t)u * C + j] = cnt > 0 ? tot / (double)cnt : 0.0;
     }
 }
 
@@ -446,8 +544,13 @@ hipError_t launch_fetch(const DeviceView &dv, int u0, int n_units, int max_moves
 
 hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s) {
     return checked([&] {
-        if (dv.D == 64) k_assign_update<64><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
-        else k_assign_update<128><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
+        if (dv.maint_mode) {
+            if (dv.D == 64) k_assign_update<64, true><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
+            else k_assign_update<128, true><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
+        } else {
+            if (dv.D == 64) k_assign_update<64, false><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
+            else k_assign_update<128, false><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
+        }
     });
 }
 
@@ -473,6 +576,13 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
             else k_lloyd_update<128><<<gu, 128, 0, s>>>(dv, n_frames);
         });
         if (e != hipSuccess) return e;
+    }
+    if (dv.maint_mode) {
+        const dim3 gv(dv.U, dv.c_init);
+        e = checked([&] {
+            if (dv.D == 64) k_exact_var<64><<<gv, kBlock, 0, s>>>(dv, n_frames);
+            else k_exact_var<128><<<gv, kBlock, 0, s>>>(dv, n_frames);
+        });
     }
     return e;
 }

@@ -56,8 +56,22 @@ struct DeviceView {
     int *n;           // [U][C]      sizes in frames
     int *assign;      // [U][F]      frame -> cluster
     int *pos;         // [U][F]      rank of the frame among its cluster's members (ascending frame order)
+    // self-adaptive maintainer (paper Sec. VI); maint_mode 0 = off (the arrays are then empty)
+    int maint_mode, c_init, split_iters, buf_max;
+    int SC;           // score columns per unit: C + buf_max
+    double tau_min, tau_max, tau_n0;
+    double *var;      // [U][C]      running intra-cluster variance (Eq. 2 / Eq. 4)
+    int *lazy;        // [U][C]      lazy-split flag
+    int *resident;    // [U][C]      1 = selected by the unit's latest retrieval
+    int *n_slots;     // [U]         cluster ids in use: [0, n_slots)
+    int *buf_frame;   // [U][buf_max] buffered singletons: frame
+    int *buf_owner;   // [U][buf_max]                       cluster they were assigned to
+    int *n_buf;       // [U]
+    long long *mt_cnt;// [U][4]      splits on insertion, deferred splits, buffered inserts, forced absorbs
+    int *mt_mem, *mt_side;   // [U][F] scratch of Split
+    double *mt_nrm;          // [U][F]
     // latest selection per unit
-    double *scores;   // [U][C]
+    double *scores;   // [U][SC]
     int *ids;         // [U][k]
     int *n_ids;       // [U]
     int *sel_pages;   // [U][F]      frames of the selected clusters, gather order

@@ -193,3 +193,166 @@ def run_workload(wl, units=None, device="cuda:0", n_questions=1, decode_steps=0,
         query_with_parity(m, wl, q, oracles, K, V, rep, layer_mode)
     m.close()
     return rep
+
+
+# ---------------------------------------------------------------------------
+# Self-adaptive maintainer (paper Sec. VI)
+# ---------------------------------------------------------------------------
+def maintainer_overrides(mt: dict) -> dict:
+    """Library config fields of an oracle maintainer dict."""
+    return dict(maint_mode=mt["mode"], init_clusters=mt["c_init"], split_iters=mt.get("split_iters", 4),
+                buffer_max=mt.get("buf_max", 0), tau_min=mt["tau_min"], tau_max=mt["tau_max"], tau_n0=mt["n0"])
+
+
+def compare_maintained_state(m: binding.Mosaic, wl, oracles, where: str, min_gap: dict):
+    """Whole clustering state of the library against the oracle units (exact integers, fp64 state
+    to rtol 1e-9).  min_gap[(l, h)] = smallest relative gap of any decision the oracle took since
+    the last comparison: a mismatch is only excusable below NEAR_TIE."""
+    A = m.assignments()
+    R, N = m.centroids()
+    S = m.maintainer()
+    for (l, h), o in oracles.items():
+        if not o.ready:
+            continue
+        u = l * wl.n_kv_heads + h
+        try:
+            np.testing.assert_array_equal(A[u, : o.n_frames], o.assignments())
+            np.testing.assert_array_equal(N[u], o.sizes())
+            assert S["n_slots"][u] == o.n_slots and S["n_buf"][u] == o.n_buf
+            np.testing.assert_array_equal(S["lazy"][u], o.lazy_flags())
+            np.testing.assert_array_equal(S["resident"][u], o.resident_flags())
+            fr, ow = o.buffer()
+            np.testing.assert_array_equal(S["buf_frame"][u, : o.n_buf], fr)
+            np.testing.assert_array_equal(S["buf_owner"][u, : o.n_buf], ow)
+        except AssertionError as ex:
+            g = min_gap.get((l, h), np.inf)
+            raise AssertionError(f"unit {(l, h)} {where}: maintainer state differs from the oracle "
+                                 f"(smallest decision gap since the last check {g:.3e}, near-tie bar {NEAR_TIE}): {ex}")
+        live = o.sizes() > 0
+        Ro = o.centroids()
+        rel = np.abs(R[u][live] - Ro[live]).max() / max(np.abs(Ro[live]).max(), 1e-30)
+        assert rel < 1e-9, f"unit {(l, h)} {where}: centroid rel err {rel:.3e}"
+        np.testing.assert_allclose(S["var"][u][live], o.variances()[live], rtol=1e-9, atol=1e-300,
+                                   err_msg=f"unit {(l, h)} {where}: variances")
+
+
+def _oracle_ingest_tracking(o, k_frame, min_gap, key):
+    dec = o.ingest(k_frame)
+    if o.ready and dec.winner >= 0:
+        g = dec.gap
+        v, t = o.last_threshold_test
+        g = min(g, abs(v - t) / max(abs(v), abs(t), 1e-30))
+        if o.last_action in (orc.ACT_SPLIT,):
+            g = min(g, o.split_min_gap)
+        min_gap[key] = min(min_gap.get(key, np.inf), g)
+
+
+def run_maintained(wl, mt: dict, units=None, device="cuda:0", batch_pattern=(1, 3, 8, 2, 16),
+                   query_every=0, n_final_queries=2, question_tokens=None):
+    """Stream `wl` through the library with the maintainer on and through oracle units with the
+    same parameters; compare the whole state after every library call.  query_every > 0 issues a
+    retrieve + attend every that many frames (in deferred mode this is what makes clusters
+    resident and carries out deferred splits), compared like the plain query path."""
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    Kd, Vd = K.to(device), V.to(device)
+    m = binding.Mosaic(binding.config_for(wl, warmup_frames=0, **maintainer_overrides(mt)), device=device)
+    rep = Report()
+    if units is None:
+        units = [(l, h) for l in range(wl.n_layers) for h in range(wl.n_kv_heads)]
+    F = wl.n_frames
+    oracles, Kcpu, min_gap = {}, {}, {}
+    for (l, h) in units:
+        oracles[(l, h)] = orc.OracleUnit(wl.n_clusters, wl.head_dim, wl.tokens_per_frame, F, 0,
+                                         wl.lloyd_iters, 0, maintainer=mt)
+        Kcpu[(l, h)] = inputs.unit_pages(K, l, h)
+    Tq = question_tokens or wl.question_tokens
+    tag = 0
+
+    def query(n_tok):
+        nonlocal tag
+        q = st.question(st.draw_scene(), n_tok, tag).to(device)
+        tag += 1
+        query_maintained_with_parity(m, wl, q, oracles, K, V, rep, mt)
+        compare_maintained_state(m, wl, oracles, f"after query {tag}", {})
+
+    f, bi, next_q = 0, 0, query_every
+    W = 2 * mt["c_init"]
+    while f < F:
+        nb = min(batch_pattern[bi % len(batch_pattern)], F - f)
+        if f < W:
+            nb = min(nb, W - f)
+        if query_every and f < next_q:
+            nb = min(nb, next_q - f)
+        bi += 1
+        m.ingest_frame(Kd[f:f + nb].contiguous(), Vd[f:f + nb].contiguous())
+        for key, o in oracles.items():
+            for ff in range(f, f + nb):
+                _oracle_ingest_tracking(o, Kcpu[key][ff], min_gap, key)
+        f += nb
+        if f >= W:
+            compare_maintained_state(m, wl, oracles, f"after {f} frames", min_gap)
+            min_gap.clear()
+        if query_every and f >= next_q and f >= W:
+            query(1)
+            next_q += query_every
+    for i in range(n_final_queries):
+        query(Tq if i == 0 else 1)
+    s = m.stats()
+    tot = {"split_now": 0, "split_deferred": 0, "deferred": 0, "forced_absorb": 0}
+    for o in oracles.values():
+        for k_, v_ in o.counters().items():
+            tot[k_] += v_
+    if len(units) == wl.n_layers * wl.n_kv_heads:
+        assert (s.splits_immediate, s.splits_deferred, s.deferred_inserts, s.forced_absorbs) == \
+            (tot["split_now"], tot["split_deferred"], tot["deferred"], tot["forced_absorb"])
+    rep.notes.append(tot)
+    m.close()
+    return rep
+
+
+def query_maintained_with_parity(m, wl, q, oracles, K, V, rep, mt):
+    """Like query_with_parity for a context with the maintainer on: in deferred mode the
+    representative set includes the buffered singletons (ids >= n_clusters) and the call changes
+    the clustering state (residency, deferred splits), on both sides."""
+    L, G, C = wl.n_layers, wl.group, wl.n_clusters
+    outs, lses = [], []
+    for l in range(L):
+        m.retrieve(l, q[l].contiguous())
+        o_, l_ = m.attend(l, q[l].contiguous())
+        outs.append(o_); lses.append(l_)
+    out, lse = torch.stack(outs), torch.stack(lses)
+    torch.cuda.synchronize()
+    out_h = out.float().cpu().numpy().astype(np.float64)
+    lse_h = lse.cpu().numpy().astype(np.float64)
+    q_h = q.float().cpu().numpy().astype(np.float64)
+    sel_cache = {}
+    for (l, h), o in oracles.items():
+        if l not in sel_cache:
+            sel_cache[l] = m.selection(l)
+        ids, n_ids, scores, toks = sel_cache[l]
+        nb_before = o.n_buf
+        sizes_before = o.sizes()
+        if mt["mode"] == 2:
+            ids_o, sc_o, tok_o, gap = o.retrieve_maintained(q_h[l], h, G, wl.top_k)
+        else:
+            ids_o, sc_o, tok_o, gap = o.retrieve(q_h[l], h, G, wl.top_k)
+        live = np.concatenate([sizes_before > 0, np.ones(nb_before, bool)]) if mt["mode"] == 2 else sizes_before > 0
+        got_sc = scores[h][: len(live)]
+        np.testing.assert_allclose(got_sc[live], sc_o[: len(live)][live], rtol=1e-9, atol=1e-12)
+        assert np.all(np.isneginf(got_sc[~live]))
+        got_ids = ids[h, : n_ids[h]]
+        assert n_ids[h] == len(ids_o) and np.all(ids[h, n_ids[h]:] == -1)
+        if not np.array_equal(got_ids, ids_o):
+            raise AssertionError(f"unit {(l, h)}: ids {got_ids} != oracle {ids_o} (gap at k {gap:.3e})")
+        np.testing.assert_array_equal(toks[h], tok_o)
+        Ku = inputs.unit_pages(K, l, h).reshape(-1, wl.head_dim)
+        Vu = inputs.unit_pages(V, l, h).reshape(-1, wl.head_dim)
+        want, want_lse = orc.attend(q_h[l], Ku, Vu, tok_o, h, G)
+        err = np.abs(out_h[l][:, h * G:(h + 1) * G, :] - want).max()
+        lerr = np.abs(lse_h[l][:, h * G:(h + 1) * G] - want_lse).max()
+        rep.max_out_err = max(rep.max_out_err, float(err))
+        rep.max_lse_err = max(rep.max_lse_err, float(lerr))
+        assert err <= OUT_TOL[wl.kv_dtype], f"unit {(l, h)}: attention max-abs err {err:.3e}"
+        assert lerr <= LSE_TOL[wl.kv_dtype], f"unit {(l, h)}: lse max-abs err {lerr:.3e}"
+    return out, lse

@@ -314,3 +314,32 @@ def test_host_tier_cache_too_small_is_an_error():
         m.retrieve(-1, q[None].contiguous())
     assert e.value.code == binding.EINVAL
     m.close()
+
+
+# ---------------------------------------------------------------------------
+# Self-adaptive maintainer (paper Sec. VI)
+# ---------------------------------------------------------------------------
+def _mt(mode, c_init, tau_min, tau_max, n0=8.0, split_iters=4, buf_max=0):
+    return dict(mode=mode, c_init=c_init, tau_min=tau_min, tau_max=tau_max, n0=n0,
+                split_iters=split_iters, buf_max=buf_max)
+
+
+@pytest.mark.gpu
+def test_maintainer_eager_fp32():
+    """Config-0 stream (8 scenes), 3 initial clusters in a table of 24: variance tracking,
+    threshold and immediate splits must follow the oracle insertion by insertion."""
+    wl = inputs.CONFIGS[0].scaled(name="maint_eager_fp32", n_clusters=24, top_k=4)
+    rep = harness.run_maintained(wl, _mt(1, 3, 1.5, 6.0))
+    tot = rep.notes[-1]
+    assert tot["split_now"] > 0, tot
+    assert rep.max_out_err <= 1e-4
+
+
+@pytest.mark.gpu
+def test_maintainer_eager_bf16_table_fills_up():
+    """D = 128, bf16, a table that is too small: splits until no id is free, then forced absorbs."""
+    wl = inputs.CONFIGS[1].scaled(name="maint_eager_bf16", n_frames=192, n_scenes=12, n_clusters=8,
+                                  top_k=3, question_tokens=4)
+    rep = harness.run_maintained(wl, _mt(1, 2, 0.5, 2.0, n0=6.0, split_iters=3), units=[(0, 0), (0, 3)])
+    tot = rep.notes[-1]
+    assert tot["split_now"] > 0 and tot["forced_absorb"] > 0, tot

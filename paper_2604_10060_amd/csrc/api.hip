@@ -657,8 +657,11 @@ int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32
         ctx->stats.retrieve_calls += 1;
         return MOSAIC_OK;
     }
-    hipError_t e = launch_retrieve(ctx->dv, u0, nu, q_dev, n_q_tokens, (int)ctx->n_frames,
-                                   ctx->cfg.score_mode, true, ctx->stream);
+    hipError_t e = ctx->dv.maint_mode == MOSAIC_MAINT_DEFERRED
+        ? launch_retrieve_deferred(ctx->dv, u0, nu, q_dev, n_q_tokens, (int)ctx->n_frames,
+                                   ctx->cfg.score_mode, ctx->stream)
+        : launch_retrieve(ctx->dv, u0, nu, q_dev, n_q_tokens, (int)ctx->n_frames,
+                          ctx->cfg.score_mode, true, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "retrieve launch");
     const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? ctx->dv.L : layer + 1;
     for (int l = l0; l < l1; ++l) { ctx->sel_epoch[l] = ctx->epoch; ctx->sel_tq[l] = n_q_tokens; }

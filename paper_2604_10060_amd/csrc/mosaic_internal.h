@@ -121,6 +121,9 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
 // write_pages = false (host tier): only scores and ids; the page list comes from the host
 hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                            int n_frames, int score_mode, bool write_pages, hipStream_t s);
+// deferred-split maintainer: singletons take part, residency and deferred splits follow the selection
+hipError_t launch_retrieve_deferred(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
+                                    int n_frames, int score_mode, hipStream_t s);
 // host tier: copy staged frames f0..f0+n-1 of every unit to host page dest[u][f - f0]
 hipError_t launch_offload(const DeviceView &dv, int f0, int n, hipStream_t s);
 // host tier: move the pages listed in moves[u0..u0+n_units) from the pinned slabs into the cache

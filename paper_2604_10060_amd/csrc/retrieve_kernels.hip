@@ -3,6 +3,7 @@
 // of the GPU-resident index, ranks them, and lists the pages of the chosen
 // clusters.  Nothing is copied: attention later reads the pages in place.
 #include "mosaic_internal.h"
+#include "maintain_device.h"
 
 namespace mosaic {
 
@@ -192,6 +193,159 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Query Retrieval with the deferred-split maintainer (paper Sec. VI-B, Alg. 1):
+// the representative set is the non-empty clusters plus the buffered singletons
+// (a singleton's representative is its own frame summary; id = C + buffer slot);
+// after the page list of this query has been written, the selected clusters
+// become the resident set and every selected cluster that carries a lazy-split
+// flag has its buffered entries merged and its split carried out (lines 12-17),
+// in selection order.  grid (n_units), kRetrBlock threads; C + buf_max <= 1024.
+// ---------------------------------------------------------------------------
+template <typename E, int D>
+__global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv, int u0, const E *q, int Tq,
+                                                                  int n_frames, int score_mode) {
+    constexpr int BLK = kRetrBlock;
+    constexpr int EPL = D / 16, RPP = BLK / 16, PARTS = BLK / D;
+    const int uc = blockIdx.x, u = u0 + uc, tid = threadIdx.x;
+    const int C = dv.C, G = dv.G, Hq = dv.Hq, k = dv.k, SC = dv.SC;
+    const int lc = uc / dv.Hkv, h = u % dv.Hkv;
+    const int lr = tid % 16, row0 = tid / 16;
+    __shared__ double qbar[D];
+    __shared__ double qpart[PARTS][D];
+    __shared__ double sc_sh[1024];
+    __shared__ int n_sh[1024];      // size in frames of a representative's cluster (0 = not live)
+    __shared__ int rank_sh[1024];
+    __shared__ int cnt_sh[1024];
+    __shared__ int ids_sh[1024];
+    __shared__ int off_sh[1025];
+    __shared__ int n_live_sh;
+    __shared__ SplitShared<D> split_sh;
+    const double *r = dv.r + (size_t)u * C * D;
+    const double *rn = dv.rnorm + (size_t)u * C;
+    const int *n = dv.n + (size_t)u * C;
+    int *assign = dv.assign + (size_t)u * dv.F;
+    const int *pos = dv.pos + (size_t)u * dv.F;
+    int *buf_frame = dv.buf_frame + (size_t)u * dv.buf_max;
+    int *buf_owner = dv.buf_owner + (size_t)u * dv.buf_max;
+    const int nb = dv.n_buf[u], R = C + nb;
+
+    for (int j = tid; j < 1024; j += BLK) { n_sh[j] = j < C ? n[j] : (j < R ? 1 : 0); cnt_sh[j] = 0; }
+    if (tid == 0) n_live_sh = 0;
+    {   // mean query, as in k_retrieve
+        const int d = tid % D, part = tid / D, RQ = Tq * G;
+        const E *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + d;
+        double a[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+        for (int r0 = part; r0 < RQ; r0 += 8 * PARTS) {
+            E v[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int rr = min(r0 + x * PARTS, RQ - 1), t = rr / G, g = rr - t * G;
+                v[x] = qb[((size_t)t * Hq + g) * D];
+            }
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+                if (r0 + x * PARTS < RQ) a[x] += to_f64<E>(v[x]);
+        }
+        qpart[part][d] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+    }
+    __syncthreads();
+    if (tid < D) {
+        double acc = 0.0;
+#pragma unroll
+        for (int p = 0; p < PARTS; ++p) acc += qpart[p][tid];
+        qbar[tid] = acc / (double)(Tq * G);
+    }
+    __syncthreads();
+    // scores of clusters and singletons
+    for (int j = row0; j < SC; j += RPP) {
+        double sc = -INFINITY;
+        if (j < R && n_sh[j] > 0) {
+            const double *rj = (j < C ? r + (size_t)j * D
+                                      : dv.summ + ((size_t)u * dv.F + buf_frame[j - C]) * D) + lr * EPL;
+            double p = 0.0, sq = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) { p += qbar[lr * EPL + e] * rj[e]; sq += rj[e] * rj[e]; }
+            p = group16_sum(p);
+            sq = group16_sum(sq);
+            const double nr = j < C ? rn[j] : sqrt(sq);
+            sc = score_mode == 1 ? p : (nr == 0.0 ? 0.0 : p / nr);
+        }
+        if (lr == 0) {
+            if (j < 1024) sc_sh[j] = sc;
+            dv.scores[(size_t)u * SC + j] = sc;
+        }
+    }
+    __syncthreads();
+    // rank among the live representatives by (score descending, id ascending)
+    for (int j = tid; j < R; j += BLK) {
+        if (n_sh[j] <= 0) continue;
+        const double sj = sc_sh[j];
+        int c = 0;
+        for (int i = 0; i < R; ++i) {
+            const double si = sc_sh[i];
+            c += n_sh[i] > 0 && ((si > sj) || (si == sj && i < j));
+        }
+        cnt_sh[j] = c;
+    }
+    __syncthreads();
+    for (int j = tid; j < 1024; j += BLK) {
+        int rk = -1;
+        if (j < R && n_sh[j] > 0) {
+            rk = cnt_sh[j];
+            atomicAdd(&n_live_sh, 1);
+            if (rk < k) ids_sh[rk] = j; else rk = -1;
+        }
+        rank_sh[j] = rk;
+    }
+    __syncthreads();
+    const int n_ids = min(k, n_live_sh);
+    if (tid == 0) {
+        int o = 0;
+        off_sh[0] = 0;
+        for (int i = 0; i < n_ids; ++i) { o += n_sh[ids_sh[i]]; off_sh[i + 1] = o; }
+        dv.n_ids[u] = n_ids;
+        dv.n_sel[u] = o;
+    }
+    for (int i = tid; i < k; i += BLK) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
+    __syncthreads();
+    // page list: representatives in selection order, member frames ascending
+    int *sel = dv.sel_pages + (size_t)u * dv.F;
+    for (int f = tid; f < n_frames; f += BLK) {
+        const int c = assign[f];
+        if (c < 0) continue;
+        const int rk = rank_sh[c];
+        if (rk >= 0) sel[off_sh[rk] + pos[f]] = f;
+    }
+    for (int b = tid; b < nb; b += BLK) {
+        const int rk = rank_sh[C + b];
+        if (rk >= 0) sel[off_sh[rk]] = buf_frame[b];
+    }
+    // the selection is what is on the GPU from now on
+    for (int j = tid; j < C; j += BLK) dv.resident[(size_t)u * C + j] = rank_sh[j] >= 0;
+    __syncthreads();
+    // deferred splits of the selected clusters
+    for (int i = 0; i < n_ids; ++i) {
+        const int j = ids_sh[i];
+        if (j >= C || !dv.lazy[(size_t)u * C + j]) continue;      // workgroup-uniform
+        __syncthreads();
+        if (tid == 0) {
+            const int cur = dv.n_buf[u];
+            int w = 0;
+            for (int b = 0; b < cur; ++b) {
+                if (buf_owner[b] == j) { assign[buf_frame[b]] = j; continue; }
+                buf_frame[w] = buf_frame[b]; buf_owner[w] = buf_owner[b]; ++w;
+            }
+            dv.n_buf[u] = w;
+            dv.lazy[(size_t)u * C + j] = 0;
+        }
+        __syncthreads();
+        const int fresh = mt_split_cluster<D>(dv, u, j, n_frames, true, split_sh);
+        if (tid == 0 && fresh >= 0) dv.mt_cnt[(size_t)u * 4 + 1] += 1;
+        __syncthreads();
+    }
+}
+
 // Token-index expansion of the page lists (observer only).  grid (n_units).
 __global__ __launch_bounds__(kBlock) void k_expand_tok_idx(DeviceView dv, int u0) {
     const int uc = blockIdx.x, u = u0 + uc, T = dv.T;
@@ -212,6 +366,18 @@ hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void
     } else {
         if (dv.D == 64) k_retrieve<unsigned short, 64><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
         else k_retrieve<unsigned short, 128><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_retrieve_deferred(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
+                                    int n_frames, int score_mode, hipStream_t s) {
+    if (dv.esize == 4) {
+        if (dv.D == 64) k_retrieve_deferred<float, 64><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode);
+        else k_retrieve_deferred<float, 128><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode);
+    } else {
+        if (dv.D == 64) k_retrieve_deferred<unsigned short, 64><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode);
+        else k_retrieve_deferred<unsigned short, 128><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode);
     }
     return hipGetLastError();
 }

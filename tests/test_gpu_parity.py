@@ -343,3 +343,43 @@ def test_maintainer_eager_bf16_table_fills_up():
     rep = harness.run_maintained(wl, _mt(1, 2, 0.5, 2.0, n0=6.0, split_iters=3), units=[(0, 0), (0, 3)])
     tot = rep.notes[-1]
     assert tot["split_now"] > 0 and tot["forced_absorb"] > 0, tot
+
+
+@pytest.mark.gpu
+def test_maintainer_deferred_fp32():
+    """Alg. 1 in full: nothing is resident before the first query, so invalid insertions are
+    buffered as singletons; queries every 12 frames make their selection resident, select
+    singletons, and carry out the deferred splits."""
+    wl = inputs.CONFIGS[0].scaled(name="maint_deferred_fp32", n_clusters=24, top_k=4)
+    rep = harness.run_maintained(wl, _mt(2, 3, 1.5, 6.0, buf_max=12), query_every=12)
+    tot = rep.notes[-1]
+    assert tot["deferred"] > 0 and tot["split_deferred"] > 0, tot
+    assert rep.max_out_err <= 1e-4
+
+
+@pytest.mark.gpu
+def test_maintainer_deferred_bf16_small_buffer():
+    """D = 128, bf16, a 3-entry buffer that overflows (forced absorbs) and a multi-token question."""
+    wl = inputs.CONFIGS[1].scaled(name="maint_deferred_bf16", n_frames=224, n_scenes=14, n_clusters=20,
+                                  top_k=3, question_tokens=5)
+    rep = harness.run_maintained(wl, _mt(2, 2, 0.5, 2.0, n0=6.0, split_iters=3, buf_max=3),
+                                 units=[(0, 1), (0, 2)], query_every=20)
+    tot = rep.notes[-1]
+    assert tot["deferred"] > 0 and tot["forced_absorb"] > 0, tot
+
+
+@pytest.mark.gpu
+def test_maintainer_config_errors():
+    wl = inputs.CONFIGS[0]
+    base = dict(maint_mode=binding.MAINT_EAGER, init_clusters=4, tau_min=1.0, tau_max=2.0, tau_n0=8.0)
+    for bad in (dict(tau_n0=0.0), dict(init_clusters=wl.n_clusters + 1), dict(maint_mode=3),
+                dict(tier=binding.TIER_HOST), dict(recluster_every=64),
+                dict(maint_mode=binding.MAINT_DEFERRED, buffer_max=1024)):
+        kw = dict(base); kw.update(bad)
+        with pytest.raises(binding.MosaicError) as ei:
+            binding.workspace_sizes(binding.config_for(wl, **kw))
+        assert ei.value.code == binding.EINVAL
+    m = binding.Mosaic(binding.config_for(wl))          # maintainer off: the observer says so
+    with pytest.raises(binding.MosaicError):
+        m.maintainer()
+    m.close()

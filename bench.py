@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "maintainer"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count")
     ap.add_argument("--all-layers-call", action="store_true",
@@ -385,6 +385,105 @@ def run_prefill_leg(n_streams=8, check=True):
             "parity_spot_check": checked}
 
 
+def run_maintainer_leg(layers=4, query_every=64, decode=64, check=True):
+    """Self-adaptive maintainer (Sec. VI) on the config-2 stream recipe (geometric scenes, 5 %
+    outlier tokens), `layers` of its 28 layers: 32 initial clusters in a table of 256, thresholds
+    tau_min 4 / tau_max 16 / N0 32 (squared distance; within-scene spread of this recipe is 0.4-2,
+    two merged scenes ~64).  Eager mode splits every invalid cluster at once; deferred mode follows
+    Alg. 1 with a decode query every `query_every` frames (its selection is the resident set).
+    Reports ingest rates, split counts of both modes (the paper's Sec. VIII figure is the
+    reduction of split operations by deferral) and the decode step on the resulting clustering."""
+    import torch
+    from paper_2604_10060_amd import binding, inputs
+    dev = "cuda:0"
+    wl = inputs.CONFIGS[2].scaled(name="cfg2_recipe_maintained", n_layers=layers, n_clusters=256, top_k=16,
+                                  recluster_every=0)
+    mt = dict(mode=1, c_init=32, tau_min=4.0, tau_max=16.0, n0=32.0, split_iters=4, buf_max=256)
+    L, Hq, D, T, F, H = wl.n_layers, wl.n_q_heads, wl.head_dim, wl.tokens_per_frame, wl.n_frames, wl.n_kv_heads
+    st = inputs.SceneStream(wl, device=dev)
+    shape = (F, L, H, T, D)
+    K_all = torch.empty(shape, dtype=wl.torch_dtype, device=dev)
+    V_all = torch.empty(shape, dtype=wl.torch_dtype, device=dev)
+    for f in range(F):
+        K_all[f], V_all[f] = st.frame(f)
+    n_q = F // query_every + decode + 8
+    q_dec = torch.stack([st.question(st.draw_scene(), 1, 1 + i) for i in range(n_q)])   # [n][L][1][Hq][D]
+    out = torch.empty((L, 1, Hq, D), dtype=wl.torch_dtype, device=dev)
+    lse = torch.empty((L, 1, Hq), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    lq = Hq * D * 2
+
+    def step(m, i):
+        qp = q_dec.data_ptr() + i * L * lq
+        for l in range(L):
+            m.retrieve_raw(l, qp + l * lq, 1)
+            m.attend_raw(l, qp + l * lq, 1, out.data_ptr() + l * lq, lse.data_ptr() + l * Hq * 4)
+
+    res = {}
+    for name, mode in (("eager", binding.MAINT_EAGER), ("deferred", binding.MAINT_DEFERRED)):
+        m = binding.Mosaic(binding.config_for(wl, warmup_frames=0, maint_mode=mode, init_clusters=mt["c_init"],
+                                              split_iters=mt["split_iters"], buffer_max=mt["buf_max"],
+                                              tau_min=mt["tau_min"], tau_max=mt["tau_max"], tau_n0=mt["n0"]),
+                           device=dev)
+        fps = {}
+        for batch in (16, 1):
+            m.reset()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            f, qi = 0, 0
+            while f < F:
+                nb = min(batch, F - f)
+                m.ingest_frame(K_all[f:f + nb], V_all[f:f + nb])
+                f += nb
+                if mode == binding.MAINT_DEFERRED and f % query_every == 0 and f >= 2 * mt["c_init"]:
+                    step(m, qi); qi += 1
+            torch.cuda.synchronize()
+            fps[batch] = F / (time.perf_counter() - t)
+        s = m.stats()
+        slots = m.maintainer()["n_slots"]
+        _, sizes = m.centroids()
+        for i in range(8):
+            step(m, F // query_every + i)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(decode):
+            step(m, F // query_every + 8 + i)
+        torch.cuda.synchronize()
+        step_us = (time.perf_counter() - t) / decode * 1e6
+        res[name] = {"ingest_frames_per_s": round(fps[1], 1), "ingest_frames_per_s_batch16": round(fps[16], 1),
+                     "splits_immediate": int(s.splits_immediate), "splits_deferred": int(s.splits_deferred),
+                     "deferred_inserts": int(s.deferred_inserts), "forced_absorbs": int(s.forced_absorbs),
+                     "clusters_per_unit_mean": round(float(slots.mean()), 1),
+                     "largest_cluster_frames": int(sizes.max()),
+                     "decode_step_us": round(step_us, 2)}
+        if check and mode == binding.MAINT_EAGER:
+            from oracle import mosaic_oracle as orc
+            l0, h0 = layers - 1, 1
+            o = orc.OracleUnit(wl.n_clusters, D, T, F, 0, wl.lloyd_iters, 0, maintainer=mt)
+            Ku = inputs.unit_pages(K_all, l0, h0)
+            for f in range(F):
+                o.ingest(Ku[f])
+            u = l0 * H + h0
+            same = bool(np.array_equal(m.assignments()[u], o.assignments())) and int(slots[u]) == o.n_slots
+            assert same, "maintainer leg: assignments differ from the oracle"
+            res[name]["parity_spot_check"] = {"unit": [l0, h0], "assignments_equal": same,
+                                              "oracle_counters": o.counters()}
+        m.close()
+        del m
+    e, d = res["eager"], res["deferred"]
+    tot_e = e["splits_immediate"] + e["splits_deferred"]
+    tot_d = d["splits_immediate"] + d["splits_deferred"]
+    del K_all, V_all
+    torch.cuda.empty_cache()
+    return {"config": {"workload": wl.name, "layers": layers, "frames": F, "tokens_per_frame": T,
+                       "cluster_table": wl.n_clusters, "init_clusters": mt["c_init"], "top_k": wl.top_k,
+                       "tau_min": mt["tau_min"], "tau_max": mt["tau_max"], "tau_n0": mt["n0"],
+                       "buffer_max": mt["buf_max"], "query_every_frames_deferred": query_every},
+            "eager": e, "deferred": d,
+            "split_operations_eager": tot_e, "split_operations_deferred": tot_d,
+            "split_reduction_by_deferral": round(1.0 - tot_d / tot_e, 4) if tot_e else None}
+
+
 def run_host_leg(layers=2, steps=128, check=True):
     """Config 3 (host-offload tier) with the layer count scaled to `layers` (the
     full 28 layers need 184 GB of pinned host memory; the per-layer shape is
@@ -561,6 +660,9 @@ def main():
     if args.workload == "cfg4":
         print(json.dumps(run_prefill_leg(check=args.check_units > 0)))
         return
+    if args.workload == "maintainer":
+        print(json.dumps(run_maintainer_leg(layers=args.layers or 4, check=args.check_units > 0)))
+        return
     if args.workload == "cfg3":
         print(json.dumps(run_host_leg(layers=args.layers or 2, check=args.check_units > 0)))
         return
@@ -597,6 +699,10 @@ def main():
             extra["cfg4_prefill_8_streams"] = run_prefill_leg()
         except Exception as ex:                      # noqa: BLE001
             extra["cfg4_prefill_8_streams"] = {"error": repr(ex)[:300]}
+        try:
+            extra["next1_maintainer"] = run_maintainer_leg()
+        except Exception as ex:                      # noqa: BLE001
+            extra["next1_maintainer"] = {"error": repr(ex)[:300]}
         for layers in (2, 1):
             try:
                 import torch

@@ -221,8 +221,11 @@ int32_t mosaic_get_summaries(mosaic_ctx *ctx, double *summaries);
  * frame as -2 - owner.  Synchronises the stream. */
 int32_t mosaic_get_maintainer(mosaic_ctx *ctx, double *var, int32_t *lazy, int32_t *resident,
                               int32_t *n_slots, int32_t *n_buf, int32_t *buf_frame, int32_t *buf_owner);
+
 /* Latest selection of one layer (layer >= 0): ids [Hkv][top_k] (-1 padded),
- * n_ids [Hkv], scores [Hkv][C] fp64 (-inf for empty clusters), tok_idx
+ * n_ids [Hkv], scores [Hkv][C] fp64 (-inf for empty clusters; with
+ * MOSAIC_MAINT_DEFERRED the rows have C + buffer_max columns, column C + b
+ * being buffered singleton b, and ids >= C name singletons), tok_idx
  * [Hkv][tok_cap] global token indices f*T+t in gather order, n_tok [Hkv].
  * ECAPACITY if a unit retrieved more than tok_cap tokens. */
 int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32_t *n_ids,

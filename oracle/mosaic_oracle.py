@@ -320,3 +320,43 @@ class OracleUnit:
         sc = self.score(qbar)
         ids, gap = select(sc, self.sizes(), top_k)
         return ids, sc, self.gather(ids), gap
+
+
+def augmented_context(unit: "OracleUnit", K_unit: np.ndarray, V_unit: np.ndarray, ids: np.ndarray,
+                      window_frames: int, global_reps: bool):
+    """Retrieval augmentation (Sec. V-C): what attention runs over besides the retrieved clusters.
+
+    K_unit, V_unit [F][T][D] of this unit.  Returns (tok_idx, K_ext, V_ext): token indices into
+    K_ext / V_ext [N + P][D], the unit's N = F*T real tokens followed by P pseudo tokens.
+      * local window: all tokens of the `window_frames` most recent frames, after the clusters,
+        ascending; a window frame that belongs to a selected cluster is listed with the window only,
+        so every real token is attended once (the paper does not say how overlaps are treated);
+      * global representatives: one pseudo token per non-empty cluster, in cluster order: key = the
+        cluster's representative (Eq. 1), value = the mean of its members' value vectors (the paper
+        keeps "the representatives of all clusters"; values follow the keys' frame->cluster map).
+    Plain numpy: the definition written out."""
+    K_unit, V_unit = f64(K_unit), f64(V_unit)
+    F, T, D = unit.n_frames, unit.T, unit.D
+    A = unit.assignments()
+    w0 = max(0, F - int(window_frames))
+    tok = []
+    for j in ids:
+        for f in range(w0):
+            if A[f] == j:
+                tok.extend(range(f * T, (f + 1) * T))
+    for f in range(w0, F):
+        tok.extend(range(f * T, (f + 1) * T))
+    Kx, Vx = K_unit[:F].reshape(F * T, D), V_unit[:F].reshape(F * T, D)
+    if global_reps:
+        R, n = unit.centroids(), unit.sizes()
+        keys, vals = [], []
+        for j in range(unit.C):
+            if n[j] > 0:
+                keys.append(R[j])
+                vals.append(V_unit[:F][A == j].reshape(-1, D).mean(axis=0))
+        P = len(keys)
+        if P:
+            Kx = np.concatenate([Kx, np.stack(keys)])
+            Vx = np.concatenate([Vx, np.stack(vals)])
+            tok.extend(range(F * T, F * T + P))
+    return np.asarray(tok, dtype=np.int32), Kx, Vx

@@ -631,3 +631,66 @@ def test_maintainer_conserves_frames():
                 assert (A < 0).sum() == u.n_buf and u.sizes().sum() + u.n_buf == f + 1
                 assert np.all(u.sizes()[u.n_slots:] == 0)
         assert u.n_slots > 3
+
+
+# --------------------------------------------------------------------------
+# Retrieval augmentation (Sec. V-C): global representatives + local window
+# --------------------------------------------------------------------------
+def _aug_unit(seed, F=40, T=3, D=8, C=5):
+    r = _rng(seed)
+    K, _ = _stream(F, T, D, 4, seed=seed)
+    V = r.normal(size=(F, T, D))
+    u = orc.OracleUnit(C, D, T, F, lloyd_iters=3)
+    for f in range(F):
+        u.ingest(K[f])
+    return u, K, V, r
+
+
+def test_window_covering_the_stream_is_dense_attention():
+    u, K, V, r = _aug_unit(31)
+    F, T, D = 40, 3, 8
+    q = r.normal(size=(2, 2, D))
+    ids, _, _, _ = u.retrieve(q, 0, 2, 2)
+    tok, Kx, Vx = orc.augmented_context(u, K, V, ids, window_frames=F + 5, global_reps=False)
+    np.testing.assert_array_equal(tok, np.arange(F * T))       # every token once, nothing from the clusters
+    out, lse = orc.attend(q, Kx, Vx, tok, 0, 2)
+    logits = np.einsum("tgd,nd->tgn", q, K.reshape(-1, D)) / np.sqrt(D)
+    np.testing.assert_allclose(out, np.einsum("tgn,nd->tgd", softmax(logits, axis=-1), V.reshape(-1, D)), rtol=1e-12)
+    np.testing.assert_allclose(lse, logsumexp(logits, axis=-1), rtol=1e-12)
+
+
+def test_window_frames_are_listed_once_and_last():
+    u, K, V, r = _aug_unit(32)
+    F, T, W = 40, 3, 6
+    A = u.assignments()
+    ids = np.array([A[F - 1], A[0]], dtype=np.int32) if A[F - 1] != A[0] else np.array([A[0]], dtype=np.int32)
+    tok, _, _ = orc.augmented_context(u, K, V, ids, window_frames=W, global_reps=False)
+    assert len(set(tok.tolist())) == len(tok)                   # no token twice
+    np.testing.assert_array_equal(tok[-W * T:], np.arange((F - W) * T, F * T))
+    want_frames = sorted(set(np.nonzero(np.isin(A[: F - W], ids))[0].tolist()) | set(range(F - W, F)))
+    assert sorted(set((tok // T).tolist())) == want_frames
+    plain = u.gather(ids)                                        # without the window: whole clusters
+    assert set(plain.tolist()) <= set(tok.tolist())
+
+
+def test_global_representatives_are_cluster_means_and_merge_by_lse():
+    u, K, V, r = _aug_unit(33)
+    F, T, D = 40, 3, 8
+    q = r.normal(size=(3, 2, D))
+    ids, _, tok_plain, _ = u.retrieve(q, 1, 1, 2)
+    tok, Kx, Vx = orc.augmented_context(u, K, V, ids, window_frames=0, global_reps=True)
+    A, n = u.assignments(), u.sizes()
+    live = np.nonzero(n > 0)[0]
+    P = len(live)
+    np.testing.assert_array_equal(tok[: len(tok_plain)], tok_plain)
+    np.testing.assert_array_equal(tok[len(tok_plain):], F * T + np.arange(P))
+    for i, j in enumerate(live):
+        np.testing.assert_allclose(Kx[F * T + i], K[A == j].reshape(-1, D).mean(axis=0), rtol=1e-12)   # Eq. 1 over member tokens
+        np.testing.assert_allclose(Vx[F * T + i], V[A == j].reshape(-1, D).mean(axis=0), rtol=1e-12)
+    # one softmax over the union == log-sum-exp merge of the two parts computed separately
+    out, lse = orc.attend(q, Kx, Vx, tok, 1, 1)
+    o1, l1 = orc.attend(q, Kx, Vx, tok[: len(tok_plain)], 1, 1)
+    o2, l2 = orc.attend(q, Kx, Vx, tok[len(tok_plain):], 1, 1)
+    w1, w2 = np.exp(l1 - np.logaddexp(l1, l2)), np.exp(l2 - np.logaddexp(l1, l2))
+    np.testing.assert_allclose(out, o1 * w1[..., None] + o2 * w2[..., None], rtol=1e-12)
+    np.testing.assert_allclose(lse, np.logaddexp(l1, l2), rtol=1e-12)

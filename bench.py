@@ -66,6 +66,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (counter calibration for rocprofv3 --pmc)")
+    ap.add_argument("--aug-window", type=int, default=0, help="retrieval augmentation: local window in frames")
+    ap.add_argument("--aug-reps", action="store_true", help="retrieval augmentation: global representatives")
     ap.add_argument("--check-units", type=int, default=2,
                     help="units spot-checked against the oracle before timing (0 = none)")
     return ap.parse_args()
@@ -84,7 +86,8 @@ def n_tok_all(m, L):
     return out
 
 
-def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrate=False):
+def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrate=False, aug=None):
+    """aug = (window_frames, global_reps) switches the retrieval augmentation of Sec. V-C on."""
     import torch
     from paper_2604_10060_amd import binding, inputs
 
@@ -115,7 +118,8 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
         torch.cuda.synchronize()
         del a, b
 
-    m = binding.Mosaic(binding.config_for(wl), device=dev)
+    aug_cfg = dict(aug_window_frames=aug[0], aug_global_reps=int(aug[1])) if aug else {}
+    m = binding.Mosaic(binding.config_for(wl, **aug_cfg), device=dev)
     frame_bytes = L * wl.n_kv_heads * T * D * esz
     kp, vp = K_all.data_ptr(), V_all.data_ptr()
     lib, h = m._L, m._h
@@ -170,8 +174,12 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
             oracles[(l, hh)] = o
         rep = harness.Report()
         lm = "all" if all_layers else "per_layer"
-        harness.query_with_parity(m, wl, q_question, oracles, K_all, V_all, rep, lm)
-        harness.query_with_parity(m, wl, q_dec[0], oracles, K_all, V_all, rep, lm)
+        if aug:
+            harness.query_augmented_with_parity(m, wl, q_question, oracles, K_all, V_all, rep, aug[0], aug[1])
+            harness.query_augmented_with_parity(m, wl, q_dec[0], oracles, K_all, V_all, rep, aug[0], aug[1])
+        else:
+            harness.query_with_parity(m, wl, q_question, oracles, K_all, V_all, rep, lm)
+            harness.query_with_parity(m, wl, q_dec[0], oracles, K_all, V_all, rep, lm)
         checked = {"units": [list(p) for p in pick], "max_out_err": rep.max_out_err,
                    "max_lse_err": rep.max_lse_err, "topk_near_ties": rep.topk_near_ties}
         log(f"[bench] parity spot check on units {pick}: out err {rep.max_out_err:.2e} "
@@ -674,7 +682,8 @@ def main():
     main_leg = run_leg(wl, steps=args.steps, warmup=args.warmup, all_layers=args.all_layers_call,
                        check_units=args.check_units,
                        cpu_seconds=0 if args.no_cpu_baseline else args.cpu_seconds,
-                       calibrate=args.calibrate_copy)
+                       calibrate=args.calibrate_copy,
+                       aug=(args.aug_window, args.aug_reps) if (args.aug_window or args.aug_reps) else None)
     extra = None
     if not args.no_extra and args.workload == "cfg1" and not (args.layers or args.frames):
         extra = {}
@@ -699,6 +708,16 @@ def main():
             extra["cfg4_prefill_8_streams"] = run_prefill_leg()
         except Exception as ex:                      # noqa: BLE001
             extra["cfg4_prefill_8_streams"] = {"error": repr(ex)[:300]}
+        try:
+            leg = run_leg(inputs.CONFIGS[1], steps=args.steps, warmup=args.warmup, all_layers=False,
+                          check_units=1, cpu_seconds=0, aug=(16, True))
+            extra["next2_augmentation_cfg1"] = {
+                "augmentation": {"window_frames": 16, "global_reps": True},
+                "decode_step_us": round(leg["us_per_step"], 2), "step_us_median": leg["step_us_median"],
+                "step_us_p95": leg["step_us_p95"], "roofline": leg["roofline"],
+                "question_ms": leg["question_ms"], "parity_spot_check": leg["parity_spot_check"]}
+        except Exception as ex:                      # noqa: BLE001
+            extra["next2_augmentation_cfg1"] = {"error": repr(ex)[:300]}
         try:
             extra["next1_maintainer"] = run_maintainer_leg()
         except Exception as ex:                      # noqa: BLE001

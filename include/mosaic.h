@@ -107,6 +107,16 @@ typedef struct {
                                      0 -> 32; n_clusters + buffer_max <= 1024.  A full buffer: absorbed */
     double tau_min, tau_max;      /* Eq. 5: threshold for large / for small clusters (squared distance) */
     double tau_n0;                /* Eq. 5: transition rate N0 > 0 */
+    /* Retrieval augmentation (paper Sec. V-C, "Retrieval Augmentation"); MOSAIC_TIER_HBM only, not
+     * with MOSAIC_MAINT_DEFERRED.  mosaic_attend then attends over the retrieved clusters AND
+     *  (1) aug_global_reps = 1: one pseudo token per non-empty cluster, key = its representative
+     *      (Eq. 1), value = the mean of its members' value vectors (a compact global view);
+     *  (2) aug_window_frames = w > 0: all tokens of the w most recent frames (local window).
+     * Every real token is attended once: a window frame that also belongs to a selected cluster
+     * is listed with the window only.  The three parts are one softmax (merged exactly through
+     * their log-sum-exp). */
+    int32_t aug_global_reps;
+    int32_t aug_window_frames;
 } mosaic_config;
 
 /* maint_mode.  _EAGER: every cluster counts as GPU resident, an invalid cluster is split at once

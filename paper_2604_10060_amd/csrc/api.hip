@@ -31,10 +31,11 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 struct Layout {
     size_t k_store, v_store, summ, r, rnorm, n, assign, pos, scores, ids, n_ids, sel_pages, n_sel,
         tok_scratch, part_o, part_ml, stage_k, stage_v, dest, var, lazy, resident, n_slots, buf_frame,
-        buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, total;
+        buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, vsumm, rvsum, rep_k, rep_v, aug_o, aug_ml, total;
     size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_moves, host_nmoves, host_assign, host_dest, host_total;   // offsets into the pinned host arena
     long long part_entries;
     int Tp, impl, v_transposed;
+    int nt_max;
     int c_init, split_iters, buf_max, W;   // maintainer (c_init = C, buf_max = 0 when off); warm-up frames
     // host tier geometry
     int SF, slabs_per_unit, HP, cache_blocks, PU, SN, max_clusters;
@@ -74,6 +75,12 @@ int check_config(const mosaic_config *c, std::string &why) {
         if (!(c->tau_min == c->tau_min) || !(c->tau_max == c->tau_max)) { why = "tau_min / tau_max is NaN"; return MOSAIC_EINVAL; }
         if (c->n_clusters + buffer_max_of(*c) > 1024) { why = "n_clusters + buffer_max must not exceed 1024"; return MOSAIC_EINVAL; }
     }
+    if (c->aug_global_reps < 0 || c->aug_global_reps > 1 || c->aug_window_frames < 0) { why = "aug_global_reps must be 0 or 1, aug_window_frames >= 0"; return MOSAIC_EINVAL; }
+    if (c->aug_window_frames > 1024) { why = "aug_window_frames must not exceed 1024"; return MOSAIC_EINVAL; }
+    if (c->aug_global_reps || c->aug_window_frames) {
+        if (c->tier != MOSAIC_TIER_HBM) { why = "retrieval augmentation is available in the HBM tier only"; return MOSAIC_EINVAL; }
+        if (c->maint_mode == MOSAIC_MAINT_DEFERRED) { why = "retrieval augmentation is not available with MOSAIC_MAINT_DEFERRED"; return MOSAIC_EINVAL; }
+    }
     const int W = warmup_of(*c);
     if (W < init_clusters_of(*c)) { why = "warmup_frames must be at least the number of initial clusters (one seed per cluster)"; return MOSAIC_EINVAL; }
     if (c->score_mode != 0 && c->score_mode != 1) { why = "score_mode must be 0 or 1"; return MOSAIC_EINVAL; }
@@ -103,6 +110,7 @@ Layout make_layout(const mosaic_config &c) {
     const int maxq = c.max_q_tokens > 0 ? c.max_q_tokens : 256;
     const long long nt_max = ((long long)maxq * G + kRowTile - 1) / kRowTile;
     L.part_entries = std::max<long long>(4096, (long long)U * nt_max * 2);
+    L.nt_max = (int)nt_max;
     L.kpage = T * D * e;
     L.vpage = D * (L.v_transposed ? (size_t)L.Tp : T) * e;
     const bool host = c.tier == MOSAIC_TIER_HOST;
@@ -157,6 +165,12 @@ Layout make_layout(const mosaic_config &c) {
     L.mt_mem = take(mt ? U * F * 4 : 0);
     L.mt_side = take(mt ? U * F * 4 : 0);
     L.mt_nrm = take(mt ? U * F * 8 : 0);
+    L.vsumm = take(c.aug_global_reps ? U * F * D * 8 : 0);
+    L.rvsum = take(c.aug_global_reps ? U * C * D * 8 : 0);
+    L.rep_k = take(c.aug_global_reps ? U * C * D * 4 : 0);
+    L.rep_v = take(c.aug_global_reps ? U * C * D * 4 : 0);
+    L.aug_o = take(c.aug_global_reps ? U * (size_t)nt_max * kRowTile * D * 4 : 0);
+    L.aug_ml = take(c.aug_global_reps ? U * (size_t)nt_max * 2 * kRowTile * 4 : 0);
     L.scores = take(U * (C + B) * 8);
     L.ids = take(U * k * 4);
     L.n_ids = take(U * 4);
@@ -292,6 +306,12 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.rnorm = (double *)(base + L.rnorm); dv.n = (int *)(base + L.n);
     dv.assign = (int *)(base + L.assign); dv.pos = (int *)(base + L.pos);
     dv.scores = (double *)(base + L.scores); dv.ids = (int *)(base + L.ids);
+    dv.aug_reps = cfg->aug_global_reps; dv.aug_window = cfg->aug_window_frames; dv.nt_max = L.nt_max;
+    dv.vsumm = cfg->aug_global_reps ? (double *)(base + L.vsumm) : nullptr;
+    dv.rvsum = (double *)(base + L.rvsum);
+    dv.rep_k = (float *)(base + L.rep_k); dv.rep_v = (float *)(base + L.rep_v);
+    dv.aug_o = (float *)(base + L.aug_o); dv.aug_ml = (float *)(base + L.aug_ml);
+    ctx->rv_epoch = -1;
     dv.maint_mode = cfg->maint_mode; dv.c_init = L.c_init; dv.split_iters = L.split_iters;
     dv.buf_max = L.buf_max; dv.SC = dv.C + L.buf_max;
     dv.tau_min = cfg->tau_min; dv.tau_max = cfg->tau_max; dv.tau_n0 = cfg->tau_n0;
@@ -699,6 +719,14 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t
         }
         ev0 = ctx->ev[ctx->ev_used]; ev1 = ctx->ev[ctx->ev_used + 1];
         ctx->ev_used += 2;
+    }
+    if (ctx->dv.aug_reps && ctx->rv_epoch != ctx->epoch) {
+        // global representatives (Sec. V-C): the clustering changed since the value sums were formed.
+        // Their attention partial is computed by extra workgroups of the attention launch below.
+        // (Its own kernel cost ~8 us per decode step; its own stream, with fork/join events, more.)
+        if ((e = launch_value_reps(ctx->dv, (int)ctx->n_frames, ctx->stream)) != hipSuccess)
+            return fail_hip(ctx, e, "value representatives launch");
+        ctx->rv_epoch = ctx->epoch;
     }
     e = ctx->impl == MOSAIC_ATTEND_MFMA
             ? launch_attend_mfma(ctx->dv, u0, nu, q_dev, n_q_tokens, S, ctx->stream, ev0, ev1)

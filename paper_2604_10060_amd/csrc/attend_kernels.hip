@@ -9,6 +9,7 @@
 // Each workgroup keeps an online softmax in the log2 domain (logits are
 // multiplied by log2(e)/sqrt(D) once) and writes (max, sum, unnormalised O).
 #include "mosaic_internal.h"
+#include "attend_reps_device.h"
 
 namespace mosaic {
 
@@ -53,13 +54,18 @@ __device__ __forceinline__ float group16_sumf(float x) {
     return x;
 }
 
-// grid (n_units * n_splits, NT), 256 threads: thread (row = tid/16, tl = tid%16)
+// grid (n_units * n_splits [+ n_units with the global-representative augmentation], NT), 256 threads:
+// thread (row = tid/16, tl = tid%16)
 template <typename E, int D>
 __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, int n_units, const E *q,
-                                                        int Tq) {
+                                                        int Tq, int B) {
     constexpr int DPT = D / 16;   // output channels per thread
     constexpr int CG = D / 8;     // 8-element groups per token row
-    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, gridDim.x, blockIdx.x);
+    if ((int)blockIdx.x >= B) {   // extra columns: the global representatives' part (augmentation)
+        attend_reps_partial<E, D>(dv, u0, (int)blockIdx.x - B, blockIdx.y, q, Tq);
+        return;
+    }
+    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, B, blockIdx.x);
     if (slot.uc < 0) return;      // block-uniform: no barrier reached yet
     const int split = slot.split, n_splits = slot.S, tile = blockIdx.y, uc = slot.uc, u = u0 + uc;
     const int NT = gridDim.y, tid = threadIdx.x, row = tid / 16, tl = tid % 16;
@@ -234,12 +240,22 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
         float o = 0.f;
 #pragma unroll
         for (int q = 0; q < 8; ++q) o += red[q][r][col];
-        const float Lr = L_sh[r];
+        float Lr = L_sh[r], Mr = M_sh[r];
+        if (dv.aug_reps) {                            // one more partial: the representatives' part
+            const size_t ae = (size_t)u * dv.nt_max + tile;
+            const float ma = dv.aug_ml[ae * 2 * kRowTile + r], la = dv.aug_ml[ae * 2 * kRowTile + kRowTile + r];
+            const float oa = dv.aug_o[(ae * kRowTile + r) * D + dg * 32 + col];
+            const float Mn = fmaxf(Mr, ma);
+            const float wa = Mr > -INFINITY ? exp2f(Mr - Mn) : 0.f, wb = ma > -INFINITY ? exp2f(ma - Mn) : 0.f;
+            o = o * wa + oa * wb;
+            Lr = Lr * wa + la * wb;
+            Mr = Mn;
+        }
         const int gr = tile * kRowTile + r, t = gr / G, g = gr % G;
         const size_t orow = ((size_t)lc * Tq + t) * Hq + (size_t)h * G + g;
         store_out<E>(out + orow * D + dg * 32 + col, Lr > 0.f ? o / Lr : 0.f);
         if (dg == 0 && col == 0 && lse != nullptr)
-            lse[orow] = Lr > 0.f ? (M_sh[r] + log2f(Lr)) * 0.6931471805599453f : -INFINITY;
+            lse[orow] = Lr > 0.f ? (Mr + log2f(Lr)) * 0.6931471805599453f : -INFINITY;
     }
 }
 
@@ -248,13 +264,14 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
 hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                               int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
-    const dim3 grid(n_units * n_splits, NT), block(kBlock);
+    const int B = n_units * n_splits;
+    const dim3 grid(B + (dv.aug_reps ? n_units : 0), NT), block(kBlock);
     if (dv.esize == 4) {
-        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<float, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const float *)q, Tq);
-        else hipExtLaunchKernelGGL((k_attend_valu<float, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const float *)q, Tq);
+        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<float, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const float *)q, Tq, B);
+        else hipExtLaunchKernelGGL((k_attend_valu<float, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const float *)q, Tq, B);
     } else {
-        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const unsigned short *)q, Tq);
-        else hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const unsigned short *)q, Tq);
+        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const unsigned short *)q, Tq, B);
+        else hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const unsigned short *)q, Tq, B);
     }
     return hipGetLastError();
 }

@@ -17,6 +17,7 @@
 // Output:  A = V^T (row slot n = channel 16*db + n, k-slots = tokens t0 + 8g + j),
 //          D = O^T[16*db + 4g + i][n].
 #include "mosaic_internal.h"
+#include "attend_reps_device.h"
 
 namespace mosaic {
 
@@ -183,12 +184,18 @@ __device__ __forceinline__ void load_q(const DeviceView &dv, const unsigned shor
 // wave w of split s takes chunks s + S*(w + 4*i); the next chunk's operands are
 // in flight while the current one is reduced.
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, bool AUG>
 __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv, int u0, int n_units,
-                                                                  const unsigned short *q, int Tq) {
+                                                                  const unsigned short *q, int Tq, int B) {
     constexpr int KK = D / 32, DB = D / 16;
+    if constexpr (AUG) {
+        if ((int)blockIdx.x >= B) {   // extra workgroups: the global representatives' part (augmentation)
+            attend_reps_partial<unsigned short, D>(dv, u0, (int)blockIdx.x - B, 0, q, Tq);
+            return;
+        }
+    }
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
-    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, gridDim.x, blockIdx.x);
+    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, B, blockIdx.x);
     if (slot.uc < 0) return;                       // block-uniform: no barrier reached yet
     const int uc = slot.uc, u = u0 + uc, split = slot.split, S = slot.S;
     const int T = dv.T, F = dv.F, cpp = dv.chunks_per_page;
@@ -322,16 +329,24 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
 // exceeds the chip or several streams' kernels interleave -- so the group's K/V is
 // fetched from memory once and found in L2 by the rest.
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, bool AUG>
 __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv, int u0, int n_units,
                                                                    const unsigned short *q, int Tq,
-                                                                   int NT, int n_groups, int n_row_blocks) {
+                                                                   int NT, int n_groups, int n_row_blocks,
+                                                                   int group_blocks) {
     constexpr int KK = D / 32, DB = D / 16, RTW = kPrefillTiles;
     constexpr int KROW = D + 8, VROW = kChunk + 8;       // LDS row strides in elements
     constexpr int KPIECES = kChunk * D / 8, VPIECES = D * kChunk / 8;   // 16-byte pieces per chunk
     constexpr int KPT = KPIECES / kBlock, VPT = VPIECES / kBlock;       // pieces per thread
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
     // workgroup id -> (group = (unit, split) slot, row block): see the mapping above
+    if constexpr (AUG) {
+        if ((int)blockIdx.x >= group_blocks) {   // extra workgroups: the global representatives' part (augmentation)
+            const int idx = (int)blockIdx.x - group_blocks;
+            attend_reps_partial<unsigned short, D>(dv, u0, idx / NT, idx % NT, q, Tq);
+            return;
+        }
+    }
     const int xcd = (int)blockIdx.x % 8, seq = (int)blockIdx.x / 8;
     const int grp = (seq / n_row_blocks) * 8 + xcd, yb = seq % n_row_blocks;
     if (grp >= n_groups) return;                   // block-uniform: no barrier reached yet
@@ -497,14 +512,26 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
     const unsigned short *qq = (const unsigned short *)q;
     const dim3 block(kBlock);
     if (NT == 1) {
-        const dim3 grid(n_units * n_splits);
-        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_decode_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq);
-        else hipExtLaunchKernelGGL(k_attend_decode_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq);
+        const int B = n_units * n_splits;
+        const dim3 grid(B + (dv.aug_reps ? n_units : 0));
+        if (dv.aug_reps) {
+            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_decode_mfma<64, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
+            else hipExtLaunchKernelGGL((k_attend_decode_mfma<128, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
+        } else {
+            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_decode_mfma<64, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
+            else hipExtLaunchKernelGGL((k_attend_decode_mfma<128, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
+        }
     } else {
         const int n_groups = n_units * n_splits, rb = (NT + 4 * kPrefillTiles - 1) / (4 * kPrefillTiles);
-        const dim3 grid((n_groups + 7) / 8 * 8 * rb);
-        if (dv.D == 64) hipExtLaunchKernelGGL(k_attend_prefill_mfma<64>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb);
-        else hipExtLaunchKernelGGL(k_attend_prefill_mfma<128>, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb);
+        const int gb = (n_groups + 7) / 8 * 8 * rb;
+        const dim3 grid(gb + (dv.aug_reps ? n_units * NT : 0));
+        if (dv.aug_reps) {
+            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_prefill_mfma<64, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            else hipExtLaunchKernelGGL((k_attend_prefill_mfma<128, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+        } else {
+            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_prefill_mfma<64, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            else hipExtLaunchKernelGGL((k_attend_prefill_mfma<128, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+        }
     }
     return hipGetLastError();
 }

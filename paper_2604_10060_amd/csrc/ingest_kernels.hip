@@ -76,8 +76,8 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
     char *kdst_base = host ? dv.stage_k : dv.k_store;
     char *vdst_base = host ? dv.stage_v : dv.v_store;
 
+    __shared__ double red[RP][D];
     if (blockIdx.z == 0) {
-        __shared__ double red[RP][D];
         const E *src = k_in + in_page;
         E *dst = reinterpret_cast<E *>(kdst_base) + spage * (size_t)T * D;
         double acc[8];
@@ -101,11 +101,33 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
         return;
     }
 
+    // With the global-representative augmentation on, the frame's value summary (mean of
+    // its T value vectors, fp64) is formed next to the copy, like the key summary.
     const E *src = v_in + in_page;
     if (!dv.v_transposed) {
         E *dst = reinterpret_cast<E *>(vdst_base) + spage * (size_t)T * D;
-        for (int t = r0; t < T; t += RP)
+        double acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+        for (int t = r0; t < T; t += RP) {
             Elem<E>::copy8(src + (size_t)t * D + cg * 8, dst + (size_t)t * D + cg * 8);
+            if (dv.vsumm) {
+                float v[8];
+                Elem<E>::load8(src + (size_t)t * D + cg * 8, v);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] += (double)v[i];
+            }
+        }
+        if (dv.vsumm) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) red[r0][cg * 8 + i] = acc[i];
+            __syncthreads();
+            if (tid < D) {
+                double sv = 0.0;
+                for (int rr = 0; rr < RP; ++rr) sv += red[rr][tid];
+                dv.vsumm[page * D + tid] = sv / (double)T;
+            }
+        }
         return;
     }
     // Transposed, chunk-blocked value page [Tp/32][D][32] (2-byte elements only):
@@ -116,6 +138,7 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
         constexpr int TC = 64;                       // tokens per LDS tile (two chunks)
         __shared__ unsigned short tile[TC][D + 2];
         const int Tp = dv.Tp;
+        double vacc = 0.0;
         unsigned short *dst = reinterpret_cast<unsigned short *>(vdst_base) + spage * (size_t)D * Tp;
         for (int tc0 = 0; tc0 < Tp; tc0 += TC) {
             for (int t = r0; t < TC; t += RP) {
@@ -126,6 +149,10 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
                 row[0] = w.x; row[1] = w.y; row[2] = w.z; row[3] = w.w;
             }
             __syncthreads();
+            if (dv.vsumm && tid < D) {
+                const int nt = min(TC, T - tc0);     // real tokens in this tile
+                for (int t = 0; t < nt; ++t) vacc += (double)bf16_to_f32(tile[t][tid]);
+            }
             const int ntg = (min(TC, Tp - tc0)) / 8;  // token groups of 8 in this tile
             for (int id = tid; id < D * ntg; id += kBlock) {
                 const int d = id / ntg, tg = id % ntg;
@@ -140,7 +167,37 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
             }
             __syncthreads();
         }
+        if (dv.vsumm && tid < D) dv.vsumm[page * D + tid] = vacc / (double)T;
     }
+}
+
+// ---------------------------------------------------------------------------
+// Retrieval augmentation, global representatives (paper Sec. V-C): per-cluster sums
+// of the member frames' value summaries; the value of a cluster's pseudo token is
+// this sum over the cluster size.  grid (U, ceil(n_frames / 32)), 128 threads; the
+// sums are cleared by the launcher first.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(128) void k_value_reps(DeviceView dv, int n_frames) {
+    const int u = blockIdx.x, f0 = blockIdx.y * 32, tid = threadIdx.x;
+    if (tid >= D) return;
+    const int *assign = dv.assign + (size_t)u * dv.F;
+    const int f1 = min(n_frames, f0 + 32);
+    for (int f = f0; f < f1; ++f) {
+        const int a = assign[f];
+        if (a < 0) continue;
+        atomicAdd(dv.rvsum + ((size_t)u * dv.C + a) * D + tid, dv.vsumm[((size_t)u * dv.F + f) * D + tid]);
+    }
+}
+
+// fp32 pseudo-token tables from the fp64 state: key = representative, value = value sum
+// over the cluster size (zero rows for empty clusters).  grid (U, C), D threads.
+template <int D>
+__global__ __launch_bounds__(D) void k_rep_tables(DeviceView dv) {
+    const size_t row = (size_t)blockIdx.x * dv.C + blockIdx.y;
+    const int nj = dv.n[row], d = threadIdx.x;
+    dv.rep_k[row * D + d] = nj > 0 ? (float)dv.r[row * D + d] : 0.f;
+    dv.rep_v[row * D + d] = nj > 0 ? (float)(dv.rvsum[row * D + d] / (double)nj) : 0.f;
 }
 
 // ---------------------------------------------------------------------------
@@ -530,6 +587,21 @@ hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const vo
             if (dv.D == 64) k_store_summary<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f0);
             else k_store_summary<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f0);
         }
+    });
+}
+
+hipError_t launch_value_reps(const DeviceView &dv, int n_frames, hipStream_t s) {
+    hipError_t e = hipMemsetAsync(dv.rvsum, 0, (size_t)dv.U * dv.C * dv.D * 8, s);
+    if (e != hipSuccess || n_frames <= 0) return e;
+    const dim3 grid(dv.U, (n_frames + 31) / 32);
+    e = checked([&] {
+        if (dv.D == 64) k_value_reps<64><<<grid, 128, 0, s>>>(dv, n_frames);
+        else k_value_reps<128><<<grid, 128, 0, s>>>(dv, n_frames);
+    });
+    if (e != hipSuccess) return e;
+    return checked([&] {
+        if (dv.D == 64) k_rep_tables<64><<<dim3(dv.U, dv.C), 64, 0, s>>>(dv);
+        else k_rep_tables<128><<<dim3(dv.U, dv.C), 128, 0, s>>>(dv);
     });
 }
 

@@ -70,6 +70,13 @@ struct DeviceView {
     long long *mt_cnt;// [U][4]      splits on insertion, deferred splits, buffered inserts, forced absorbs
     int *mt_mem, *mt_side;   // [U][F] scratch of Split
     double *mt_nrm;          // [U][F]
+    // retrieval augmentation (paper Sec. V-C); both 0 = off
+    int aug_reps, aug_window, nt_max;
+    double *vsumm;    // [U][F][D]   per-frame value summaries (mean of the frame's T value vectors)
+    double *rvsum;    // [U][C][D]   per-cluster sums of them (value representative = rvsum / n)
+    float *rep_k, *rep_v;   // [U][C][D] fp32 pseudo-token tables: representative, value representative
+    float *aug_o;     // [U][nt_max][16][D]  partial of the representatives' part, same form as part_o
+    float *aug_ml;    // [U][nt_max][2][16]
     // latest selection per unit
     double *scores;   // [U][SC]
     int *ids;         // [U][k]
@@ -97,6 +104,7 @@ struct Ctx {
     std::vector<long long> sel_epoch; // per layer: epoch at which the selection was made
     std::vector<int> sel_tq;
     long long epoch;     // bumped by ingest and reset
+    long long rv_epoch;  // epoch the value representatives were last computed at
     mosaic_stats stats;
     std::string err;
     HostTier *host;      // non-null in the host tier
@@ -138,6 +146,9 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
                               int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
                                  void *out, float *lse, hipStream_t s);
+// retrieval augmentation: per-cluster value sums of all units (after the clustering changed); the
+// attention partial over the representatives is computed by extra workgroups of the attention launches
+hipError_t launch_value_reps(const DeviceView &dv, int n_frames, hipStream_t s);
 
 // ---- small device helpers ----
 __device__ __forceinline__ const char *k_page(const DeviceView &dv, int u, int p) {

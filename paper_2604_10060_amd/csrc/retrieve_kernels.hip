@@ -49,6 +49,7 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     __shared__ int n_sh[1024];
     __shared__ int rank_sh[1024];   // selection rank of cluster j, or -1
     __shared__ int cnt_sh[1024];
+    __shared__ int wcnt_sh[1024];   // members inside the local window
     __shared__ int ids_sh[1024];
     __shared__ int off_sh[1025];
     __shared__ int n_live_sh;
@@ -67,8 +68,14 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         fa[i] = in ? assign[f] : -1;
         fp[i] = in ? pos[f] : 0;
     }
-    for (int j = tid; j < C; j += BLK) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; cnt_sh[j] = 0; }
+    for (int j = tid; j < C; j += BLK) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; cnt_sh[j] = 0; wcnt_sh[j] = 0; }
     if (tid == 0) n_live_sh = 0;
+    // local-window augmentation (Sec. V-C): the w most recent frames are listed once, after the
+    // clusters; they are the last members of their clusters (ranks ascend with the frame id), so
+    // a cluster's list is simply cut short by its number of window members
+    const int w0 = write_pages && dv.aug_window > 0 ? max(0, n_frames - dv.aug_window) : n_frames;
+    int wa = -1;
+    if (w0 + tid < n_frames) wa = assign[w0 + tid];          // aug_window <= 1024 (checked at create)
     // representative rows of the first RPF passes (row index clamped, loads unconditional)
     double rpre[RPF][EPL];
 #pragma unroll
@@ -98,6 +105,7 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         qpart[part][d] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     }
     __syncthreads();
+    if (wa >= 0) atomicAdd(&wcnt_sh[wa], 1);
     if (tid < D) {
         double acc = 0.0;
 #pragma unroll
@@ -170,9 +178,9 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     if (tid == 0) {
         int o = 0;
         off_sh[0] = 0;
-        for (int i = 0; i < n_ids; ++i) { o += n_sh[ids_sh[i]]; off_sh[i + 1] = o; }
+        for (int i = 0; i < n_ids; ++i) { o += n_sh[ids_sh[i]] - wcnt_sh[ids_sh[i]]; off_sh[i + 1] = o; }
         dv.n_ids[u] = n_ids;
-        if (write_pages) dv.n_sel[u] = o;
+        if (write_pages) dv.n_sel[u] = o + (n_frames - w0);
     }
     for (int i = tid; i < k; i += BLK) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
     __syncthreads();
@@ -181,16 +189,18 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     int *sel = dv.sel_pages + (size_t)u * dv.F;
 #pragma unroll
     for (int i = 0; i < FPT; ++i) {
-        if (fa[i] < 0) continue;
+        if (fa[i] < 0 || tid + BLK * i >= w0) continue;
         const int rk = rank_sh[fa[i]];
         if (rk >= 0) sel[off_sh[rk] + fp[i]] = tid + BLK * i;
     }
-    for (int f = tid + BLK * FPT; f < n_frames; f += BLK) {
+    for (int f = tid + BLK * FPT; f < w0; f += BLK) {
         const int c = assign[f];
         if (c < 0) continue;
         const int rk = rank_sh[c];
         if (rk >= 0) sel[off_sh[rk] + pos[f]] = f;
     }
+    const int n_ids_f = min(k, n_live_sh);
+    if (w0 + tid < n_frames) sel[off_sh[n_ids_f] + tid] = w0 + tid;      // the local window, ascending
 }
 
 // ---------------------------------------------------------------------------

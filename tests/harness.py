@@ -356,3 +356,79 @@ def query_maintained_with_parity(m, wl, q, oracles, K, V, rep, mt):
         assert err <= OUT_TOL[wl.kv_dtype], f"unit {(l, h)}: attention max-abs err {err:.3e}"
         assert lerr <= LSE_TOL[wl.kv_dtype], f"unit {(l, h)}: lse max-abs err {lerr:.3e}"
     return out, lse
+
+
+# ---------------------------------------------------------------------------
+# Retrieval augmentation (paper Sec. V-C)
+# ---------------------------------------------------------------------------
+def query_augmented_with_parity(m, wl, q, oracles, K, V, rep, window_frames, global_reps):
+    """Retrieve + attend with the augmentation on: selection as in the plain path; the token list
+    must be the retrieved clusters without their window frames followed by the window; the output
+    must be one softmax over those tokens and the clusters' pseudo tokens."""
+    L, G = wl.n_layers, wl.group
+    outs, lses = [], []
+    for l in range(L):
+        m.retrieve(l, q[l].contiguous())
+        o_, l_ = m.attend(l, q[l].contiguous())
+        outs.append(o_); lses.append(l_)
+    out, lse = torch.stack(outs), torch.stack(lses)
+    torch.cuda.synchronize()
+    out_h = out.float().cpu().numpy().astype(np.float64)
+    lse_h = lse.cpu().numpy().astype(np.float64)
+    q_h = q.float().cpu().numpy().astype(np.float64)
+    sel_cache = {}
+    for (l, h), o in oracles.items():
+        if l not in sel_cache:
+            sel_cache[l] = m.selection(l)
+        ids, n_ids, scores, toks = sel_cache[l]
+        ids_o, sc_o, _, gap = o.retrieve(q_h[l], h, G, wl.top_k)
+        np.testing.assert_array_equal(ids[h, : n_ids[h]], ids_o)
+        Ku = inputs.unit_pages(K, l, h)
+        Vu = inputs.unit_pages(V, l, h)
+        tok_o, Kx, Vx = orc.augmented_context(o, Ku, Vu, ids_o, window_frames, global_reps)
+        n_real = int((tok_o < o.n_frames * wl.tokens_per_frame).sum())
+        np.testing.assert_array_equal(toks[h], tok_o[:n_real])
+        want, want_lse = orc.attend(q_h[l], Kx, Vx, tok_o, h, G)
+        err = np.abs(out_h[l][:, h * G:(h + 1) * G, :] - want).max()
+        lerr = np.abs(lse_h[l][:, h * G:(h + 1) * G] - want_lse).max()
+        rep.max_out_err = max(rep.max_out_err, float(err))
+        rep.max_lse_err = max(rep.max_lse_err, float(lerr))
+        assert err <= OUT_TOL[wl.kv_dtype], f"unit {(l, h)}: augmented attention max-abs err {err:.3e}"
+        assert lerr <= LSE_TOL[wl.kv_dtype], f"unit {(l, h)}: augmented lse max-abs err {lerr:.3e}"
+    return out, lse
+
+
+def run_augmented(wl, window_frames, global_reps, units=None, device="cuda:0", decode_steps=2,
+                  ingest_between=True, **cfg_overrides):
+    """Plain ingest parity, then questions with the augmentation on; with ingest_between the stream
+    is ingested in two halves with queries after each (the representatives' values must follow)."""
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    Kd, Vd = K.to(device), V.to(device)
+    m = binding.Mosaic(binding.config_for(wl, aug_global_reps=int(global_reps), aug_window_frames=window_frames,
+                                          **cfg_overrides), device=device)
+    rep = Report()
+    if units is None:
+        units = [(l, h) for l in range(wl.n_layers) for h in range(wl.n_kv_heads)]
+    F = wl.n_frames
+    cut = max(wl.warmup + 8, F // 2) if ingest_between else F
+    oracles = {key: orc.OracleUnit(wl.n_clusters, wl.head_dim, wl.tokens_per_frame, F, wl.warmup_frames,
+                                   wl.lloyd_iters, wl.recluster_every) for key in units}
+    Kcpu = {key: inputs.unit_pages(K, *key) for key in units}
+    tag = 0
+    f = 0
+    for end in ([cut, F] if cut < F else [F]):
+        m.ingest_frame(Kd[f:end].contiguous(), Vd[f:end].contiguous())
+        for key, o in oracles.items():
+            for ff in range(f, end):
+                o.ingest(Kcpu[key][ff])
+        f = end
+        A = m.assignments()
+        for (l, h), o in oracles.items():
+            np.testing.assert_array_equal(A[l * wl.n_kv_heads + h, :f], o.assignments())
+        for n_tok in [wl.question_tokens] + [1] * decode_steps:
+            q = st.question(st.draw_scene(), n_tok, tag).to(device)
+            tag += 1
+            query_augmented_with_parity(m, wl, q, oracles, K[:f], V[:f], rep, window_frames, global_reps)
+    m.close()
+    return rep

@@ -383,3 +383,41 @@ def test_maintainer_config_errors():
     with pytest.raises(binding.MosaicError):
         m.maintainer()
     m.close()
+
+
+# ---------------------------------------------------------------------------
+# Retrieval augmentation (paper Sec. V-C)
+# ---------------------------------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("window,reps", [(6, False), (0, True), (9, True)])
+def test_augmentation_fp32(window, reps):
+    rep = harness.run_augmented(inputs.CONFIGS[0], window, reps)
+    assert rep.max_out_err <= 1e-4
+
+
+@pytest.mark.gpu
+def test_augmentation_bf16_mfma_decode_and_question():
+    wl = inputs.CONFIGS[1].scaled(name="aug_bf16", n_frames=160, n_scenes=10, n_clusters=12, top_k=3,
+                                  question_tokens=37)
+    rep = harness.run_augmented(wl, 5, True, units=[(0, 0), (0, 3)], decode_steps=3)
+    assert rep.max_out_err <= 2e-2
+
+
+@pytest.mark.gpu
+def test_augmentation_window_larger_than_stream_and_recluster():
+    """Window >= frames ingested: nothing comes from the clusters; with re-clustering on, the
+    representatives' values follow the changed membership."""
+    wl = inputs.CONFIGS[0].scaled(name="aug_recluster", recluster_every=48)
+    rep = harness.run_augmented(wl, 1000, True)
+    assert rep.max_out_err <= 1e-4
+
+
+@pytest.mark.gpu
+def test_augmentation_config_errors():
+    wl = inputs.CONFIGS[0]
+    for bad in (dict(aug_global_reps=2), dict(aug_window_frames=-1), dict(aug_window_frames=2000),
+                dict(aug_window_frames=4, tier=binding.TIER_HOST),
+                dict(aug_global_reps=1, maint_mode=binding.MAINT_DEFERRED, init_clusters=4, tau_n0=8.0)):
+        with pytest.raises(binding.MosaicError) as ei:
+            binding.workspace_sizes(binding.config_for(wl, **bad))
+        assert ei.value.code == binding.EINVAL

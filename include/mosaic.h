@@ -143,6 +143,10 @@ typedef struct {
     double h2d_busy_ms;                 /* time of those fetch kernels (event pairs around each launch while
                                            mosaic_profile_enable is on; filled by mosaic_get_stats, which
                                            synchronises) */
+    /* cross-layer prefetch (host tier) */
+    int64_t prefetch_calls;             /* mosaic_prefetch calls */
+    int64_t prefetch_fetched;           /* clusters a prefetch had to bring into the GPU cache */
+    int64_t prefetch_useful;            /* of those, clusters that the layer's retrieval then selected */
     /* maintainer, summed over the units (filled by mosaic_get_stats, which synchronises) */
     int64_t splits_immediate;           /* invalid clusters split on insertion */
     int64_t splits_deferred;            /* deferred splits carried out at retrieval */
@@ -200,6 +204,19 @@ int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_de
  * ECAPACITY if the selection does not fit the cache. */
 int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
                         int32_t n_q_tokens);
+
+/* Overlap-aware prefetch (paper Sec. VII-B), host tier only.  While layer l is being computed,
+ * its query q^(l) serves as a proxy for the next layer's: the call selects the top-k clusters of
+ * `layer` (= l + 1) with q_proxy_dev -- same shape and dtype as mosaic_retrieve's q_dev, one layer --
+ * and starts fetching those that are not in the GPU cluster cache, asynchronously on the library's
+ * copy stream, so that the transfer overlaps whatever the caller enqueues next (layer l's
+ * attention).  It does not make a selection: the later mosaic_retrieve(layer, q^(l+1)) verifies the
+ * prediction against the actual query and fetches whatever is still missing (the completion
+ * step); results never depend on whether, or with which proxy, mosaic_prefetch was called.
+ * Contains the same short host wait as the host tier's mosaic_retrieve (read-back of k ids).
+ * Errors: EINVAL (not the host tier, layer < 0, NULL, n_q_tokens out of range); ENOTREADY;
+ * ECAPACITY if the predicted clusters do not fit the cache. */
+int32_t mosaic_prefetch(mosaic_ctx *ctx, int32_t layer, const void *q_proxy_dev, int32_t n_q_tokens);
 
 /* Query Retrieval, attention part (Sec. V-A (2)): softmax(q K^T/sqrt(D)) V over
  * the tokens of the clusters chosen by the latest mosaic_retrieve for `layer`

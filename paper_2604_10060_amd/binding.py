@@ -25,7 +25,7 @@ _STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ECAPACITY", -4: "ENOTREADY"
 
 EXPORTS = (
     "mosaic_workspace_size", "mosaic_create", "mosaic_destroy", "mosaic_reset",
-    "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_attend",
+    "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_prefetch", "mosaic_attend",
     "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries", "mosaic_get_maintainer",
     "mosaic_get_selection", "mosaic_get_stats", "mosaic_profile_enable",
     "mosaic_profile_read", "mosaic_calibration_copy", "mosaic_last_error",
@@ -65,6 +65,7 @@ class Stats(C.Structure):
         ("last_n_splits", C.c_int32), ("reserved", C.c_int32),
         ("cache_hits", C.c_int64), ("cache_misses", C.c_int64),
         ("h2d_bytes", C.c_int64), ("h2d_copies", C.c_int64), ("h2d_busy_ms", C.c_double),
+        ("prefetch_calls", C.c_int64), ("prefetch_fetched", C.c_int64), ("prefetch_useful", C.c_int64),
         ("splits_immediate", C.c_int64), ("splits_deferred", C.c_int64),
         ("deferred_inserts", C.c_int64), ("forced_absorbs", C.c_int64),
     ]
@@ -91,6 +92,7 @@ def load_library():
     L.mosaic_ingest_frame.argtypes = [vp, vp, vp, i32]
     L.mosaic_retrieve.argtypes = [vp, i32, vp, i32]
     L.mosaic_attend.argtypes = [vp, i32, vp, i32, vp, vp]
+    L.mosaic_prefetch.argtypes = [vp, i32, vp, i32]
     L.mosaic_get_assignments.argtypes = [vp, vp]
     L.mosaic_get_centroids.argtypes = [vp, vp, vp]
     L.mosaic_get_summaries.argtypes = [vp, vp]
@@ -228,6 +230,17 @@ class Mosaic:
         shape, tq = self._q_shape(layer, q)
         self._check_tensor(q, shape, "q")
         self._check(self._L.mosaic_retrieve(self._h, layer, _ptr(q), tq))
+
+    def prefetch(self, layer: int, q_proxy):
+        """Host tier: predict `layer`'s clusters with a proxy query [Tq][Hq][D] and start fetching them."""
+        shape, tq = self._q_shape(max(layer, 0), q_proxy)
+        self._check_tensor(q_proxy, shape, "q_proxy")
+        self._check(self._L.mosaic_prefetch(self._h, layer, _ptr(q_proxy), tq))
+
+    def prefetch_raw(self, layer: int, q_ptr: int, n_q_tokens: int):
+        rc = self._L.mosaic_prefetch(self._h, layer, q_ptr, n_q_tokens)
+        if rc != OK:
+            self._check(rc)
 
     def attend(self, layer: int, q, out=None, lse=None):
         torch = self._torch

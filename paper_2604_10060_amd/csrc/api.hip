@@ -442,6 +442,7 @@ int32_t mosaic_reset(mosaic_ctx *ctx) {
         (void)hipStreamSynchronize(ht->copy_stream);
         ht->reset();
         ht->hits = ht->misses = ht->evictions = ht->h2d_bytes = ht->h2d_copies = 0;
+        ht->pf_calls = ht->pf_fetched = ht->pf_useful = 0;
         ht->busy_ms = 0.0;
         for (hipEvent_t e : ht->busy_ev) (void)hipEventDestroy(e);
         ht->busy_ev.clear();
@@ -597,7 +598,7 @@ static int check_query_args(mosaic_ctx *ctx, int32_t layer, const void *q_dev, i
 }
 
 // Host tier: selection on the selection stream, LRU + fetches on the copy stream.
-static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq) {
+static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq, bool prefetch) {
     const DeviceView &dv = ctx->dv;
     HostTier *ht = ctx->host;
     const int u0 = layer * dv.Hkv, nu = dv.Hkv, k = dv.k;
@@ -631,7 +632,7 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq) 
     for (int i = 0; i < nu; ++i) {
         const int u = u0 + i;
         pages.clear(); moves.clear();
-        const int rc = ht->fetch(u, ids + (size_t)i * k, nids[i], moves, pages);
+        const int rc = ht->fetch(u, ids + (size_t)i * k, nids[i], moves, pages, prefetch);
         if (rc != MOSAIC_OK) {
             char b[256];
             snprintf(b, sizeof b, "the selected clusters do not fit the GPU cluster cache: unit %d selects %d pages "
@@ -640,7 +641,7 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq) 
                      ht->fail_free, ht->fail_cached);
             return fail(ctx, rc, b);
         }
-        ht->last_ids[u].assign(ids + (size_t)i * k, ids + (size_t)i * k + nids[i]);
+        if (!prefetch) ht->last_ids[u].assign(ids + (size_t)i * k, ids + (size_t)i * k + nids[i]);
         std::copy(moves.begin(), moves.end(), ctx->h_moves + (size_t)u * dv.F * 2);
         ctx->h_nmoves[u] = (int)moves.size() / 2;
         max_moves = std::max(max_moves, (int)moves.size() / 2);
@@ -671,7 +672,7 @@ int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32
     if (ctx->n_frames < ctx->W) return fail(ctx, MOSAIC_ENOTREADY, "initial clustering has not run yet (fewer than warmup_frames frames ingested)");
     if (ctx->host) {
         if (layer < 0) return fail(ctx, MOSAIC_EINVAL, "the host tier retrieves one layer per call");
-        rc = retrieve_host(ctx, layer, q_dev, n_q_tokens);
+        rc = retrieve_host(ctx, layer, q_dev, n_q_tokens, false);
         if (rc != MOSAIC_OK) return rc;
         ctx->sel_epoch[layer] = ctx->epoch; ctx->sel_tq[layer] = n_q_tokens;
         ctx->stats.retrieve_calls += 1;
@@ -686,6 +687,21 @@ int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32
     const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? ctx->dv.L : layer + 1;
     for (int l = l0; l < l1; ++l) { ctx->sel_epoch[l] = ctx->epoch; ctx->sel_tq[l] = n_q_tokens; }
     ctx->stats.retrieve_calls += 1;
+    return MOSAIC_OK;
+}
+
+int32_t mosaic_prefetch(mosaic_ctx *ctx, int32_t layer, const void *q_proxy_dev, int32_t n_q_tokens) {
+    if (!ctx) return MOSAIC_EINVAL;
+    if (!ctx->host) return fail(ctx, MOSAIC_EINVAL, "mosaic_prefetch needs the host tier (MOSAIC_TIER_HOST)");
+    if (layer < 0) return fail(ctx, MOSAIC_EINVAL, "mosaic_prefetch takes one layer per call");
+    int u0, nu;
+    int rc = check_query_args(ctx, layer, q_proxy_dev, n_q_tokens, &u0, &nu);
+    if (rc != MOSAIC_OK) return rc;
+    if (ctx->n_frames < ctx->W) return fail(ctx, MOSAIC_ENOTREADY, "initial clustering has not run yet (fewer than warmup_frames frames ingested)");
+    rc = retrieve_host(ctx, layer, q_proxy_dev, n_q_tokens, true);
+    if (rc != MOSAIC_OK) return rc;
+    ctx->sel_epoch[layer] = -1;          // a prediction is not a selection: attend needs mosaic_retrieve
+    ctx->host->pf_calls += 1;
     return MOSAIC_OK;
 }
 
@@ -883,6 +899,8 @@ int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats) {
         ctx->stats.cache_hits = ht->hits; ctx->stats.cache_misses = ht->misses;
         ctx->stats.h2d_bytes = ht->h2d_bytes; ctx->stats.h2d_copies = ht->h2d_copies;
         ctx->stats.h2d_busy_ms = ht->busy_ms;
+        ctx->stats.prefetch_calls = ht->pf_calls; ctx->stats.prefetch_fetched = ht->pf_fetched;
+        ctx->stats.prefetch_useful = ht->pf_useful;
     }
     if (ctx->dv.maint_mode) {
         const DeviceView &dv = ctx->dv;

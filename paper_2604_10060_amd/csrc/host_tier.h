@@ -12,6 +12,7 @@ struct HostTier {
         int pages = 0;             // frames of the cluster that are resident
         long long stamp = 0;       // last use (LRU)
         bool present = false;
+        bool by_prefetch = false;  // brought in (or completed) by a prefetch and not used by a retrieval yet
     };
     struct Unit {
         std::vector<std::vector<int>> slabs;    // per cluster: its host slabs in arrival order
@@ -28,6 +29,8 @@ struct HostTier {
     long long clock = 0;
     int fail_need = 0, fail_free = 0, fail_cached = 0, fail_sel_pages = 0;   // context of the last ECAPACITY
     long long hits = 0, misses = 0, evictions = 0, h2d_bytes = 0, h2d_copies = 0;
+    // cross-layer prefetch: clusters a prefetch had to fetch, and how many of them a retrieval then used
+    long long pf_calls = 0, pf_fetched = 0, pf_useful = 0;
     // streams and events owned by the context
     hipStream_t sel_stream = nullptr;    // selection kernel + read-back of the ids
     hipStream_t copy_stream = nullptr;   // fetch kernel, page-list upload, `ready` events
@@ -43,7 +46,8 @@ struct HostTier {
               size_t kpage, size_t vpage);
     void reset();
     int append(int u, int f, int c);
-    int fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, std::vector<int> &pages);
+    int fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, std::vector<int> &pages,
+              bool prefetch = false);
 };
 
 } // namespace mosaic

@@ -53,6 +53,8 @@ int HostTier::append(int u, int f, int c) {
     return un.slabs[c].back() * SF + slot;
 }
 
+// (With `prefetch` the ids are a prediction for a coming layer, see mosaic_prefetch: the same
+// cache work, counted apart.)
 // Make clusters ids[0..n_ids) of unit u resident: decide what must move (LRU at
 // cluster granularity), append the moves as (host page, cache page) pairs to
 // `moves`, and append the cache pages of the selection, in gather order, to
@@ -60,7 +62,8 @@ int HostTier::append(int u, int f, int c) {
 // that reads the pinned slabs directly over PCIe (measured at the rate of a
 // large DMA copy, without a per-copy API cost).  Returns MOSAIC_OK or
 // MOSAIC_ECAPACITY.
-int HostTier::fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, std::vector<int> &pages) {
+int HostTier::fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, std::vector<int> &pages,
+                    bool prefetch) {
     Unit &un = units[u];
     std::vector<char> pinned(C, 0);
     for (int i = 0; i < n_ids; ++i) pinned[ids[i]] = 1;
@@ -69,7 +72,13 @@ int HostTier::fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, s
         Entry &e = un.cache[c];
         const int have = e.present ? e.pages : 0;
         const int want = un.n[c];
-        if (e.present && have == want) hits += 1; else misses += 1;
+        const bool complete = e.present && have == want;
+        if (prefetch) {                      // a guess for a coming layer: not a retrieval's hit or miss
+            if (!complete) { pf_fetched += 1; e.by_prefetch = true; }
+        } else {
+            if (complete) { hits += 1; if (e.by_prefetch) pf_useful += 1; } else misses += 1;
+            e.by_prefetch = false;
+        }
         const int need_blocks = (want + SF - 1) / SF;
         // room: enough free blocks, and not more resident clusters than allowed
         while ((int)un.free_blocks.size() < need_blocks - (int)e.blocks.size() ||
@@ -86,7 +95,7 @@ int HostTier::fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, s
             }
             Entry &v = un.cache[victim];
             for (int b : v.blocks) un.free_blocks.push_back(b);
-            v.blocks.clear(); v.pages = 0; v.present = false;
+            v.blocks.clear(); v.pages = 0; v.present = false; v.by_prefetch = false;
             un.n_cached -= 1;
             evictions += 1;
         }

@@ -55,6 +55,7 @@ class Workload:
     noise: float = 0.3
     drift: float = 0.05
     outlier_frac: float = 0.0
+    layer_corr: float = 0.0       # correlation of adjacent layers' scene centres and question noise (0 = independent)
     warmup_frames: int = 0        # 0 -> 2 * n_clusters
     lloyd_iters: int = 8
     recluster_every: int = 0
@@ -165,6 +166,13 @@ class SceneStream:
                                  dtype=torch.float32)
         self.centre_k = rn()
         self.centre_v = rn()
+        if wl.layer_corr > 0.0:
+            # adjacent layers see similar states (residual connections, paper Sec. VII-B): an AR(1)
+            # chain over the layer index with unit variance, built from the same draws
+            rho, mix = float(wl.layer_corr), float(np.sqrt(1.0 - wl.layer_corr ** 2))
+            for c in (self.centre_k, self.centre_v):
+                for l in range(1, wl.n_layers):
+                    c[:, l] = rho * c[:, l - 1] + mix * c[:, l]
         inv = 1.0 / float(np.sqrt(wl.head_dim))
         self.drift_k = rn() * inv
         self.drift_v = rn() * inv
@@ -217,6 +225,10 @@ class SceneStream:
         c = c.repeat_interleave(wl.group, dim=1)                   # [L][Hq][D]
         x = torch.randn((wl.n_layers, n_tokens, wl.n_q_heads, wl.head_dim),
                         generator=g, device=self.device, dtype=torch.float32)
+        if wl.layer_corr > 0.0:
+            rho, mix = float(wl.layer_corr), float(np.sqrt(1.0 - wl.layer_corr ** 2))
+            for l in range(1, wl.n_layers):
+                x[l] = rho * x[l - 1] + mix * x[l]
         q = c.unsqueeze(1) + 0.5 * x
         return q.to(wl.torch_dtype)
 

@@ -421,3 +421,75 @@ def test_augmentation_config_errors():
         with pytest.raises(binding.MosaicError) as ei:
             binding.workspace_sizes(binding.config_for(wl, **bad))
         assert ei.value.code == binding.EINVAL
+
+
+# ---------------------------------------------------------------------------
+# Overlap-aware cross-layer prefetch (paper Sec. VII-B), host tier
+# ---------------------------------------------------------------------------
+@pytest.mark.gpu
+def test_prefetch_never_changes_results_and_perfect_proxy_covers_everything():
+    """Layer l's query predicts layer l+1's clusters.  Results must be bitwise those of the run
+    without prefetch, whatever the proxy; with the actual next-layer query as the 'proxy' every
+    cluster the retrieval selects has been prefetched (no completion fetch), with an unrelated
+    proxy the completion step fetches the rest."""
+    wl = _small(n_layers=3, n_frames=160, n_clusters=10, top_k=3)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    qs = [st.question(st.draw_scene(), 1, i).to(DEV) for i in range(5)]
+    unrelated = [st.question(st.draw_scene(), 1, 100 + i).to(DEV) for i in range(5)]
+
+    def run(mode):
+        m = _ingest_all(wl, K, V, (16,), **HOST)
+        res = []
+        for qi, q in enumerate(qs):
+            o = torch.empty_like(q)
+            l = torch.empty(q.shape[:-1], dtype=torch.float32, device=DEV)
+            for layer in range(wl.n_layers):
+                m.retrieve(layer, q[layer].contiguous())
+                if layer + 1 < wl.n_layers and mode != "none":
+                    proxy = q[layer + 1] if mode == "perfect" else unrelated[qi][layer]
+                    m.prefetch(layer + 1, proxy.contiguous())
+                m.attend(layer, q[layer].contiguous(), o[layer], l[layer])
+            torch.cuda.synchronize()
+            res.append((o.clone(), l.clone()))
+        s = m.stats()
+        m.close()
+        return res, s
+
+    base, s0 = run("none")
+    perfect, s1 = run("perfect")
+    wrong, s2 = run("unrelated")
+    for a, b, c in zip(base, perfect, wrong):
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+        assert torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
+    assert s0.prefetch_calls == 0 and s1.prefetch_calls == 2 * len(qs) == s2.prefetch_calls
+    # retrievals of layers 1.. found everything in the cache; only layer 0 (never predicted) misses
+    per_call = wl.n_kv_heads * wl.top_k
+    assert s1.prefetch_fetched > 0 and s1.prefetch_useful == s1.prefetch_fetched
+    assert s1.cache_misses <= len(qs) * per_call and s1.cache_misses < s0.cache_misses
+    assert s2.prefetch_useful <= s2.prefetch_fetched and s2.cache_misses > s1.cache_misses
+    assert s1.cache_hits + s1.cache_misses == s0.cache_hits + s0.cache_misses == len(qs) * wl.n_layers * per_call
+
+
+@pytest.mark.gpu
+def test_prefetch_errors():
+    wl = _small(n_frames=96)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    q = st.question(st.draw_scene(), 1, 0).to(DEV)
+    m = _ingest_all(wl, K, V, (16,))                     # HBM tier: nothing to prefetch
+    with pytest.raises(binding.MosaicError) as ei:
+        m.prefetch(0, q[0].contiguous())
+    assert ei.value.code == binding.EINVAL
+    m.close()
+    m = _ingest_all(wl, K, V, (16,), **HOST)
+    m.prefetch(0, q[0].contiguous())
+    with pytest.raises(binding.MosaicError) as ei:       # a prediction is not a selection
+        m.attend(0, q[0].contiguous())
+    assert ei.value.code == binding.ENOTREADY
+    with pytest.raises(binding.MosaicError) as ei:
+        m._check(m._L.mosaic_prefetch(m._h, -1, q.data_ptr(), 1))
+    assert ei.value.code == binding.EINVAL
+    m.retrieve(0, q[0].contiguous()); m.attend(0, q[0].contiguous())
+    torch.cuda.synchronize()
+    m.close()

@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "maintainer"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "maintainer", "prefetch"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count")
     ap.add_argument("--all-layers-call", action="store_true",
@@ -492,6 +492,89 @@ def run_maintainer_leg(layers=4, query_every=64, decode=64, check=True):
             "split_reduction_by_deferral": round(1.0 - tot_d / tot_e, 4) if tot_e else None}
 
 
+def run_prefetch_leg(layers=3, steps=96, rhos=(0.95, 0.7)):
+    """Overlap-aware cross-layer prefetch (Sec. VII-B) on the config-3 host tier, `layers` of its 28
+    layers, with adjacent layers' states correlated by rho (the stream generator's stand-in for the
+    similarity that residual connections give real models).  Per decode step and layer l:
+      sequential   retrieve(l, q_l); attend(l)                      -- every fetch is on the critical path
+      proxy        retrieve(l, q_l); prefetch(l+1, q_l); attend(l)  -- the paper's scheme
+      lookahead    retrieve(l+1, q_{l+1}) before attend(l)          -- needs q_{l+1} early: an upper bound
+    4 topics, steps/4 consecutive steps each.  Reports step latencies and how much of what the
+    retrievals needed had been prefetched."""
+    import torch
+    from paper_2604_10060_amd import binding, inputs
+    dev = "cuda:0"
+    out_all = {}
+    for rho in rhos:
+        wl = inputs.CONFIGS[3].scaled(n_layers=layers, layer_corr=rho)
+        L, Hq, D, T, F = wl.n_layers, wl.n_q_heads, wl.head_dim, wl.tokens_per_frame, wl.n_frames
+        st = inputs.SceneStream(wl, device=dev)
+        topics = [st.draw_scene() for _ in range(4)]
+        per_topic = steps // 4
+        qs = torch.stack([st.question(topics[i // per_topic], 1, 1 + i) for i in range(steps)])   # [n][L][1][Hq][D]
+        out = torch.empty((L, 1, Hq, D), dtype=wl.torch_dtype, device=dev)
+        lse = torch.empty((L, 1, Hq), dtype=torch.float32, device=dev)
+        lq = Hq * D * 2
+        res = {}
+        for mode in ("sequential", "proxy", "proxy_top8", "lookahead"):
+            m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
+                                                  cache_pages_per_unit=F + 52 * 16,
+                                                  prefetch_top_k=8 if mode == "proxy_top8" else 0), device=dev)
+            for f0 in range(0, F, 256):
+                K, V = st.frames(f0, min(F, f0 + 256))
+                for b in range(0, K.shape[0], 64):
+                    m.ingest_frame(K[b:b + 64], V[b:b + 64])
+            torch.cuda.synchronize()
+
+            def step(i):
+                qp = qs.data_ptr() + i * L * lq
+                op, lp = out.data_ptr(), lse.data_ptr()
+                if mode == "lookahead":
+                    m.retrieve_raw(0, qp, 1)
+                for l in range(L):
+                    if mode == "lookahead":
+                        if l + 1 < L:
+                            m.retrieve_raw(l + 1, qp + (l + 1) * lq, 1)
+                    else:
+                        m.retrieve_raw(l, qp + l * lq, 1)
+                        if mode.startswith("proxy") and l + 1 < L:
+                            m.prefetch_raw(l + 1, qp + l * lq, 1)
+                    m.attend_raw(l, qp + l * lq, 1, op + l * lq, lp + l * Hq * 4)
+
+            lat = []
+            for i in range(steps):
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                step(i)
+                torch.cuda.synchronize()
+                lat.append((time.perf_counter() - t) * 1e6)
+            s = m.stats()
+            lat = np.array(lat)
+            cold = lat[::per_topic]
+            warm = np.delete(lat, np.arange(0, steps, per_topic))
+            res[mode] = {"step_us_warm_median": round(float(np.median(warm)), 1),
+                         "step_us_warm_mean": round(float(warm.mean()), 1),
+                         "step_us_topic_switch_mean": round(float(cold.mean()), 1),
+                         "cache_hits": int(s.cache_hits), "cache_misses": int(s.cache_misses),
+                         "prefetch_fetched": int(s.prefetch_fetched), "prefetch_useful": int(s.prefetch_useful),
+                         "h2d_gb": round(s.h2d_bytes / 1e9, 2)}
+            m.close()
+            del m
+            torch.cuda.empty_cache()
+        q_ = res["sequential"]
+        for name in ("proxy", "proxy_top8"):
+            p = res[name]
+            # of the clusters the retrievals needed from the host, the share that had arrived by prefetch
+            p["share_of_fetches_prefetched"] = round(p["prefetch_useful"] / max(p["prefetch_useful"] + p["cache_misses"], 1), 4)
+            p["prefetch_precision"] = round(p["prefetch_useful"] / max(p["prefetch_fetched"], 1), 4)
+            p["warm_step_change_vs_sequential"] = round(p["step_us_warm_mean"] / q_["step_us_warm_mean"] - 1.0, 4)
+            p["topic_switch_change_vs_sequential"] = round(p["step_us_topic_switch_mean"] / q_["step_us_topic_switch_mean"] - 1.0, 4)
+        out_all["rho_%.2f" % rho] = res
+    return {"config": {"workload": "cfg3_host_offload", "layers": layers, "layers_of_full_config": 28,
+                       "frames": 16384, "tokens_per_frame": 196, "clusters": 512, "top_k": 32,
+                       "slab_frames": 16, "cache_fraction": 0.10, "decode_steps": steps}, **out_all}
+
+
 def run_host_leg(layers=2, steps=128, check=True):
     """Config 3 (host-offload tier) with the layer count scaled to `layers` (the
     full 28 layers need 184 GB of pinned host memory; the per-layer shape is
@@ -668,6 +751,9 @@ def main():
     if args.workload == "cfg4":
         print(json.dumps(run_prefill_leg(check=args.check_units > 0)))
         return
+    if args.workload == "prefetch":
+        print(json.dumps(run_prefetch_leg(layers=args.layers or 3)))
+        return
     if args.workload == "maintainer":
         print(json.dumps(run_maintainer_leg(layers=args.layers or 4, check=args.check_units > 0)))
         return
@@ -722,6 +808,12 @@ def main():
             extra["next1_maintainer"] = run_maintainer_leg()
         except Exception as ex:                      # noqa: BLE001
             extra["next1_maintainer"] = {"error": repr(ex)[:300]}
+        try:
+            import torch
+            torch.cuda.empty_cache()
+            extra["next3_cross_layer_prefetch"] = run_prefetch_leg(layers=2, steps=64, rhos=(0.95,))
+        except Exception as ex:                      # noqa: BLE001
+            extra["next3_cross_layer_prefetch"] = {"error": repr(ex)[:300]}
         for layers in (2, 1):
             try:
                 import torch

@@ -117,6 +117,11 @@ typedef struct {
      * their log-sum-exp). */
     int32_t aug_global_reps;
     int32_t aug_window_frames;
+    /* mosaic_prefetch (host tier): how many of the predicted top-k clusters are fetched ahead,
+     * best first; 0 -> top_k (the paper's scheme).  A smaller number wastes less PCIe time on
+     * marginal predictions that the actual query may not confirm. */
+    int32_t prefetch_top_k;
+    int32_t reserved2;
 } mosaic_config;
 
 /* maint_mode.  _EAGER: every cluster counts as GPU resident, an invalid cluster is split at once

@@ -54,6 +54,7 @@ class Config(C.Structure):
         ("buffer_max", C.c_int32), ("tau_min", C.c_double), ("tau_max", C.c_double),
         ("tau_n0", C.c_double),
         ("aug_global_reps", C.c_int32), ("aug_window_frames", C.c_int32),
+        ("prefetch_top_k", C.c_int32), ("reserved2", C.c_int32),
     ]
 
 
@@ -116,7 +117,8 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
                 score_mode=0, max_q_tokens=0, attend_impl=ATTEND_AUTO, tier=TIER_HBM,
                 slab_frames=0, cache_pages_per_unit=0, cache_fraction=0.0,
                 maint_mode=MAINT_OFF, init_clusters=0, split_iters=0, buffer_max=0,
-                tau_min=0.0, tau_max=0.0, tau_n0=1.0, aug_global_reps=0, aug_window_frames=0) -> Config:
+                tau_min=0.0, tau_max=0.0, tau_n0=1.0, aug_global_reps=0, aug_window_frames=0,
+                prefetch_top_k=0) -> Config:
     c = Config()
     c.n_layers, c.n_q_heads, c.n_kv_heads = n_layers, n_q_heads, n_kv_heads
     c.head_dim, c.tokens_per_frame, c.max_frames = head_dim, tokens_per_frame, max_frames
@@ -129,6 +131,7 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
     c.maint_mode, c.init_clusters, c.split_iters, c.buffer_max = maint_mode, init_clusters, split_iters, buffer_max
     c.tau_min, c.tau_max, c.tau_n0 = tau_min, tau_max, tau_n0
     c.aug_global_reps, c.aug_window_frames = aug_global_reps, aug_window_frames
+    c.prefetch_top_k = prefetch_top_k
     return c
 
 

@@ -75,6 +75,7 @@ int check_config(const mosaic_config *c, std::string &why) {
         if (!(c->tau_min == c->tau_min) || !(c->tau_max == c->tau_max)) { why = "tau_min / tau_max is NaN"; return MOSAIC_EINVAL; }
         if (c->n_clusters + buffer_max_of(*c) > 1024) { why = "n_clusters + buffer_max must not exceed 1024"; return MOSAIC_EINVAL; }
     }
+    if (c->prefetch_top_k < 0 || c->prefetch_top_k > c->top_k) { why = "prefetch_top_k must be in 0..top_k"; return MOSAIC_EINVAL; }
     if (c->aug_global_reps < 0 || c->aug_global_reps > 1 || c->aug_window_frames < 0) { why = "aug_global_reps must be 0 or 1, aug_window_frames >= 0"; return MOSAIC_EINVAL; }
     if (c->aug_window_frames > 1024) { why = "aug_window_frames must not exceed 1024"; return MOSAIC_EINVAL; }
     if (c->aug_global_reps || c->aug_window_frames) {
@@ -632,7 +633,8 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq, 
     for (int i = 0; i < nu; ++i) {
         const int u = u0 + i;
         pages.clear(); moves.clear();
-        const int rc = ht->fetch(u, ids + (size_t)i * k, nids[i], moves, pages, prefetch);
+        const int n_take = prefetch && ctx->cfg.prefetch_top_k > 0 ? std::min(nids[i], ctx->cfg.prefetch_top_k) : nids[i];
+        const int rc = ht->fetch(u, ids + (size_t)i * k, n_take, moves, pages, prefetch);
         if (rc != MOSAIC_OK) {
             char b[256];
             snprintf(b, sizeof b, "the selected clusters do not fit the GPU cluster cache: unit %d selects %d pages "

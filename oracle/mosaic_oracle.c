@@ -18,6 +18,11 @@
  * two-means, equality with the plain online rule when the threshold is out of
  * reach, and the state transitions of Alg. 1 (buffered singletons, their
  * visibility to retrieval, materialization on retrieval, conservation).
+ * The nested visual-semantic hierarchy (Sec. V-B) and two-stage retrieval
+ * (Sec. V-C) are pinned by the special cases P = 1 and top_p = P (both must
+ * be the flat path), the nesting invariant, seeds read back after zero
+ * K-means rounds, a per-partition brute-force K-means, a numpy argmax over the
+ * partition's clusters only, and a whole-array numpy two-stage selection.
  * End-to-end retrieval *quality* has no value in the paper to pin it to:
  * parity unpinned for that quantity only (it is reported, never gated).
  */
@@ -54,6 +59,10 @@ typedef struct {
     double last_var, last_tau;     /* the two sides of its threshold test */
     double split_min_gap;  /* smallest relative gap of any comparison inside the
                               latest Split (diagnostic only) */
+    /* nested visual-semantic hierarchy (Sec. V-B); n_part 0 = flat */
+    int n_part;            /* visual partitions P; cluster ids [p*Cs, (p+1)*Cs) belong to partition p */
+    int Cs;                /* semantic clusters per partition, C / P */
+    int *part;             /* [max_frames] frame -> visual partition */
 } orc_unit;
 
 enum { ORC_ACT_NONE = 0, ORC_ACT_ABSORB = 1, ORC_ACT_SPLIT = 2, ORC_ACT_DEFER = 3,
@@ -68,6 +77,8 @@ typedef struct {
 
 void orc_unit_score(const orc_unit *u, const double *qbar, double *score);
 int orc_select(const double *score, const int *n, int C, int k, int *ids, double *gap_k);
+int orc_unit_ingest(orc_unit *u, const double *k_frame, int force, orc_decision *dec);
+void orc_summary(const double *k_frame, int T, int D, double *s);
 
 static double rel_gap(double a, double b)
 {
@@ -114,6 +125,7 @@ void orc_unit_free(orc_unit *u)
     if (!u) return;
     free(u->summ); free(u->r); free(u->n); free(u->assign);
     free(u->var); free(u->lazy); free(u->resident); free(u->buf_frame); free(u->buf_owner);
+    free(u->part);
     free(u);
 }
 
@@ -124,6 +136,8 @@ void orc_unit_reset(orc_unit *u)
     memset(u->r, 0, (size_t)u->C * u->D * sizeof(double));
     memset(u->n, 0, (size_t)u->C * sizeof(int));
     for (int f = 0; f < u->max_frames; ++f) u->assign[f] = -1;
+    if (u->n_part > 0)
+        for (int f = 0; f < u->max_frames; ++f) u->part[f] = -1;
     if (u->maint_mode) {
         memset(u->var, 0, (size_t)u->C * sizeof(double));
         memset(u->lazy, 0, (size_t)u->C * sizeof(int));
@@ -149,20 +163,34 @@ void orc_summary(const double *k_frame, int T, int D, double *s)
  * (cosine, Sec. V-B) among the non-empty ones; equal similarities go to the
  * lowest cluster id.  `all_live` treats every cluster as non-empty (first
  * Lloyd iteration from seeds). */
-static void nearest(const orc_unit *u, const double *s, int all_live,
-                    orc_decision *dec)
+static void nearest_in(const orc_unit *u, const double *s, int all_live,
+                       int lo, int hi, orc_decision *dec)
 {
     int best = -1, second = -1;
     double bs = -INFINITY, ss = -INFINITY;
-    for (int j = 0; j < u->n_slots; ++j) {
+    for (int j = lo; j < hi; ++j) {
         if (!all_live && u->n[j] == 0) continue;
         double c = cosine(s, u->r + (size_t)j * u->D, u->D);
         if (best < 0 || c > bs) { second = best; ss = bs; best = j; bs = c; }
         else if (second < 0 || c > ss) { second = j; ss = c; }
     }
-    if (best < 0) { best = 0; bs = 0.0; }      /* no live cluster at all */
+    if (best < 0) { best = lo; bs = 0.0; }     /* no live cluster at all */
     dec->winner = best; dec->runner_up = second; dec->sim = bs;
     dec->gap = second >= 0 ? rel_gap(bs, ss) : INFINITY;
+}
+
+/* Candidates of frame f: all cluster ids in use, or -- under the nested
+ * hierarchy (Sec. V-B "Nested Hierarchy": a new state is compared only with
+ * the clusters of its own visual partition) -- the ids of partition part[f]. */
+static void nearest(const orc_unit *u, int f, const double *s, int all_live,
+                    orc_decision *dec)
+{
+    if (u->n_part > 0) {
+        const int p = u->part[f];
+        nearest_in(u, s, all_live, p * u->Cs, (p + 1) * u->Cs, dec);
+    } else {
+        nearest_in(u, s, all_live, 0, u->n_slots, dec);
+    }
 }
 
 /* Modified K-means of Sec. V-B: `iters` rounds of (assign every stored summary
@@ -178,7 +206,7 @@ static void lloyd(orc_unit *u, int first_all_live)
         int all_live = first_all_live && it == 0;
         for (int f = 0; f < F; ++f) {
             orc_decision dec;
-            nearest(u, u->summ + (size_t)f * D, all_live, &dec);
+            nearest(u, f, u->summ + (size_t)f * D, all_live, &dec);
             u->assign[f] = dec.winner;
             if (dec.gap < u->lloyd_min_gap) u->lloyd_min_gap = dec.gap;
         }
@@ -440,13 +468,141 @@ int orc_unit_retrieve_maintained(orc_unit *u, const double *qbar, int k, int *id
     return kept;
 }
 
+/* ------------------------------------------------------------------------
+ * Nested visual-semantic hierarchy and two-stage retrieval (Sec. V-B, V-C).
+ *
+ * The visual level is the same modified K-means, run once per stream on the
+ * per-frame visual embeddings (an orc_unit of its own with T = 1 and C = P,
+ * see the Python wrapper); it hands every frame a partition id.  This unit,
+ * the semantic level of one (layer, KV head), clusters key summaries inside
+ * each partition only.  The paper fixes neither how the C cluster ids are
+ * shared out nor how a partition's K-means starts; the reading taken: every
+ * partition owns Cs = C / P ids, and a partition with np warm-up members
+ * starts L = min(Cs, np) clusters from its members floor(j*np/L), j < L (the
+ * flat seeding rule applied to the partition's member list); ids that are
+ * not started stay empty.  Periodic re-clustering and the maintainer are not
+ * combined with the hierarchy.
+ * ------------------------------------------------------------------------ */
+
+/* Switch the hierarchy on with P partitions; call before the first frame.
+ * Returns 0, or -1 (P < 1, C not a multiple of P, maintainer or periodic
+ * re-clustering on, frames already in). */
+int orc_unit_set_nested(orc_unit *u, int P)
+{
+    if (P < 1 || u->C % P != 0 || u->maint_mode || u->recluster_every || u->n_frames > 0) return -1;
+    u->n_part = P; u->Cs = u->C / P;
+    free(u->part);
+    u->part = (int *)malloc((size_t)u->max_frames * sizeof(int));
+    for (int f = 0; f < u->max_frames; ++f) u->part[f] = -1;
+    return 0;
+}
+
+static void seed_nested(orc_unit *u)
+{
+    const int W = u->warmup, D = u->D, Cs = u->Cs;
+    int *mem = (int *)malloc((size_t)W * sizeof(int));
+    memset(u->n, 0, (size_t)u->C * sizeof(int));
+    memset(u->r, 0, (size_t)u->C * D * sizeof(double));
+    for (int p = 0; p < u->n_part; ++p) {
+        int np = 0;
+        for (int f = 0; f < W; ++f) if (u->part[f] == p) mem[np++] = f;
+        const int L = np < Cs ? np : Cs;
+        for (int j = 0; j < L; ++j) {
+            const int src = mem[(int)(((long long)j * np) / L)];
+            memcpy(u->r + (size_t)(p * Cs + j) * D, u->summ + (size_t)src * D, (size_t)D * sizeof(double));
+            u->n[p * Cs + j] = 1;          /* started: takes part in the first assignment round */
+        }
+    }
+    free(mem);
+}
+
+/* Frame Encoding under the hierarchy: as orc_unit_ingest, with the visual
+ * level's frame -> partition map.  part[0..n_frames] must be valid from the
+ * frame that completes the warm-up on (the visual level uses the same warm-up
+ * length, so it becomes ready on that very frame); before that it is not read. */
+int orc_unit_ingest_nested(orc_unit *u, const double *k_frame, const int *part,
+                           int force, orc_decision *dec)
+{
+    if (u->n_part <= 0 || u->n_frames >= u->max_frames) return -1;
+    const int f = u->n_frames;
+    if (u->ready) u->part[f] = part[f];
+    else if (f + 1 == u->warmup) memcpy(u->part, part, (size_t)u->warmup * sizeof(int));
+    return orc_unit_ingest(u, k_frame, force, dec);
+}
+
+/* What the greedy rule would decide for a frame of partition p (no change of state). */
+void orc_unit_peek_nested(const orc_unit *u, const double *k_frame, int p, orc_decision *dec)
+{
+    double *s = (double *)malloc((size_t)u->D * sizeof(double));
+    orc_summary(k_frame, u->T, u->D, s);
+    nearest_in(u, s, 0, p * u->Cs, (p + 1) * u->Cs, dec);
+    free(s);
+}
+
+/* Visual-level representative as this unit's query sees it.  The query lives
+ * in the layer's key space, not in the vision encoder's, so the partition is
+ * summarized the way every cluster is (Eq. 1): the mean of the key summaries
+ * of its frames, in ascending frame order.  rp [D]; returns the frame count. */
+int orc_unit_partition_rep(const orc_unit *u, int p, double *rp)
+{
+    const int D = u->D;
+    int cnt = 0;
+    for (int d = 0; d < D; ++d) rp[d] = 0.0;
+    for (int f = 0; f < u->n_frames; ++f) {
+        if (u->part[f] != p) continue;
+        for (int d = 0; d < D; ++d) rp[d] += u->summ[(size_t)f * D + d];
+        ++cnt;
+    }
+    if (cnt > 0) for (int d = 0; d < D; ++d) rp[d] /= (double)cnt;
+    return cnt;
+}
+
+/* Two-Stage Retrieval (Sec. V-C): (1) score the P partition representatives
+ * with the query (same relevance as for clusters) and keep the top_p best
+ * non-empty partitions; (2) score the non-empty clusters of those partitions
+ * only and keep the top k of them.  part_score [P] and score [C] receive the
+ * scores (-inf for empty or pruned entries); part_ids [top_p]; ids [k];
+ * gap_p / gap_k = relative gap at each cut; *n_cand = clusters scored in
+ * stage 2.  Returns the number of clusters kept; *n_part_kept partitions. */
+int orc_unit_retrieve_nested(const orc_unit *u, const double *qbar, int top_p, int k,
+                             int *part_ids, int *n_part_kept, double *part_score,
+                             int *ids, double *score, double *gap_p, double *gap_k,
+                             int *n_cand)
+{
+    const int P = u->n_part, D = u->D, Cs = u->Cs;
+    double *rp = (double *)malloc((size_t)D * sizeof(double));
+    int *pn = (int *)malloc((size_t)P * sizeof(int));
+    for (int p = 0; p < P; ++p) {
+        pn[p] = orc_unit_partition_rep(u, p, rp);
+        if (pn[p] == 0) { part_score[p] = -INFINITY; continue; }
+        double dp = dot(qbar, rp, D);
+        if (u->score_mode == 1) { part_score[p] = dp; continue; }
+        double nr = sqrt(dot(rp, rp, D));
+        part_score[p] = nr == 0.0 ? 0.0 : dp / nr;
+    }
+    const int kept_p = orc_select(part_score, pn, P, top_p, part_ids, gap_p);
+    *n_part_kept = kept_p;
+    int *live = (int *)calloc((size_t)u->C, sizeof(int));
+    double *full = (double *)malloc((size_t)u->C * sizeof(double));
+    orc_unit_score(u, qbar, full);
+    int cand = 0;
+    for (int j = 0; j < u->C; ++j) score[j] = -INFINITY;
+    for (int i = 0; i < kept_p; ++i)
+        for (int j = part_ids[i] * Cs; j < (part_ids[i] + 1) * Cs; ++j)
+            if (u->n[j] > 0) { live[j] = u->n[j]; score[j] = full[j]; ++cand; }
+    if (n_cand) *n_cand = cand;
+    const int kept = orc_select(score, live, u->C, k, ids, gap_k);
+    free(rp); free(pn); free(live); free(full);
+    return kept;
+}
+
 /* What the greedy rule would decide for a frame, without changing state.
  * Only meaningful once the unit is ready and no (re-)clustering is due. */
 void orc_unit_peek(const orc_unit *u, const double *k_frame, orc_decision *dec)
 {
     double *s = (double *)malloc((size_t)u->D * sizeof(double));
     orc_summary(k_frame, u->T, u->D, s);
-    nearest(u, s, 0, dec);
+    nearest_in(u, s, 0, 0, u->n_slots, dec);
     free(s);
 }
 
@@ -473,7 +629,11 @@ int orc_unit_ingest(orc_unit *u, const double *k_frame, int force,
     local.winner = -1; local.runner_up = -1; local.gap = INFINITY; local.sim = 0.0;
     if (!u->ready) {
         u->n_frames = f + 1;
-        if (u->n_frames == u->warmup) {
+        if (u->n_frames == u->warmup && u->n_part > 0) {
+            seed_nested(u);
+            lloyd(u, 0);
+            u->ready = 1;
+        } else if (u->n_frames == u->warmup) {
             const int W = u->warmup;
             for (int j = 0; j < u->n_slots; ++j) {
                 int src = (int)(((long long)j * W) / u->n_slots);
@@ -487,11 +647,11 @@ int orc_unit_ingest(orc_unit *u, const double *k_frame, int force,
             u->ready = 1;
         }
     } else if (u->maint_mode) {
-        nearest(u, s, 0, &local);
+        nearest(u, f, s, 0, &local);
         u->n_frames = f + 1;                            /* the new state is part of what a split sees */
         maintain_insert(u, f, s, force >= 0 ? force : local.winner);
     } else {
-        nearest(u, s, 0, &local);
+        nearest(u, f, s, 0, &local);
         int a = force >= 0 ? force : local.winner;
         double *ra = u->r + (size_t)a * D;
         double na = (double)u->n[a];
@@ -645,3 +805,4 @@ const int *orc_unit_lazy(const orc_unit *u) { return u->lazy; }
 const int *orc_unit_resident(const orc_unit *u) { return u->resident; }
 const int *orc_unit_buf_frame(const orc_unit *u) { return u->buf_frame; }
 const int *orc_unit_buf_owner(const orc_unit *u) { return u->buf_owner; }
+const int *orc_unit_part(const orc_unit *u) { return u->part; }

@@ -74,6 +74,18 @@ def lib():
         L.orc_tau.argtypes = [C.c_double] * 4
         L.orc_unit_retrieve_maintained.restype = C.c_int
         L.orc_unit_retrieve_maintained.argtypes = [C.c_void_p, _dp, C.c_int, _ip, _dp, _ip, _ip, _dp]
+        L.orc_unit_set_nested.restype = C.c_int
+        L.orc_unit_set_nested.argtypes = [C.c_void_p, C.c_int]
+        L.orc_unit_ingest_nested.restype = C.c_int
+        L.orc_unit_ingest_nested.argtypes = [C.c_void_p, _dp, _ip, C.c_int, C.POINTER(_Decision)]
+        L.orc_unit_peek_nested.argtypes = [C.c_void_p, _dp, C.c_int, C.POINTER(_Decision)]
+        L.orc_unit_partition_rep.restype = C.c_int
+        L.orc_unit_partition_rep.argtypes = [C.c_void_p, C.c_int, _dp]
+        L.orc_unit_retrieve_nested.restype = C.c_int
+        L.orc_unit_retrieve_nested.argtypes = [C.c_void_p, _dp, C.c_int, C.c_int, _ip, _ip, _dp, _ip, _dp,
+                                               _dp, _dp, _ip]
+        L.orc_unit_part.restype = _ip
+        L.orc_unit_part.argtypes = [C.c_void_p]
         for name, rt in (("orc_unit_n_slots", C.c_int), ("orc_unit_n_buf", C.c_int),
                          ("orc_unit_last_action", C.c_int), ("orc_unit_last_var", C.c_double),
                          ("orc_unit_last_tau", C.c_double), ("orc_unit_split_min_gap", C.c_double),
@@ -164,11 +176,16 @@ class OracleUnit:
     maintainer = dict(mode=1|2, c_init=.., tau_min=.., tau_max=.., n0=..,
     split_iters=.., buf_max=..) switches the self-adaptive maintainer on
     (Sec. VI): n_clusters is then the size of the cluster table, c_init the
-    number of clusters the initial K-means builds."""
+    number of clusters the initial K-means builds.
+
+    nested = P switches the nested visual-semantic hierarchy on (Sec. V-B):
+    the C cluster ids are shared out over P visual partitions and every frame
+    is ingested with the visual level's frame -> partition map (ingest_nested)."""
 
     def __init__(self, n_clusters: int, head_dim: int, tokens_per_frame: int,
                  max_frames: int, warmup_frames: int = 0, lloyd_iters: int = 8,
-                 recluster_every: int = 0, score_mode: int = 0, maintainer: dict | None = None):
+                 recluster_every: int = 0, score_mode: int = 0, maintainer: dict | None = None,
+                 nested: int = 0):
         self.C, self.D, self.T = n_clusters, head_dim, tokens_per_frame
         self.max_frames = max_frames
         self._L = lib()
@@ -185,6 +202,10 @@ class OracleUnit:
                                                  int(m.get("split_iters", 4)), self.buf_max)
             if rc != 0:
                 raise ValueError("bad maintainer parameters")
+        self.n_part = int(nested)
+        if self.n_part:
+            if self._L.orc_unit_set_nested(self._u, self.n_part) != 0:
+                raise ValueError("bad nested-hierarchy parameters")
 
     def __del__(self):
         if getattr(self, "_u", None):
@@ -312,6 +333,55 @@ class OracleUnit:
         m = self._L.orc_unit_retrieve_maintained(self._u, _d(qbar), top_k, _i(ids), _d(sc), _i(tok),
                                                  C.byref(n_tok), C.byref(gap))
         return ids[:m].copy(), sc[: self.C + nb].copy(), tok[: n_tok.value].copy(), gap.value
+
+    # -- nested visual-semantic hierarchy ----------------------------------
+    def ingest_nested(self, k_frame: np.ndarray, part: np.ndarray, force: int = -1) -> Decision:
+        """part: the visual level's frame -> partition map, valid for frames
+        0..n_frames once the warm-up completes (not read before)."""
+        k_frame = f64(k_frame)
+        assert k_frame.shape == (self.T, self.D)
+        part = np.ascontiguousarray(part, dtype=np.int32)
+        assert part.shape[0] > self.n_frames
+        d = _Decision()
+        rc = self._L.orc_unit_ingest_nested(self._u, _d(k_frame), _i(part), force, C.byref(d))
+        if rc != 0:
+            raise RuntimeError("oracle unit is full or not nested")
+        return Decision(d.winner, d.runner_up, d.gap, d.sim)
+
+    def peek_nested(self, k_frame: np.ndarray, p: int) -> Decision:
+        k_frame = f64(k_frame)
+        d = _Decision()
+        self._L.orc_unit_peek_nested(self._u, _d(k_frame), int(p), C.byref(d))
+        return Decision(d.winner, d.runner_up, d.gap, d.sim)
+
+    def partitions(self) -> np.ndarray:
+        p = self._L.orc_unit_part(self._u)
+        return np.ctypeslib.as_array(p, shape=(self.max_frames,))[: self.n_frames].copy()
+
+    def partition_rep(self, p: int):
+        """-> (mean key summary of partition p's frames, frame count)"""
+        rp = np.empty(self.D, dtype=np.float64)
+        cnt = self._L.orc_unit_partition_rep(self._u, int(p), _d(rp))
+        return rp, cnt
+
+    def retrieve_nested(self, q: np.ndarray, h: int, G: int, top_p: int, top_k: int):
+        """Two-stage retrieval (Sec. V-C): q [Tq][Hq][D] -> dict(part_ids, part_scores [P], gap_p,
+        ids, scores [C] (-inf for empty or pruned clusters), gap_k, n_candidates, tok_idx)."""
+        qbar = mean_query(q, h, G)
+        P = self.n_part
+        part_ids = np.empty(max(top_p, 1), dtype=np.int32)
+        part_sc = np.empty(P, dtype=np.float64)
+        ids = np.empty(max(top_k, 1), dtype=np.int32)
+        sc = np.empty(self.C, dtype=np.float64)
+        n_pk, n_cand = C.c_int(), C.c_int()
+        gap_p, gap_k = C.c_double(), C.c_double()
+        m = self._L.orc_unit_retrieve_nested(self._u, _d(qbar), top_p, top_k, _i(part_ids), C.byref(n_pk),
+                                             _d(part_sc), _i(ids), _d(sc), C.byref(gap_p), C.byref(gap_k),
+                                             C.byref(n_cand))
+        ids = ids[:m].copy()
+        return dict(part_ids=part_ids[: n_pk.value].copy(), part_scores=part_sc, gap_p=gap_p.value,
+                    ids=ids, scores=sc, gap_k=gap_k.value, n_candidates=n_cand.value,
+                    tok_idx=self.gather(ids))
 
     # -- the whole query side for this unit --------------------------------
     def retrieve(self, q: np.ndarray, h: int, G: int, top_k: int):

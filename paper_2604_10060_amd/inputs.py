@@ -26,6 +26,13 @@ Scene segmentation:
   'geometric'  i.i.d. Geometric(1/mean_scene_len) lengths until F is filled
   'rapid'      i.i.d. Uniform{1,2,3} lengths (low visual coherence)
 Values are generated in fp32 and rounded (RNE) to the workload's KV dtype.
+
+Visual embeddings (visual_dim > 0; a stand-in for the vision encoder's pooled
+per-frame output, which the nested visual-semantic hierarchy of Sec. V-B
+clusters first): every scene belongs to one of n_visual appearance classes,
+  class centre   a[v]  ~ N(0, I_Dv),  scene offset  o[s] ~ N(0, I_Dv)
+  embedding      e_f = a[class(s)] + 0.3 * o[s] + visual_noise * N(0, I_Dv)   (fp32)
+so scenes of one class look alike while their key states differ.
 """
 from __future__ import annotations
 
@@ -56,6 +63,9 @@ class Workload:
     drift: float = 0.05
     outlier_frac: float = 0.0
     layer_corr: float = 0.0       # correlation of adjacent layers' scene centres and question noise (0 = independent)
+    visual_dim: int = 0           # > 0: per-frame visual embeddings of this size are generated as well
+    n_visual: int = 8             # appearance classes the scenes are drawn from
+    visual_noise: float = 0.3
     warmup_frames: int = 0        # 0 -> 2 * n_clusters
     lloyd_iters: int = 8
     recluster_every: int = 0
@@ -178,6 +188,15 @@ class SceneStream:
         self.drift_v = rn() * inv
         self._gen = torch.Generator(device=self.device)
         self._qrng = np.random.Generator(np.random.PCG64(wl.seed + 500_000))
+        if wl.visual_dim > 0:      # draws of their own: the K/V stream does not depend on them
+            vr = np.random.Generator(np.random.PCG64(wl.seed + 900_000))
+            self.visual_class_of_scene = vr.integers(0, wl.n_visual, size=self.n_scenes)
+            gv = torch.Generator(device=self.device)
+            gv.manual_seed(wl.seed * 7919 + 3)
+            self.visual_centre = torch.randn((wl.n_visual, wl.visual_dim), generator=gv,
+                                             device=self.device, dtype=torch.float32)
+            self.visual_offset = torch.randn((self.n_scenes, wl.visual_dim), generator=gv,
+                                             device=self.device, dtype=torch.float32)
 
     # -- frames ------------------------------------------------------------
     def frame(self, f: int) -> tuple[torch.Tensor, torch.Tensor]:
@@ -210,6 +229,22 @@ class SceneStream:
         """K and V of frames f0..f1-1, each [f1-f0][L][Hkv][T][D]."""
         ks, vs = zip(*(self.frame(f) for f in range(f0, f1)))
         return torch.stack(ks), torch.stack(vs)
+
+    # -- visual embeddings -------------------------------------------------
+    def embedding(self, f: int) -> torch.Tensor:
+        """Visual embedding of frame f, fp32 [Dv]."""
+        wl = self.wl
+        assert wl.visual_dim > 0
+        s = int(self.scene_of_frame[f])
+        g = self._gen
+        g.manual_seed(wl.seed * 3_000_017 + 13 * f + 7)
+        x = torch.randn((wl.visual_dim,), generator=g, device=self.device, dtype=torch.float32)
+        return self.visual_centre[int(self.visual_class_of_scene[s])] + 0.3 * self.visual_offset[s] \
+            + wl.visual_noise * x
+
+    def embeddings(self, f0: int, f1: int) -> torch.Tensor:
+        """Visual embeddings of frames f0..f1-1, fp32 [f1-f0][Dv]."""
+        return torch.stack([self.embedding(f) for f in range(f0, f1)])
 
     # -- questions ---------------------------------------------------------
     def draw_scene(self) -> int:

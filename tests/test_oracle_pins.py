@@ -694,3 +694,228 @@ def test_global_representatives_are_cluster_means_and_merge_by_lse():
     w1, w2 = np.exp(l1 - np.logaddexp(l1, l2)), np.exp(l2 - np.logaddexp(l1, l2))
     np.testing.assert_allclose(out, o1 * w1[..., None] + o2 * w2[..., None], rtol=1e-12)
     np.testing.assert_allclose(lse, np.logaddexp(l1, l2), rtol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# Nested visual-semantic hierarchy and two-stage retrieval (Sec. V-B, V-C)
+# --------------------------------------------------------------------------
+def _nested_stream(seed, F=96, T=2, D=8, Dv=6, n_visual=3, n_scenes=9):
+    """Scene-structured keys plus visual embeddings whose classes group the scenes."""
+    r = _rng(seed)
+    K, labels = _stream(F, T, D, n_scenes, seed)
+    r.shuffle(labels)                      # scenes interleaved in time: partitions are not contiguous runs
+    centres = r.normal(size=(n_scenes, D))
+    K = centres[labels][:, None, :] + 0.3 * r.normal(size=(F, T, D))
+    cls = r.integers(0, n_visual, size=n_scenes)
+    vc = 3.0 * r.normal(size=(n_visual, Dv))
+    E = vc[cls[labels]] + 0.2 * r.normal(size=(F, Dv))
+    return K, E, labels, cls[labels]
+
+
+def _run_nested(K, E, P, C, W, iters=4, score_mode=0):
+    F, T, D = K.shape
+    vis = orc.OracleUnit(P, E.shape[1], 1, F, warmup_frames=W, lloyd_iters=iters)
+    sem = orc.OracleUnit(C, D, T, F, warmup_frames=W, lloyd_iters=iters, score_mode=score_mode, nested=P)
+    part = np.full(F, -1, dtype=np.int32)
+    for f in range(F):
+        vis.ingest(E[f][None, :])
+        if vis.ready:
+            part[: f + 1] = vis.assignments()
+        sem.ingest_nested(K[f], part)
+    return vis, sem
+
+
+def test_nested_with_one_partition_is_the_flat_index():
+    # special case: P = 1 puts every frame into the same partition, so seeding, K-means,
+    # online assignment and the two-stage selection must reduce to the flat path
+    K, E, _, _ = _nested_stream(61)
+    F, T, D = K.shape
+    flat = orc.OracleUnit(6, D, T, F, warmup_frames=18, lloyd_iters=4)
+    for f in range(F):
+        flat.ingest(K[f])
+    _, sem = _run_nested(K, E, 1, 6, 18)
+    np.testing.assert_array_equal(sem.assignments(), flat.assignments())
+    np.testing.assert_array_equal(sem.centroids(), flat.centroids())
+    q = _rng(62).normal(size=(3, 4, D))
+    a = sem.retrieve_nested(q, 1, 2, 1, 3)
+    ids, sc, tok, _ = flat.retrieve(q, 1, 2, 3)
+    np.testing.assert_array_equal(a["ids"], ids)
+    np.testing.assert_array_equal(a["scores"], sc)
+    np.testing.assert_array_equal(a["tok_idx"], tok)
+
+
+def test_nested_clusters_stay_inside_their_visual_partition():
+    K, E, _, _ = _nested_stream(63)
+    P, Cs = 3, 4
+    vis, sem = _run_nested(K, E, P, P * Cs, 24)
+    part, A = vis.assignments(), sem.assignments()
+    np.testing.assert_array_equal(sem.partitions(), part)
+    np.testing.assert_array_equal(A // Cs, part)                  # the nesting itself
+    # sizes count the members, every frame is in exactly one cluster
+    np.testing.assert_array_equal(sem.sizes(), np.bincount(A, minlength=P * Cs))
+
+
+def test_nested_seeds_follow_the_partition_member_lists():
+    # zero K-means rounds leave the seeds in place: slot j of partition p holds the summary of
+    # the partition's member floor(j * np / L), L = min(Cs, np); slots beyond L stay empty
+    K, E, _, _ = _nested_stream(64, F=40)
+    F, T, D = K.shape
+    P, Cs, W = 3, 5, 12
+    vis = orc.OracleUnit(P, E.shape[1], 1, F, warmup_frames=W, lloyd_iters=4)
+    for f in range(W):
+        vis.ingest(E[f][None, :])
+    part = vis.assignments().astype(np.int32)
+    sem = orc.OracleUnit(P * Cs, D, T, F, warmup_frames=W, lloyd_iters=0, nested=P)
+    for f in range(W):
+        sem.ingest_nested(K[f], np.concatenate([part, [-1] * (F - W)]).astype(np.int32))
+    assert sem.ready
+    S = K[:W].mean(axis=1)
+    R, n = sem.centroids(), sem.sizes()
+    saw_short = False
+    for p in range(P):
+        mem = np.flatnonzero(part == p)
+        L = min(Cs, len(mem))
+        saw_short |= L < Cs
+        for j in range(Cs):
+            if j < L:
+                np.testing.assert_allclose(R[p * Cs + j], S[mem[(j * len(mem)) // L]], rtol=0, atol=1e-15)
+                assert n[p * Cs + j] == 1
+            else:
+                assert n[p * Cs + j] == 0
+    assert saw_short        # the case of a partition with fewer members than ids is exercised
+
+
+@pytest.mark.parametrize("seed", [65, 66])
+def test_nested_online_assignment_is_argmax_over_the_partition_only(seed):
+    K, E, _, _ = _nested_stream(seed)
+    F, T, D = K.shape
+    P, Cs, W = 3, 3, 18
+    vis = orc.OracleUnit(P, E.shape[1], 1, F, warmup_frames=W, lloyd_iters=4)
+    sem = orc.OracleUnit(P * Cs, D, T, F, warmup_frames=W, lloyd_iters=4, nested=P)
+    part = np.full(F, -1, dtype=np.int32)
+    crossed = 0
+    for f in range(F):
+        vis.ingest(E[f][None, :])
+        if vis.ready:
+            part[: f + 1] = vis.assignments()
+        if sem.ready:
+            R, n = sem.centroids(), sem.sizes()
+            s = K[f].mean(axis=0)
+            cos = _cos_matrix(s[None, :], np.where(n[:, None] > 0, R, 1.0))[0]
+            cos[n == 0] = -np.inf
+            inside = np.full_like(cos, -np.inf)
+            lo = part[f] * Cs
+            inside[lo: lo + Cs] = cos[lo: lo + Cs]
+            want = int(np.argmax(inside))
+            crossed += int(np.argmax(cos)) != want       # the restriction changes some decisions
+            n_before = n[want]
+            dec = sem.ingest_nested(K[f], part)
+            assert dec.winner == want and sem.assignments()[f] == want
+            # Eq. 3 on the winner, nothing else moves
+            R2 = sem.centroids()
+            np.testing.assert_allclose(R2[want], (n_before * R[want] + s) / (n_before + 1), rtol=1e-14)
+            mask = np.arange(P * Cs) != want
+            np.testing.assert_array_equal(R2[mask], R[mask])
+        else:
+            sem.ingest_nested(K[f], part)
+    assert crossed > 0
+
+
+def test_nested_lloyd_matches_brute_force_inside_each_partition():
+    # the initial clustering equals an independent brute-force K-means run on each partition's
+    # members alone (that is what "constrained within each visual cluster" means)
+    K, E, _, _ = _nested_stream(67, F=60)
+    F, T, D = K.shape
+    P, Cs, W, iters = 3, 3, 36, 3
+    vis, sem = _run_nested(K[:W], E[:W], P, P * Cs, W, iters=iters)
+    part = vis.assignments()
+    S = K[:W].mean(axis=1)
+    for p in range(P):
+        mem = np.flatnonzero(part == p)
+        L = min(Cs, len(mem))
+        R0 = np.stack([S[mem[(j * len(mem)) // L]] for j in range(L)])
+        A, R, n = _lloyd_brute(S[mem], R0, np.ones(L, dtype=np.int64), iters, False)
+        np.testing.assert_array_equal(sem.assignments()[mem] - p * Cs, A)
+        np.testing.assert_allclose(sem.centroids()[p * Cs: p * Cs + L][n > 0], R[n > 0], rtol=1e-13)
+
+
+def test_partition_representative_is_member_mean_and_weighted_centroid_mean():
+    K, E, _, _ = _nested_stream(68)
+    P, Cs = 3, 4
+    vis, sem = _run_nested(K, E, P, P * Cs, 24)
+    part = vis.assignments()
+    S = K.mean(axis=1)
+    R, n = sem.centroids(), sem.sizes()
+    for p in range(P):
+        rp, cnt = sem.partition_rep(p)
+        assert cnt == int((part == p).sum())
+        np.testing.assert_allclose(rp, S[part == p].mean(axis=0), rtol=1e-13)
+        # Eq. 1 one level up: the partition's mean is the size-weighted mean of its clusters' means
+        w = n[p * Cs:(p + 1) * Cs].astype(np.float64)
+        np.testing.assert_allclose(rp, (w[:, None] * R[p * Cs:(p + 1) * Cs]).sum(axis=0) / w.sum(), rtol=1e-12)
+
+
+@pytest.mark.parametrize("seed,score_mode", [(69, 0), (70, 1), (71, 0)])
+def test_two_stage_retrieval_matches_brute_force(seed, score_mode):
+    K, E, _, _ = _nested_stream(seed)
+    F, T, D = K.shape
+    P, Cs, top_p, k = 3, 4, 2, 3
+    vis, sem = _run_nested(K, E, P, P * Cs, 24, score_mode=score_mode)
+    part, A = vis.assignments(), sem.assignments()
+    S = K.mean(axis=1)
+    R, n = sem.centroids(), sem.sizes()
+    q = _rng(seed + 100).normal(size=(2, 4, D))
+    h, G = 1, 2
+    qbar = q[:, h * G:(h + 1) * G].reshape(-1, D).mean(axis=0)
+    # stage 1 with whole-array numpy
+    PR = np.stack([S[part == p].mean(axis=0) for p in range(P)])
+    ps = PR @ qbar if score_mode == 1 else (PR @ qbar) / np.linalg.norm(PR, axis=1)
+    want_parts = np.lexsort((np.arange(P), -ps))[:top_p]
+    # stage 2 over the clusters of those partitions
+    cs = R @ qbar if score_mode == 1 else (R @ qbar) / np.where(n > 0, np.linalg.norm(R, axis=1), 1.0)
+    cand = np.array([j for j in range(P * Cs) if n[j] > 0 and j // Cs in want_parts])
+    order = cand[np.lexsort((cand, -cs[cand]))][:k]
+    got = sem.retrieve_nested(q, h, G, top_p, k)
+    np.testing.assert_array_equal(got["part_ids"], want_parts)
+    np.testing.assert_allclose(got["part_scores"], ps, rtol=1e-12)
+    np.testing.assert_array_equal(got["ids"], order)
+    assert got["n_candidates"] == len(cand)
+    assert set(np.flatnonzero(np.isfinite(got["scores"]))) == set(cand)
+    np.testing.assert_allclose(got["scores"][cand], cs[cand], rtol=1e-12)
+    # the gather is the members of the chosen clusters, clusters in selection order
+    want_tok = np.concatenate([(np.flatnonzero(A == j)[:, None] * T + np.arange(T)).ravel() for j in order])
+    np.testing.assert_array_equal(got["tok_idx"], want_tok)
+
+
+def test_two_stage_with_all_partitions_is_the_flat_selection():
+    K, E, _, _ = _nested_stream(72)
+    P, Cs = 3, 4
+    _, sem = _run_nested(K, E, P, P * Cs, 24)
+    q = _rng(73).normal(size=(2, 4, K.shape[2]))
+    got = sem.retrieve_nested(q, 0, 2, P, 5)
+    ids, sc, tok, gap = sem.retrieve(q, 0, 2, 5)
+    np.testing.assert_array_equal(got["ids"], ids)
+    np.testing.assert_array_equal(got["scores"], sc)
+    np.testing.assert_array_equal(got["tok_idx"], tok)
+    assert got["gap_k"] == gap
+
+
+def test_nested_hierarchy_rejects_bad_parameters():
+    with pytest.raises(ValueError):
+        orc.OracleUnit(10, 8, 2, 32, nested=3)            # C not a multiple of P
+    with pytest.raises(ValueError):
+        orc.OracleUnit(8, 8, 2, 32, recluster_every=8, nested=2)
+
+
+def test_synthetic_visual_embeddings_group_scenes_by_class():
+    wl = inputs.CONFIGS[0].scaled(visual_dim=16, n_visual=3, visual_noise=0.1)
+    st = inputs.SceneStream(wl)
+    E = st.embeddings(0, wl.n_frames).numpy().astype(np.float64)
+    cls = st.visual_class_of_scene[st.scene_of_frame]
+    C = _cos_matrix(E, E)
+    same = cls[:, None] == cls[None, :]
+    assert C[same].mean() > C[~same].mean() + 0.3
+    # the K/V stream does not depend on the visual draws
+    k0, _ = inputs.SceneStream(inputs.CONFIGS[0]).frame(5)
+    k1, _ = st.frame(5)
+    assert (k0 == k1).all()

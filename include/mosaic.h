@@ -121,7 +121,25 @@ typedef struct {
      * best first; 0 -> top_k (the paper's scheme).  A smaller number wastes less PCIe time on
      * marginal predictions that the actual query may not confirm. */
     int32_t prefetch_top_k;
-    int32_t reserved2;
+    /* Nested visual-semantic hierarchy and two-stage retrieval (paper Sec. V-B "Nested Hierarchy",
+     * Sec. V-C "Two-Stage Retrieval"); n_partitions = 0: flat index.  MOSAIC_TIER_HBM only, without
+     * the maintainer, periodic re-clustering and augmentation.  With P = n_partitions > 0:
+     *  - frames are ingested with mosaic_ingest_frame_visual, which also takes the frame's visual
+     *    embedding (visual_dim floats).  The visual level clusters these embeddings once per stream
+     *    with the same modified K-means as the semantic level (warm-up of W frames, then P-means with
+     *    seeds = embeddings of frames floor(p*W/P), then greedy cosine assignment and Eq. 3), and
+     *    gives every frame a partition;
+     *  - n_clusters must be a multiple of P: partition p owns the cluster ids [p*Cs, (p+1)*Cs),
+     *    Cs = n_clusters / P.  A unit's K-means runs inside each partition (a partition with np
+     *    warm-up members starts min(Cs, np) clusters from its members floor(j*np/min(Cs, np))), and a
+     *    new frame is compared with the non-empty clusters of its own partition only;
+     *  - mosaic_retrieve first scores, per unit, the P partition representatives (mean key summary
+     *    of the partition's frames: the query lives in the layer's key space, not the vision
+     *    encoder's), keeps the top_partitions best, then scores only the clusters of those and
+     *    keeps the top_k of them. */
+    int32_t n_partitions;         /* P, 0..64 */
+    int32_t visual_dim;           /* Dv, 1..4096 */
+    int32_t top_partitions;       /* 1..P; 0 -> max(1, P / 4) */
 } mosaic_config;
 
 /* maint_mode.  _EAGER: every cluster counts as GPU resident, an invalid cluster is split at once
@@ -189,6 +207,13 @@ int32_t mosaic_reset(mosaic_ctx *ctx);
 int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_dev,
                             int32_t n_frames);
 
+/* Frame Encoding under the nested hierarchy (Sec. V-B; config.n_partitions > 0, where it replaces
+ * mosaic_ingest_frame, which then fails with EINVAL -- and vice versa).  k_dev, v_dev, n_frames
+ * as for mosaic_ingest_frame; e_dev: device pointer, fp32 [n_frames][visual_dim], 16-byte
+ * aligned, the frames' visual embeddings.  Identical to n_frames calls with one frame each. */
+int32_t mosaic_ingest_frame_visual(mosaic_ctx *ctx, const void *k_dev, const void *v_dev,
+                                   const float *e_dev, int32_t n_frames);
+
 /* Query Retrieval, selection part (Sec. V-C "Cluster Indexing" / second stage
  * of "Two-Stage Retrieval"; top-K of Sec. VII-B).
  * layer >= 0: that layer only, q_dev is [Tq][Hq][D]; layer == -1: all layers,
@@ -253,6 +278,19 @@ int32_t mosaic_get_summaries(mosaic_ctx *ctx, double *summaries);
  * frame as -2 - owner.  Synchronises the stream. */
 int32_t mosaic_get_maintainer(mosaic_ctx *ctx, double *var, int32_t *lazy, int32_t *resident,
                               int32_t *n_slots, int32_t *n_buf, int32_t *buf_frame, int32_t *buf_owner);
+
+/* Nested hierarchy (n_partitions > 0 only).  HOST pointers, any may be NULL; synchronises.
+ * frame_to_partition [n_frames_ingested] (-1 before the visual level's initial clustering);
+ * visual_r [P][visual_dim] fp64 visual centroids, visual_n [P] their sizes in frames;
+ * part_r [L*Hkv][P][D] fp64 per-unit partition representatives (key space), part_n [L*Hkv][P]. */
+int32_t mosaic_get_partitions(mosaic_ctx *ctx, int32_t *frame_to_partition, double *visual_r,
+                              int32_t *visual_n, double *part_r, int32_t *part_n);
+/* First stage of the latest two-stage selection of one layer: part_ids [Hkv][top_partitions]
+ * (-1 padded) in (score descending, id ascending) order, n_part_ids [Hkv], part_scores [Hkv][P]
+ * (-inf for empty partitions).  mosaic_get_selection's scores are -inf for the clusters of
+ * partitions that were not chosen. */
+int32_t mosaic_get_partition_selection(mosaic_ctx *ctx, int32_t layer, int32_t *part_ids,
+                                       int32_t *n_part_ids, double *part_scores);
 
 /* Latest selection of one layer (layer >= 0): ids [Hkv][top_k] (-1 padded),
  * n_ids [Hkv], scores [Hkv][C] fp64 (-inf for empty clusters; with

@@ -27,6 +27,7 @@ EXPORTS = (
     "mosaic_workspace_size", "mosaic_create", "mosaic_destroy", "mosaic_reset",
     "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_prefetch", "mosaic_attend",
     "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries", "mosaic_get_maintainer",
+    "mosaic_ingest_frame_visual", "mosaic_get_partitions", "mosaic_get_partition_selection",
     "mosaic_get_selection", "mosaic_get_stats", "mosaic_profile_enable",
     "mosaic_profile_read", "mosaic_calibration_copy", "mosaic_last_error",
 )
@@ -54,7 +55,8 @@ class Config(C.Structure):
         ("buffer_max", C.c_int32), ("tau_min", C.c_double), ("tau_max", C.c_double),
         ("tau_n0", C.c_double),
         ("aug_global_reps", C.c_int32), ("aug_window_frames", C.c_int32),
-        ("prefetch_top_k", C.c_int32), ("reserved2", C.c_int32),
+        ("prefetch_top_k", C.c_int32), ("n_partitions", C.c_int32),
+        ("visual_dim", C.c_int32), ("top_partitions", C.c_int32),
     ]
 
 
@@ -91,6 +93,9 @@ def load_library():
     L.mosaic_destroy.argtypes = [vp]
     L.mosaic_reset.argtypes = [vp]
     L.mosaic_ingest_frame.argtypes = [vp, vp, vp, i32]
+    L.mosaic_ingest_frame_visual.argtypes = [vp, vp, vp, vp, i32]
+    L.mosaic_get_partitions.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.mosaic_get_partition_selection.argtypes = [vp, i32, vp, vp, vp]
     L.mosaic_retrieve.argtypes = [vp, i32, vp, i32]
     L.mosaic_attend.argtypes = [vp, i32, vp, i32, vp, vp]
     L.mosaic_prefetch.argtypes = [vp, i32, vp, i32]
@@ -118,7 +123,7 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
                 slab_frames=0, cache_pages_per_unit=0, cache_fraction=0.0,
                 maint_mode=MAINT_OFF, init_clusters=0, split_iters=0, buffer_max=0,
                 tau_min=0.0, tau_max=0.0, tau_n0=1.0, aug_global_reps=0, aug_window_frames=0,
-                prefetch_top_k=0) -> Config:
+                prefetch_top_k=0, n_partitions=0, visual_dim=0, top_partitions=0) -> Config:
     c = Config()
     c.n_layers, c.n_q_heads, c.n_kv_heads = n_layers, n_q_heads, n_kv_heads
     c.head_dim, c.tokens_per_frame, c.max_frames = head_dim, tokens_per_frame, max_frames
@@ -132,6 +137,7 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
     c.tau_min, c.tau_max, c.tau_n0 = tau_min, tau_max, tau_n0
     c.aug_global_reps, c.aug_window_frames = aug_global_reps, aug_window_frames
     c.prefetch_top_k = prefetch_top_k
+    c.n_partitions, c.visual_dim, c.top_partitions = n_partitions, visual_dim, top_partitions
     return c
 
 
@@ -222,6 +228,18 @@ class Mosaic:
         self._check_tensor(v, shape, "v")
         self._check(self._L.mosaic_ingest_frame(self._h, _ptr(k), _ptr(v), n))
 
+    def ingest_frame_visual(self, k, v, e):
+        """Nested hierarchy: k, v as for ingest_frame; e: fp32 [n_frames][visual_dim]"""
+        c = self.cfg
+        n = k.shape[0]
+        shape = (n, c.n_layers, c.n_kv_heads, c.tokens_per_frame, c.head_dim)
+        self._check_tensor(k, shape, "k")
+        self._check_tensor(v, shape, "v")
+        if c.n_partitions > 0 and (e.device != self.device or e.dtype != self._torch.float32
+                                   or not e.is_contiguous() or tuple(e.shape) != (n, c.visual_dim)):
+            raise ValueError(f"e: need a contiguous float32 [{n}][{c.visual_dim}] tensor on {self.device}")
+        self._check(self._L.mosaic_ingest_frame_visual(self._h, _ptr(k), _ptr(v), _ptr(e), n))
+
     def _q_shape(self, layer, q):
         c = self.cfg
         tq = q.shape[-3]
@@ -310,6 +328,34 @@ class Mosaic:
                                                      buf.ctypes.data, cap, None))
             toks = [buf[h, : n_tok[h]].copy() for h in range(H)]
         return ids, n_ids, scores, toks
+
+    def partitions(self) -> dict:
+        """Nested hierarchy: frame_to_partition [n_frames]; visual_r [P][Dv], visual_n [P];
+        part_r [U][P][D], part_n [U][P]."""
+        c = self.cfg
+        F = int(self.stats().frames_ingested)
+        U, P = c.n_layers * c.n_kv_heads, c.n_partitions
+        out = {"frame_to_partition": np.empty(max(F, 1), np.int32),
+               "visual_r": np.empty((P, c.visual_dim), np.float64), "visual_n": np.empty(P, np.int32),
+               "part_r": np.empty((U, P, c.head_dim), np.float64), "part_n": np.empty((U, P), np.int32)}
+        self._check(self._L.mosaic_get_partitions(
+            self._h, out["frame_to_partition"].ctypes.data, out["visual_r"].ctypes.data,
+            out["visual_n"].ctypes.data, out["part_r"].ctypes.data, out["part_n"].ctypes.data))
+        out["frame_to_partition"] = out["frame_to_partition"][:F]
+        return out
+
+    def partition_selection(self, layer: int):
+        """First stage of the latest two-stage selection: part_ids [Hkv][top_partitions],
+        n_part_ids [Hkv], part_scores [Hkv][P]."""
+        c = self.cfg
+        H = c.n_kv_heads
+        tp = c.top_partitions or max(1, c.n_partitions // 4)
+        ids = np.empty((H, tp), dtype=np.int32)
+        n_ids = np.empty(H, dtype=np.int32)
+        sc = np.empty((H, c.n_partitions), dtype=np.float64)
+        self._check(self._L.mosaic_get_partition_selection(self._h, layer, ids.ctypes.data,
+                                                           n_ids.ctypes.data, sc.ctypes.data))
+        return ids, n_ids, sc
 
     def maintainer(self) -> dict:
         """State of the self-adaptive maintainer: var, lazy, resident [U][C]; n_slots, n_buf [U];

@@ -31,7 +31,8 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 struct Layout {
     size_t k_store, v_store, summ, r, rnorm, n, assign, pos, scores, ids, n_ids, sel_pages, n_sel,
         tok_scratch, part_o, part_ml, stage_k, stage_v, dest, var, lazy, resident, n_slots, buf_frame,
-        buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, vsumm, rvsum, rep_k, rep_v, aug_o, aug_ml, total;
+        buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, vsumm, rvsum, rep_k, rep_v, aug_o, aug_ml,
+        vemb, vr, vrn, vn, part, pr, prn, pn, pscores, pids, n_pids, total;
     size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_moves, host_nmoves, host_assign, host_dest, host_total;   // offsets into the pinned host arena
     long long part_entries;
     int Tp, impl, v_transposed;
@@ -50,6 +51,10 @@ int init_clusters_of(const mosaic_config &c) {
 int buffer_max_of(const mosaic_config &c) {
     if (c.maint_mode != MOSAIC_MAINT_DEFERRED) return 0;
     return c.buffer_max > 0 ? c.buffer_max : 32;
+}
+int top_partitions_of(const mosaic_config &c) {
+    if (c.n_partitions <= 0) return 0;
+    return c.top_partitions > 0 ? c.top_partitions : std::max(1, c.n_partitions / 4);
 }
 int warmup_of(const mosaic_config &c) {
     return c.warmup_frames > 0 ? c.warmup_frames : 2 * init_clusters_of(c);
@@ -81,6 +86,15 @@ int check_config(const mosaic_config *c, std::string &why) {
     if (c->aug_global_reps || c->aug_window_frames) {
         if (c->tier != MOSAIC_TIER_HBM) { why = "retrieval augmentation is available in the HBM tier only"; return MOSAIC_EINVAL; }
         if (c->maint_mode == MOSAIC_MAINT_DEFERRED) { why = "retrieval augmentation is not available with MOSAIC_MAINT_DEFERRED"; return MOSAIC_EINVAL; }
+    }
+    if (c->n_partitions < 0 || c->n_partitions > 64) { why = "n_partitions must be in 0..64"; return MOSAIC_EINVAL; }
+    if (c->n_partitions > 0) {
+        if (c->tier != MOSAIC_TIER_HBM) { why = "the nested hierarchy is available in the HBM tier only"; return MOSAIC_EINVAL; }
+        if (c->maint_mode != MOSAIC_MAINT_OFF || c->recluster_every != 0) { why = "the nested hierarchy excludes the maintainer and periodic re-clustering"; return MOSAIC_EINVAL; }
+        if (c->aug_global_reps || c->aug_window_frames) { why = "the nested hierarchy is not combined with retrieval augmentation"; return MOSAIC_EINVAL; }
+        if (c->n_clusters % c->n_partitions) { why = "n_clusters must be a multiple of n_partitions"; return MOSAIC_EINVAL; }
+        if (c->visual_dim < 1 || c->visual_dim > 4096) { why = "visual_dim must be in 1..4096"; return MOSAIC_EINVAL; }
+        if (c->top_partitions < 0 || c->top_partitions > c->n_partitions) { why = "top_partitions must be in 0..n_partitions"; return MOSAIC_EINVAL; }
     }
     const int W = warmup_of(*c);
     if (W < init_clusters_of(*c)) { why = "warmup_frames must be at least the number of initial clusters (one seed per cluster)"; return MOSAIC_EINVAL; }
@@ -172,6 +186,18 @@ Layout make_layout(const mosaic_config &c) {
     L.rep_v = take(c.aug_global_reps ? U * C * D * 4 : 0);
     L.aug_o = take(c.aug_global_reps ? U * (size_t)nt_max * kRowTile * D * 4 : 0);
     L.aug_ml = take(c.aug_global_reps ? U * (size_t)nt_max * 2 * kRowTile * 4 : 0);
+    const size_t P = (size_t)c.n_partitions, Dv = (size_t)c.visual_dim, tp = (size_t)top_partitions_of(c);
+    L.vemb = take(P ? F * Dv * 8 : 0);
+    L.vr = take(P * Dv * 8);
+    L.vrn = take(P * 8);
+    L.vn = take(P * 4);
+    L.part = take(P ? F * 4 : 0);
+    L.pr = take(U * P * D * 8);
+    L.prn = take(U * P * 8);
+    L.pn = take(U * P * 4);
+    L.pscores = take(U * P * 8);
+    L.pids = take(U * tp * 4);
+    L.n_pids = take(P ? U * 4 : 0);
     L.scores = take(U * (C + B) * 8);
     L.ids = take(U * k * 4);
     L.n_ids = take(U * 4);
@@ -322,6 +348,13 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.n_buf = (int *)(base + L.n_buf); dv.mt_cnt = (long long *)(base + L.mt_cnt);
     dv.mt_mem = (int *)(base + L.mt_mem); dv.mt_side = (int *)(base + L.mt_side);
     dv.mt_nrm = (double *)(base + L.mt_nrm);
+    dv.P = cfg->n_partitions; dv.Cs = dv.P > 0 ? dv.C / dv.P : 0; dv.Dv = cfg->visual_dim;
+    dv.top_p = top_partitions_of(*cfg);
+    dv.vemb = (double *)(base + L.vemb); dv.vr = (double *)(base + L.vr); dv.vrn = (double *)(base + L.vrn);
+    dv.vn = (int *)(base + L.vn); dv.part = (int *)(base + L.part);
+    dv.pr = (double *)(base + L.pr); dv.prn = (double *)(base + L.prn); dv.pn = (int *)(base + L.pn);
+    dv.pscores = (double *)(base + L.pscores); dv.pids = (int *)(base + L.pids);
+    dv.n_pids = (int *)(base + L.n_pids);
     dv.n_ids = (int *)(base + L.n_ids); dv.sel_pages = (int *)(base + L.sel_pages);
     dv.n_sel = (int *)(base + L.n_sel); dv.tok_scratch = (int *)(base + L.tok_scratch);
     dv.part_o = (float *)(base + L.part_o); dv.part_ml = (float *)(base + L.part_ml);
@@ -527,8 +560,26 @@ static int ingest_host(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, in
     return MOSAIC_OK;
 }
 
+static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, const float *e_dev,
+                         int32_t n_frames);
+
 int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, int32_t n_frames) {
     if (!ctx) return MOSAIC_EINVAL;
+    if (ctx->dv.P > 0) return fail(ctx, MOSAIC_EINVAL, "n_partitions > 0: frames are ingested with mosaic_ingest_frame_visual");
+    return ingest_frames(ctx, k_dev, v_dev, nullptr, n_frames);
+}
+
+int32_t mosaic_ingest_frame_visual(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, const float *e_dev,
+                                   int32_t n_frames) {
+    if (!ctx) return MOSAIC_EINVAL;
+    if (ctx->dv.P <= 0) return fail(ctx, MOSAIC_EINVAL, "n_partitions == 0: frames are ingested with mosaic_ingest_frame");
+    if (!e_dev) return fail(ctx, MOSAIC_EINVAL, "e_dev is NULL");
+    if ((uintptr_t)e_dev % 16) return fail(ctx, MOSAIC_EINVAL, "e_dev must be 16-byte aligned");
+    return ingest_frames(ctx, k_dev, v_dev, e_dev, n_frames);
+}
+
+static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, const float *e_dev,
+                         int32_t n_frames) {
     if (!k_dev || !v_dev) return fail(ctx, MOSAIC_EINVAL, "k_dev / v_dev is NULL");
     if (((uintptr_t)k_dev | (uintptr_t)v_dev) % 16) return fail(ctx, MOSAIC_EINVAL, "k_dev / v_dev must be 16-byte aligned");
     if (n_frames < 1) return fail(ctx, MOSAIC_EINVAL, "n_frames must be >= 1");
@@ -552,6 +603,10 @@ int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_de
         e = launch_store_summary(dv, (const char *)k_dev + in_off, (const char *)v_dev + in_off,
                                  (int)ctx->n_frames + done, nb, ctx->stream);
         if (e != hipSuccess) return fail_hip(ctx, e, "store_summary launch");
+        if (e_dev) {
+            e = launch_visual_store(dv, e_dev + (size_t)done * dv.Dv, (int)ctx->n_frames + done, nb, ctx->stream);
+            if (e != hipSuccess) return fail_hip(ctx, e, "visual_store launch");
+        }
         done += nb;
     }
     // temporally dependent part, in stream order
@@ -561,14 +616,26 @@ int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_de
         if (f < W) {
             f = std::min(end, W);
             if (f == W) {
+                if (dv.P > 0) {      // the visual level first: the units' K-means runs inside its partitions
+                    e = launch_visual_lloyd(dv, (int)W, ctx->iters, ctx->stream);
+                    if (e != hipSuccess) return fail_hip(ctx, e, "visual clustering launch");
+                }
                 e = launch_lloyd(dv, (int)W, ctx->iters, true, ctx->stream);
                 if (e != hipSuccess) return fail_hip(ctx, e, "initial clustering launch");
+                if (dv.P > 0) {
+                    e = launch_partition_reps(dv, (int)W, ctx->stream);
+                    if (e != hipSuccess) return fail_hip(ctx, e, "partition representatives launch");
+                }
                 ctx->stats.lloyd_runs += 1;
             }
             continue;
         }
         long long seg_end = end;
         if (every > 0) seg_end = std::min(end, (f / every + 1) * every);
+        if (dv.P > 0) {
+            e = launch_visual_assign(dv, (int)f, (int)seg_end, ctx->stream);
+            if (e != hipSuccess) return fail_hip(ctx, e, "visual assignment launch");
+        }
         e = launch_assign_update(dv, (int)f, (int)seg_end, ctx->stream);
         if (e != hipSuccess) return fail_hip(ctx, e, "assign_update launch");
         f = seg_end;
@@ -831,6 +898,51 @@ int32_t mosaic_get_maintainer(mosaic_ctx *ctx, double *var, int32_t *lazy, int32
     if (buf_frame && UB && (rc = d2h(ctx, buf_frame, dv.buf_frame, UB * 4)) != MOSAIC_OK) return rc;
     if (buf_owner && UB && (rc = d2h(ctx, buf_owner, dv.buf_owner, UB * 4)) != MOSAIC_OK) return rc;
     return sync(ctx);
+}
+
+int32_t mosaic_get_partitions(mosaic_ctx *ctx, int32_t *frame_to_partition, double *visual_r,
+                              int32_t *visual_n, double *part_r, int32_t *part_n) {
+    if (!ctx) return MOSAIC_EINVAL;
+    const DeviceView &dv = ctx->dv;
+    if (dv.P <= 0) return fail(ctx, MOSAIC_EINVAL, "n_partitions == 0: there is no visual level");
+    int rc = sync(ctx);
+    if (rc != MOSAIC_OK) return rc;
+    const bool ready = ctx->n_frames >= ctx->W;
+    if (frame_to_partition) {
+        if (!ready) {
+            for (long long f = 0; f < ctx->n_frames; ++f) frame_to_partition[f] = -1;
+        } else if ((rc = d2h(ctx, frame_to_partition, dv.part, (size_t)ctx->n_frames * 4)) != MOSAIC_OK) {
+            return rc;
+        }
+    }
+    if (!ready) {       // nothing has been built yet
+        if (visual_r) memset(visual_r, 0, (size_t)dv.P * dv.Dv * 8);
+        if (visual_n) memset(visual_n, 0, (size_t)dv.P * 4);
+        if (part_r) memset(part_r, 0, (size_t)dv.U * dv.P * dv.D * 8);
+        if (part_n) memset(part_n, 0, (size_t)dv.U * dv.P * 4);
+        return MOSAIC_OK;
+    }
+    if (visual_r && (rc = d2h(ctx, visual_r, dv.vr, (size_t)dv.P * dv.Dv * 8)) != MOSAIC_OK) return rc;
+    if (visual_n && (rc = d2h(ctx, visual_n, dv.vn, (size_t)dv.P * 4)) != MOSAIC_OK) return rc;
+    if (part_r && (rc = d2h(ctx, part_r, dv.pr, (size_t)dv.U * dv.P * dv.D * 8)) != MOSAIC_OK) return rc;
+    if (part_n && (rc = d2h(ctx, part_n, dv.pn, (size_t)dv.U * dv.P * 4)) != MOSAIC_OK) return rc;
+    return MOSAIC_OK;
+}
+
+int32_t mosaic_get_partition_selection(mosaic_ctx *ctx, int32_t layer, int32_t *part_ids,
+                                       int32_t *n_part_ids, double *part_scores) {
+    if (!ctx) return MOSAIC_EINVAL;
+    const DeviceView &dv = ctx->dv;
+    if (dv.P <= 0) return fail(ctx, MOSAIC_EINVAL, "n_partitions == 0: there is no visual level");
+    if (layer < 0 || layer >= dv.L) return fail(ctx, MOSAIC_EINVAL, "layer out of range");
+    if (ctx->sel_epoch[layer] != ctx->epoch) return fail(ctx, MOSAIC_ENOTREADY, "no current selection for this layer");
+    int rc = sync(ctx);
+    if (rc != MOSAIC_OK) return rc;
+    const size_t u0 = (size_t)layer * dv.Hkv;
+    if (part_ids && (rc = d2h(ctx, part_ids, dv.pids + u0 * dv.top_p, (size_t)dv.Hkv * dv.top_p * 4)) != MOSAIC_OK) return rc;
+    if (n_part_ids && (rc = d2h(ctx, n_part_ids, dv.n_pids + u0, (size_t)dv.Hkv * 4)) != MOSAIC_OK) return rc;
+    if (part_scores && (rc = d2h(ctx, part_scores, dv.pscores + u0 * dv.P, (size_t)dv.Hkv * dv.P * 8)) != MOSAIC_OK) return rc;
+    return MOSAIC_OK;
 }
 
 int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32_t *n_ids,

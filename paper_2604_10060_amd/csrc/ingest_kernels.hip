@@ -217,14 +217,19 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
     __shared__ double dot_sh[1024];
     __shared__ double red_v[4];
     __shared__ int red_i[4];
-    __shared__ double snorm_sh, nsum_sh[2], dsum_sh[2];
+    __shared__ double snorm_sh, nsum_sh[2], dsum_sh[2], psum_sh[2];
     __shared__ int win_sh, act_sh;
     __shared__ SplitShared<MAINT ? D : 16> split_sh;   // (small placeholder when the maintainer is off)
     double *r = dv.r + (size_t)u * C * D;
     double *rn = dv.rnorm + (size_t)u * C;
     int *n = dv.n + (size_t)u * C;
 
+    const bool nested = dv.P > 0;
     for (int f = f0; f < f1; ++f) {
+        // candidates: every cluster id, or (nested hierarchy, Sec. V-B) the ids of the frame's
+        // visual partition only
+        const int part_f = nested ? dv.part[f] : 0;
+        const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : C;
         if (tid < D) s_sh[tid] = dv.summ[((size_t)u * dv.F + f) * D + tid];
         __syncthreads();
         if (wave == 0) {
@@ -233,7 +238,7 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
             x = wave_sum(x);
             if (lane == 0) snorm_sh = sqrt(x);
         }
-        for (int j = row0; j < C; j += 16) {
+        for (int j = lo + row0; j < hi; j += 16) {
             double p = 0.0;
             if (n[j] > 0) {
                 const double *rj = r + (size_t)j * D + lr * EPL;
@@ -248,7 +253,7 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
         double bv = -INFINITY;
         int bi = 0x7fffffff;
         const double sn = snorm_sh;
-        for (int j = tid; j < C; j += kBlock) {
+        for (int j = lo + tid; j < hi; j += kBlock) {
             if (n[j] <= 0) continue;
             const double den = sn * rn[j];
             const double c = (sn == 0.0 || rn[j] == 0.0) ? 0.0 : dot_sh[j] / den;
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
         if (tid == 0) {
             for (int w = 1; w < 4; ++w)
                 if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
-            win_sh = bi == 0x7fffffff ? 0 : bi;
+            win_sh = bi == 0x7fffffff ? lo : bi;
         }
         __syncthreads();
         const int a = win_sh;
@@ -286,8 +291,29 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
             if (MAINT) dq = wave_sum(dq);
             if (lane == 0) { nsum_sh[wave] = sq; dsum_sh[wave] = dq; }
         }
+        // nested hierarchy: the partition's representative in this unit's key space follows the
+        // same running mean (Eq. 3 one level up)
+        int pn_i = 0;
+        if (nested) {
+            double *prow = dv.pr + ((size_t)u * dv.P + part_f) * D;
+            pn_i = dv.pn[(size_t)u * dv.P + part_f];
+            double psq = 0.0;
+            if (tid < D) {
+                const double pv = ((double)pn_i * prow[tid] + s_sh[tid]) / ((double)pn_i + 1.0);
+                prow[tid] = pv;
+                psq = pv * pv;
+            }
+            if (wave < 2) {
+                psq = wave_sum(psq);
+                if (lane == 0) psum_sh[wave] = psq;
+            }
+        }
         __syncthreads();   // all threads have read n[a] and written r before the scalars change
         if (tid == 0) {
+            if (nested) {
+                dv.prn[(size_t)u * dv.P + part_f] = sqrt(D > 64 ? psum_sh[0] + psum_sh[1] : psum_sh[0]);
+                dv.pn[(size_t)u * dv.P + part_f] = pn_i + 1;
+            }
             rn[a] = sqrt(D > 64 ? nsum_sh[0] + nsum_sh[1] : nsum_sh[0]);
             int act = kActAbsorb;
             if (MAINT) {
@@ -373,6 +399,81 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_seed(DeviceView dv, int W) {
 }
 
 // ---------------------------------------------------------------------------
+// Seeds under the nested hierarchy (Sec. V-B).  grid (U), 256 threads.
+// Cluster id j = p*Cs + jj belongs to visual partition p.  With np warm-up
+// frames in p and L = min(Cs, np), id j is started (n_j = 1 as a placeholder)
+// from the summary of the partition's member floor(jj*np/L) if jj < L and is
+// left empty otherwise.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_lloyd_seed_nested(DeviceView dv, int W) {
+    constexpr int EPL = D / 16;
+    const int u = blockIdx.x, tid = threadIdx.x, C = dv.C, Cs = dv.Cs;
+    const int lr = tid % 16, row0 = tid / 16;
+    __shared__ int np_sh[64];
+    if (tid < dv.P) {
+        int c = 0;
+        for (int f = 0; f < W; ++f) c += dv.part[f] == tid;
+        np_sh[tid] = c;
+    }
+    __syncthreads();
+    for (int j = row0; j < C; j += 16) {
+        const int p = j / Cs, jj = j - p * Cs, np = np_sh[p], L = min(Cs, np);
+        double *rj = dv.r + ((size_t)u * C + j) * D + lr * EPL;
+        if (jj >= L) {
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) rj[i] = 0.0;
+            if (lr == 0) { dv.rnorm[(size_t)u * C + j] = 0.0; dv.n[(size_t)u * C + j] = 0; }
+            continue;
+        }
+        const int want = (int)(((long long)jj * np) / L);   // index in the partition's member list
+        int src = 0, seen = 0;
+        for (int f = 0; f < W; ++f) {
+            if (dv.part[f] != p) continue;
+            if (seen == want) { src = f; break; }
+            ++seen;
+        }
+        const double *s = dv.summ + ((size_t)u * dv.F + src) * D + lr * EPL;
+        double sq = 0.0;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) { rj[i] = s[i]; sq += s[i] * s[i]; }
+        sq = group16_sum(sq);
+        if (lr == 0) { dv.rnorm[(size_t)u * C + j] = sqrt(sq); dv.n[(size_t)u * C + j] = 1; }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Partition representatives from the member lists: per unit and visual
+// partition the mean of the key summaries of the partition's frames, in
+// ascending frame order.  grid (U, P), 128 threads (thread d owns channel d).
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(128) void k_partition_reps(DeviceView dv, int n_frames) {
+    const int u = blockIdx.x, p = blockIdx.y, tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    __shared__ double nsum_sh[2];
+    double acc = 0.0;
+    int count = 0;
+    for (int f = 0; f < n_frames; ++f) {
+        if (dv.part[f] != p) continue;                   // workgroup-uniform
+        if (tid < D) acc += dv.summ[((size_t)u * dv.F + f) * D + tid];
+        ++count;
+    }
+    double sq = 0.0;
+    if (tid < D) {
+        const double rv = count > 0 ? acc / (double)count : 0.0;
+        dv.pr[((size_t)u * dv.P + p) * D + tid] = rv;
+        sq = rv * rv;
+    }
+    sq = wave_sum(sq);
+    if (lane == 0) nsum_sh[wave] = sq;
+    __syncthreads();
+    if (tid == 0) {
+        dv.prn[(size_t)u * dv.P + p] = sqrt(nsum_sh[0] + nsum_sh[1]);
+        dv.pn[(size_t)u * dv.P + p] = count;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Intra-cluster variance from the member lists (Eq. 2), after a K-means run.
 // grid (U, clusters), 256 threads: 16-lane groups take members in turn, the
 // group partials are added in a fixed order.
@@ -433,6 +534,9 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_fr
     const int *n = dv.n + (size_t)u * C;
     double bv = -INFINITY;
     int bi = 0x7fffffff;
+    // nested hierarchy: only the ids of the frame's visual partition are candidates
+    int plo = 0, phi = C;
+    if (dv.P > 0) { plo = dv.part[min(ft0 + fi, n_frames - 1)] * dv.Cs; phi = plo + dv.Cs; }
     for (int jb = cq * 4; jb < C; jb += 32) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
         const double *rj[4];
@@ -451,7 +555,7 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_fr
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int j = jb + q;
-            if (j < C && n[j] > 0) {
+            if (j >= plo && j < phi && n[j] > 0) {
                 const double c = (sn == 0.0 || rn[j] == 0.0) ? 0.0 : acc[q] / (sn * rn[j]);
                 if (better(c, j, bv, bi)) { bv = c; bi = j; }
             }
@@ -464,7 +568,9 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_fr
         bv = bv_sh[0][tid]; bi = bi_sh[0][tid];
         for (int q = 1; q < 8; ++q)
             if (better(bv_sh[q][tid], bi_sh[q][tid], bv, bi)) { bv = bv_sh[q][tid]; bi = bi_sh[q][tid]; }
-        dv.assign[(size_t)u * dv.F + ft0 + tid] = bi == 0x7fffffff ? 0 : bi;
+        int none = 0;
+        if (dv.P > 0) none = dv.part[ft0 + tid] * dv.Cs;
+        dv.assign[(size_t)u * dv.F + ft0 + tid] = bi == 0x7fffffff ? none : bi;
     }
 }
 
@@ -631,8 +737,13 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
     hipError_t e = hipSuccess;
     if (seed_from_warmup) {
         e = checked([&] {
-            if (dv.D == 64) k_lloyd_seed<64><<<dv.U, kBlock, 0, s>>>(dv, n_frames);
-            else k_lloyd_seed<128><<<dv.U, kBlock, 0, s>>>(dv, n_frames);
+            if (dv.P > 0) {
+                if (dv.D == 64) k_lloyd_seed_nested<64><<<dv.U, kBlock, 0, s>>>(dv, n_frames);
+                else k_lloyd_seed_nested<128><<<dv.U, kBlock, 0, s>>>(dv, n_frames);
+            } else {
+                if (dv.D == 64) k_lloyd_seed<64><<<dv.U, kBlock, 0, s>>>(dv, n_frames);
+                else k_lloyd_seed<128><<<dv.U, kBlock, 0, s>>>(dv, n_frames);
+            }
         });
         if (e != hipSuccess) return e;
     }
@@ -657,6 +768,14 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
         });
     }
     return e;
+}
+
+hipError_t launch_partition_reps(const DeviceView &dv, int n_frames, hipStream_t s) {
+    const dim3 g(dv.U, dv.P);
+    return checked([&] {
+        if (dv.D == 64) k_partition_reps<64><<<g, 128, 0, s>>>(dv, n_frames);
+        else k_partition_reps<128><<<g, 128, 0, s>>>(dv, n_frames);
+    });
 }
 
 } // namespace mosaic

@@ -77,6 +77,19 @@ struct DeviceView {
     float *rep_k, *rep_v;   // [U][C][D] fp32 pseudo-token tables: representative, value representative
     float *aug_o;     // [U][nt_max][16][D]  partial of the representatives' part, same form as part_o
     float *aug_ml;    // [U][nt_max][2][16]
+    // nested visual-semantic hierarchy (paper Sec. V-B, V-C); P = 0: flat index
+    int P, Cs, Dv, top_p;
+    double *vemb;     // [F][Dv]     visual embeddings of the frames (the visual level's states)
+    double *vr;       // [P][Dv]     visual centroids
+    double *vrn;      // [P]         their norms
+    int *vn;          // [P]         their sizes in frames
+    int *part;        // [F]         frame -> visual partition (shared by all units)
+    double *pr;       // [U][P][D]   partition representatives in the unit's key space
+    double *prn;      // [U][P]
+    int *pn;          // [U][P]
+    double *pscores;  // [U][P]      first-stage scores of the latest retrieval
+    int *pids;        // [U][top_p]  partitions it kept
+    int *n_pids;      // [U]
     // latest selection per unit
     double *scores;   // [U][SC]
     int *ids;         // [U][k]
@@ -126,6 +139,13 @@ hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const vo
 hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s);
 hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed_from_warmup,
                         hipStream_t s);
+// nested hierarchy: embeddings of frames f0.. into the visual level's state array
+hipError_t launch_visual_store(const DeviceView &dv, const float *e_in, int f0, int n_frames, hipStream_t s);
+// visual level: initial P-means over the first W embeddings / greedy assignment of frames f0..f1-1
+hipError_t launch_visual_lloyd(const DeviceView &dv, int W, int iters, hipStream_t s);
+hipError_t launch_visual_assign(const DeviceView &dv, int f0, int f1, hipStream_t s);
+// per-unit partition representatives recomputed from the member lists (after a K-means run)
+hipError_t launch_partition_reps(const DeviceView &dv, int n_frames, hipStream_t s);
 // write_pages = false (host tier): only scores and ids; the page list comes from the host
 hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                            int n_frames, int score_mode, bool write_pages, hipStream_t s);

@@ -29,7 +29,10 @@ template <> __device__ __forceinline__ double to_f64<unsigned short>(unsigned sh
 // follows runs out of LDS and registers.
 constexpr int kRetrBlock = 1024;
 
-template <typename E, int D>
+// NESTED (paper Sec. V-C "Two-Stage Retrieval"): the mean query is first scored against the
+// unit's P partition representatives; only the clusters of the top_p best partitions are then
+// scored (the rest count as empty: their rows are never read) and ranked.
+template <typename E, int D, bool NESTED>
 __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, const E *q, int Tq,
                                                          int n_frames, int score_mode, bool write_pages) {
     constexpr int BLK = kRetrBlock;
@@ -53,6 +56,9 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     __shared__ int ids_sh[1024];
     __shared__ int off_sh[1025];
     __shared__ int n_live_sh;
+    __shared__ double ps_sh[64];    // first-stage scores
+    __shared__ int psel_sh[64];     // partition kept by the first stage
+    __shared__ int p_live_sh;
     const double *r = dv.r + (size_t)u * C * D;
     const double *rn = dv.rnorm + (size_t)u * C;
     const int *n = dv.n + (size_t)u * C;
@@ -78,11 +84,26 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     if (w0 + tid < n_frames) wa = assign[w0 + tid];          // aug_window <= 1024 (checked at create)
     // representative rows of the first RPF passes (row index clamped, loads unconditional)
     double rpre[RPF][EPL];
+    if constexpr (!NESTED) {
 #pragma unroll
-    for (int i = 0; i < RPF; ++i) {
-        const double *rj = r + (size_t)min(row0 + RPP * i, C - 1) * D + lr * EPL;
+        for (int i = 0; i < RPF; ++i) {
+            const double *rj = r + (size_t)min(row0 + RPP * i, C - 1) * D + lr * EPL;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
+            for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
+        }
+    }
+    // first stage: the partition rows (P <= 64: one 16-lane group each), loaded up front as well
+    double ppre[EPL];
+    int pn_pre = 0;
+    double prn_pre = 0.0;
+    if constexpr (NESTED) {
+        const int pj = min(row0, dv.P - 1);
+        const double *prow = dv.pr + ((size_t)u * dv.P + pj) * D + lr * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) ppre[e] = prow[e];
+        pn_pre = dv.pn[(size_t)u * dv.P + pj];
+        prn_pre = dv.prn[(size_t)u * dv.P + pj];
+        if (tid == 0) p_live_sh = 0;
     }
     // mean query over the Tq tokens and the G query heads of this KV head: PARTS
     // threads per channel, each over a strided share of the Tq * G query rows, eight
@@ -113,6 +134,43 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         qbar[tid] = acc / (double)(Tq * G);
     }
     __syncthreads();
+    if constexpr (NESTED) {
+        const int P = dv.P, top_p = dv.top_p;
+        if (row0 < P) {
+            double p = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * ppre[e];
+            p = group16_sum(p);
+            if (lr == 0) {
+                double sc = -INFINITY;
+                if (pn_pre > 0) {
+                    sc = score_mode == 1 ? p : (prn_pre == 0.0 ? 0.0 : p / prn_pre);
+                    atomicAdd(&p_live_sh, 1);
+                }
+                ps_sh[row0] = sc;
+                dv.pscores[(size_t)u * P + row0] = sc;
+            }
+        }
+        __syncthreads();
+        if (tid < P) {      // rank by (score descending, id ascending); empty partitions carry -inf
+            const double sj = ps_sh[tid];
+            int c = 0;
+            for (int i = 0; i < P; ++i) {
+                const double si = ps_sh[i];
+                c += (si > sj) || (si == sj && i < tid);
+            }
+            const bool keep = sj != -INFINITY && c < top_p;
+            psel_sh[tid] = keep;
+            if (keep) dv.pids[(size_t)u * top_p + c] = tid;
+        }
+        const int n_pk = min(top_p, p_live_sh);
+        for (int i = n_pk + tid; i < top_p; i += BLK) dv.pids[(size_t)u * top_p + i] = -1;
+        if (tid == 0) dv.n_pids[u] = n_pk;
+        __syncthreads();
+        for (int j = tid; j < C; j += BLK)
+            if (!psel_sh[j / dv.Cs]) n_sh[j] = 0;        // pruned: treated as empty from here on
+        __syncthreads();
+    }
     // score_j = (qbar . r_j) / |r_j|   (plain dot product in score_mode 1)
     auto finish_row = [&](int j, double p) {
         p = group16_sum(p);
@@ -126,22 +184,34 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
             dv.scores[(size_t)u * C + j] = sc;
         }
     };
-#pragma unroll
-    for (int i = 0; i < RPF; ++i) {
-        const int j = row0 + RPP * i;
-        if (j < C) {
+    if constexpr (NESTED) {
+        for (int j = row0; j < C; j += RPP) {
             double p = 0.0;
+            if (n_sh[j] > 0) {                           // uniform within the 16-lane group
+                const double *rj = r + (size_t)j * D + lr * EPL;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rpre[i][e];
+                for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rj[e];
+            }
             finish_row(j, p);
         }
-    }
-    for (int j = row0 + RPP * RPF; j < C; j += RPP) {
-        const double *rj = r + (size_t)j * D + lr * EPL;
-        double p = 0.0;
+    } else {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rj[e];
-        finish_row(j, p);
+        for (int i = 0; i < RPF; ++i) {
+            const int j = row0 + RPP * i;
+            if (j < C) {
+                double p = 0.0;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rpre[i][e];
+                finish_row(j, p);
+            }
+        }
+        for (int j = row0 + RPP * RPF; j < C; j += RPP) {
+            const double *rj = r + (size_t)j * D + lr * EPL;
+            double p = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rj[e];
+            finish_row(j, p);
+        }
     }
     __syncthreads();
     // rank among non-empty clusters by (score descending, id ascending).  Empty
@@ -368,15 +438,22 @@ __global__ __launch_bounds__(kBlock) void k_expand_tok_idx(DeviceView dv, int u0
 
 } // namespace
 
+template <bool NESTED>
+static void launch_retrieve_t(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
+                              int n_frames, int score_mode, bool write_pages, hipStream_t s) {
+    if (dv.esize == 4) {
+        if (dv.D == 64) k_retrieve<float, 64, NESTED><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
+        else k_retrieve<float, 128, NESTED><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
+    } else {
+        if (dv.D == 64) k_retrieve<unsigned short, 64, NESTED><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
+        else k_retrieve<unsigned short, 128, NESTED><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
+    }
+}
+
 hipError_t launch_retrieve(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                            int n_frames, int score_mode, bool write_pages, hipStream_t s) {
-    if (dv.esize == 4) {
-        if (dv.D == 64) k_retrieve<float, 64><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
-        else k_retrieve<float, 128><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const float *)q, Tq, n_frames, score_mode, write_pages);
-    } else {
-        if (dv.D == 64) k_retrieve<unsigned short, 64><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
-        else k_retrieve<unsigned short, 128><<<n_units, kRetrBlock, 0, s>>>(dv, u0, (const unsigned short *)q, Tq, n_frames, score_mode, write_pages);
-    }
+    if (dv.P > 0) launch_retrieve_t<true>(dv, u0, n_units, q, Tq, n_frames, score_mode, write_pages, s);
+    else launch_retrieve_t<false>(dv, u0, n_units, q, Tq, n_frames, score_mode, write_pages, s);
     return hipGetLastError();
 }
 

@@ -1,0 +1,167 @@
+// Visual level of the nested visual-semantic hierarchy (paper Sec. V-B (1)):
+// the per-frame visual embeddings are clustered once per stream, with the same
+// modified K-means as the key summaries (cosine criterion, representative =
+// mean of the members, Eq. 1 / Eq. 3), into P partitions that every unit's
+// semantic clustering is then confined to.
+//   k_visual_store   embeddings (fp32) -> the visual level's fp64 state array
+//   k_visual_lloyd   initial P-means over the warm-up embeddings
+//   k_visual_assign  greedy assignment + running-mean update, frame by frame
+// One stream has one visual level, P <= 64 and a few hundred warm-up frames, so
+// each of the two clustering kernels is a single wide workgroup: a wavefront
+// per (frame, centroid) dot product, lanes striding the Dv channels.
+#include "mosaic_internal.h"
+
+namespace mosaic {
+
+namespace {
+
+constexpr int kVisBlock = 1024, kVisWaves = kVisBlock / 64;
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+__device__ __forceinline__ bool better(double v, int i, double bv, int bi) {
+    return v > bv || (v == bv && i < bi);
+}
+
+// grid (n_frames), 256 threads
+__global__ __launch_bounds__(256) void k_visual_store(DeviceView dv, const float *e_in, int f0) {
+    const int i = blockIdx.x;
+    const float *src = e_in + (size_t)i * dv.Dv;
+    double *dst = dv.vemb + (size_t)(f0 + i) * dv.Dv;
+    for (int d = threadIdx.x; d < dv.Dv; d += 256) dst[d] = (double)src[d];
+}
+
+// Sum of one value per thread over the workgroup, in a fixed order.  Every thread
+// gets the result.  red: kVisWaves doubles of LDS.
+__device__ __forceinline__ double block_sum(double x, double *red) {
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    x = wave_sum(x);
+    __syncthreads();                 // the previous use of red is over
+    if (lane == 0) red[wave] = x;
+    __syncthreads();
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < kVisWaves; ++w) t += red[w];
+    return t;
+}
+
+// The non-empty centroid most similar (cosine) to embedding e, ties to the lowest
+// id; `live_all` treats every centroid as non-empty.  Called by one wavefront.
+__device__ __forceinline__ int visual_nearest(const DeviceView &dv, const double *e, bool live_all) {
+    const int lane = threadIdx.x % 64, Dv = dv.Dv;
+    double en = 0.0;
+    for (int d = lane; d < Dv; d += 64) en += e[d] * e[d];
+    en = sqrt(wave_sum(en));
+    double bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int p = 0; p < dv.P; ++p) {
+        if (!live_all && dv.vn[p] <= 0) continue;        // wave-uniform
+        const double *rp = dv.vr + (size_t)p * Dv;
+        double x = 0.0;
+        for (int d = lane; d < Dv; d += 64) x += e[d] * rp[d];
+        x = wave_sum(x);
+        const double rn = dv.vrn[p];
+        const double c = (en == 0.0 || rn == 0.0) ? 0.0 : x / (en * rn);
+        if (better(c, p, bv, bi)) { bv = c; bi = p; }
+    }
+    return bi == 0x7fffffff ? 0 : bi;
+}
+
+// Initial clustering of the visual level over the first W embeddings: seeds =
+// embeddings of frames floor(p*W/P), every centroid live in the first
+// assignment round, `iters` rounds; a centroid left without members keeps its
+// vector and is skipped afterwards.  Members are summed in ascending frame order.
+// grid (1), kVisBlock threads.
+__global__ __launch_bounds__(kVisBlock) void k_visual_lloyd(DeviceView dv, int W, int iters) {
+    const int tid = threadIdx.x, wave = tid / 64, P = dv.P, Dv = dv.Dv;
+    __shared__ double red[kVisWaves];
+    for (int p = 0; p < P; ++p) {
+        const double *src = dv.vemb + (size_t)(((long long)p * W) / P) * Dv;
+        double sq = 0.0;
+        for (int d = tid; d < Dv; d += kVisBlock) { const double v = src[d]; dv.vr[(size_t)p * Dv + d] = v; sq += v * v; }
+        sq = block_sum(sq, red);
+        if (tid == 0) { dv.vrn[p] = sqrt(sq); dv.vn[p] = 0; }
+    }
+    __syncthreads();
+    for (int it = 0; it < iters; ++it) {
+        for (int f = wave; f < W; f += kVisWaves) {
+            const int a = visual_nearest(dv, dv.vemb + (size_t)f * Dv, it == 0);
+            if (tid % 64 == 0) dv.part[f] = a;
+        }
+        __syncthreads();
+        for (int p = 0; p < P; ++p) {
+            int count = 0;
+            for (int f = 0; f < W; ++f) count += dv.part[f] == p;
+            if (count == 0) {                            // workgroup-uniform
+                if (tid == 0) dv.vn[p] = 0;
+                continue;
+            }
+            double sq = 0.0;
+            for (int d = tid; d < Dv; d += kVisBlock) {
+                double acc = 0.0;
+                for (int f = 0; f < W; ++f)
+                    if (dv.part[f] == p) acc += dv.vemb[(size_t)f * Dv + d];
+                const double rv = acc / (double)count;
+                dv.vr[(size_t)p * Dv + d] = rv;
+                sq += rv * rv;
+            }
+            sq = block_sum(sq, red);
+            if (tid == 0) { dv.vrn[p] = sqrt(sq); dv.vn[p] = count; }
+        }
+        __syncthreads();
+    }
+}
+
+// Frames f0..f1-1, in order: partition = most similar non-empty visual centroid,
+// which then moves by Eq. 3.  grid (1), kVisBlock threads; wavefront 0 decides.
+__global__ __launch_bounds__(kVisBlock) void k_visual_assign(DeviceView dv, int f0, int f1) {
+    const int tid = threadIdx.x, wave = tid / 64, Dv = dv.Dv;
+    __shared__ double red[kVisWaves];
+    __shared__ int win_sh;
+    for (int f = f0; f < f1; ++f) {
+        const double *e = dv.vemb + (size_t)f * Dv;
+        if (wave == 0) {
+            const int a = visual_nearest(dv, e, false);
+            if (tid == 0) { win_sh = a; dv.part[f] = a; }
+        }
+        __syncthreads();
+        const int a = win_sh;
+        const double na = (double)dv.vn[a];
+        double sq = 0.0;
+        for (int d = tid; d < Dv; d += kVisBlock) {
+            // Eq. 3, each operation rounded separately
+            const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, dv.vr[(size_t)a * Dv + d]), e[d]), na + 1.0);
+            dv.vr[(size_t)a * Dv + d] = rv;
+            sq += rv * rv;
+        }
+        sq = block_sum(sq, red);     // (its barriers also order the reads of vn[a] before the update)
+        if (tid == 0) { dv.vrn[a] = sqrt(sq); dv.vn[a] = (int)na + 1; }
+        __syncthreads();
+    }
+}
+
+hipError_t after_launch() {
+    return hipGetLastError();
+}
+
+} // namespace
+
+hipError_t launch_visual_store(const DeviceView &dv, const float *e_in, int f0, int n_frames, hipStream_t s) {
+    k_visual_store<<<n_frames, 256, 0, s>>>(dv, e_in, f0);
+    return after_launch();
+}
+
+hipError_t launch_visual_lloyd(const DeviceView &dv, int W, int iters, hipStream_t s) {
+    k_visual_lloyd<<<1, kVisBlock, 0, s>>>(dv, W, iters);
+    return after_launch();
+}
+
+hipError_t launch_visual_assign(const DeviceView &dv, int f0, int f1, hipStream_t s) {
+    k_visual_assign<<<1, kVisBlock, 0, s>>>(dv, f0, f1);
+    return after_launch();
+}
+
+} // namespace mosaic

@@ -432,3 +432,164 @@ def run_augmented(wl, window_frames, global_reps, units=None, device="cuda:0", d
             query_augmented_with_parity(m, wl, q, oracles, K[:f], V[:f], rep, window_frames, global_reps)
     m.close()
     return rep
+
+
+# ---------------------------------------------------------------------------
+# Nested visual-semantic hierarchy and two-stage retrieval (paper Sec. V-B, V-C)
+# ---------------------------------------------------------------------------
+def run_nested(wl, n_partitions, top_partitions, units=None, device="cuda:0", batch_pattern=(1, 3, 8, 2, 16),
+               n_questions=2, decode_steps=2, score_mode=0):
+    """Stream `wl` (with visual embeddings) through the library with the nested hierarchy on and
+    through the oracle (one visual-level unit per stream, one nested semantic unit per checked
+    (layer, head)); compare partitions, assignments and state after every library call, then the
+    two-stage selection, the gathered tokens and the attention output of a few questions."""
+    assert wl.visual_dim > 0
+    P, Dv, F = n_partitions, wl.visual_dim, wl.n_frames
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, F)
+    E = st.embeddings(0, F)
+    Kd, Vd, Ed = K.to(device), V.to(device), E.to(device)
+    E64 = E.numpy().astype(np.float64)
+    m = binding.Mosaic(binding.config_for(wl, n_partitions=P, visual_dim=Dv, top_partitions=top_partitions,
+                                          score_mode=score_mode), device=device)
+    rep = Report()
+    if units is None:
+        units = [(l, h) for l in range(wl.n_layers) for h in range(wl.n_kv_heads)]
+    vis = orc.OracleUnit(P, Dv, 1, F, wl.warmup, wl.lloyd_iters)
+    sem = {(l, h): orc.OracleUnit(wl.n_clusters, wl.head_dim, wl.tokens_per_frame, F, wl.warmup,
+                                  wl.lloyd_iters, 0, score_mode, nested=P) for (l, h) in units}
+    Kcpu = {key: inputs.unit_pages(K, *key) for key in units}
+    part_o = np.full(F, -1, dtype=np.int32)
+    W = wl.warmup
+    f, bi = 0, 0
+    while f < F:
+        limit = W if f < W else F
+        nb = min(batch_pattern[bi % len(batch_pattern)], limit - f)
+        bi += 1
+        m.ingest_frame_visual(Kd[f:f + nb].contiguous(), Vd[f:f + nb].contiguous(), Ed[f:f + nb].contiguous())
+        st_lib = m.partitions()
+        A = m.assignments()
+        R, N = m.centroids()
+        for ff in range(f, f + nb):
+            # visual level
+            force = -1
+            if vis.ready:
+                dec = vis.peek(E64[ff][None, :])
+                got = int(st_lib["frame_to_partition"][ff])
+                rep.online_decisions += 1
+                if got != dec.winner:
+                    assert dec.gap < NEAR_TIE and got == dec.runner_up, (
+                        f"frame {ff}: library partition {got}, oracle {dec.winner} (gap {dec.gap:.3e})")
+                    rep.forced_near_ties += 1
+                    force = got
+            vis.ingest(E64[ff][None, :], force)
+            if vis.ready:
+                part_o[: ff + 1] = vis.assignments()
+            # semantic level of every checked unit
+            for key, o in sem.items():
+                u = key[0] * wl.n_kv_heads + key[1]
+                force = -1
+                if o.ready:
+                    dec = o.peek_nested(Kcpu[key][ff], int(part_o[ff]))
+                    got = int(A[u, ff])
+                    rep.online_decisions += 1
+                    if got != dec.winner:
+                        assert dec.gap < NEAR_TIE and got == dec.runner_up, (
+                            f"unit {key} frame {ff}: library chose {got}, oracle {dec.winner} (gap {dec.gap:.3e})")
+                        rep.forced_near_ties += 1
+                        force = got
+                o.ingest_nested(Kcpu[key][ff], part_o, force)
+        f += nb
+        if f == W:
+            rep.lloyd_runs += 1
+        if not vis.ready:
+            assert np.all(st_lib["frame_to_partition"] == -1)
+            continue
+        where = f"after {f} frames"
+        assert np.array_equal(st_lib["frame_to_partition"], part_o[:f]), (
+            f"{where}: partitions differ (smallest visual K-means gap {vis.lloyd_min_gap:.3e})")
+        np.testing.assert_array_equal(st_lib["visual_n"], vis.sizes())
+        vlive = vis.sizes() > 0
+        np.testing.assert_allclose(st_lib["visual_r"][vlive], vis.centroids()[vlive], rtol=1e-9, atol=1e-12)
+        for key, o in sem.items():
+            u = key[0] * wl.n_kv_heads + key[1]
+            assert np.array_equal(A[u, :f], o.assignments()), (
+                f"unit {key} {where}: assignments differ (smallest K-means gap {o.lloyd_min_gap:.3e})")
+            np.testing.assert_array_equal(A[u, :f] // (wl.n_clusters // P), part_o[:f])
+            np.testing.assert_array_equal(N[u], o.sizes())
+            live = o.sizes() > 0
+            Ro = o.centroids()
+            rel = np.abs(R[u][live] - Ro[live]).max() / max(np.abs(Ro[live]).max(), 1e-30)
+            rep.max_centroid_rel = max(rep.max_centroid_rel, float(rel))
+            assert rel < 1e-9, f"unit {key} {where}: centroid rel err {rel:.3e}"
+            for p in range(P):
+                rp, cnt = o.partition_rep(p)
+                assert st_lib["part_n"][u, p] == cnt
+                if cnt:
+                    np.testing.assert_allclose(st_lib["part_r"][u, p], rp, rtol=1e-9, atol=1e-12)
+    tag = 0
+    for tq in [wl.question_tokens] * n_questions + [1] * decode_steps:
+        q = st.question(st.draw_scene(), tq, tag).to(device)
+        tag += 1
+        query_nested_with_parity(m, wl, q, sem, K, V, rep, P, top_partitions)
+    m.close()
+    return rep
+
+
+def query_nested_with_parity(m, wl, q, oracles, K, V, rep, P, top_p):
+    L, G = wl.n_layers, wl.group
+    outs, lses = [], []
+    sel, psel = {}, {}
+    for l in range(L):
+        m.retrieve(l, q[l].contiguous())
+        o_, l_ = m.attend(l, q[l].contiguous())
+        outs.append(o_); lses.append(l_)
+        sel[l] = m.selection(l)
+        psel[l] = m.partition_selection(l)
+    torch.cuda.synchronize()
+    out_h = torch.stack(outs).float().cpu().numpy().astype(np.float64)
+    lse_h = torch.stack(lses).cpu().numpy().astype(np.float64)
+    q_h = q.float().cpu().numpy().astype(np.float64)
+    for (l, h), o in oracles.items():
+        ids, n_ids, scores, toks = sel[l]
+        pids, n_pids, pscores = psel[l]
+        want = o.retrieve_nested(q_h[l], h, G, top_p, wl.top_k)
+        plive = np.isfinite(want["part_scores"])
+        np.testing.assert_allclose(pscores[h][plive], want["part_scores"][plive], rtol=1e-9, atol=1e-12)
+        assert np.all(np.isneginf(pscores[h][~plive]))
+        assert n_pids[h] == len(want["part_ids"]) and np.all(pids[h, n_pids[h]:] == -1)
+        if not np.array_equal(pids[h, : n_pids[h]], want["part_ids"]):
+            # only a near-tie between partitions excuses it; the second stage then has other candidates
+            assert want["gap_p"] < NEAR_TIE or _min_rel_gap(want["part_scores"][plive]) < NEAR_TIE, (
+                f"unit {(l, h)}: partitions {pids[h, : n_pids[h]]} != oracle {want['part_ids']}")
+            rep.topk_near_ties += 1
+            continue
+        cand = np.isfinite(want["scores"])
+        assert np.array_equal(np.isfinite(scores[h]), cand), f"unit {(l, h)}: candidate sets differ"
+        assert int(cand.sum()) == want["n_candidates"]
+        np.testing.assert_allclose(scores[h][cand], want["scores"][cand], rtol=1e-9, atol=1e-12)
+        got_ids = ids[h, : n_ids[h]]
+        assert n_ids[h] == len(want["ids"]) and np.all(ids[h, n_ids[h]:] == -1)
+        tok_o = want["tok_idx"]
+        if not np.array_equal(got_ids, want["ids"]):
+            assert _min_rel_gap(want["scores"][cand]) < NEAR_TIE, (
+                f"unit {(l, h)}: ids {got_ids} != oracle {want['ids']} with no near-tie")
+            rep.topk_near_ties += 1
+            tok_o = o.gather(got_ids)
+        np.testing.assert_array_equal(toks[h], tok_o)
+        Ku = inputs.unit_pages(K, l, h).reshape(-1, wl.head_dim)
+        Vu = inputs.unit_pages(V, l, h).reshape(-1, wl.head_dim)
+        ref, ref_lse = orc.attend(q_h[l], Ku, Vu, tok_o, h, G)
+        err = np.abs(out_h[l][:, h * G:(h + 1) * G, :] - ref).max()
+        lerr = np.abs(lse_h[l][:, h * G:(h + 1) * G] - ref_lse).max()
+        rep.max_out_err = max(rep.max_out_err, float(err))
+        rep.max_lse_err = max(rep.max_lse_err, float(lerr))
+        assert err <= OUT_TOL[wl.kv_dtype], f"unit {(l, h)}: attention max-abs err {err:.3e}"
+        assert lerr <= LSE_TOL[wl.kv_dtype], f"unit {(l, h)}: lse max-abs err {lerr:.3e}"
+
+
+def _min_rel_gap(x):
+    s = np.sort(np.asarray(x, dtype=np.float64))[::-1]
+    if len(s) < 2:
+        return np.inf
+    return float((np.abs(np.diff(s)) / np.maximum(np.maximum(np.abs(s[1:]), np.abs(s[:-1])), 1e-30)).min())

@@ -493,3 +493,96 @@ def test_prefetch_errors():
     m.retrieve(0, q[0].contiguous()); m.attend(0, q[0].contiguous())
     torch.cuda.synchronize()
     m.close()
+
+
+# ---------------------------------------------------------------------------
+# Nested visual-semantic hierarchy and two-stage retrieval (paper Sec. V-B, V-C)
+# ---------------------------------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("score_mode", [0, 1])
+def test_nested_fp32(score_mode):
+    wl = inputs.CONFIGS[0].scaled(name="nested_fp32", visual_dim=24, n_visual=4, n_clusters=16, top_k=4)
+    rep = harness.run_nested(wl, 4, 2, score_mode=score_mode)
+    _report(rep)
+    assert rep.max_out_err <= 1e-4 and rep.online_decisions > 0
+
+
+@pytest.mark.gpu
+def test_nested_bf16_ragged_visual_dim_and_short_partitions():
+    """Dv not a multiple of 64, more ids per partition than some partitions have warm-up members
+    (ids that are never started), a question spanning several row tiles, and decode steps."""
+    wl = inputs.CONFIGS[1].scaled(name="nested_bf16", n_frames=200, n_scenes=14, n_clusters=48, top_k=5,
+                                  question_tokens=21, visual_dim=100, n_visual=5, warmup_frames=60)
+    rep = harness.run_nested(wl, 6, 2, units=[(0, 0), (0, 2), (0, 3)], decode_steps=3)
+    _report(rep)
+    assert rep.max_out_err <= 2e-2
+
+
+@pytest.mark.gpu
+def test_nested_two_layers_all_partitions_kept_equals_flat_selection_over_nested_clusters():
+    """top_partitions = P: the first stage prunes nothing, so every non-empty cluster is scored."""
+    wl = inputs.CONFIGS[0].scaled(name="nested_2l", n_layers=2, visual_dim=64, n_visual=3, n_clusters=12,
+                                  top_k=3)
+    rep = harness.run_nested(wl, 3, 3)
+    _report(rep)
+    assert rep.max_out_err <= 1e-4
+
+
+@pytest.mark.gpu
+def test_nested_single_partition_is_bitwise_the_flat_index():
+    wl = inputs.CONFIGS[0].scaled(name="nested_p1", visual_dim=8)
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    E = st.embeddings(0, wl.n_frames).to(DEV)
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    flat = binding.Mosaic(binding.config_for(wl), device=DEV)
+    nest = binding.Mosaic(binding.config_for(wl, n_partitions=1, visual_dim=8, top_partitions=1), device=DEV)
+    flat.ingest_frame(Kd, Vd)
+    nest.ingest_frame_visual(Kd, Vd, E)
+    np.testing.assert_array_equal(flat.assignments(), nest.assignments())
+    Rf, Nf = flat.centroids()
+    Rn, Nn = nest.centroids()
+    np.testing.assert_array_equal(Rf, Rn)
+    np.testing.assert_array_equal(Nf, Nn)
+    q = st.question(0, 4, 0).to(DEV)[0].contiguous()
+    for m in (flat, nest):
+        m.retrieve(0, q)
+    of, lf = flat.attend(0, q)
+    on, ln = nest.attend(0, q)
+    torch.cuda.synchronize()
+    a, b = flat.selection(0), nest.selection(0)
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_array_equal(a[2], b[2])
+    assert torch.equal(of, on) and torch.equal(lf, ln)
+    flat.close(); nest.close()
+
+
+@pytest.mark.gpu
+def test_nested_config_and_call_errors():
+    wl = inputs.CONFIGS[0].scaled(visual_dim=8)
+    ok = dict(n_partitions=4, visual_dim=8, top_partitions=2)
+    for bad in (dict(n_partitions=3), dict(n_partitions=65), dict(visual_dim=0), dict(visual_dim=5000),
+                dict(top_partitions=5), dict(tier=binding.TIER_HOST), dict(recluster_every=64),
+                dict(aug_window_frames=4),
+                dict(maint_mode=binding.MAINT_EAGER, init_clusters=4, tau_n0=8.0)):
+        kw = dict(ok); kw.update(bad)
+        with pytest.raises(binding.MosaicError) as ei:
+            binding.workspace_sizes(binding.config_for(wl, **kw))
+        assert ei.value.code == binding.EINVAL
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, 2)
+    E = st.embeddings(0, 2).to(DEV)
+    m = binding.Mosaic(binding.config_for(wl, **ok), device=DEV)
+    with pytest.raises(binding.MosaicError) as ei:
+        m.ingest_frame(K.to(DEV), V.to(DEV))                 # needs the embeddings
+    assert ei.value.code == binding.EINVAL
+    m.ingest_frame_visual(K.to(DEV), V.to(DEV), E)
+    assert np.all(m.partitions()["frame_to_partition"] == -1)   # still warming up
+    m.close()
+    m = binding.Mosaic(binding.config_for(wl), device=DEV)
+    with pytest.raises(binding.MosaicError) as ei:
+        m.ingest_frame_visual(K.to(DEV), V.to(DEV), E)       # flat index: no visual level
+    assert ei.value.code == binding.EINVAL
+    with pytest.raises(binding.MosaicError):
+        m.partitions()
+    m.close()

@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "maintainer", "prefetch"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "maintainer", "prefetch", "nested"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count")
     ap.add_argument("--all-layers-call", action="store_true",
@@ -492,6 +492,127 @@ def run_maintainer_leg(layers=4, query_every=64, decode=64, check=True):
             "split_reduction_by_deferral": round(1.0 - tot_d / tot_e, 4) if tot_e else None}
 
 
+def run_nested_leg(layers=4, steps=64, n_quality=24, check=True):
+    """Nested visual-semantic hierarchy and two-stage retrieval (Sec. V-B, V-C) on the config-2 stream
+    recipe, `layers` of its 28 layers, 512 clusters per unit and top-16 retrieval, against the flat
+    index on the same stream: 16 visual partitions of 32 cluster ids, the 4 best partitions kept by
+    the first stage (128 instead of 512 candidates); 1024-wide synthetic visual embeddings from 16
+    appearance classes whose scenes share half of their key centre.  Reports ingest rates, the time of a retrieve call and of a decode step,
+    candidates scored, and -- reported, never gated -- how many of the frames of the scene a
+    question is about each index retrieves."""
+    import torch
+    from paper_2604_10060_amd import binding, inputs
+    dev = "cuda:0"
+    P, top_p = 16, 4
+    wl = inputs.CONFIGS[2].scaled(name="cfg2_recipe_nested", n_layers=layers, n_clusters=512, top_k=16,
+                                  recluster_every=0, visual_dim=1024, n_visual=16, visual_key_corr=0.5)
+    L, Hq, D, T, F, H = wl.n_layers, wl.n_q_heads, wl.head_dim, wl.tokens_per_frame, wl.n_frames, wl.n_kv_heads
+    st = inputs.SceneStream(wl, device=dev)
+    shape = (F, L, H, T, D)
+    K_all = torch.empty(shape, dtype=wl.torch_dtype, device=dev)
+    V_all = torch.empty(shape, dtype=wl.torch_dtype, device=dev)
+    for f in range(F):
+        K_all[f], V_all[f] = st.frame(f)
+    E_all = st.embeddings(0, F).contiguous()
+    n_q = steps + 8 + n_quality
+    scenes = [st.draw_scene() for _ in range(n_q)]
+    q_dec = torch.stack([st.question(scenes[i], 1, 1 + i) for i in range(n_q)])   # [n][L][1][Hq][D]
+    out = torch.empty((L, 1, Hq, D), dtype=wl.torch_dtype, device=dev)
+    lse = torch.empty((L, 1, Hq), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    lq = Hq * D * 2
+
+    def step(m, i, attend=True):
+        qp = q_dec.data_ptr() + i * L * lq
+        for l in range(L):
+            m.retrieve_raw(l, qp + l * lq, 1)
+            if attend:
+                m.attend_raw(l, qp + l * lq, 1, out.data_ptr() + l * lq, lse.data_ptr() + l * Hq * 4)
+
+    res = {}
+    for name in ("flat", "nested"):
+        nested = name == "nested"
+        kw = dict(n_partitions=P, visual_dim=wl.visual_dim, top_partitions=top_p) if nested else {}
+        m = binding.Mosaic(binding.config_for(wl, **kw), device=dev)
+        fps = {}
+        for batch in (16, 1):
+            m.reset()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for f in range(0, F, batch):
+                nb = min(batch, F - f)
+                if nested:
+                    m.ingest_frame_visual(K_all[f:f + nb], V_all[f:f + nb], E_all[f:f + nb])
+                else:
+                    m.ingest_frame(K_all[f:f + nb], V_all[f:f + nb])
+            torch.cuda.synchronize()
+            fps[batch] = F / (time.perf_counter() - t)
+        times = {}
+        for what, attend in (("retrieve_call_us", False), ("decode_step_us", True)):
+            for i in range(8):
+                step(m, i, attend)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for i in range(steps):
+                step(m, 8 + i, attend)
+            torch.cuda.synchronize()
+            times[what] = (time.perf_counter() - t) / steps * 1e6 / (1 if attend else L)
+        # what the selection looks like (reported, not gated)
+        cand, hit, toks = [], [], []
+        for i in range(n_quality):
+            qi = steps + 8 + i
+            step(m, qi, attend=False)
+            want = np.flatnonzero(st.scene_of_frame == scenes[qi])
+            for l in range(L):
+                ids, n_ids, scores, tk = m.selection(l)
+                for h in range(H):
+                    cand.append(int(np.isfinite(scores[h]).sum()))
+                    got = np.unique(tk[h] // T)
+                    hit.append(len(np.intersect1d(got, want)) / max(len(want), 1))
+                    toks.append(len(tk[h]))
+        _, sizes = m.centroids()
+        res[name] = {"ingest_frames_per_s": round(fps[1], 1), "ingest_frames_per_s_batch16": round(fps[16], 1),
+                     "retrieve_call_us": round(times["retrieve_call_us"], 2),
+                     "decode_step_us": round(times["decode_step_us"], 2),
+                     "candidates_scored_mean": round(float(np.mean(cand)), 1),
+                     "non_empty_clusters_mean": round(float((sizes > 0).sum(axis=1).mean()), 1),
+                     "question_scene_frames_retrieved_mean": round(float(np.mean(hit)), 4),
+                     "retrieved_tokens_mean": round(float(np.mean(toks)), 1)}
+        if check and nested:
+            from oracle import mosaic_oracle as orc
+            l0, h0 = layers - 1, 1
+            u = l0 * H + h0
+            E64 = E_all.cpu().numpy().astype(np.float64)
+            vis = orc.OracleUnit(P, wl.visual_dim, 1, F, wl.warmup, wl.lloyd_iters)
+            o = orc.OracleUnit(wl.n_clusters, D, T, F, wl.warmup, wl.lloyd_iters, 0, 0, nested=P)
+            Ku = inputs.unit_pages(K_all, l0, h0)
+            part = np.full(F, -1, dtype=np.int32)
+            for f in range(F):
+                vis.ingest(E64[f][None, :])
+                if vis.ready:
+                    part[: f + 1] = vis.assignments()
+                o.ingest_nested(Ku[f], part)
+            same_p = bool(np.array_equal(m.partitions()["frame_to_partition"], vis.assignments()))
+            same_a = bool(np.array_equal(m.assignments()[u], o.assignments()))
+            qi = steps + 8 + n_quality - 1
+            ids, n_ids, _, _ = m.selection(l0)
+            want = o.retrieve_nested(q_dec[qi, l0].float().cpu().numpy().astype(np.float64), h0, wl.group,
+                                     top_p, wl.top_k)
+            same_s = bool(np.array_equal(ids[h0, : n_ids[h0]], want["ids"]))
+            assert same_p and same_a and same_s, "nested leg: partitions, assignments or selection differ from the oracle"
+            res[name]["parity_spot_check"] = {"unit": [l0, h0], "partitions_equal": same_p,
+                                              "assignments_equal": same_a, "selection_equal": same_s}
+        m.close()
+        del m
+    del K_all, V_all
+    torch.cuda.empty_cache()
+    return {"config": {"workload": wl.name, "layers": layers, "frames": F, "tokens_per_frame": T,
+                       "clusters": wl.n_clusters, "top_k": wl.top_k, "partitions": P, "top_partitions": top_p,
+                       "visual_dim": wl.visual_dim, "appearance_classes": wl.n_visual,
+                       "visual_key_corr": wl.visual_key_corr},
+            "flat": res["flat"], "nested": res["nested"]}
+
+
 def run_prefetch_leg(layers=3, steps=96, rhos=(0.95, 0.7)):
     """Overlap-aware cross-layer prefetch (Sec. VII-B) on the config-3 host tier, `layers` of its 28
     layers, with adjacent layers' states correlated by rho (the stream generator's stand-in for the
@@ -757,6 +878,9 @@ def main():
     if args.workload == "maintainer":
         print(json.dumps(run_maintainer_leg(layers=args.layers or 4, check=args.check_units > 0)))
         return
+    if args.workload == "nested":
+        print(json.dumps(run_nested_leg(layers=args.layers or 4, check=args.check_units > 0)))
+        return
     if args.workload == "cfg3":
         print(json.dumps(run_host_leg(layers=args.layers or 2, check=args.check_units > 0)))
         return
@@ -808,6 +932,10 @@ def main():
             extra["next1_maintainer"] = run_maintainer_leg()
         except Exception as ex:                      # noqa: BLE001
             extra["next1_maintainer"] = {"error": repr(ex)[:300]}
+        try:
+            extra["next4_nested_index"] = run_nested_leg()
+        except Exception as ex:                      # noqa: BLE001
+            extra["next4_nested_index"] = {"error": repr(ex)[:300]}
         try:
             import torch
             torch.cuda.empty_cache()

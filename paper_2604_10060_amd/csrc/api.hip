@@ -603,8 +603,10 @@ static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, 
         e = launch_store_summary(dv, (const char *)k_dev + in_off, (const char *)v_dev + in_off,
                                  (int)ctx->n_frames + done, nb, ctx->stream);
         if (e != hipSuccess) return fail_hip(ctx, e, "store_summary launch");
-        if (e_dev) {
-            e = launch_visual_store(dv, e_dev + (size_t)done * dv.Dv, (int)ctx->n_frames + done, nb, ctx->stream);
+        // embeddings of warm-up frames are only filed; later ones are filed by the visual assignment
+        const long long first = ctx->n_frames + done, n_warm = std::min<long long>(first + nb, ctx->W) - first;
+        if (e_dev && n_warm > 0) {
+            e = launch_visual_store(dv, e_dev + (size_t)done * dv.Dv, (int)first, (int)n_warm, ctx->stream);
             if (e != hipSuccess) return fail_hip(ctx, e, "visual_store launch");
         }
         done += nb;
@@ -633,7 +635,7 @@ static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, 
         long long seg_end = end;
         if (every > 0) seg_end = std::min(end, (f / every + 1) * every);
         if (dv.P > 0) {
-            e = launch_visual_assign(dv, (int)f, (int)seg_end, ctx->stream);
+            e = launch_visual_assign(dv, e_dev + (size_t)(f - ctx->n_frames) * dv.Dv, (int)f, (int)seg_end, ctx->stream);
             if (e != hipSuccess) return fail_hip(ctx, e, "visual assignment launch");
         }
         e = launch_assign_update(dv, (int)f, (int)seg_end, ctx->stream);

@@ -143,7 +143,8 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
 hipError_t launch_visual_store(const DeviceView &dv, const float *e_in, int f0, int n_frames, hipStream_t s);
 // visual level: initial P-means over the first W embeddings / greedy assignment of frames f0..f1-1
 hipError_t launch_visual_lloyd(const DeviceView &dv, int W, int iters, hipStream_t s);
-hipError_t launch_visual_assign(const DeviceView &dv, int f0, int f1, hipStream_t s);
+// (e_in: fp32 embeddings of frames f0..f1-1, which the kernel also files in the state array)
+hipError_t launch_visual_assign(const DeviceView &dv, const float *e_in, int f0, int f1, hipStream_t s);
 // per-unit partition representatives recomputed from the member lists (after a K-means run)
 hipError_t launch_partition_reps(const DeviceView &dv, int n_frames, hipStream_t s);
 // write_pages = false (host tier): only scores and ids; the page list comes from the host

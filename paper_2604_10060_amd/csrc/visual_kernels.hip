@@ -3,7 +3,7 @@
 // modified K-means as the key summaries (cosine criterion, representative =
 // mean of the members, Eq. 1 / Eq. 3), into P partitions that every unit's
 // semantic clustering is then confined to.
-//   k_visual_store   embeddings (fp32) -> the visual level's fp64 state array
+//   k_visual_store   warm-up embeddings (fp32) -> the visual level's fp64 state array
 //   k_visual_lloyd   initial P-means over the warm-up embeddings
 //   k_visual_assign  greedy assignment + running-mean update, frame by frame
 // One stream has one visual level, P <= 64 and a few hundred warm-up frames, so
@@ -116,16 +116,49 @@ __global__ __launch_bounds__(kVisBlock) void k_visual_lloyd(DeviceView dv, int W
 }
 
 // Frames f0..f1-1, in order: partition = most similar non-empty visual centroid,
-// which then moves by Eq. 3.  grid (1), kVisBlock threads; wavefront 0 decides.
-__global__ __launch_bounds__(kVisBlock) void k_visual_assign(DeviceView dv, int f0, int f1) {
-    const int tid = threadIdx.x, wave = tid / 64, Dv = dv.Dv;
+// which then moves by Eq. 3.  grid (1), kVisBlock threads.  e_in: the fp32
+// embeddings of these frames as the caller passed them; the kernel also files
+// them in the visual level's state array.  Per frame: the embedding is staged in
+// LDS, wavefront w scores centroids w, w+16, ..., thread 0 picks the winner, all
+// threads update its row.
+__global__ __launch_bounds__(kVisBlock) void k_visual_assign(DeviceView dv, const float *e_in, int f0, int f1) {
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, Dv = dv.Dv, P = dv.P;
+    __shared__ double e_sh[4096];
     __shared__ double red[kVisWaves];
+    __shared__ double bv_sh[kVisWaves];
+    __shared__ int bi_sh[kVisWaves];
     __shared__ int win_sh;
     for (int f = f0; f < f1; ++f) {
-        const double *e = dv.vemb + (size_t)f * Dv;
-        if (wave == 0) {
-            const int a = visual_nearest(dv, e, false);
-            if (tid == 0) { win_sh = a; dv.part[f] = a; }
+        const float *src = e_in + (size_t)(f - f0) * Dv;
+        for (int d = tid; d < Dv; d += kVisBlock) {
+            const double v = (double)src[d];
+            e_sh[d] = v;
+            dv.vemb[(size_t)f * Dv + d] = v;
+        }
+        __syncthreads();
+        double en = 0.0;
+        for (int d = lane; d < Dv; d += 64) en += e_sh[d] * e_sh[d];
+        en = sqrt(wave_sum(en));
+        double bv = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int p = wave; p < P; p += kVisWaves) {
+            if (dv.vn[p] <= 0) continue;                 // wave-uniform
+            const double *rp = dv.vr + (size_t)p * Dv;
+            double x = 0.0;
+            for (int d = lane; d < Dv; d += 64) x += e_sh[d] * rp[d];
+            x = wave_sum(x);
+            const double rn = dv.vrn[p];
+            const double c = (en == 0.0 || rn == 0.0) ? 0.0 : x / (en * rn);
+            if (better(c, p, bv, bi)) { bv = c; bi = p; }
+        }
+        if (lane == 0) { bv_sh[wave] = bv; bi_sh[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < kVisWaves; ++w)
+                if (better(bv_sh[w], bi_sh[w], bv, bi)) { bv = bv_sh[w]; bi = bi_sh[w]; }
+            const int a = bi == 0x7fffffff ? 0 : bi;
+            win_sh = a;
+            dv.part[f] = a;
         }
         __syncthreads();
         const int a = win_sh;
@@ -133,7 +166,7 @@ __global__ __launch_bounds__(kVisBlock) void k_visual_assign(DeviceView dv, int 
         double sq = 0.0;
         for (int d = tid; d < Dv; d += kVisBlock) {
             // Eq. 3, each operation rounded separately
-            const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, dv.vr[(size_t)a * Dv + d]), e[d]), na + 1.0);
+            const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, dv.vr[(size_t)a * Dv + d]), e_sh[d]), na + 1.0);
             dv.vr[(size_t)a * Dv + d] = rv;
             sq += rv * rv;
         }
@@ -159,8 +192,8 @@ hipError_t launch_visual_lloyd(const DeviceView &dv, int W, int iters, hipStream
     return after_launch();
 }
 
-hipError_t launch_visual_assign(const DeviceView &dv, int f0, int f1, hipStream_t s) {
-    k_visual_assign<<<1, kVisBlock, 0, s>>>(dv, f0, f1);
+hipError_t launch_visual_assign(const DeviceView &dv, const float *e_in, int f0, int f1, hipStream_t s) {
+    k_visual_assign<<<1, kVisBlock, 0, s>>>(dv, e_in, f0, f1);
     return after_launch();
 }
 

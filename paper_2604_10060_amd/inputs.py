@@ -32,7 +32,11 @@ per-frame output, which the nested visual-semantic hierarchy of Sec. V-B
 clusters first): every scene belongs to one of n_visual appearance classes,
   class centre   a[v]  ~ N(0, I_Dv),  scene offset  o[s] ~ N(0, I_Dv)
   embedding      e_f = a[class(s)] + 0.3 * o[s] + visual_noise * N(0, I_Dv)   (fp32)
-so scenes of one class look alike while their key states differ.
+so scenes of one class look alike while their key states differ.  With
+visual_key_corr = a > 0 the scenes of a class also share a part of their key
+centre, cK[s] <- a * bK[class(s)] + sqrt(1 - a^2) * cK[s] with bK ~ N(0, I_D) per
+layer and head (the cross-modal regularity of Sec. III-A: visually similar
+content tends to be retrieved together); a = 0 leaves the K/V stream untouched.
 """
 from __future__ import annotations
 
@@ -66,6 +70,7 @@ class Workload:
     visual_dim: int = 0           # > 0: per-frame visual embeddings of this size are generated as well
     n_visual: int = 8             # appearance classes the scenes are drawn from
     visual_noise: float = 0.3
+    visual_key_corr: float = 0.0  # share of a scene's key centre that it has in common with its appearance class
     warmup_frames: int = 0        # 0 -> 2 * n_clusters
     lloyd_iters: int = 8
     recluster_every: int = 0
@@ -197,6 +202,12 @@ class SceneStream:
                                              device=self.device, dtype=torch.float32)
             self.visual_offset = torch.randn((self.n_scenes, wl.visual_dim), generator=gv,
                                              device=self.device, dtype=torch.float32)
+            if wl.visual_key_corr > 0.0:
+                a = float(wl.visual_key_corr)
+                bk = torch.randn((wl.n_visual,) + shape[1:], generator=gv, device=self.device,
+                                 dtype=torch.float32)
+                cls = torch.as_tensor(self.visual_class_of_scene, device=self.device)
+                self.centre_k = a * bk[cls] + float(np.sqrt(1.0 - a * a)) * self.centre_k
 
     # -- frames ------------------------------------------------------------
     def frame(self, f: int) -> tuple[torch.Tensor, torch.Tensor]:

@@ -167,6 +167,20 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
     __shared__ float pm[16][kRowTile], pl[16][kRowTile];
     __shared__ float M_sh[kRowTile], L_sh[kRowTile];
     __shared__ float red[8][kRowTile][33];
+    const int sg = tid / 32, col = tid % 32;
+    // All partial loads of this thread are issued first, ahead of the (independent) loads
+    // and barriers of the weight computation: the partials were written by other compute
+    // units, so every load is a full memory round trip, and the two round trips overlap.
+    // Split and row indices are clamped instead of tested, so the loads are unconditional
+    // (straight-line code); what a clamped load brings is never used.
+    float v[kMaxSplits / 8][kRowTile];
+#pragma unroll
+    for (int i = 0; i < kMaxSplits / 8; ++i) {
+        const int s = min(sg + 8 * i, max(n_splits - 1, 0));
+        const float *po = dv.part_o + (e0 + s) * kRowTile * D + dg * 32 + col;
+#pragma unroll
+        for (int r = 0; r < kRowTile; ++r) v[i][r] = po[(size_t)min(r, rows - 1) * D];
+    }
     {   // per-row maximum and normaliser over the splits
         const int row = tid % 16, part = tid / 16;
         float mr[kMaxSplits / 16], lr[kMaxSplits / 16];
@@ -206,28 +220,15 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
             L_sh[row] = Ls;
         }
     }
-    const int sg = tid / 32, col = tid % 32;
     float acc[kRowTile];
 #pragma unroll
     for (int r = 0; r < kRowTile; ++r) acc[r] = 0.f;
-    {   // all loads of this thread are issued before the first use: the partials were
-        // written by other compute units, so every load is a full memory round trip
-        float v[kMaxSplits / 8][kRowTile];
 #pragma unroll
-        for (int i = 0; i < kMaxSplits / 8; ++i) {
-            const int s = sg + 8 * i;
-            const float *po = dv.part_o + (e0 + s) * kRowTile * D + dg * 32 + col;
+    for (int i = 0; i < kMaxSplits / 8; ++i) {
+        const int s = sg + 8 * i;
+        if (s < n_splits) {
 #pragma unroll
-            for (int r = 0; r < kRowTile; ++r)
-                v[i][r] = (s < n_splits && r < rows) ? po[(size_t)r * D] : 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < kMaxSplits / 8; ++i) {
-            const int s = sg + 8 * i;
-            if (s < n_splits) {
-#pragma unroll
-                for (int r = 0; r < kRowTile; ++r) acc[r] += w_sh[s][r] * v[i][r];
-            }
+            for (int r = 0; r < kRowTile; ++r) acc[r] += w_sh[s][r] * v[i][r];
         }
     }
 #pragma unroll

@@ -410,11 +410,33 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_seed_nested(DeviceView dv, int
     constexpr int EPL = D / 16;
     const int u = blockIdx.x, tid = threadIdx.x, C = dv.C, Cs = dv.Cs;
     const int lr = tid % 16, row0 = tid / 16;
+    constexpr int kPartLds = 8192;            // warm-up partitions are scanned out of LDS when they fit
     __shared__ int np_sh[64];
+    __shared__ int part_sh[kPartLds];
+    const bool in_lds = W <= kPartLds;
+    if (in_lds)
+        for (int f = tid; f < W; f += kBlock) part_sh[f] = dv.part[f];
+    __syncthreads();
+    const int *part = in_lds ? part_sh : dv.part;
+    // member lists of the partitions, ascending, back to back in the unit's (not yet used)
+    // rank array: thread p counts, thread 0 lays out the starts, thread p fills its list
+    __shared__ int start_sh[65];
+    int *order = dv.pos + (size_t)u * dv.F;
     if (tid < dv.P) {
         int c = 0;
-        for (int f = 0; f < W; ++f) c += dv.part[f] == tid;
+        for (int f = 0; f < W; ++f) c += part[f] == tid;
         np_sh[tid] = c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int o = 0;
+        for (int p = 0; p < dv.P; ++p) { start_sh[p] = o; o += np_sh[p]; }
+    }
+    __syncthreads();
+    if (tid < dv.P) {
+        int o = start_sh[tid];
+        for (int f = 0; f < W; ++f)
+            if (part[f] == tid) order[o++] = f;
     }
     __syncthreads();
     for (int j = row0; j < C; j += 16) {
@@ -426,13 +448,7 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_seed_nested(DeviceView dv, int
             if (lr == 0) { dv.rnorm[(size_t)u * C + j] = 0.0; dv.n[(size_t)u * C + j] = 0; }
             continue;
         }
-        const int want = (int)(((long long)jj * np) / L);   // index in the partition's member list
-        int src = 0, seen = 0;
-        for (int f = 0; f < W; ++f) {
-            if (dv.part[f] != p) continue;
-            if (seen == want) { src = f; break; }
-            ++seen;
-        }
+        const int src = order[start_sh[p] + (int)(((long long)jj * np) / L)];
         const double *s = dv.summ + ((size_t)u * dv.F + src) * D + lr * EPL;
         double sq = 0.0;
 #pragma unroll

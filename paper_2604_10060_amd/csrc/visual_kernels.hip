@@ -4,11 +4,12 @@
 // mean of the members, Eq. 1 / Eq. 3), into P partitions that every unit's
 // semantic clustering is then confined to.
 //   k_visual_store   warm-up embeddings (fp32) -> the visual level's fp64 state array
-//   k_visual_lloyd   initial P-means over the warm-up embeddings
+//   k_visual_seed / k_visual_lloyd_assign / _update   initial P-means over the warm-up embeddings
 //   k_visual_assign  greedy assignment + running-mean update, frame by frame
-// One stream has one visual level, P <= 64 and a few hundred warm-up frames, so
-// each of the two clustering kernels is a single wide workgroup: a wavefront
-// per (frame, centroid) dot product, lanes striding the Dv channels.
+// One stream has one visual level and P <= 64: the online kernel is a single wide
+// workgroup (frames are strictly sequential), the K-means rounds spread frames and
+// centroids over workgroups; a wavefront computes a (frame, centroid) cosine with
+// its lanes striding the Dv channels.
 #include "mosaic_internal.h"
 
 namespace mosaic {
@@ -73,46 +74,55 @@ __device__ __forceinline__ int visual_nearest(const DeviceView &dv, const double
 // Initial clustering of the visual level over the first W embeddings: seeds =
 // embeddings of frames floor(p*W/P), every centroid live in the first
 // assignment round, `iters` rounds; a centroid left without members keeps its
-// vector and is skipped afterwards.  Members are summed in ascending frame order.
-// grid (1), kVisBlock threads.
-__global__ __launch_bounds__(kVisBlock) void k_visual_lloyd(DeviceView dv, int W, int iters) {
-    const int tid = threadIdx.x, wave = tid / 64, P = dv.P, Dv = dv.Dv;
+// vector and is skipped afterwards.  Three small kernels per round trip of the
+// algorithm, launched back to back on the stream:
+//   k_visual_seed          grid (P): copy the seed embedding, its norm
+//   k_visual_lloyd_assign  grid (ceil(W/16)): one wavefront per frame
+//   k_visual_lloyd_update  grid (P): members summed in ascending frame order
+__global__ __launch_bounds__(kVisBlock) void k_visual_seed(DeviceView dv, int W) {
+    const int tid = threadIdx.x, p = blockIdx.x, Dv = dv.Dv;
     __shared__ double red[kVisWaves];
-    for (int p = 0; p < P; ++p) {
-        const double *src = dv.vemb + (size_t)(((long long)p * W) / P) * Dv;
-        double sq = 0.0;
-        for (int d = tid; d < Dv; d += kVisBlock) { const double v = src[d]; dv.vr[(size_t)p * Dv + d] = v; sq += v * v; }
-        sq = block_sum(sq, red);
-        if (tid == 0) { dv.vrn[p] = sqrt(sq); dv.vn[p] = 0; }
-    }
+    const double *src = dv.vemb + (size_t)(((long long)p * W) / dv.P) * Dv;
+    double sq = 0.0;
+    for (int d = tid; d < Dv; d += kVisBlock) { const double v = src[d]; dv.vr[(size_t)p * Dv + d] = v; sq += v * v; }
+    sq = block_sum(sq, red);
+    if (tid == 0) { dv.vrn[p] = sqrt(sq); dv.vn[p] = 0; }
+}
+
+__global__ __launch_bounds__(kVisBlock) void k_visual_lloyd_assign(DeviceView dv, int W, int live_all) {
+    const int f = blockIdx.x * kVisWaves + threadIdx.x / 64;
+    if (f >= W) return;                                  // wave-uniform; no barrier in this kernel
+    const int a = visual_nearest(dv, dv.vemb + (size_t)f * dv.Dv, live_all != 0);
+    if (threadIdx.x % 64 == 0) dv.part[f] = a;
+}
+
+__global__ __launch_bounds__(kVisBlock) void k_visual_lloyd_update(DeviceView dv, int W) {
+    const int tid = threadIdx.x, p = blockIdx.x, Dv = dv.Dv;
+    constexpr int kPartLds = 8192;            // the assignments are scanned out of LDS when they fit
+    __shared__ double red[kVisWaves];
+    __shared__ int part_sh[kPartLds];
+    const bool in_lds = W <= kPartLds;
+    if (in_lds)
+        for (int f = tid; f < W; f += kVisBlock) part_sh[f] = dv.part[f];
     __syncthreads();
-    for (int it = 0; it < iters; ++it) {
-        for (int f = wave; f < W; f += kVisWaves) {
-            const int a = visual_nearest(dv, dv.vemb + (size_t)f * Dv, it == 0);
-            if (tid % 64 == 0) dv.part[f] = a;
-        }
-        __syncthreads();
-        for (int p = 0; p < P; ++p) {
-            int count = 0;
-            for (int f = 0; f < W; ++f) count += dv.part[f] == p;
-            if (count == 0) {                            // workgroup-uniform
-                if (tid == 0) dv.vn[p] = 0;
-                continue;
-            }
-            double sq = 0.0;
-            for (int d = tid; d < Dv; d += kVisBlock) {
-                double acc = 0.0;
-                for (int f = 0; f < W; ++f)
-                    if (dv.part[f] == p) acc += dv.vemb[(size_t)f * Dv + d];
-                const double rv = acc / (double)count;
-                dv.vr[(size_t)p * Dv + d] = rv;
-                sq += rv * rv;
-            }
-            sq = block_sum(sq, red);
-            if (tid == 0) { dv.vrn[p] = sqrt(sq); dv.vn[p] = count; }
-        }
-        __syncthreads();
+    const int *part = in_lds ? part_sh : dv.part;
+    int count = 0;
+    for (int f = 0; f < W; ++f) count += part[f] == p;
+    if (count == 0) {                                    // workgroup-uniform
+        if (tid == 0) dv.vn[p] = 0;
+        return;
     }
+    double sq = 0.0;
+    for (int d = tid; d < Dv; d += kVisBlock) {
+        double acc = 0.0;
+        for (int f = 0; f < W; ++f)
+            if (part[f] == p) acc += dv.vemb[(size_t)f * Dv + d];
+        const double rv = acc / (double)count;
+        dv.vr[(size_t)p * Dv + d] = rv;
+        sq += rv * rv;
+    }
+    sq = block_sum(sq, red);
+    if (tid == 0) { dv.vrn[p] = sqrt(sq); dv.vn[p] = count; }
 }
 
 // Frames f0..f1-1, in order: partition = most similar non-empty visual centroid,
@@ -188,8 +198,15 @@ hipError_t launch_visual_store(const DeviceView &dv, const float *e_in, int f0, 
 }
 
 hipError_t launch_visual_lloyd(const DeviceView &dv, int W, int iters, hipStream_t s) {
-    k_visual_lloyd<<<1, kVisBlock, 0, s>>>(dv, W, iters);
-    return after_launch();
+    k_visual_seed<<<dv.P, kVisBlock, 0, s>>>(dv, W);
+    hipError_t e = after_launch();
+    for (int it = 0; it < iters && e == hipSuccess; ++it) {
+        k_visual_lloyd_assign<<<(W + kVisWaves - 1) / kVisWaves, kVisBlock, 0, s>>>(dv, W, it == 0);
+        if ((e = after_launch()) != hipSuccess) break;
+        k_visual_lloyd_update<<<dv.P, kVisBlock, 0, s>>>(dv, W);
+        e = after_launch();
+    }
+    return e;
 }
 
 hipError_t launch_visual_assign(const DeviceView &dv, const float *e_in, int f0, int f1, hipStream_t s) {

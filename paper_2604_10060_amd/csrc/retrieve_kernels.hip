@@ -4,6 +4,7 @@
 // clusters.  Nothing is copied: attention later reads the pages in place.
 #include "mosaic_internal.h"
 #include "maintain_device.h"
+#include "topk_device.h"
 
 namespace mosaic {
 
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     __shared__ int wcnt_sh[1024];   // members inside the local window
     __shared__ int ids_sh[1024];
     __shared__ int off_sh[1025];
-    __shared__ int n_live_sh;
+    __shared__ TopkShared tk_sh;
     __shared__ double ps_sh[64];    // first-stage scores
     __shared__ int psel_sh[64];     // partition kept by the first stage
     __shared__ int p_live_sh;
@@ -74,8 +75,7 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         fa[i] = in ? assign[f] : -1;
         fp[i] = in ? pos[f] : 0;
     }
-    for (int j = tid; j < C; j += BLK) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; cnt_sh[j] = 0; wcnt_sh[j] = 0; }
-    if (tid == 0) n_live_sh = 0;
+    for (int j = tid; j < C; j += BLK) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; wcnt_sh[j] = 0; }
     // local-window augmentation (Sec. V-C): the w most recent frames are listed once, after the
     // clusters; they are the last members of their clusters (ranks ascend with the frame id), so
     // a cluster's list is simply cut short by its number of window members
@@ -214,37 +214,10 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         }
     }
     __syncthreads();
-    // rank among non-empty clusters by (score descending, id ascending).  Empty
-    // clusters carry -inf and so never outrank a live one.  The comparison range of
-    // a cluster is shared by P threads.
-    {
-        const int P = C <= 64 ? 16 : (C <= 128 ? 8 : (C <= 256 ? 4 : (C <= 512 ? 2 : 1)));
-        for (int item = tid; item < C * P; item += BLK) {
-            const int j = item % C, part = item / C;
-            if (n_sh[j] <= 0) continue;
-            const double sj = sc_sh[j];
-            const int i0 = (C * part) / P, i1 = (C * (part + 1)) / P;
-            int c = 0;
-#pragma unroll 8
-            for (int i = i0; i < i1; ++i) {
-                const double si = sc_sh[i];
-                c += (si > sj) || (si == sj && i < j);
-            }
-            atomicAdd(&cnt_sh[j], c);
-        }
-        __syncthreads();
-        for (int j = tid; j < C; j += BLK) {
-            int rk = -1;
-            if (n_sh[j] > 0) {
-                rk = cnt_sh[j];
-                atomicAdd(&n_live_sh, 1);
-                if (rk < k) ids_sh[rk] = j; else rk = -1;
-            }
-            rank_sh[j] = rk;
-        }
-    }
-    __syncthreads();
-    const int n_ids = min(k, n_live_sh);
+    // ranks of the k best non-empty clusters by (score descending, id ascending); empty and
+    // pruned clusters have n_sh = 0 and take no part
+    const int n_live = topk_rank(sc_sh, n_sh, C, k, rank_sh, ids_sh, cnt_sh, off_sh, tk_sh);
+    const int n_ids = min(k, n_live);
     if (tid == 0) {
         int o = 0;
         off_sh[0] = 0;
@@ -269,8 +242,7 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         const int rk = rank_sh[c];
         if (rk >= 0) sel[off_sh[rk] + pos[f]] = f;
     }
-    const int n_ids_f = min(k, n_live_sh);
-    if (w0 + tid < n_frames) sel[off_sh[n_ids_f] + tid] = w0 + tid;      // the local window, ascending
+    if (w0 + tid < n_frames) sel[off_sh[n_ids] + tid] = w0 + tid;      // the local window, ascending
 }
 
 // ---------------------------------------------------------------------------
@@ -299,7 +271,7 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv,
     __shared__ int cnt_sh[1024];
     __shared__ int ids_sh[1024];
     __shared__ int off_sh[1025];
-    __shared__ int n_live_sh;
+    __shared__ TopkShared tk_sh;
     __shared__ SplitShared<D> split_sh;
     const double *r = dv.r + (size_t)u * C * D;
     const double *rn = dv.rnorm + (size_t)u * C;
@@ -310,8 +282,7 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv,
     int *buf_owner = dv.buf_owner + (size_t)u * dv.buf_max;
     const int nb = dv.n_buf[u], R = C + nb;
 
-    for (int j = tid; j < 1024; j += BLK) { n_sh[j] = j < C ? n[j] : (j < R ? 1 : 0); cnt_sh[j] = 0; }
-    if (tid == 0) n_live_sh = 0;
+    for (int j = tid; j < 1024; j += BLK) n_sh[j] = j < C ? n[j] : (j < R ? 1 : 0);
     {   // mean query, as in k_retrieve
         const int d = tid % D, part = tid / D, RQ = Tq * G;
         const E *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + d;
@@ -357,29 +328,9 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv,
         }
     }
     __syncthreads();
-    // rank among the live representatives by (score descending, id ascending)
-    for (int j = tid; j < R; j += BLK) {
-        if (n_sh[j] <= 0) continue;
-        const double sj = sc_sh[j];
-        int c = 0;
-        for (int i = 0; i < R; ++i) {
-            const double si = sc_sh[i];
-            c += n_sh[i] > 0 && ((si > sj) || (si == sj && i < j));
-        }
-        cnt_sh[j] = c;
-    }
-    __syncthreads();
-    for (int j = tid; j < 1024; j += BLK) {
-        int rk = -1;
-        if (j < R && n_sh[j] > 0) {
-            rk = cnt_sh[j];
-            atomicAdd(&n_live_sh, 1);
-            if (rk < k) ids_sh[rk] = j; else rk = -1;
-        }
-        rank_sh[j] = rk;
-    }
-    __syncthreads();
-    const int n_ids = min(k, n_live_sh);
+    // ranks of the k best live representatives by (score descending, id ascending)
+    const int n_live = topk_rank(sc_sh, n_sh, R, k, rank_sh, ids_sh, cnt_sh, off_sh, tk_sh);
+    const int n_ids = min(k, n_live);
     if (tid == 0) {
         int o = 0;
         off_sh[0] = 0;

@@ -586,3 +586,17 @@ def test_nested_config_and_call_errors():
     with pytest.raises(binding.MosaicError):
         m.partitions()
     m.close()
+
+
+# ---------------------------------------------------------------------------
+# Large cluster tables: the binned exact top-k (more than 128 representatives)
+# ---------------------------------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("C,k", [(160, 24), (384, 1), (384, 383)])
+def test_large_cluster_table_topk(C, k):
+    """k = 1, a mid-sized k and k close to the number of clusters (all bins become candidates)."""
+    wl = _small(name=f"large_table_{C}_{k}", n_frames=2 * C + 40, n_scenes=40, n_clusters=C, top_k=k,
+                tokens_per_frame=8, question_tokens=3)
+    rep = harness.run_workload(wl, units=[(0, 0), (0, 3)], n_questions=2, decode_steps=3)
+    _report(rep)
+    assert rep.max_out_err <= 2e-2

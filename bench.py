@@ -768,6 +768,14 @@ def run_host_leg(layers=2, steps=128, check=True):
         step(i)
         torch.cuda.synchronize()
         lat.append((time.perf_counter() - t) * 1e6)
+    # the attention kernel on warm steps (everything selected is in the GPU cluster cache)
+    m.profile_read()
+    for i in range(8):
+        step(steps - 1 - i)
+    att_ms, att_n = m.profile_read()
+    warm_tokens = int(sum(n_tok_all(m, L)))          # selection of the last step issued, all layers
+    att_us = att_ms * 1e3 / max(att_n, 1)
+    att_bytes = warm_tokens / L * 2 * D * esz
     s = m.stats()
     lat = np.array(lat)
     cold = lat[::per_topic]
@@ -810,6 +818,10 @@ def run_host_leg(layers=2, steps=128, check=True):
                          "bytes": int(s.h2d_bytes), "copies": int(s.h2d_copies),
                          "busy_ms": round(s.h2d_busy_ms, 3)},
             "cache": {"hits": int(s.cache_hits), "misses": int(s.cache_misses)},
+            "attention_warm": {"kernel": "k_attend_decode_mfma", "kernel_us": round(att_us, 1),
+                               "bytes_per_launch": int(att_bytes),
+                               "hbm_gbps": round(att_bytes / (att_us * 1e-6) / 1e9, 1) if att_us else None,
+                               "frac_of_8TBps": round(att_bytes / (att_us * 1e-6) / 8e12, 4) if att_us else None},
             "parity_spot_check": checked}
 
 

@@ -525,68 +525,101 @@ __global__ __launch_bounds__(kBlock) void k_exact_var(DeviceView dv, int n_frame
 }
 
 // ---------------------------------------------------------------------------
-// Lloyd assignment round.  grid (U, ceil(F/32)), 256 threads.
-// Thread (fi = tid%32, cq = tid/32): frame ft0+fi against 4 centroids at a time.
+// Lloyd assignment round: similarity table = summaries x representatives^T, a
+// dense fp64 contraction, on the matrix cores (v_mfma_f64_16x16x4_f64: A lane
+// (row = lane%16, k = lane/16), B lane (col = lane%16, k = lane/16), result
+// register v of a lane = element (row 4v + lane/16, col lane%16)).
+// grid (U, ceil(F/64)), 256 threads: a wavefront owns 16 frames, keeps their
+// summaries in registers as the A operand for the whole call, and sweeps the
+// representatives 16 at a time (operands straight from global memory / L2, the
+// next tile's loads issued before the current tile's MFMAs).  Lane group k
+// holds channels 8s + 2k and 8s + 2k + 1 of k-step s (one 16-byte load feeds two
+// MFMAs); the order of the additions inside a dot product is therefore not the
+// channel order, which moves a similarity by rounding only.
 // ---------------------------------------------------------------------------
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
 template <int D>
 __global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_frames) {
-    constexpr int FT = 32, LDP = D + 2;
-    const int u = blockIdx.x, ft0 = blockIdx.y * FT, tid = threadIdx.x, C = dv.C;
-    const int fi = tid % FT, cq = tid / FT;
-    __shared__ double s_sh[FT][LDP];
-    __shared__ double bv_sh[8][FT];
-    __shared__ int bi_sh[8][FT];
-    for (int idx = tid; idx < FT * D; idx += kBlock) {
-        const int ff = idx / D, d = idx % D;
-        s_sh[ff][d] = (ft0 + ff < n_frames) ? dv.summ[((size_t)u * dv.F + ft0 + ff) * D + d] : 0.0;
+    constexpr int KS = D / 8;
+    const int u = blockIdx.x, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, C = dv.C;
+    const int row = lane % 16, kq = lane / 16;
+    const int fbase = blockIdx.y * 64 + wave * 16;
+    __shared__ double sn_sh[4][16];
+    f64x2 a[KS];
+    {
+        const int f = min(fbase + row, n_frames - 1);
+        const double *sp = dv.summ + ((size_t)u * dv.F + f) * D + 2 * kq;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const f64x2 *>(sp + 8 * s);
+        double sq = 0.0;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) sq += a[s].x * a[s].x + a[s].y * a[s].y;
+        sq += __shfl_xor(sq, 16, 64);
+        sq += __shfl_xor(sq, 32, 64);
+        if (kq == 0) sn_sh[wave][row] = sqrt(sq);
     }
     __syncthreads();
-    double sn = 0.0;
-#pragma unroll 4
-    for (int d = 0; d < D; ++d) sn += s_sh[fi][d] * s_sh[fi][d];
-    sn = sqrt(sn);
+    // the four result rows of this lane: frames fbase + 4v + kq
+    double snv[4], bv[4];
+    int plo[4], phi[4], bi[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        snv[v] = sn_sh[wave][4 * v + kq];
+        bv[v] = -INFINITY; bi[v] = 0x7fffffff;
+        plo[v] = 0; phi[v] = C;
+        if (dv.P > 0) {      // nested hierarchy: only the ids of the frame's visual partition are candidates
+            plo[v] = dv.part[min(fbase + 4 * v + kq, n_frames - 1)] * dv.Cs;
+            phi[v] = plo[v] + dv.Cs;
+        }
+    }
     const double *r = dv.r + (size_t)u * C * D;
     const double *rn = dv.rnorm + (size_t)u * C;
     const int *n = dv.n + (size_t)u * C;
-    double bv = -INFINITY;
-    int bi = 0x7fffffff;
-    // nested hierarchy: only the ids of the frame's visual partition are candidates
-    int plo = 0, phi = C;
-    if (dv.P > 0) { plo = dv.part[min(ft0 + fi, n_frames - 1)] * dv.Cs; phi = plo + dv.Cs; }
-    for (int jb = cq * 4; jb < C; jb += 32) {
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        const double *rj[4];
+    const int n_tiles = (C + 15) / 16;
+    f64x2 b[KS], bn[KS];
+    auto load_tile = [&](int ct, f64x2 (&dst)[KS]) {
+        const double *rp = r + (size_t)min(16 * ct + row, C - 1) * D + 2 * kq;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) rj[q] = r + (size_t)min(jb + q, C - 1) * D;
-#pragma unroll 4
-        for (int d = 0; d < D; d += 2) {
-            const double s0 = s_sh[fi][d], s1 = s_sh[fi][d + 1];
+        for (int s = 0; s < KS; ++s) dst[s] = *reinterpret_cast<const f64x2 *>(rp + 8 * s);
+    };
+    load_tile(0, b);
+    for (int ct = 0; ct < n_tiles; ++ct) {
+        load_tile(min(ct + 1, n_tiles - 1), bn);
+        f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const double2 rv = *reinterpret_cast<const double2 *>(rj[q] + d);
-                acc[q] += s0 * rv.x;
-                acc[q] += s1 * rv.y;
+        for (int s = 0; s < KS; ++s) {
+            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].x, b[s].x, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].y, b[s].y, acc1, 0, 0, 0);
+        }
+        const int j = 16 * ct + row;
+        if (j < C) {
+            const int nj = n[j];
+            const double rnj = rn[j];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (nj > 0 && j >= plo[v] && j < phi[v]) {
+                    const double dot = acc0[v] + acc1[v];
+                    const double c = (snv[v] == 0.0 || rnj == 0.0) ? 0.0 : dot / (snv[v] * rnj);
+                    if (better(c, j, bv[v], bi[v])) { bv[v] = c; bi[v] = j; }
+                }
             }
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int j = jb + q;
-            if (j >= plo && j < phi && n[j] > 0) {
-                const double c = (sn == 0.0 || rn[j] == 0.0) ? 0.0 : acc[q] / (sn * rn[j]);
-                if (better(c, j, bv, bi)) { bv = c; bi = j; }
-            }
-        }
+        for (int s = 0; s < KS; ++s) b[s] = bn[s];
     }
-    bv_sh[cq][fi] = bv;
-    bi_sh[cq][fi] = bi;
-    __syncthreads();
-    if (tid < FT && ft0 + tid < n_frames) {
-        bv = bv_sh[0][tid]; bi = bi_sh[0][tid];
-        for (int q = 1; q < 8; ++q)
-            if (better(bv_sh[q][tid], bi_sh[q][tid], bv, bi)) { bv = bv_sh[q][tid]; bi = bi_sh[q][tid]; }
-        int none = 0;
-        if (dv.P > 0) none = dv.part[ft0 + tid] * dv.Cs;
-        dv.assign[(size_t)u * dv.F + ft0 + tid] = bi == 0x7fffffff ? none : bi;
+    // best over the 16 columns a lane group covers (lanes 16k .. 16k + 15)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) {
+            const double ov = __shfl_xor(bv[v], o, 16);
+            const int oi = __shfl_xor(bi[v], o, 16);
+            if (better(ov, oi, bv[v], bi[v])) { bv[v] = ov; bi[v] = oi; }
+        }
+        const int f = fbase + 4 * v + kq;
+        if (row == 0 && f < n_frames) dv.assign[(size_t)u * dv.F + f] = bi[v] == 0x7fffffff ? plo[v] : bi[v];
     }
 }
 
@@ -763,7 +796,7 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
         });
         if (e != hipSuccess) return e;
     }
-    dim3 ga(dv.U, (n_frames + 31) / 32), gu(dv.U, dv.C);
+    dim3 ga(dv.U, (n_frames + 63) / 64), gu(dv.U, dv.C);
     for (int it = 0; it < iters; ++it) {
         e = checked([&] {
             if (dv.D == 64) k_lloyd_assign<64><<<ga, kBlock, 0, s>>>(dv, n_frames);

@@ -75,7 +75,8 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         fa[i] = in ? assign[f] : -1;
         fp[i] = in ? pos[f] : 0;
     }
-    for (int j = tid; j < C; j += BLK) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; wcnt_sh[j] = 0; }
+    for (int j = tid; j < C; j += BLK) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; cnt_sh[j] = 0; wcnt_sh[j] = 0; }
+    if (tid == 0) tk_sh.n_live = 0;
     // local-window augmentation (Sec. V-C): the w most recent frames are listed once, after the
     // clusters; they are the last members of their clusters (ranks ascend with the frame id), so
     // a cluster's list is simply cut short by its number of window members
@@ -282,7 +283,8 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv,
     int *buf_owner = dv.buf_owner + (size_t)u * dv.buf_max;
     const int nb = dv.n_buf[u], R = C + nb;
 
-    for (int j = tid; j < 1024; j += BLK) n_sh[j] = j < C ? n[j] : (j < R ? 1 : 0);
+    for (int j = tid; j < 1024; j += BLK) { n_sh[j] = j < C ? n[j] : (j < R ? 1 : 0); cnt_sh[j] = 0; }
+    if (tid == 0) tk_sh.n_live = 0;
     {   // mean query, as in k_retrieve
         const int d = tid % D, part = tid / D, RQ = Tq * G;
         const E *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + d;

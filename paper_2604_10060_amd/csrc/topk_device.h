@@ -32,6 +32,8 @@ struct TopkShared {
 
 // cnt_sh, cand_sh: 1024 ints of scratch each (contents destroyed).  R <= 1024.
 // All 1024 threads of the workgroup must call it; it contains barriers.
+// Precondition (saves a barrier on the small-table path): cnt_sh[0..R) and
+// sh.n_live were set to zero by the caller before its latest barrier.
 __device__ __forceinline__ int topk_rank(const double *sc_sh, const int *n_sh, int R, int k,
                                          int *rank_sh, int *ids_sh, int *cnt_sh, int *cand_sh,
                                          TopkShared &sh) {
@@ -40,14 +42,11 @@ __device__ __forceinline__ int topk_rank(const double *sc_sh, const int *n_sh, i
     const bool live = tid < R && n_sh[tid] > 0;
     const double s = live ? sc_sh[tid] : 0.0;
     if (R <= 128) {
-        // small tables: the direct count, four threads per entry
-        cnt_sh[tid] = 0;
-        if (tid == 0) sh.n_live = 0;
-        __syncthreads();
-        const int j = tid % 256, part = tid / 256;
-        if (j < R && n_sh[j] > 0) {
+        // small tables: the direct count, 1024 / R threads per entry
+        const int per = BLK / R, j = tid % R, part = tid / R;
+        if (part < per && n_sh[j] > 0) {
             const double sj = sc_sh[j];
-            const int i0 = (R * part) / 4, i1 = (R * (part + 1)) / 4;
+            const int i0 = (R * part) / per, i1 = (R * (part + 1)) / per;
             int c = 0;
             for (int i = i0; i < i1; ++i) {
                 const double si = sc_sh[i];

@@ -531,8 +531,8 @@ __global__ __launch_bounds__(kBlock) void k_exact_var(DeviceView dv, int n_frame
 // register v of a lane = element (row 4v + lane/16, col lane%16)).
 // grid (U, ceil(F/64)), 256 threads: a wavefront owns 16 frames, keeps their
 // summaries in registers as the A operand for the whole call, and sweeps the
-// representatives 16 at a time (operands straight from global memory / L2, the
-// next tile's loads issued before the current tile's MFMAs).  Lane group k
+// representatives 16 at a time (each tile staged once per workgroup in LDS,
+// double buffered, the next tile in flight behind the current tile's MFMAs).  Lane group k
 // holds channels 8s + 2k and 8s + 2k + 1 of k-step s (one 16-byte load feeds two
 // MFMAs); the order of the additions inside a dot product is therefore not the
 // channel order, which moves a similarity by rounding only.
@@ -541,7 +541,7 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef double f64x2 __attribute__((ext_vector_type(2)));
 
 template <int D>
-__global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_frames) {
+__global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n_frames) {
     constexpr int KS = D / 8;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, C = dv.C;
     const int row = lane % 16, kq = lane / 16;
@@ -578,15 +578,39 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_fr
     const double *rn = dv.rnorm + (size_t)u * C;
     const int *n = dv.n + (size_t)u * C;
     const int n_tiles = (C + 15) / 16;
-    f64x2 b[KS], bn[KS];
-    auto load_tile = [&](int ct, f64x2 (&dst)[KS]) {
-        const double *rp = r + (size_t)min(16 * ct + row, C - 1) * D + 2 * kq;
+    // A tile of 16 representatives is shared by the four wavefronts through LDS (each row is read
+    // from L2 once per workgroup); rows are padded by 16 bytes so that the 16 lanes of a k group hit
+    // 16 different 16-byte bank groups.  Tile ct+1 travels global -> registers while tile ct is used.
+    constexpr int LROW = D + 2, PPT = 16 * D / 2 / kBlock;        // doubles per LDS row; 16-byte pieces per thread
+    __shared__ __attribute__((aligned(16))) double b_lds[2][16][LROW];
+    f64x2 stg[PPT];
+    auto fetch_tile = [&](int ct) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) dst[s] = *reinterpret_cast<const f64x2 *>(rp + 8 * s);
+        for (int i = 0; i < PPT; ++i) {
+            const int p = tid + kBlock * i, trow = p / (D / 2), seg = p % (D / 2);
+            stg[i] = *reinterpret_cast<const f64x2 *>(r + (size_t)min(16 * ct + trow, C - 1) * D + 2 * seg);
+        }
     };
-    load_tile(0, b);
+    auto stage_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int p = tid + kBlock * i, trow = p / (D / 2), seg = p % (D / 2);
+            *reinterpret_cast<f64x2 *>(&b_lds[buf][trow][2 * seg]) = stg[i];
+        }
+    };
+    fetch_tile(0);
+    int nj = n[min(row, C - 1)];
+    double rnj = rn[min(row, C - 1)];
+    stage_tile(0);
+    __syncthreads();
     for (int ct = 0; ct < n_tiles; ++ct) {
-        load_tile(min(ct + 1, n_tiles - 1), bn);
+        const int ctn = min(ct + 1, n_tiles - 1), jn = min(16 * ctn + row, C - 1);
+        fetch_tile(ctn);
+        const int nj_next = n[jn];
+        const double rnj_next = rn[jn];
+        f64x2 b[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) b[s] = *reinterpret_cast<const f64x2 *>(&b_lds[ct & 1][row][8 * s + 2 * kq]);
         f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
@@ -595,8 +619,6 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_fr
         }
         const int j = 16 * ct + row;
         if (j < C) {
-            const int nj = n[j];
-            const double rnj = rn[j];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 if (nj > 0 && j >= plo[v] && j < phi[v]) {
@@ -606,8 +628,9 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_assign(DeviceView dv, int n_fr
                 }
             }
         }
-#pragma unroll
-        for (int s = 0; s < KS; ++s) b[s] = bn[s];
+        stage_tile((ct + 1) & 1);       // the other buffer: last read before the previous barrier
+        __syncthreads();
+        nj = nj_next; rnj = rnj_next;
     }
     // best over the 16 columns a lane group covers (lanes 16k .. 16k + 15)
 #pragma unroll

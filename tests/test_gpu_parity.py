@@ -600,3 +600,27 @@ def test_large_cluster_table_topk(C, k):
     rep = harness.run_workload(wl, units=[(0, 0), (0, 3)], n_questions=2, decode_steps=3)
     _report(rep)
     assert rep.max_out_err <= 2e-2
+
+
+@pytest.mark.gpu
+def test_nested_reset_and_reingest_reproduces_the_state():
+    wl = inputs.CONFIGS[0].scaled(name="nested_reset", visual_dim=16, n_visual=3, n_clusters=16)
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    E = st.embeddings(0, wl.n_frames).to(DEV)
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    m = binding.Mosaic(binding.config_for(wl, n_partitions=4, visual_dim=16, top_partitions=2), device=DEV)
+    snaps = []
+    for batch in (7, 128):                       # different call sizes, same result
+        m.reset()
+        assert m.stats().frames_ingested == 0
+        for f in range(0, wl.n_frames, batch):
+            m.ingest_frame_visual(Kd[f:f + batch].contiguous(), Vd[f:f + batch].contiguous(),
+                                  E[f:f + batch].contiguous())
+        p = m.partitions()
+        R, N = m.centroids()
+        snaps.append((m.assignments().copy(), R.copy(), N.copy(), p["frame_to_partition"].copy(),
+                      p["visual_r"].copy(), p["part_r"].copy(), p["part_n"].copy()))
+    for a, b in zip(*snaps):
+        np.testing.assert_array_equal(a, b)
+    m.close()

@@ -359,6 +359,156 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
 }
 
 // ---------------------------------------------------------------------------
+// Online assignment + Eq. 3 with the representative table held in registers
+// (maintainer off, C <= THREADS / 2).  grid (U), THREADS threads.
+// The frames of a call are strictly sequential and every step of the global-
+// memory version above is a dependent round trip to L2 (summary, table rows,
+// winner row).  Here each 16-lane group keeps its RPG rows of the unit's table
+// (row j = group + (THREADS/16) i) in registers for the whole call, sizes and
+// norms sit in LDS, the next frame's summary is fetched while the current frame
+// is processed, and the winner's row is updated in place (and written through),
+// so nothing in the per-frame chain waits on memory.  Same arithmetic per
+// element as the version above; only the norm's additions are grouped by lane.
+// ---------------------------------------------------------------------------
+template <int D, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_assign_update_reg(DeviceView dv, int f0, int f1) {
+    constexpr int EPL = D / 16, NG = THREADS / 16, RPG = 8, NW = THREADS / 64, ROWS = NG * RPG;
+    const int u = blockIdx.x, tid = threadIdx.x, C = dv.C;
+    const int lr = tid % 16, grp = tid / 16, wave = tid / 64, lane = tid % 64;
+    __shared__ double s_sh[2][D];
+    __shared__ double dot_sh[ROWS], rn_sh[ROWS];
+    __shared__ int n_sh[ROWS];
+    __shared__ double red_v[NW];
+    __shared__ int red_i[NW];
+    __shared__ double snorm_sh, psum_sh[2];
+    __shared__ int win_sh;
+    double *r = dv.r + (size_t)u * C * D;
+    double rr[RPG][EPL];
+#pragma unroll
+    for (int i = 0; i < RPG; ++i) {
+        const double *rj = r + (size_t)min(grp + NG * i, C - 1) * D + lr * EPL;
+        if (NG * i < C) {                 // block-uniform: passes beyond the table are not loaded
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) rr[i][e] = rj[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) rr[i][e] = 0.0;
+        }
+    }
+    for (int j = tid; j < ROWS; j += THREADS) {
+        n_sh[j] = j < C ? dv.n[(size_t)u * C + j] : 0;
+        rn_sh[j] = j < C ? dv.rnorm[(size_t)u * C + j] : 0.0;
+    }
+    if (tid < D) s_sh[0][tid] = dv.summ[((size_t)u * dv.F + f0) * D + tid];
+    const bool nested = dv.P > 0;
+    __syncthreads();
+    for (int f = f0; f < f1; ++f) {
+        const int cur = (f - f0) & 1;
+        const double *sv = s_sh[cur];
+        // the next frame's summary: issued now, stored into the other buffer at the end
+        double s_next = 0.0;
+        if (tid < D && f + 1 < f1) s_next = dv.summ[((size_t)u * dv.F + f + 1) * D + tid];
+        const int part_f = nested ? dv.part[f] : 0;
+        const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : C;
+        if (wave == 0) {
+            double x = 0.0;
+            for (int d = lane; d < D; d += 64) x += sv[d] * sv[d];
+            x = wave_sum(x);
+            if (lane == 0) snorm_sh = sqrt(x);
+        }
+        double sl[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) sl[e] = sv[lr * EPL + e];
+#pragma unroll
+        for (int i = 0; i < RPG; ++i) {
+            const int j = grp + NG * i;
+            if (j >= lo && j < hi && n_sh[j] > 0) {          // uniform within the 16-lane group
+                double p = 0.0;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) p += sl[e] * rr[i][e];
+                p = group16_sum(p);
+                if (lr == 0) dot_sh[j] = p;
+            }
+        }
+        __syncthreads();
+        // argmax of the cosine over the candidates, ties to the lowest id
+        double bv = -INFINITY;
+        int bi = 0x7fffffff;
+        const double sn = snorm_sh;
+        for (int j = lo + tid; j < hi; j += THREADS) {
+            if (n_sh[j] <= 0) continue;
+            const double c = (sn == 0.0 || rn_sh[j] == 0.0) ? 0.0 : dot_sh[j] / (sn * rn_sh[j]);
+            if (better(c, j, bv, bi)) { bv = c; bi = j; }
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+            const double ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < NW; ++w)
+                if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
+            win_sh = bi == 0x7fffffff ? lo : bi;
+        }
+        // nested hierarchy: the partition's representative follows the same running mean
+        int pn_i = 0;
+        if (nested) {
+            double *prow = dv.pr + ((size_t)u * dv.P + part_f) * D;
+            pn_i = dv.pn[(size_t)u * dv.P + part_f];
+            double psq = 0.0;
+            if (tid < D) {
+                const double pv = ((double)pn_i * prow[tid] + sv[tid]) / ((double)pn_i + 1.0);
+                prow[tid] = pv;
+                psq = pv * pv;
+            }
+            if (wave < 2) {
+                psq = wave_sum(psq);
+                if (lane == 0) psum_sh[wave] = psq;
+            }
+        }
+        __syncthreads();
+        const int a = win_sh;
+        if (grp == a % NG) {                                  // the group that holds row a
+            const int na_i = n_sh[a];
+            const double na = (double)na_i;
+            double sq = 0.0;
+#pragma unroll
+            for (int i = 0; i < RPG; ++i) {
+                if (i == a / NG) {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) {
+                        // Eq. 3 with each operation rounded separately (no contraction)
+                        const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, rr[i][e]), sl[e]), na + 1.0);
+                        rr[i][e] = rv;
+                        r[(size_t)a * D + lr * EPL + e] = rv;
+                        sq += rv * rv;
+                    }
+                }
+            }
+            sq = group16_sum(sq);
+            if (lr == 0) {
+                const double nr = sqrt(sq);
+                rn_sh[a] = nr;
+                dv.rnorm[(size_t)u * C + a] = nr;
+                n_sh[a] = na_i + 1;
+                dv.n[(size_t)u * C + a] = na_i + 1;
+                dv.assign[(size_t)u * dv.F + f] = a;
+                dv.pos[(size_t)u * dv.F + f] = na_i;
+            }
+        }
+        if (nested && tid == 0) {
+            dv.prn[(size_t)u * dv.P + part_f] = sqrt(D > 64 ? psum_sh[0] + psum_sh[1] : psum_sh[0]);
+            dv.pn[(size_t)u * dv.P + part_f] = pn_i + 1;
+        }
+        if (tid < D) s_sh[cur ^ 1][tid] = s_next;
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Lloyd: seeds from the warm-up buffer.  grid (U), 256 threads.
 // r_j = summary of frame floor(j*W/C); every cluster counts as non-empty for
 // the first assignment round (n_j = 1 as a placeholder).
@@ -797,6 +947,12 @@ hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_
         if (dv.maint_mode) {
             if (dv.D == 64) k_assign_update<64, true><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
             else k_assign_update<128, true><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
+        } else if (dv.C <= 128) {          // table in registers: 8 rows per 16-lane group
+            if (dv.D == 64) k_assign_update_reg<64, 256><<<dv.U, 256, 0, s>>>(dv, f0, f1);
+            else k_assign_update_reg<128, 256><<<dv.U, 256, 0, s>>>(dv, f0, f1);
+        } else if (dv.C <= 256) {
+            if (dv.D == 64) k_assign_update_reg<64, 512><<<dv.U, 512, 0, s>>>(dv, f0, f1);
+            else k_assign_update_reg<128, 512><<<dv.U, 512, 0, s>>>(dv, f0, f1);
         } else {
             if (dv.D == 64) k_assign_update<64, false><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);
             else k_assign_update<128, false><<<dv.U, kBlock, 0, s>>>(dv, f0, f1);

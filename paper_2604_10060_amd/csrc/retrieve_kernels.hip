@@ -30,6 +30,64 @@ template <> __device__ __forceinline__ double to_f64<unsigned short>(unsigned sh
 // follows runs out of LDS and registers.
 constexpr int kRetrBlock = 1024;
 
+// ---------------------------------------------------------------------------
+// Mean query of a unit, first half: per-wavefront partial sums of the Tq * G
+// query rows of KV head h (fp64), written to wpart[wave][channel].  A thread
+// owns 8 consecutive channels (one 16-byte load per row for bf16, two for
+// fp32) of every (BLK / (D/8))-th row, with eight rows' loads in flight (row
+// index clamped, loads unconditional), so a 256-token question costs a handful
+// of memory round trips and a decode query exactly one.  The caller adds the 16
+// wavefront partials after a barrier.
+// ---------------------------------------------------------------------------
+template <typename E> __device__ __forceinline__ void load8_f64(const E *p, double (&out)[8]);
+template <> __device__ __forceinline__ void load8_f64<float>(const float *p, double (&out)[8]) {
+    const float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w; out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+template <> __device__ __forceinline__ void load8_f64<unsigned short>(const unsigned short *p, double (&out)[8]) {
+    const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    const unsigned int w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = (double)__uint_as_float(w[i] << 16);
+        out[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+
+template <typename E, int D>
+__device__ __forceinline__ void mean_query_partials(const E *q, int lc, int h, int Tq, int G, int Hq,
+                                                    double (*wpart)[D]) {
+    constexpr int BLK = kRetrBlock, LPR = D / 8, NPART = BLK / LPR, UN = 8;
+    const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+    const int c8 = tid % LPR, part = tid / LPR, R = Tq * G;
+    const E *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + 8 * c8;
+    double a[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int r0 = part; r0 < R; r0 += UN * NPART) {
+        double v[UN][8];
+#pragma unroll
+        for (int x = 0; x < UN; ++x) {
+            const int rr = min(r0 + x * NPART, R - 1), t = rr / G, g = rr - t * G;
+            load8_f64<E>(qb + ((size_t)t * Hq + g) * D, v[x]);
+        }
+#pragma unroll
+        for (int x = 0; x < UN; ++x)
+            if (r0 + x * NPART < R) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a[e] += v[x][e];
+            }
+    }
+    // the 64 / LPR parts inside a wavefront
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) a[e] += __shfl_xor(a[e], o, 64);
+    }
+    if (lane < LPR) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wpart[wave][8 * c8 + e] = a[e];
+    }
+}
+
 // NESTED (paper Sec. V-C "Two-Stage Retrieval"): the mean query is first scored against the
 // unit's P partition representatives; only the clusters of the top_p best partitions are then
 // scored (the rest count as empty: their rows are never read) and ranked.
@@ -41,13 +99,12 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     constexpr int RPP = BLK / 16;      // representative rows per pass
     constexpr int FPT = 4;             // frames per thread prefetched for the page-list scatter
     constexpr int RPF = 2;             // passes of representative rows prefetched into registers
-    constexpr int PARTS = BLK / D;     // threads sharing one channel of the mean query
     const int uc = blockIdx.x, u = u0 + uc, tid = threadIdx.x;
     const int C = dv.C, G = dv.G, Hq = dv.Hq, k = dv.k;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv;
     const int lr = tid % 16, row0 = tid / 16;
     __shared__ double qbar[D];
-    __shared__ double qpart[PARTS][D];
+    __shared__ double qpart[BLK / 64][D];   // per-wavefront partial sums of the query rows
     __shared__ double sc_sh[1024];
     __shared__ double rn_sh[1024];
     __shared__ int n_sh[1024];
@@ -106,32 +163,14 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         prn_pre = dv.prn[(size_t)u * dv.P + pj];
         if (tid == 0) p_live_sh = 0;
     }
-    // mean query over the Tq tokens and the G query heads of this KV head: PARTS
-    // threads per channel, each over a strided share of the Tq * G query rows, eight
-    // rows' loads in flight at a time (row index clamped, loads unconditional)
-    {
-        const int d = tid % D, part = tid / D, R = Tq * G;
-        const E *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + d;
-        double a[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-        for (int r0 = part; r0 < R; r0 += 8 * PARTS) {
-            E v[8];
-#pragma unroll
-            for (int x = 0; x < 8; ++x) {
-                const int rr = min(r0 + x * PARTS, R - 1), t = rr / G, g = rr - t * G;
-                v[x] = qb[((size_t)t * Hq + g) * D];
-            }
-#pragma unroll
-            for (int x = 0; x < 8; ++x)
-                if (r0 + x * PARTS < R) a[x] += to_f64<E>(v[x]);
-        }
-        qpart[part][d] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
-    }
+    // mean query over the Tq tokens and the G query heads of this KV head
+    mean_query_partials<E, D>(q, lc, h, Tq, G, Hq, qpart);
     __syncthreads();
     if (wa >= 0) atomicAdd(&wcnt_sh[wa], 1);
     if (tid < D) {
         double acc = 0.0;
 #pragma unroll
-        for (int p = 0; p < PARTS; ++p) acc += qpart[p][tid];
+        for (int p = 0; p < BLK / 64; ++p) acc += qpart[p][tid];
         qbar[tid] = acc / (double)(Tq * G);
     }
     __syncthreads();
@@ -259,13 +298,13 @@ template <typename E, int D>
 __global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv, int u0, const E *q, int Tq,
                                                                   int n_frames, int score_mode) {
     constexpr int BLK = kRetrBlock;
-    constexpr int EPL = D / 16, RPP = BLK / 16, PARTS = BLK / D;
+    constexpr int EPL = D / 16, RPP = BLK / 16;
     const int uc = blockIdx.x, u = u0 + uc, tid = threadIdx.x;
     const int C = dv.C, G = dv.G, Hq = dv.Hq, k = dv.k, SC = dv.SC;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv;
     const int lr = tid % 16, row0 = tid / 16;
     __shared__ double qbar[D];
-    __shared__ double qpart[PARTS][D];
+    __shared__ double qpart[BLK / 64][D];   // per-wavefront partial sums of the query rows
     __shared__ double sc_sh[1024];
     __shared__ int n_sh[1024];      // size in frames of a representative's cluster (0 = not live)
     __shared__ int rank_sh[1024];
@@ -285,28 +324,12 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv,
 
     for (int j = tid; j < 1024; j += BLK) { n_sh[j] = j < C ? n[j] : (j < R ? 1 : 0); cnt_sh[j] = 0; }
     if (tid == 0) tk_sh.n_live = 0;
-    {   // mean query, as in k_retrieve
-        const int d = tid % D, part = tid / D, RQ = Tq * G;
-        const E *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + d;
-        double a[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-        for (int r0 = part; r0 < RQ; r0 += 8 * PARTS) {
-            E v[8];
-#pragma unroll
-            for (int x = 0; x < 8; ++x) {
-                const int rr = min(r0 + x * PARTS, RQ - 1), t = rr / G, g = rr - t * G;
-                v[x] = qb[((size_t)t * Hq + g) * D];
-            }
-#pragma unroll
-            for (int x = 0; x < 8; ++x)
-                if (r0 + x * PARTS < RQ) a[x] += to_f64<E>(v[x]);
-        }
-        qpart[part][d] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
-    }
+    mean_query_partials<E, D>(q, lc, h, Tq, G, Hq, qpart);
     __syncthreads();
     if (tid < D) {
         double acc = 0.0;
 #pragma unroll
-        for (int p = 0; p < PARTS; ++p) acc += qpart[p][tid];
+        for (int p = 0; p < BLK / 64; ++p) acc += qpart[p][tid];
         qbar[tid] = acc / (double)(Tq * G);
     }
     __syncthreads();

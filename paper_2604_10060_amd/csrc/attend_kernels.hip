@@ -149,44 +149,42 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, i
     }
 }
 
-// Merge of the per-split partials (log-sum-exp weights), normalisation, output.
-// grid (D/32, NT, n_units), 256 threads.  A workgroup owns 32 output channels of
-// one row tile; its 8 groups of 32 threads share the splits, so the partial
-// buffer is read with many independent 128-byte loads in flight.
-template <typename E, int D>
-__global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0, int n_units, int Tq,
-                                                           int B, E *out, float *lse) {
-    const int dg = blockIdx.x, tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc, NT = gridDim.y;
-    const int tid = threadIdx.x;
-    const int G = dv.G, Hq = dv.Hq, lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
-    const int rows = min(kRowTile, R - tile * kRowTile);
-    const SplitSlot slot = split_slot<true>(dv.n_sel + u0, n_units, B, uc);
-    const int n_splits = slot.S;                 // 0 if the unit retrieved nothing
-    const size_t e0 = (size_t)slot.base * NT + (size_t)tile * n_splits;
-    __shared__ float w_sh[kMaxSplits][kRowTile];
-    __shared__ float pm[16][kRowTile], pl[16][kRowTile];
-    __shared__ float M_sh[kRowTile], L_sh[kRowTile];
-    __shared__ float red[8][kRowTile][33];
-    const int sg = tid / 32, col = tid % 32;
-    // All partial loads of this thread are issued first, ahead of the (independent) loads
-    // and barriers of the weight computation: the partials were written by other compute
-    // units, so every load is a full memory round trip, and the two round trips overlap.
-    // Split and row indices are clamped instead of tested, so the loads are unconditional
-    // (straight-line code); what a clamped load brings is never used.
-    float v[kMaxSplits / 8][kRowTile];
+// Weighted sum of one unit's split partials for 32 output channels of one row tile
+// (the per-thread share): log-sum-exp weights into w_sh, row maxima and normalisers
+// into M_sh / L_sh, partial sums into acc.  RMAX = 8 or 16 bounds the valid rows of the
+// tile (a decode step has G <= 8 rows), MAXS the splits handled.  A thread keeps 128
+// partial values in registers per pass, i.e. 64 splits of 16 rows or 128 splits of 8
+// rows; MAXS beyond that (a unit that retrieved far more than the others of its launch)
+// takes further passes, each one more memory round trip.
+// The partial loads of the first pass are issued first, ahead of the (independent) loads
+// and barriers of the weight computation: the partials were written by other compute
+// units, so every load is a full memory round trip, and the two round trips overlap.
+// Split and row indices are clamped instead of tested, so the loads are unconditional
+// (straight-line code); what a clamped load brings is never used.
+template <int D, int MAXS, int RMAX>
+__device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t e0, int n_splits, int rows, int dg,
+                                                   float (*w_sh)[kRowTile], float (*pm)[kRowTile],
+                                                   float (*pl)[kRowTile], float *M_sh, float *L_sh,
+                                                   float (&acc)[kRowTile]) {
+    constexpr int SPP = 64 * (kRowTile / RMAX);  // splits per pass
+    const int tid = threadIdx.x, sg = tid / 32, col = tid % 32;
+    float v[SPP / 8][RMAX];
+    auto load_pass = [&](int s0) {
 #pragma unroll
-    for (int i = 0; i < kMaxSplits / 8; ++i) {
-        const int s = min(sg + 8 * i, max(n_splits - 1, 0));
-        const float *po = dv.part_o + (e0 + s) * kRowTile * D + dg * 32 + col;
+        for (int i = 0; i < SPP / 8; ++i) {
+            const int s = min(s0 + sg + 8 * i, max(n_splits - 1, 0));
+            const float *po = dv.part_o + (e0 + s) * kRowTile * D + dg * 32 + col;
 #pragma unroll
-        for (int r = 0; r < kRowTile; ++r) v[i][r] = po[(size_t)min(r, rows - 1) * D];
-    }
+            for (int r = 0; r < RMAX; ++r) v[i][r] = po[(size_t)min(r, rows - 1) * D];
+        }
+    };
+    load_pass(0);
     {   // per-row maximum and normaliser over the splits
         const int row = tid % 16, part = tid / 16;
-        float mr[kMaxSplits / 16], lr[kMaxSplits / 16];
+        float mr[MAXS / 16], lr[MAXS / 16];
         float mx = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < kMaxSplits / 16; ++i) {
+        for (int i = 0; i < MAXS / 16; ++i) {
             const int s = part + 16 * i;
             mr[i] = -INFINITY; lr[i] = 0.f;
             if (s < n_splits) {
@@ -202,7 +200,7 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
         for (int p = 0; p < 16; ++p) M = fmaxf(M, pm[p][row]);
         float ls = 0.f;
 #pragma unroll
-        for (int i = 0; i < kMaxSplits / 16; ++i) {
+        for (int i = 0; i < MAXS / 16; ++i) {
             const int s = part + 16 * i;
             if (s < n_splits) {
                 const float w = M > -INFINITY ? exp2f(mr[i] - M) : 0.f;
@@ -220,16 +218,47 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
             L_sh[row] = Ls;
         }
     }
-    float acc[kRowTile];
 #pragma unroll
     for (int r = 0; r < kRowTile; ++r) acc[r] = 0.f;
+    for (int s0 = 0; s0 < (MAXS > SPP ? n_splits : 1); s0 += SPP) {
+        if (MAXS > SPP && s0 > 0) load_pass(s0);
 #pragma unroll
-    for (int i = 0; i < kMaxSplits / 8; ++i) {
-        const int s = sg + 8 * i;
-        if (s < n_splits) {
+        for (int i = 0; i < SPP / 8; ++i) {
+            const int s = s0 + sg + 8 * i;
+            if (s < n_splits) {
 #pragma unroll
-            for (int r = 0; r < kRowTile; ++r) acc[r] += w_sh[s][r] * v[i][r];
+                for (int r = 0; r < RMAX; ++r) acc[r] += w_sh[s][r] * v[i][r];
+            }
         }
+    }
+}
+
+// Merge of the per-split partials (log-sum-exp weights), normalisation, output.
+// grid (D/32, NT, n_units), 256 threads.  A workgroup owns 32 output channels of
+// one row tile; its 8 groups of 32 threads share the splits, so the partial
+// buffer is read with many independent 128-byte loads in flight.
+template <typename E, int D>
+__global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0, int n_units, int Tq,
+                                                           int B, E *out, float *lse) {
+    const int dg = blockIdx.x, tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc, NT = gridDim.y;
+    const int tid = threadIdx.x;
+    const int G = dv.G, Hq = dv.Hq, lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
+    const int rows = min(kRowTile, R - tile * kRowTile);
+    const SplitSlot slot = split_slot<true>(dv.n_sel + u0, n_units, B, uc);
+    const int n_splits = slot.S;                 // 0 if the unit retrieved nothing
+    const size_t e0 = (size_t)slot.base * NT + (size_t)tile * n_splits;
+    __shared__ float w_sh[kMaxUnitSplits][kRowTile];
+    __shared__ float pm[16][kRowTile], pl[16][kRowTile];
+    __shared__ float M_sh[kRowTile], L_sh[kRowTile];
+    __shared__ float red[8][kRowTile][33];
+    const int sg = tid / 32, col = tid % 32;
+    float acc[kRowTile];
+    if (rows <= 8) {             // block-uniform choices
+        if (n_splits <= 128) combine_accumulate<D, 128, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+        else combine_accumulate<D, kMaxUnitSplits, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+    } else {
+        if (n_splits <= 64) combine_accumulate<D, 64, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+        else combine_accumulate<D, kMaxUnitSplits, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
     }
 #pragma unroll
     for (int r = 0; r < kRowTile; ++r) red[sg][r][col] = acc[r];

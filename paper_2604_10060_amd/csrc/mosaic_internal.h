@@ -13,7 +13,8 @@ namespace mosaic {
 constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts of 64)
 constexpr int kRowTile = 16;      // query rows per attention tile
 constexpr int kChunk = 32;        // tokens per attention step, always inside one page
-constexpr int kMaxSplits = 64;    // KV splits per (unit, row tile)
+constexpr int kMaxSplits = 64;    // KV splits per (unit, row tile), average over the units of a launch
+constexpr int kMaxUnitSplits = 256; // ... and the most one unit can be given when the units retrieve unequal amounts
 constexpr int kPrefillTiles = 2;  // row tiles per wavefront in the multi-tile MFMA kernel
 
 // Device-side view of one context: plain pointers into the caller's arena.
@@ -194,7 +195,7 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
 // block) for the n_units units of the call.  Units retrieve different numbers
 // of tokens, so the splits are shared out in proportion to the selected page
 // counts: unit i gets (n_sel_i > 0) + floor((B - n_units) * n_sel_i / total),
-// capped at kMaxSplits, contiguous workgroup ids, in unit order.  The attention
+// capped at kMaxUnitSplits, contiguous workgroup ids, in unit order.  The attention
 // kernels (by workgroup id) and the combine kernel (by unit) evaluate the same
 // function of the same device-resident sizes, so they agree without any
 // host round trip.  Every lane of the calling wavefront gets the result.
@@ -221,7 +222,7 @@ __device__ __forceinline__ SplitSlot split_slot(const int *n_sel_call, int n_uni
         int want = 0;
         if (i < n_units && ns > 0) {
             want = 1 + (int)(((long long)(B - n_units) * ns) / (total > 0 ? total : 1));
-            want = min(want, kMaxSplits);
+            want = min(want, kMaxUnitSplits);
         }
         int incl = want;
 #pragma unroll

@@ -39,9 +39,9 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 # (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter read on
 # k_calibration_copy, a 256 MiB copy): see profiles/.  Keyed by (workload, calls).
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg1_single_layer_hbm", "per_layer"): 27_150_000,     # 26.41 MB read + 0.74 MB written
-    ("cfg2_full_stack_hbm", "per_layer"): 117_650_000,      # 116.94 MB + 0.71 MB
-    ("cfg2_full_stack_hbm", "all_layers"): 3_279_920_000,   # 3272.38 MB + 7.54 MB
+    ("cfg1_single_layer_hbm", "per_layer", "k_attend_decode_mfma"): 27_150_000,     # 26.41 MB read + 0.74 MB written
+    ("cfg2_full_stack_hbm", "per_layer", "k_attend_decode_mfma"): 117_650_000,      # 116.94 MB + 0.71 MB
+    ("cfg2_full_stack_hbm", "all_layers", "k_attend_decode_mfma"): 3_279_920_000,   # 3272.38 MB + 7.54 MB
 }
 
 
@@ -59,6 +59,8 @@ def parse():
     ap.add_argument("--frames", type=int, default=0, help="override the frame count")
     ap.add_argument("--all-layers-call", action="store_true",
                     help="one retrieve/attend call for all layers instead of per-layer calls")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="per-layer decode steps as mosaic_retrieve + mosaic_attend instead of mosaic_decode_step")
     ap.add_argument("--no-extra", action="store_true",
                     help="skip the config-2 legs reported under `extra`")
     ap.add_argument("--extra-steps", type=int, default=32)
@@ -86,15 +88,19 @@ def n_tok_all(m, L):
     return out
 
 
-def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrate=False, aug=None):
-    """aug = (window_frames, global_reps) switches the retrieval augmentation of Sec. V-C on."""
+def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrate=False, aug=None,
+            two_calls=False):
+    """aug = (window_frames, global_reps) switches the retrieval augmentation of Sec. V-C on.
+    Per-layer decode steps go through mosaic_decode_step (selection and attention in one kernel
+    where the library supports it) unless two_calls asks for mosaic_retrieve + mosaic_attend."""
     import torch
     from paper_2604_10060_amd import binding, inputs
 
     dev = "cuda:0"
     L, Hq, D, T, F = wl.n_layers, wl.n_q_heads, wl.head_dim, wl.tokens_per_frame, wl.n_frames
     esz = 4 if wl.kv_dtype == "fp32" else 2
-    mode = "all_layers" if all_layers else "per_layer"
+    one_call = not all_layers and not two_calls
+    mode = "all_layers" if all_layers else ("per_layer_decode_step" if one_call else "per_layer")
 
     # ---- synthetic stream, generated on the device ---------------------------------
     t0 = time.time()
@@ -173,7 +179,7 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
             assert np.array_equal(A[u], o.assignments()), f"unit {(l, hh)}: assignments differ from the oracle"
             oracles[(l, hh)] = o
         rep = harness.Report()
-        lm = "all" if all_layers else "per_layer"
+        lm = "all" if all_layers else ("fused" if one_call else "per_layer")
         if aug:
             harness.query_augmented_with_parity(m, wl, q_question, oracles, K_all, V_all, rep, aug[0], aug[1])
             harness.query_augmented_with_parity(m, wl, q_dec[0], oracles, K_all, V_all, rep, aug[0], aug[1])
@@ -221,6 +227,9 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
         if all_layers:
             m.retrieve_raw(-1, qp, 1)
             m.attend_raw(-1, qp, 1, op, lp)
+        elif one_call:
+            for l in range(L):
+                m.decode_step_raw(l, qp + l * layer_q_bytes, 1, op + l * out_layer, lp + l * lse_layer)
         else:
             for l in range(L):
                 m.retrieve_raw(l, qp + l * layer_q_bytes, 1)
@@ -278,6 +287,8 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
     step_gbps = (bytes_total / steps) / (us_per_step * 1e-6) / 1e9
     stats = m.stats()
     kernel = ("k_attend_decode_mfma" if stats.attend_impl == binding.ATTEND_MFMA else "k_attend_valu")
+    if one_call and stats.last_decode_fused:       # selection and attention ran as one kernel
+        kernel = "k_decode_fused"
 
     cpu = None
     if cpu_seconds > 0:
@@ -293,7 +304,7 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
                    "top_k": wl.top_k, "calls": mode, "kv_splits": stats.last_n_splits},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode)),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode, kernel)),
                      "kernel": kernel, "kernel_us": round(kern_us, 3),
                      "launches": int(launches), "bytes_per_launch": round(bytes_per_launch)},
         "cpu_baseline": cpu,
@@ -905,14 +916,25 @@ def main():
                        check_units=args.check_units,
                        cpu_seconds=0 if args.no_cpu_baseline else args.cpu_seconds,
                        calibrate=args.calibrate_copy,
-                       aug=(args.aug_window, args.aug_reps) if (args.aug_window or args.aug_reps) else None)
+                       aug=(args.aug_window, args.aug_reps) if (args.aug_window or args.aug_reps) else None,
+                       two_calls=args.two_calls)
     extra = None
     if not args.no_extra and args.workload == "cfg1" and not (args.layers or args.frames):
         extra = {}
+        if not args.two_calls:
+            try:
+                leg = run_leg(inputs.CONFIGS[1], steps=args.steps, warmup=args.warmup, all_layers=False,
+                              check_units=1, cpu_seconds=0, two_calls=True)
+                extra["cfg1_retrieve_then_attend"] = {
+                    "decode_step_us": round(leg["us_per_step"], 2), "config": leg["config"],
+                    "step_us_median": leg["step_us_median"], "step_us_p95": leg["step_us_p95"],
+                    "roofline": leg["roofline"], "parity_spot_check": leg["parity_spot_check"]}
+            except Exception as ex:                  # noqa: BLE001
+                extra["cfg1_retrieve_then_attend"] = {"error": repr(ex)[:300]}
         for all_layers in (False, True):
             try:
                 leg = run_leg(inputs.CONFIGS[2], steps=args.extra_steps, warmup=4, all_layers=all_layers,
-                              check_units=1 if all_layers else 0, cpu_seconds=0)
+                              check_units=1 if all_layers else 0, cpu_seconds=0, two_calls=args.two_calls)
             except Exception as ex:                  # noqa: BLE001
                 extra["cfg2_" + ("all_layers" if all_layers else "per_layer")] = {"error": repr(ex)[:300]}
                 continue

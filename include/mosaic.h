@@ -159,7 +159,7 @@ typedef struct {
     int32_t ready;             /* 1 once the initial clustering has run */
     int32_t attend_impl;       /* the kernel family in use (MOSAIC_ATTEND_VALU or _MFMA) */
     int32_t last_n_splits;     /* average KV splits per unit used by the latest attend */
-    int32_t reserved;
+    int32_t last_decode_fused; /* 1 if the latest mosaic_decode_step ran the single fused kernel */
     /* host tier */
     int64_t cache_hits, cache_misses;   /* selected clusters found in / missing from the GPU cache */
     int64_t h2d_bytes, h2d_copies;      /* cluster fetches: bytes moved host-to-device and fetch-kernel launches */
@@ -258,6 +258,20 @@ int32_t mosaic_prefetch(mosaic_ctx *ctx, int32_t layer, const void *q_proxy_dev,
  * Host tier: the stream first waits (on the device) for the layer's fetches. */
 int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
                       int32_t n_q_tokens, void *out_dev, float *lse_dev);
+
+/* One decode step in one call: mosaic_retrieve(layer, q) followed by mosaic_attend(layer, q) --
+ * same arguments, errors, selection left behind (ids, scores, page list: the observers and a
+ * later mosaic_attend see it) and the same output up to the order in which fp32 partial sums are
+ * merged.  Where it applies -- MOSAIC_TIER_HBM, bf16 MFMA attention, layer >= 0, at most 16 query
+ * rows per KV head (n_q_tokens * Hq/Hkv <= 16), n_clusters <= 256, maintainer, augmentation and
+ * nested index off, and an expected K/V volume of the step (frames * top_k / n_clusters pages per
+ * KV head) of at most 48 MiB, i.e. a step that is bound by launch and memory latency rather than
+ * by bandwidth -- the selection and the attention over the selected clusters run in ONE kernel
+ * (every attention workgroup repeats its unit's selection for itself, which is cheaper than a
+ * launch boundary and the dependent loads after it; KV splits are then equal per unit instead of
+ * proportional to the retrieved size); everywhere else it simply makes the two calls. */
+int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
+                           void *out_dev, float *lse_dev);
 
 /* Observers for parity checks.  All outputs are HOST pointers, caller-allocated;
  * each call synchronises the stream.  NULL outputs are skipped. */

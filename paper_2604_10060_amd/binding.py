@@ -27,7 +27,7 @@ EXPORTS = (
     "mosaic_workspace_size", "mosaic_create", "mosaic_destroy", "mosaic_reset",
     "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_prefetch", "mosaic_attend",
     "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries", "mosaic_get_maintainer",
-    "mosaic_ingest_frame_visual", "mosaic_get_partitions", "mosaic_get_partition_selection",
+    "mosaic_decode_step", "mosaic_ingest_frame_visual", "mosaic_get_partitions", "mosaic_get_partition_selection",
     "mosaic_get_selection", "mosaic_get_stats", "mosaic_profile_enable",
     "mosaic_profile_read", "mosaic_calibration_copy", "mosaic_last_error",
 )
@@ -65,7 +65,7 @@ class Stats(C.Structure):
         ("frames_ingested", C.c_int64), ("lloyd_runs", C.c_int64),
         ("retrieve_calls", C.c_int64), ("attend_calls", C.c_int64),
         ("kv_bytes_stored", C.c_int64), ("ready", C.c_int32), ("attend_impl", C.c_int32),
-        ("last_n_splits", C.c_int32), ("reserved", C.c_int32),
+        ("last_n_splits", C.c_int32), ("last_decode_fused", C.c_int32),
         ("cache_hits", C.c_int64), ("cache_misses", C.c_int64),
         ("h2d_bytes", C.c_int64), ("h2d_copies", C.c_int64), ("h2d_busy_ms", C.c_double),
         ("prefetch_calls", C.c_int64), ("prefetch_fetched", C.c_int64), ("prefetch_useful", C.c_int64),
@@ -99,6 +99,7 @@ def load_library():
     L.mosaic_retrieve.argtypes = [vp, i32, vp, i32]
     L.mosaic_attend.argtypes = [vp, i32, vp, i32, vp, vp]
     L.mosaic_prefetch.argtypes = [vp, i32, vp, i32]
+    L.mosaic_decode_step.argtypes = [vp, i32, vp, i32, vp, vp]
     L.mosaic_get_assignments.argtypes = [vp, vp]
     L.mosaic_get_centroids.argtypes = [vp, vp, vp]
     L.mosaic_get_summaries.argtypes = [vp, vp]
@@ -274,7 +275,24 @@ class Mosaic:
         self._check(self._L.mosaic_attend(self._h, layer, _ptr(q), tq, _ptr(out), _ptr(lse)))
         return out, lse
 
+    def decode_step(self, layer: int, q, out=None, lse=None):
+        """retrieve + attend in one call (one fused kernel where it applies)"""
+        torch = self._torch
+        shape, tq = self._q_shape(layer, q)
+        self._check_tensor(q, shape, "q")
+        if out is None:
+            out = torch.empty(shape, dtype=self.dtype, device=self.device)
+        if lse is None:
+            lse = torch.empty(shape[:-1], dtype=torch.float32, device=self.device)
+        self._check(self._L.mosaic_decode_step(self._h, layer, _ptr(q), tq, _ptr(out), _ptr(lse)))
+        return out, lse
+
     # -- unchecked variants for timed loops: raw device addresses, same C calls --
+    def decode_step_raw(self, layer: int, q_ptr: int, n_q_tokens: int, out_ptr: int, lse_ptr: int):
+        rc = self._L.mosaic_decode_step(self._h, layer, q_ptr, n_q_tokens, out_ptr, lse_ptr)
+        if rc != OK:
+            self._check(rc)
+
     def retrieve_raw(self, layer: int, q_ptr: int, n_q_tokens: int):
         rc = self._L.mosaic_retrieve(self._h, layer, q_ptr, n_q_tokens)
         if rc != OK:

@@ -832,6 +832,63 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t
     return MOSAIC_OK;
 }
 
+int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
+                           void *out_dev, float *lse_dev) {
+    if (!ctx) return MOSAIC_EINVAL;
+    const DeviceView &dv = ctx->dv;
+    const long long NT = ((long long)n_q_tokens * dv.G + kRowTile - 1) / kRowTile;
+    // The fused kernel pays for a shorter launch chain with equal (not size-proportional) splits and a
+    // selection repeated by every workgroup: it wins while the step is latency-bound, i.e. while the
+    // expected K/V volume of the launch is small (measured: 26 MB -15 %, 118 MB +7 %).
+    const long long est_pages = std::max<long long>(1, (ctx->n_frames * dv.k + dv.C - 1) / dv.C);
+    const long long est_bytes = (long long)dv.Hkv * est_pages * (long long)(dv.kpage + dv.vpage);
+    const bool fused = !ctx->host && ctx->impl == MOSAIC_ATTEND_MFMA && layer >= 0 && NT == 1 &&
+                       dv.maint_mode == MOSAIC_MAINT_OFF && !dv.aug_reps && !dv.aug_window && dv.P == 0 &&
+                       dv.C <= 256 && est_bytes <= (48ll << 20);
+    int S = 0;
+    if (fused) {
+        S = choose_splits(ctx, dv.Hkv, n_q_tokens);
+        // a workgroup lists the pages of its chunk range in LDS (2048 entries)
+        while (S < kMaxSplits && ctx->n_frames / S + 2 > 2048) ++S;
+    }
+    if (!fused || ctx->n_frames / std::max(S, 1) + 2 > 2048 ||
+        (long long)dv.Hkv * S > dv.part_entries) {
+        ctx->stats.last_decode_fused = 0;
+        const int rc = mosaic_retrieve(ctx, layer, q_dev, n_q_tokens);
+        return rc != MOSAIC_OK ? rc : mosaic_attend(ctx, layer, q_dev, n_q_tokens, out_dev, lse_dev);
+    }
+    int u0, nu;
+    int rc = check_query_args(ctx, layer, q_dev, n_q_tokens, &u0, &nu);
+    if (rc != MOSAIC_OK) return rc;
+    if (!out_dev) return fail(ctx, MOSAIC_EINVAL, "out_dev is NULL");
+    if (ctx->n_frames < ctx->W) return fail(ctx, MOSAIC_ENOTREADY, "initial clustering has not run yet (fewer than warmup_frames frames ingested)");
+    hipError_t e;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (ctx->profile) {
+        if (ctx->ev_used + 2 > ctx->ev.size()) {
+            for (int i = 0; i < 2; ++i) {
+                hipEvent_t x;
+                e = hipEventCreate(&x);
+                if (e != hipSuccess) return fail_hip(ctx, e, "hipEventCreate");
+                ctx->ev.push_back(x);
+            }
+        }
+        ev0 = ctx->ev[ctx->ev_used]; ev1 = ctx->ev[ctx->ev_used + 1];
+        ctx->ev_used += 2;
+    }
+    e = launch_decode_fused(dv, u0, nu, q_dev, n_q_tokens, S, (int)ctx->n_frames, ctx->cfg.score_mode,
+                            ctx->stream, ev0, ev1);
+    if (e != hipSuccess) return fail_hip(ctx, e, "fused decode launch");
+    e = launch_attend_combine(dv, u0, nu, n_q_tokens, S, out_dev, lse_dev, ctx->stream, true);
+    if (e != hipSuccess) return fail_hip(ctx, e, "combine launch");
+    ctx->sel_epoch[layer] = ctx->epoch; ctx->sel_tq[layer] = n_q_tokens;
+    ctx->stats.retrieve_calls += 1;
+    ctx->stats.attend_calls += 1;
+    ctx->stats.last_n_splits = S;
+    ctx->stats.last_decode_fused = 1;
+    return MOSAIC_OK;
+}
+
 static int d2h(mosaic_ctx *ctx, void *dst, const void *src, size_t bytes) {
     hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync D2H");

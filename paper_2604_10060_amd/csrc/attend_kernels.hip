@@ -239,12 +239,15 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
 // buffer is read with many independent 128-byte loads in flight.
 template <typename E, int D>
 __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0, int n_units, int Tq,
-                                                           int B, E *out, float *lse) {
+                                                           int B, int uniform_S, E *out, float *lse) {
     const int dg = blockIdx.x, tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc, NT = gridDim.y;
     const int tid = threadIdx.x;
     const int G = dv.G, Hq = dv.Hq, lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
     const int rows = min(kRowTile, R - tile * kRowTile);
-    const SplitSlot slot = split_slot<true>(dv.n_sel + u0, n_units, B, uc);
+    // uniform_S > 0: every unit has exactly that many splits (the fused decode step); else the
+    // splits were shared out by retrieved size and split_slot() says how
+    SplitSlot slot{uc, 0, uniform_S, uc * uniform_S};
+    if (uniform_S <= 0) slot = split_slot<true>(dv.n_sel + u0, n_units, B, uc);
     const int n_splits = slot.S;                 // 0 if the unit retrieved nothing
     const size_t e0 = (size_t)slot.base * NT + (size_t)tile * n_splits;
     __shared__ float w_sh[kMaxUnitSplits][kRowTile];
@@ -307,16 +310,17 @@ hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const v
 }
 
 hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
-                                 void *out, float *lse, hipStream_t s) {
+                                 void *out, float *lse, hipStream_t s, bool uniform) {
+    const int us = uniform ? n_splits : 0;
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
     const int B = n_units * n_splits;
     dim3 grid(dv.D / 32, NT, n_units);
     if (dv.esize == 4) {
-        if (dv.D == 64) k_attend_combine<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, (float *)out, lse);
-        else k_attend_combine<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, (float *)out, lse);
+        if (dv.D == 64) k_attend_combine<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, us, (float *)out, lse);
+        else k_attend_combine<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, us, (float *)out, lse);
     } else {
-        if (dv.D == 64) k_attend_combine<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, (unsigned short *)out, lse);
-        else k_attend_combine<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, (unsigned short *)out, lse);
+        if (dv.D == 64) k_attend_combine<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, us, (unsigned short *)out, lse);
+        else k_attend_combine<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, us, (unsigned short *)out, lse);
     }
     return hipGetLastError();
 }

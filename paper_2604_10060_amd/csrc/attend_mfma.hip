@@ -177,6 +177,48 @@ __device__ __forceinline__ void load_q(const DeviceView &dv, const unsigned shor
     }
 }
 
+// Merge of the four wavefronts' running (m, l, O) of one row tile and store of the
+// workgroup's partial at `entry` (shared by the decode kernels).  All threads call it.
+template <int D>
+__device__ __forceinline__ void merge_waves_store(const DeviceView &dv, const f32x4 (&acc)[D / 16], float m, float l,
+                                                  int R, size_t entry) {
+    constexpr int DB = D / 16;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    __shared__ float o_sh[4][D][kRowTile + 1];
+    __shared__ float m_sh[4][kRowTile], l_sh[4][kRowTile];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o_sh[wave][16 * db + 4 * g + i][n] = acc[db][i];
+    if (g == 0) { m_sh[wave][n] = m; l_sh[wave][n] = l; }
+    __syncthreads();
+    const int row = tid / 16, dl = tid % 16;
+    if (row >= R) return;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, m_sh[w][row]);
+    float wgt[4], Lsum = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        wgt[w] = M > -INFINITY ? __builtin_amdgcn_exp2f(m_sh[w][row] - M) : 0.f;
+        Lsum += wgt[w] * l_sh[w][row];
+    }
+    float *po = dv.part_o + (entry * kRowTile + row) * D;
+#pragma unroll
+    for (int d = dl; d < D; d += 16) {
+        float o = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) o += wgt[w] * o_sh[w][d][row];
+        po[d] = o;
+    }
+    if (dl == 0) {
+        dv.part_ml[entry * 2 * kRowTile + row] = M;
+        dv.part_ml[entry * 2 * kRowTile + kRowTile + row] = Lsum;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Decode shape: at most 16 query rows per unit (one row tile).
 // grid (n_units * n_splits), 4 waves; split_slot() shares the workgroups out
@@ -272,42 +314,237 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
             step(kA, vA, ccA);
         }
     }
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-
     // merge the four waves, write one partial per workgroup
-    __shared__ float o_sh[4][D][kRowTile + 1];
-    __shared__ float m_sh[4][kRowTile], l_sh[4][kRowTile];
+    merge_waves_store<D>(dv, acc, m, l, R, (size_t)slot.base + split);        // one row tile
+}
+
+// ---------------------------------------------------------------------------
+// Fused decode step (one row tile, per-layer call): selection and attention in one
+// launch.  grid (n_units * S), 4 waves; workgroup = (unit, split), S uniform.
+// Every workgroup of a unit first repeats the unit's selection for itself -- mean
+// query, scores of the C <= 256 representatives, ranks of the k best, page offsets --
+// which costs it 64-128 KB of table reads that hit L2 and ~1.5 us of arithmetic, but
+// removes the separate selection launch and the two dependent round trips (sizes,
+// page ids) at the start of the attention kernel; it then lists the pages of its own
+// contiguous chunk range in LDS and reduces them like k_attend_decode_mfma.  Split 0
+// of each unit also writes the selection (scores, ids, page list, counts) to memory,
+// so the observers and a later mosaic_attend see what mosaic_retrieve would have left.
+// Same arithmetic, lane for lane, as k_retrieve (scores, ranking) and as the decode
+// kernel (chunk steps), hence the same ids, token lists and -- up to the order in
+// which partials are merged -- outputs.
+// ---------------------------------------------------------------------------
+constexpr int kFusedMaxC = 256, kFusedList = 2048;
+
+__device__ __forceinline__ double group16_sum_f64(double x) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int o = 8; o >= 1; o >>= 1) x += __shfl_xor(x, o, 16);
+    return x;
+}
+
+template <int D>
+__global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, const unsigned short *q, int Tq,
+                                                         int S, int n_frames, int score_mode) {
+    constexpr int KK = D / 32, DB = D / 16, EPL = D / 16, NG = kBlock / 16, RPF = 8, FPT = 8;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
+    const int lr = tid % 16, grp = tid / 16;
+    const int uc = (int)blockIdx.x / S, split = (int)blockIdx.x % S, u = u0 + uc;
+    const int C = dv.C, k = dv.k, G = dv.G, Hq = dv.Hq, T = dv.T, F = dv.F, cpp = dv.chunks_per_page;
+    const int lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
+    __shared__ double qbar[D];
+    __shared__ double sc_sh[kFusedMaxC], rn_sh[kFusedMaxC];
+    __shared__ int n_sh[kFusedMaxC], rank_sh[kFusedMaxC], cnt_sh[kFusedMaxC], ids_sh[kFusedMaxC], off_sh[kFusedMaxC + 1];
+    __shared__ int list_sh[kFusedList];
+    __shared__ int n_live_sh;
+    const double *r = dv.r + (size_t)u * C * D;
+    const int *assign = dv.assign + (size_t)u * F;
+    const int *pos = dv.pos + (size_t)u * F;
+
+    // ---- independent loads, all issued up front ----
+    bf16x8 qf[KK];
+    load_q<D>(dv, q, lc, h, Tq, n, g, qf);
+    int fa[FPT], fp[FPT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o_sh[wave][16 * db + 4 * g + i][n] = acc[db][i];
-    if (g == 0) { m_sh[wave][n] = m; l_sh[wave][n] = l; }
+    for (int i = 0; i < FPT; ++i) {
+        const int f = tid + kBlock * i;
+        fa[i] = f < n_frames ? assign[f] : -1;
+        fp[i] = f < n_frames ? pos[f] : 0;
+    }
+    for (int j = tid; j < C; j += kBlock) {
+        n_sh[j] = dv.n[(size_t)u * C + j];
+        rn_sh[j] = dv.rnorm[(size_t)u * C + j];
+        cnt_sh[j] = 0;
+    }
+    if (tid == 0) n_live_sh = 0;
+    double rpre[RPF][EPL];
+#pragma unroll
+    for (int i = 0; i < RPF; ++i) {
+        const double *rj = r + (size_t)min(grp + NG * i, C - 1) * D + lr * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
+    }
+    if (tid < D) {      // mean query over the Tq tokens and the G query heads of this KV head
+        // (R <= 16: two batches of eight loads, row index clamped, loads unconditional)
+        const unsigned short *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + tid;
+        double a = 0.0;
+        for (int r0 = 0; r0 < R; r0 += 8) {
+            unsigned short v[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int rr = min(r0 + x, R - 1), t = rr / G, gg = rr - t * G;
+                v[x] = qb[((size_t)t * Hq + gg) * D];
+            }
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+                if (r0 + x < R) a += (double)bf16_to_f32(v[x]);
+        }
+        qbar[tid] = a / (double)R;
+    }
     __syncthreads();
-    const int row = tid / 16, dl = tid % 16;
-    if (row >= R) return;
-    float M = -INFINITY;
+    // ---- scores: score_j = (qbar . r_j) / |r_j|   (plain dot product in score_mode 1) ----
+    // the 16-lane groups leave the raw dot products in LDS; thread j then finishes entry j
+    // (one fp64 division per thread instead of one per row on a single lane)
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, m_sh[w][row]);
-    float wgt[4], Lsum = 0.f;
+    for (int i = 0; i < RPF; ++i) {
+        const int j = grp + NG * i;
+        if (j < C) {
+            double p = 0.0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        wgt[w] = M > -INFINITY ? __builtin_amdgcn_exp2f(m_sh[w][row] - M) : 0.f;
-        Lsum += wgt[w] * l_sh[w][row];
+            for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rpre[i][e];
+            p = group16_sum_f64(p);
+            if (lr == 0) sc_sh[j] = p;
+        }
     }
-    const size_t entry = (size_t)slot.base + split;        // one row tile
-    float *po = dv.part_o + (entry * kRowTile + row) * D;
+    for (int j = grp + NG * RPF; j < C; j += NG) {
+        const double *rj = r + (size_t)j * D + lr * EPL;
+        double p = 0.0;
 #pragma unroll
-    for (int d = dl; d < D; d += 16) {
-        float o = 0.f;
+        for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rj[e];
+        p = group16_sum_f64(p);
+        if (lr == 0) sc_sh[j] = p;
+    }
+    __syncthreads();
+    if (tid < C) {
+        double sc = -INFINITY;
+        if (n_sh[tid] > 0) {
+            const double p = sc_sh[tid], nr = rn_sh[tid];
+            sc = score_mode == 1 ? p : (nr == 0.0 ? 0.0 : p / nr);
+        }
+        sc_sh[tid] = sc;
+        if (split == 0) dv.scores[(size_t)u * dv.SC + tid] = sc;
+    }
+    __syncthreads();
+    // ---- ranks by (score descending, id ascending) among the non-empty clusters ----
+    {
+        const int per = max(1, kBlock / C);
+        for (int item = tid; item < C * per; item += kBlock) {
+            const int j = item % C, part = item / C;
+            if (n_sh[j] <= 0) continue;
+            const double sj = sc_sh[j];
+            const int i0 = (C * part) / per, i1 = (C * (part + 1)) / per;
+            int c = 0;           // (an empty cluster carries -inf and never outranks a live one)
+#pragma unroll 8
+            for (int i = i0; i < i1; ++i) {
+                const double si = sc_sh[i];
+                c += (si > sj) || (si == sj && i < j);
+            }
+            atomicAdd(&cnt_sh[j], c);
+        }
+    }
+    __syncthreads();
+    {   // C <= 256 = kBlock: thread j owns entry j; live entries counted with one atomic per wavefront
+        const bool live = tid < C && n_sh[tid] > 0;
+        int rk = -1;
+        if (live) {
+            rk = cnt_sh[tid];
+            if (rk < k) ids_sh[rk] = tid; else rk = -1;
+        }
+        if (tid < C) rank_sh[tid] = rk;
+        const unsigned long long lb = __ballot(live);
+        if (lane == 0 && lb) atomicAdd(&n_live_sh, __popcll(lb));
+    }
+    __syncthreads();
+    const int n_ids = min(k, n_live_sh);
+    if (tid == 0) {
+        int o = 0;
+        off_sh[0] = 0;
+        for (int i = 0; i < n_ids; ++i) { o += n_sh[ids_sh[i]]; off_sh[i + 1] = o; }
+        if (split == 0) { dv.n_ids[u] = n_ids; dv.n_sel[u] = o; }
+    }
+    if (split == 0)
+        for (int i = tid; i < k; i += kBlock) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
+    __syncthreads();
+    // ---- this workgroup's chunk range and its pages ----
+    const int NC = off_sh[n_ids] * cpp;
+    const int cps = (NC + S - 1) / S;
+    const int c0 = split * cps, c1 = min(NC, c0 + cps);
+    const int p_lo = c0 / cpp, p_hi = c1 > c0 ? (c1 - 1) / cpp : p_lo - 1;
+    int *sel = dv.sel_pages + (size_t)u * F;
+    auto place = [&](int f, int a, int ps) {
+        if (a < 0) return;
+        const int rk = rank_sh[a];
+        if (rk < 0) return;
+        const int p = off_sh[rk] + ps;
+        if (p >= p_lo && p <= p_hi) list_sh[p - p_lo] = f;
+        if (split == 0) sel[p] = f;
+    };
 #pragma unroll
-        for (int w = 0; w < 4; ++w) o += wgt[w] * o_sh[w][d][row];
-        po[d] = o;
+    for (int i = 0; i < FPT; ++i) place(tid + kBlock * i, fa[i], fp[i]);
+    for (int f0 = tid + kBlock * FPT; f0 < n_frames; f0 += kBlock * FPT) {      // further batches of FPT loads
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) {
+            const int f = f0 + kBlock * i;
+            fa[i] = f < n_frames ? assign[f] : -1;
+            fp[i] = f < n_frames ? pos[f] : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) place(f0 + kBlock * i, fa[i], fp[i]);
     }
-    if (dl == 0) {
-        dv.part_ml[entry * 2 * kRowTile + row] = M;
-        dv.part_ml[entry * 2 * kRowTile + kRowTile + row] = Lsum;
+    __syncthreads();
+
+    // ---- attention over chunks c0 + wave, + 4, ... of the range ----
+    const float sl2 = 1.4426950408889634f / sqrtf((float)D);
+    f32x4 acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+    const int first = c0 + wave;
+    const int n_my = first < c1 ? (c1 - first + 3) / 4 : 0;
+    bf16x8 kA[2 * KK], vA[DB], kB[2 * KK], vB[DB];
+    int ccA = 0, ccB = 0;
+    auto issue = [&](int c, bf16x8 (&kf)[2 * KK], bf16x8 (&vf)[DB], int &cc) {
+        const int pi = c / cpp;
+        cc = c - pi * cpp;
+        const int page = list_sh[pi - p_lo];
+        const char *kp = dv.k_store + (size_t)u * dv.k_ustride + (size_t)page * dv.k_bstride;
+        const char *vp = dv.v_store + (size_t)u * dv.v_ustride + (size_t)page * dv.v_bstride;
+        issue_chunk<D>(reinterpret_cast<const unsigned short *>(kp),
+                       reinterpret_cast<const unsigned short *>(vp) + (size_t)cc * D * 32,
+                       cc * kChunk, T, g, n, kf, vf);
+    };
+    auto step = [&](const bf16x8 (&kf)[2 * KK], const bf16x8 (&vf)[DB], int cc) {
+        chunk_step<D>(kf, vf, qf, min(kChunk, T - cc * kChunk), g, sl2, acc, m, l);
+    };
+    if (n_my > 0) {
+        issue(first, kA, vA, ccA);
+        int i = 0;
+        for (; i + 2 < n_my; i += 2) {
+            issue(first + 4 * (i + 1), kB, vB, ccB);
+            __builtin_amdgcn_sched_barrier(0);
+            step(kA, vA, ccA);
+            issue(first + 4 * (i + 2), kA, vA, ccA);
+            __builtin_amdgcn_sched_barrier(0);
+            step(kB, vB, ccB);
+        }
+        if (i + 2 == n_my) {
+            issue(first + 4 * (i + 1), kB, vB, ccB);
+            __builtin_amdgcn_sched_barrier(0);
+            step(kA, vA, ccA);
+            step(kB, vB, ccB);
+        } else {
+            step(kA, vA, ccA);
+        }
     }
+    merge_waves_store<D>(dv, acc, m, l, R, (size_t)uc * S + split);
 }
 
 // ---------------------------------------------------------------------------
@@ -505,6 +742,15 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
 }
 
 } // namespace
+
+hipError_t launch_decode_fused(const DeviceView &dv, int u0, int n_units, const void *q, int Tq, int n_splits,
+                               int n_frames, int score_mode, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+    const dim3 grid(n_units * n_splits), block(kBlock);
+    const unsigned short *qq = (const unsigned short *)q;
+    if (dv.D == 64) hipExtLaunchKernelGGL((k_decode_fused<64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+    else hipExtLaunchKernelGGL((k_decode_fused<128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+    return hipGetLastError();
+}
 
 hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                               int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {

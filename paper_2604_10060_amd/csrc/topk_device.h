@@ -47,10 +47,11 @@ __device__ __forceinline__ int topk_rank(const double *sc_sh, const int *n_sh, i
         if (part < per && n_sh[j] > 0) {
             const double sj = sc_sh[j];
             const int i0 = (R * part) / per, i1 = (R * (part + 1)) / per;
-            int c = 0;
+            int c = 0;           // (an entry that is not live carries -inf and never outranks a live one)
+#pragma unroll 8
             for (int i = i0; i < i1; ++i) {
                 const double si = sc_sh[i];
-                c += n_sh[i] > 0 && ((si > sj) || (si == sj && i < j));
+                c += (si > sj) || (si == sj && i < j);
             }
             atomicAdd(&cnt_sh[j], c);
         }
@@ -58,10 +59,12 @@ __device__ __forceinline__ int topk_rank(const double *sc_sh, const int *n_sh, i
         int rk = -1;
         if (live) {
             rk = cnt_sh[tid];
-            atomicAdd(&sh.n_live, 1);
             if (rk < k) ids_sh[rk] = tid; else rk = -1;
         }
         if (tid < R) rank_sh[tid] = rk;
+        // live entries: one LDS atomic per wavefront (64 lanes adding to one word serialize)
+        const unsigned long long lb = __ballot(live);
+        if (lane == 0 && lb) atomicAdd(&sh.n_live, __popcll(lb));
         __syncthreads();
         return sh.n_live;
     }
@@ -110,7 +113,13 @@ __device__ __forceinline__ int topk_rank(const double *sc_sh, const int *n_sh, i
     __syncthreads();
     // ---- candidates: everything from bin b* upwards ----
     const bool cand = live && bin >= sh.bstar;
-    if (cand) cand_sh[atomicAdd(&sh.n_cand, 1)] = tid;
+    {   // compaction with one LDS atomic per wavefront
+        const unsigned long long cb = __ballot(cand);
+        int base = 0;
+        if (lane == 0 && cb) base = atomicAdd(&sh.n_cand, __popcll(cb));
+        base = __shfl(base, 0, 64);
+        if (cand) cand_sh[base + __popcll(cb & ((1ull << lane) - 1ull))] = tid;
+    }
     __syncthreads();
     const int M = sh.n_cand;
     // ---- exact ranks among the candidates, `per` threads per candidate ----
@@ -121,6 +130,7 @@ __device__ __forceinline__ int topk_rank(const double *sc_sh, const int *n_sh, i
         const double sj = sc_sh[j];
         const int i0 = (M * part) / per, i1 = (M * (part + 1)) / per;
         int c = 0;
+#pragma unroll 4
         for (int x = i0; x < i1; ++x) {
             const int i = cand_sh[x];
             const double si = sc_sh[i];

@@ -126,6 +126,12 @@ def query_with_parity(m: binding.Mosaic, wl, q: torch.Tensor, oracles, K, V, rep
     if layer_mode == "all":
         m.retrieve(-1, q)
         out, lse = m.attend(-1, q)
+    elif layer_mode == "fused":          # one C call per layer (one kernel for both stages where it applies)
+        outs, lses = [], []
+        for l in range(L):
+            o_, l_ = m.decode_step(l, q[l].contiguous())
+            outs.append(o_); lses.append(l_)
+        out, lse = torch.stack(outs), torch.stack(lses)
     else:
         outs, lses = [], []
         for l in range(L):

@@ -624,3 +624,78 @@ def test_nested_reset_and_reingest_reproduces_the_state():
     for a, b in zip(*snaps):
         np.testing.assert_array_equal(a, b)
     m.close()
+
+
+# ---------------------------------------------------------------------------
+# mosaic_decode_step: retrieve + attend in one call / one kernel
+# ---------------------------------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw", [
+    dict(),                                                   # the realistic head shape, C = 12
+    dict(n_clusters=200, top_k=9, n_frames=460),              # C > 128: one thread per entry in the ranking
+    dict(tokens_per_frame=50, n_frames=140),                  # ragged pages (two chunks, the second partly empty)
+    dict(head_dim=64, n_q_heads=8, n_kv_heads=2),             # D = 64, G = 4
+    dict(n_layers=2, n_frames=120),                           # two layers, one call each
+])
+def test_decode_step_fused_parity(kw):
+    wl = _small(name="fused", **kw)
+    rep = harness.run_workload(wl, n_questions=0, decode_steps=4, layer_mode="fused")
+    _report(rep)
+    assert rep.max_out_err <= 2e-2
+
+
+@pytest.mark.gpu
+def test_decode_step_equals_retrieve_then_attend():
+    """Same ids, scores and token lists bit for bit; outputs equal up to the merge order of the
+    fp32 partials (equal splits per unit instead of proportional ones)."""
+    wl = _small(name="fused_vs_calls", n_frames=300, n_clusters=24, top_k=6)
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    a = binding.Mosaic(binding.config_for(wl), device=DEV)
+    b = binding.Mosaic(binding.config_for(wl), device=DEV)
+    for m in (a, b):
+        m.ingest_frame(K.to(DEV), V.to(DEV))
+    for i in range(3):
+        q = st.question(st.draw_scene(), 1, i).to(DEV)[0].contiguous()
+        a.retrieve(0, q)
+        oa, la = a.attend(0, q)
+        ob, lb = b.decode_step(0, q)
+        torch.cuda.synchronize()
+        assert b.stats().last_decode_fused == 1           # the single-kernel path is what is compared
+        sa, sb = a.selection(0), b.selection(0)
+        np.testing.assert_array_equal(sa[0], sb[0])
+        np.testing.assert_array_equal(sa[1], sb[1])
+        np.testing.assert_array_equal(sa[2], sb[2])
+        for x, y in zip(sa[3], sb[3]):
+            np.testing.assert_array_equal(x, y)
+        assert (oa.float() - ob.float()).abs().max().item() <= 2e-2
+        assert (la - lb).abs().max().item() <= 1e-3
+        # a plain attend after the fused step uses the selection it left behind
+        oc, lc = b.attend(0, q)
+        torch.cuda.synchronize()
+        assert torch.equal(oc, oa) and torch.equal(lc, la)
+    a.close(); b.close()
+
+
+@pytest.mark.gpu
+def test_decode_step_falls_back_where_the_fused_kernel_does_not_apply():
+    # fp32 KV (vector-ALU attention), a multi-token question, all layers at once, the host tier
+    rep = harness.run_workload(inputs.CONFIGS[0], n_questions=1, decode_steps=2, layer_mode="fused")
+    assert rep.max_out_err <= 1e-4
+    wl = _small(name="fused_fallback", question_tokens=5)
+    rep = harness.run_workload(wl, n_questions=2, decode_steps=0, layer_mode="fused")
+    assert rep.max_out_err <= 2e-2
+    m = binding.Mosaic(binding.config_for(wl), device=DEV)
+    q = torch.zeros((1, 28, 128), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(binding.MosaicError) as ei:
+        m.decode_step(0, q)                                   # nothing ingested yet
+    assert ei.value.code == binding.ENOTREADY
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    m.ingest_frame(K.to(DEV), V.to(DEV))
+    q5 = st.question(0, 5, 0).to(DEV)[0].contiguous()         # 35 query rows per KV head: two calls
+    m.decode_step(0, q5)
+    assert m.stats().last_decode_fused == 0
+    m.decode_step(0, q5[:1].contiguous())                     # one token: the fused kernel
+    assert m.stats().last_decode_fused == 1
+    m.close()

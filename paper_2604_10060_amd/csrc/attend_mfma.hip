@@ -593,8 +593,12 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
     const int T = dv.T, F = dv.F, cpp = dv.chunks_per_page;
     const int lc = uc / dv.Hkv, h = u % dv.Hkv;
     const int tile0 = (yb * 4 + wave) * RTW;
-    __shared__ __attribute__((aligned(16))) unsigned short k_lds[2][kChunk][KROW];
-    __shared__ __attribute__((aligned(16))) unsigned short v_lds[2][D][VROW];
+    // LDS (dynamic: 74 KB at D = 128): two buffers of two 32-token chunks each, K then V
+    extern __shared__ __attribute__((aligned(16))) unsigned short prefill_lds[];
+    typedef unsigned short (*KTile)[kChunk][KROW];      // [buffer * 2 + half][token slot][channel]
+    typedef unsigned short (*VTile)[D][VROW];           // [buffer * 2 + half][channel][token]
+    const KTile k_lds = reinterpret_cast<KTile>(prefill_lds);
+    const VTile v_lds = reinterpret_cast<VTile>(prefill_lds + 4 * kChunk * KROW);
 
     bf16x8 qf[RTW][KK];
 #pragma unroll
@@ -666,7 +670,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
         }
         return r;
     };
-    auto stage = [&](int buf, const Regs &r) {   // registers -> LDS
+    auto stage = [&](int buf, const Regs &r) {   // registers -> LDS; buf = buffer * 2 + half
         auto kput = [&](int i, u32x4 x) {
             const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);
             const int row = 16 * ((t / 4) % 2) + 4 * (t / 8) + t % 4;   // MFMA slot order
@@ -698,30 +702,47 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
         chunk_step_multi<D, RTW, f32x4>(kf, vf, qf, n_valid, g, sl2, acc, m, l);
     };
 
-    // Pipeline: chunk c is computed from LDS buffer (c-c0)&1 while chunk c+1 sits in one
-    // register set and chunk c+2 is in flight in the other (two chunks of memory latency
-    // hidden behind every chunk of arithmetic).  Fetches past the end re-read the last
-    // chunk instead of being skipped, so the register sets are written unconditionally
-    // and stay in registers.
+    // Pipeline, two chunks (64 tokens) per barrier: the pair (c, c+1) is computed from LDS
+    // buffer b (slots 2b, 2b+1) while the next pair travels global -> the two register sets,
+    // and is stored into the other buffer once the pair is done.  Half as many barriers and
+    // twice the arithmetic between them as with one chunk per barrier; the same 64 tokens of
+    // memory latency hidden.  Fetches past the end re-read the last chunk instead of being
+    // skipped, so the register sets are written unconditionally and stay in registers.
     if (c0 < c1) {
         ra = fetch();
         rb = fetch();
         stage(0, ra);
+        stage(1, rb);
         __syncthreads();
         int c = c0;
-        for (; c + 1 < c1; c += 2) {
-            // LDS[0] holds c, regs B hold c+1
+        for (; c + 4 <= c1; c += 4) {
             ra = fetch();
+            rb = fetch();
             compute(0);
+            compute(1);
+            stage(2, ra);
+            stage(3, rb);
+            __syncthreads();
+            ra = fetch();
+            rb = fetch();
+            compute(2);
+            compute(3);
+            stage(0, ra);
             stage(1, rb);
             __syncthreads();
-            // LDS[1] holds c+1, regs A hold c+2
-            rb = fetch();
-            compute(1);
-            stage(0, ra);
-            __syncthreads();
         }
-        if (c < c1) compute(0);
+        const int rem = c1 - c;                       // 0..3 chunks left, the first two in buffer 0
+        if (rem > 2) {
+            ra = fetch();
+            compute(0);
+            compute(1);
+            stage(2, ra);
+            __syncthreads();
+            compute(2);
+        } else if (rem > 0) {
+            compute(0);
+            if (rem > 1) compute(1);
+        }
     }
 #pragma unroll
     for (int r = 0; r < RTW; ++r) {
@@ -768,15 +789,25 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
             else hipExtLaunchKernelGGL((k_attend_decode_mfma<128, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
         }
     } else {
+        // dynamic LDS of the multi-token kernel: 4 K tiles [32][D + 8] and 4 V tiles [D][40] of bf16
+        const size_t lds = (size_t)(4 * kChunk * (dv.D + 8) + 4 * dv.D * (kChunk + 8)) * 2;
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<64, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<64, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<128, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<128, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+            attr_set = true;
+        }
         const int n_groups = n_units * n_splits, rb = (NT + 4 * kPrefillTiles - 1) / (4 * kPrefillTiles);
         const int gb = (n_groups + 7) / 8 * 8 * rb;
         const dim3 grid(gb + (dv.aug_reps ? n_units * NT : 0));
         if (dv.aug_reps) {
-            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_prefill_mfma<64, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
-            else hipExtLaunchKernelGGL((k_attend_prefill_mfma<128, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_prefill_mfma<64, true>), grid, block, lds, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            else hipExtLaunchKernelGGL((k_attend_prefill_mfma<128, true>), grid, block, lds, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
         } else {
-            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_prefill_mfma<64, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
-            else hipExtLaunchKernelGGL((k_attend_prefill_mfma<128, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_prefill_mfma<64, false>), grid, block, lds, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            else hipExtLaunchKernelGGL((k_attend_prefill_mfma<128, false>), grid, block, lds, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
         }
     }
     return hipGetLastError();

@@ -205,6 +205,72 @@ def run_workload(wl, units=None, device="cuda:0", n_questions=1, decode_steps=0,
     return rep
 
 
+def run_full_size(wl, check_units, layer_modes=("per_layer",), device="cuda:0", ingest_batch=16,
+                  decode_steps=1, question=True, **cfg_overrides):
+    """A workload at its full size, generated on the device frame by frame (the
+    host never holds the stream) and ingested `ingest_batch` frames per call as
+    the benchmark does.  The oracle replays only the (layer, head) units in
+    `check_units`: its assignments must equal the library's after the whole
+    stream (online decisions made after the last K-means run are replayed
+    teacher-forced, as in ingest_with_parity), then every query is compared --
+    scores, ids, token lists, attention -- in each of `layer_modes`."""
+    st = inputs.SceneStream(wl, device=device)
+    F, L = wl.n_frames, wl.n_layers
+    shape = (F, L, wl.n_kv_heads, wl.tokens_per_frame, wl.head_dim)
+    K = torch.empty(shape, dtype=wl.torch_dtype, device=device)
+    V = torch.empty(shape, dtype=wl.torch_dtype, device=device)
+    for f in range(F):
+        K[f], V[f] = st.frame(f)
+    m = binding.Mosaic(binding.config_for(wl, **cfg_overrides), device=device)
+    for f in range(0, F, ingest_batch):
+        m.ingest_frame(K[f:f + ingest_batch], V[f:f + ingest_batch])
+    torch.cuda.synchronize()
+    rep = Report()
+    A = m.assignments()
+    _, N = m.centroids()
+    bounds = segment_bounds(wl, F)
+    last_lloyd = max([b for b in bounds if b == wl.warmup or
+                      (wl.recluster_every > 0 and b % wl.recluster_every == 0 and b > wl.warmup)], default=0)
+    oracles = {}
+    for (l, h) in check_units:
+        o = orc.OracleUnit(wl.n_clusters, wl.head_dim, wl.tokens_per_frame, F,
+                           wl.warmup_frames, wl.lloyd_iters, wl.recluster_every)
+        Ku = inputs.unit_pages(K, l, h)
+        u = l * wl.n_kv_heads + h
+        for f in range(F):
+            force = -1
+            if o.ready and f >= last_lloyd:          # still visible in A: no K-means run came after it
+                dec = o.peek(Ku[f])
+                got = int(A[u, f])
+                rep.online_decisions += 1
+                if got != dec.winner:
+                    assert dec.gap < NEAR_TIE and got == dec.runner_up, (
+                        f"unit {(l, h)} frame {f}: library chose {got}, oracle {dec.winner} "
+                        f"(runner-up {dec.runner_up}, gap {dec.gap:.3e})")
+                    rep.forced_near_ties += 1
+                    force = got
+            o.ingest(Ku[f], force)
+        a_or = o.assignments()
+        if not np.array_equal(A[u], a_or):
+            bad = np.nonzero(A[u] != a_or)[0]
+            raise AssertionError(f"unit {(l, h)}: {len(bad)} of {F} assignments differ (first frame {bad[0]}); "
+                                 f"smallest Lloyd gap {o.lloyd_min_gap:.3e}")
+        np.testing.assert_array_equal(N[u], o.sizes())
+        oracles[(l, h)] = o
+    tag = 0
+    for mode in layer_modes:
+        if question:
+            q = st.question(st.draw_scene(), wl.question_tokens, tag)
+            tag += 1
+            query_with_parity(m, wl, q, oracles, K, V, rep, "per_layer" if mode == "fused" else mode)
+        for _ in range(decode_steps):
+            q = st.question(st.draw_scene(), 1, tag)
+            tag += 1
+            query_with_parity(m, wl, q, oracles, K, V, rep, mode)
+    m.close()
+    return rep
+
+
 # ---------------------------------------------------------------------------
 # Self-adaptive maintainer (paper Sec. VI)
 # ---------------------------------------------------------------------------

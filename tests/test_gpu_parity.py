@@ -202,6 +202,40 @@ def test_cfg1_full_size():
     assert rep.max_out_err <= 2e-2
 
 
+def test_cfg2_full_size_sampled_units():
+    """The full stack at full size (28 layers, 4096 frames of 64 tokens, 15 GB of KV, a
+    full re-clustering every 256 frames): two sampled units against the oracle in the three
+    launch configurations the benchmark times (all layers in one call, one decode-step call
+    per layer, retrieve + attend per layer)."""
+    rep = harness.run_full_size(inputs.CONFIGS[2], [(3, 1), (27, 2)],
+                                layer_modes=("all", "fused", "per_layer"))
+    _report(rep)
+    assert rep.max_out_err <= 2e-2
+
+
+@pytest.mark.parametrize("stream_id", [0, 5])
+def test_cfg4_full_size_question_prefill(stream_id):
+    """One stream of the 8-stream prefill workload at full size (2048 frames, 256 clusters,
+    top-32): a 256-token question through the multi-token MFMA kernel, one sampled unit.
+    Stream 5 changes scene every few frames (many small clusters, ragged selection)."""
+    wl = inputs.cfg4_stream(stream_id)
+    rep = harness.run_full_size(wl, [(0, 1 + stream_id % 3)], ingest_batch=64, decode_steps=0)
+    _report(rep)
+    assert rep.online_decisions == wl.n_frames - wl.warmup
+
+
+def test_cfg3_full_shape_one_layer_host_tier():
+    """The host-offload workload with its per-layer shape kept (16384 frames of 196 tokens,
+    512 clusters, top-32, slabs of 16 frames, 10 % of the clusters cacheable) and one of its
+    28 layers: 6.6 GB of KV in pinned host memory; decode steps on a sampled unit."""
+    wl = inputs.CONFIGS[3].scaled(n_layers=1)
+    rep = harness.run_full_size(wl, [(0, 2)], ingest_batch=64, decode_steps=2, question=False,
+                                tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
+                                cache_pages_per_unit=wl.n_frames + 52 * 16)
+    _report(rep)
+    assert rep.online_decisions == wl.n_frames - wl.warmup
+
+
 # --------------------------------------------------------------------------
 # host tier: pinned-host cluster slabs + GPU cluster cache
 # --------------------------------------------------------------------------

@@ -733,3 +733,42 @@ def test_decode_step_falls_back_where_the_fused_kernel_does_not_apply():
     m.decode_step(0, q5[:1].contiguous())                     # one token: the fused kernel
     assert m.stats().last_decode_fused == 1
     m.close()
+
+
+# --------------------------------------------------------------------------
+# the extensions at the sizes the benchmark runs them at (one layer of the stack)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("mode,query_every", [(1, 0), (2, 64)])
+def test_maintainer_benchmark_recipe(mode, query_every):
+    """Maintainer on the config-2 stream recipe (4096 frames of 64 tokens, geometric scenes, 5 %
+    outlier tokens), 32 initial clusters in a table of 256, the benchmark's thresholds; eager, and
+    deferred with a decode query every 64 frames.  One layer, two units followed by the oracle."""
+    wl = inputs.CONFIGS[2].scaled(name="cfg2_recipe_maintained", n_layers=1, n_clusters=256, top_k=16,
+                                  recluster_every=0)
+    mt = dict(mode=mode, c_init=32, tau_min=4.0, tau_max=16.0, n0=32.0, split_iters=4, buf_max=256)
+    rep = harness.run_maintained(wl, mt, units=[(0, 1), (0, 3)], batch_pattern=(16, 1, 16, 5),
+                                 query_every=query_every, question_tokens=1)
+    _report(rep)
+    tot = rep.notes[-1]
+    print("  ", tot, flush=True)
+    assert tot["split_now"] + tot["split_deferred"] > 0
+    assert rep.max_out_err <= 2e-2
+
+
+def test_nested_benchmark_recipe():
+    """Nested index on the config-2 stream recipe: 512 clusters in 16 visual partitions, the 4 best
+    partitions kept, 1024-wide visual embeddings; one layer, one unit followed by the oracle."""
+    wl = inputs.CONFIGS[2].scaled(name="cfg2_recipe_nested", n_layers=1, n_clusters=512, top_k=16,
+                                  recluster_every=0, visual_dim=1024, n_visual=16, visual_key_corr=0.5)
+    rep = harness.run_nested(wl, 16, 4, units=[(0, 2)], batch_pattern=(16, 1, 16, 7), n_questions=1,
+                             decode_steps=3)
+    _report(rep)
+    assert rep.max_out_err <= 2e-2 and rep.online_decisions > 0
+
+
+def test_augmentation_cfg1_full_size():
+    """Config 1 at full size with the benchmark's augmentation (window of 16 frames and the
+    representatives as pseudo-KV)."""
+    rep = harness.run_augmented(inputs.CONFIGS[1], 16, True, decode_steps=3)
+    _report(rep)
+    assert rep.max_out_err <= 2e-2

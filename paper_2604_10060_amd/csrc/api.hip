@@ -379,7 +379,7 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     ctx->host = nullptr;
     if (cfg->tier == MOSAIC_TIER_HOST) {
         auto bail = [&](int code, const std::string &msg) {
-            delete ctx->host; delete ctx;
+            (void)mosaic_destroy(ctx);             // also ends the streams and events made so far
             return fail(nullptr, code, msg);
         };
         if (!cfg->host_arena) return bail(MOSAIC_EINVAL, "host_arena is NULL");
@@ -425,11 +425,9 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
                 (e = hipEventCreateWithFlags(&ht->attend_done[l], hipEventDisableTiming)) != hipSuccess)
                 return bail(MOSAIC_EHIP, std::string("host tier event creation: ") + hipGetErrorString(e));
     }
-    if (hipError_t e = clear_maintainer(ctx); e != hipSuccess) {
-        const std::string msg = std::string("hipMemsetAsync: ") + hipGetErrorString(e);
-        delete ctx;
+    if (clear_maintainer(ctx) != hipSuccess) {     // (no context to keep a message in: the code says it)
+        (void)mosaic_destroy(ctx);
         *out = nullptr;
-        (void)msg;
         return MOSAIC_EHIP;
     }
     *out = ctx;

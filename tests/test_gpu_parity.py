@@ -52,6 +52,7 @@ def test_all_layers_in_one_call():
 @pytest.mark.parametrize("kw", [
     dict(tokens_per_frame=5, n_clusters=7, top_k=7),            # ragged page, k = C (dense attention)
     dict(tokens_per_frame=13, top_k=1),                         # k = 1
+    dict(tokens_per_frame=1, n_frames=300, n_clusters=20, top_k=6),   # one token per frame: a page is 1/32 of a chunk
     dict(tokens_per_frame=196, n_frames=64, n_clusters=6, top_k=2, n_scenes=4),   # 7 chunks per page, last ragged
     dict(tokens_per_frame=40, question_tokens=3),               # 21 query rows: two row tiles
     dict(n_q_heads=4, n_kv_heads=4, question_tokens=5),         # G = 1
@@ -182,6 +183,8 @@ def test_error_paths():
     assert L.mosaic_retrieve(m._h, 0, q.data_ptr(), 10 ** 6) == binding.EINVAL
     assert L.mosaic_ingest_frame(m._h, None, None, 1) == binding.EINVAL
     assert b"NULL" in L.mosaic_last_error(m._h)
+    assert L.mosaic_ingest_frame(m._h, K.data_ptr(), V.data_ptr(), 0) == binding.EINVAL       # empty batch
+    assert m.stats().frames_ingested == 31
     m.close()
     # arena too small
     cfg = binding.config_for(wl)
@@ -626,9 +629,10 @@ def test_nested_config_and_call_errors():
 # Large cluster tables: the binned exact top-k (more than 128 representatives)
 # ---------------------------------------------------------------------------
 @pytest.mark.gpu
-@pytest.mark.parametrize("C,k", [(160, 24), (384, 1), (384, 383)])
+@pytest.mark.parametrize("C,k", [(160, 24), (384, 1), (384, 383), (1024, 48), (1024, 1024)])
 def test_large_cluster_table_topk(C, k):
-    """k = 1, a mid-sized k and k close to the number of clusters (all bins become candidates)."""
+    """k = 1, a mid-sized k and k close to the number of clusters (all bins become candidates);
+    1024 is the largest table the library accepts."""
     wl = _small(name=f"large_table_{C}_{k}", n_frames=2 * C + 40, n_scenes=40, n_clusters=C, top_k=k,
                 tokens_per_frame=8, question_tokens=3)
     rep = harness.run_workload(wl, units=[(0, 0), (0, 3)], n_questions=2, decode_steps=3)

@@ -594,9 +594,12 @@ static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, 
         return rc;
     }
     hipError_t e;
+    // A single frame of the online phase takes one launch where the assignment kernel that keeps
+    // the table in registers applies: its workgroups store the pages and form the summary themselves.
+    const bool one_launch = n_frames == 1 && ctx->n_frames >= ctx->W && !dv.maint_mode && dv.C <= 128;
     // pages + summaries of the whole batch (independent across frames); the grid's
     // y dimension is limited to 65535 frames per launch
-    for (int done = 0; done < n_frames;) {
+    for (int done = 0; done < n_frames && !one_launch;) {
         const int nb = std::min(n_frames - done, 32768);
         const size_t in_off = (size_t)done * dv.U * dv.T * dv.D * dv.esize;
         e = launch_store_summary(dv, (const char *)k_dev + in_off, (const char *)v_dev + in_off,
@@ -637,7 +640,8 @@ static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, 
             e = launch_visual_assign(dv, e_dev + (size_t)(f - ctx->n_frames) * dv.Dv, (int)f, (int)seg_end, ctx->stream);
             if (e != hipSuccess) return fail_hip(ctx, e, "visual assignment launch");
         }
-        e = launch_assign_update(dv, (int)f, (int)seg_end, ctx->stream);
+        e = one_launch ? launch_ingest_one(dv, k_dev, v_dev, (int)f, ctx->stream)
+                       : launch_assign_update(dv, (int)f, (int)seg_end, ctx->stream);
         if (e != hipSuccess) return fail_hip(ctx, e, "assign_update launch");
         f = seg_end;
         if (every > 0 && f % every == 0) {

@@ -58,49 +58,57 @@ __device__ __forceinline__ bool better(double v, int i, double bv, int bi) {
 }
 
 // ---------------------------------------------------------------------------
-// Page store + key summary.  grid (U, n_frames, 2): z = 0 keys, z = 1 values.
+// Page store + summaries.  store_key_page / store_value_page are run by one
+// 256-thread workgroup per (unit, frame): the page goes to the arena's store (HBM
+// tier) or the staging ring (host tier); the key summary (mean of the frame's T key
+// vectors, fp64) goes to dv.summ and, if s_out is given, to that LDS array too.
+// red: kBlock / (D / 8) rows of D doubles of LDS scratch.
 // ---------------------------------------------------------------------------
 template <typename E, int D>
-__global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E *k_in,
-                                                          const E *v_in, int f0) {
+__device__ __forceinline__ void store_key_page(const DeviceView &dv, const E *k_in, char *kdst_base, int u, int fl,
+                                               int f, double (&red)[kBlock / (D / 8)][D], double *s_out) {
     constexpr int LPR = D / 8;          // lanes per row, 8 elements each
     constexpr int RP = kBlock / LPR;    // rows per pass
-    const int u = blockIdx.x, fl = blockIdx.y, f = f0 + fl;
     const int tid = threadIdx.x, cg = tid % LPR, r0 = tid / LPR;
     const int T = dv.T;
     const size_t in_page = ((size_t)fl * dv.U + u) * (size_t)T * D;
     const size_t page = (size_t)u * dv.F + f;          // summary slot
-    // where the pages go: the arena's store (HBM tier) or the staging ring (host tier)
     const bool host = dv.tier == MOSAIC_TIER_HOST;
     const size_t spage = host ? (size_t)(f % dv.SN) * dv.U + u : (size_t)u * dv.PU + f;   // HBM tier: SFd = 1
-    char *kdst_base = host ? dv.stage_k : dv.k_store;
-    char *vdst_base = host ? dv.stage_v : dv.v_store;
-
-    __shared__ double red[RP][D];
-    if (blockIdx.z == 0) {
-        const E *src = k_in + in_page;
-        E *dst = reinterpret_cast<E *>(kdst_base) + spage * (size_t)T * D;
-        double acc[8];
+    const E *src = k_in + in_page;
+    E *dst = reinterpret_cast<E *>(kdst_base) + spage * (size_t)T * D;
+    double acc[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = 0.0;
-        for (int t = r0; t < T; t += RP) {
-            float v[8];
-            Elem<E>::load8(src + (size_t)t * D + cg * 8, v);
-            Elem<E>::copy8(src + (size_t)t * D + cg * 8, dst + (size_t)t * D + cg * 8);
+    for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+    for (int t = r0; t < T; t += RP) {
+        float v[8];
+        Elem<E>::load8(src + (size_t)t * D + cg * 8, v);
+        Elem<E>::copy8(src + (size_t)t * D + cg * 8, dst + (size_t)t * D + cg * 8);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += (double)v[i];
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) red[r0][cg * 8 + i] = acc[i];
-        __syncthreads();
-        if (tid < D) {
-            double s = 0.0;
-            for (int rr = 0; rr < RP; ++rr) s += red[rr][tid];
-            dv.summ[page * D + tid] = s / (double)T;
-        }
-        return;
+        for (int i = 0; i < 8; ++i) acc[i] += (double)v[i];
     }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) red[r0][cg * 8 + i] = acc[i];
+    __syncthreads();
+    if (tid < D) {
+        double sm = 0.0;
+        for (int rr = 0; rr < RP; ++rr) sm += red[rr][tid];
+        sm /= (double)T;
+        dv.summ[page * D + tid] = sm;
+        if (s_out) s_out[tid] = sm;
+    }
+}
 
+template <typename E, int D>
+__device__ __forceinline__ void store_value_page(const DeviceView &dv, const E *v_in, char *vdst_base, int u, int fl,
+                                                 int f, double (&red)[kBlock / (D / 8)][D]) {
+    constexpr int LPR = D / 8, RP = kBlock / LPR;
+    const int tid = threadIdx.x, cg = tid % LPR, r0 = tid / LPR;
+    const int T = dv.T;
+    const size_t in_page = ((size_t)fl * dv.U + u) * (size_t)T * D;
+    const size_t page = (size_t)u * dv.F + f;
+    const bool host = dv.tier == MOSAIC_TIER_HOST;
+    const size_t spage = host ? (size_t)(f % dv.SN) * dv.U + u : (size_t)u * dv.PU + f;
     // With the global-representative augmentation on, the frame's value summary (mean of
     // its T value vectors, fp64) is formed next to the copy, like the key summary.
     const E *src = v_in + in_page;
@@ -169,6 +177,17 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
         }
         if (dv.vsumm && tid < D) dv.vsumm[page * D + tid] = vacc / (double)T;
     }
+}
+
+// grid (U, n_frames, 2): z = 0 keys, z = 1 values.
+template <typename E, int D>
+__global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E *k_in,
+                                                          const E *v_in, int f0) {
+    __shared__ double red[kBlock / (D / 8)][D];
+    const int u = blockIdx.x, fl = blockIdx.y;
+    const bool host = dv.tier == MOSAIC_TIER_HOST;
+    if (blockIdx.z == 0) store_key_page<E, D>(dv, k_in, host ? dv.stage_k : dv.k_store, u, fl, f0 + fl, red, nullptr);
+    else store_value_page<E, D>(dv, v_in, host ? dv.stage_v : dv.v_store, u, fl, f0 + fl, red);
 }
 
 // ---------------------------------------------------------------------------
@@ -370,10 +389,13 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
 // so nothing in the per-frame chain waits on memory.  Same arithmetic per
 // element as the version above; only the norm's additions are grouped by lane.
 // ---------------------------------------------------------------------------
-template <int D, int THREADS>
-__global__ __launch_bounds__(THREADS) void k_assign_update_reg(DeviceView dv, int f0, int f1) {
+// k_in != nullptr (one frame, THREADS = 256): the workgroup first stores frame f0's key
+// page and forms its summary itself (the table loads are already in flight by then), so a
+// single-frame call needs one launch instead of two.
+template <int D, int THREADS, typename E>
+__device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int u, int f0, int f1, const E *k_in) {
     constexpr int EPL = D / 16, NG = THREADS / 16, RPG = 8, NW = THREADS / 64, ROWS = NG * RPG;
-    const int u = blockIdx.x, tid = threadIdx.x, C = dv.C;
+    const int tid = threadIdx.x, C = dv.C;
     const int lr = tid % 16, grp = tid / 16, wave = tid / 64, lane = tid % 64;
     __shared__ double s_sh[2][D];
     __shared__ double dot_sh[ROWS], rn_sh[ROWS];
@@ -399,7 +421,14 @@ __global__ __launch_bounds__(THREADS) void k_assign_update_reg(DeviceView dv, in
         n_sh[j] = j < C ? dv.n[(size_t)u * C + j] : 0;
         rn_sh[j] = j < C ? dv.rnorm[(size_t)u * C + j] : 0.0;
     }
-    if (tid < D) s_sh[0][tid] = dv.summ[((size_t)u * dv.F + f0) * D + tid];
+    if (k_in != nullptr) {
+        if constexpr (THREADS == kBlock) {
+            __shared__ double red[kBlock / (D / 8)][D];
+            store_key_page<E, D>(dv, k_in, dv.k_store, u, 0, f0, red, s_sh[0]);      // HBM tier only
+        }
+    } else if (tid < D) {
+        s_sh[0][tid] = dv.summ[((size_t)u * dv.F + f0) * D + tid];
+    }
     const bool nested = dv.P > 0;
     __syncthreads();
     for (int f = f0; f < f1; ++f) {
@@ -506,6 +535,23 @@ __global__ __launch_bounds__(THREADS) void k_assign_update_reg(DeviceView dv, in
         if (tid < D) s_sh[cur ^ 1][tid] = s_next;
         __syncthreads();
     }
+}
+
+template <int D, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_assign_update_reg(DeviceView dv, int f0, int f1) {
+    assign_update_reg_run<D, THREADS, float>(dv, blockIdx.x, f0, f1, nullptr);
+}
+
+// One frame in one launch (maintainer off, C <= 128, HBM tier, online phase).
+// grid (U, 2), 256 threads: y = 0 key page + summary + assignment + Eq. 3, y = 1 value page.
+template <typename E, int D>
+__global__ __launch_bounds__(kBlock) void k_ingest_one(DeviceView dv, const E *k_in, const E *v_in, int f) {
+    if (blockIdx.y == 1) {
+        __shared__ double red[kBlock / (D / 8)][D];
+        store_value_page<E, D>(dv, v_in, dv.v_store, blockIdx.x, 0, f, red);         // HBM tier only
+        return;
+    }
+    assign_update_reg_run<D, kBlock, E>(dv, blockIdx.x, f, f + 1, k_in);
 }
 
 // ---------------------------------------------------------------------------
@@ -914,6 +960,19 @@ hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const vo
         } else {
             if (dv.D == 64) k_store_summary<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f0);
             else k_store_summary<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f0);
+        }
+    });
+}
+
+hipError_t launch_ingest_one(const DeviceView &dv, const void *k_in, const void *v_in, int f, hipStream_t s) {
+    dim3 grid(dv.U, 2);
+    return checked([&] {
+        if (dv.esize == 4) {
+            if (dv.D == 64) k_ingest_one<float, 64><<<grid, kBlock, 0, s>>>(dv, (const float *)k_in, (const float *)v_in, f);
+            else k_ingest_one<float, 128><<<grid, kBlock, 0, s>>>(dv, (const float *)k_in, (const float *)v_in, f);
+        } else {
+            if (dv.D == 64) k_ingest_one<unsigned short, 64><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f);
+            else k_ingest_one<unsigned short, 128><<<grid, kBlock, 0, s>>>(dv, (const unsigned short *)k_in, (const unsigned short *)v_in, f);
         }
     });
 }

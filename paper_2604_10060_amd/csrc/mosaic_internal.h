@@ -137,6 +137,9 @@ struct Ctx {
 // ---- launchers (each checks its own launch; returns hipError_t) ----
 hipError_t launch_store_summary(const DeviceView &dv, const void *k_in, const void *v_in,
                                 int f0, int n_frames, hipStream_t s);
+// pages, summary, assignment and Eq. 3 of one frame in one launch (HBM tier, maintainer off,
+// C <= 128, frame f beyond the warm-up)
+hipError_t launch_ingest_one(const DeviceView &dv, const void *k_in, const void *v_in, int f, hipStream_t s);
 hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s);
 hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed_from_warmup,
                         hipStream_t s);

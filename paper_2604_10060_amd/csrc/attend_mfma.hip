@@ -335,11 +335,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
 // ---------------------------------------------------------------------------
 constexpr int kFusedMaxC = 256, kFusedList = 2048;
 
-__device__ __forceinline__ double group16_sum_f64(double x) {
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) x += __shfl_xor(x, o, 16);
-    return x;
-}
+__device__ __forceinline__ double group16_sum_f64(double x) { return row16_sum(x); }   // as in k_retrieve
 
 template <int D>
 __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, const unsigned short *q, int Tq,
@@ -403,15 +399,17 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
     // ---- scores: score_j = (qbar . r_j) / |r_j|   (plain dot product in score_mode 1) ----
     // the 16-lane groups leave the raw dot products in LDS; thread j then finishes entry j
     // (one fp64 division per thread instead of one per row on a single lane)
+    // (no lane-dependent branch around a row: the rows' reduction chains interleave; a row
+    // beyond the table repeats the last one and is not stored)
 #pragma unroll
     for (int i = 0; i < RPF; ++i) {
         const int j = grp + NG * i;
-        if (j < C) {
+        if (NG * i < C) {                                     // workgroup-uniform
             double p = 0.0;
 #pragma unroll
             for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rpre[i][e];
             p = group16_sum_f64(p);
-            if (lr == 0) sc_sh[j] = p;
+            if (lr == 0 && j < C) sc_sh[j] = p;
         }
     }
     for (int j = grp + NG * RPF; j < C; j += NG) {

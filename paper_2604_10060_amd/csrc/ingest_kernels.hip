@@ -42,11 +42,8 @@ template <> struct Elem<unsigned short> {
     }
 };
 
-__device__ __forceinline__ double group16_sum(double x) {
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) x += __shfl_xor(x, o, 16);
-    return x;
-}
+// (every call site has all 16 lanes of the group active)
+__device__ __forceinline__ double group16_sum(double x) { return row16_sum(x); }
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
@@ -55,6 +52,34 @@ __device__ __forceinline__ double wave_sum(double x) {
 // (value, id) ordered by value descending then id ascending
 __device__ __forceinline__ bool better(double v, int i, double bv, int bi) {
     return v > bv || (v == bv && i < bi);
+}
+// Best (value, id) of a wavefront, left in every lane: a butterfly inside each row of 16
+// lanes with data-parallel primitives (the order is total, so every lane of a row ends
+// with the same pair), then the four rows' pairs are read from their first lanes.
+template <int CTRL> __device__ __forceinline__ void best_step(double &bv, int &bi) {
+    const double ov = dpp_f64<CTRL>(bv);
+    const int oi = dpp_i32<CTRL>(bi);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+}
+__device__ __forceinline__ void wave_best(double &bv, int &bi) {
+    best_step<kDppXor8>(bv, bi);
+    best_step<kDppXor7>(bv, bi);
+    best_step<kDppXor3>(bv, bi);
+    best_step<kDppXor1>(bv, bi);
+    const long long b = __double_as_longlong(bv);
+    const int lo = (int)b, hi = (int)(b >> 32);
+    double rv[4];
+    int ri[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int l = __builtin_amdgcn_readlane(lo, 16 * r), h = __builtin_amdgcn_readlane(hi, 16 * r);
+        rv[r] = __longlong_as_double(((long long)h << 32) | (long long)(unsigned int)l);
+        ri[r] = __builtin_amdgcn_readlane(bi, 16 * r);
+    }
+    bv = rv[0]; bi = ri[0];
+#pragma unroll
+    for (int r = 1; r < 4; ++r)
+        if (better(rv[r], ri[r], bv, bi)) { bv = rv[r]; bi = ri[r]; }
 }
 
 // ---------------------------------------------------------------------------
@@ -402,8 +427,7 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
     __shared__ int n_sh[ROWS];
     __shared__ double red_v[NW];
     __shared__ int red_i[NW];
-    __shared__ double snorm_sh, psum_sh[2];
-    __shared__ int win_sh;
+    __shared__ double psum_sh[2];
     double *r = dv.r + (size_t)u * C * D;
     double rr[RPG][EPL];
 #pragma unroll
@@ -439,49 +463,41 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
         if (tid < D && f + 1 < f1) s_next = dv.summ[((size_t)u * dv.F + f + 1) * D + tid];
         const int part_f = nested ? dv.part[f] : 0;
         const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : C;
-        if (wave == 0) {
-            double x = 0.0;
-            for (int d = lane; d < D; d += 64) x += sv[d] * sv[d];
-            x = wave_sum(x);
-            if (lane == 0) snorm_sh = sqrt(x);
-        }
+        // Dot products of the summary with every row the group holds, unconditionally and
+        // without lane-dependent branches so that the rows' reduction chains interleave (rows
+        // beyond the table or of empty clusters give values nobody reads); the group also
+        // forms |s|^2 from its own share of the channels, the same bits in every group.
         double sl[EPL];
 #pragma unroll
         for (int e = 0; e < EPL; ++e) sl[e] = sv[lr * EPL + e];
+        double ssq = 0.0;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) ssq += sl[e] * sl[e];
+        const double sn = sqrt(row16_sum(ssq));
 #pragma unroll
         for (int i = 0; i < RPG; ++i) {
-            const int j = grp + NG * i;
-            if (j >= lo && j < hi && n_sh[j] > 0) {          // uniform within the 16-lane group
+            if (NG * i < C) {                                 // block-uniform
                 double p = 0.0;
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) p += sl[e] * rr[i][e];
-                p = group16_sum(p);
-                if (lr == 0) dot_sh[j] = p;
+                p = row16_sum(p);
+                if (lr == 0) dot_sh[grp + NG * i] = p;
             }
         }
         __syncthreads();
-        // argmax of the cosine over the candidates, ties to the lowest id
+        // argmax of the cosine over the candidates, ties to the lowest id (THREADS >= C: at
+        // most one candidate per thread)
         double bv = -INFINITY;
         int bi = 0x7fffffff;
-        const double sn = snorm_sh;
-        for (int j = lo + tid; j < hi; j += THREADS) {
-            if (n_sh[j] <= 0) continue;
-            const double c = (sn == 0.0 || rn_sh[j] == 0.0) ? 0.0 : dot_sh[j] / (sn * rn_sh[j]);
-            if (better(c, j, bv, bi)) { bv = c; bi = j; }
+        {
+            const int j = lo + tid;
+            if (j < hi && n_sh[j] > 0) {
+                bv = (sn == 0.0 || rn_sh[j] == 0.0) ? 0.0 : dot_sh[j] / (sn * rn_sh[j]);
+                bi = j;
+            }
         }
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) {
-            const double ov = __shfl_xor(bv, o, 64);
-            const int oi = __shfl_xor(bi, o, 64);
-            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-        }
+        wave_best(bv, bi);
         if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
-        __syncthreads();
-        if (tid == 0) {
-            for (int w = 1; w < NW; ++w)
-                if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
-            win_sh = bi == 0x7fffffff ? lo : bi;
-        }
         // nested hierarchy: the partition's representative follows the same running mean
         int pn_i = 0;
         if (nested) {
@@ -499,14 +515,20 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
             }
         }
         __syncthreads();
-        const int a = win_sh;
+        // every thread merges the wavefronts' winners itself (no second barrier for one thread's merge)
+        bv = red_v[0]; bi = red_i[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w)
+            if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
+        const int a = bi == 0x7fffffff ? lo : bi;
+        const int ai = __builtin_amdgcn_readfirstlane(a / NG);      // workgroup-uniform: a scalar
         if (grp == a % NG) {                                  // the group that holds row a
             const int na_i = n_sh[a];
             const double na = (double)na_i;
             double sq = 0.0;
 #pragma unroll
             for (int i = 0; i < RPG; ++i) {
-                if (i == a / NG) {
+                if (i == ai) {                                // scalar branch: one pass runs
 #pragma unroll
                     for (int e = 0; e < EPL; ++e) {
                         // Eq. 3 with each operation rounded separately (no contraction)
@@ -517,7 +539,7 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
                     }
                 }
             }
-            sq = group16_sum(sq);
+            sq = row16_sum(sq);
             if (lr == 0) {
                 const double nr = sqrt(sq);
                 rn_sh[a] = nr;

@@ -198,6 +198,31 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
 
 
 // ---------------------------------------------------------------------------
+// Reductions over the 16 lanes of a DPP row (lanes 16k .. 16k + 15) with data-parallel
+// primitives instead of LDS permutes: a butterfly over the lane-index masks 8, 7, 3, 1
+// (row_ror:8, row_half_mirror, quad_perm [3,2,1,0], quad_perm [1,0,3,2]), which span all
+// 16 lanes.  Every step adds a lane's partner symmetrically, so all 16 lanes end with the
+// same bits.  About 80 cycles for a double against about 500 with ds_bpermute.
+// ---------------------------------------------------------------------------
+template <int CTRL> __device__ __forceinline__ int dpp_i32(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double x) {
+    const long long b = __double_as_longlong(x);
+    const int lo = dpp_i32<CTRL>((int)b), hi = dpp_i32<CTRL>((int)(b >> 32));
+    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
+}
+constexpr int kDppXor8 = 0x128, kDppXor7 = 0x141, kDppXor3 = 0x1B, kDppXor1 = 0xB1;
+__device__ __forceinline__ double row16_sum(double x) {
+    x += dpp_f64<kDppXor8>(x);
+    x += dpp_f64<kDppXor7>(x);
+    x += dpp_f64<kDppXor3>(x);
+    x += dpp_f64<kDppXor1>(x);
+    return x;
+}
+
+
+// ---------------------------------------------------------------------------
 // Load-balanced KV splits.  An attend launch has B split workgroups (per row
 // block) for the n_units units of the call.  Units retrieve different numbers
 // of tokens, so the splits are shared out in proportion to the selected page

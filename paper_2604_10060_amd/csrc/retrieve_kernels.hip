@@ -10,11 +10,8 @@ namespace mosaic {
 
 namespace {
 
-__device__ __forceinline__ double group16_sum(double x) {
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) x += __shfl_xor(x, o, 16);
-    return x;
-}
+// (every call site has all 16 lanes of the group active; k_decode_fused uses the same sum)
+__device__ __forceinline__ double group16_sum(double x) { return row16_sum(x); }
 
 template <typename E> __device__ __forceinline__ double to_f64(E v);
 template <> __device__ __forceinline__ double to_f64<float>(float v) { return (double)v; }
@@ -212,8 +209,8 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         __syncthreads();
     }
     // score_j = (qbar . r_j) / |r_j|   (plain dot product in score_mode 1)
-    auto finish_row = [&](int j, double p) {
-        p = group16_sum(p);
+    auto finish_row = [&](int j, double p, bool reduced = false) {
+        if (!reduced) p = group16_sum(p);
         if (lr == 0) {
             double sc = -INFINITY;
             if (n_sh[j] > 0) {
@@ -235,15 +232,22 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
             finish_row(j, p);
         }
     } else {
+        // the prefetched rows: all reductions first, without lane-dependent branches, so that the
+        // rows' chains interleave (a row beyond the table repeats the last one and is not stored)
+        double pv[RPF];
+#pragma unroll
+        for (int i = 0; i < RPF; ++i) {
+            pv[i] = 0.0;
+            if (RPP * i < C) {                                // workgroup-uniform
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) pv[i] += qbar[lr * EPL + e] * rpre[i][e];
+                pv[i] = group16_sum(pv[i]);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < RPF; ++i) {
             const int j = row0 + RPP * i;
-            if (j < C) {
-                double p = 0.0;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) p += qbar[lr * EPL + e] * rpre[i][e];
-                finish_row(j, p);
-            }
+            if (j < C) finish_row(j, pv[i], true);
         }
         for (int j = row0 + RPP * RPF; j < C; j += RPP) {
             const double *rj = r + (size_t)j * D + lr * EPL;

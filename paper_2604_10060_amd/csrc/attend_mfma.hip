@@ -432,13 +432,12 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
     }
     __syncthreads();
     // ---- ranks by (score descending, id ascending) among the non-empty clusters ----
-    {
-        const int per = max(1, kBlock / C);
-        for (int item = tid; item < C * per; item += kBlock) {
-            const int j = item % C, part = item / C;
-            if (n_sh[j] <= 0) continue;
+    {   // 2^pl threads per entry (the largest power of two that fits the workgroup: shifts, no divisions)
+        const int pl = 31 - __clz(kBlock / C);
+        const int j = tid >> pl, part = tid & ((1 << pl) - 1);
+        if (j < C && n_sh[j] > 0) {
             const double sj = sc_sh[j];
-            const int i0 = (C * part) / per, i1 = (C * (part + 1)) / per;
+            const int i0 = (C * part) >> pl, i1 = (C * (part + 1)) >> pl;
             int c = 0;           // (an empty cluster carries -inf and never outranks a live one)
 #pragma unroll 8
             for (int i = i0; i < i1; ++i) {
@@ -462,11 +461,24 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
     }
     __syncthreads();
     const int n_ids = min(k, n_live_sh);
-    if (tid == 0) {
-        int o = 0;
-        off_sh[0] = 0;
-        for (int i = 0; i < n_ids; ++i) { o += n_sh[ids_sh[i]]; off_sh[i + 1] = o; }
-        if (split == 0) { dv.n_ids[u] = n_ids; dv.n_sel[u] = o; }
+    if (wave == 0) {     // page offsets of the selected clusters: running sums of their sizes, 64 at a time
+        int run = 0;
+        for (int i0 = 0; i0 < n_ids; i0 += 64) {
+            const int i = i0 + lane;
+            const int sz = i < n_ids ? n_sh[ids_sh[i]] : 0;
+            int incl = sz;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += t;
+            }
+            if (i < n_ids) off_sh[i + 1] = run + incl;
+            run += __shfl(incl, 63, 64);
+        }
+        if (lane == 0) {
+            off_sh[0] = 0;
+            if (split == 0) { dv.n_ids[u] = n_ids; dv.n_sel[u] = run; }
+        }
     }
     if (split == 0)
         for (int i = tid; i < k; i += kBlock) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
@@ -477,13 +489,12 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
     const int c0 = split * cps, c1 = min(NC, c0 + cps);
     const int p_lo = c0 / cpp, p_hi = c1 > c0 ? (c1 - 1) / cpp : p_lo - 1;
     int *sel = dv.sel_pages + (size_t)u * F;
-    auto place = [&](int f, int a, int ps) {
-        if (a < 0) return;
-        const int rk = rank_sh[a];
-        if (rk < 0) return;
-        const int p = off_sh[rk] + ps;
-        if (p >= p_lo && p <= p_hi) list_sh[p - p_lo] = f;
-        if (split == 0) sel[p] = f;
+    auto place = [&](int f, int a, int ps) {   // (no early exits: the LDS look-ups of a batch overlap)
+        const int rk = rank_sh[max(a, 0)];
+        const bool sel_f = a >= 0 && rk >= 0;
+        const int p = off_sh[max(rk, 0)] + ps;
+        if (sel_f && p >= p_lo && p <= p_hi) list_sh[p - p_lo] = f;
+        if (sel_f && split == 0) sel[p] = f;
     };
 #pragma unroll
     for (int i = 0; i < FPT; ++i) place(tid + kBlock * i, fa[i], fp[i]);

@@ -262,12 +262,25 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     // pruned clusters have n_sh = 0 and take no part
     const int n_live = topk_rank(sc_sh, n_sh, C, k, rank_sh, ids_sh, cnt_sh, off_sh, tk_sh);
     const int n_ids = min(k, n_live);
-    if (tid == 0) {
-        int o = 0;
-        off_sh[0] = 0;
-        for (int i = 0; i < n_ids; ++i) { o += n_sh[ids_sh[i]] - wcnt_sh[ids_sh[i]]; off_sh[i + 1] = o; }
-        dv.n_ids[u] = n_ids;
-        if (write_pages) dv.n_sel[u] = o + (n_frames - w0);
+    if (tid < 64) {      // page offsets of the selected clusters: running sums of their sizes, 64 at a time
+        int run = 0;
+        for (int i0 = 0; i0 < n_ids; i0 += 64) {
+            const int i = i0 + tid;
+            const int sz = i < n_ids ? n_sh[ids_sh[i]] - wcnt_sh[ids_sh[i]] : 0;
+            int incl = sz;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o, 64);
+                if (tid >= o) incl += t;
+            }
+            if (i < n_ids) off_sh[i + 1] = run + incl;
+            run += __shfl(incl, 63, 64);
+        }
+        if (tid == 0) {
+            off_sh[0] = 0;
+            dv.n_ids[u] = n_ids;
+            if (write_pages) dv.n_sel[u] = run + (n_frames - w0);
+        }
     }
     for (int i = tid; i < k; i += BLK) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
     __syncthreads();
@@ -275,10 +288,10 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     // page list: clusters in selection order, member frames ascending
     int *sel = dv.sel_pages + (size_t)u * dv.F;
 #pragma unroll
-    for (int i = 0; i < FPT; ++i) {
-        if (fa[i] < 0 || tid + BLK * i >= w0) continue;
-        const int rk = rank_sh[fa[i]];
-        if (rk >= 0) sel[off_sh[rk] + fp[i]] = tid + BLK * i;
+    for (int i = 0; i < FPT; ++i) {   // (no early exits: the LDS look-ups of the batch overlap)
+        const int rk = rank_sh[max(fa[i], 0)];
+        const int p = off_sh[max(rk, 0)] + fp[i];
+        if (fa[i] >= 0 && tid + BLK * i < w0 && rk >= 0) sel[p] = tid + BLK * i;
     }
     for (int f = tid + BLK * FPT; f < w0; f += BLK) {
         const int c = assign[f];

@@ -42,11 +42,13 @@ __device__ __forceinline__ int topk_rank(const double *sc_sh, const int *n_sh, i
     const bool live = tid < R && n_sh[tid] > 0;
     const double s = live ? sc_sh[tid] : 0.0;
     if (R <= 128) {
-        // small tables: the direct count, 1024 / R threads per entry
-        const int per = BLK / R, j = tid % R, part = tid / R;
-        if (part < per && n_sh[j] > 0) {
+        // small tables: the direct count, 2^pl threads per entry (the largest power of two that
+        // fits the workgroup: shifts instead of integer divisions)
+        const int pl = 31 - __clz(BLK / R);
+        const int j = tid >> pl, part = tid & ((1 << pl) - 1);
+        if (j < R && n_sh[j] > 0) {
             const double sj = sc_sh[j];
-            const int i0 = (R * part) / per, i1 = (R * (part + 1)) / per;
+            const int i0 = (R * part) >> pl, i1 = (R * (part + 1)) >> pl;
             int c = 0;           // (an entry that is not live carries -inf and never outranks a live one)
 #pragma unroll 8
             for (int i = i0; i < i1; ++i) {

@@ -866,46 +866,71 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
 
 // ---------------------------------------------------------------------------
 // Lloyd update round.  grid (U, C), 128 threads (thread d owns channel d).
-// Members are found by an order-preserving compaction of the assignment array
-// (2048 frames at a time) and summed in ascending frame order, so the mean is
-// the same sequence of additions a sequential loop would perform.
+// Members are found by an order-preserving compaction of the assignment array,
+// 2048 frames at a time: the assignments are staged in LDS with coalesced loads,
+// every thread then looks at 16 consecutive frames, a scan over the threads' match
+// counts gives each match its slot, and the member summaries are added in ascending
+// frame order, so the mean is the same sequence of additions a sequential loop would
+// perform.  The launch reads every fp64 summary of every unit once (1 KB per frame and
+// unit: 470 MB at 112 units x 4096 frames), which is what bounds it.
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frames) {
-    constexpr int CH = 2048, NT = 128;
+    constexpr int NT = 128, FPT = 16, CH = NT * FPT;
     const int u = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, C = dv.C;
     const int wave = tid / 64, lane = tid % 64;
+    __shared__ int a_sh[CH];
     __shared__ int mem[CH];
-    __shared__ int wcnt[2];
+    __shared__ int wtot[2];
     __shared__ double nsum_sh[2];
     const int *assign = dv.assign + (size_t)u * dv.F;
     int *pos = dv.pos + (size_t)u * dv.F;
     double acc = 0.0;
     int count = 0;
     for (int c0 = 0; c0 < n_frames; c0 += CH) {
-        int filled = 0;  // members found in this chunk so far (same in every thread)
         const int cend = min(n_frames, c0 + CH);
-        for (int b = c0; b < cend; b += NT) {
-            const int f = b + tid;
-            const bool is = f < cend && assign[f] == j;
-            const unsigned long long bal = __ballot(is);
-            const int before = __popcll(bal & ((1ull << lane) - 1ull));
-            if (lane == 0) wcnt[wave] = __popcll(bal);
-            __syncthreads();
-            const int w0 = wcnt[0], w1 = wcnt[1];
-            if (is) {
-                const int slot = filled + (wave == 1 ? w0 : 0) + before;
-                mem[slot] = f;
-                pos[f] = count + slot;
-            }
-            filled += w0 + w1;
-            __syncthreads();
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) {
+            const int f = c0 + tid + NT * i;
+            a_sh[tid + NT * i] = f < cend ? assign[f] : -1;
         }
-        if (tid < D)
-            for (int m = 0; m < filled; ++m)
-                acc += dv.summ[((size_t)u * dv.F + mem[m]) * D + tid];
-        count += filled;
         __syncthreads();
+        unsigned int mask = 0;               // bit i: frame c0 + 16 tid + i belongs to cluster j
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) mask |= (a_sh[tid * FPT + i] == j ? 1u : 0u) << i;
+        const int mine = __popc(mask);
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) wtot[wave] = incl;
+        __syncthreads();
+        int slot = incl - mine + (wave == 1 ? wtot[0] : 0);
+        const int filled = wtot[0] + wtot[1];   // members found in this chunk (same in every thread)
+        while (mask) {
+            const int i = __ffs((int)mask) - 1;
+            mask &= mask - 1;
+            const int f = c0 + tid * FPT + i;
+            mem[slot] = f;
+            pos[f] = count + slot;
+            ++slot;
+        }
+        __syncthreads();
+        if (tid < D) {
+            // sixteen members' loads in flight at a time (index clamped, loads unconditional), added in order
+            const double *sb = dv.summ + (size_t)u * dv.F * D + tid;
+            for (int m0 = 0; m0 < filled; m0 += 16) {
+                double v[16];
+#pragma unroll
+                for (int x = 0; x < 16; ++x) v[x] = sb[(size_t)mem[min(m0 + x, filled - 1)] * D];
+#pragma unroll
+                for (int x = 0; x < 16; ++x)
+                    if (m0 + x < filled) acc += v[x];
+            }
+        }
+        count += filled;
     }
     if (count == 0) {                      // keeps its representative, skipped from now on
         if (tid == 0) dv.n[(size_t)u * C + j] = 0;

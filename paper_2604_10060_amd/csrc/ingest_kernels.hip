@@ -7,6 +7,8 @@
 //                    periodic warm-started re-clustering
 // All decision arithmetic is fp64: on CDNA4 the fp64 vector rate equals the
 // non-packed fp32 rate, so exact-to-rounding decisions cost only table bytes.
+#include <type_traits>
+
 #include "mosaic_internal.h"
 #include "maintain_device.h"
 
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
     __shared__ double red_v[4];
     __shared__ int red_i[4];
     __shared__ double snorm_sh, nsum_sh[2], dsum_sh[2], psum_sh[2];
-    __shared__ int win_sh, act_sh;
+    __shared__ int act_sh;
     __shared__ SplitShared<MAINT ? D : 16> split_sh;   // (small placeholder when the maintainer is off)
     double *r = dv.r + (size_t)u * C * D;
     double *rn = dv.rnorm + (size_t)u * C;
@@ -282,42 +284,66 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
             x = wave_sum(x);
             if (lane == 0) snorm_sh = sqrt(x);
         }
-        for (int j = lo + row0; j < hi; j += 16) {
-            double p = 0.0;
-            if (n[j] > 0) {
-                const double *rj = r + (size_t)j * D + lr * EPL;
+        // sizes and norms of this thread's candidates (at most four: C <= 1024), fetched ahead of the rows
+        int nj[4];
+        double rnj[4];
 #pragma unroll
-                for (int i = 0; i < EPL; ++i) p += s_sh[lr * EPL + i] * rj[i];
-            }
-            p = group16_sum(p);
-            if (lr == 0) dot_sh[j] = p;
+        for (int x = 0; x < 4; ++x) {
+            const int j = min(lo + tid + kBlock * x, hi - 1);
+            nj[x] = n[j]; rnj[x] = rn[j];
+        }
+        // Dot products with the candidates' rows, eight rows of a 16-lane group in flight at a time
+        // (row index clamped, loads unconditional, no test of the size: a row nobody reads costs
+        // nothing extra, a dependent load per row costs a trip to L2)
+        for (int jb = lo; jb < hi; jb += 16 * 8) {
+            const int passes = min(8, (hi - jb + 15) / 16);   // workgroup-uniform
+            const int j0 = jb + row0;
+            auto rows = [&](auto full) {      // full: all eight passes (straight-line code); else only `passes`
+                double rv[8][EPL];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    if (decltype(full)::value || x < passes) {
+                        const double *rj = r + (size_t)min(j0 + 16 * x, hi - 1) * D + lr * EPL;
+#pragma unroll
+                        for (int i = 0; i < EPL; ++i) rv[x][i] = rj[i];
+                    }
+                }
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    if (decltype(full)::value || x < passes) {
+                        double p = 0.0;
+#pragma unroll
+                        for (int i = 0; i < EPL; ++i) p += s_sh[lr * EPL + i] * rv[x][i];
+                        p = group16_sum(p);
+                        if (lr == 0 && j0 + 16 * x < hi) dot_sh[j0 + 16 * x] = p;
+                    }
+                }
+            };
+            if (passes == 8) rows(std::true_type{});
+            else rows(std::false_type{});
         }
         __syncthreads();
         // argmax of the cosine over non-empty clusters, ties to the lowest id
         double bv = -INFINITY;
         int bi = 0x7fffffff;
         const double sn = snorm_sh;
-        for (int j = lo + tid; j < hi; j += kBlock) {
-            if (n[j] <= 0) continue;
-            const double den = sn * rn[j];
-            const double c = (sn == 0.0 || rn[j] == 0.0) ? 0.0 : dot_sh[j] / den;
-            if (better(c, j, bv, bi)) { bv = c; bi = j; }
-        }
 #pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) {
-            const double ov = __shfl_xor(bv, o, 64);
-            const int oi = __shfl_xor(bi, o, 64);
-            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        for (int x = 0; x < 4; ++x) {
+            const int j = lo + tid + kBlock * x;
+            if (j < hi && nj[x] > 0) {
+                const double c = (sn == 0.0 || rnj[x] == 0.0) ? 0.0 : dot_sh[j] / (sn * rnj[x]);
+                if (better(c, j, bv, bi)) { bv = c; bi = j; }
+            }
         }
+        wave_best(bv, bi);
         if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
         __syncthreads();
-        if (tid == 0) {
-            for (int w = 1; w < 4; ++w)
-                if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
-            win_sh = bi == 0x7fffffff ? lo : bi;
-        }
-        __syncthreads();
-        const int a = win_sh;
+        // every thread merges the four wavefronts' winners itself
+        bv = red_v[0]; bi = red_i[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w)
+            if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
+        const int a = bi == 0x7fffffff ? lo : bi;
         const int na_i = n[a];
         const double na = (double)na_i;
         double sq = 0.0, dq = 0.0;

@@ -129,6 +129,30 @@ def test_batched_ingest_equals_single_frame_calls_bitwise():
             np.testing.assert_array_equal(a, b)
 
 
+@pytest.mark.parametrize("kw,over", [
+    (dict(), dict(aug_global_reps=1, aug_window_frames=5)),          # value summaries formed by the one-launch path
+    (dict(kv_dtype="fp32", head_dim=64, n_q_heads=8, n_kv_heads=4), dict()),   # fp32 pages, D = 64
+    (dict(n_clusters=150, top_k=6, n_frames=400), dict()),           # table too large for the one-launch path
+])
+def test_single_frame_calls_equal_batched_ingest_variants(kw, over):
+    """A single-frame call of the online phase takes one launch (pages, summary, assignment, Eq. 3)
+    where the register-table kernel applies; its state and outputs equal the batched path's bit for bit."""
+    wl = _small(n_frames=kw.pop("n_frames", 140), **kw)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    q = st.question(0, 1, 0).to(DEV)
+    res = []
+    for pattern in ((1,), (16,)):
+        m = _ingest_all(wl, K, V, pattern, **over)
+        m.retrieve(0, q[0].contiguous())
+        out, lse = m.attend(0, q[0].contiguous())
+        r, n = m.centroids()
+        res.append((m.assignments(), r, n, m.summaries(), out.float().cpu().numpy(), lse.cpu().numpy()))
+        m.close()
+    for a, b in zip(res[0], res[1]):
+        np.testing.assert_array_equal(a, b)
+
+
 def test_reset_and_rerun_is_deterministic():
     wl = _small(n_frames=80, n_clusters=6, top_k=2)
     st = inputs.SceneStream(wl)

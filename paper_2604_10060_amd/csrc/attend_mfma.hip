@@ -33,6 +33,15 @@ __device__ __forceinline__ bf16x8 ld_frag(const unsigned short *p) {
     const uint4 w = *reinterpret_cast<const uint4 *>(p);
     return __builtin_bit_cast(bf16x8, w);
 }
+// The decode kernels read every K/V operand once per step.  When the stored KV is far larger than
+// the chip's caches the loads carry the non-temporal hint (nothing worth keeping is displaced and
+// the lines are not allocated for reuse): 562 -> 519 us for a 3.3 GB launch.  A small store (all of
+// it fits the 256 MB memory-side cache) is read faster without the hint.
+__device__ __forceinline__ bf16x8 ld_frag_stream(const unsigned short *p) {
+    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return __builtin_bit_cast(bf16x8, w);
+}
 __device__ __forceinline__ bf16x8 zero_frag() {
     return __builtin_bit_cast(bf16x8, make_uint4(0u, 0u, 0u, 0u));
 }
@@ -144,7 +153,7 @@ __device__ __forceinline__ void chunk_step(const bf16x8 (&kf)[2 * (D / 32)], con
 // Issue the 16-byte operand loads of one chunk.  Tokens beyond the page's T are
 // clamped to the last token (valid memory, weight 0 later); the value blocks are
 // zero-padded to 32 tokens at ingest.
-template <int D>
+template <int D, bool STREAM>
 __device__ __forceinline__ void issue_chunk(const unsigned short *kpage, const unsigned short *vchunk,
                                             int t0, int T, int g, int n, bf16x8 (&kf)[2 * (D / 32)],
                                             bf16x8 (&vf)[D / 16]) {
@@ -154,11 +163,11 @@ __device__ __forceinline__ void issue_chunk(const unsigned short *kpage, const u
         const int tok = min(t0 + 8 * (n / 4) + 4 * tau + (n % 4), T - 1);
         const unsigned short *kr = kpage + (size_t)tok * D + 8 * g;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) kf[tau * KK + kk] = ld_frag(kr + 32 * kk);
+        for (int kk = 0; kk < KK; ++kk) kf[tau * KK + kk] = STREAM ? ld_frag_stream(kr + 32 * kk) : ld_frag(kr + 32 * kk);
     }
     const unsigned short *vr = vchunk + n * 32 + 8 * g;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) vf[db] = ld_frag(vr + 16 * db * 32);
+    for (int db = 0; db < DB; ++db) vf[db] = STREAM ? ld_frag_stream(vr + 16 * db * 32) : ld_frag(vr + 16 * db * 32);
 }
 
 template <int D>
@@ -226,7 +235,7 @@ __device__ __forceinline__ void merge_waves_store(const DeviceView &dv, const f3
 // wave w of split s takes chunks s + S*(w + 4*i); the next chunk's operands are
 // in flight while the current one is reduced.
 // ---------------------------------------------------------------------------
-template <int D, bool AUG>
+template <int D, bool AUG, bool STREAM>
 __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv, int u0, int n_units,
                                                                   const unsigned short *q, int Tq, int B) {
     constexpr int KK = D / 32, DB = D / 16;
@@ -281,9 +290,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
         const int b = dv.SFd == 1 ? page : page / dv.SFd, r = dv.SFd == 1 ? 0 : page - b * dv.SFd;
         const char *kp = dv.k_store + (size_t)u * dv.k_ustride + (size_t)b * dv.k_bstride + (size_t)r * dv.kpage;
         const char *vp = dv.v_store + (size_t)u * dv.v_ustride + (size_t)b * dv.v_bstride + (size_t)r * dv.vpage;
-        issue_chunk<D>(reinterpret_cast<const unsigned short *>(kp),
-                       reinterpret_cast<const unsigned short *>(vp) + (size_t)cc * D * 32,
-                       cc * kChunk, T, g, n, kf, vf);
+        issue_chunk<D, STREAM>(reinterpret_cast<const unsigned short *>(kp),
+                               reinterpret_cast<const unsigned short *>(vp) + (size_t)cc * D * 32,
+                               cc * kChunk, T, g, n, kf, vf);
     };
     auto step = [&](const bf16x8 (&kf)[2 * KK], const bf16x8 (&vf)[DB], int cc) {
         chunk_step<D>(kf, vf, qf, min(kChunk, T - cc * kChunk), g, sl2, acc, m, l);
@@ -337,7 +346,7 @@ constexpr int kFusedMaxC = 256, kFusedList = 2048;
 
 __device__ __forceinline__ double group16_sum_f64(double x) { return row16_sum(x); }   // as in k_retrieve
 
-template <int D>
+template <int D, bool STREAM>
 __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, const unsigned short *q, int Tq,
                                                          int S, int n_frames, int score_mode) {
     constexpr int KK = D / 32, DB = D / 16, EPL = D / 16, NG = kBlock / 16, RPF = 8, FPT = 8;
@@ -374,9 +383,11 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
     double rpre[RPF][EPL];
 #pragma unroll
     for (int i = 0; i < RPF; ++i) {
-        const double *rj = r + (size_t)min(grp + NG * i, C - 1) * D + lr * EPL;
+        if (NG * i < C) {               // workgroup-uniform: passes beyond the table are not loaded
+            const double *rj = r + (size_t)min(grp + NG * i, C - 1) * D + lr * EPL;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
+            for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
+        }
     }
     if (tid < D) {      // mean query over the Tq tokens and the G query heads of this KV head
         // (R <= 16: two batches of eight loads, row index clamped, loads unconditional)
@@ -526,9 +537,9 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
         const int page = list_sh[pi - p_lo];
         const char *kp = dv.k_store + (size_t)u * dv.k_ustride + (size_t)page * dv.k_bstride;
         const char *vp = dv.v_store + (size_t)u * dv.v_ustride + (size_t)page * dv.v_bstride;
-        issue_chunk<D>(reinterpret_cast<const unsigned short *>(kp),
-                       reinterpret_cast<const unsigned short *>(vp) + (size_t)cc * D * 32,
-                       cc * kChunk, T, g, n, kf, vf);
+        issue_chunk<D, STREAM>(reinterpret_cast<const unsigned short *>(kp),
+                               reinterpret_cast<const unsigned short *>(vp) + (size_t)cc * D * 32,
+                               cc * kChunk, T, g, n, kf, vf);
     };
     auto step = [&](const bf16x8 (&kf)[2 * KK], const bf16x8 (&vf)[DB], int cc) {
         chunk_step<D>(kf, vf, qf, min(kChunk, T - cc * kChunk), g, sl2, acc, m, l);
@@ -774,28 +785,35 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
 } // namespace
 
 hipError_t launch_decode_fused(const DeviceView &dv, int u0, int n_units, const void *q, int Tq, int n_splits,
-                               int n_frames, int score_mode, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+                               int n_frames, int score_mode, bool stream_kv, hipStream_t s, hipEvent_t ev0,
+                               hipEvent_t ev1) {
     const dim3 grid(n_units * n_splits), block(kBlock);
     const unsigned short *qq = (const unsigned short *)q;
-    if (dv.D == 64) hipExtLaunchKernelGGL((k_decode_fused<64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
-    else hipExtLaunchKernelGGL((k_decode_fused<128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+    if (stream_kv) {
+        if (dv.D == 64) hipExtLaunchKernelGGL((k_decode_fused<64, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+        else hipExtLaunchKernelGGL((k_decode_fused<128, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+    } else {
+        if (dv.D == 64) hipExtLaunchKernelGGL((k_decode_fused<64, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+        else hipExtLaunchKernelGGL((k_decode_fused<128, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
-                              int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+                              int n_splits, bool stream_kv, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
     const unsigned short *qq = (const unsigned short *)q;
     const dim3 block(kBlock);
     if (NT == 1) {
         const int B = n_units * n_splits;
         const dim3 grid(B + (dv.aug_reps ? n_units : 0));
+        auto go = [&](auto kern) { hipExtLaunchKernelGGL(kern, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B); };
         if (dv.aug_reps) {
-            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_decode_mfma<64, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
-            else hipExtLaunchKernelGGL((k_attend_decode_mfma<128, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
+            if (dv.D == 64) stream_kv ? go(k_attend_decode_mfma<64, true, true>) : go(k_attend_decode_mfma<64, true, false>);
+            else stream_kv ? go(k_attend_decode_mfma<128, true, true>) : go(k_attend_decode_mfma<128, true, false>);
         } else {
-            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_decode_mfma<64, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
-            else hipExtLaunchKernelGGL((k_attend_decode_mfma<128, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B);
+            if (dv.D == 64) stream_kv ? go(k_attend_decode_mfma<64, false, true>) : go(k_attend_decode_mfma<64, false, false>);
+            else stream_kv ? go(k_attend_decode_mfma<128, false, true>) : go(k_attend_decode_mfma<128, false, false>);
         }
     } else {
         // dynamic LDS of the multi-token kernel: 4 K tiles [32][D + 8] and 4 V tiles [D][40] of bf16

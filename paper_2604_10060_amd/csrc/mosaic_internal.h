@@ -167,14 +167,16 @@ hipError_t launch_expand_tok_idx(const DeviceView &dv, int u0, int n_units, hipS
 // ev0/ev1 (may be null) receive the kernel's own start/stop timestamps
 hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                               int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+// stream_kv: the decode-shape kernels load K/V with the non-temporal hint (stores far beyond the caches)
 hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
-                              int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+                              int n_splits, bool stream_kv, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 // uniform: every unit has exactly n_splits splits at slots unit * n_splits + split (fused decode step)
 hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
                                  void *out, float *lse, hipStream_t s, bool uniform = false);
 // selection + attention of one decode step in one launch (one row tile, bf16, C <= 256, uniform splits)
 hipError_t launch_decode_fused(const DeviceView &dv, int u0, int n_units, const void *q, int Tq, int n_splits,
-                               int n_frames, int score_mode, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
+                               int n_frames, int score_mode, bool stream_kv, hipStream_t s, hipEvent_t ev0,
+                               hipEvent_t ev1);
 // retrieval augmentation: per-cluster value sums of all units (after the clustering changed); the
 // attention partial over the representatives is computed by extra workgroups of the attention launches
 hipError_t launch_value_reps(const DeviceView &dv, int n_frames, hipStream_t s);

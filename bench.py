@@ -41,9 +41,9 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
 MEASURED_TRAFFIC_BYTES = {
     ("cfg1_single_layer_hbm", "per_layer_decode_step", "k_decode_fused"): 29_870_000,   # 28.93 MB read + 0.94 MB written
     ("cfg1_single_layer_hbm", "per_layer", "k_attend_decode_mfma"): 27_150_000,     # 26.41 MB read + 0.74 MB written
-    ("cfg2_full_stack_hbm", "per_layer", "k_attend_decode_mfma"): 117_650_000,      # 116.94 MB + 0.71 MB
-    ("cfg2_full_stack_hbm", "per_layer_decode_step", "k_attend_decode_mfma"): 117_650_000,   # (same kernel: two calls inside)
-    ("cfg2_full_stack_hbm", "all_layers", "k_attend_decode_mfma"): 3_279_920_000,   # 3272.38 MB + 7.54 MB
+    ("cfg2_full_stack_hbm", "per_layer", "k_attend_decode_mfma"): 118_290_000,      # 117.37 MB + 0.93 MB
+    ("cfg2_full_stack_hbm", "per_layer_decode_step", "k_attend_decode_mfma"): 118_290_000,   # (same kernel: two calls inside)
+    ("cfg2_full_stack_hbm", "all_layers", "k_attend_decode_mfma"): 3_298_000_000,   # 3291.67 MB + 6.33 MB (32-step run)
 }
 
 

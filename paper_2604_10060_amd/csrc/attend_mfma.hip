@@ -332,7 +332,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
 // launch.  grid (n_units * S), 4 waves; workgroup = (unit, split), S uniform.
 // Every workgroup of a unit first repeats the unit's selection for itself -- mean
 // query, scores of the C <= 256 representatives, ranks of the k best, page offsets --
-// which costs it 64-128 KB of table reads that hit L2 and ~1.5 us of arithmetic, but
+// which costs it the table's C x D x 8 bytes through L2 (the longest part of its life: the query is
+// back after ~2 k cycles, the table after 6-7 k) and ~4 k cycles of arithmetic, but
 // removes the separate selection launch and the two dependent round trips (sizes,
 // page ids) at the start of the attention kernel; it then lists the pages of its own
 // contiguous chunk range in LDS and reduces them like k_attend_decode_mfma.  Split 0

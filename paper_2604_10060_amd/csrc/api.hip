@@ -781,13 +781,14 @@ int32_t mosaic_prefetch(mosaic_ctx *ctx, int32_t layer, const void *q_proxy_dev,
 
 // The decode kernels read K/V with the non-temporal hint once the stored KV is well beyond the 256 MB
 // memory-side cache (measured: 15 GB store, 3.3 GB per launch 562 -> 519 us; 134 MB store, 26 MB per
-// launch 18.1 -> 19.5 us with the hint, so small stores go without it).
+// launch 18.1 -> 19.5 us with the hint; at 268 MB 22.5 -> 24.5 us, at 537 MB equal, at 1074 MB 48.5 -> 45.9 us:
+// stores beyond 768 MiB get it).
 static bool kv_beyond_caches(const mosaic_ctx *ctx) {
     const DeviceView &dv = ctx->dv;
     // (host tier: what the kernels read is the GPU cluster cache, PU pages per unit)
     const long long pages = ctx->host ? (long long)dv.PU : ctx->n_frames;
     const long long stored = pages * (long long)dv.U * (long long)(dv.kpage + dv.vpage);
-    return stored > (1ll << 30);
+    return stored > (768ll << 20);
 }
 
 int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,

@@ -433,6 +433,7 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
         if (lr == 0) sc_sh[j] = p;
     }
     __syncthreads();
+    float *key_sh = reinterpret_cast<float *>(off_sh);     // (the page offsets are formed after the ranking)
     if (tid < C) {
         double sc = -INFINITY;
         if (n_sh[tid] > 0) {
@@ -440,23 +441,27 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
             sc = score_mode == 1 ? p : (nr == 0.0 ? 0.0 : p / nr);
         }
         sc_sh[tid] = sc;
+        key_sh[tid] = (float)sc;          // fp32 rounding for the pair count below
         if (split == 0) dv.scores[(size_t)u * dv.SC + tid] = sc;
     }
     __syncthreads();
     // ---- ranks by (score descending, id ascending) among the non-empty clusters ----
-    {   // 2^pl threads per entry (the largest power of two that fits the workgroup: shifts, no divisions)
+    {   // 2^pl threads per entry (the largest power of two that fits the workgroup: shifts, no divisions);
+        // pairs compared on the fp32 roundings (monotone, so a strict fp32 order is the fp64 order; fp64
+        // compares run at a quarter of the rate), collisions settled exactly below
         const int pl = 31 - __clz(kBlock / C);
         const int j = tid >> pl, part = tid & ((1 << pl) - 1);
         if (j < C && n_sh[j] > 0) {
-            const double sj = sc_sh[j];
+            const float fj = key_sh[j];
             const int i0 = (C * part) >> pl, i1 = (C * (part + 1)) >> pl;
-            int c = 0;           // (an empty cluster carries -inf and never outranks a live one)
+            int c = 0, ceq = 0;  // (an empty cluster carries -inf and neither outranks nor equals a live one)
 #pragma unroll 8
             for (int i = i0; i < i1; ++i) {
-                const double si = sc_sh[i];
-                c += (si > sj) || (si == sj && i < j);
+                const float fi = key_sh[i];
+                c += fi > fj;
+                ceq += fi == fj;
             }
-            atomicAdd(&cnt_sh[j], c);
+            atomicAdd(&cnt_sh[j], c + (ceq << 16));     // c <= 256, ceq <= 256
         }
     }
     __syncthreads();
@@ -464,7 +469,17 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
         const bool live = tid < C && n_sh[tid] > 0;
         int rk = -1;
         if (live) {
-            rk = cnt_sh[tid];
+            const int v = cnt_sh[tid];
+            rk = v & 0xffff;
+            if ((v >> 16) > 1) {                        // collisions (the entry itself counts once): exact order among them
+                const float fj = key_sh[tid];
+                const double sj = sc_sh[tid];
+                for (int i = 0; i < C; ++i) {
+                    if (i == tid || key_sh[i] != fj) continue;
+                    const double si = sc_sh[i];
+                    rk += (si > sj) || (si == sj && i < tid);
+                }
+            }
             if (rk < k) ids_sh[rk] = tid; else rk = -1;
         }
         if (tid < C) rank_sh[tid] = rk;

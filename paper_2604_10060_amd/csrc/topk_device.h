@@ -42,25 +42,41 @@ __device__ __forceinline__ int topk_rank(const double *sc_sh, const int *n_sh, i
     const bool live = tid < R && n_sh[tid] > 0;
     const double s = live ? sc_sh[tid] : 0.0;
     if (R <= 128) {
-        // small tables: the direct count, 2^pl threads per entry (the largest power of two that
-        // fits the workgroup: shifts instead of integer divisions)
+        // Small tables: the direct count over all pairs, 2^pl threads per entry (the largest power of
+        // two that fits the workgroup: shifts instead of integer divisions).  The pairs are compared
+        // on fp32 roundings of the scores (rounding is monotone, so a strict fp32 order is the fp64
+        // order; fp64 compares run at a quarter of the rate and were what this count waited for);
+        // an entry whose rounding collides with another one's is settled exactly afterwards.
+        float *key_sh = reinterpret_cast<float *>(cand_sh);
+        if (tid < R) key_sh[tid] = live ? (float)s : -INFINITY;
+        __syncthreads();
         const int pl = 31 - __clz(BLK / R);
         const int j = tid >> pl, part = tid & ((1 << pl) - 1);
         if (j < R && n_sh[j] > 0) {
-            const double sj = sc_sh[j];
+            const float fj = key_sh[j];
             const int i0 = (R * part) >> pl, i1 = (R * (part + 1)) >> pl;
-            int c = 0;           // (an entry that is not live carries -inf and never outranks a live one)
+            int c = 0, ceq = 0;  // (an entry that is not live carries -inf and neither outranks nor equals a live one)
 #pragma unroll 8
             for (int i = i0; i < i1; ++i) {
-                const double si = sc_sh[i];
-                c += (si > sj) || (si == sj && i < j);
+                const float fi = key_sh[i];
+                c += fi > fj;
+                ceq += fi == fj;
             }
-            atomicAdd(&cnt_sh[j], c);
+            atomicAdd(&cnt_sh[j], c + (ceq << 16));     // c <= 128, ceq <= 128
         }
         __syncthreads();
         int rk = -1;
         if (live) {
-            rk = cnt_sh[tid];
+            const int v = cnt_sh[tid];
+            rk = v & 0xffff;
+            if ((v >> 16) > 1) {                        // collisions (the entry itself counts once): exact order among them
+                const float fj = key_sh[tid];
+                for (int i = 0; i < R; ++i) {
+                    if (i == tid || key_sh[i] != fj) continue;
+                    const double si = sc_sh[i];
+                    rk += (si > s) || (si == s && i < tid);
+                }
+            }
             if (rk < k) ids_sh[rk] = tid; else rk = -1;
         }
         if (tid < R) rank_sh[tid] = rk;

@@ -800,3 +800,59 @@ def test_augmentation_cfg1_full_size():
     rep = harness.run_augmented(inputs.CONFIGS[1], 16, True, decode_steps=3)
     _report(rep)
     assert rep.max_out_err <= 2e-2
+
+
+# --------------------------------------------------------------------------
+# ranking: scores that differ only beyond fp32 resolution
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("higher_id_wins", [False, True])
+@pytest.mark.parametrize("n_clusters", [4, 160])
+def test_topk_scores_that_collide_in_fp32_are_ordered_exactly(higher_id_wins, n_clusters):
+    """The pair count of the ranking compares fp32 roundings of the scores and settles collisions in
+    fp64.  Two scenes whose constant key vectors differ by 2^-20 in one channel the query does not
+    use give two clusters whose scores differ by ~1e-12 relative: equal in fp32, ordered in fp64.
+    With k = 1 the selection must be the cluster the oracle picks, whichever of the two ids it has
+    (table of 4: the direct count; table of 160: the binned path), through mosaic_retrieve and
+    through mosaic_decode_step."""
+    from oracle import mosaic_oracle as orc
+    C, D, T, Hkv, G = n_clusters, 128, 8, 1, 2
+    W = 2 * C
+    F = W + 8
+    wl = inputs.CONFIGS[1].scaled(name="fp32_collision", n_layers=1, n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=D,
+                                  tokens_per_frame=T, n_frames=F, n_clusters=C, top_k=1, warmup_frames=W)
+    rng = np.random.Generator(np.random.PCG64(42))
+    base = rng.standard_normal((C, D)).astype(np.float32)
+    base = torch.tensor(base).to(torch.bfloat16).float().numpy()       # bf16-representable centres
+    base[:, 0] = 0.0
+    base[1] = base[0]                                                   # scenes 0 and 1: same vector ...
+    base[1 if not higher_id_wins else 0, 0] = 2.0 ** -20                # ... but for channel 0 of one of them
+    # warm-up frames 2j, 2j+1 show scene j (the K-means seeds are frames 0, 2, 4, ...); then more of 0 and 1
+    scene_of = [j // 2 for j in range(W)] + [0, 1] * 4
+    K = torch.tensor(np.stack([np.tile(base[sc], (1, Hkv, T, 1)) for sc in scene_of])).to(torch.bfloat16)
+    V = torch.tensor(rng.standard_normal(K.shape).astype(np.float32)).to(torch.bfloat16)
+    q = torch.tensor(np.tile(base[0] + 0.25 * base[2], (1, 1, Hkv * G, 1))).to(torch.bfloat16)   # [L][Tq][Hq][D]
+    q[..., 0] = 0.0
+    Kd, Vd, qd = K.to(DEV), V.to(DEV), q.to(DEV)
+    o = orc.OracleUnit(C, D, T, F, W, wl.lloyd_iters, 0)
+    Kc = inputs.unit_pages(K, 0, 0)
+    for f in range(F):
+        o.ingest(Kc[f])
+    ids_o, sc_o, tok_o, gap = o.retrieve(q[0].float().numpy().astype(np.float64), 0, G, 1)
+    top2 = np.sort(sc_o[o.sizes() > 0])[::-1][:2]
+    rel = (top2[0] - top2[1]) / abs(top2[0])
+    assert 0 < rel < 1e-9 and np.float32(top2[0]) == np.float32(top2[1]), (top2, rel)   # the case is what it claims
+    assert int(ids_o[0]) == (1 if higher_id_wins else 0)
+    m = binding.Mosaic(binding.config_for(wl), device=DEV)
+    for f in range(0, F, 5):
+        m.ingest_frame(Kd[f:f + 5].contiguous(), Vd[f:f + 5].contiguous())
+    np.testing.assert_array_equal(m.assignments()[0], o.assignments())
+    m.retrieve(0, qd[0].contiguous())
+    ids, n_ids, scores, toks = m.selection(0)
+    assert n_ids[0] == 1 and int(ids[0, 0]) == int(ids_o[0])
+    np.testing.assert_array_equal(toks[0], tok_o)
+    m.decode_step(0, qd[0].contiguous())
+    if C <= 256:
+        assert m.stats().last_decode_fused == 1
+    ids, n_ids, scores, toks = m.selection(0)
+    assert n_ids[0] == 1 and int(ids[0, 0]) == int(ids_o[0])
+    m.close()

@@ -142,9 +142,11 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     if constexpr (!NESTED) {
 #pragma unroll
         for (int i = 0; i < RPF; ++i) {
-            const double *rj = r + (size_t)min(row0 + RPP * i, C - 1) * D + lr * EPL;
+            if (RPP * i < C) {              // workgroup-uniform: passes beyond the table are not loaded
+                const double *rj = r + (size_t)min(row0 + RPP * i, C - 1) * D + lr * EPL;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
+                for (int e = 0; e < EPL; ++e) rpre[i][e] = rj[e];
+            }
         }
     }
     // first stage: the partition rows (P <= 64: one 16-lane group each), loaded up front as well

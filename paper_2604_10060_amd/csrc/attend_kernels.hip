@@ -166,12 +166,13 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
                                                    float (*w_sh)[kRowTile], float (*pm)[kRowTile],
                                                    float (*pl)[kRowTile], float *M_sh, float *L_sh,
                                                    float (&acc)[kRowTile]) {
-    constexpr int SPP = 64 * (kRowTile / RMAX);  // splits per pass
+    constexpr int SPP = 64 * (kRowTile / RMAX);  // splits per pass (128 partial values per thread) ...
+    constexpr int NB = (MAXS < SPP ? MAXS : SPP) / 8;   // ... in batches of 8 (fewer when the unit cannot have that many)
     const int tid = threadIdx.x, sg = tid / 32, col = tid % 32;
-    float v[SPP / 8][RMAX];
+    float v[NB][RMAX];
     auto load_pass = [&](int s0) {
 #pragma unroll
-        for (int i = 0; i < SPP / 8; ++i) {
+        for (int i = 0; i < NB; ++i) {
             const int s = min(s0 + sg + 8 * i, max(n_splits - 1, 0));
             const float *po = dv.part_o + (e0 + s) * kRowTile * D + dg * 32 + col;
 #pragma unroll
@@ -223,7 +224,7 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
     for (int s0 = 0; s0 < (MAXS > SPP ? n_splits : 1); s0 += SPP) {
         if (MAXS > SPP && s0 > 0) load_pass(s0);
 #pragma unroll
-        for (int i = 0; i < SPP / 8; ++i) {
+        for (int i = 0; i < NB; ++i) {
             const int s = s0 + sg + 8 * i;
             if (s < n_splits) {
 #pragma unroll
@@ -257,7 +258,10 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
     const int sg = tid / 32, col = tid % 32;
     float acc[kRowTile];
     if (rows <= 8) {             // block-uniform choices
-        if (n_splits <= 128) combine_accumulate<D, 128, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+        if (n_splits <= 16) combine_accumulate<D, 16, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+        else if (n_splits <= 32) combine_accumulate<D, 32, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+        else if (n_splits <= 64) combine_accumulate<D, 64, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+        else if (n_splits <= 128) combine_accumulate<D, 128, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
         else combine_accumulate<D, kMaxUnitSplits, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
     } else {
         if (n_splits <= 64) combine_accumulate<D, 64, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);

@@ -271,12 +271,17 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
     int *n = dv.n + (size_t)u * C;
 
     const bool nested = dv.P > 0;
+    // the summary of the next frame travels while the current frame is processed
+    double s_ahead = tid < D ? dv.summ[((size_t)u * dv.F + f0) * D + tid] : 0.0;
     for (int f = f0; f < f1; ++f) {
         // candidates: every cluster id, or (nested hierarchy, Sec. V-B) the ids of the frame's
         // visual partition only
         const int part_f = nested ? dv.part[f] : 0;
         const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : C;
-        if (tid < D) s_sh[tid] = dv.summ[((size_t)u * dv.F + f) * D + tid];
+        if (tid < D) {
+            s_sh[tid] = s_ahead;
+            if (f + 1 < f1) s_ahead = dv.summ[((size_t)u * dv.F + f + 1) * D + tid];
+        }
         __syncthreads();
         if (wave == 0) {
             double x = 0.0;

@@ -277,7 +277,8 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
         // candidates: every cluster id, or (nested hierarchy, Sec. V-B) the ids of the frame's
         // visual partition only
         const int part_f = nested ? dv.part[f] : 0;
-        const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : C;
+        // (maintainer: only the ids in use, [0, n_slots), can have members; the table behind them is not read)
+        const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : (MAINT ? min(C, max(dv.n_slots[u], 1)) : C);
         if (tid < D) {
             s_sh[tid] = s_ahead;
             if (f + 1 < f1) s_ahead = dv.summ[((size_t)u * dv.F + f + 1) * D + tid];

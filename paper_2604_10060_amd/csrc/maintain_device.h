@@ -29,11 +29,8 @@ template <int D> struct SplitShared {
     int m, cnt1, fresh;
 };
 
-__device__ __forceinline__ double mt_g16sum(double x) {
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) x += __shfl_xor(x, o, 16);
-    return x;
-}
+// (every call site has all 16 lanes of the group active)
+__device__ __forceinline__ double mt_g16sum(double x) { return row16_sum(x); }
 __device__ __forceinline__ double mt_wave_sum(double x) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
@@ -135,15 +132,33 @@ __device__ int mt_split_cluster(const DeviceView &dv, int u, int a, int n_frames
 #pragma unroll
             for (int e = 0; e < EPL; ++e) si[e] = s[e];
             const double ni = nrm[i];
-            for (int k = i + 1; k < m; ++k) {
-                const double *t = summ + (size_t)mem[k] * D + lr * EPL;
-                double p = 0.0;
+            // four partners at a time: their indices, then their rows, are fetched together (one chain of
+            // two round trips per batch instead of per pair); compared in k order
+            for (int k0 = i + 1; k0 < m; k0 += 4) {
+                int row[4];
+                double nk[4], t[4][EPL];
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) p += si[e] * t[e];
-                p = mt_g16sum(p);
-                const double nk = nrm[k];
-                const double cs = (ni == 0.0 || nk == 0.0) ? 0.0 : p / (ni * nk);
-                if (cs < bv || (cs == bv && (i < bi || (i == bi && k < bk)))) { bv = cs; bi = i; bk = k; }
+                for (int x = 0; x < 4; ++x) {
+                    const int kk = min(k0 + x, m - 1);
+                    row[x] = mem[kk];
+                    nk[x] = nrm[kk];
+                }
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const double *tp = summ + (size_t)row[x] * D + lr * EPL;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) t[x][e] = tp[e];
+                }
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int k = k0 + x;
+                    double p = 0.0;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) p += si[e] * t[x][e];
+                    p = mt_g16sum(p);
+                    const double cs = (ni == 0.0 || nk[x] == 0.0) ? 0.0 : p / (ni * nk[x]);
+                    if (k < m && (cs < bv || (cs == bv && (i < bi || (i == bi && k < bk))))) { bv = cs; bi = i; bk = k; }
+                }
             }
         }
 #pragma unroll

@@ -216,9 +216,17 @@ __device__ int mt_split_cluster(const DeviceView &dv, int u, int a, int n_frames
             va = 0.0; vb = 0.0;
             if (tid < D) {
                 double acc0 = 0.0, acc1 = 0.0;
-                for (int i = 0; i < m; ++i) {
-                    const double v = summ[(size_t)mem[i] * D + tid];
-                    if (side[i]) acc1 += v; else acc0 += v;
+                // eight members' indices, sides and rows in flight at a time (clamped, unconditional), added in member order
+                for (int i0 = 0; i0 < m; i0 += 8) {
+                    int row[8], sd[8];
+                    double v[8];
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) { const int i = min(i0 + x, m - 1); row[x] = mem[i]; sd[x] = side[i]; }
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) v[x] = summ[(size_t)row[x] * D + tid];
+#pragma unroll
+                    for (int x = 0; x < 8; ++x)
+                        if (i0 + x < m) { if (sd[x]) acc1 += v[x]; else acc0 += v[x]; }
                 }
                 if (n0 > 0) sh.ca[tid] = acc0 / (double)n0;
                 if (n1 > 0) sh.cb[tid] = acc1 / (double)n1;
@@ -260,8 +268,15 @@ __device__ int mt_split_cluster(const DeviceView &dv, int u, int a, int n_frames
             __syncthreads();
             if (tid < 2) {                        // thread 0: cluster a, thread 1: the new cluster
                 double acc = 0.0;
-                for (int i = 0; i < m; ++i)
-                    if (side[i] == tid) acc += nrm[i];
+                for (int i0 = 0; i0 < m; i0 += 8) {      // eight entries in flight, added in member order
+                    int sd[8];
+                    double v[8];
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) { const int i = min(i0 + x, m - 1); sd[x] = side[i]; v[x] = nrm[i]; }
+#pragma unroll
+                    for (int x = 0; x < 8; ++x)
+                        if (i0 + x < m && sd[x] == tid) acc += v[x];
+                }
                 const int j = tid ? fresh : a, cnt = tid ? n1 : m - n1;
                 dv.var[(size_t)u * C + j] = acc / (double)cnt;
                 dv.n[(size_t)u * C + j] = cnt;
@@ -281,7 +296,17 @@ __device__ int mt_split_cluster(const DeviceView &dv, int u, int a, int n_frames
         double v = 0.0;
         if (tid < D && m > 0) {
             double acc = 0.0;
-            for (int i = 0; i < m; ++i) acc += summ[(size_t)mem[i] * D + tid];
+            for (int i0 = 0; i0 < m; i0 += 8) {          // eight members in flight, added in member order
+                int row[8];
+                double w[8];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) row[x] = mem[min(i0 + x, m - 1)];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) w[x] = summ[(size_t)row[x] * D + tid];
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+                    if (i0 + x < m) acc += w[x];
+            }
             v = acc / (double)m;
             sh.ca[tid] = v;
             r[(size_t)a * D + tid] = v;
@@ -299,7 +324,14 @@ __device__ int mt_split_cluster(const DeviceView &dv, int u, int a, int n_frames
         __syncthreads();
         if (tid == 0) {
             double acc = 0.0;
-            for (int i = 0; i < m; ++i) acc += nrm[i];
+            for (int i0 = 0; i0 < m; i0 += 8) {
+                double w[8];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) w[x] = nrm[min(i0 + x, m - 1)];
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+                    if (i0 + x < m) acc += w[x];
+            }
             dv.var[(size_t)u * C + a] = m > 0 ? acc / (double)m : 0.0;
             dv.n[(size_t)u * C + a] = m;
             if (m > 0) dv.rnorm[(size_t)u * C + a] = sqrt(q);

@@ -404,15 +404,22 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv,
         const int j = ids_sh[i];
         if (j >= C || !dv.lazy[(size_t)u * C + j]) continue;      // workgroup-uniform
         __syncthreads();
-        if (tid == 0) {
+        {   // the cluster's buffered entries join it, the others close ranks in order: one entry per
+            // thread (C + buf_max <= 1024), kept entries placed by an exclusive scan over the workgroup
             const int cur = dv.n_buf[u];
-            int w = 0;
-            for (int b = 0; b < cur; ++b) {
-                if (buf_owner[b] == j) { assign[buf_frame[b]] = j; continue; }
-                buf_frame[w] = buf_frame[b]; buf_owner[w] = buf_owner[b]; ++w;
+            const bool have = tid < cur;
+            int fr = 0, ow = -1;
+            if (have) { fr = buf_frame[tid]; ow = buf_owner[tid]; }
+            const bool mine = have && ow == j;
+            if (mine) assign[fr] = j;
+            const int keep = have && !mine;
+            int total;
+            const int w = mt_block_excl_scan<D>(keep, split_sh, &total);   // (its barriers come after every load above)
+            if (keep) { buf_frame[w] = fr; buf_owner[w] = ow; }
+            if (tid == 0) {
+                dv.n_buf[u] = total;
+                dv.lazy[(size_t)u * C + j] = 0;
             }
-            dv.n_buf[u] = w;
-            dv.lazy[(size_t)u * C + j] = 0;
         }
         __syncthreads();
         const int fresh = mt_split_cluster<D>(dv, u, j, n_frames, true, split_sh);

@@ -46,11 +46,8 @@ template <> struct Elem<unsigned short> {
 
 // (every call site has all 16 lanes of the group active)
 __device__ __forceinline__ double group16_sum(double x) { return row16_sum(x); }
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
-}
+// (every call site has the whole wavefront active)
+__device__ __forceinline__ double wave_sum(double x) { return wave64_sum(x); }
 // (value, id) ordered by value descending then id ascending
 __device__ __forceinline__ bool better(double v, int i, double bv, int bi) {
     return v > bv || (v == bv && i < bi);

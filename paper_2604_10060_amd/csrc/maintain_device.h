@@ -31,11 +31,8 @@ template <int D> struct SplitShared {
 
 // (every call site has all 16 lanes of the group active)
 __device__ __forceinline__ double mt_g16sum(double x) { return row16_sum(x); }
-__device__ __forceinline__ double mt_wave_sum(double x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
-}
+// (every call site has the whole wavefront active)
+__device__ __forceinline__ double mt_wave_sum(double x) { return wave64_sum(x); }
 
 // Exclusive prefix of one count per thread over the workgroup, in thread order;
 // *total receives the sum.  Uses sh.wtot; ends with a barrier.

@@ -222,6 +222,20 @@ __device__ __forceinline__ double row16_sum(double x) {
     x += dpp_f64<kDppXor1>(x);
     return x;
 }
+// Sum over the 64 lanes of a wavefront (all lanes active), the same bits in every lane: the four rows'
+// sums are read from their first lanes and added in a fixed order.
+__device__ __forceinline__ double wave64_sum(double x) {
+    x = row16_sum(x);
+    const long long b = __double_as_longlong(x);
+    const int lo = (int)b, hi = (int)(b >> 32);
+    double r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int l = __builtin_amdgcn_readlane(lo, 16 * i), h = __builtin_amdgcn_readlane(hi, 16 * i);
+        r[i] = __longlong_as_double(((long long)h << 32) | (long long)(unsigned int)l);
+    }
+    return (r[0] + r[1]) + (r[2] + r[3]);
+}
 
 
 // ---------------------------------------------------------------------------

@@ -18,11 +18,8 @@ namespace {
 
 constexpr int kVisBlock = 1024, kVisWaves = kVisBlock / 64;
 
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
-}
+// (every call site has the whole wavefront active)
+__device__ __forceinline__ double wave_sum(double x) { return wave64_sum(x); }
 __device__ __forceinline__ bool better(double v, int i, double bv, int bi) {
     return v > bv || (v == bv && i < bi);
 }

@@ -135,6 +135,7 @@ def query_with_parity(m: binding.Mosaic, wl, q: torch.Tensor, oracles, K, V, rep
         for l in range(L):
             o_, l_ = m.decode_step(l, q[l].contiguous())
             outs.append(o_); lses.append(l_)
+            rep.notes.append(("decode_step_fused", int(m.stats().last_decode_fused)))
         out, lse = torch.stack(outs), torch.stack(lses)
     else:
         outs, lses = [], []

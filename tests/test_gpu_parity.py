@@ -807,6 +807,15 @@ def test_nested_benchmark_recipe():
     assert rep.max_out_err <= 2e-2 and rep.online_decisions > 0
 
 
+def test_augmentation_on_a_store_beyond_the_caches():
+    """840 MB of stored KV: the decode kernel's instantiation with the representatives' extra workgroups
+    and non-temporal K/V loads (no benchmark leg combines the two)."""
+    wl = inputs.CONFIGS[1].scaled(name="aug_long_stream", n_frames=6400, n_scenes=250, question_tokens=2)
+    rep = harness.run_augmented(wl, 16, True, units=[(0, 2)], decode_steps=2, ingest_between=False)
+    _report(rep)
+    assert rep.max_out_err <= 2e-2
+
+
 def test_augmentation_cfg1_full_size():
     """Config 1 at full size with the benchmark's augmentation (window of 16 frames and the
     representatives as pseudo-KV)."""

@@ -240,11 +240,12 @@ def test_cfg2_full_size_sampled_units():
     assert rep.max_out_err <= 2e-2
 
 
-def test_decode_step_fused_on_a_store_beyond_the_caches():
-    """A long stream with a narrow selection: 1.07 GB of stored KV (the decode kernels then load K/V with
-    the non-temporal hint) but only ~34 MB per step, so mosaic_decode_step still takes the one-kernel
+@pytest.mark.parametrize("kw", [dict(n_frames=8192, n_scenes=320), dict(n_frames=13000, n_scenes=500, head_dim=64)])
+def test_decode_step_fused_on_a_store_beyond_the_caches(kw):
+    """A long stream with a narrow selection: 0.85-1.07 GB of stored KV (the decode kernels then load K/V
+    with the non-temporal hint) but only ~30 MB per step, so mosaic_decode_step still takes the one-kernel
     path -- the streaming instantiation of the fused kernel, which no benchmark configuration reaches."""
-    wl = inputs.CONFIGS[1].scaled(name="long_stream_narrow_selection", n_frames=8192, n_scenes=320, top_k=2)
+    wl = inputs.CONFIGS[1].scaled(name="long_stream_narrow_selection", top_k=2, **kw)
     rep = harness.run_full_size(wl, [(0, 0), (0, 3)], layer_modes=("fused", "per_layer"), ingest_batch=64,
                                 decode_steps=2, question=False)
     _report(rep)

@@ -17,7 +17,12 @@
  * fixture, closed forms of Eq. 5, Eq. 2 against numpy, Split against a numpy
  * two-means, equality with the plain online rule when the threshold is out of
  * reach, and the state transitions of Alg. 1 (buffered singletons, their
- * visibility to retrieval, materialization on retrieval, conservation).
+ * visibility to retrieval, materialization on retrieval, conservation); the
+ * readings inside Alg. 1 by a hand-worked fixture whose verdict flips between
+ * tau(|C|) and tau(|C| + 1) (the size before the insertion enters Eq. 5),
+ * Eq. 3 / Eq. 4 in numpy on the owner of a buffered state (statistics move,
+ * size does not), singleton scores in both score modes against numpy, and
+ * reset + re-ingest against a fresh unit.
  * The nested visual-semantic hierarchy (Sec. V-B) and two-stage retrieval
  * (Sec. V-C) are pinned by the special cases P = 1 and top_p = P (both must
  * be the flat path), the nesting invariant, seeds read back after zero

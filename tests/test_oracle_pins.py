@@ -463,6 +463,140 @@ def test_eq5_threshold_closed_forms():
     np.testing.assert_allclose(orc.tau(lo, hi, n0, n0 * np.log(2.0)) - lo, (hi - lo) / 2, rtol=1e-14)
 
 
+def test_eq5_threshold_is_evaluated_at_the_size_before_the_insertion():
+    """Alg. 1 tests the threshold (line 2) before the union (line 3): tau takes the cluster size
+    without the new state.  Hand-worked fixture with tau_min != tau_max whose first row is absorbed
+    at tau(|C|) and would be invalid at tau(|C| + 1)."""
+    import math
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "eq5_threshold_before_insertion.txt"))
+            if l.strip() and not l.startswith("#")]
+    lo, hi, n0 = 1.0, 5.0, 2.0
+    u = orc.OracleUnit(2, 1, 1, 16, warmup_frames=2, lloyd_iters=2,
+                       maintainer=_maint(tau_min=lo, tau_max=hi, n0=n0))
+    u.ingest(np.array([[1.0]]))
+    u.ingest(np.array([[3.0]]))
+    flips = 0
+    for x, n_before, var, tau_n, tau_n1, verdict in rows:
+        assert u.sizes()[0] == int(n_before)
+        u.ingest(np.array([[float(x)]]))
+        got_var, got_tau = u.last_threshold_test
+        np.testing.assert_allclose(got_var, float(var), rtol=1e-14)
+        np.testing.assert_allclose(got_tau, float(tau_n), rtol=1e-15)
+        np.testing.assert_allclose(got_tau, lo + (hi - lo) * math.exp(-int(n_before) / n0), rtol=1e-15)
+        assert (u.last_action == orc.ACT_ABSORB) == (verdict == "absorb")
+        assert (float(var) <= float(tau_n)) == (verdict == "absorb")
+        flips += (float(var) <= float(tau_n)) != (float(var) <= float(tau_n1))
+        assert u.sizes()[0] == int(n_before) + 1      # (a 1-D cluster cannot be split: absorbed either way)
+    assert flips >= 1                                  # the fixture does tell the two readings apart
+    assert u.counters()["forced_absorb"] == 1
+
+
+def test_deferred_insertion_moves_the_owners_statistics_but_not_its_size():
+    """Alg. 1 line 1 runs before the case analysis: representative (Eq. 3) and variance (Eq. 4) of
+    the assigned cluster move also when the state is then buffered (lines 7-10); membership and
+    size do not.  Two deferred insertions in a row, compared with Eq. 3 / Eq. 4 in numpy."""
+    r = _rng(30)
+    u, K, ca, cb = _deferred_unit(r, n_a=10, n_b=0)
+    S = u.summaries()
+    n = 10
+    rep = S.mean(axis=0)
+    np.testing.assert_allclose(u.centroids()[0], rep, rtol=1e-13)
+    var = u.variances()[0]            # Eq. 2 at the warm-up, Eq. 4 since (pinned by the Eq. 4 fixture)
+    assert 0.0 < var < 2.0 and u.lazy_flags()[0] == 0
+    for i in range(2):
+        k_new = cb[None, :] + 0.2 * r.normal(size=(2, 8))
+        s = k_new.mean(axis=0)
+        u.ingest(k_new)
+        assert u.last_action == orc.ACT_DEFER and u.n_buf == i + 1
+        rep = (n * rep + s) / (n + 1)                                  # Eq. 3 with the size of the members
+        var = (n * var + ((s - rep) ** 2).sum()) / (n + 1)             # Eq. 4
+        np.testing.assert_allclose(u.centroids()[0], rep, rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(u.variances()[0], var, rtol=1e-13)
+        got_var, got_tau = u.last_threshold_test
+        np.testing.assert_allclose(got_var, var, rtol=1e-13)
+        assert got_var > got_tau == 2.0
+        assert u.sizes()[0] == n and u.assignments()[10 + i] == -2 and u.lazy_flags()[0] == 1
+    # the owner's moved representative is what the next query scores
+    q = r.normal(size=(1, 1, 8))
+    ids, sc, tok, _ = u.retrieve_maintained(q, 0, 1, 3)
+    np.testing.assert_allclose(sc[0], q[0, 0] @ rep / np.linalg.norm(rep), rtol=1e-13)
+
+
+@pytest.mark.parametrize("score_mode", [0, 1])
+def test_buffered_singletons_are_scored_like_clusters(score_mode):
+    """Alg. 1 line 10 registers a buffered state as a singleton cluster: its representative is its
+    own summary and its relevance follows the cluster formula -- (q . s)/|s|, or the plain dot
+    product in score_mode 1 -- so that clusters and singletons rank on one scale (numpy)."""
+    r = _rng(31 + score_mode)
+    D, T, C = 8, 2, 6
+    ca, cb = r.normal(size=D) * 3, r.normal(size=D) * 3
+    K = np.stack([ca] * 10 + [cb] * 4)[:, None, :] + 0.2 * r.normal(size=(14, T, D))
+    u = orc.OracleUnit(C, D, T, 64, warmup_frames=6, lloyd_iters=2, score_mode=score_mode,
+                       maintainer=_maint(mode=2, c_init=1, tau_min=2.0, tau_max=2.0, buf_max=8))
+    for f in range(14):
+        u.ingest(K[f])
+    assert u.n_buf == 4
+    S, R = u.summaries(), u.centroids()
+    q = r.normal(size=(3, 2, D))                        # 3 tokens, G = 2 heads on this KV head
+    qbar = q.reshape(-1, D).mean(axis=0)
+    fr, _ = u.buffer()
+    want_single = S[fr] @ qbar
+    want_cluster = R[0] @ qbar
+    if score_mode == 0:
+        want_single = want_single / np.linalg.norm(S[fr], axis=1)
+        want_cluster = want_cluster / np.linalg.norm(R[0])
+    k = 3
+    ids, sc, tok, gap = u.retrieve_maintained(q, 0, 2, k)
+    assert sc.shape == (C + 4,)
+    np.testing.assert_allclose(sc[C:], want_single, rtol=1e-13)
+    np.testing.assert_allclose(sc[0], want_cluster, rtol=1e-13)
+    assert np.all(np.isneginf(sc[1:C]))
+    # ranking over clusters and singletons together: full numpy sort, ties to the lower id
+    cand = np.array([0] + [C + b for b in range(4)])
+    val = np.concatenate([[want_cluster], want_single])
+    order = cand[np.lexsort((cand, -val))][:k]
+    np.testing.assert_array_equal(ids, order)
+    # the two score modes differ by the norms only: a scaled copy of a state ranks differently
+    if score_mode == 1:
+        assert not np.allclose(want_single, want_single / np.linalg.norm(S[fr], axis=1))
+
+
+def test_reset_and_reingest_equals_a_fresh_unit():
+    """orc_unit_reset forgets frames, clusters and maintainer state: the same stream through a
+    reset unit gives exactly the state of a new one (flat, maintainer in both modes, nested)."""
+    K, _ = _stream(120, 2, 8, 6, seed=32, noise=0.4)
+    part = (np.arange(120) // 7 % 3).astype(np.int32)
+    variants = [dict(), dict(recluster_every=40),
+                dict(maintainer=_maint(mode=1, c_init=3, tau_min=1.0, tau_max=3.0, n0=10.0)),
+                dict(maintainer=_maint(mode=2, c_init=3, tau_min=1.0, tau_max=3.0, n0=10.0, buf_max=6)),
+                dict(nested=3)]
+    for kw in variants:
+        def run(u):
+            rq = _rng(33)
+            for f in range(120):
+                if kw.get("nested"):
+                    u.ingest_nested(K[f], part)
+                else:
+                    u.ingest(K[f])
+                if kw.get("maintainer", {}).get("mode") == 2 and f >= 6 and f % 25 == 0:
+                    u.retrieve_maintained(rq.normal(size=(1, 1, 8)), 0, 1, 3)
+            st = dict(a=u.assignments(), n=u.sizes(), r=u.centroids(), s=u.summaries(), runs=u.n_lloyd_runs)
+            if kw.get("maintainer"):
+                st.update(v=u.variances(), lz=u.lazy_flags(), res=u.resident_flags(), nb=u.n_buf,
+                          ns=u.n_slots, buf=np.concatenate(u.buffer()), cnt=tuple(u.counters().values()))
+            return st
+        C = 12
+        used = orc.OracleUnit(C, 8, 2, 120, lloyd_iters=3, **kw)
+        first = run(used)
+        used.reset()
+        assert used.n_frames == 0 and not used.ready and used.sizes().sum() == 0
+        again = run(used)
+        fresh = run(orc.OracleUnit(C, 8, 2, 120, lloyd_iters=3, **kw))
+        for key in fresh:
+            np.testing.assert_array_equal(again[key], fresh[key], err_msg=f"{kw}: {key} after reset")
+            np.testing.assert_array_equal(first[key], fresh[key], err_msg=f"{kw}: {key}")
+
+
 def test_maintainer_with_unreachable_threshold_is_the_plain_online_rule():
     """With tau = 1e300 nothing is ever invalid: assignments, sizes and representatives must be
     those of the plain greedy rule with C = c_init (Sec. VI-A without refinement)."""

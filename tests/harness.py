@@ -41,6 +41,46 @@ class Report:
     notes: list = field(default_factory=list)
 
 
+def _rel_gap(a, b):
+    return abs(a - b) / max(abs(a), abs(b), 1e-30)
+
+
+def selection_within_near_ties(got_ids, want_ids, score) -> bool:
+    """The near-tie rule for a ranked selection (ids by score descending, ties to the lower id).
+
+    `want_ids` is the oracle's list, `score` the oracle's score per id.  A different list
+    `got_ids` is acceptable only if it is the oracle's list up to exchanges of near-tied entries:
+      * same length, no id twice, every id has a finite score;
+      * at every rank where the two lists differ, the scores of the two ids at that rank are
+        within NEAR_TIE (relative) of each other -- which covers both an exchange inside the list
+        and an exchange across the k / k+1 cut;
+      * every id that was kept scores at least as much as every id that was dropped, up to
+        NEAR_TIE, and the list is in descending order up to NEAR_TIE.
+    An id set that differs from the oracle's anywhere away from a near-tie fails."""
+    got = [int(x) for x in got_ids]
+    want = [int(x) for x in want_ids]
+    if got == want:
+        return True
+    if len(got) != len(want) or len(set(got)) != len(got):
+        return False
+    sc = np.asarray(score, dtype=np.float64)
+    if any(g < 0 or g >= len(sc) or not np.isfinite(sc[g]) for g in got):
+        return False
+    for g, w in zip(got, want):
+        if g != w and not _rel_gap(sc[g], sc[w]) < NEAR_TIE:
+            return False
+    for a, b in zip(got, got[1:]):
+        if sc[a] < sc[b] and not _rel_gap(sc[a], sc[b]) < NEAR_TIE:
+            return False
+    dropped = [j for j in range(len(sc)) if np.isfinite(sc[j]) and j not in set(got)]
+    if dropped and got:
+        lo = min(sc[g] for g in got)
+        hi = max(sc[j] for j in dropped)
+        if hi > lo and not _rel_gap(hi, lo) < NEAR_TIE:
+            return False
+    return True
+
+
 def segment_bounds(wl, F):
     """Frame counts at which a Lloyd run happens (init, re-clusterings), plus F."""
     W = wl.warmup
@@ -161,11 +201,9 @@ def query_with_parity(m: binding.Mosaic, wl, q: torch.Tensor, oracles, K, V, rep
         assert n_ids[h] == len(ids_o)
         assert np.all(ids[h, n_ids[h]:] == -1)
         if not np.array_equal(got_ids, ids_o):
-            # acceptable only at a documented near-tie in the ranking
-            srt = np.sort(sc_o[live])[::-1]
-            gaps = np.abs(np.diff(srt)) / np.maximum(np.maximum(np.abs(srt[1:]), np.abs(srt[:-1])), 1e-30)
-            assert gaps.min() < NEAR_TIE, (
-                f"unit {(l, h)}: ids {got_ids} != oracle {ids_o} with no near-tie (min gap {gaps.min():.3e})")
+            # acceptable only where the differing entries are near-tied in the oracle's scores
+            assert selection_within_near_ties(got_ids, ids_o, sc_o), (
+                f"unit {(l, h)}: ids {got_ids} != oracle {ids_o} away from any near-tie (gap at the cut {gap:.3e})")
             rep.topk_near_ties += 1
             tok_o = o.gather(got_ids)
         np.testing.assert_array_equal(toks[h], tok_o)
@@ -636,11 +674,12 @@ def query_nested_with_parity(m, wl, q, oracles, K, V, rep, P, top_p):
         assert np.all(np.isneginf(pscores[h][~plive]))
         assert n_pids[h] == len(want["part_ids"]) and np.all(pids[h, n_pids[h]:] == -1)
         if not np.array_equal(pids[h, : n_pids[h]], want["part_ids"]):
-            # only a near-tie between partitions excuses it; the second stage then has other candidates
-            assert want["gap_p"] < NEAR_TIE or _min_rel_gap(want["part_scores"][plive]) < NEAR_TIE, (
-                f"unit {(l, h)}: partitions {pids[h, : n_pids[h]]} != oracle {want['part_ids']}")
+            # only near-tied partition scores excuse it; the second stage is then checked against the
+            # oracle's second stage run over the partitions the library kept
+            assert selection_within_near_ties(pids[h, : n_pids[h]], want["part_ids"], want["part_scores"]), (
+                f"unit {(l, h)}: partitions {pids[h, : n_pids[h]]} != oracle {want['part_ids']} away from any near-tie")
             rep.topk_near_ties += 1
-            continue
+            want = _second_stage_over(o, q_h[l], h, G, pids[h, : n_pids[h]], P, wl.top_k, want)
         cand = np.isfinite(want["scores"])
         assert np.array_equal(np.isfinite(scores[h]), cand), f"unit {(l, h)}: candidate sets differ"
         assert int(cand.sum()) == want["n_candidates"]
@@ -649,8 +688,8 @@ def query_nested_with_parity(m, wl, q, oracles, K, V, rep, P, top_p):
         assert n_ids[h] == len(want["ids"]) and np.all(ids[h, n_ids[h]:] == -1)
         tok_o = want["tok_idx"]
         if not np.array_equal(got_ids, want["ids"]):
-            assert _min_rel_gap(want["scores"][cand]) < NEAR_TIE, (
-                f"unit {(l, h)}: ids {got_ids} != oracle {want['ids']} with no near-tie")
+            assert selection_within_near_ties(got_ids, want["ids"], want["scores"]), (
+                f"unit {(l, h)}: ids {got_ids} != oracle {want['ids']} away from any near-tie")
             rep.topk_near_ties += 1
             tok_o = o.gather(got_ids)
         np.testing.assert_array_equal(toks[h], tok_o)
@@ -665,8 +704,19 @@ def query_nested_with_parity(m, wl, q, oracles, K, V, rep, P, top_p):
         assert lerr <= LSE_TOL[wl.kv_dtype], f"unit {(l, h)}: lse max-abs err {lerr:.3e}"
 
 
-def _min_rel_gap(x):
-    s = np.sort(np.asarray(x, dtype=np.float64))[::-1]
-    if len(s) < 2:
-        return np.inf
-    return float((np.abs(np.diff(s)) / np.maximum(np.maximum(np.abs(s[1:]), np.abs(s[:-1])), 1e-30)).min())
+def _second_stage_over(o, q_l, h, G, part_ids, P, top_k, first):
+    """Second retrieval stage of the oracle over a given set of partitions (used when the library's
+    first stage differs from the oracle's at a near-tie): the oracle's own scoring and selection
+    routines on the clusters of those partitions only."""
+    Cs = o.C // P
+    sc_all = o.score(orc.mean_query(q_l, h, G))
+    sizes = o.sizes()
+    keep = np.zeros(o.C, dtype=bool)
+    for p in part_ids:
+        keep[int(p) * Cs:(int(p) + 1) * Cs] = True
+    live = np.where(keep, sizes, 0).astype(np.int32)
+    sc = np.where(live > 0, sc_all, -np.inf)
+    ids, gap = orc.select(sc, live, top_k)
+    out = dict(first)
+    out.update(ids=ids, scores=sc, gap_k=gap, n_candidates=int((live > 0).sum()), tok_idx=o.gather(ids))
+    return out

@@ -84,9 +84,10 @@ typedef struct {
     /* host tier only (ignored for MOSAIC_TIER_HBM) */
     int32_t slab_frames;          /* frames per host slab (a cluster's pages are contiguous in runs of
                                      this many frames, keys then values); 0 -> 8 */
-    int32_t cache_pages_per_unit; /* GPU cluster-cache capacity per unit, in frame pages (rounded up to
-                                     whole slabs); 0 -> 3 * max(cache_fraction, top_k/C) * (max_frames +
-                                     C * slab_frames) + top_k * slab_frames, at most the whole stream */
+    int32_t cache_pages_per_unit; /* GPU cluster-cache capacity per unit, in frame pages; 0 -> 3 *
+                                     max(cache_fraction, top_k/C) * max_frames + top_k, at most the
+                                     whole stream.  A selection whose clusters hold more frames than
+                                     this cannot be attended: mosaic_retrieve then fails (ECAPACITY) */
     float cache_fraction;         /* at most floor(cache_fraction * C) clusters (but at least top_k) are
                                      cached per unit, least recently used evicted first; 0 -> 0.10 */
     int32_t reserved1;
@@ -182,11 +183,23 @@ typedef struct {
  * ignored).  dev_bytes, host_bytes: host pointers; host_bytes may be NULL. */
 int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes, size_t *host_bytes);
 
-/* Validate cfg, carve the arena, enqueue nothing.  out: host pointer. */
+/* One context per video stream: the "layer-wise KVCache" that Frame Encoding updates and Query
+ * Retrieval reads (Sec. V-A "Setup"), with the state Alg. 1 lists per cluster (representative,
+ * variance, lazy-split flag, GPU buffer, representative set).  Validates cfg, carves the arena;
+ * the only device work it enqueues clears the maintainer's counters.  out: host pointer.
+ * Host tier: the library creates two default-priority streams of its own (selection; fetches)
+ * and per-layer events, because the overlap of Sec. VII-B is between the library's own fetch of
+ * layer l+1 and the caller's attention of layer l: the caller hands over one stream and the
+ * library orders its internal streams against it with events, never with a host wait on the
+ * caller's stream.  Errors: EINVAL, ENOMEM (arena too small), EHIP. */
 int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out);
+/* Waits for the context's streams, releases the library's streams and events; the arenas stay
+ * the caller's. */
 int32_t mosaic_destroy(mosaic_ctx *ctx);
 
-/* Forget all frames and clusters; keep the arena and configuration. */
+/* A new video stream on the same context (Sec. V-A: the cache is built per stream): forget all
+ * frames, clusters, maintainer state (Alg. 1 "State") and cache contents; keep the arenas and the
+ * configuration.  Stream-ordered in the HBM tier; the host tier waits for its streams first. */
 int32_t mosaic_reset(mosaic_ctx *ctx);
 
 /* Frame Encoding (Sec. V-A (1); Sec. VI-A greedy assignment and Eq. 3; Sec. VII-A
@@ -231,7 +244,8 @@ int32_t mosaic_ingest_frame_visual(mosaic_ctx *ctx, const void *k_dev, const voi
  * moved by one fetch kernel per call on an internal copy stream (the kernel
  * reads the pinned slabs over PCIe), so that the fetch for layer l+1 overlaps
  * mosaic_attend of layer l when retrieve(l+1) is issued before attend(l).
- * ECAPACITY if the selection does not fit the cache. */
+ * ECAPACITY if the selection does not fit the cache: the cache and its directory are then left
+ * exactly as they were and the layer has no current selection. */
 int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
                         int32_t n_q_tokens);
 
@@ -245,7 +259,7 @@ int32_t mosaic_retrieve(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
  * step); results never depend on whether, or with which proxy, mosaic_prefetch was called.
  * Contains the same short host wait as the host tier's mosaic_retrieve (read-back of k ids).
  * Errors: EINVAL (not the host tier, layer < 0, NULL, n_q_tokens out of range); ENOTREADY;
- * ECAPACITY if the predicted clusters do not fit the cache. */
+ * ECAPACITY if the predicted clusters do not fit the cache (nothing is fetched or evicted then). */
 int32_t mosaic_prefetch(mosaic_ctx *ctx, int32_t layer, const void *q_proxy_dev, int32_t n_q_tokens);
 
 /* Query Retrieval, attention part (Sec. V-A (2)): softmax(q K^T/sqrt(D)) V over
@@ -273,8 +287,10 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
 int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
                            void *out_dev, float *lse_dev);
 
-/* Observers for parity checks.  All outputs are HOST pointers, caller-allocated;
- * each call synchronises the stream.  NULL outputs are skipped. */
+/* Observers for parity checks: the clustering state of Sec. V-B / Sec. VI (frame -> cluster
+ * map, representatives of Eq. 1 / Eq. 3, per-frame states) as the library holds it.  All
+ * outputs are HOST pointers, caller-allocated; each call synchronises the stream.  NULL
+ * outputs are skipped. */
 
 /* frame_to_cluster [L*Hkv][n_frames_ingested] (row stride = frames ingested);
  * -1 for frames still buffered before the initial clustering. */
@@ -315,11 +331,22 @@ int32_t mosaic_get_partition_selection(mosaic_ctx *ctx, int32_t layer, int32_t *
 int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32_t *n_ids,
                              double *scores, int32_t *tok_idx, int64_t tok_cap,
                              int32_t *n_tok);
+/* Host tier: directory of the GPU cluster cache (the "small working set" of Sec. V-A that stays
+ * on the GPU).  cached_pages: HOST pointer, [L*Hkv][C]; -1 = the cluster is not resident, else the
+ * number of its frames that are (fewer than its size if it grew since it was fetched).  Reads
+ * host-side bookkeeping only; does not synchronise.  EINVAL outside the host tier. */
+int32_t mosaic_get_cache_directory(mosaic_ctx *ctx, int32_t *cached_pages);
+
+/* Counters of the path: frames, K-means runs (Sec. V-B), cache hits / misses and bytes moved
+ * host-to-device (Sec. V-C, VII-B), prefetch accounting (Sec. VII-B), split counts of Alg. 1. */
 int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats);
 
 /* Kernel timing for benchmarks: when enabled, the split-KV attention kernel of
  * every mosaic_attend is launched with a HIP start/stop event pair that receives
- * the kernel's own begin and end timestamps on the context's stream.
+ * the kernel's own begin and end timestamps on the context's stream.  The event
+ * pairs come from a fixed pool that mosaic_profile_enable(on) creates (the query
+ * calls create none); when the pool is used up the next timed call waits for the
+ * stream and folds the times read so far into the running sum.
  * mosaic_profile_read synchronises and returns the summed kernel time and the
  * number of launches since the last read (host pointers), then clears them. */
 int32_t mosaic_profile_enable(mosaic_ctx *ctx, int32_t on);

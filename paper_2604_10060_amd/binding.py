@@ -28,7 +28,7 @@ EXPORTS = (
     "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_prefetch", "mosaic_attend",
     "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries", "mosaic_get_maintainer",
     "mosaic_decode_step", "mosaic_ingest_frame_visual", "mosaic_get_partitions", "mosaic_get_partition_selection",
-    "mosaic_get_selection", "mosaic_get_stats", "mosaic_profile_enable",
+    "mosaic_get_selection", "mosaic_get_stats", "mosaic_get_cache_directory", "mosaic_profile_enable",
     "mosaic_profile_read", "mosaic_calibration_copy", "mosaic_last_error",
 )
 
@@ -106,6 +106,7 @@ def load_library():
     L.mosaic_get_maintainer.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.mosaic_get_selection.argtypes = [vp, i32, vp, vp, vp, vp, C.c_int64, vp]
     L.mosaic_get_stats.argtypes = [vp, C.POINTER(Stats)]
+    L.mosaic_get_cache_directory.argtypes = [vp, vp]
     L.mosaic_profile_enable.argtypes = [vp, i32]
     L.mosaic_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     L.mosaic_calibration_copy.argtypes = [vp, vp, sz, vp]
@@ -308,6 +309,12 @@ class Mosaic:
         s = Stats()
         self._check(self._L.mosaic_get_stats(self._h, C.byref(s)))
         return s
+
+    def cache_directory(self) -> np.ndarray:
+        """Host tier: [U][C] frames of each cluster resident in the GPU cluster cache, -1 = not resident"""
+        d = np.empty((self.U, self.cfg.n_clusters), dtype=np.int32)
+        self._check(self._L.mosaic_get_cache_directory(self._h, d.ctypes.data))
+        return d
 
     def assignments(self) -> np.ndarray:
         nf = self.stats().frames_ingested

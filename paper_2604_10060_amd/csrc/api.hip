@@ -39,7 +39,7 @@ struct Layout {
     int nt_max;
     int c_init, split_iters, buf_max, W;   // maintainer (c_init = C, buf_max = 0 when off); warm-up frames
     // host tier geometry
-    int SF, slabs_per_unit, HP, cache_blocks, PU, SN, max_clusters;
+    int SF, slabs_per_unit, HP, PU, SN, max_clusters;
     size_t kpage, vpage;
 };
 
@@ -139,23 +139,16 @@ Layout make_layout(const mosaic_config &c) {
         L.max_clusters = std::max<int>((int)k, (int)(frac * (float)C));
         // default capacity: three times the average footprint of the clusters that may be resident
         const double share = std::max((double)frac, (double)k / (double)C);
-        long long cp = c.cache_pages_per_unit > 0
-                           ? c.cache_pages_per_unit
-                           : std::min<long long>((long long)(3.0 * share * (double)(F + C * (size_t)L.SF)) + (long long)k * L.SF,
-                                                 (long long)(F + C * (size_t)L.SF));
-        L.cache_blocks = (int)((cp + L.SF - 1) / L.SF);
-        L.PU = L.cache_blocks * L.SF;
+        const long long cp = c.cache_pages_per_unit > 0
+                                 ? std::min<long long>(c.cache_pages_per_unit, (long long)F)
+                                 : std::min<long long>((long long)(3.0 * share * (double)F) + (long long)k, (long long)F);
+        L.PU = (int)std::max<long long>(cp, 1);
         L.SN = std::max(W, 64);                 // staging ring: the warm-up plus one batch
     }
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-    if (host) {       // one pool of blocks [SF K pages][SF V pages] per unit
-        L.k_store = take(U * (size_t)L.PU * (L.kpage + L.vpage));
-        L.v_store = L.k_store + (size_t)L.SF * L.kpage;
-    } else {
-        L.k_store = take(U * (size_t)L.PU * L.kpage);
-        L.v_store = take(U * (size_t)L.PU * L.vpage);
-    }
+    L.k_store = take(U * (size_t)L.PU * L.kpage);     // (host tier: PU = page slots of the cluster cache)
+    L.v_store = take(U * (size_t)L.PU * L.vpage);
     L.stage_k = take(host ? (size_t)L.SN * U * L.kpage : 0);
     L.stage_v = take(host ? (size_t)L.SN * U * L.vpage : 0);
     L.dest = take(host ? U * (size_t)L.SN * 4 : 0);
@@ -205,7 +198,7 @@ Layout make_layout(const mosaic_config &c) {
     L.n_sel = take(U * 4);
     L.tok_scratch = take((size_t)c.n_kv_heads * F * T * 4);
     L.part_o = take((size_t)L.part_entries * kRowTile * D * 4);
-    L.part_ml = take((size_t)L.part_entries * 2 * kRowTile * 4);
+    L.part_ml = take((size_t)L.part_entries * kMlRows * kRowTile * 4);
     L.total = off;
     L.host_k = 0;
     L.host_v = host ? (size_t)L.SF * L.kpage : 0;     // inside the first slab: [SF K pages][SF V pages]
@@ -228,7 +221,7 @@ Layout make_layout(const mosaic_config &c) {
 }
 
 // KV splits for one attend call, bounded by the partial-buffer capacity.
-int choose_splits(const mosaic_ctx *ctx, int n_units, int Tq) {
+int choose_splits(const mosaic_ctx *ctx, int n_units, int Tq, long long part_entries) {
     const DeviceView &dv = ctx->dv;
     const long long NT = ((long long)Tq * dv.G + kRowTile - 1) / kRowTile;
     const bool mfma = ctx->impl == MOSAIC_ATTEND_MFMA;
@@ -254,7 +247,7 @@ int choose_splits(const mosaic_ctx *ctx, int n_units, int Tq) {
         s = std::min(s, std::max<long long>(1, est_chunks / 4));
     }
     s = std::min<long long>(s, kMaxSplits);
-    s = std::min(s, std::max<long long>(1, dv.part_entries / (n_units * NT)));
+    s = std::min(s, std::max<long long>(1, part_entries / (n_units * NT)));
     return (int)std::max<long long>(1, s);
 }
 
@@ -319,6 +312,7 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     ctx->sel_tq.assign(cfg->n_layers, 0);
     ctx->profile = false;
     ctx->ev_used = 0;
+    ctx->prof_ms = 0.0; ctx->prof_n = 0;
     memset(&ctx->stats, 0, sizeof ctx->stats);
     ctx->stats.attend_impl = L.impl;
     DeviceView &dv = ctx->dv;
@@ -362,17 +356,13 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.part_entries = L.part_entries;
     dv.tier = cfg->tier; dv.PU = L.PU; dv.SN = L.SN; dv.HP = L.HP;
     dv.kpage = L.kpage; dv.vpage = L.vpage;
+    dv.k_ustride = (size_t)L.PU * L.kpage;
+    dv.v_ustride = (size_t)L.PU * L.vpage;
+    dv.SFh = 1; dv.h_bstride = dv.h_ustride = 0;
     if (cfg->tier == MOSAIC_TIER_HOST) {
-        dv.SFd = L.SF;
-        dv.k_bstride = dv.v_bstride = (size_t)L.SF * (L.kpage + L.vpage);
-        dv.k_ustride = dv.v_ustride = (size_t)L.cache_blocks * dv.k_bstride;
-        dv.h_bstride = dv.k_bstride;
+        dv.SFh = L.SF;
+        dv.h_bstride = (size_t)L.SF * (L.kpage + L.vpage);
         dv.h_ustride = (size_t)L.slabs_per_unit * dv.h_bstride;
-    } else {
-        dv.SFd = 1;
-        dv.k_bstride = L.kpage; dv.k_ustride = (size_t)L.PU * L.kpage;
-        dv.v_bstride = L.vpage; dv.v_ustride = (size_t)L.PU * L.vpage;
-        dv.h_bstride = dv.h_ustride = 0;
     }
     dv.stage_k = base + L.stage_k; dv.stage_v = base + L.stage_v; dv.dest = (int *)(base + L.dest);
     dv.host_k = dv.host_v = nullptr;
@@ -410,8 +400,7 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
         HostTier *ht = new (std::nothrow) HostTier();
         if (!ht) return bail(MOSAIC_ENOMEM, "host allocation failed");
         ctx->host = ht;
-        ht->init(dv.U, dv.C, L.SF, L.slabs_per_unit, L.cache_blocks, L.max_clusters, L.kpage, L.vpage);
-        ht->last_ids.assign(dv.U, {});
+        ht->init(dv.U, dv.C, dv.F, L.SF, L.slabs_per_unit, L.PU, L.max_clusters, dv.k, L.kpage, L.vpage);
         // default-priority streams for selection and for the fetches
         // two internal streams only: selection (+ value fetches) and key fetches
         if ((e = hipStreamCreateWithFlags(&ht->sel_stream, hipStreamNonBlocking)) != hipSuccess ||
@@ -477,8 +466,7 @@ int32_t mosaic_reset(mosaic_ctx *ctx) {
         ht->hits = ht->misses = ht->evictions = ht->h2d_bytes = ht->h2d_copies = 0;
         ht->pf_calls = ht->pf_fetched = ht->pf_useful = 0;
         ht->busy_ms = 0.0;
-        for (hipEvent_t e : ht->busy_ev) (void)hipEventDestroy(e);
-        ht->busy_ev.clear();
+        ht->busy_used = 0;
         std::fill(ht->attend_recorded.begin(), ht->attend_recorded.end(), 0);
         std::fill(ht->ready_recorded.begin(), ht->ready_recorded.end(), 0);
     }
@@ -670,6 +658,21 @@ static int check_query_args(mosaic_ctx *ctx, int32_t layer, const void *q_dev, i
     return MOSAIC_OK;
 }
 
+// Host tier, profiling: add the elapsed times of the event pairs used so far to busy_ms (waits for
+// the copy stream) and make the pool available again.
+static hipError_t fold_busy_events(mosaic_ctx *ctx) {
+    HostTier *ht = ctx->host;
+    if (ht->busy_used == 0) return hipSuccess;
+    hipError_t e = hipStreamSynchronize(ht->copy_stream);
+    if (e != hipSuccess) return e;
+    for (size_t i = 0; i + 1 < ht->busy_used; i += 2) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ht->busy_ev[i], ht->busy_ev[i + 1]) == hipSuccess) ht->busy_ms += ms;
+    }
+    ht->busy_used = 0;
+    return hipSuccess;
+}
+
 // Host tier: selection on the selection stream, LRU + fetches on the copy stream.
 static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq, bool prefetch) {
     const DeviceView &dv = ctx->dv;
@@ -695,39 +698,56 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq, 
         (e = hipStreamWaitEvent(ht->copy_stream, ht->attend_done[layer], 0)) != hipSuccess)
         return fail_hip(ctx, e, "hipStreamWaitEvent");
     hipEvent_t b0 = nullptr, b1 = nullptr;
-    if (ctx->profile) {            // time the copy stream's work for this retrieve
-        if ((e = hipEventCreate(&b0)) != hipSuccess || (e = hipEventCreate(&b1)) != hipSuccess)
-            return fail_hip(ctx, e, "hipEventCreate");
-        ht->busy_ev.push_back(b0); ht->busy_ev.push_back(b1);
+    if (ctx->profile && !ht->busy_ev.empty()) {   // time the copy stream's work for this retrieve (pooled events)
+        if (ht->busy_used + 2 > ht->busy_ev.size() && (e = fold_busy_events(ctx)) != hipSuccess)
+            return fail_hip(ctx, e, "fetch timing");
+        b0 = ht->busy_ev[ht->busy_used]; b1 = ht->busy_ev[ht->busy_used + 1];
+        ht->busy_used += 2;
     }
-    std::vector<int> pages, moves;
+    // all or nothing: the cache directory is only touched once every unit's selection is known to fit
+    const auto n_take_of = [&](int i) {
+        return prefetch && ctx->cfg.prefetch_top_k > 0 ? std::min(nids[i], ctx->cfg.prefetch_top_k) : nids[i];
+    };
+    for (int i = 0; i < nu; ++i) {
+        if (ht->fits(u0 + i, ids + (size_t)i * k, n_take_of(i))) continue;
+        char b[256];
+        snprintf(b, sizeof b, "the selected clusters do not fit the GPU cluster cache: unit %d selects %d pages in %d "
+                 "clusters (cache: %d pages, at most %d clusters) (raise cache_pages_per_unit / cache_fraction)",
+                 u0 + i, ht->fail_sel_pages, n_take_of(i), dv.PU, ht->max_clusters);
+        if (b0) ht->busy_used -= 2;
+        ctx->sel_epoch[layer] = -1;          // whatever selection the layer had is no longer current
+        return fail(ctx, MOSAIC_ECAPACITY, b);
+    }
     int max_moves = 0;
     for (int i = 0; i < nu; ++i) {
         const int u = u0 + i;
-        pages.clear(); moves.clear();
-        const int n_take = prefetch && ctx->cfg.prefetch_top_k > 0 ? std::min(nids[i], ctx->cfg.prefetch_top_k) : nids[i];
-        const int rc = ht->fetch(u, ids + (size_t)i * k, n_take, moves, pages, prefetch);
-        if (rc != MOSAIC_OK) {
-            char b[256];
-            snprintf(b, sizeof b, "the selected clusters do not fit the GPU cluster cache: unit %d selects %d pages "
-                     "(cache %d pages), a cluster needs %d blocks with %d free and %d clusters resident, none evictable "
-                     "(raise cache_pages_per_unit / cache_fraction)", u, ht->fail_sel_pages, dv.PU, ht->fail_need,
-                     ht->fail_free, ht->fail_cached);
-            return fail(ctx, rc, b);
-        }
-        if (!prefetch) ht->last_ids[u].assign(ids + (size_t)i * k, ids + (size_t)i * k + nids[i]);
-        std::copy(moves.begin(), moves.end(), ctx->h_moves + (size_t)u * dv.F * 2);
-        ctx->h_nmoves[u] = (int)moves.size() / 2;
-        max_moves = std::max(max_moves, (int)moves.size() / 2);
+        int nm = 0, np = 0;
         int *hs = ctx->h_sel + (size_t)u * dv.F;
-        std::copy(pages.begin(), pages.end(), hs);
-        ctx->h_nsel[u] = (int)pages.size();
-        if (!pages.empty() &&
-            (e = hipMemcpyAsync(dv.sel_pages + (size_t)u * dv.F, hs, pages.size() * 4, hipMemcpyHostToDevice,
-                                ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "page list upload");
+        const int rc = ht->fetch(u, ids + (size_t)i * k, n_take_of(i), ctx->h_moves + (size_t)u * dv.F * 2, &nm,
+                                 hs, &np, prefetch);
+        if (rc != MOSAIC_OK) {               // (fits() above rules this out)
+            ctx->sel_epoch[layer] = -1;
+            return fail(ctx, rc, "cluster cache bookkeeping failed after the capacity check");
+        }
+        if (!prefetch) {
+            HostTier::Unit &un = ht->units[u];
+            un.n_last = nids[i];
+            std::copy(ids + (size_t)i * k, ids + (size_t)i * k + nids[i], un.last_ids.begin());
+        }
+        ctx->h_nmoves[u] = nm;
+        max_moves = std::max(max_moves, nm);
+        ctx->h_nsel[u] = np;
+        if (np > 0 && (e = hipMemcpyAsync(dv.sel_pages + (size_t)u * dv.F, hs, (size_t)np * 4, hipMemcpyHostToDevice,
+                                          ht->copy_stream)) != hipSuccess) {
+            ctx->sel_epoch[layer] = -1;
+            return fail_hip(ctx, e, "page list upload");
+        }
     }
     if ((e = hipMemcpyAsync(dv.n_sel + u0, ctx->h_nsel + u0, (size_t)nu * 4, hipMemcpyHostToDevice,
-                            ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "page count upload");
+                            ht->copy_stream)) != hipSuccess) {
+        ctx->sel_epoch[layer] = -1;
+        return fail_hip(ctx, e, "page count upload");
+    }
     // one kernel moves every missing page of this layer (timed when profiling is on)
     if (b0) (void)hipEventRecord(b0, ht->copy_stream);
     if ((e = launch_fetch(dv, u0, nu, max_moves, ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "fetch launch");
@@ -791,18 +811,56 @@ static bool kv_beyond_caches(const mosaic_ctx *ctx) {
     return stored > (768ll << 20);
 }
 
-int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
-                      void *out_dev, float *lse_dev) {
-    if (!ctx) return MOSAIC_EINVAL;
+// Profiling: sum the kernel times of the event pairs used so far into prof_ms (waits for the
+// stream) and make the pool available again.
+static hipError_t fold_profile_events(mosaic_ctx *ctx) {
+    if (ctx->ev_used == 0) return hipSuccess;
+    hipError_t e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return e;
+    for (size_t i = 0; i + 1 < ctx->ev_used; i += 2) {
+        float ms = 0.f;
+        if ((e = hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1])) != hipSuccess) return e;
+        ctx->prof_ms += ms;
+    }
+    ctx->prof_n += (long long)(ctx->ev_used / 2);
+    ctx->ev_used = 0;
+    return hipSuccess;
+}
+
+// An event pair from the pool for one attention launch while profiling is on (else both null).
+static hipError_t take_profile_events(mosaic_ctx *ctx, hipEvent_t *ev0, hipEvent_t *ev1) {
+    *ev0 = *ev1 = nullptr;
+    if (!ctx->profile || ctx->ev.empty()) return hipSuccess;
+    if (ctx->ev_used + 2 > ctx->ev.size()) {
+        const hipError_t e = fold_profile_events(ctx);
+        if (e != hipSuccess) return e;
+    }
+    *ev0 = ctx->ev[ctx->ev_used]; *ev1 = ctx->ev[ctx->ev_used + 1];
+    ctx->ev_used += 2;
+    return hipSuccess;
+}
+
+// Body of mosaic_attend: `dv` is the context's view with the partial
+// buffers the kernels are to use; `timed`: attach the
+// profiling events when profiling is on.
+static int attend_with(mosaic_ctx *ctx, const DeviceView &dv, int32_t layer, const void *q_dev, int32_t n_q_tokens,
+                       void *out_dev, float *lse_dev, bool timed) {
     int u0, nu;
     int rc = check_query_args(ctx, layer, q_dev, n_q_tokens, &u0, &nu);
     if (rc != MOSAIC_OK) return rc;
     if (!out_dev) return fail(ctx, MOSAIC_EINVAL, "out_dev is NULL");
-    const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? ctx->dv.L : layer + 1;
+    const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? dv.L : layer + 1;
     for (int l = l0; l < l1; ++l)
         if (ctx->sel_epoch[l] != ctx->epoch)
             return fail(ctx, MOSAIC_ENOTREADY, "no current selection for this layer: call mosaic_retrieve after the last ingest");
-    const int S = choose_splits(ctx, nu, n_q_tokens);
+    const long long NT = ((long long)n_q_tokens * dv.G + kRowTile - 1) / kRowTile;
+    if ((long long)nu * NT > dv.part_entries) {
+        char b[200];
+        snprintf(b, sizeof b, "attention partials of this call need %lld entries (units x row tiles), the buffer holds %lld",
+                 (long long)nu * NT, dv.part_entries);
+        return fail(ctx, MOSAIC_ECAPACITY, b);
+    }
+    const int S = choose_splits(ctx, nu, n_q_tokens, dv.part_entries);
     hipError_t e;
     if (ctx->host) {
         if (layer < 0) return fail(ctx, MOSAIC_EINVAL, "the host tier attends one layer per call");
@@ -810,31 +868,20 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t
             return fail_hip(ctx, e, "hipStreamWaitEvent");
     }
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    if (ctx->profile) {
-        if (ctx->ev_used + 2 > ctx->ev.size()) {
-            for (int i = 0; i < 2; ++i) {
-                hipEvent_t x;
-                e = hipEventCreate(&x);
-                if (e != hipSuccess) return fail_hip(ctx, e, "hipEventCreate");
-                ctx->ev.push_back(x);
-            }
-        }
-        ev0 = ctx->ev[ctx->ev_used]; ev1 = ctx->ev[ctx->ev_used + 1];
-        ctx->ev_used += 2;
-    }
-    if (ctx->dv.aug_reps && ctx->rv_epoch != ctx->epoch) {
+    if (timed && (e = take_profile_events(ctx, &ev0, &ev1)) != hipSuccess) return fail_hip(ctx, e, "kernel timing");
+    if (dv.aug_reps && ctx->rv_epoch != ctx->epoch) {
         // global representatives (Sec. V-C): the clustering changed since the value sums were formed.
         // Their attention partial is computed by extra workgroups of the attention launch below.
         // (Its own kernel cost ~8 us per decode step; its own stream, with fork/join events, more.)
-        if ((e = launch_value_reps(ctx->dv, (int)ctx->n_frames, ctx->stream)) != hipSuccess)
+        if ((e = launch_value_reps(dv, (int)ctx->n_frames, ctx->stream)) != hipSuccess)
             return fail_hip(ctx, e, "value representatives launch");
         ctx->rv_epoch = ctx->epoch;
     }
     e = ctx->impl == MOSAIC_ATTEND_MFMA
-            ? launch_attend_mfma(ctx->dv, u0, nu, q_dev, n_q_tokens, S, kv_beyond_caches(ctx), ctx->stream, ev0, ev1)
-            : launch_attend_valu(ctx->dv, u0, nu, q_dev, n_q_tokens, S, ctx->stream, ev0, ev1);
+            ? launch_attend_mfma(dv, u0, nu, q_dev, n_q_tokens, S, kv_beyond_caches(ctx), ctx->stream, ev0, ev1)
+            : launch_attend_valu(dv, u0, nu, q_dev, n_q_tokens, S, ctx->stream, ev0, ev1);
     if (e != hipSuccess) return fail_hip(ctx, e, "attend launch");
-    e = launch_attend_combine(ctx->dv, u0, nu, n_q_tokens, S, out_dev, lse_dev, ctx->stream);
+    e = launch_attend_combine(dv, u0, nu, n_q_tokens, S, out_dev, lse_dev, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "combine launch");
     if (ctx->host) {
         if ((e = hipEventRecord(ctx->host->attend_done[layer], ctx->stream)) != hipSuccess)
@@ -844,6 +891,12 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t
     ctx->stats.attend_calls += 1;
     ctx->stats.last_n_splits = S;
     return MOSAIC_OK;
+}
+
+int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
+                      void *out_dev, float *lse_dev) {
+    if (!ctx) return MOSAIC_EINVAL;
+    return attend_with(ctx, ctx->dv, layer, q_dev, n_q_tokens, out_dev, lse_dev, true);
 }
 
 int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
@@ -861,7 +914,7 @@ int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, in
                        dv.C <= 256 && est_bytes <= (48ll << 20);
     int S = 0;
     if (fused) {
-        S = choose_splits(ctx, dv.Hkv, n_q_tokens);
+        S = choose_splits(ctx, dv.Hkv, n_q_tokens, dv.part_entries);
         // a workgroup lists the pages of its chunk range in LDS (2048 entries)
         while (S < kMaxSplits && ctx->n_frames / S + 2 > 2048) ++S;
     }
@@ -878,18 +931,7 @@ int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, in
     if (ctx->n_frames < ctx->W) return fail(ctx, MOSAIC_ENOTREADY, "initial clustering has not run yet (fewer than warmup_frames frames ingested)");
     hipError_t e;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    if (ctx->profile) {
-        if (ctx->ev_used + 2 > ctx->ev.size()) {
-            for (int i = 0; i < 2; ++i) {
-                hipEvent_t x;
-                e = hipEventCreate(&x);
-                if (e != hipSuccess) return fail_hip(ctx, e, "hipEventCreate");
-                ctx->ev.push_back(x);
-            }
-        }
-        ev0 = ctx->ev[ctx->ev_used]; ev1 = ctx->ev[ctx->ev_used + 1];
-        ctx->ev_used += 2;
-    }
+    if ((e = take_profile_events(ctx, &ev0, &ev1)) != hipSuccess) return fail_hip(ctx, e, "kernel timing");
     e = launch_decode_fused(dv, u0, nu, q_dev, n_q_tokens, S, (int)ctx->n_frames, ctx->cfg.score_mode,
                             kv_beyond_caches(ctx), ctx->stream, ev0, ev1);
     if (e != hipSuccess) return fail_hip(ctx, e, "fused decode launch");
@@ -1039,13 +1081,13 @@ int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32
         for (int h = 0; h < H; ++h) {
             const HostTier::Unit &un = ht->units[u0 + h];
             int64_t m = 0;
-            for (int c : ht->last_ids[u0 + h]) m += (int64_t)un.frames[c].size() * dv.T;
+            for (int i = 0; i < un.n_last; ++i) m += (int64_t)un.n[un.last_ids[i]] * dv.T;
             if (n_tok) n_tok[h] = (int32_t)m;
             if (!tok_idx) continue;
             if (m > tok_cap) return fail(ctx, MOSAIC_ECAPACITY, "tok_cap too small for the retrieved token list");
             int32_t *o = tok_idx + (size_t)h * tok_cap;
-            for (int c : ht->last_ids[u0 + h])
-                for (int f : un.frames[c])
+            for (int i = 0; i < un.n_last; ++i)
+                for (int f = un.head_f[un.last_ids[i]]; f >= 0; f = un.next_f[f])
                     for (int t = 0; t < dv.T; ++t) *o++ = f * dv.T + t;
         }
         return MOSAIC_OK;
@@ -1070,20 +1112,23 @@ int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32
     return MOSAIC_OK;
 }
 
+int32_t mosaic_get_cache_directory(mosaic_ctx *ctx, int32_t *cached_pages) {
+    if (!ctx) return MOSAIC_EINVAL;
+    if (!ctx->host) return fail(ctx, MOSAIC_EINVAL, "the cluster cache exists in the host tier only");
+    if (!cached_pages) return fail(ctx, MOSAIC_EINVAL, "cached_pages is NULL");
+    const DeviceView &dv = ctx->dv;
+    for (int u = 0; u < dv.U; ++u) {
+        const HostTier::Unit &un = ctx->host->units[u];
+        for (int c = 0; c < dv.C; ++c) cached_pages[(size_t)u * dv.C + c] = un.present[c] ? un.cached[c] : -1;
+    }
+    return MOSAIC_OK;
+}
+
 int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats) {
     if (!ctx || !stats) return MOSAIC_EINVAL;
     if (HostTier *ht = ctx->host) {
-        if (!ht->busy_ev.empty()) {
-            hipError_t e = hipStreamSynchronize(ht->copy_stream);
-            if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
-            for (size_t i = 0; i + 1 < ht->busy_ev.size(); i += 2) {
-                float ms = 0.f;
-                if (hipEventElapsedTime(&ms, ht->busy_ev[i], ht->busy_ev[i + 1]) == hipSuccess) ht->busy_ms += ms;
-                (void)hipEventDestroy(ht->busy_ev[i]);
-                (void)hipEventDestroy(ht->busy_ev[i + 1]);
-            }
-            ht->busy_ev.clear();
-        }
+        hipError_t e = fold_busy_events(ctx);
+        if (e != hipSuccess) return fail_hip(ctx, e, "fetch timing");
         ctx->stats.cache_hits = ht->hits; ctx->stats.cache_misses = ht->misses;
         ctx->stats.h2d_bytes = ht->h2d_bytes; ctx->stats.h2d_copies = ht->h2d_copies;
         ctx->stats.h2d_busy_ms = ht->busy_ms;
@@ -1105,8 +1150,25 @@ int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats) {
     return MOSAIC_OK;
 }
 
+// Event pools of the profiling mode: created here, never on the query path.
+constexpr size_t kProfileEvents = 2 * 2048;
+
 int32_t mosaic_profile_enable(mosaic_ctx *ctx, int32_t on) {
     if (!ctx) return MOSAIC_EINVAL;
+    if (on) {
+        hipError_t e;
+        while (ctx->ev.size() < kProfileEvents) {
+            hipEvent_t x;
+            if ((e = hipEventCreate(&x)) != hipSuccess) return fail_hip(ctx, e, "hipEventCreate");
+            ctx->ev.push_back(x);
+        }
+        if (HostTier *ht = ctx->host)
+            while (ht->busy_ev.size() < kProfileEvents) {
+                hipEvent_t x;
+                if ((e = hipEventCreate(&x)) != hipSuccess) return fail_hip(ctx, e, "hipEventCreate");
+                ht->busy_ev.push_back(x);
+            }
+    }
     ctx->profile = on != 0;
     return MOSAIC_OK;
 }
@@ -1115,16 +1177,11 @@ int32_t mosaic_profile_read(mosaic_ctx *ctx, double *attend_kernel_ms, int64_t *
     if (!ctx) return MOSAIC_EINVAL;
     int rc = sync(ctx);
     if (rc != MOSAIC_OK) return rc;
-    double total = 0.0;
-    for (size_t i = 0; i + 1 < ctx->ev_used; i += 2) {
-        float ms = 0.f;
-        hipError_t e = hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]);
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventElapsedTime");
-        total += ms;
-    }
-    if (attend_kernel_ms) *attend_kernel_ms = total;
-    if (launches) *launches = (int64_t)(ctx->ev_used / 2);
-    ctx->ev_used = 0;
+    const hipError_t e = fold_profile_events(ctx);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventElapsedTime");
+    if (attend_kernel_ms) *attend_kernel_ms = ctx->prof_ms;
+    if (launches) *launches = (int64_t)ctx->prof_n;
+    ctx->prof_ms = 0.0; ctx->prof_n = 0;
     return MOSAIC_OK;
 }
 

@@ -143,9 +143,10 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, i
     const size_t entry = (size_t)slot.base * NT + (size_t)tile * n_splits + split;
 #pragma unroll
     for (int i = 0; i < DPT; ++i) dv.part_o[(entry * kRowTile + row) * D + tl + 16 * i] = acc[i];
-    if (tl == 0) {
-        dv.part_ml[entry * 2 * kRowTile + row] = m;
-        dv.part_ml[entry * 2 * kRowTile + kRowTile + row] = l;
+    if (tl == 0) {     // fp32 weights throughout: the two normalisers coincide
+        dv.part_ml[entry * kMlRows * kRowTile + row] = m;
+        dv.part_ml[entry * kMlRows * kRowTile + kRowTile + row] = l;
+        dv.part_ml[entry * kMlRows * kRowTile + 2 * kRowTile + row] = l;
     }
 }
 
@@ -164,8 +165,8 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, i
 template <int D, int MAXS, int RMAX>
 __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t e0, int n_splits, int rows, int dg,
                                                    float (*w_sh)[kRowTile], float (*pm)[kRowTile],
-                                                   float (*pl)[kRowTile], float *M_sh, float *L_sh,
-                                                   float (&acc)[kRowTile]) {
+                                                   float (*pl)[kRowTile], float (*px)[kRowTile], float *M_sh,
+                                                   float *L_sh, float *X_sh, float (&acc)[kRowTile]) {
     constexpr int SPP = 64 * (kRowTile / RMAX);  // splits per pass (128 partial values per thread) ...
     constexpr int NB = (MAXS < SPP ? MAXS : SPP) / 8;   // ... in batches of 8 (fewer when the unit cannot have that many)
     const int tid = threadIdx.x, sg = tid / 32, col = tid % 32;
@@ -182,15 +183,16 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
     load_pass(0);
     {   // per-row maximum and normaliser over the splits
         const int row = tid % 16, part = tid / 16;
-        float mr[MAXS / 16], lr[MAXS / 16];
+        float mr[MAXS / 16], lr[MAXS / 16], xr[MAXS / 16];
         float mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < MAXS / 16; ++i) {
             const int s = part + 16 * i;
-            mr[i] = -INFINITY; lr[i] = 0.f;
+            mr[i] = -INFINITY; lr[i] = 0.f; xr[i] = 0.f;
             if (s < n_splits) {
-                mr[i] = dv.part_ml[(e0 + s) * 2 * kRowTile + row];
-                lr[i] = dv.part_ml[(e0 + s) * 2 * kRowTile + kRowTile + row];
+                mr[i] = dv.part_ml[(e0 + s) * kMlRows * kRowTile + row];
+                lr[i] = dv.part_ml[(e0 + s) * kMlRows * kRowTile + kRowTile + row];
+                xr[i] = dv.part_ml[(e0 + s) * kMlRows * kRowTile + 2 * kRowTile + row];
             }
             mx = fmaxf(mx, mr[i]);
         }
@@ -199,7 +201,7 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
         float M = -INFINITY;
 #pragma unroll
         for (int p = 0; p < 16; ++p) M = fmaxf(M, pm[p][row]);
-        float ls = 0.f;
+        float ls = 0.f, xs = 0.f;
 #pragma unroll
         for (int i = 0; i < MAXS / 16; ++i) {
             const int s = part + 16 * i;
@@ -207,16 +209,19 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
                 const float w = M > -INFINITY ? exp2f(mr[i] - M) : 0.f;
                 w_sh[s][row] = w;
                 ls += w * lr[i];
+                xs += w * xr[i];
             }
         }
         pl[part][row] = ls;
+        px[part][row] = xs;
         __syncthreads();
         if (part == 0) {
-            float Ls = 0.f;
+            float Ls = 0.f, Xs = 0.f;
 #pragma unroll
-            for (int p = 0; p < 16; ++p) Ls += pl[p][row];
+            for (int p = 0; p < 16; ++p) { Ls += pl[p][row]; Xs += px[p][row]; }
             M_sh[row] = M;
             L_sh[row] = Ls;
+            X_sh[row] = Xs;
         }
     }
 #pragma unroll
@@ -252,20 +257,20 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
     const int n_splits = slot.S;                 // 0 if the unit retrieved nothing
     const size_t e0 = (size_t)slot.base * NT + (size_t)tile * n_splits;
     __shared__ float w_sh[kMaxUnitSplits][kRowTile];
-    __shared__ float pm[16][kRowTile], pl[16][kRowTile];
-    __shared__ float M_sh[kRowTile], L_sh[kRowTile];
+    __shared__ float pm[16][kRowTile], pl[16][kRowTile], px[16][kRowTile];
+    __shared__ float M_sh[kRowTile], L_sh[kRowTile], X_sh[kRowTile];
     __shared__ float red[8][kRowTile][33];
     const int sg = tid / 32, col = tid % 32;
     float acc[kRowTile];
     if (rows <= 8) {             // block-uniform choices
-        if (n_splits <= 16) combine_accumulate<D, 16, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
-        else if (n_splits <= 32) combine_accumulate<D, 32, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
-        else if (n_splits <= 64) combine_accumulate<D, 64, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
-        else if (n_splits <= 128) combine_accumulate<D, 128, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
-        else combine_accumulate<D, kMaxUnitSplits, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+        if (n_splits <= 16) combine_accumulate<D, 16, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+        else if (n_splits <= 32) combine_accumulate<D, 32, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+        else if (n_splits <= 64) combine_accumulate<D, 64, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+        else if (n_splits <= 128) combine_accumulate<D, 128, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+        else combine_accumulate<D, kMaxUnitSplits, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
     } else {
-        if (n_splits <= 64) combine_accumulate<D, 64, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
-        else combine_accumulate<D, kMaxUnitSplits, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, M_sh, L_sh, acc);
+        if (n_splits <= 64) combine_accumulate<D, 64, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+        else combine_accumulate<D, kMaxUnitSplits, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
     }
 #pragma unroll
     for (int r = 0; r < kRowTile; ++r) red[sg][r][col] = acc[r];
@@ -277,7 +282,9 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
         float o = 0.f;
 #pragma unroll
         for (int q = 0; q < 8; ++q) o += red[q][r][col];
-        float Lr = L_sh[r], Mr = M_sh[r];
+        // Lr: normaliser of the output (the weights the value contraction used, bf16-rounded in the
+        // MFMA kernels); Xr: the same sum over the unrounded fp32 weights, for the log-sum-exp
+        float Lr = L_sh[r], Xr = X_sh[r], Mr = M_sh[r];
         if (dv.aug_reps) {                            // one more partial: the representatives' part
             const size_t ae = (size_t)u * dv.nt_max + tile;
             const float ma = dv.aug_ml[ae * 2 * kRowTile + r], la = dv.aug_ml[ae * 2 * kRowTile + kRowTile + r];
@@ -286,13 +293,14 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
             const float wa = Mr > -INFINITY ? exp2f(Mr - Mn) : 0.f, wb = ma > -INFINITY ? exp2f(ma - Mn) : 0.f;
             o = o * wa + oa * wb;
             Lr = Lr * wa + la * wb;
+            Xr = Xr * wa + la * wb;                   // (the representatives' weights are fp32)
             Mr = Mn;
         }
         const int gr = tile * kRowTile + r, t = gr / G, g = gr % G;
         const size_t orow = ((size_t)lc * Tq + t) * Hq + (size_t)h * G + g;
         store_out<E>(out + orow * D + dg * 32 + col, Lr > 0.f ? o / Lr : 0.f);
         if (dg == 0 && col == 0 && lse != nullptr)
-            lse[orow] = Lr > 0.f ? (Mr + log2f(Lr)) * 0.6931471805599453f : -INFINITY;
+            lse[orow] = Xr > 0.f ? (Mr + log2f(Xr)) * 0.6931471805599453f : -INFINITY;
     }
 }
 

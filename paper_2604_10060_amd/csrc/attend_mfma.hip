@@ -16,6 +16,8 @@
 //          t0 + 8g + j, j = 0..7 -- exactly the B operand P^T[8g+j][n] of
 // Output:  A = V^T (row slot n = channel 16*db + n, k-slots = tokens t0 + 8g + j),
 //          D = O^T[16*db + 4g + i][n].
+#include <mutex>
+
 #include "mosaic_internal.h"
 #include "attend_reps_device.h"
 
@@ -70,11 +72,14 @@ constexpr float kLazy = 8.0f;
 // adds the four lane groups at the end) or an f32x4 accumulator fed by one more MFMA
 // whose A operand is all ones: every element of it is then the row's full sum over
 // the 32 tokens, and the 8 adds per tile leave the vector ALU.
+// lx is the per-lane sum of the UNROUNDED fp32 weights (this lane's 8 tokens of a row): the
+// output divides by l, whose weights are the bf16-rounded ones the PV contraction used, while the
+// log-sum-exp the caller gets is formed from lx, so it carries fp32 rounding only.
 template <int D, int R, typename LT>
 __device__ __forceinline__ void chunk_step_multi(const bf16x8 (&kf)[2 * (D / 32)], const bf16x8 (&vf)[D / 16],
                                                  const bf16x8 (&qf)[R][D / 32], int n_valid, int g,
                                                  float sl2, f32x4 (&acc)[R][D / 16], float (&m)[R],
-                                                 LT (&l)[R]) {
+                                                 LT (&l)[R], float (&lx)[R]) {
     constexpr int KK = D / 32, DB = D / 16;
     constexpr bool kSumByMfma = sizeof(LT) == sizeof(f32x4);
     f32x4 s[R][2];
@@ -106,18 +111,22 @@ __device__ __forceinline__ void chunk_step_multi(const bf16x8 (&kf)[2 * (D / 32)
             const float mnew = fmaxf(m[r], cm);
             const float alpha = __builtin_amdgcn_exp2f(m[r] - mnew);
             l[r] = l[r] * alpha;
+            lx[r] = lx[r] * alpha;
             m[r] = mnew;
 #pragma unroll
             for (int db = 0; db < DB; ++db) acc[r][db] = acc[r][db] * alpha;
         }
         const float nm = -m[r];
         unsigned int pw[4];
+        float xs = 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r][(2 * j) / 4][(2 * j) % 4], sl2, nm));
             const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r][(2 * j + 1) / 4][(2 * j + 1) % 4], sl2, nm));
             pw[j] = pack_bf16(p0, p1);
+            xs += p0 + p1;
         }
+        lx[r] += xs;
         pf[r] = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
         if constexpr (!kSumByMfma) {               // the normaliser uses the rounded weights
             float psum = 0.f;
@@ -142,12 +151,13 @@ __device__ __forceinline__ void chunk_step_multi(const bf16x8 (&kf)[2 * (D / 32)
 template <int D>
 __device__ __forceinline__ void chunk_step(const bf16x8 (&kf)[2 * (D / 32)], const bf16x8 (&vf)[D / 16],
                                            const bf16x8 (&qf)[D / 32], int n_valid, int g, float sl2,
-                                           f32x4 (&acc)[D / 16], float &m, float &l) {
+                                           f32x4 (&acc)[D / 16], float &m, float &l, float &lx) {
     const bf16x8 (&q1)[1][D / 32] = reinterpret_cast<const bf16x8 (&)[1][D / 32]>(qf);
     f32x4 (&a1)[1][D / 16] = reinterpret_cast<f32x4 (&)[1][D / 16]>(acc);
     float (&m1)[1] = reinterpret_cast<float (&)[1]>(m);
     float (&l1)[1] = reinterpret_cast<float (&)[1]>(l);
-    chunk_step_multi<D, 1, float>(kf, vf, q1, n_valid, g, sl2, a1, m1, l1);
+    float (&x1)[1] = reinterpret_cast<float (&)[1]>(lx);
+    chunk_step_multi<D, 1, float>(kf, vf, q1, n_valid, g, sl2, a1, m1, l1, x1);
 }
 
 // Issue the 16-byte operand loads of one chunk.  Tokens beyond the page's T are
@@ -190,29 +200,32 @@ __device__ __forceinline__ void load_q(const DeviceView &dv, const unsigned shor
 // workgroup's partial at `entry` (shared by the decode kernels).  All threads call it.
 template <int D>
 __device__ __forceinline__ void merge_waves_store(const DeviceView &dv, const f32x4 (&acc)[D / 16], float m, float l,
-                                                  int R, size_t entry) {
+                                                  float lx, int R, size_t entry) {
     constexpr int DB = D / 16;
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
+    lx += __shfl_xor(lx, 16, 64);
+    lx += __shfl_xor(lx, 32, 64);
     __shared__ float o_sh[4][D][kRowTile + 1];
-    __shared__ float m_sh[4][kRowTile], l_sh[4][kRowTile];
+    __shared__ float m_sh[4][kRowTile], l_sh[4][kRowTile], x_sh[4][kRowTile];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 4; ++i) o_sh[wave][16 * db + 4 * g + i][n] = acc[db][i];
-    if (g == 0) { m_sh[wave][n] = m; l_sh[wave][n] = l; }
+    if (g == 0) { m_sh[wave][n] = m; l_sh[wave][n] = l; x_sh[wave][n] = lx; }
     __syncthreads();
     const int row = tid / 16, dl = tid % 16;
     if (row >= R) return;
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < 4; ++w) M = fmaxf(M, m_sh[w][row]);
-    float wgt[4], Lsum = 0.f;
+    float wgt[4], Lsum = 0.f, Xsum = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
         wgt[w] = M > -INFINITY ? __builtin_amdgcn_exp2f(m_sh[w][row] - M) : 0.f;
         Lsum += wgt[w] * l_sh[w][row];
+        Xsum += wgt[w] * x_sh[w][row];
     }
     float *po = dv.part_o + (entry * kRowTile + row) * D;
 #pragma unroll
@@ -223,8 +236,9 @@ __device__ __forceinline__ void merge_waves_store(const DeviceView &dv, const f3
         po[d] = o;
     }
     if (dl == 0) {
-        dv.part_ml[entry * 2 * kRowTile + row] = M;
-        dv.part_ml[entry * 2 * kRowTile + kRowTile + row] = Lsum;
+        dv.part_ml[entry * kMlRows * kRowTile + row] = M;
+        dv.part_ml[entry * kMlRows * kRowTile + kRowTile + row] = Lsum;
+        dv.part_ml[entry * kMlRows * kRowTile + 2 * kRowTile + row] = Xsum;
     }
 }
 
@@ -264,7 +278,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
     f32x4 acc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, l = 0.f;
+    float m = -INFINITY, l = 0.f, lx = 0.f;
 
     const int NC = __builtin_amdgcn_readfirstlane(dv.n_sel[u]) * cpp;
     const int n_my = __builtin_amdgcn_readfirstlane(first < NC ? (NC - first + stride - 1) / stride : 0);
@@ -287,15 +301,14 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
     };
     auto issue = [&](int page, int cc_in, bf16x8 (&kf)[2 * KK], bf16x8 (&vf)[DB], int &cc) {
         cc = cc_in;
-        const int b = dv.SFd == 1 ? page : page / dv.SFd, r = dv.SFd == 1 ? 0 : page - b * dv.SFd;
-        const char *kp = dv.k_store + (size_t)u * dv.k_ustride + (size_t)b * dv.k_bstride + (size_t)r * dv.kpage;
-        const char *vp = dv.v_store + (size_t)u * dv.v_ustride + (size_t)b * dv.v_bstride + (size_t)r * dv.vpage;
+        const char *kp = k_page(dv, u, page);
+        const char *vp = v_page(dv, u, page);
         issue_chunk<D, STREAM>(reinterpret_cast<const unsigned short *>(kp),
                                reinterpret_cast<const unsigned short *>(vp) + (size_t)cc * D * 32,
                                cc * kChunk, T, g, n, kf, vf);
     };
     auto step = [&](const bf16x8 (&kf)[2 * KK], const bf16x8 (&vf)[DB], int cc) {
-        chunk_step<D>(kf, vf, qf, min(kChunk, T - cc * kChunk), g, sl2, acc, m, l);
+        chunk_step<D>(kf, vf, qf, min(kChunk, T - cc * kChunk), g, sl2, acc, m, l, lx);
     };
 
     if (n_my > 0) {
@@ -324,7 +337,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
         }
     }
     // merge the four waves, write one partial per workgroup
-    merge_waves_store<D>(dv, acc, m, l, R, (size_t)slot.base + split);        // one row tile
+    merge_waves_store<D>(dv, acc, m, l, lx, R, (size_t)slot.base + split);        // one row tile
 }
 
 // ---------------------------------------------------------------------------
@@ -542,7 +555,7 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
     f32x4 acc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, l = 0.f;
+    float m = -INFINITY, l = 0.f, lx = 0.f;
     const int first = c0 + wave;
     const int n_my = first < c1 ? (c1 - first + 3) / 4 : 0;
     bf16x8 kA[2 * KK], vA[DB], kB[2 * KK], vB[DB];
@@ -551,14 +564,14 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
         const int pi = c / cpp;
         cc = c - pi * cpp;
         const int page = list_sh[pi - p_lo];
-        const char *kp = dv.k_store + (size_t)u * dv.k_ustride + (size_t)page * dv.k_bstride;
-        const char *vp = dv.v_store + (size_t)u * dv.v_ustride + (size_t)page * dv.v_bstride;
+        const char *kp = k_page(dv, u, page);
+        const char *vp = v_page(dv, u, page);
         issue_chunk<D, STREAM>(reinterpret_cast<const unsigned short *>(kp),
                                reinterpret_cast<const unsigned short *>(vp) + (size_t)cc * D * 32,
                                cc * kChunk, T, g, n, kf, vf);
     };
     auto step = [&](const bf16x8 (&kf)[2 * KK], const bf16x8 (&vf)[DB], int cc) {
-        chunk_step<D>(kf, vf, qf, min(kChunk, T - cc * kChunk), g, sl2, acc, m, l);
+        chunk_step<D>(kf, vf, qf, min(kChunk, T - cc * kChunk), g, sl2, acc, m, l, lx);
     };
     if (n_my > 0) {
         issue(first, kA, vA, ccA);
@@ -580,7 +593,7 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
             step(kA, vA, ccA);
         }
     }
-    merge_waves_store<D>(dv, acc, m, l, R, (size_t)uc * S + split);
+    merge_waves_store<D>(dv, acc, m, l, lx, R, (size_t)uc * S + split);
 }
 
 // ---------------------------------------------------------------------------
@@ -648,10 +661,10 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
     const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 
     f32x4 acc[RTW][DB], l[RTW];                    // l: row sums, kept by an all-ones MFMA
-    float m[RTW];
+    float m[RTW], lx[RTW];
 #pragma unroll
     for (int r = 0; r < RTW; ++r) {
-        m[r] = -INFINITY; l[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m[r] = -INFINITY; l[r] = f32x4{0.f, 0.f, 0.f, 0.f}; lx[r] = 0.f;
 #pragma unroll
         for (int db = 0; db < DB; ++db) acc[r][db] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -666,9 +679,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
     int nf = c0, f_pi = c0 / cpp, f_cc = c0 - f_pi * cpp;
     const unsigned short *f_kp = nullptr, *f_vp = nullptr;
     auto set_page = [&](int page) {
-        const int b = dv.SFd == 1 ? page : page / dv.SFd, r = dv.SFd == 1 ? 0 : page - b * dv.SFd;
-        f_kp = reinterpret_cast<const unsigned short *>(kbase + (size_t)b * dv.k_bstride + (size_t)r * dv.kpage);
-        f_vp = reinterpret_cast<const unsigned short *>(vbase + (size_t)b * dv.v_bstride + (size_t)r * dv.vpage);
+        f_kp = reinterpret_cast<const unsigned short *>(kbase + (size_t)page * dv.kpage);
+        f_vp = reinterpret_cast<const unsigned short *>(vbase + (size_t)page * dv.vpage);
     };
     int pg_next = 0;
     if (c0 < c1) {
@@ -735,7 +747,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
                 bf16x8, *reinterpret_cast<const uint4 *>(&v_lds[buf][16 * db + n][8 * g]));
         const int n_valid = min(kChunk, T - c_cc * kChunk);
         c_cc = c_cc + 1 == cpp ? 0 : c_cc + 1;
-        chunk_step_multi<D, RTW, f32x4>(kf, vf, qf, n_valid, g, sl2, acc, m, l);
+        chunk_step_multi<D, RTW, f32x4>(kf, vf, qf, n_valid, g, sl2, acc, m, l, lx);
     };
 
     // Pipeline, two chunks (64 tokens) per barrier: the pair (c, c+1) is computed from LDS
@@ -785,6 +797,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
         const int tile = tile0 + r;
         if (tile >= NT) break;
         const float lr = l[r][0];
+        float xr = lx[r];                              // this lane's 8 tokens per chunk: add the four lane groups
+        xr += __shfl_xor(xr, 16, 64);
+        xr += __shfl_xor(xr, 32, 64);
         const size_t entry = (size_t)slot.base * NT + (size_t)tile * n_splits + split;
         float *po = dv.part_o + (entry * kRowTile + n) * D;
 #pragma unroll
@@ -792,8 +807,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv
             *reinterpret_cast<float4 *>(po + 16 * db + 4 * g) =
                 make_float4(acc[r][db][0], acc[r][db][1], acc[r][db][2], acc[r][db][3]);
         if (g == 0) {
-            dv.part_ml[entry * 2 * kRowTile + n] = m[r];
-            dv.part_ml[entry * 2 * kRowTile + kRowTile + n] = lr;
+            dv.part_ml[entry * kMlRows * kRowTile + n] = m[r];
+            dv.part_ml[entry * kMlRows * kRowTile + kRowTile + n] = lr;
+            dv.part_ml[entry * kMlRows * kRowTile + 2 * kRowTile + n] = xr;
         }
     }
 }
@@ -834,14 +850,13 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
     } else {
         // dynamic LDS of the multi-token kernel: 4 K tiles [32][D + 8] and 4 V tiles [D][40] of bf16
         const size_t lds = (size_t)(4 * kChunk * (dv.D + 8) + 4 * dv.D * (kChunk + 8)) * 2;
-        static bool attr_set = false;
-        if (!attr_set) {
+        static std::once_flag attr_once;          // process-wide, but set exactly once whichever handle comes first
+        std::call_once(attr_once, [] {
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<64, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<64, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<128, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<128, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-            attr_set = true;
-        }
+        });
         const int n_groups = n_units * n_splits, rb = (NT + 4 * kPrefillTiles - 1) / (4 * kPrefillTiles);
         const int gb = (n_groups + 7) / 8 * 8 * rb;
         const dim3 grid(gb + (dv.aug_reps ? n_units * NT : 0));

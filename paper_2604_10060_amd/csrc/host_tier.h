@@ -1,5 +1,7 @@
-// Host-side bookkeeping of the pinned-host tier: slab chains per cluster and the
-// per-unit GPU cluster cache (LRU at cluster granularity).  See host_tier.hip.
+// Host-side bookkeeping of the pinned-host tier: where every frame's page lives in pinned
+// memory (cluster-contiguous slab chains), which frames are in the GPU cluster cache, and
+// the least-recently-used replacement at cluster granularity.  See host_tier.hip.
+// Every array is sized when the context is created: nothing here allocates afterwards.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <vector>
@@ -7,25 +9,30 @@
 namespace mosaic {
 
 struct HostTier {
-    struct Entry {
-        std::vector<int> blocks;   // cache blocks (of SF pages) holding the cluster, in slab order
-        int pages = 0;             // frames of the cluster that are resident
-        long long stamp = 0;       // last use (LRU)
-        bool present = false;
-        bool by_prefetch = false;  // brought in (or completed) by a prefetch and not used by a retrieval yet
-    };
     struct Unit {
-        std::vector<std::vector<int>> slabs;    // per cluster: its host slabs in arrival order
-        std::vector<std::vector<int>> frames;   // per cluster: member frame ids, ascending
-        std::vector<int> n;                     // per cluster: frames
-        int next_slab = 0;                      // bump allocator of the unit's host pool
-        std::vector<Entry> cache;               // per cluster
-        std::vector<int> free_blocks;
-        int n_cached = 0;
+        // clusters as ascending frame lists (singly linked through next_f)
+        std::vector<int> n, head_f, tail_f;      // [C]
+        std::vector<int> next_f;                 // [F]
+        // pinned-host placement: a cluster appends to its open slab; host_page[f] = slab * SF + slot
+        std::vector<int> open_slab, open_fill;   // [C]  -1 / frames already in the open slab
+        std::vector<int> host_page;              // [F]
+        int next_slab = 0;                       // bump allocator of the unit's slab pool
+        // GPU cluster cache: a page slot per cached frame
+        std::vector<int> slot;                   // [F]  cache slot of the frame, -1 = not cached
+        std::vector<int> free_slots;             // stack of free slots
+        std::vector<int> cached;                 // [C]  member frames that are in the cache
+        std::vector<long long> stamp;            // [C]  last use (LRU)
+        std::vector<char> present;               // [C]  has an entry in the cache directory
+        std::vector<char> by_prefetch;           // [C]  brought in (or completed) by a prefetch, not used by a retrieval yet
+        int n_cached = 0;                        // clusters present
+        // latest selection, kept for the observer
+        std::vector<int> last_ids;               // [top_k]
+        int n_last = 0;
     };
-    int U = 0, C = 0, SF = 8, slabs_per_unit = 0, cache_blocks = 0, max_clusters = 0;
+    int U = 0, C = 0, F = 0, SF = 8, slabs_per_unit = 0, cache_pages = 0, max_clusters = 0, top_k = 0;
     size_t kpage = 0, vpage = 0;                // bytes of one K / V page
     std::vector<Unit> units;
+    std::vector<char> pinned;                   // [C] scratch of fetch(): the current selection
     long long clock = 0;
     int fail_need = 0, fail_free = 0, fail_cached = 0, fail_sel_pages = 0;   // context of the last ECAPACITY
     long long hits = 0, misses = 0, evictions = 0, h2d_bytes = 0, h2d_copies = 0;
@@ -37,16 +44,18 @@ struct HostTier {
     hipEvent_t main_mark = nullptr;                 // marks the caller's stream at each retrieve
     std::vector<hipEvent_t> ready, attend_done;     // per layer
     std::vector<char> attend_recorded, ready_recorded;
-    std::vector<hipEvent_t> busy_ev;                // pairs around each retrieve's copies
+    // timing of the fetch kernels while profiling is on: a fixed pool of event pairs, folded into
+    // busy_ms when it is full or when the statistics are read
+    std::vector<hipEvent_t> busy_ev;
+    size_t busy_used = 0;
     double busy_ms = 0.0;
-    // latest selection per unit, kept for the observer
-    std::vector<std::vector<int>> last_ids;
 
-    void init(int U, int C, int SF, int slabs_per_unit, int cache_blocks, int max_clusters,
+    void init(int U, int C, int F, int SF, int slabs_per_unit, int cache_pages, int max_clusters, int top_k,
               size_t kpage, size_t vpage);
     void reset();
     int append(int u, int f, int c);
-    int fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, std::vector<int> &pages,
+    bool fits(int u, const int *ids, int n_ids);
+    int fetch(int u, const int *ids, int n_ids, int *moves, int *n_moves, int *pages, int *n_pages,
               bool prefetch = false);
 };
 

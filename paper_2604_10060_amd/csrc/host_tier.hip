@@ -1,15 +1,18 @@
 // Host tier (paper Sec. V-A, V-C: all clusters are offloaded to CPU memory and
 // fetched on demand as retrieval units; Sec. VII-B: transfers overlap compute).
 //
-// Pinned host memory holds, per unit, a pool of slabs of `SF` frame pages.  A
-// cluster owns a chain of slabs, so its pages are contiguous in runs of SF
-// ([SF K pages][SF V pages]) and a fetch streams a few large contiguous regions.  The GPU side keeps, per unit, a cache of slab-sized blocks with
-// least-recently-used replacement at cluster granularity; the attention kernels
-// read cache slots through the same page list they use in the HBM tier.
+// Pinned host memory holds, per unit, a pool of slabs of `SF` frame pages
+// ([SF K pages][SF V pages]).  A cluster appends its frames to a slab of its own and
+// opens a new one when that is full, so a cluster's pages lie in runs of SF frames and
+// a fetch streams a few large contiguous regions.  The GPU side keeps, per unit, a
+// cache of page slots with least-recently-used replacement at cluster granularity
+// (a cluster is fetched, counted and evicted as a whole; its slots need not be
+// adjacent); the attention kernels read cache slots through the same page list they
+// use in the HBM tier.
 //
-// All bookkeeping (slab chains, cache directory, LRU) is plain host code; the
-// data moves by device stores into pinned memory (ingest, k_offload) and by
-// device loads from pinned memory (fetch, k_fetch).
+// All bookkeeping (frame lists, slab placement, cache directory, LRU) is plain host
+// code over arrays sized at creation; the data moves by device stores into pinned
+// memory (ingest, k_offload) and by device loads from pinned memory (fetch, k_fetch).
 #include <algorithm>
 
 #include "../../include/mosaic.h"
@@ -17,102 +20,143 @@
 
 namespace mosaic {
 
-void HostTier::init(int U_, int C_, int SF_, int slabs_per_unit_, int cache_blocks_, int max_clusters_,
-                    size_t kpage_, size_t vpage_) {
-    U = U_; C = C_; SF = SF_; slabs_per_unit = slabs_per_unit_; cache_blocks = cache_blocks_;
-    max_clusters = max_clusters_; kpage = kpage_; vpage = vpage_;
+void HostTier::init(int U_, int C_, int F_, int SF_, int slabs_per_unit_, int cache_pages_, int max_clusters_,
+                    int top_k_, size_t kpage_, size_t vpage_) {
+    U = U_; C = C_; F = F_; SF = SF_; slabs_per_unit = slabs_per_unit_; cache_pages = cache_pages_;
+    max_clusters = max_clusters_; top_k = top_k_; kpage = kpage_; vpage = vpage_;
     units.assign(U, Unit());
+    pinned.assign(C, 0);
+    for (Unit &un : units) {
+        un.n.resize(C); un.head_f.resize(C); un.tail_f.resize(C);
+        un.next_f.resize(F);
+        un.open_slab.resize(C); un.open_fill.resize(C);
+        un.host_page.resize(F);
+        un.slot.resize(F);
+        un.free_slots.reserve(cache_pages);
+        un.cached.resize(C); un.stamp.resize(C); un.present.resize(C); un.by_prefetch.resize(C);
+        un.last_ids.resize(std::max(top_k, 1));
+    }
     reset();
 }
 
 void HostTier::reset() {
     for (Unit &un : units) {
-        un.slabs.assign(C, {});
-        un.frames.assign(C, {});
-        un.n.assign(C, 0);
+        std::fill(un.n.begin(), un.n.end(), 0);
+        std::fill(un.head_f.begin(), un.head_f.end(), -1);
+        std::fill(un.tail_f.begin(), un.tail_f.end(), -1);
+        std::fill(un.next_f.begin(), un.next_f.end(), -1);
+        std::fill(un.open_slab.begin(), un.open_slab.end(), -1);
+        std::fill(un.open_fill.begin(), un.open_fill.end(), 0);
+        std::fill(un.host_page.begin(), un.host_page.end(), -1);
+        std::fill(un.slot.begin(), un.slot.end(), -1);
         un.next_slab = 0;
-        un.cache.assign(C, Entry());
-        un.free_blocks.clear();
-        for (int b = cache_blocks - 1; b >= 0; --b) un.free_blocks.push_back(b);
+        un.free_slots.clear();
+        for (int s = cache_pages - 1; s >= 0; --s) un.free_slots.push_back(s);
+        std::fill(un.cached.begin(), un.cached.end(), 0);
+        std::fill(un.stamp.begin(), un.stamp.end(), 0);
+        std::fill(un.present.begin(), un.present.end(), 0);
+        std::fill(un.by_prefetch.begin(), un.by_prefetch.end(), 0);
         un.n_cached = 0;
+        un.n_last = 0;
     }
     clock = 0;
 }
 
-// Frame f of unit u joins cluster c; returns the host page (within the unit's
-// pool) it must be stored at, or -1 if the pool is exhausted.
+// Frame f of unit u (frames arrive in ascending order) joins cluster c; returns the host
+// page (within the unit's pool) it must be stored at, or -1 if the pool is exhausted.
 int HostTier::append(int u, int f, int c) {
     Unit &un = units[u];
-    const int slot = un.n[c] % SF;
-    if (slot == 0) {
+    if (un.open_slab[c] < 0 || un.open_fill[c] == SF) {
         if (un.next_slab >= slabs_per_unit) return -1;
-        un.slabs[c].push_back(un.next_slab++);
+        un.open_slab[c] = un.next_slab++;
+        un.open_fill[c] = 0;
     }
+    const int hp = un.open_slab[c] * SF + un.open_fill[c]++;
+    un.host_page[f] = hp;
+    un.next_f[f] = -1;
+    if (un.tail_f[c] < 0) un.head_f[c] = f; else un.next_f[un.tail_f[c]] = f;
+    un.tail_f[c] = f;
     un.n[c] += 1;
-    un.frames[c].push_back(f);
-    return un.slabs[c].back() * SF + slot;
+    return hp;
+}
+
+// Can clusters ids[0..n_ids) of unit u be resident together?  Everything that is not part of
+// the selection may be evicted, so the answer depends only on the selection's own footprint
+// in pages and on its cluster count.  Fills the fail_* fields when the answer is no.
+bool HostTier::fits(int u, const int *ids, int n_ids) {
+    const Unit &un = units[u];
+    long long need = 0;
+    for (int i = 0; i < n_ids; ++i) need += un.n[ids[i]];
+    if (need <= cache_pages && n_ids <= std::max(max_clusters, 1)) return true;
+    fail_need = (int)need; fail_free = (int)un.free_slots.size(); fail_cached = un.n_cached;
+    fail_sel_pages = (int)need;
+    return false;
 }
 
 // (With `prefetch` the ids are a prediction for a coming layer, see mosaic_prefetch: the same
 // cache work, counted apart.)
-// Make clusters ids[0..n_ids) of unit u resident: decide what must move (LRU at
-// cluster granularity), append the moves as (host page, cache page) pairs to
-// `moves`, and append the cache pages of the selection, in gather order, to
-// `pages`.  The data itself is moved afterwards by ONE fetch kernel per retrieve
-// that reads the pinned slabs directly over PCIe (measured at the rate of a
-// large DMA copy, without a per-copy API cost).  Returns MOSAIC_OK or
-// MOSAIC_ECAPACITY.
-int HostTier::fetch(int u, const int *ids, int n_ids, std::vector<int> &moves, std::vector<int> &pages,
+// Make clusters ids[0..n_ids) of unit u resident: decide what must move (LRU at cluster
+// granularity, the selection itself is never evicted), write the moves as (host page,
+// cache slot) pairs to `moves` (room for 2 ints per frame of the unit) and the cache slots
+// of the selection, in gather order (clusters as listed, frames ascending), to `pages`
+// (room for one int per frame); the counts come back in *n_moves / *n_pages.  A selection
+// that cannot be resident together (fits()) changes nothing and returns MOSAIC_ECAPACITY:
+// the directory only ever describes data that a fetch kernel was given to move.  The data
+// itself is moved afterwards by ONE fetch kernel per retrieve that reads the pinned slabs
+// directly over PCIe (measured at the rate of a large DMA copy, without a per-copy API
+// cost).  Allocates nothing.
+int HostTier::fetch(int u, const int *ids, int n_ids, int *moves, int *n_moves, int *pages, int *n_pages,
                     bool prefetch) {
     Unit &un = units[u];
-    std::vector<char> pinned(C, 0);
+    *n_moves = 0; *n_pages = 0;
+    if (!fits(u, ids, n_ids)) return MOSAIC_ECAPACITY;
+    std::fill(pinned.begin(), pinned.end(), 0);
     for (int i = 0; i < n_ids; ++i) pinned[ids[i]] = 1;
+    int nm = 0, np = 0;
     for (int i = 0; i < n_ids; ++i) {
         const int c = ids[i];
-        Entry &e = un.cache[c];
-        const int have = e.present ? e.pages : 0;
+        const int have = un.present[c] ? un.cached[c] : 0;
         const int want = un.n[c];
-        const bool complete = e.present && have == want;
+        const bool complete = un.present[c] && have == want;
         if (prefetch) {                      // a guess for a coming layer: not a retrieval's hit or miss
-            if (!complete) { pf_fetched += 1; e.by_prefetch = true; }
+            if (!complete) { pf_fetched += 1; un.by_prefetch[c] = 1; }
         } else {
-            if (complete) { hits += 1; if (e.by_prefetch) pf_useful += 1; } else misses += 1;
-            e.by_prefetch = false;
+            if (complete) { hits += 1; if (un.by_prefetch[c]) pf_useful += 1; } else misses += 1;
+            un.by_prefetch[c] = 0;
         }
-        const int need_blocks = (want + SF - 1) / SF;
-        // room: enough free blocks, and not more resident clusters than allowed
-        while ((int)un.free_blocks.size() < need_blocks - (int)e.blocks.size() ||
-               (!e.present && un.n_cached >= max_clusters)) {
+        // room: enough free slots, and not more resident clusters than allowed
+        while ((int)un.free_slots.size() < want - have || (!un.present[c] && un.n_cached >= max_clusters)) {
             int victim = -1;
             for (int j = 0; j < C; ++j)
-                if (un.cache[j].present && !pinned[j] &&
-                    (victim < 0 || un.cache[j].stamp < un.cache[victim].stamp)) victim = j;
-            if (victim < 0) {
-                fail_need = need_blocks; fail_free = (int)un.free_blocks.size(); fail_cached = un.n_cached;
+                if (un.present[j] && !pinned[j] && (victim < 0 || un.stamp[j] < un.stamp[victim])) victim = j;
+            if (victim < 0) {                 // cannot happen after fits(); kept as a guard
+                fail_need = want - have; fail_free = (int)un.free_slots.size(); fail_cached = un.n_cached;
                 fail_sel_pages = 0;
                 for (int q = 0; q < n_ids; ++q) fail_sel_pages += un.n[ids[q]];
                 return MOSAIC_ECAPACITY;
             }
-            Entry &v = un.cache[victim];
-            for (int b : v.blocks) un.free_blocks.push_back(b);
-            v.blocks.clear(); v.pages = 0; v.present = false; v.by_prefetch = false;
+            for (int f = un.head_f[victim]; f >= 0; f = un.next_f[f])
+                if (un.slot[f] >= 0) { un.free_slots.push_back(un.slot[f]); un.slot[f] = -1; }
+            un.cached[victim] = 0; un.present[victim] = 0; un.by_prefetch[victim] = 0;
             un.n_cached -= 1;
             evictions += 1;
         }
-        if (!e.present) { e.present = true; un.n_cached += 1; }
-        while ((int)e.blocks.size() < need_blocks) {
-            e.blocks.push_back(un.free_blocks.back());
-            un.free_blocks.pop_back();
+        if (!un.present[c]) { un.present[c] = 1; un.n_cached += 1; }
+        for (int f = un.head_f[c]; f >= 0; f = un.next_f[f]) {
+            if (un.slot[f] < 0) {                     // still in host memory only
+                un.slot[f] = un.free_slots.back();
+                un.free_slots.pop_back();
+                moves[2 * nm] = un.host_page[f];
+                moves[2 * nm + 1] = un.slot[f];
+                ++nm;
+            }
+            pages[np++] = un.slot[f];
         }
-        for (int p = have; p < want; ++p) {          // pages still in host memory only
-            moves.push_back(un.slabs[c][p / SF] * SF + p % SF);
-            moves.push_back(e.blocks[p / SF] * SF + p % SF);
-        }
-        h2d_bytes += (long long)(want - have) * (kpage + vpage);
-        e.pages = want;
-        e.stamp = ++clock;
-        for (int p = 0; p < want; ++p) pages.push_back(e.blocks[p / SF] * SF + p % SF);
+        h2d_bytes += (long long)(want - have) * (long long)(kpage + vpage);
+        un.cached[c] = want;
+        un.stamp[c] = ++clock;
     }
+    *n_moves = nm; *n_pages = np;
     return MOSAIC_OK;
 }
 

@@ -98,7 +98,7 @@ __device__ __forceinline__ void store_key_page(const DeviceView &dv, const E *k_
     const size_t in_page = ((size_t)fl * dv.U + u) * (size_t)T * D;
     const size_t page = (size_t)u * dv.F + f;          // summary slot
     const bool host = dv.tier == MOSAIC_TIER_HOST;
-    const size_t spage = host ? (size_t)(f % dv.SN) * dv.U + u : (size_t)u * dv.PU + f;   // HBM tier: SFd = 1
+    const size_t spage = host ? (size_t)(f % dv.SN) * dv.U + u : (size_t)u * dv.PU + f;
     const E *src = k_in + in_page;
     E *dst = reinterpret_cast<E *>(kdst_base) + spage * (size_t)T * D;
     double acc[8];
@@ -215,32 +215,74 @@ __global__ __launch_bounds__(kBlock) void k_store_summary(DeviceView dv, const E
 }
 
 // ---------------------------------------------------------------------------
-// Retrieval augmentation, global representatives (paper Sec. V-C): per-cluster sums
-// of the member frames' value summaries; the value of a cluster's pseudo token is
-// this sum over the cluster size.  grid (U, ceil(n_frames / 32)), 128 threads; the
-// sums are cleared by the launcher first.
+// Retrieval augmentation, global representatives (paper Sec. V-C): the value of a
+// cluster's pseudo token is the mean of its member frames' value summaries, its key the
+// cluster's representative.  grid (U, C), 128 threads: one workgroup per cluster lists
+// the cluster's frames in ascending order (ballot-free compaction of the assignment
+// array: every thread looks at 16 consecutive frames, a scan over the threads' match
+// counts gives each match its slot) and adds their value summaries in that order, so
+// the sum is one fixed sequence of additions: the same bits on every run, whatever the
+// order in which workgroups are scheduled.  It then writes the fp32 key / value rows of
+// the pseudo-token tables (zero rows for empty clusters).
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(128) void k_value_reps(DeviceView dv, int n_frames) {
-    const int u = blockIdx.x, f0 = blockIdx.y * 32, tid = threadIdx.x;
-    if (tid >= D) return;
+    constexpr int NT = 128, FPT = 16, CH = NT * FPT;
+    const int u = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, C = dv.C;
+    const int wave = tid / 64, lane = tid % 64;
+    __shared__ int a_sh[CH];
+    __shared__ int mem[CH];
+    __shared__ int wtot[2];
+    const size_t row = (size_t)u * C + j;
+    const int nj = dv.n[row];                       // workgroup-uniform
     const int *assign = dv.assign + (size_t)u * dv.F;
-    const int f1 = min(n_frames, f0 + 32);
-    for (int f = f0; f < f1; ++f) {
-        const int a = assign[f];
-        if (a < 0) continue;
-        atomicAdd(dv.rvsum + ((size_t)u * dv.C + a) * D + tid, dv.vsumm[((size_t)u * dv.F + f) * D + tid]);
+    double acc = 0.0;
+    for (int c0 = 0; nj > 0 && c0 < n_frames; c0 += CH) {
+        const int cend = min(n_frames, c0 + CH);
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) {
+            const int f = c0 + tid + NT * i;
+            a_sh[tid + NT * i] = f < cend ? assign[f] : -1;
+        }
+        __syncthreads();
+        unsigned int mask = 0;               // bit i: frame c0 + 16 tid + i belongs to cluster j
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) mask |= (a_sh[tid * FPT + i] == j ? 1u : 0u) << i;
+        const int mine = __popc(mask);
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) wtot[wave] = incl;
+        __syncthreads();
+        int slot = incl - mine + (wave == 1 ? wtot[0] : 0);
+        const int filled = wtot[0] + wtot[1];
+        while (mask) {
+            const int i = __ffs((int)mask) - 1;
+            mask &= mask - 1;
+            mem[slot++] = c0 + tid * FPT + i;
+        }
+        __syncthreads();
+        if (tid < D) {
+            const double *vb = dv.vsumm + (size_t)u * dv.F * D + tid;
+            for (int m0 = 0; m0 < filled; m0 += 16) {      // sixteen loads in flight, added in order
+                double v[16];
+#pragma unroll
+                for (int x = 0; x < 16; ++x) v[x] = vb[(size_t)mem[min(m0 + x, filled - 1)] * D];
+#pragma unroll
+                for (int x = 0; x < 16; ++x)
+                    if (m0 + x < filled) acc += v[x];
+            }
+        }
+        __syncthreads();                     // mem / a_sh are rewritten by the next chunk
     }
-}
-
-// fp32 pseudo-token tables from the fp64 state: key = representative, value = value sum
-// over the cluster size (zero rows for empty clusters).  grid (U, C), D threads.
-template <int D>
-__global__ __launch_bounds__(D) void k_rep_tables(DeviceView dv) {
-    const size_t row = (size_t)blockIdx.x * dv.C + blockIdx.y;
-    const int nj = dv.n[row], d = threadIdx.x;
-    dv.rep_k[row * D + d] = nj > 0 ? (float)dv.r[row * D + d] : 0.f;
-    dv.rep_v[row * D + d] = nj > 0 ? (float)(dv.rvsum[row * D + d] / (double)nj) : 0.f;
+    if (tid < D) {
+        dv.rvsum[row * D + tid] = acc;
+        dv.rep_k[row * D + tid] = nj > 0 ? (float)dv.r[row * D + tid] : 0.f;
+        dv.rep_v[row * D + tid] = nj > 0 ? (float)(acc / (double)nj) : 0.f;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -990,7 +1032,7 @@ __global__ __launch_bounds__(kBlock) void k_offload(DeviceView dv, int f0) {
     const size_t bytes = blockIdx.z == 0 ? dv.kpage : dv.vpage;
     const size_t spage = (size_t)(f % dv.SN) * dv.U + u;
     const int hp = dv.dest[(size_t)u * dv.SN + fl];        // page within the unit's host pool
-    const size_t hoff = (size_t)u * dv.h_ustride + (size_t)(hp / dv.SFd) * dv.h_bstride + (size_t)(hp % dv.SFd) * bytes;
+    const size_t hoff = (size_t)u * dv.h_ustride + (size_t)(hp / dv.SFh) * dv.h_bstride + (size_t)(hp % dv.SFh) * bytes;
     const uint4 *src = reinterpret_cast<const uint4 *>((blockIdx.z == 0 ? dv.stage_k : dv.stage_v) + spage * bytes);
     uint4 *dst = reinterpret_cast<uint4 *>((blockIdx.z == 0 ? dv.host_k : dv.host_v) + hoff);
     for (size_t i = threadIdx.x; i < bytes / 16; i += kBlock) dst[i] = src[i];
@@ -1011,9 +1053,8 @@ __global__ __launch_bounds__(kBlock) void k_fetch(DeviceView dv, int u0) {
     const bool val = blockIdx.y == 1;
     const size_t bytes = val ? dv.vpage : dv.kpage;
     const char *src = (val ? dv.host_v : dv.host_k) + (size_t)u * dv.h_ustride +
-                      (size_t)(hp / dv.SFd) * dv.h_bstride + (size_t)(hp % dv.SFd) * bytes;
-    char *dst = (val ? dv.v_store : dv.k_store) + (size_t)u * dv.k_ustride +
-                (size_t)(cp / dv.SFd) * dv.k_bstride + (size_t)(cp % dv.SFd) * bytes;
+                      (size_t)(hp / dv.SFh) * dv.h_bstride + (size_t)(hp % dv.SFh) * bytes;
+    char *dst = (val ? dv.v_store + (size_t)u * dv.v_ustride : dv.k_store + (size_t)u * dv.k_ustride) + (size_t)cp * bytes;
     const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
     uint4 *d4 = reinterpret_cast<uint4 *>(dst);
     for (size_t j = threadIdx.x; j < bytes / 16; j += kBlock) d4[j] = s4[j];
@@ -1054,17 +1095,10 @@ hipError_t launch_ingest_one(const DeviceView &dv, const void *k_in, const void 
 }
 
 hipError_t launch_value_reps(const DeviceView &dv, int n_frames, hipStream_t s) {
-    hipError_t e = hipMemsetAsync(dv.rvsum, 0, (size_t)dv.U * dv.C * dv.D * 8, s);
-    if (e != hipSuccess || n_frames <= 0) return e;
-    const dim3 grid(dv.U, (n_frames + 31) / 32);
-    e = checked([&] {
+    const dim3 grid(dv.U, dv.C);
+    return checked([&] {
         if (dv.D == 64) k_value_reps<64><<<grid, 128, 0, s>>>(dv, n_frames);
         else k_value_reps<128><<<grid, 128, 0, s>>>(dv, n_frames);
-    });
-    if (e != hipSuccess) return e;
-    return checked([&] {
-        if (dv.D == 64) k_rep_tables<64><<<dim3(dv.U, dv.C), 64, 0, s>>>(dv);
-        else k_rep_tables<128><<<dim3(dv.U, dv.C), 128, 0, s>>>(dv);
     });
 }
 

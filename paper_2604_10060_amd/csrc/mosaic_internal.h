@@ -16,6 +16,7 @@ constexpr int kChunk = 32;        // tokens per attention step, always inside on
 constexpr int kMaxSplits = 64;    // KV splits per (unit, row tile), average over the units of a launch
 constexpr int kMaxUnitSplits = 256; // ... and the most one unit can be given when the units retrieve unequal amounts
 constexpr int kPrefillTiles = 2;  // row tiles per wavefront in the multi-tile MFMA kernel
+constexpr int kMlRows = 3;        // rows of 16 floats per attention partial besides O: max, normaliser, exact-weight sum
 
 // Device-side view of one context: plain pointers into the caller's arena.
 struct DeviceView {
@@ -27,24 +28,21 @@ struct DeviceView {
     int tier;         // MOSAIC_TIER_*
     int PU;           // pages per unit in k_store / v_store: F (HBM tier) or the cluster-cache capacity (host tier)
     int SN;           // host tier: frames in the staging ring
-    // KV pages the attention kernels read, addressed through k_page()/v_page() below.
-    // HBM tier: page p = frame id (arrival order), K pages and V pages in two arrays
-    //   k_store [U][PU] K pages, v_store [U][PU] V pages (SFd = 1).
-    // Host tier: page p = slot of the unit's cluster cache, which is an array of blocks with
-    //   the layout of a host slab, [SFd K pages][SFd V pages], so that a whole slab moves
-    //   with one copy; v_store = k_store + SFd K pages.
+    // KV pages the attention kernels read, addressed through k_page()/v_page() below: two arrays,
+    //   k_store [U][PU] K pages, v_store [U][PU] V pages.
+    // HBM tier: page p = frame id (arrival order).  Host tier: page p = a slot of the unit's GPU
+    //   cluster cache (slots are handed out frame by frame; a cluster's frames need not be adjacent).
     // A K page is [T][D]; a V page is [T][D] or, for the MFMA path, [Tp/32][D][32].
     char *k_store;
     char *v_store;
-    int SFd;                       // pages per block (1 in the HBM tier)
     size_t kpage, vpage;           // bytes of one K / V page
-    size_t k_ustride, k_bstride;   // bytes between units / between blocks, K array
-    size_t v_ustride, v_bstride;   // same for V
+    size_t k_ustride, v_ustride;   // bytes between units, K array / V array
     // host tier: staging ring the ingest kernel writes (frame f at slot f % SN), and the
     // device-visible address of the pinned host pools the offload kernel writes
     char *stage_k, *stage_v;   // [SN][U][page]
-    char *host_k, *host_v;     // pinned pools, same slab layout: [U][HP/SFd] x ([SFd K pages][SFd V pages])
+    char *host_k, *host_v;     // pinned pools: [U][HP/SFh] slabs of [SFh K pages][SFh V pages]
     size_t h_ustride, h_bstride;
+    int SFh;                   // frames per host slab
     int HP;                    // host pages per unit
     int *dest;                 // [U][SN] host page of each staged frame of the current batch
     // fetch work lists, written by the host into pinned memory and read by k_fetch over PCIe
@@ -100,7 +98,8 @@ struct DeviceView {
     int *tok_scratch; // [Hkv][F*T]  token-index expansion for the observer
     // attention partials: entry e = base_slot(unit)*NT + tile*S(unit) + split, see split_slot()
     float *part_o;    // [entries][16][D]
-    float *part_ml;   // [entries][2][16]  running max (log2 domain) and sum
+    float *part_ml;   // [entries][3][16]  running max (log2 domain), sum of the weights the value contraction
+                      //                   used (bf16-rounded in the MFMA kernels), sum of the unrounded weights
     long long part_entries;
 };
 
@@ -130,8 +129,10 @@ struct Ctx {
     int *h_assign, *h_dest; // staged batch: assignments read back / slab positions, [U][SN]
     // profiling
     bool profile;
-    std::vector<hipEvent_t> ev;      // pairs
+    std::vector<hipEvent_t> ev;      // pool of pairs, created by mosaic_profile_enable
     size_t ev_used;
+    double prof_ms;                  // kernel time and launches folded out of the pool so far
+    long long prof_n;
 };
 
 // ---- launchers (each checks its own launch; returns hipError_t) ----
@@ -183,10 +184,10 @@ hipError_t launch_value_reps(const DeviceView &dv, int n_frames, hipStream_t s);
 
 // ---- small device helpers ----
 __device__ __forceinline__ const char *k_page(const DeviceView &dv, int u, int p) {
-    return dv.k_store + (size_t)u * dv.k_ustride + (size_t)(p / dv.SFd) * dv.k_bstride + (size_t)(p % dv.SFd) * dv.kpage;
+    return dv.k_store + (size_t)u * dv.k_ustride + (size_t)p * dv.kpage;
 }
 __device__ __forceinline__ const char *v_page(const DeviceView &dv, int u, int p) {
-    return dv.v_store + (size_t)u * dv.v_ustride + (size_t)(p / dv.SFd) * dv.v_bstride + (size_t)(p % dv.SFd) * dv.vpage;
+    return dv.v_store + (size_t)u * dv.v_ustride + (size_t)p * dv.vpage;
 }
 __device__ __forceinline__ float bf16_to_f32(unsigned short h) {
     return __uint_as_float(((unsigned int)h) << 16);

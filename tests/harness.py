@@ -22,11 +22,10 @@ from paper_2604_10060_amd import binding, inputs
 
 NEAR_TIE = 1e-5
 OUT_TOL = {"fp32": 1e-4, "bf16": 2e-2}
-# The bf16 kernels sum the bf16-ROUNDED softmax weights into the normaliser (numerator and denominator then
-# use the same weights, which is what keeps the output within its bar): each weight carries a relative
-# rounding error of at most 2^-8, so |lse - exact| <= 2^-8 = 3.9e-3 in the worst case of a few dominant
-# tokens, and far less when many tokens share the mass.
-LSE_TOL = {"fp32": 1e-4, "bf16": 2.0 ** -8}
+# Log-sum-exp: the normaliser behind it is a sum of unrounded fp32 weights on both kernel families (the
+# bf16 kernels keep a second, bf16-rounded sum for the output only), so what is left is the fp32
+# accumulation of the logits of bf16 operands: |logit| <= ~40, relative error ~2^-20 per logit.
+LSE_TOL = {"fp32": 1e-4, "bf16": 1e-3}
 
 
 @dataclass

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import cache_model
 from paper_2604_10060_amd import binding, inputs
 from tests import harness
 
@@ -323,36 +324,25 @@ def test_host_tier_matches_hbm_tier_bitwise_and_overlaps_layers():
         assert torch.equal(o1, o2) and torch.equal(l1, l2)
 
 
-def _lru_sim(seq_ids, sizes_at, max_clusters, blocks, SF):
-    """Reference LRU at cluster granularity: returns (hits, misses)."""
-    present, stamp, used, clock, hits, misses = {}, {}, 0, 0, 0, 0
-    for ids, sizes in zip(seq_ids, sizes_at):
-        for c in ids:
-            need = -(-int(sizes[c]) // SF)
-            if c in present and present[c][1] == sizes[c]:
-                hits += 1
-            else:
-                misses += 1
-            have_blocks = present[c][0] if c in present else 0
-            while blocks - used < need - have_blocks or (c not in present and len(present) >= max_clusters):
-                victim = min((j for j in present if j not in ids), key=lambda j: stamp[j])
-                used -= present.pop(victim)[0]
-            used += need - have_blocks
-            present[c] = (need, int(sizes[c]))
-            clock += 1
-            stamp[c] = clock
-    return hits, misses
+def _model_directory(model, C):
+    d = np.full(C, -1, dtype=np.int32)
+    for c, p in model.pages.items():
+        d[c] = p
+    return d
 
 
-def test_host_tier_cache_follows_lru_and_grows_with_the_stream():
-    wl = _small(n_kv_heads=1, n_q_heads=7, n_frames=240, n_clusters=12, top_k=3, n_scenes=10)
+def test_host_tier_cache_follows_the_lru_model_and_grows_with_the_stream():
+    """The GPU cluster cache against the oracle's working-set model (least recently used at cluster
+    granularity, capacity in pages and in clusters): directory after every retrieval, hit / miss /
+    byte counters at the end, while the stream keeps growing between questions."""
+    wl = _small(n_kv_heads=1, n_q_heads=7, n_frames=240, n_clusters=12, top_k=3, n_scenes=10, warmup_frames=120)
     st = inputs.SceneStream(wl)
     K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
-    SF, pages = 4, 55 * 4
-    m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=SF,
+    pages = 170           # the three largest clusters hold 154 of the 240 frames
+    m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=4,
                                           cache_pages_per_unit=pages, cache_fraction=5 / 12), device=DEV)
+    model = cache_model.ClusterCacheModel(capacity_pages=pages, max_clusters=5)
     m.ingest_frame(K[:160].contiguous(), V[:160].contiguous())
-    seq, sizes_at = [], []
     f = 160
     for i in range(24):
         if i % 6 == 5 and f < wl.n_frames:          # the stream keeps growing between questions
@@ -363,31 +353,66 @@ def test_host_tier_cache_follows_lru_and_grows_with_the_stream():
         out, _ = m.attend(0, q)
         ids, n_ids, _, toks = m.selection(0)
         _, n = m.centroids()
-        seq.append([int(c) for c in ids[0, : n_ids[0]]])
-        sizes_at.append(n[0].copy())
+        model.access([int(c) for c in ids[0, : n_ids[0]]], n[0])
+        np.testing.assert_array_equal(m.cache_directory()[0], _model_directory(model, wl.n_clusters),
+                                      err_msg=f"cache directory after question {i}")
         assert len(toks[0]) == wl.tokens_per_frame * n[0][ids[0, : n_ids[0]]].sum()
         assert torch.isfinite(out.float()).all()
     s = m.stats()
-    hits, misses = _lru_sim(seq, sizes_at, max_clusters=5, blocks=pages // SF, SF=SF)
-    assert (s.cache_hits, s.cache_misses) == (hits, misses)
-    assert s.cache_hits > 0 and s.cache_misses > 0
+    assert (s.cache_hits, s.cache_misses) == (model.hits, model.misses)
+    page_bytes = 2 * wl.tokens_per_frame * wl.head_dim * 2
+    assert s.h2d_bytes == model.pages_moved * page_bytes
+    assert s.cache_hits > 0 and s.cache_misses > 0 and model.evictions > 0
     m.close()
 
 
-def test_host_tier_cache_too_small_is_an_error():
+def test_host_tier_cache_too_small_is_an_error_that_leaves_the_cache_usable():
+    """A selection that cannot be resident together is refused without touching the cache: the
+    directory still describes what was really fetched, the layer has no selection, and a smaller
+    selection afterwards is served and attends correctly (compared with the oracle)."""
     wl = _small(n_frames=120, n_clusters=6, top_k=4)
     st = inputs.SceneStream(wl)
-    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    K, V = st.frames(0, wl.n_frames)
+    Kd, Vd = K.to(DEV), V.to(DEV)
     m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=4,
                                           cache_pages_per_unit=8), device=DEV)
-    m.ingest_frame(K, V)
+    m.ingest_frame(Kd, Vd)
     q = st.question(0, 1, 0).to(DEV)[0].contiguous()
-    with pytest.raises(binding.MosaicError) as e:
-        m.retrieve(0, q)
-    assert e.value.code == binding.ECAPACITY
+    before = m.cache_directory().copy()
+    for call in (m.retrieve, m.prefetch):
+        with pytest.raises(binding.MosaicError) as e:
+            call(0, q)
+        assert e.value.code == binding.ECAPACITY
+        np.testing.assert_array_equal(m.cache_directory(), before)
+        with pytest.raises(binding.MosaicError) as e:     # no selection is current after the refusal
+            m.attend(0, q)
+        assert e.value.code == binding.ENOTREADY
+    s = m.stats()
+    assert s.cache_hits == s.cache_misses == s.h2d_bytes == 0
     with pytest.raises(binding.MosaicError) as e:     # all-layers calls are not part of the host tier
         m.retrieve(-1, q[None].contiguous())
     assert e.value.code == binding.EINVAL
+    m.close()
+    # the same stream with a cache that holds a top-1 selection but not a top-4 one
+    _, n = _ingest_all(wl, Kd, Vd, (16,)).centroids()
+    biggest = int(n.max())
+    wl1 = _small(n_frames=120, n_clusters=6, top_k=1)
+    m = binding.Mosaic(binding.config_for(wl1, tier=binding.TIER_HOST, slab_frames=4,
+                                          cache_pages_per_unit=biggest, cache_fraction=1 / 6), device=DEV)
+    rep = harness.Report()
+    oracles = harness.ingest_with_parity(m, wl1, Kd, Vd, [(0, 0), (0, 1)], rep)
+    model = {h: cache_model.ClusterCacheModel(biggest, 1) for h in range(wl1.n_kv_heads)}
+    for i in range(4):
+        qq = st.question(st.draw_scene(), 1, 10 + i).to(DEV)
+        harness.query_with_parity(m, wl1, qq, oracles, K, V, rep)
+        ids, n_ids, _, _ = m.selection(0)
+        _, n = m.centroids()
+        for h in range(wl1.n_kv_heads):
+            model[h].access([int(c) for c in ids[h, : n_ids[h]]], n[h])
+            np.testing.assert_array_equal(m.cache_directory()[h], _model_directory(model[h], wl1.n_clusters))
+    s = m.stats()
+    assert s.cache_hits == sum(x.hits for x in model.values())
+    assert s.cache_misses == sum(x.misses for x in model.values())
     m.close()
 
 
@@ -488,6 +513,38 @@ def test_augmentation_window_larger_than_stream_and_recluster():
 
 
 @pytest.mark.gpu
+def test_augmentation_is_bitwise_repeatable():
+    """The pseudo tokens' values are per-cluster sums over the member frames, added in ascending frame
+    order by one workgroup per cluster: two contexts fed the same stream, and a reset + re-run of one
+    of them, give bit-identical outputs and log-sum-exps."""
+    wl = inputs.CONFIGS[1].scaled(name="aug_repeat", n_frames=224, n_scenes=9, n_clusters=12, top_k=3,
+                                  question_tokens=5)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    qs = [st.question(st.draw_scene(), n, i).to(DEV) for i, n in enumerate((5, 1, 1))]
+
+    def run(m):
+        m.ingest_frame(K, V)
+        res = []
+        for q in qs:
+            m.retrieve(0, q[0].contiguous())
+            o, l = m.attend(0, q[0].contiguous())
+            res.append((o.clone(), l.clone()))
+        torch.cuda.synchronize()
+        return res
+    cfg = dict(aug_global_reps=1, aug_window_frames=4)
+    m1 = binding.Mosaic(binding.config_for(wl, **cfg), device=DEV)
+    m2 = binding.Mosaic(binding.config_for(wl, **cfg), device=DEV)
+    a, b = run(m1), run(m2)
+    m1.reset()
+    c = run(m1)
+    for x, y, z in zip(a, b, c):
+        assert torch.equal(x[0], y[0]) and torch.equal(x[1], y[1])
+        assert torch.equal(x[0], z[0]) and torch.equal(x[1], z[1])
+    m1.close(); m2.close()
+
+
+@pytest.mark.gpu
 def test_augmentation_config_errors():
     wl = inputs.CONFIGS[0]
     for bad in (dict(aug_global_reps=2), dict(aug_window_frames=-1), dict(aug_window_frames=2000),
@@ -544,6 +601,107 @@ def test_prefetch_never_changes_results_and_perfect_proxy_covers_everything():
     assert s1.cache_misses <= len(qs) * per_call and s1.cache_misses < s0.cache_misses
     assert s2.prefetch_useful <= s2.prefetch_fetched and s2.cache_misses > s1.cache_misses
     assert s1.cache_hits + s1.cache_misses == s0.cache_hits + s0.cache_misses == len(qs) * wl.n_layers * per_call
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("prefetch_top_k", [0, 2])
+def test_prefetch_follows_the_oracle_predict_verify_complete(prefetch_top_k):
+    """Sec. VII-B against the oracle: for every layer transition and unit, the clusters predicted
+    with the previous layer's query, the clusters the actual query selects and the completion set
+    come from oracle units + the working-set model; the library's cache directory must equal the
+    model's after every call, and its prefetch / hit / miss / byte counters at the end."""
+    wl = _small(n_layers=3, n_frames=160, n_clusters=10, top_k=3, warmup_frames=80)
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    pages = 120           # a unit's three largest clusters hold at most 116 of the 160 frames
+    m = binding.Mosaic(binding.config_for(wl, prefetch_top_k=prefetch_top_k, cache_pages_per_unit=pages,
+                                          cache_fraction=0.4, **HOST), device=DEV)
+    rep = harness.Report()
+    units = [(l, h) for l in range(wl.n_layers) for h in range(wl.n_kv_heads)]
+    oracles = harness.ingest_with_parity(m, wl, Kd, Vd, units, rep)
+    H, G, C = wl.n_kv_heads, wl.group, wl.n_clusters
+    models = {key: cache_model.ClusterCacheModel(pages, 4) for key in units}
+
+    def check_directory(where):
+        d = m.cache_directory()
+        for (l, h), mod in models.items():
+            np.testing.assert_array_equal(d[l * H + h], _model_directory(mod, C), err_msg=f"{where}, unit {(l, h)}")
+
+    for qi in range(6):
+        q = st.question(st.draw_scene(), 1, qi).to(DEV)
+        q_h = q.float().cpu().numpy().astype(np.float64)
+        # a related proxy on even questions (the next layer's own query plus noise-free copy of this
+        # layer's), an unrelated one on odd questions
+        other = st.question(st.draw_scene(), 1, 50 + qi).to(DEV)
+        m.retrieve(0, q[0].contiguous())
+        for h in range(H):
+            o = oracles[(0, h)]
+            models[(0, h)].access(o.retrieve(q_h[0], h, G, wl.top_k)[0], o.sizes())
+        check_directory(f"question {qi}, layer 0 retrieve")
+        for layer in range(wl.n_layers):
+            if layer + 1 < wl.n_layers:
+                proxy = q[layer] if qi % 2 == 0 else other[layer]
+                proxy_h = proxy.float().cpu().numpy().astype(np.float64)
+                m.prefetch(layer + 1, proxy.contiguous())
+                rounds = {}
+                for h in range(H):
+                    # the model's prefetch step now, its verification + completion after the retrieve
+                    o = oracles[(layer + 1, h)]
+                    ids_p = [int(c) for c in o.retrieve(proxy_h, h, G, wl.top_k)[0]]
+                    if prefetch_top_k:
+                        ids_p = ids_p[:prefetch_top_k]
+                    rounds[h] = models[(layer + 1, h)].access(ids_p, o.sizes(), prefetch=True)
+                check_directory(f"question {qi}, prefetch for layer {layer + 1}")
+            m.attend(layer, q[layer].contiguous())
+            if layer + 1 < wl.n_layers:
+                m.retrieve(layer + 1, q[layer + 1].contiguous())
+                ids, n_ids, _, _ = m.selection(layer + 1)
+                for h in range(H):
+                    o = oracles[(layer + 1, h)]
+                    want = o.retrieve(q_h[layer + 1], h, G, wl.top_k)[0]
+                    np.testing.assert_array_equal(ids[h, : n_ids[h]], want)
+                    models[(layer + 1, h)].access(want, o.sizes())
+                check_directory(f"question {qi}, layer {layer + 1} retrieve (verification + completion)")
+        torch.cuda.synchronize()
+    s = m.stats()
+    tot = lambda name: sum(getattr(x, name) for x in models.values())
+    assert (s.prefetch_fetched, s.prefetch_useful) == (tot("prefetch_fetched"), tot("prefetch_useful"))
+    assert (s.cache_hits, s.cache_misses) == (tot("hits"), tot("misses"))
+    page_bytes = 2 * wl.tokens_per_frame * wl.head_dim * 2
+    assert s.h2d_bytes == tot("pages_moved") * page_bytes
+    assert s.prefetch_calls == 6 * (wl.n_layers - 1)
+    assert tot("prefetch_fetched") > 0 and tot("evictions") > 0 and tot("prefetch_useful") > 0
+    m.close()
+
+
+@pytest.mark.gpu
+def test_prefetch_round_of_the_oracle_matches_the_library_on_one_transition():
+    """cache_model.prefetch_round (predict, verify, complete in one call) on a cold cache against
+    the library's prefetch + retrieve for one layer transition."""
+    wl = _small(n_layers=2, n_frames=128, n_clusters=8, top_k=3)
+    st = inputs.SceneStream(wl)
+    K, V = st.frames(0, wl.n_frames)
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    m = binding.Mosaic(binding.config_for(wl, cache_pages_per_unit=wl.n_frames, cache_fraction=1.0, **HOST), device=DEV)
+    rep = harness.Report()
+    units = [(1, h) for h in range(wl.n_kv_heads)]
+    oracles = harness.ingest_with_parity(m, wl, Kd, Vd, units, rep)
+    q = st.question(st.draw_scene(), 1, 0).to(DEV)
+    q_h = q.float().cpu().numpy().astype(np.float64)
+    m.prefetch(1, q[0].contiguous())
+    m.retrieve(1, q[1].contiguous())
+    d = m.cache_directory()
+    s = m.stats()
+    fetched = useful = misses = 0
+    for (l, h), o in oracles.items():
+        mod = cache_model.ClusterCacheModel(wl.n_frames, wl.n_clusters)
+        out = cache_model.prefetch_round(o, mod, q_h[0], q_h[1], h, wl.group, wl.top_k)
+        np.testing.assert_array_equal(d[l * wl.n_kv_heads + h], _model_directory(mod, wl.n_clusters))
+        assert set(out["actual"]) - set(out["predicted"]) == {c for c, _ in out["completion"]}
+        fetched += mod.prefetch_fetched; useful += mod.prefetch_useful; misses += mod.misses
+    assert (s.prefetch_fetched, s.prefetch_useful, s.cache_misses) == (fetched, useful, misses)
+    m.close()
 
 
 @pytest.mark.gpu

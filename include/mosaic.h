@@ -273,6 +273,21 @@ int32_t mosaic_prefetch(mosaic_ctx *ctx, int32_t layer, const void *q_proxy_dev,
 int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev,
                       int32_t n_q_tokens, void *out_dev, float *lse_dev);
 
+/* mosaic_attend for callers that cannot allocate or be handed scratch memory sized per call: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as mosaic_attend (the same kernels run), but the per-split attention partials
+ * live in a 16 MiB buffer that is part of the library's device image (one per GPU, held until the
+ * process ends) instead of in the arena; the call allocates nothing on the host or the device and
+ * ignores mosaic_profile_enable.  A call needs units x row tiles partial entries at the least
+ * (units = n_kv_heads, or L * n_kv_heads for layer == -1; row tiles = ceil(n_q_tokens * G / 16);
+ * an entry is 16 * head_dim * 4 + 192 bytes: 2001 entries at head_dim 128, 3912 at 64) and takes
+ * fewer KV splits when the buffer is short; ECAPACITY if even one split per row tile does not fit.
+ * Nothing in the buffer has to survive or be cleared between calls (every entry a call reads it has
+ * written itself), but all handles on one GPU share it: calls whose kernels may overlap on that GPU
+ * (different streams, no ordering between them) race and must be serialised by the caller. */
+int32_t mosaic_attend_static(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
+                             void *out_dev, float *lse_dev);
+
 /* One decode step in one call: mosaic_retrieve(layer, q) followed by mosaic_attend(layer, q) --
  * same arguments, errors, selection left behind (ids, scores, page list: the observers and a
  * later mosaic_attend see it) and the same output up to the order in which fp32 partial sums are

@@ -25,7 +25,7 @@ _STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ECAPACITY", -4: "ENOTREADY"
 
 EXPORTS = (
     "mosaic_workspace_size", "mosaic_create", "mosaic_destroy", "mosaic_reset",
-    "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_prefetch", "mosaic_attend",
+    "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_prefetch", "mosaic_attend", "mosaic_attend_static",
     "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries", "mosaic_get_maintainer",
     "mosaic_decode_step", "mosaic_ingest_frame_visual", "mosaic_get_partitions", "mosaic_get_partition_selection",
     "mosaic_get_selection", "mosaic_get_stats", "mosaic_get_cache_directory", "mosaic_profile_enable",
@@ -98,6 +98,7 @@ def load_library():
     L.mosaic_get_partition_selection.argtypes = [vp, i32, vp, vp, vp]
     L.mosaic_retrieve.argtypes = [vp, i32, vp, i32]
     L.mosaic_attend.argtypes = [vp, i32, vp, i32, vp, vp]
+    L.mosaic_attend_static.argtypes = [vp, i32, vp, i32, vp, vp]
     L.mosaic_prefetch.argtypes = [vp, i32, vp, i32]
     L.mosaic_decode_step.argtypes = [vp, i32, vp, i32, vp, vp]
     L.mosaic_get_assignments.argtypes = [vp, vp]
@@ -274,6 +275,15 @@ class Mosaic:
         if lse is None:
             lse = torch.empty(shape[:-1], dtype=torch.float32, device=self.device)
         self._check(self._L.mosaic_attend(self._h, layer, _ptr(q), tq, _ptr(out), _ptr(lse)))
+        return out, lse
+
+    def attend_static(self, layer: int, q, out, lse):
+        """mosaic_attend with its partials in the library's static buffer; out and lse are the
+        caller's (the call itself allocates nothing)."""
+        shape, tq = self._q_shape(layer, q)
+        self._check_tensor(q, shape, "q")
+        self._check_tensor(out, shape, "out")
+        self._check(self._L.mosaic_attend_static(self._h, layer, _ptr(q), tq, _ptr(out), _ptr(lse)))
         return out, lse
 
     def decode_step(self, layer: int, q, out=None, lse=None):

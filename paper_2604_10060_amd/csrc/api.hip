@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "mosaic_internal.h"
@@ -19,6 +20,30 @@ namespace {
 thread_local std::string g_create_err = "";
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Attention partials for callers that cannot allocate (mosaic_attend_static): one buffer per GPU,
+// in the library's image, shared by every handle on that GPU.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; the address kernels are given is looked up once per device.
+constexpr size_t kStaticScratchBytes = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on `device`, which must be the current device.
+hipError_t static_scratch(int device, void **out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 int fail(mosaic_ctx *ctx, int code, const std::string &msg) {
     if (ctx) ctx->err = msg; else g_create_err = msg;
@@ -302,6 +327,11 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     ctx->cfg = *cfg;
     hipError_t e = hipGetDevice(&ctx->device);
     if (e != hipSuccess) { delete ctx; return fail_hip(nullptr, e, "hipGetDevice"); }
+    ctx->static_scratch = nullptr;
+    if ((e = static_scratch(ctx->device, &ctx->static_scratch)) != hipSuccess) {
+        delete ctx;
+        return fail_hip(nullptr, e, "hipGetSymbolAddress(static attention scratch)");
+    }
     ctx->stream = (hipStream_t)cfg->stream;
     ctx->W = L.W;
     ctx->iters = cfg->lloyd_iters > 0 ? cfg->lloyd_iters : 8;
@@ -840,8 +870,8 @@ static hipError_t take_profile_events(mosaic_ctx *ctx, hipEvent_t *ev0, hipEvent
     return hipSuccess;
 }
 
-// Body of mosaic_attend: `dv` is the context's view with the partial
-// buffers the kernels are to use; `timed`: attach the
+// Body of mosaic_attend and mosaic_attend_static: `dv` is the context's view with the partial
+// buffers the kernels are to use (the arena's, or the static scratch); `timed`: attach the
 // profiling events when profiling is on.
 static int attend_with(mosaic_ctx *ctx, const DeviceView &dv, int32_t layer, const void *q_dev, int32_t n_q_tokens,
                        void *out_dev, float *lse_dev, bool timed) {
@@ -897,6 +927,21 @@ int32_t mosaic_attend(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t
                       void *out_dev, float *lse_dev) {
     if (!ctx) return MOSAIC_EINVAL;
     return attend_with(ctx, ctx->dv, layer, q_dev, n_q_tokens, out_dev, lse_dev, true);
+}
+
+int32_t mosaic_attend_static(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
+                             void *out_dev, float *lse_dev) {
+    if (!ctx) return MOSAIC_EINVAL;
+    if (!ctx->static_scratch) return fail(ctx, MOSAIC_EHIP, "the static scratch buffer has no device address");
+    // the same kernels, with their split partials in the library's static buffer instead of the arena:
+    // [entries][16][D] outputs, then [entries][3][16] statistics; every entry a launch reads was written
+    // by that launch, so nothing has to be cleared between calls
+    DeviceView dv = ctx->dv;
+    const size_t per_entry = (size_t)kRowTile * dv.D * 4 + (size_t)kMlRows * kRowTile * 4;
+    dv.part_entries = (long long)(kStaticScratchBytes / per_entry);
+    dv.part_o = (float *)ctx->static_scratch;
+    dv.part_ml = dv.part_o + (size_t)dv.part_entries * kRowTile * dv.D;
+    return attend_with(ctx, dv, layer, q_dev, n_q_tokens, out_dev, lse_dev, false);
 }
 
 int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,

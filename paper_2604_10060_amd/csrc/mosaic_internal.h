@@ -120,6 +120,7 @@ struct Ctx {
     long long rv_epoch;  // epoch the value representatives were last computed at
     mosaic_stats stats;
     std::string err;
+    void *static_scratch; // device address, on this context's GPU, of the library's static partial buffer
     HostTier *host;      // non-null in the host tier
     // host tier: host-side views of the pinned arena
     char *h_k, *h_v;     // slab pools

@@ -90,7 +90,9 @@ typedef struct {
                                      this cannot be attended: mosaic_retrieve then fails (ECAPACITY) */
     float cache_fraction;         /* at most floor(cache_fraction * C) clusters (but at least top_k) are
                                      cached per unit, least recently used evicted first; 0 -> 0.10 */
-    int32_t reserved1;
+    int32_t decode_fused_max_mib; /* (any tier; sits here for alignment) mosaic_decode_step runs its single
+                                     fused kernel while the expected K/V volume of the step is at most this
+                                     many MiB; 0 -> 48 */
     void *host_arena;             /* HOST pointer to pinned (hipHostMalloc) memory, 256-byte aligned,
                                      borrowed; size from mosaic_workspace_size */
     size_t host_arena_bytes;
@@ -294,7 +296,7 @@ int32_t mosaic_attend_static(mosaic_ctx *ctx, int32_t layer, const void *q_dev, 
  * merged.  Where it applies -- MOSAIC_TIER_HBM, bf16 MFMA attention, layer >= 0, at most 16 query
  * rows per KV head (n_q_tokens * Hq/Hkv <= 16), n_clusters <= 256, maintainer, augmentation and
  * nested index off, and an expected K/V volume of the step (frames * top_k / n_clusters pages per
- * KV head) of at most 48 MiB, i.e. a step that is bound by launch and memory latency rather than
+ * KV head) of at most decode_fused_max_mib (default 48) MiB, i.e. a step that is bound by launch and memory latency rather than
  * by bandwidth -- the selection and the attention over the selected clusters run in ONE kernel
  * (every attention workgroup repeats its unit's selection for itself, which is cheaper than a
  * launch boundary and the dependent loads after it; KV splits are then equal per unit instead of

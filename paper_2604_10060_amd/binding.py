@@ -49,7 +49,7 @@ class Config(C.Structure):
         ("max_q_tokens", C.c_int32), ("attend_impl", C.c_int32), ("tier", C.c_int32),
         ("dev_arena", C.c_void_p), ("dev_arena_bytes", C.c_size_t), ("stream", C.c_void_p),
         ("slab_frames", C.c_int32), ("cache_pages_per_unit", C.c_int32),
-        ("cache_fraction", C.c_float), ("reserved1", C.c_int32),
+        ("cache_fraction", C.c_float), ("decode_fused_max_mib", C.c_int32),
         ("host_arena", C.c_void_p), ("host_arena_bytes", C.c_size_t),
         ("maint_mode", C.c_int32), ("init_clusters", C.c_int32), ("split_iters", C.c_int32),
         ("buffer_max", C.c_int32), ("tau_min", C.c_double), ("tau_max", C.c_double),
@@ -126,7 +126,7 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
                 slab_frames=0, cache_pages_per_unit=0, cache_fraction=0.0,
                 maint_mode=MAINT_OFF, init_clusters=0, split_iters=0, buffer_max=0,
                 tau_min=0.0, tau_max=0.0, tau_n0=1.0, aug_global_reps=0, aug_window_frames=0,
-                prefetch_top_k=0, n_partitions=0, visual_dim=0, top_partitions=0) -> Config:
+                prefetch_top_k=0, n_partitions=0, visual_dim=0, top_partitions=0, decode_fused_max_mib=0) -> Config:
     c = Config()
     c.n_layers, c.n_q_heads, c.n_kv_heads = n_layers, n_q_heads, n_kv_heads
     c.head_dim, c.tokens_per_frame, c.max_frames = head_dim, tokens_per_frame, max_frames
@@ -140,6 +140,7 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
     c.tau_min, c.tau_max, c.tau_n0 = tau_min, tau_max, tau_n0
     c.aug_global_reps, c.aug_window_frames = aug_global_reps, aug_window_frames
     c.prefetch_top_k = prefetch_top_k
+    c.decode_fused_max_mib = decode_fused_max_mib
     c.n_partitions, c.visual_dim, c.top_partitions = n_partitions, visual_dim, top_partitions
     return c
 

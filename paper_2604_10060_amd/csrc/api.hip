@@ -127,6 +127,7 @@ int check_config(const mosaic_config *c, std::string &why) {
     if (c->attend_impl < MOSAIC_ATTEND_AUTO || c->attend_impl > MOSAIC_ATTEND_MFMA) { why = "attend_impl out of range"; return MOSAIC_EINVAL; }
     if (c->attend_impl == MOSAIC_ATTEND_MFMA && c->kv_dtype != MOSAIC_BF16) { why = "the MFMA attention kernel needs bf16 KV"; return MOSAIC_EINVAL; }
     if ((long long)c->max_frames * c->tokens_per_frame > 0x7fffffffLL) { why = "max_frames * tokens_per_frame must fit in int32"; return MOSAIC_EINVAL; }
+    if (c->decode_fused_max_mib < 0) { why = "decode_fused_max_mib must not be negative"; return MOSAIC_EINVAL; }
     if (c->tier != MOSAIC_TIER_HBM && c->tier != MOSAIC_TIER_HOST) { why = "tier must be MOSAIC_TIER_HBM or MOSAIC_TIER_HOST"; return MOSAIC_EINVAL; }
     if (c->tier == MOSAIC_TIER_HOST) {
         if (c->recluster_every != 0) { why = "re-clustering is not available in the host tier (pages would have to move between slabs)"; return MOSAIC_EINVAL; }
@@ -956,7 +957,7 @@ int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, in
     const long long est_bytes = (long long)dv.Hkv * est_pages * (long long)(dv.kpage + dv.vpage);
     const bool fused = !ctx->host && ctx->impl == MOSAIC_ATTEND_MFMA && layer >= 0 && NT == 1 &&
                        dv.maint_mode == MOSAIC_MAINT_OFF && !dv.aug_reps && !dv.aug_window && dv.P == 0 &&
-                       dv.C <= 256 && est_bytes <= (48ll << 20);
+                       dv.C <= 256 && est_bytes <= ((long long)(ctx->cfg.decode_fused_max_mib > 0 ? ctx->cfg.decode_fused_max_mib : 48) << 20);
     int S = 0;
     if (fused) {
         S = choose_splits(ctx, dv.Hkv, n_q_tokens, dv.part_entries);

@@ -312,11 +312,11 @@ hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const v
     const int B = n_units * n_splits;
     const dim3 grid(B + (dv.aug_reps ? n_units : 0), NT), block(kBlock);
     if (dv.esize == 4) {
-        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<float, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const float *)q, Tq, B);
-        else hipExtLaunchKernelGGL((k_attend_valu<float, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const float *)q, Tq, B);
+        if (dv.D == 64) launch_timed((k_attend_valu<float, 64>), grid, block, 0, s, ev0, ev1, dv, u0, n_units, (const float *)q, Tq, B);
+        else launch_timed((k_attend_valu<float, 128>), grid, block, 0, s, ev0, ev1, dv, u0, n_units, (const float *)q, Tq, B);
     } else {
-        if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 64>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const unsigned short *)q, Tq, B);
-        else hipExtLaunchKernelGGL((k_attend_valu<unsigned short, 128>), grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, (const unsigned short *)q, Tq, B);
+        if (dv.D == 64) launch_timed((k_attend_valu<unsigned short, 64>), grid, block, 0, s, ev0, ev1, dv, u0, n_units, (const unsigned short *)q, Tq, B);
+        else launch_timed((k_attend_valu<unsigned short, 128>), grid, block, 0, s, ev0, ev1, dv, u0, n_units, (const unsigned short *)q, Tq, B);
     }
     return hipGetLastError();
 }

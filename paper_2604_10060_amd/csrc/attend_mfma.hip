@@ -822,11 +822,11 @@ hipError_t launch_decode_fused(const DeviceView &dv, int u0, int n_units, const 
     const dim3 grid(n_units * n_splits), block(kBlock);
     const unsigned short *qq = (const unsigned short *)q;
     if (stream_kv) {
-        if (dv.D == 64) hipExtLaunchKernelGGL((k_decode_fused<64, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
-        else hipExtLaunchKernelGGL((k_decode_fused<128, true>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+        if (dv.D == 64) launch_timed((k_decode_fused<64, true>), grid, block, 0, s, ev0, ev1, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+        else launch_timed((k_decode_fused<128, true>), grid, block, 0, s, ev0, ev1, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
     } else {
-        if (dv.D == 64) hipExtLaunchKernelGGL((k_decode_fused<64, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
-        else hipExtLaunchKernelGGL((k_decode_fused<128, false>), grid, block, 0, s, ev0, ev1, 0, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+        if (dv.D == 64) launch_timed((k_decode_fused<64, false>), grid, block, 0, s, ev0, ev1, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
+        else launch_timed((k_decode_fused<128, false>), grid, block, 0, s, ev0, ev1, dv, u0, qq, Tq, n_splits, n_frames, score_mode);
     }
     return hipGetLastError();
 }
@@ -839,7 +839,7 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
     if (NT == 1) {
         const int B = n_units * n_splits;
         const dim3 grid(B + (dv.aug_reps ? n_units : 0));
-        auto go = [&](auto kern) { hipExtLaunchKernelGGL(kern, grid, block, 0, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, B); };
+        auto go = [&](auto kern) { launch_timed(kern, grid, block, 0, s, ev0, ev1, dv, u0, n_units, qq, Tq, B); };
         if (dv.aug_reps) {
             if (dv.D == 64) stream_kv ? go(k_attend_decode_mfma<64, true, true>) : go(k_attend_decode_mfma<64, true, false>);
             else stream_kv ? go(k_attend_decode_mfma<128, true, true>) : go(k_attend_decode_mfma<128, true, false>);
@@ -861,11 +861,11 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
         const int gb = (n_groups + 7) / 8 * 8 * rb;
         const dim3 grid(gb + (dv.aug_reps ? n_units * NT : 0));
         if (dv.aug_reps) {
-            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_prefill_mfma<64, true>), grid, block, lds, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
-            else hipExtLaunchKernelGGL((k_attend_prefill_mfma<128, true>), grid, block, lds, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            if (dv.D == 64) launch_timed((k_attend_prefill_mfma<64, true>), grid, block, lds, s, ev0, ev1, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            else launch_timed((k_attend_prefill_mfma<128, true>), grid, block, lds, s, ev0, ev1, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
         } else {
-            if (dv.D == 64) hipExtLaunchKernelGGL((k_attend_prefill_mfma<64, false>), grid, block, lds, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
-            else hipExtLaunchKernelGGL((k_attend_prefill_mfma<128, false>), grid, block, lds, s, ev0, ev1, 0, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            if (dv.D == 64) launch_timed((k_attend_prefill_mfma<64, false>), grid, block, lds, s, ev0, ev1, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
+            else launch_timed((k_attend_prefill_mfma<128, false>), grid, block, lds, s, ev0, ev1, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
         }
     }
     return hipGetLastError();

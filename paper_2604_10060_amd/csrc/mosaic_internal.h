@@ -183,6 +183,16 @@ hipError_t launch_decode_fused(const DeviceView &dv, int u0, int n_units, const 
 // attention partial over the representatives is computed by extra workgroups of the attention launches
 hipError_t launch_value_reps(const DeviceView &dv, int n_frames, hipStream_t s);
 
+// A kernel launch that carries a HIP start/stop event pair when one is given (the events receive the
+// kernel's own begin and end timestamps) and is a plain launch otherwise, which a caller may also
+// record into a HIP graph.
+template <typename K, typename... A>
+inline void launch_timed(K kern, dim3 grid, dim3 block, size_t lds, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1,
+                         A... args) {
+    if (ev0 || ev1) hipExtLaunchKernelGGL(kern, grid, block, (unsigned)lds, s, ev0, ev1, 0, args...);
+    else hipLaunchKernelGGL(kern, grid, block, (unsigned)lds, s, args...);
+}
+
 // ---- small device helpers ----
 __device__ __forceinline__ const char *k_page(const DeviceView &dv, int u, int p) {
     return dv.k_store + (size_t)u * dv.k_ustride + (size_t)p * dv.kpage;

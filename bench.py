@@ -2,29 +2,34 @@
 """Benchmark of the cluster-driven KV-cache hot path on one MI355X.
 
 A timed "step" is one autoregressive decode step of the workload: for every
-layer, mosaic_retrieve (mean query, scores, top-k, page list) followed by
-mosaic_attend (split-KV attention over the retrieved pages + combine), chained
-on one stream.  The stream is ingested beforehand through mosaic_ingest_frame
-(timed separately: frames/s), and the multi-token question is prefilled once.
-All inputs are resident in HBM before any timed region starts.
+layer, mosaic_decode_step -- mosaic_retrieve (mean query, scores, top-k, page
+list) followed by mosaic_attend (split-KV attention over the retrieved pages +
+combine) -- the layers chained on one stream in order, as a decoder issues them.
+The stream is ingested beforehand through mosaic_ingest_frame (timed separately:
+frames/s, with its own roofline figure), and the multi-token question is
+prefilled once.  All inputs are resident in HBM before any timed region starts.
 
-Prints ONE JSON line.  The headline numbers are those of the single-layer
-realistic workload (config 1 of the benchmark definition); `extra` repeats the
-measurement on the full 28-layer stack (config 2, ~15 GB of KV streamed from
-HBM), once with per-layer calls and once with all layers in one call.
+Prints ONE JSON line.  The headline numbers are those of the full streaming stack
+(config 2 of the benchmark definition: 28 layers, 4096 frames, ~15 GB of KV
+streamed from HBM, per-layer calls); `extra` holds the same stack with all layers
+in one call, the single-layer config 1, the 8-stream question prefill (config 4),
+the host-offload tier (config 3, measured in a process of its own) and the
+extensions.
 
 `roofline` refers to the split-KV attention kernel (the dominant kernel):
 algorithmic bytes = K and V of the retrieved tokens read once, divided by that
 kernel's mean duration, measured with a HIP start/stop event pair attached to
 every launch on the library's stream (the kernel's own begin/end timestamps).
+`roofline.traffic` is read from the rocprofv3 counter summary under profiles/.
 `cpu_baseline` is the fp64 CPU oracle timed on this host on a bounded sample of
-the same decode steps.
+the same workload (whole streams of a few units; one thread and all cores).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
@@ -35,16 +40,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
-# HBM bytes per launch of the decode attention kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter read on
-# k_calibration_copy, a 256 MiB copy): see profiles/.  Keyed by (workload, calls).
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg1_single_layer_hbm", "per_layer_decode_step", "k_decode_fused"): 29_870_000,   # 28.93 MB read + 0.94 MB written
-    ("cfg1_single_layer_hbm", "per_layer", "k_attend_decode_mfma"): 27_150_000,     # 26.41 MB read + 0.74 MB written
-    ("cfg2_full_stack_hbm", "per_layer", "k_attend_decode_mfma"): 118_290_000,      # 117.37 MB + 0.93 MB
-    ("cfg2_full_stack_hbm", "per_layer_decode_step", "k_attend_decode_mfma"): 118_290_000,   # (same kernel: two calls inside)
-    ("cfg2_full_stack_hbm", "all_layers", "k_attend_decode_mfma"): 3_298_000_000,   # 3291.67 MB + 6.33 MB (32-step run)
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attend_kernels_hbm_traffic_pmc.txt")
+
+
+def measured_traffic_bytes(workload, calls, kernel):
+    """HBM bytes per launch of an attention kernel as the hardware counters saw them (FETCH_SIZE +
+    WRITE_SIZE from two rocprofv3 --pmc runs, each scaled by the same counter read on a plain copy of
+    known size): the `traffic_bytes <workload> <calls> <kernel> <bytes>` lines of the committed
+    summary.  Raises if the summary has no line for the key: a changed kernel or workload must be
+    measured again, not reported with old bytes."""
+    with open(TRAFFIC_FILE) as fh:
+        for line in fh:
+            w = line.split()
+            if len(w) == 5 and w[0] == "traffic_bytes" and (w[1], w[2], w[3]) == (workload, calls, kernel):
+                return int(w[4])
+    raise KeyError(f"{TRAFFIC_FILE} has no traffic_bytes line for {workload} {calls} {kernel}")
 
 
 def log(*a):
@@ -54,9 +64,9 @@ def log(*a):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "maintainer", "prefetch", "nested"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "maintainer", "prefetch", "nested"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count")
     ap.add_argument("--frames", type=int, default=0, help="override the frame count")
     ap.add_argument("--all-layers-call", action="store_true",
@@ -64,9 +74,10 @@ def parse():
     ap.add_argument("--two-calls", action="store_true",
                     help="per-layer decode steps as mosaic_retrieve + mosaic_attend instead of mosaic_decode_step")
     ap.add_argument("--no-extra", action="store_true",
-                    help="skip the config-2 legs reported under `extra`")
+                    help="skip the legs reported under `extra`")
     ap.add_argument("--extra-steps", type=int, default=32)
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle leg")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0, help="budget of each timed decode part of the oracle leg")
+    ap.add_argument("--cpu-units", type=int, default=0, help="units the oracle leg samples (0 = one per host thread, at most 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (counter calibration for rocprofv3 --pmc)")
@@ -91,7 +102,7 @@ def n_tok_all(m, L):
 
 
 def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrate=False, aug=None,
-            two_calls=False):
+            two_calls=False, cpu_units=0, traffic_lookup=True, ingest_without_recluster=False):
     """aug = (window_frames, global_reps) switches the retrieval augmentation of Sec. V-C on.
     Per-layer decode steps go through mosaic_decode_step (selection and attention in one kernel
     where the library supports it) unless two_calls asks for mosaic_retrieve + mosaic_attend."""
@@ -292,13 +303,40 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
     if one_call and stats.last_decode_fused:       # selection and attention ran as one kernel
         kernel = "k_decode_fused"
 
+    # ---- ingest against its roofline ------------------------------------------------
+    # Algorithmic bytes per frame: the K and V pages read once and written once into the store
+    # (the key summary is formed from the same read) plus the fp64 summary row per unit.
+    U = L * wl.n_kv_heads
+    ingest_bytes = 4 * U * T * D * esz + U * D * 8
+    ingest_rf = {"bytes_per_frame": ingest_bytes,
+              "frames_per_s": round(fps_b1, 1), "frames_per_s_batch16": round(fps_b16, 1),
+              "hbm_frac": round(fps_b1 * ingest_bytes / 1e9 / HBM_PEAK_GBPS, 4),
+              "hbm_frac_batch16": round(fps_b16 * ingest_bytes / 1e9 / HBM_PEAK_GBPS, 4),
+              "recluster_every": wl.recluster_every}
+    m.close()
+    m = None
+    if ingest_without_recluster and wl.recluster_every > 0:
+        torch.cuda.empty_cache()
+        m = binding.Mosaic(binding.config_for(wl, recluster_every=0), device=dev)   # (ingest() below sees this context)
+        lib, h = m._L, m._h
+        ingest(16)
+        nr16, nr1 = ingest(16), ingest(1)
+        ingest_nr = {"frames_per_s_without_reclustering": round(nr1, 1),
+                     "frames_per_s_batch16_without_reclustering": round(nr16, 1),
+                     "hbm_frac_without_reclustering": round(nr1 * ingest_bytes / 1e9 / HBM_PEAK_GBPS, 4),
+                     "hbm_frac_batch16_without_reclustering": round(nr16 * ingest_bytes / 1e9 / HBM_PEAK_GBPS, 4)}
+        m.close()
+        m = None
+    else:
+        ingest_nr = {}
+
     cpu = None
     if cpu_seconds > 0:
-        cpu = cpu_baseline(wl, K_all, V_all, q_dec[warmup:], cpu_seconds)
+        cpu = cpu_baseline(wl, K_all, V_all, q_dec[warmup:], cpu_seconds, cpu_units)
 
-    m.close()
-    del K_all, V_all, m
+    del K_all, V_all
     torch.cuda.empty_cache()
+    traffic = measured_traffic_bytes(wl.name, mode, kernel) if traffic_lookup else None
     return {
         "us_per_step": us_per_step,
         "config": {"workload": wl.name, "layers": L, "q_heads": Hq, "kv_heads": wl.n_kv_heads,
@@ -306,7 +344,7 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
                    "top_k": wl.top_k, "calls": mode, "kv_splits": stats.last_n_splits},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode, kernel)),
+                     "traffic": traffic,
                      "kernel": kernel, "kernel_us": round(kern_us, 3),
                      "launches": int(launches), "bytes_per_launch": round(bytes_per_launch)},
         "cpu_baseline": cpu,
@@ -318,6 +356,7 @@ def run_leg(wl, *, steps, warmup, all_layers, check_units, cpu_seconds, calibrat
         "frac_of_stream_kernel": round(achieved / stream_gbps, 4),
         "ingest_frames_per_s": round(fps_b1, 1),
         "ingest_frames_per_s_batch16": round(fps_b16, 1),
+        "ingest_roofline": {"bound": "hbm", "peak": HBM_PEAK_GBPS, "unit": "GB/s", **ingest_rf, **ingest_nr},
         "question_tokens": wl.question_tokens,
         "question_ms": round(question_ms, 4),
         "parity_spot_check": checked,
@@ -652,7 +691,7 @@ def run_prefetch_leg(layers=3, steps=96, rhos=(0.95, 0.7)):
         res = {}
         for mode in ("sequential", "proxy", "proxy_top8", "lookahead"):
             m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
-                                                  cache_pages_per_unit=F + 52 * 16,
+                                                  cache_pages_per_unit=F,
                                                   prefetch_top_k=8 if mode == "proxy_top8" else 0), device=dev)
             for f0 in range(0, F, 256):
                 K, V = st.frames(f0, min(F, f0 + 256))
@@ -709,7 +748,26 @@ def run_prefetch_leg(layers=3, steps=96, rhos=(0.95, 0.7)):
                        "slab_frames": 16, "cache_fraction": 0.10, "decode_steps": steps}, **out_all}
 
 
-def run_host_leg(layers=2, steps=128, check=True):
+def host_layers_that_fit(wl_full, cfg_kw, reserve=0.35, cap_bytes=170 << 30):
+    """As many of the configuration's layers as pinned host memory allows: the largest layer count whose
+    pinned arena is at most (1 - reserve) of MemAvailable and of cap_bytes (one command may hold
+    about 270 GiB of host memory on these boxes; the stream generator and torch need their share)."""
+    from paper_2604_10060_amd import binding
+    avail = None
+    with open("/proc/meminfo") as fh:
+        info = {l.split(":")[0]: int(l.split()[1]) * 1024 for l in fh if ":" in l}
+    avail = info.get("MemAvailable", info.get("MemTotal", 0))
+    budget = min(int(avail * (1.0 - reserve)), cap_bytes)
+    best = 1
+    for layers in range(1, wl_full.n_layers + 1):
+        _, hbytes = binding.workspace_sizes(binding.config_for(wl_full.scaled(n_layers=layers), **cfg_kw))
+        if hbytes <= budget:
+            best = layers
+    return best, {"MemTotal_GB": round(info.get("MemTotal", 0) / 1e9, 1), "MemAvailable_GB": round(avail / 1e9, 1),
+                  "pinned_budget_GB": round(budget / 1e9, 1)}
+
+
+def run_host_leg(layers=0, steps=128, check=True):
     """Config 3 (host-offload tier) with the layer count scaled to `layers` (the
     full 28 layers need 184 GB of pinned host memory; the per-layer shape is
     kept): clusters live in pinned host memory in slabs of 16 frames, the GPU
@@ -719,8 +777,30 @@ def run_host_leg(layers=2, steps=128, check=True):
     import torch
     from paper_2604_10060_amd import binding, inputs
     dev = "cuda:0"
+    host_kw = dict(tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
+                   cache_pages_per_unit=inputs.CONFIGS[3].n_frames)
+    mem = None
+    m = None
+    if layers <= 0:
+        # as many layers as pinned memory allows: bounded by MemAvailable, then by what hipHostMalloc
+        # really grants (on these boxes pinned allocations stop far below the free host memory)
+        layers, mem = host_layers_that_fit(inputs.CONFIGS[3], host_kw)
+        layers = min(layers, int(os.environ.get("MOSAIC_BENCH_HOST_LAYERS_MAX", "6")))
+        refused = []
+        while layers >= 1:
+            try:
+                m = binding.Mosaic(binding.config_for(inputs.CONFIGS[3].scaled(n_layers=layers), **host_kw), device=dev)
+                break
+            except (RuntimeError, binding.MosaicError) as ex:
+                _, hb = binding.workspace_sizes(binding.config_for(inputs.CONFIGS[3].scaled(n_layers=layers), **host_kw))
+                refused.append({"layers": layers, "pinned_GB": round(hb / 1e9, 1), "error": repr(ex)[:80]})
+                layers -= 1
+        mem["pinned_allocations_refused"] = refused
+        if m is None:
+            raise RuntimeError("no pinned host arena could be allocated")
     wl = inputs.CONFIGS[3].scaled(n_layers=layers)
     L, Hq, D, T, F, H = wl.n_layers, wl.n_q_heads, wl.head_dim, wl.tokens_per_frame, wl.n_frames, wl.n_kv_heads
+    log(f"[bench] {wl.name}: {layers} of 28 layers ({mem})")
     # measured pinned host-to-device rate of this machine: one 1 GiB copy
     src = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
     dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -735,8 +815,9 @@ def run_host_leg(layers=2, steps=128, check=True):
     # resident clusters capped at 10 % (51 of 512), least recently used evicted first.  The block pool
     # is sized for the worst case (any 51 clusters): with a fixed number of clusters and no splitting a
     # few clusters grow very large (here up to ~1500 of 16384 frames) and top-32 can cover half the stream.
-    m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
-                                          cache_pages_per_unit=F + 52 * 16), device=dev)
+    if m is None:
+        m = binding.Mosaic(binding.config_for(wl, **host_kw), device=dev)
+    _, hbytes = binding.workspace_sizes(binding.config_for(wl, **host_kw))
     cu = (layers - 1, 2)                             # unit checked against the oracle
     keepK, keepV = [], []
     t0 = time.perf_counter()
@@ -821,7 +902,8 @@ def run_host_leg(layers=2, steps=128, check=True):
     torch.cuda.empty_cache()
     return {"config": {"workload": wl.name, "layers": layers, "layers_of_full_config": 28,
                        "frames": F, "tokens_per_frame": T, "clusters": wl.n_clusters, "top_k": wl.top_k,
-                       "slab_frames": 16, "cache_fraction": 0.10},
+                       "slab_frames": 16, "cache_fraction": 0.10, "pinned_host_GB": round(hbytes / 1e9, 1),
+                       "host_memory": mem},
             "decode_step_us_warm_median": round(float(np.median(warm)), 1),
             "decode_step_us_topic_switch_mean": round(float(cold.mean()), 1),
             "ingest_frames_per_s": round(ingest_fps, 1),
@@ -838,52 +920,97 @@ def run_host_leg(layers=2, steps=128, check=True):
             "parity_spot_check": checked}
 
 
-def cpu_baseline(wl, K_all, V_all, q_steps, budget_s):
-    """The oracle as it stands, on this host: clustering of the sampled units'
-    streams (untimed here), then timed decode steps (retrieve + attend), units
-    in parallel threads (the C code releases the GIL)."""
+def cpu_baseline(wl, K_all, V_all, q_steps, budget_s, n_units=0):
+    """The oracle as it stands, on this host, on a bounded sample of the same workload: the WHOLE
+    stream of a few (layer, KV head) units (units are independent, so a unit is a fair sample of
+    the job) -- (i) on one thread, (ii) on all host threads, one unit per thread (the C code
+    releases the GIL) -- for Frame Encoding (frames/s) and for decode steps (retrieve + attend).
+    Unit times are scaled to the whole job (all L * Hkv units)."""
     from oracle import mosaic_oracle as orc
     from paper_2604_10060_amd import inputs
     L, H, G, D, T, F = wl.n_layers, wl.n_kv_heads, wl.group, wl.head_dim, wl.tokens_per_frame, wl.n_frames
     units = [(l, h) for l in range(L) for h in range(H)]
-    max_units = 8                               # bounded sample of units for big stacks
-    sample = units if len(units) <= max_units else [units[i] for i in
-                                                    np.linspace(0, len(units) - 1, max_units).astype(int)]
-    threads = min(len(sample), 16, os.cpu_count() or 1)
-    t0 = time.time()
-    state = {}
-    for (l, h) in sample:                       # sequential: bounds host memory
-        Ku = inputs.unit_pages(K_all, l, h)
-        Vu = inputs.unit_pages(V_all, l, h)
+    nproc = os.cpu_count() or 1
+    try:
+        nproc = min(nproc, len(os.sched_getaffinity(0)))
+    except AttributeError:
+        pass
+    threads = max(1, min(nproc, 16))
+    n_s = min(len(units), n_units if n_units > 0 else min(threads, 8))
+    sample = [units[i] for i in np.linspace(0, len(units) - 1, n_s).astype(int)]
+    threads = min(threads, n_s)
+    log(f"[bench] oracle: nproc {nproc}, {threads} threads, {n_s} of {len(units)} units sampled")
+    pages = {lh: (inputs.unit_pages(K_all, *lh), inputs.unit_pages(V_all, *lh)) for lh in sample}
+
+    def ingest_unit(lh):
         o = orc.OracleUnit(wl.n_clusters, D, T, F, wl.warmup_frames, wl.lloyd_iters, wl.recluster_every)
-        ti = time.perf_counter()
+        Ku = pages[lh][0]
         for f in range(F):
             o.ingest(Ku[f])
-        state[(l, h)] = (o, Ku.reshape(-1, D), Vu.reshape(-1, D), time.perf_counter() - ti)
-    ingest_s = sum(v[3] for v in state.values()) / len(state)     # per unit, one thread
-    log(f"[bench] oracle: {len(sample)} unit streams clustered in {time.time() - t0:.1f}s "
-        f"({F / ingest_s:.0f} frames/s per unit-thread)")
+        return o
+
+    # (i) one thread: one unit's whole stream
+    t = time.perf_counter()
+    first = ingest_unit(sample[0])
+    t_one = time.perf_counter() - t
+    # (ii) all threads: one unit per thread, all sampled units
+    t = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        oracles = list(ex.map(ingest_unit, sample))
+    t_all = time.perf_counter() - t
+    state = {lh: (o, pages[lh][0].reshape(-1, D), pages[lh][1].reshape(-1, D)) for lh, o in zip(sample, oracles)}
+    del first
+    fps_one = F / (t_one * len(units))                       # whole job on one thread
+    fps_all = F / (t_all * len(units) / n_s)                 # whole job, n_s units at a time
+    log(f"[bench] oracle ingest: one unit stream {t_one:.1f}s on one thread; {n_s} streams {t_all:.1f}s on {threads} threads "
+        f"-> whole job {fps_one:.1f} / {fps_all:.1f} frames/s")
     q_h = q_steps.float().cpu().numpy().astype(np.float64)        # [n][L][1][Hq][D]
 
     def one(lh, i):
         l, h = lh
-        o, Ku, Vu, _ = state[lh]
+        o, Ku, Vu = state[lh]
         ids, sc, tok, gap = o.retrieve(q_h[i, l], h, G, wl.top_k)
         orc.attend(q_h[i, l], Ku, Vu, tok, h, G)
 
-    done = 0
-    t_start = time.perf_counter()
-    with ThreadPoolExecutor(threads) as ex:
-        while done < len(q_h) and (time.perf_counter() - t_start) < budget_s:
-            list(ex.map(lambda lh: one(lh, done), sample))
-            done += 1
-    el = time.perf_counter() - t_start
-    # scale the sampled units to the whole step (all units), same thread count
-    us = el / max(done, 1) * 1e6 * (len(units) / len(sample))
-    return {"value": round(us, 1), "unit": "us", "cores": threads, "kind": "oracle",
-            "sample": f"{done} decode steps x {len(sample)} of {len(units)} units "
-                      f"(time scaled to all units), {threads} threads",
-            "ingest_frames_per_s_per_thread": round(F / ingest_s, 1)}
+    def timed(parallel):
+        done, t0 = 0, time.perf_counter()
+        with ThreadPoolExecutor(threads) as ex:
+            while done < len(q_h) and (time.perf_counter() - t0) < budget_s:
+                if parallel:
+                    list(ex.map(lambda lh: one(lh, done), sample))
+                else:
+                    for lh in sample:
+                        one(lh, done)
+                done += 1
+        return (time.perf_counter() - t0) / max(done, 1) * 1e6 * (len(units) / n_s), done
+
+    us_one, n_one = timed(False)
+    us_all, n_all = timed(True)
+    return {"value": round(us_all, 1), "unit": "us", "cores": threads, "kind": "oracle",
+            "sample": f"decode steps (retrieve + attend) on the whole streams of {n_s} of {len(units)} units, times "
+                      f"scaled to all units: {n_all} steps on {threads} threads, {n_one} steps on one thread",
+            "nproc": nproc,
+            "value_one_thread": round(us_one, 1),
+            "ingest_frames_per_s": round(fps_all, 2), "ingest_frames_per_s_one_thread": round(fps_one, 2),
+            "ingest_sample": f"whole stream ({F} frames, re-clustering every {wl.recluster_every}) of {n_s} units on "
+                             f"{threads} threads ({t_all:.1f} s) and of one unit on one thread ({t_one:.1f} s), "
+                             f"scaled to all {len(units)} units"}
+
+
+def host_leg_in_its_own_process(layers):
+    """Config 3 needs tens of GB of pinned host memory next to an 18 GB cluster cache: it runs in a
+    process of its own (started before this process touches the GPU) so that no other leg's
+    allocations stand beside it.  Returns the leg's JSON (or an error record)."""
+    cmd = [sys.executable, os.path.abspath(__file__), "--workload", "cfg3"] + (["--layers", str(layers)] if layers else [])
+    try:
+        p = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
+        sys.stderr.write(p.stderr[-4000:])
+        lines = [l for l in p.stdout.splitlines() if l.startswith("{")]
+        if p.returncode != 0 or not lines:
+            return {"error": f"cfg3 process ended with {p.returncode}: {p.stderr[-300:]}"}
+        return json.loads(lines[-1])
+    except Exception as ex:                          # noqa: BLE001
+        return {"error": repr(ex)[:300]}
 
 
 def main():
@@ -907,56 +1034,54 @@ def main():
         print(json.dumps(run_nested_leg(layers=args.layers or 4, check=args.check_units > 0)))
         return
     if args.workload == "cfg3":
-        print(json.dumps(run_host_leg(layers=args.layers or 2, check=args.check_units > 0)))
+        print(json.dumps(run_host_leg(layers=args.layers, check=args.check_units > 0)))
         return
     wl = inputs.CONFIGS[int(args.workload[-1])]
+    modified = bool(args.layers or args.frames)
     if args.layers:
         wl = wl.scaled(n_layers=args.layers)
     if args.frames:
         wl = wl.scaled(n_frames=args.frames)
+    headline = args.workload == "cfg2" and not modified and not args.all_layers_call
+    with_extra = headline and not args.no_extra
+    extra = {} if with_extra else None
+    if with_extra:          # first, while this process has not touched the GPU yet
+        extra["cfg3_host_offload"] = host_leg_in_its_own_process(0)
+    aug = (args.aug_window, args.aug_reps) if (args.aug_window or args.aug_reps) else None
     main_leg = run_leg(wl, steps=args.steps, warmup=args.warmup, all_layers=args.all_layers_call,
                        check_units=args.check_units,
-                       cpu_seconds=0 if args.no_cpu_baseline else args.cpu_seconds,
-                       calibrate=args.calibrate_copy,
-                       aug=(args.aug_window, args.aug_reps) if (args.aug_window or args.aug_reps) else None,
-                       two_calls=args.two_calls)
-    extra = None
-    if not args.no_extra and args.workload == "cfg1" and not (args.layers or args.frames):
-        extra = {}
-        if not args.two_calls:
+                       cpu_seconds=0 if args.no_cpu_baseline else args.cpu_seconds, cpu_units=args.cpu_units,
+                       calibrate=args.calibrate_copy, aug=aug, two_calls=args.two_calls,
+                       traffic_lookup=not modified and aug is None, ingest_without_recluster=True)
+    if with_extra:
+        def keep(leg, *more):
+            out = {"decode_step_us": round(leg["us_per_step"], 2), "config": leg["config"],
+                   "step_us_median": leg["step_us_median"], "step_us_p95": leg["step_us_p95"],
+                   "roofline": leg["roofline"], "step_hbm_gbps": leg["step_hbm_gbps"],
+                   "step_hbm_frac": leg["step_hbm_frac"], "parity_spot_check": leg["parity_spot_check"]}
+            out.update({k: leg[k] for k in more})
+            return out
+        # every leg in its own try block: none of them takes the headline line down
+        try:
+            leg = run_leg(inputs.CONFIGS[2], steps=args.steps, warmup=args.warmup, all_layers=True, check_units=1,
+                          cpu_seconds=0)
+            extra["cfg2_all_layers"] = keep(leg, "stream_kernel_gbps", "frac_of_stream_kernel", "question_ms")
+        except Exception as ex:                      # noqa: BLE001
+            extra["cfg2_all_layers"] = {"error": repr(ex)[:300]}
+        for name, two in (("cfg1_decode_step", False), ("cfg1_retrieve_then_attend", True)):
             try:
-                leg = run_leg(inputs.CONFIGS[1], steps=args.steps, warmup=args.warmup, all_layers=False,
-                              check_units=1, cpu_seconds=0, two_calls=True)
-                extra["cfg1_retrieve_then_attend"] = {
-                    "decode_step_us": round(leg["us_per_step"], 2), "config": leg["config"],
-                    "step_us_median": leg["step_us_median"], "step_us_p95": leg["step_us_p95"],
-                    "roofline": leg["roofline"], "parity_spot_check": leg["parity_spot_check"]}
+                leg = run_leg(inputs.CONFIGS[1], steps=256, warmup=10, all_layers=False, check_units=1,
+                              cpu_seconds=0, two_calls=two)
+                extra[name] = keep(leg, "ingest_roofline", "question_ms")
             except Exception as ex:                  # noqa: BLE001
-                extra["cfg1_retrieve_then_attend"] = {"error": repr(ex)[:300]}
-        for all_layers in (False, True):
-            try:
-                leg = run_leg(inputs.CONFIGS[2], steps=args.extra_steps, warmup=4, all_layers=all_layers,
-                              check_units=1 if all_layers else 0, cpu_seconds=0, two_calls=args.two_calls)
-            except Exception as ex:                  # noqa: BLE001
-                extra["cfg2_" + ("all_layers" if all_layers else "per_layer")] = {"error": repr(ex)[:300]}
-                continue
-            extra["cfg2_" + leg["config"]["calls"]] = {
-                "decode_step_us": round(leg["us_per_step"], 2), "config": leg["config"],
-                "step_us_median": leg["step_us_median"], "step_us_p95": leg["step_us_p95"],
-                "roofline": leg["roofline"], "step_hbm_gbps": leg["step_hbm_gbps"],
-                "step_hbm_frac": leg["step_hbm_frac"], "stream_kernel_gbps": leg["stream_kernel_gbps"],
-                "frac_of_stream_kernel": leg["frac_of_stream_kernel"],
-                "ingest_frames_per_s": leg["ingest_frames_per_s"],
-                "ingest_frames_per_s_batch16": leg["ingest_frames_per_s_batch16"],
-                "question_ms": leg["question_ms"], "parity_spot_check": leg["parity_spot_check"]}
-        # the remaining legs never take the headline line down with them
+                extra[name] = {"error": repr(ex)[:300]}
         try:
             extra["cfg4_prefill_8_streams"] = run_prefill_leg()
         except Exception as ex:                      # noqa: BLE001
             extra["cfg4_prefill_8_streams"] = {"error": repr(ex)[:300]}
         try:
-            leg = run_leg(inputs.CONFIGS[1], steps=args.steps, warmup=args.warmup, all_layers=False,
-                          check_units=1, cpu_seconds=0, aug=(16, True))
+            leg = run_leg(inputs.CONFIGS[1], steps=256, warmup=10, all_layers=False,
+                          check_units=1, cpu_seconds=0, aug=(16, True), traffic_lookup=False)
             extra["next2_augmentation_cfg1"] = {
                 "augmentation": {"window_frames": 16, "global_reps": True},
                 "decode_step_us": round(leg["us_per_step"], 2), "step_us_median": leg["step_us_median"],
@@ -978,14 +1103,6 @@ def main():
             extra["next3_cross_layer_prefetch"] = run_prefetch_leg(layers=2, steps=64, rhos=(0.95,))
         except Exception as ex:                      # noqa: BLE001
             extra["next3_cross_layer_prefetch"] = {"error": repr(ex)[:300]}
-        for layers in (2, 1):
-            try:
-                import torch
-                torch.cuda.empty_cache()
-                extra["cfg3_host_offload"] = run_host_leg(layers=layers)
-                break
-            except Exception as ex:                  # noqa: BLE001
-                extra["cfg3_host_offload"] = {"error": repr(ex)[:300], "layers": layers}
     us = main_leg.pop("us_per_step")
     result = {
         "metric": "decode_step_retrieve_attend_latency_us",

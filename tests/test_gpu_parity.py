@@ -273,7 +273,7 @@ def test_cfg3_full_shape_one_layer_host_tier():
     wl = inputs.CONFIGS[3].scaled(n_layers=1)
     rep = harness.run_full_size(wl, [(0, 2)], ingest_batch=64, decode_steps=2, question=False,
                                 tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
-                                cache_pages_per_unit=wl.n_frames + 52 * 16)
+                                cache_pages_per_unit=wl.n_frames)
     _report(rep)
     assert rep.online_decisions == wl.n_frames - wl.warmup
 

@@ -96,7 +96,11 @@ typedef struct {
     void *host_arena;             /* HOST pointer to pinned (hipHostMalloc) memory, 256-byte aligned,
                                      borrowed; size from mosaic_workspace_size */
     size_t host_arena_bytes;
-    /* Self-adaptive maintainer (paper Sec. VI); MOSAIC_TIER_HBM only, excludes recluster_every.
+    /* Self-adaptive maintainer (paper Sec. VI); excludes recluster_every.  In the host tier a split
+     * moves no page: a frame keeps its place in pinned memory and its slot in the GPU cluster cache,
+     * the host follows the new membership (it reads the unit's frame -> cluster map back when the
+     * unit's split counters or buffer fill have moved), and both halves inherit what the cache holds
+     * of the parent and its time of last use.
      * Every insertion updates the cluster's running variance (Eq. 4) next to its representative
      * (Eq. 3); a cluster whose variance exceeds the size-adaptive threshold (Eq. 5, evaluated at
      * its size before the insertion) is refined by a two-way Split (two-means under the cosine
@@ -146,9 +150,11 @@ typedef struct {
 } mosaic_config;
 
 /* maint_mode.  _EAGER: every cluster counts as GPU resident, an invalid cluster is split at once
- * (Alg. 1 lines 4-6).  _DEFERRED: Alg. 1 in full with "GPU resident" = selected by the unit's
- * latest mosaic_retrieve (the working set a GPU cluster cache would hold): an invalid cluster that
- * is not resident gets a lazy-split flag and the new state is kept in the buffer as a singleton
+ * (Alg. 1 lines 4-6).  _DEFERRED: Alg. 1 in full.  "GPU resident" means, in the host tier, that
+ * the GPU cluster cache holds frames of the cluster (the split itself needs only the frame
+ * summaries, which never leave the GPU); in the HBM tier, where everything is resident, it is
+ * emulated as "selected by the unit's latest mosaic_retrieve" (the working set such a cache would
+ * hold).  An invalid cluster that is not resident gets a lazy-split flag and the new state is kept in the buffer as a singleton
  * cluster that retrieval can select (id n_clusters + buffer slot); the split is carried out when
  * mosaic_retrieve next selects the flagged cluster (lines 12-17), after that query's page list
  * has been built. */

@@ -7,6 +7,15 @@ small working set" on the GPU; it does not name the replacement policy.  Reading
 taken: least recently used at cluster granularity, the clusters of the call being
 served never evicted, capacity counted in frame pages and in clusters.
 
+The self-adaptive maintainer (Sec. VI) changes cluster membership under the cache:
+a split hands part of a cached cluster's frames to a new cluster id.  The model
+therefore keeps its state per FRAME (cached or not, time of last use, fetched ahead
+or not) and derives everything cluster-level from the membership it is given at each
+call: a cluster is resident if any of its frames is cached, complete if all are, and
+its time of last use is the latest of its cached frames' -- so both halves of a split
+cluster inherit the parent's recency without the model knowing about the split.
+Equal times (the halves of a split) evict the lower cluster id first.
+
 Sec. VII-B ("Overlap-Aware Prefetch"): while layer l runs, its query predicts the
 top-K clusters of layer l+1 and they are fetched ahead; at layer l+1 the actual query
 verifies the prediction and whatever is still missing is fetched on demand (the
@@ -25,13 +34,32 @@ class CapacityError(Exception):
     """The clusters of one call cannot be resident together."""
 
 
+def membership_from_sizes(sizes) -> dict:
+    """Clusters with the given frame counts as disjoint frame lists (cluster c owns frames
+    1000*c .. 1000*c + sizes[c] - 1): enough when membership never changes except by growth."""
+    items = sizes.items() if isinstance(sizes, dict) else enumerate(sizes)
+    return {int(c): [1000 * int(c) + i for i in range(int(n))] for c, n in items}
+
+
+def membership_from_assignments(assign, buf_frames=(), n_clusters=None) -> dict:
+    """Cluster -> ascending frame list from a frame -> cluster array (negative = in no cluster);
+    buffered singletons (Alg. 1, line 10) are entries n_clusters + b holding their one frame."""
+    mem: dict = {}
+    for f, c in enumerate(assign):
+        if c >= 0:
+            mem.setdefault(int(c), []).append(f)
+    for b, f in enumerate(buf_frames):
+        mem[int(n_clusters) + b] = [int(f)]
+    return mem
+
+
 @dataclass
 class ClusterCacheModel:
     capacity_pages: int
     max_clusters: int
-    pages: dict = field(default_factory=dict)        # cluster -> pages resident
-    stamp: dict = field(default_factory=dict)        # cluster -> time of last use
-    by_prefetch: dict = field(default_factory=dict)  # cluster -> fetched ahead and not used yet
+    cached: set = field(default_factory=set)         # frames whose page is in the GPU cache
+    fstamp: dict = field(default_factory=dict)       # frame -> time of last use
+    ahead: set = field(default_factory=set)          # frames fetched by a prefetch and not used since
     clock: int = 0
     hits: int = 0
     misses: int = 0
@@ -40,49 +68,66 @@ class ClusterCacheModel:
     prefetch_fetched: int = 0
     prefetch_useful: int = 0
 
+    # -- cluster-level views of the per-frame state -----------------------------------
+    def have(self, frames) -> int:
+        return sum(1 for f in frames if f in self.cached)
+
+    def directory(self, membership) -> dict:
+        """cluster -> frames of it that are cached, for the clusters that have any"""
+        out = {}
+        for c, frames in membership.items():
+            h = self.have(frames)
+            if h:
+                out[c] = h
+        return out
+
+    def stamp(self, frames) -> int:
+        return max((self.fstamp.get(f, 0) for f in frames if f in self.cached), default=0)
+
     def used(self) -> int:
-        return sum(self.pages.values())
+        return len(self.cached)
 
-    def complete(self, c: int, sizes) -> bool:
-        return c in self.pages and self.pages[c] == int(sizes[c])
-
-    def access(self, ids, sizes, prefetch: bool = False):
-        """Make clusters `ids` (in this order) resident; sizes[c] = frames of cluster c now.
+    def access(self, ids, membership, prefetch: bool = False):
+        """Make clusters `ids` (in this order) resident.  membership: cluster -> frame list of
+        EVERY cluster of the unit as it is now (what may be evicted is decided over all of them).
         Returns [(cluster, pages moved host-to-device), ...] for the clusters that needed data.
         A retrieval counts a hit for a cluster found complete and a miss otherwise; a prefetch
         counts neither, only what it had to fetch.  Raises CapacityError, leaving everything as
         it was, if the clusters of the call cannot be resident together."""
         ids = [int(c) for c in ids]
-        if sum(int(sizes[c]) for c in ids) > self.capacity_pages or len(ids) > max(self.max_clusters, 1):
+        if sum(len(membership[c]) for c in ids) > self.capacity_pages or len(ids) > max(self.max_clusters, 1):
             raise CapacityError(ids)
         moved = []
         for c in ids:
-            want = int(sizes[c])
-            have = self.pages.get(c, 0)
-            done = c in self.pages and have == want
+            frames = membership[c]
+            want, have = len(frames), self.have(frames)
+            done = have == want
             if prefetch:
                 if not done:
                     self.prefetch_fetched += 1
-                    self.by_prefetch[c] = True
+                    self.ahead.update(frames)
             else:
                 if done:
                     self.hits += 1
-                    self.prefetch_useful += bool(self.by_prefetch.get(c))
+                    self.prefetch_useful += any(f in self.ahead for f in frames)
                 else:
                     self.misses += 1
-                self.by_prefetch[c] = False
-            while self.capacity_pages - self.used() < want - have or \
-                    (c not in self.pages and len(self.pages) >= self.max_clusters):
-                victim = min((j for j in self.pages if j not in ids), key=lambda j: self.stamp[j])
-                del self.pages[victim]
-                self.by_prefetch[victim] = False
+                self.ahead.difference_update(frames)
+            while self.capacity_pages - len(self.cached) < want - have or \
+                    (have == 0 and len(self.directory(membership)) >= self.max_clusters):
+                victims = [j for j in sorted(membership) if j not in ids and self.have(membership[j]) > 0]
+                victim = min(victims, key=lambda j: self.stamp(membership[j]))      # first lowest: lowest id on ties
+                self.cached.difference_update(membership[victim])
+                self.ahead.difference_update(membership[victim])
                 self.evictions += 1
-            self.pages[c] = want
             self.clock += 1
-            self.stamp[c] = self.clock
+            for f in frames:
+                self.cached.add(f)
+                self.fstamp[f] = self.clock
             self.pages_moved += want - have
             if want > have:
                 moved.append((c, want - have))
+            have = want
         return moved
 
 
@@ -96,13 +141,13 @@ def prefetch_round(unit, cache: ClusterCacheModel, q_proxy, q_actual, h: int, G:
     (2) actual = top-K under the actual query; (3) completion = the actual clusters that are not
     complete in the cache after (1), fetched on demand.  Returns dict(predicted, prefetched,
     actual, completion): id lists, `prefetched` / `completion` as [(cluster, pages)]."""
-    sizes = unit.sizes()
+    membership = membership_from_assignments(unit.assignments())
     predicted, prefetched = [], []
     if q_proxy is not None:
         ids_p, _, _, _ = unit.retrieve(q_proxy, h, G, top_k)
         predicted = [int(c) for c in (ids_p[:prefetch_top_k] if prefetch_top_k > 0 else ids_p)]
-        prefetched = cache.access(predicted, sizes, prefetch=True)
+        prefetched = cache.access(predicted, membership, prefetch=True)
     ids_a, _, _, _ = unit.retrieve(q_actual, h, G, top_k)
     actual = [int(c) for c in ids_a]
-    completion = cache.access(actual, sizes, prefetch=False)
+    completion = cache.access(actual, membership, prefetch=False)
     return dict(predicted=predicted, prefetched=prefetched, actual=actual, completion=completion)

@@ -57,6 +57,7 @@ typedef struct {
     double *var;           /* [C] running intra-cluster variance (Eq. 2 / Eq. 4) */
     int *lazy;             /* [C] lazy-split flag */
     int *resident;         /* [C] 1 = the cluster's contents are on the GPU */
+    int resident_external; /* 1 = the caller says what is on the GPU (a cache model); retrieval leaves the flags alone */
     int *buf_frame, *buf_owner;    /* GPU-side buffer of singletons: frame, owning cluster */
     int n_buf;
     long n_split_now, n_split_deferred, n_deferred, n_forced_absorb;
@@ -263,6 +264,17 @@ int orc_unit_set_maintainer(orc_unit *u, int mode, int c_init, double tau_min,
     return 0;
 }
 
+/* "C is in GPU memory" (Alg. 1 line 4) decided outside: with an offloading tier the clusters that
+ * are on the GPU are those its working set holds (see oracle/cache_model.py).  After
+ * orc_unit_external_residency(u, 1) the retrieval procedure no longer marks its selection as
+ * resident; the caller sets the flags with orc_unit_set_resident (flags [C], copied).  A split
+ * still hands the parent's flag to the new cluster. */
+void orc_unit_external_residency(orc_unit *u, int on) { u->resident_external = on != 0; }
+void orc_unit_set_resident(orc_unit *u, const int *flags)
+{
+    if (u->maint_mode) memcpy(u->resident, flags, (size_t)u->C * sizeof(int));
+}
+
 /* Size-adaptive threshold, Eq. 5. */
 double orc_tau(double tau_min, double tau_max, double n0, double N)
 {
@@ -466,8 +478,10 @@ int orc_unit_retrieve_maintained(orc_unit *u, const double *qbar, int k, int *id
     }
     *n_tok = m;
     if (u->maint_mode == 2) {
-        memset(u->resident, 0, (size_t)C * sizeof(int));
-        for (int i = 0; i < kept; ++i) if (ids[i] < C) u->resident[ids[i]] = 1;
+        if (!u->resident_external) {
+            memset(u->resident, 0, (size_t)C * sizeof(int));
+            for (int i = 0; i < kept; ++i) if (ids[i] < C) u->resident[ids[i]] = 1;
+        }
         for (int i = 0; i < kept; ++i) if (ids[i] < C) materialize(u, ids[i]);
     }
     return kept;

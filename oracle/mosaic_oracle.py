@@ -70,6 +70,8 @@ def lib():
         L.orc_unit_set_maintainer.restype = C.c_int
         L.orc_unit_set_maintainer.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_double,
                                               C.c_double, C.c_int, C.c_int]
+        L.orc_unit_external_residency.argtypes = [C.c_void_p, C.c_int]
+        L.orc_unit_set_resident.argtypes = [C.c_void_p, _ip]
         L.orc_tau.restype = C.c_double
         L.orc_tau.argtypes = [C.c_double] * 4
         L.orc_unit_retrieve_maintained.restype = C.c_int
@@ -309,6 +311,15 @@ class OracleUnit:
 
     def resident_flags(self) -> np.ndarray:
         return np.ctypeslib.as_array(self._L.orc_unit_resident(self._u), shape=(self.C,)).copy()
+
+    def external_residency(self, on: bool = True):
+        """The caller decides which clusters are "in GPU memory" (Alg. 1 line 4), e.g. from a cache model."""
+        self._L.orc_unit_external_residency(self._u, int(on))
+
+    def set_resident(self, flags):
+        flags = np.ascontiguousarray(flags, dtype=np.int32)
+        assert flags.shape == (self.C,)
+        self._L.orc_unit_set_resident(self._u, _i(flags))
 
     def buffer(self):
         """-> (frames, owning clusters) of the buffered singletons"""

@@ -58,7 +58,8 @@ struct Layout {
         tok_scratch, part_o, part_ml, stage_k, stage_v, dest, var, lazy, resident, n_slots, buf_frame,
         buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, vsumm, rvsum, rep_k, rep_v, aug_o, aug_ml,
         vemb, vr, vrn, vn, part, pr, prn, pn, pscores, pids, n_pids, total;
-    size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_moves, host_nmoves, host_assign, host_dest, host_total;   // offsets into the pinned host arena
+    size_t host_k, host_v, host_sel, host_nsel, host_ids, host_nids, host_moves, host_nmoves, host_assign, host_dest,
+        host_assign_full, host_cnt, host_nbuf, host_buf_frame, host_buf_owner, host_resident, host_total;   // offsets into the pinned host arena
     long long part_entries;
     int Tp, impl, v_transposed;
     int nt_max;
@@ -97,7 +98,6 @@ int check_config(const mosaic_config *c, std::string &why) {
     if (c->warmup_frames < 0 || c->lloyd_iters < 0 || c->recluster_every < 0 || c->max_q_tokens < 0) { why = "negative count"; return MOSAIC_EINVAL; }
     if (c->maint_mode < MOSAIC_MAINT_OFF || c->maint_mode > MOSAIC_MAINT_DEFERRED) { why = "maint_mode out of range"; return MOSAIC_EINVAL; }
     if (c->maint_mode != MOSAIC_MAINT_OFF) {
-        if (c->tier != MOSAIC_TIER_HBM) { why = "the maintainer is available in the HBM tier only"; return MOSAIC_EINVAL; }
         if (c->recluster_every != 0) { why = "the maintainer and periodic re-clustering exclude each other"; return MOSAIC_EINVAL; }
         if (c->init_clusters < 0 || c->init_clusters > c->n_clusters) { why = "init_clusters must be in 0..n_clusters"; return MOSAIC_EINVAL; }
         if (c->split_iters < 0 || c->buffer_max < 0) { why = "negative maintainer count"; return MOSAIC_EINVAL; }
@@ -239,6 +239,13 @@ Layout make_layout(const mosaic_config &c) {
         L.host_nmoves = htake(U * 4);
         L.host_assign = htake(U * (size_t)L.SN * 4);  // assignments of a staged batch on their way back
         L.host_dest = htake(U * (size_t)L.SN * 4);    // their slab positions on their way to the device
+        // maintainer on the host tier: what the host reads back to follow splits, and the residency flags it sends
+        L.host_assign_full = htake(mt ? U * F * 4 : 0);
+        L.host_cnt = htake(mt ? U * 4 * 8 : 0);
+        L.host_nbuf = htake(mt ? U * 4 : 0);
+        L.host_buf_frame = htake(mt ? U * B * 4 : 0);
+        L.host_buf_owner = htake(mt ? U * B * 4 : 0);
+        L.host_resident = htake(mt ? U * C * 4 : 0);
         L.host_total = ho;
     } else {
         L.host_total = 0;
@@ -426,12 +433,18 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
         ctx->h_nmoves = (int *)((char *)cfg->host_arena + L.host_nmoves);
         ctx->h_assign = (int *)((char *)cfg->host_arena + L.host_assign);
         ctx->h_dest = (int *)((char *)cfg->host_arena + L.host_dest);
+        ctx->h_assign_full = (int *)((char *)cfg->host_arena + L.host_assign_full);
+        ctx->h_cnt = (long long *)((char *)cfg->host_arena + L.host_cnt);
+        ctx->h_nbuf = (int *)((char *)cfg->host_arena + L.host_nbuf);
+        ctx->h_buf_frame = (int *)((char *)cfg->host_arena + L.host_buf_frame);
+        ctx->h_buf_owner = (int *)((char *)cfg->host_arena + L.host_buf_owner);
+        ctx->h_resident = (int *)((char *)cfg->host_arena + L.host_resident);
         dv.moves = (const int *)((char *)dptr + L.host_moves);
         dv.n_moves = (const int *)((char *)dptr + L.host_nmoves);
         HostTier *ht = new (std::nothrow) HostTier();
         if (!ht) return bail(MOSAIC_ENOMEM, "host allocation failed");
         ctx->host = ht;
-        ht->init(dv.U, dv.C, dv.F, L.SF, L.slabs_per_unit, L.PU, L.max_clusters, dv.k, L.kpage, L.vpage);
+        ht->init(dv.U, dv.C, dv.C + L.buf_max, dv.F, L.SF, L.slabs_per_unit, L.PU, L.max_clusters, dv.k, L.kpage, L.vpage);
         // default-priority streams for selection and for the fetches
         // two internal streams only: selection (+ value fetches) and key fetches
         if ((e = hipStreamCreateWithFlags(&ht->sel_stream, hipStreamNonBlocking)) != hipSuccess ||
@@ -509,8 +522,69 @@ int32_t mosaic_reset(mosaic_ctx *ctx) {
     return MOSAIC_OK;
 }
 
+// Host tier + deferred-split maintainer: "C is in GPU memory" (Alg. 1 line 4) = the GPU cluster cache
+// holds frames of C.  Send the flags of the units whose directory changed since the last time.
+static int upload_residency(mosaic_ctx *ctx) {
+    const DeviceView &dv = ctx->dv;
+    HostTier *ht = ctx->host;
+    if (!ht || dv.maint_mode != MOSAIC_MAINT_DEFERRED) return MOSAIC_OK;
+    for (int u = 0; u < dv.U; ++u) {
+        HostTier::Unit &un = ht->units[u];
+        if (!un.resident_dirty) continue;
+        int *fl = ctx->h_resident + (size_t)u * dv.C;
+        for (int c = 0; c < dv.C; ++c) fl[c] = un.cached[c] > 0;
+        const hipError_t e = hipMemcpyAsync(dv.resident + (size_t)u * dv.C, fl, (size_t)dv.C * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "residency flags upload");
+        un.resident_dirty = false;
+    }
+    return MOSAIC_OK;
+}
+
+// Host tier + maintainer: bring the host's frame lists of units [u0, u0 + nu) up to date after device
+// work on `s` that may have changed membership (splits on insertion, deferred splits carried out,
+// states buffered or released).  The counters and the buffer are small and always read; a unit's whole
+// frame -> cluster map only when they say that something moved.  Waits for `s`.
+static int follow_membership(mosaic_ctx *ctx, int u0, int nu, hipStream_t s) {
+    const DeviceView &dv = ctx->dv;
+    HostTier *ht = ctx->host;
+    const size_t B = (size_t)dv.buf_max;
+    hipError_t e;
+    if ((e = hipMemcpyAsync(ctx->h_cnt + (size_t)u0 * 4, dv.mt_cnt + (size_t)u0 * 4, (size_t)nu * 4 * 8, hipMemcpyDeviceToHost, s)) != hipSuccess ||
+        (e = hipMemcpyAsync(ctx->h_nbuf + u0, dv.n_buf + u0, (size_t)nu * 4, hipMemcpyDeviceToHost, s)) != hipSuccess)
+        return fail_hip(ctx, e, "maintainer counters read-back");
+    if (B && ((e = hipMemcpyAsync(ctx->h_buf_frame + (size_t)u0 * B, dv.buf_frame + (size_t)u0 * B, (size_t)nu * B * 4, hipMemcpyDeviceToHost, s)) != hipSuccess))
+        return fail_hip(ctx, e, "singleton buffer read-back");
+    if ((e = hipStreamSynchronize(s)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+    const size_t nf = (size_t)ctx->n_frames;
+    bool any = false;
+    for (int u = u0; u < u0 + nu; ++u) {
+        const bool moved = ctx->h_cnt[(size_t)u * 4] != ht->seen_splits[(size_t)u * 2] ||
+                           ctx->h_cnt[(size_t)u * 4 + 1] != ht->seen_splits[(size_t)u * 2 + 1] ||
+                           ctx->h_nbuf[u] != ht->seen_nbuf[u];
+        if (!moved) continue;
+        any = true;
+        if ((e = hipMemcpyAsync(ctx->h_assign_full + (size_t)u * dv.F, dv.assign + (size_t)u * dv.F, nf * 4, hipMemcpyDeviceToHost, s)) != hipSuccess)
+            return fail_hip(ctx, e, "frame map read-back");
+    }
+    if (!any) return MOSAIC_OK;
+    if ((e = hipStreamSynchronize(s)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+    for (int u = u0; u < u0 + nu; ++u) {
+        const bool moved = ctx->h_cnt[(size_t)u * 4] != ht->seen_splits[(size_t)u * 2] ||
+                           ctx->h_cnt[(size_t)u * 4 + 1] != ht->seen_splits[(size_t)u * 2 + 1] ||
+                           ctx->h_nbuf[u] != ht->seen_nbuf[u];
+        if (!moved) continue;
+        const int nb = std::min<int>(ctx->h_nbuf[u], (int)B);
+        ht->rebuild(u, ctx->h_assign_full + (size_t)u * dv.F, (int)nf, ctx->h_buf_frame + (size_t)u * B, nb);
+        ht->seen_splits[(size_t)u * 2] = ctx->h_cnt[(size_t)u * 4];
+        ht->seen_splits[(size_t)u * 2 + 1] = ctx->h_cnt[(size_t)u * 4 + 1];
+        ht->seen_nbuf[u] = ctx->h_nbuf[u];
+    }
+    return MOSAIC_OK;
+}
+
 // Host tier: read back the assignments of staged frames f0..f1-1, give every
 // page its slab position, and store the pages into pinned host memory.
+// (ctx->n_frames must already count the frames up to f1.)
 static int offload_range(mosaic_ctx *ctx, int f0, int f1) {
     const DeviceView &dv = ctx->dv;
     HostTier *ht = ctx->host;
@@ -529,15 +603,18 @@ static int offload_range(mosaic_ctx *ctx, int f0, int f1) {
     if ((e = hipStreamSynchronize(ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
     for (int fl = 0; fl < n; ++fl)
         for (int u = 0; u < dv.U; ++u) {
-            const int c = a[(size_t)u * n + fl];
-            if (c < 0 || c >= dv.C) return fail(ctx, MOSAIC_EHIP, "assignment read-back returned an invalid cluster id");
-            const int hp = ht->append(u, f0 + fl, c);
+            // a state held in the singleton buffer (-2 - owner) is filed with its owner's pages
+            const int c = a[(size_t)u * n + fl], filed = c >= 0 ? c : -2 - c;
+            if (filed < 0 || filed >= dv.C) return fail(ctx, MOSAIC_EHIP, "assignment read-back returned an invalid cluster id");
+            const int hp = ht->place(u, f0 + fl, filed);
             if (hp < 0) return fail(ctx, MOSAIC_ECAPACITY, "host slab pool exhausted");
             dest[(size_t)u * dv.SN + fl] = hp;
+            if (c >= 0) ht->join(u, f0 + fl, c);     // (units whose membership moved are rebuilt below)
         }
     e = hipMemcpyAsync(dv.dest, dest, (size_t)dv.U * dv.SN * 4, hipMemcpyHostToDevice, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "slab table upload");
     if ((e = launch_offload(dv, f0, n, ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "offload launch");
+    if (dv.maint_mode) return follow_membership(ctx, 0, dv.U, ctx->stream);
     return MOSAIC_OK;
 }
 
@@ -551,6 +628,7 @@ static int ingest_host(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, in
     hipError_t e;
     int rc;
     while (f < end) {
+        if ((rc = upload_residency(ctx)) != MOSAIC_OK) return rc;
         // warm-up frames stay in the staging ring (SN >= W); afterwards batches of <= 64
         const int nb = (int)(f < W ? std::min(end, W) - f : std::min<long long>(end - f, 64));
         e = launch_store_summary(dv, (const char *)k_dev + done * frame_bytes,
@@ -562,11 +640,13 @@ static int ingest_host(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, in
                 if ((e = launch_lloyd(dv, (int)W, ctx->iters, true, ctx->stream)) != hipSuccess)
                     return fail_hip(ctx, e, "initial clustering launch");
                 ctx->stats.lloyd_runs += 1;
+                ctx->n_frames = f;
                 if ((rc = offload_range(ctx, 0, (int)W)) != MOSAIC_OK) return rc;
             }
         } else {
             if ((e = launch_assign_update(dv, (int)f, (int)f + nb, ctx->stream)) != hipSuccess)
                 return fail_hip(ctx, e, "assign_update launch");
+            ctx->n_frames = f + nb;
             if ((rc = offload_range(ctx, (int)f, (int)f + nb)) != MOSAIC_OK) return rc;
             f += nb;
         }
@@ -714,8 +794,13 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq, 
     // (and the representatives by the last ingest): mark the stream, wait for the mark
     if ((e = hipEventRecord(ht->main_mark, ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     if ((e = hipStreamWaitEvent(ht->sel_stream, ht->main_mark, 0)) != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
-    if ((e = launch_retrieve(dv, u0, nu, q_dev, Tq, (int)ctx->n_frames, ctx->cfg.score_mode, false,
-                             ht->sel_stream)) != hipSuccess) return fail_hip(ctx, e, "retrieve launch");
+    // Alg. 1, retrieval procedure: with the deferred-split maintainer the buffered singletons take part
+    // in the selection and the selected clusters' deferred splits are carried out by the same kernel
+    // (a prefetch only predicts: clusters alone, nothing changes)
+    const bool deferred = dv.maint_mode == MOSAIC_MAINT_DEFERRED && !prefetch;
+    e = deferred ? launch_retrieve_deferred(dv, u0, nu, q_dev, Tq, (int)ctx->n_frames, ctx->cfg.score_mode, ht->sel_stream)
+                 : launch_retrieve(dv, u0, nu, q_dev, Tq, (int)ctx->n_frames, ctx->cfg.score_mode, false, ht->sel_stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "retrieve launch");
     int *ids = ctx->h_ids + (size_t)u0 * k, *nids = ctx->h_nids + u0;
     if ((e = hipMemcpyAsync(ids, dv.ids + (size_t)u0 * k, (size_t)nu * k * 4, hipMemcpyDeviceToHost, ht->sel_stream)) != hipSuccess ||
         (e = hipMemcpyAsync(nids, dv.n_ids + u0, (size_t)nu * 4, hipMemcpyDeviceToHost, ht->sel_stream)) != hipSuccess)
@@ -747,6 +832,10 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq, 
                  u0 + i, ht->fail_sel_pages, n_take_of(i), dv.PU, ht->max_clusters);
         if (b0) ht->busy_used -= 2;
         ctx->sel_epoch[layer] = -1;          // whatever selection the layer had is no longer current
+        if (deferred) {                      // the kernel has carried out its deferred splits all the same
+            const int rc2 = follow_membership(ctx, u0, nu, ht->sel_stream);
+            if (rc2 != MOSAIC_OK) return rc2;
+        }
         return fail(ctx, MOSAIC_ECAPACITY, b);
     }
     int max_moves = 0;
@@ -786,6 +875,8 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq, 
     if (b1) (void)hipEventRecord(b1, ht->copy_stream);
     if ((e = hipEventRecord(ht->ready[layer], ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     ht->ready_recorded[layer] = 1;
+    // the query saw the clusters as they were; now follow what the kernel's deferred splits changed
+    if (deferred) return follow_membership(ctx, u0, nu, ht->sel_stream);
     return MOSAIC_OK;
 }
 
@@ -1050,6 +1141,10 @@ int32_t mosaic_get_maintainer(mosaic_ctx *ctx, double *var, int32_t *lazy, int32
     if (!ctx) return MOSAIC_EINVAL;
     const DeviceView &dv = ctx->dv;
     if (!dv.maint_mode) return fail(ctx, MOSAIC_EINVAL, "the maintainer is off (maint_mode = MOSAIC_MAINT_OFF)");
+    {   // (host tier: the residency flags follow the cache directory; send what is pending)
+        const int rc0 = upload_residency(ctx);
+        if (rc0 != MOSAIC_OK) return rc0;
+    }
     const size_t UC = (size_t)dv.U * dv.C, UB = (size_t)dv.U * dv.buf_max;
     int rc;
     if (var && (rc = d2h(ctx, var, dv.var, UC * 8)) != MOSAIC_OK) return rc;
@@ -1126,15 +1221,13 @@ int32_t mosaic_get_selection(mosaic_ctx *ctx, int32_t layer, int32_t *ids, int32
         if ((rc = sync(ctx)) != MOSAIC_OK) return rc;
         for (int h = 0; h < H; ++h) {
             const HostTier::Unit &un = ht->units[u0 + h];
-            int64_t m = 0;
-            for (int i = 0; i < un.n_last; ++i) m += (int64_t)un.n[un.last_ids[i]] * dv.T;
+            const int64_t m = (int64_t)un.n_last_frames * dv.T;     // the frames the query was given, in gather order
             if (n_tok) n_tok[h] = (int32_t)m;
             if (!tok_idx) continue;
             if (m > tok_cap) return fail(ctx, MOSAIC_ECAPACITY, "tok_cap too small for the retrieved token list");
             int32_t *o = tok_idx + (size_t)h * tok_cap;
-            for (int i = 0; i < un.n_last; ++i)
-                for (int f = un.head_f[un.last_ids[i]]; f >= 0; f = un.next_f[f])
-                    for (int t = 0; t < dv.T; ++t) *o++ = f * dv.T + t;
+            for (int i = 0; i < un.n_last_frames; ++i)
+                for (int t = 0; t < dv.T; ++t) *o++ = un.last_frames[i] * dv.T + t;
         }
         return MOSAIC_OK;
     }
@@ -1165,7 +1258,7 @@ int32_t mosaic_get_cache_directory(mosaic_ctx *ctx, int32_t *cached_pages) {
     const DeviceView &dv = ctx->dv;
     for (int u = 0; u < dv.U; ++u) {
         const HostTier::Unit &un = ctx->host->units[u];
-        for (int c = 0; c < dv.C; ++c) cached_pages[(size_t)u * dv.C + c] = un.present[c] ? un.cached[c] : -1;
+        for (int c = 0; c < dv.C; ++c) cached_pages[(size_t)u * dv.C + c] = un.cached[c] > 0 ? un.cached[c] : -1;
     }
     return MOSAIC_OK;
 }

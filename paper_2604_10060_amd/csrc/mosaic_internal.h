@@ -128,6 +128,10 @@ struct Ctx {
     int *h_moves, *h_nmoves; // fetch work lists, [U][F][2] / [U]
     int *h_ids, *h_nids; // selections read back, [U][k] / [U]
     int *h_assign, *h_dest; // staged batch: assignments read back / slab positions, [U][SN]
+    int *h_assign_full;      // maintainer: a unit's whole frame -> cluster map read back, [U][F]
+    long long *h_cnt;        // ... its counters, [U][4]
+    int *h_nbuf, *h_buf_frame, *h_buf_owner;   // ... its singleton buffer, [U] / [U][buf_max]
+    int *h_resident;         // residency flags on their way to the device, [U][C]
     // profiling
     bool profile;
     std::vector<hipEvent_t> ev;      // pool of pairs, created by mosaic_profile_enable

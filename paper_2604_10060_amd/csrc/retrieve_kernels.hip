@@ -396,8 +396,10 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve_deferred(DeviceView dv,
         const int rk = rank_sh[C + b];
         if (rk >= 0) sel[off_sh[rk]] = buf_frame[b];
     }
-    // the selection is what is on the GPU from now on
-    for (int j = tid; j < C; j += BLK) dv.resident[(size_t)u * C + j] = rank_sh[j] >= 0;
+    // the selection is what is on the GPU from now on (host tier: the host sends the flags of its
+    // cluster cache's directory instead)
+    if (dv.tier == MOSAIC_TIER_HBM)
+        for (int j = tid; j < C; j += BLK) dv.resident[(size_t)u * C + j] = rank_sh[j] >= 0;
     __syncthreads();
     // deferred splits of the selected clusters
     for (int i = 0; i < n_ids; ++i) {

@@ -17,6 +17,7 @@ from dataclasses import dataclass, field
 import numpy as np
 import torch
 
+from oracle import cache_model
 from oracle import mosaic_oracle as orc
 from paper_2604_10060_amd import binding, inputs
 
@@ -362,25 +363,67 @@ def _oracle_ingest_tracking(o, k_frame, min_gap, key):
         min_gap[key] = min(min_gap.get(key, np.inf), g)
 
 
+def oracle_membership(o):
+    """cluster (and buffered-singleton entry) -> frames, for the working-set model"""
+    fr, _ = o.buffer() if o.maintainer else (np.empty(0, np.int32), None)
+    return cache_model.membership_from_assignments(o.assignments(), fr, o.C)
+
+
+def sync_residency(oracles, models, m=None, wl=None, where=""):
+    """Host tier: what counts as "in GPU memory" (Alg. 1 line 4) is what the working-set model holds.
+    Hand every oracle unit its model's residency flags (they apply from the next library call on) and,
+    if `m` is given, compare the library's cache directory with the model's."""
+    d = m.cache_directory() if m is not None else None
+    for (l, h), o in oracles.items():
+        if not o.ready:
+            continue
+        have = models[(l, h)].directory(oracle_membership(o))
+        flags = np.zeros(o.C, dtype=np.int32)
+        want_dir = np.full(o.C, -1, dtype=np.int32)
+        for c, n in have.items():
+            if c < o.C:
+                flags[c] = 1
+                want_dir[c] = n
+        if o.maintainer and o.maintainer["mode"] == 2:
+            o.set_resident(flags)
+        if d is not None:
+            np.testing.assert_array_equal(d[l * wl.n_kv_heads + h], want_dir,
+                                          err_msg=f"unit {(l, h)} {where}: cache directory differs from the model")
+
+
 def run_maintained(wl, mt: dict, units=None, device="cuda:0", batch_pattern=(1, 3, 8, 2, 16),
-                   query_every=0, n_final_queries=2, question_tokens=None):
+                   query_every=0, n_final_queries=2, question_tokens=None, host=None):
     """Stream `wl` through the library with the maintainer on and through oracle units with the
     same parameters; compare the whole state after every library call.  query_every > 0 issues a
     retrieve + attend every that many frames (in deferred mode this is what makes clusters
-    resident and carries out deferred splits), compared like the plain query path."""
+    resident and carries out deferred splits), compared like the plain query path.
+    host = dict(slab_frames=.., cache_pages_per_unit=.., cache_fraction=..) runs the host tier: a
+    cluster is then "in GPU memory" while the GPU cluster cache holds frames of it, which the oracle
+    side takes from the working-set model (oracle/cache_model.py), fed the oracle's own selections
+    and memberships; the library's cache directory is compared with the model's after every call."""
     st = inputs.SceneStream(wl)
     K, V = st.frames(0, wl.n_frames)
     Kd, Vd = K.to(device), V.to(device)
-    m = binding.Mosaic(binding.config_for(wl, warmup_frames=0, **maintainer_overrides(mt)), device=device)
+    over = dict(maintainer_overrides(mt))
+    if host:
+        over.update(tier=binding.TIER_HOST, **host)
+    m = binding.Mosaic(binding.config_for(wl, warmup_frames=0, **over), device=device)
     rep = Report()
     if units is None:
         units = [(l, h) for l in range(wl.n_layers) for h in range(wl.n_kv_heads)]
     F = wl.n_frames
-    oracles, Kcpu, min_gap = {}, {}, {}
+    oracles, Kcpu, min_gap, models = {}, {}, {}, None
     for (l, h) in units:
         oracles[(l, h)] = orc.OracleUnit(wl.n_clusters, wl.head_dim, wl.tokens_per_frame, F, 0,
                                          wl.lloyd_iters, 0, maintainer=mt)
         Kcpu[(l, h)] = inputs.unit_pages(K, l, h)
+    if host:
+        assert len(units) == wl.n_layers * wl.n_kv_heads
+        max_clusters = max(wl.top_k, int(np.float32(host.get("cache_fraction", 0.10)) * np.float32(wl.n_clusters)))
+        models = {key: cache_model.ClusterCacheModel(min(host["cache_pages_per_unit"], F), max_clusters) for key in units}
+        for o in oracles.values():
+            if mt["mode"] == 2:
+                o.external_residency(True)
     Tq = question_tokens or wl.question_tokens
     tag = 0
 
@@ -388,7 +431,9 @@ def run_maintained(wl, mt: dict, units=None, device="cuda:0", batch_pattern=(1, 
         nonlocal tag
         q = st.question(st.draw_scene(), n_tok, tag).to(device)
         tag += 1
-        query_maintained_with_parity(m, wl, q, oracles, K, V, rep, mt)
+        query_maintained_with_parity(m, wl, q, oracles, K, V, rep, mt, models)
+        if models:
+            sync_residency(oracles, models, m, wl, f"after query {tag}")
         compare_maintained_state(m, wl, oracles, f"after query {tag}", {})
 
     f, bi, next_q = 0, 0, query_every
@@ -406,6 +451,8 @@ def run_maintained(wl, mt: dict, units=None, device="cuda:0", batch_pattern=(1, 
                 _oracle_ingest_tracking(o, Kcpu[key][ff], min_gap, key)
         f += nb
         if f >= W:
+            if models:
+                sync_residency(oracles, models, m, wl, f"after {f} frames")
             compare_maintained_state(m, wl, oracles, f"after {f} frames", min_gap)
             min_gap.clear()
         if query_every and f >= next_q and f >= W:
@@ -421,12 +468,20 @@ def run_maintained(wl, mt: dict, units=None, device="cuda:0", batch_pattern=(1, 
     if len(units) == wl.n_layers * wl.n_kv_heads:
         assert (s.splits_immediate, s.splits_deferred, s.deferred_inserts, s.forced_absorbs) == \
             (tot["split_now"], tot["split_deferred"], tot["deferred"], tot["forced_absorb"])
+    if models:
+        tot["cache"] = {name: sum(getattr(x, name) for x in models.values())
+                        for name in ("hits", "misses", "evictions", "pages_moved")}
+        assert (s.cache_hits, s.cache_misses) == (tot["cache"]["hits"], tot["cache"]["misses"])
+        page_bytes = 2 * wl.tokens_per_frame * wl.head_dim * (4 if wl.kv_dtype == "fp32" else 2)
+        if wl.kv_dtype == "bf16":          # (value pages are padded to whole 32-token chunks)
+            page_bytes = (wl.tokens_per_frame + (wl.tokens_per_frame + 31) // 32 * 32) * wl.head_dim * 2
+        assert s.h2d_bytes == tot["cache"]["pages_moved"] * page_bytes
     rep.notes.append(tot)
     m.close()
     return rep
 
 
-def query_maintained_with_parity(m, wl, q, oracles, K, V, rep, mt):
+def query_maintained_with_parity(m, wl, q, oracles, K, V, rep, mt, models=None):
     """Like query_with_parity for a context with the maintainer on: in deferred mode the
     representative set includes the buffered singletons (ids >= n_clusters) and the call changes
     the clustering state (residency, deferred splits), on both sides."""
@@ -448,10 +503,13 @@ def query_maintained_with_parity(m, wl, q, oracles, K, V, rep, mt):
         ids, n_ids, scores, toks = sel_cache[l]
         nb_before = o.n_buf
         sizes_before = o.sizes()
+        mem_before = oracle_membership(o) if models else None
         if mt["mode"] == 2:
             ids_o, sc_o, tok_o, gap = o.retrieve_maintained(q_h[l], h, G, wl.top_k)
         else:
             ids_o, sc_o, tok_o, gap = o.retrieve(q_h[l], h, G, wl.top_k)
+        if models:       # the query is served from the clusters as they were before its deferred splits
+            models[(l, h)].access(ids_o, mem_before)
         live = np.concatenate([sizes_before > 0, np.ones(nb_before, bool)]) if mt["mode"] == 2 else sizes_before > 0
         got_sc = scores[h][: len(live)]
         np.testing.assert_allclose(got_sc[live], sc_o[: len(live)][live], rtol=1e-9, atol=1e-12)

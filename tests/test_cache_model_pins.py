@@ -27,17 +27,18 @@ def test_hand_worked_lru_trace():
         ids = [int(x) for x in ids.split(",")]
         if step == "6":
             sizes[2] = 6
+        mem = cm.membership_from_sizes(sizes)
         if moved == "refused":
-            before = (dict(m.pages), dict(m.stamp), m.hits, m.misses, m.evictions, m.pages_moved)
+            before = (set(m.cached), dict(m.fstamp), m.hits, m.misses, m.evictions, m.pages_moved)
             with pytest.raises(cm.CapacityError):
-                m.access(ids, sizes, prefetch=(op == "prefetch"))
-            assert before == (dict(m.pages), dict(m.stamp), m.hits, m.misses, m.evictions, m.pages_moved)
+                m.access(ids, mem, prefetch=(op == "prefetch"))
+            assert before == (set(m.cached), dict(m.fstamp), m.hits, m.misses, m.evictions, m.pages_moved)
         else:
-            got = m.access(ids, sizes, prefetch=(op == "prefetch"))
+            got = m.access(ids, mem, prefetch=(op == "prefetch"))
             assert dict(got) == _pairs(moved), f"step {step}: moved {got}"
         want = [int(x) for x in counts.split()]
         assert [m.hits, m.misses, m.evictions, m.prefetch_fetched, m.prefetch_useful, m.pages_moved] == want, f"step {step}"
-        assert m.pages == _pairs(resident), f"step {step}: resident {m.pages}"
+        assert m.directory(mem) == _pairs(resident), f"step {step}: resident {m.directory(mem)}"
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -53,17 +54,18 @@ def test_cache_model_invariants_on_random_traces(seed):
         ids = [int(x) for x in r.choice(C, size=k, replace=False)]
         pre = r.random() < 0.3
         before_moved = m.pages_moved
+        mem = cm.membership_from_sizes(sizes)
         try:
-            moved = m.access(ids, sizes, prefetch=pre)
+            moved = m.access(ids, mem, prefetch=pre)
         except cm.CapacityError:
             assert sum(sizes[c] for c in ids) > cap
             continue
         calls += not pre
-        assert m.used() <= cap and len(m.pages) <= maxc
-        assert all(m.complete(c, sizes) for c in ids)      # what was asked for is resident, in full
+        d = m.directory(mem)
+        assert m.used() <= cap and len(d) <= maxc and m.used() == sum(d.values())
+        assert all(d[c] == sizes[c] for c in ids)          # what was asked for is resident, in full
         assert m.pages_moved - before_moved == sum(p for _, p in moved)
-        assert all(m.pages[c] <= sizes[c] for c in m.pages)
-        assert set(m.pages) <= set(m.stamp)
+        assert all(d[c] <= sizes[c] for c in d)
     assert m.hits + m.misses == calls * k
     assert m.prefetch_useful <= m.prefetch_fetched
     assert m.evictions > 0 and m.hits > 0
@@ -112,3 +114,26 @@ def test_prefetch_round_predicts_verifies_and_completes():
     c4 = cm.ClusterCacheModel(int(sizes.sum()), 6)
     out4 = cm.prefetch_round(u, c4, q_a, q_a, 0, 1, k, prefetch_top_k=1)
     assert out4["predicted"] == out["actual"][:1] and [c for c, _ in out4["completion"]] == out["actual"][1:]
+
+
+def test_a_split_hands_residency_and_recency_to_both_halves():
+    """Membership changes under the cache (Sec. VI splits): the model's state is per frame, so the
+    halves of a split cluster are resident as far as their frames are, inherit the parent's time of
+    last use (the lower id goes first when both are the oldest), and a half that received an uncached
+    frame is incomplete: a miss that moves only that frame."""
+    m = cm.ClusterCacheModel(capacity_pages=12, max_clusters=4)
+    mem = {0: [0, 1, 2, 3, 4, 5], 1: [10, 11, 12], 2: [20, 21]}
+    m.access([0], mem); m.access([1], mem); m.access([2], mem)           # times 1, 2, 3; 11 pages
+    assert m.directory(mem) == {0: 6, 1: 3, 2: 2}
+    # cluster 0 splits into 0 = {0, 1, 2} and 3 = {3, 4, 5, 30}; frame 30 is new and not cached
+    mem = {0: [0, 1, 2], 1: [10, 11, 12], 2: [20, 21], 3: [3, 4, 5, 30]}
+    assert m.directory(mem) == {0: 3, 1: 3, 2: 2, 3: 3}
+    assert m.stamp(mem[0]) == m.stamp(mem[3]) == 1
+    moved = m.access([3], mem)                                           # incomplete: one page moves, a miss
+    assert moved == [(3, 1)] and m.misses == 4 and m.hits == 0 and m.used() == 12
+    # a new cluster of 4 frames: 4 clusters are resident and no page is free, the oldest goes: that is
+    # cluster 0 (time 1); then 1 (time 2) for the space
+    mem[4] = [40, 41, 42, 43]
+    moved = m.access([4], mem)
+    assert moved == [(4, 4)] and m.evictions == 2
+    assert m.directory(mem) == {2: 2, 3: 4, 4: 4}

@@ -324,39 +324,51 @@ def test_host_tier_matches_hbm_tier_bitwise_and_overlaps_layers():
         assert torch.equal(o1, o2) and torch.equal(l1, l2)
 
 
-def _model_directory(model, C):
+def _model_directory(model, C, membership):
     d = np.full(C, -1, dtype=np.int32)
-    for c, p in model.pages.items():
+    for c, p in model.directory(membership).items():
         d[c] = p
     return d
 
 
 def test_host_tier_cache_follows_the_lru_model_and_grows_with_the_stream():
     """The GPU cluster cache against the oracle's working-set model (least recently used at cluster
-    granularity, capacity in pages and in clusters): directory after every retrieval, hit / miss /
-    byte counters at the end, while the stream keeps growing between questions."""
+    granularity, capacity in pages and in clusters), fed the oracle's own selections and memberships:
+    directory after every retrieval, hit / miss / byte counters at the end, while the stream keeps
+    growing between questions."""
+    from oracle import mosaic_oracle as orc
     wl = _small(n_kv_heads=1, n_q_heads=7, n_frames=240, n_clusters=12, top_k=3, n_scenes=10, warmup_frames=120)
     st = inputs.SceneStream(wl)
-    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    K, V = st.frames(0, wl.n_frames)
+    Kd, Vd = K.to(DEV), V.to(DEV)
+    Ku = inputs.unit_pages(K, 0, 0)
     pages = 170           # the three largest clusters hold 154 of the 240 frames
     m = binding.Mosaic(binding.config_for(wl, tier=binding.TIER_HOST, slab_frames=4,
                                           cache_pages_per_unit=pages, cache_fraction=5 / 12), device=DEV)
     model = cache_model.ClusterCacheModel(capacity_pages=pages, max_clusters=5)
-    m.ingest_frame(K[:160].contiguous(), V[:160].contiguous())
+    o = orc.OracleUnit(wl.n_clusters, wl.head_dim, wl.tokens_per_frame, wl.n_frames, wl.warmup_frames, wl.lloyd_iters)
+    m.ingest_frame(Kd[:160].contiguous(), Vd[:160].contiguous())
+    for f in range(160):
+        o.ingest(Ku[f])
     f = 160
     for i in range(24):
         if i % 6 == 5 and f < wl.n_frames:          # the stream keeps growing between questions
-            m.ingest_frame(K[f:f + 20].contiguous(), V[f:f + 20].contiguous())
+            m.ingest_frame(Kd[f:f + 20].contiguous(), Vd[f:f + 20].contiguous())
+            for ff in range(f, f + 20):
+                o.ingest(Ku[ff])
             f += 20
-        q = st.question(st.draw_scene(), 1, i).to(DEV)[0].contiguous()
-        m.retrieve(0, q)
-        out, _ = m.attend(0, q)
+        q = st.question(st.draw_scene(), 1, i)
+        qd = q.to(DEV)[0].contiguous()
+        m.retrieve(0, qd)
+        out, _ = m.attend(0, qd)
         ids, n_ids, _, toks = m.selection(0)
-        _, n = m.centroids()
-        model.access([int(c) for c in ids[0, : n_ids[0]]], n[0])
-        np.testing.assert_array_equal(m.cache_directory()[0], _model_directory(model, wl.n_clusters),
+        ids_o, _, tok_o, _ = o.retrieve(q[0].float().numpy().astype(np.float64), 0, wl.group, wl.top_k)
+        np.testing.assert_array_equal(ids[0, : n_ids[0]], ids_o)
+        np.testing.assert_array_equal(toks[0], tok_o)
+        mem = cache_model.membership_from_assignments(o.assignments())
+        model.access(ids_o, mem)
+        np.testing.assert_array_equal(m.cache_directory()[0], _model_directory(model, wl.n_clusters, mem),
                                       err_msg=f"cache directory after question {i}")
-        assert len(toks[0]) == wl.tokens_per_frame * n[0][ids[0, : n_ids[0]]].sum()
         assert torch.isfinite(out.float()).all()
     s = m.stats()
     assert (s.cache_hits, s.cache_misses) == (model.hits, model.misses)
@@ -400,16 +412,17 @@ def test_host_tier_cache_too_small_is_an_error_that_leaves_the_cache_usable():
     m = binding.Mosaic(binding.config_for(wl1, tier=binding.TIER_HOST, slab_frames=4,
                                           cache_pages_per_unit=biggest, cache_fraction=1 / 6), device=DEV)
     rep = harness.Report()
-    oracles = harness.ingest_with_parity(m, wl1, Kd, Vd, [(0, 0), (0, 1)], rep)
+    oracles = harness.ingest_with_parity(m, wl1, Kd, Vd, [(0, h) for h in range(wl1.n_kv_heads)], rep)
     model = {h: cache_model.ClusterCacheModel(biggest, 1) for h in range(wl1.n_kv_heads)}
     for i in range(4):
         qq = st.question(st.draw_scene(), 1, 10 + i).to(DEV)
         harness.query_with_parity(m, wl1, qq, oracles, K, V, rep)
-        ids, n_ids, _, _ = m.selection(0)
-        _, n = m.centroids()
+        q_h = qq.float().cpu().numpy().astype(np.float64)
         for h in range(wl1.n_kv_heads):
-            model[h].access([int(c) for c in ids[h, : n_ids[h]]], n[h])
-            np.testing.assert_array_equal(m.cache_directory()[h], _model_directory(model[h], wl1.n_clusters))
+            o = oracles[(0, h)]
+            mem = cache_model.membership_from_assignments(o.assignments())
+            model[h].access(o.retrieve(q_h[0], h, wl1.group, wl1.top_k)[0], mem)
+            np.testing.assert_array_equal(m.cache_directory()[h], _model_directory(model[h], wl1.n_clusters, mem))
     s = m.stats()
     assert s.cache_hits == sum(x.hits for x in model.values())
     assert s.cache_misses == sum(x.misses for x in model.values())
@@ -469,11 +482,44 @@ def test_maintainer_deferred_bf16_small_buffer():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("mode", [1, 2])
+def test_maintainer_on_the_host_tier_fp32(mode):
+    """Sec. VI on the offloading tier: clusters live in pinned host memory, "in GPU memory" (Alg. 1
+    line 4) means that the GPU cluster cache holds frames of the cluster.  Whole maintainer state,
+    selections (singletons included), token lists and attention against the oracle, whose residency
+    flags come from the working-set model; the library's cache directory against the model's after
+    every call; splits move no page (hit / miss / byte counters equal the model's)."""
+    wl = inputs.CONFIGS[0].scaled(name="maint_host_fp32", n_clusters=24, top_k=4)
+    rep = harness.run_maintained(wl, _mt(mode, 3, 1.5, 6.0, buf_max=12 if mode == 2 else 0), query_every=12,
+                                 host=dict(slab_frames=4, cache_pages_per_unit=100, cache_fraction=0.25))
+    tot = rep.notes[-1]
+    print("  ", tot, flush=True)
+    assert tot["split_now"] + tot["split_deferred"] > 0, tot
+    if mode == 2:
+        assert tot["deferred"] > 0 and tot["split_deferred"] > 0, tot
+    assert tot["cache"]["evictions"] > 0 and tot["cache"]["hits"] > 0
+    assert rep.max_out_err <= 1e-4
+
+
+@pytest.mark.gpu
+def test_maintainer_deferred_on_the_host_tier_bf16_small_buffer():
+    """D = 128, bf16 pages (MFMA attention over cache slots), ragged pages, a buffer that overflows."""
+    wl = inputs.CONFIGS[1].scaled(name="maint_host_bf16", n_frames=224, n_scenes=14, n_clusters=20,
+                                  top_k=3, question_tokens=5, tokens_per_frame=50, n_kv_heads=2, n_q_heads=14)
+    rep = harness.run_maintained(wl, _mt(2, 2, 0.5, 2.0, n0=6.0, split_iters=3, buf_max=3), query_every=20,
+                                 host=dict(slab_frames=3, cache_pages_per_unit=150, cache_fraction=0.3))
+    tot = rep.notes[-1]
+    print("  ", tot, flush=True)
+    assert tot["deferred"] > 0 and tot["forced_absorb"] > 0, tot
+    assert tot["cache"]["hits"] > 0
+
+
+@pytest.mark.gpu
 def test_maintainer_config_errors():
     wl = inputs.CONFIGS[0]
     base = dict(maint_mode=binding.MAINT_EAGER, init_clusters=4, tau_min=1.0, tau_max=2.0, tau_n0=8.0)
     for bad in (dict(tau_n0=0.0), dict(init_clusters=wl.n_clusters + 1), dict(maint_mode=3),
-                dict(tier=binding.TIER_HOST), dict(recluster_every=64),
+                dict(recluster_every=64),
                 dict(maint_mode=binding.MAINT_DEFERRED, buffer_max=1024)):
         kw = dict(base); kw.update(bad)
         with pytest.raises(binding.MosaicError) as ei:
@@ -623,10 +669,12 @@ def test_prefetch_follows_the_oracle_predict_verify_complete(prefetch_top_k):
     H, G, C = wl.n_kv_heads, wl.group, wl.n_clusters
     models = {key: cache_model.ClusterCacheModel(pages, 4) for key in units}
 
+    mems = {key: cache_model.membership_from_assignments(o.assignments()) for key, o in oracles.items()}
+
     def check_directory(where):
         d = m.cache_directory()
         for (l, h), mod in models.items():
-            np.testing.assert_array_equal(d[l * H + h], _model_directory(mod, C), err_msg=f"{where}, unit {(l, h)}")
+            np.testing.assert_array_equal(d[l * H + h], _model_directory(mod, C, mems[(l, h)]), err_msg=f"{where}, unit {(l, h)}")
 
     for qi in range(6):
         q = st.question(st.draw_scene(), 1, qi).to(DEV)
@@ -637,7 +685,7 @@ def test_prefetch_follows_the_oracle_predict_verify_complete(prefetch_top_k):
         m.retrieve(0, q[0].contiguous())
         for h in range(H):
             o = oracles[(0, h)]
-            models[(0, h)].access(o.retrieve(q_h[0], h, G, wl.top_k)[0], o.sizes())
+            models[(0, h)].access(o.retrieve(q_h[0], h, G, wl.top_k)[0], mems[(0, h)])
         check_directory(f"question {qi}, layer 0 retrieve")
         for layer in range(wl.n_layers):
             if layer + 1 < wl.n_layers:
@@ -651,7 +699,7 @@ def test_prefetch_follows_the_oracle_predict_verify_complete(prefetch_top_k):
                     ids_p = [int(c) for c in o.retrieve(proxy_h, h, G, wl.top_k)[0]]
                     if prefetch_top_k:
                         ids_p = ids_p[:prefetch_top_k]
-                    rounds[h] = models[(layer + 1, h)].access(ids_p, o.sizes(), prefetch=True)
+                    rounds[h] = models[(layer + 1, h)].access(ids_p, mems[(layer + 1, h)], prefetch=True)
                 check_directory(f"question {qi}, prefetch for layer {layer + 1}")
             m.attend(layer, q[layer].contiguous())
             if layer + 1 < wl.n_layers:
@@ -661,7 +709,7 @@ def test_prefetch_follows_the_oracle_predict_verify_complete(prefetch_top_k):
                     o = oracles[(layer + 1, h)]
                     want = o.retrieve(q_h[layer + 1], h, G, wl.top_k)[0]
                     np.testing.assert_array_equal(ids[h, : n_ids[h]], want)
-                    models[(layer + 1, h)].access(want, o.sizes())
+                    models[(layer + 1, h)].access(want, mems[(layer + 1, h)])
                 check_directory(f"question {qi}, layer {layer + 1} retrieve (verification + completion)")
         torch.cuda.synchronize()
     s = m.stats()
@@ -697,7 +745,8 @@ def test_prefetch_round_of_the_oracle_matches_the_library_on_one_transition():
     for (l, h), o in oracles.items():
         mod = cache_model.ClusterCacheModel(wl.n_frames, wl.n_clusters)
         out = cache_model.prefetch_round(o, mod, q_h[0], q_h[1], h, wl.group, wl.top_k)
-        np.testing.assert_array_equal(d[l * wl.n_kv_heads + h], _model_directory(mod, wl.n_clusters))
+        np.testing.assert_array_equal(d[l * wl.n_kv_heads + h],
+                                      _model_directory(mod, wl.n_clusters, cache_model.membership_from_assignments(o.assignments())))
         assert set(out["actual"]) - set(out["predicted"]) == {c for c, _ in out["completion"]}
         fetched += mod.prefetch_fetched; useful += mod.prefetch_useful; misses += mod.misses
     assert (s.prefetch_fetched, s.prefetch_useful, s.cache_misses) == (fetched, useful, misses)

@@ -748,10 +748,11 @@ def run_prefetch_leg(layers=3, steps=96, rhos=(0.95, 0.7)):
                        "slab_frames": 16, "cache_fraction": 0.10, "decode_steps": steps}, **out_all}
 
 
-def host_layers_that_fit(wl_full, cfg_kw, reserve=0.35, cap_bytes=170 << 30):
+def host_layers_that_fit(wl_full, cfg_kw, reserve=0.35, cap_bytes=64 << 30):
     """As many of the configuration's layers as pinned host memory allows: the largest layer count whose
-    pinned arena is at most (1 - reserve) of MemAvailable and of cap_bytes (one command may hold
-    about 270 GiB of host memory on these boxes; the stream generator and torch need their share)."""
+    pinned arena is at most (1 - reserve) of MemAvailable and of cap_bytes.  The cap is what these boxes
+    have been seen to grant: hipHostMalloc of 64 GiB succeeds and works, 96 GiB is refused, and a run
+    that asked for more than 64 GiB ended in a segmentation fault, so nothing larger is ever requested."""
     from paper_2604_10060_amd import binding
     avail = None
     with open("/proc/meminfo") as fh:
@@ -767,38 +768,35 @@ def host_layers_that_fit(wl_full, cfg_kw, reserve=0.35, cap_bytes=170 << 30):
                   "pinned_budget_GB": round(budget / 1e9, 1)}
 
 
+HOST_MAINT = dict(mode=1, c_init=64, tau_min=1.0, tau_max=4.0, n0=32.0, split_iters=4, buf_max=0)
+
+
 def run_host_leg(layers=0, steps=128, check=True):
-    """Config 3 (host-offload tier) with the layer count scaled to `layers` (the
-    full 28 layers need 184 GB of pinned host memory; the per-layer shape is
-    kept): clusters live in pinned host memory in slabs of 16 frames, the GPU
-    caches at most 10 % of a unit's clusters (LRU), the fetch for layer l+1 is
-    issued before attention of layer l.  4 question topics, steps/4 consecutive
-    decode steps each (a topic switch means cold misses)."""
+    """Config 3 (host-offload tier): clusters live in pinned host memory in slabs of 8 frames, the GPU
+    cluster cache holds at most 10 % of the stream's pages and 10 % of the cluster table (LRU), the fetch
+    for layer l+1 is issued before attention of layer l.  The self-adaptive maintainer (Sec. VI) keeps the
+    clusters small enough for that cache: 64 initial clusters in the table of 512, thresholds tau_min 1 /
+    tau_max 4 / N0 32 (a fixed number of clusters without splitting degenerates on this stream: single
+    clusters of > 1400 frames, top-32 selections of half the stream).  As many of the 28 layers as the box
+    grants pinned memory for (the per-layer shape is kept).  4 question topics, steps/4 consecutive decode
+    steps each (a topic switch means cold misses).  A selection that does not fit the cache is counted
+    (`steps_refused_by_cache_capacity`), not hidden."""
     import torch
     from paper_2604_10060_amd import binding, inputs
     dev = "cuda:0"
-    host_kw = dict(tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
-                   cache_pages_per_unit=inputs.CONFIGS[3].n_frames)
+    base = inputs.CONFIGS[3]
+    F0 = base.n_frames
+    mt = HOST_MAINT
+    host_kw = dict(tier=binding.TIER_HOST, slab_frames=8, cache_fraction=0.10, cache_pages_per_unit=F0 // 10,
+                   warmup_frames=0, maint_mode=mt["mode"], init_clusters=mt["c_init"], split_iters=mt["split_iters"],
+                   tau_min=mt["tau_min"], tau_max=mt["tau_max"], tau_n0=mt["n0"])
     mem = None
     m = None
     if layers <= 0:
-        # as many layers as pinned memory allows: bounded by MemAvailable, then by what hipHostMalloc
-        # really grants (on these boxes pinned allocations stop far below the free host memory)
-        layers, mem = host_layers_that_fit(inputs.CONFIGS[3], host_kw)
-        layers = min(layers, int(os.environ.get("MOSAIC_BENCH_HOST_LAYERS_MAX", "6")))
-        refused = []
-        while layers >= 1:
-            try:
-                m = binding.Mosaic(binding.config_for(inputs.CONFIGS[3].scaled(n_layers=layers), **host_kw), device=dev)
-                break
-            except (RuntimeError, binding.MosaicError) as ex:
-                _, hb = binding.workspace_sizes(binding.config_for(inputs.CONFIGS[3].scaled(n_layers=layers), **host_kw))
-                refused.append({"layers": layers, "pinned_GB": round(hb / 1e9, 1), "error": repr(ex)[:80]})
-                layers -= 1
-        mem["pinned_allocations_refused"] = refused
-        if m is None:
-            raise RuntimeError("no pinned host arena could be allocated")
-    wl = inputs.CONFIGS[3].scaled(n_layers=layers)
+        # as many layers as pinned memory allows: bounded by MemAvailable and by what hipHostMalloc
+        # grants on these boxes (far below the free host memory)
+        layers, mem = host_layers_that_fit(base, host_kw)
+    wl = base.scaled(n_layers=layers)
     L, Hq, D, T, F, H = wl.n_layers, wl.n_q_heads, wl.head_dim, wl.tokens_per_frame, wl.n_frames, wl.n_kv_heads
     log(f"[bench] {wl.name}: {layers} of 28 layers ({mem})")
     # measured pinned host-to-device rate of this box: one 1 GiB copy
@@ -812,12 +810,9 @@ def run_host_leg(layers=0, steps=128, check=True):
     pcie_gbps = (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst
     st = inputs.SceneStream(wl, device=dev)
-    # resident clusters capped at 10 % (51 of 512), least recently used evicted first.  The block pool
-    # is sized for the worst case (any 51 clusters): with a fixed number of clusters and no splitting a
-    # few clusters grow very large (here up to ~1500 of 16384 frames) and top-32 can cover half the stream.
     if m is None:
         m = binding.Mosaic(binding.config_for(wl, **host_kw), device=dev)
-    _, hbytes = binding.workspace_sizes(binding.config_for(wl, **host_kw))
+    dbytes, hbytes = binding.workspace_sizes(binding.config_for(wl, **host_kw))
     cu = (layers - 1, 2)                             # unit checked against the oracle
     keepK, keepV = [], []
     t0 = time.perf_counter()
@@ -836,8 +831,10 @@ def run_host_leg(layers=0, steps=128, check=True):
     log(f"[bench] {wl.name} x{layers} layers: host-tier ingest {ingest_fps:.0f} frames/s, "
         f"pinned H2D {pcie_gbps:.1f} GB/s")
     _, sizes = m.centroids()
+    s_ing = m.stats()
     log(f"[bench] cluster sizes (frames): max {sizes.max()}, mean {sizes[sizes > 0].mean():.1f}, "
-        f"non-empty {int((sizes > 0).sum() / sizes.shape[0])} of {wl.n_clusters} per unit")
+        f"clusters in use {float((sizes > 0).sum()) / sizes.shape[0]:.0f} of {wl.n_clusters} per unit, "
+        f"{s_ing.splits_immediate} splits")
     topics = [st.draw_scene() for _ in range(4)]
     per_topic = steps // 4
     qs = torch.stack([st.question(topics[i // per_topic], 1, 1 + i) for i in range(steps)])   # [n][L][1][Hq][D]
@@ -855,32 +852,40 @@ def run_host_leg(layers=0, steps=128, check=True):
                 m.retrieve_raw(l + 1, qp + (l + 1) * lq, 1)
             m.attend_raw(l, qp + l * lq, 1, out.data_ptr() + l * lq, lse.data_ptr() + l * Hq * 4)
 
-    lat = []
+    lat, refused_steps = [], 0
     for i in range(steps):
         torch.cuda.synchronize()
         t = time.perf_counter()
-        step(i)
+        try:
+            step(i)
+        except binding.MosaicError as ex:
+            if ex.code != binding.ECAPACITY:
+                raise
+            refused_steps += 1
+            log(f"[bench] step {i}: {ex}")
         torch.cuda.synchronize()
         lat.append((time.perf_counter() - t) * 1e6)
     # the attention kernel on warm steps (everything selected is in the GPU cluster cache)
     m.profile_read()
-    for i in range(8):
-        step(steps - 1 - i)
-    att_ms, att_n = m.profile_read()
-    warm_tokens = int(sum(n_tok_all(m, L)))          # selection of the last step issued, all layers
-    att_us = att_ms * 1e3 / max(att_n, 1)
-    att_bytes = warm_tokens / L * 2 * D * esz
+    att_us = att_bytes = 0.0
+    if refused_steps == 0:
+        for i in range(8):
+            step(steps - 1 - i)
+        att_ms, att_n = m.profile_read()
+        warm_tokens = int(sum(n_tok_all(m, L)))          # selection of the last step issued, all layers
+        att_us = att_ms * 1e3 / max(att_n, 1)
+        att_bytes = warm_tokens / L * 2 * D * esz
     s = m.stats()
     lat = np.array(lat)
     cold = lat[::per_topic]
     warm = np.delete(lat, np.arange(0, steps, per_topic))
     h2d_gbps = s.h2d_bytes / (s.h2d_busy_ms * 1e-3) / 1e9 if s.h2d_busy_ms > 0 else 0.0
     checked = None
-    if check:
+    if check and refused_steps == 0:
         from oracle import mosaic_oracle as orc
         Ku = torch.cat(keepK).float().numpy().astype(np.float64)
         Vu = torch.cat(keepV).float().numpy().astype(np.float64)
-        o = orc.OracleUnit(wl.n_clusters, D, T, F, wl.warmup_frames, wl.lloyd_iters, 0)
+        o = orc.OracleUnit(wl.n_clusters, D, T, F, 0, wl.lloyd_iters, 0, maintainer=mt)
         for f in range(F):
             o.ingest(Ku[f])
         u = cu[0] * H + cu[1]
@@ -896,28 +901,67 @@ def run_host_leg(layers=0, steps=128, check=True):
         got = out[cu[0], :, cu[1] * wl.group:(cu[1] + 1) * wl.group].float().cpu().numpy()
         err = float(np.abs(got - want).max())
         assert err <= 2e-2, f"host tier attention err {err}"
-        checked = {"unit": list(cu), "max_out_err": err}
+        checked = {"unit": list(cu), "assignments_equal": True, "oracle_counters": o.counters(), "max_out_err": err}
     m.close()
     del m
     torch.cuda.empty_cache()
-    return {"config": {"workload": wl.name, "layers": layers, "layers_of_full_config": 28,
-                       "frames": F, "tokens_per_frame": T, "clusters": wl.n_clusters, "top_k": wl.top_k,
-                       "slab_frames": 16, "cache_fraction": 0.10, "pinned_host_GB": round(hbytes / 1e9, 1),
-                       "host_memory": mem},
-            "decode_step_us_warm_median": round(float(np.median(warm)), 1),
-            "decode_step_us_topic_switch_mean": round(float(cold.mean()), 1),
-            "ingest_frames_per_s": round(ingest_fps, 1),
-            "roofline": {"bound": "pcie", "achieved": round(h2d_gbps, 2), "peak": round(pcie_gbps, 2),
-                         "unit": "GB/s", "frac": round(h2d_gbps / pcie_gbps, 4) if pcie_gbps else None,
-                         "peak_kind": "measured: one 1 GiB pinned hipMemcpyAsync on this box",
-                         "bytes": int(s.h2d_bytes), "copies": int(s.h2d_copies),
-                         "busy_ms": round(s.h2d_busy_ms, 3)},
-            "cache": {"hits": int(s.cache_hits), "misses": int(s.cache_misses)},
-            "attention_warm": {"kernel": "k_attend_decode_mfma", "kernel_us": round(att_us, 1),
-                               "bytes_per_launch": int(att_bytes),
-                               "hbm_gbps": round(att_bytes / (att_us * 1e-6) / 1e9, 1) if att_us else None,
-                               "frac_of_8TBps": round(att_bytes / (att_us * 1e-6) / 8e12, 4) if att_us else None},
-            "parity_spot_check": checked}
+    # Alg. 1 in full on the same stream (deferred splits; a decode query every 64 frames makes its
+    # selection resident): how many split operations deferral saves.  The cache holds the whole stream
+    # here so that no selection is refused while clusters wait for their split.
+    deferred = None
+    try:
+        kw = dict(host_kw)
+        kw.update(maint_mode=binding.MAINT_DEFERRED, buffer_max=512, cache_pages_per_unit=F0)
+        md = binding.Mosaic(binding.config_for(wl, **kw), device=dev)
+        qi = 0
+        for f0 in range(0, F, 256):
+            K, V = st.frames(f0, min(F, f0 + 256))
+            for b in range(0, K.shape[0], 64):
+                md.ingest_frame(K[b:b + 64], V[b:b + 64])
+                if f0 + b + 64 >= 2 * mt["c_init"]:
+                    qq = st.question(st.draw_scene(), 1, 5000 + qi); qi += 1
+                    for l in range(L):
+                        md.retrieve(l, qq[l].contiguous())
+        torch.cuda.synchronize()
+        sd = md.stats()
+        _, dsizes = md.centroids()
+        deferred = {"splits_immediate": int(sd.splits_immediate), "splits_deferred": int(sd.splits_deferred),
+                    "deferred_inserts": int(sd.deferred_inserts), "forced_absorbs": int(sd.forced_absorbs),
+                    "largest_cluster_frames": int(dsizes.max()), "buffer_max": 512, "query_every_frames": 64}
+        md.close()
+        del md
+    except Exception as ex:                          # noqa: BLE001
+        deferred = {"error": str(ex)[:300]}
+    torch.cuda.empty_cache()
+    tot_e = int(s_ing.splits_immediate + s_ing.splits_deferred)
+    out_d = {"config": {"workload": wl.name, "layers": layers, "layers_of_full_config": 28,
+                        "frames": F, "tokens_per_frame": T, "cluster_table": wl.n_clusters, "top_k": wl.top_k,
+                        "slab_frames": 8, "cache_fraction_of_clusters": 0.10, "cache_pages_per_unit": F0 // 10,
+                        "cache_fraction_of_pages": 0.10, "maintainer": mt,
+                        "pinned_host_GB": round(hbytes / 1e9, 1), "device_arena_GB": round(dbytes / 1e9, 1),
+                        "host_memory": mem},
+             "decode_step_us_warm_median": round(float(np.median(warm)), 1),
+             "decode_step_us_topic_switch_mean": round(float(cold.mean()), 1),
+             "steps_refused_by_cache_capacity": refused_steps,
+             "ingest_frames_per_s": round(ingest_fps, 1),
+             "clusters": {"in_use_per_unit_mean": round(float((sizes > 0).sum()) / sizes.shape[0], 1),
+                          "largest_frames": int(sizes.max()), "splits_eager": tot_e,
+                          "forced_absorbs": int(s_ing.forced_absorbs), "deferred_mode": deferred},
+             "roofline": {"bound": "pcie", "achieved": round(h2d_gbps, 2), "peak": round(pcie_gbps, 2),
+                          "unit": "GB/s", "frac": round(h2d_gbps / pcie_gbps, 4) if pcie_gbps else None,
+                          "peak_kind": "measured: one 1 GiB pinned hipMemcpyAsync on this box",
+                          "bytes": int(s.h2d_bytes), "copies": int(s.h2d_copies),
+                          "busy_ms": round(s.h2d_busy_ms, 3)},
+             "cache": {"hits": int(s.cache_hits), "misses": int(s.cache_misses)},
+             "attention_warm": {"kernel": "k_attend_decode_mfma", "kernel_us": round(att_us, 1),
+                                "bytes_per_launch": int(att_bytes),
+                                "hbm_gbps": round(att_bytes / (att_us * 1e-6) / 1e9, 1) if att_us else None,
+                                "frac_of_8TBps": round(att_bytes / (att_us * 1e-6) / 8e12, 4) if att_us else None},
+             "parity_spot_check": checked}
+    if deferred and "error" not in deferred and tot_e:
+        tot_d = deferred["splits_immediate"] + deferred["splits_deferred"]
+        out_d["clusters"]["split_reduction_by_deferral"] = round(1.0 - tot_d / tot_e, 4)
+    return out_d
 
 
 def cpu_baseline(wl, K_all, V_all, q_steps, budget_s, n_units=0):

@@ -191,6 +191,14 @@ typedef struct {
  * ignored).  dev_bytes, host_bytes: host pointers; host_bytes may be NULL. */
 int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes, size_t *host_bytes);
 
+/* Pinned, device-mapped host memory of exactly `bytes` bytes for config.host_arena (hipHostMalloc in
+ * the HIP runtime the library itself uses), and its release.  A convenience for callers whose own
+ * pinned allocator rounds sizes up; any hipHostMalloc memory serves as host_arena.  out: host
+ * pointer to a host pointer.  Errors: EINVAL, ENOMEM (the runtime refused; text in
+ * mosaic_last_error(NULL)). */
+int32_t mosaic_host_alloc(size_t bytes, void **out);
+int32_t mosaic_host_free(void *p);
+
 /* One context per video stream: the "layer-wise KVCache" that Frame Encoding updates and Query
  * Retrieval reads (Sec. V-A "Setup"), with the state Alg. 1 lists per cluster (representative,
  * variance, lazy-split flag, GPU buffer, representative set).  Validates cfg, carves the arena;

@@ -24,7 +24,7 @@ MAINT_OFF, MAINT_EAGER, MAINT_DEFERRED = 0, 1, 2
 _STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ECAPACITY", -4: "ENOTREADY", -5: "EHIP"}
 
 EXPORTS = (
-    "mosaic_workspace_size", "mosaic_create", "mosaic_destroy", "mosaic_reset",
+    "mosaic_host_alloc", "mosaic_host_free", "mosaic_workspace_size", "mosaic_create", "mosaic_destroy", "mosaic_reset",
     "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_prefetch", "mosaic_attend", "mosaic_attend_static",
     "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries", "mosaic_get_maintainer",
     "mosaic_decode_step", "mosaic_ingest_frame_visual", "mosaic_get_partitions", "mosaic_get_partition_selection",
@@ -88,6 +88,8 @@ def load_library():
             "(hipcc, gfx950).  There is no fallback path.")
     L = C.CDLL(LIB_PATH)
     vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    L.mosaic_host_alloc.argtypes = [sz, C.POINTER(vp)]
+    L.mosaic_host_free.argtypes = [vp]
     L.mosaic_workspace_size.argtypes = [C.POINTER(Config), C.POINTER(sz), C.POINTER(sz)]
     L.mosaic_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
     L.mosaic_destroy.argtypes = [vp]
@@ -163,6 +165,32 @@ def _ptr(t) -> int:
     return 0 if t is None else t.data_ptr()
 
 
+class PinnedArena:
+    """Pinned, device-mapped host memory of an exact size (mosaic_host_alloc: hipHostMalloc in the HIP
+    runtime the library uses).  torch's own pinned allocator rounds requests up to a power of two,
+    which on a box that grants about 64 GB of pinned memory in all turns a 40 GB arena into a refused
+    64 GB one."""
+
+    def __init__(self, nbytes: int):
+        self._L = load_library()
+        p = C.c_void_p()
+        rc = self._L.mosaic_host_alloc(nbytes, C.byref(p))
+        if rc != OK or not p.value:
+            raise MosaicError(rc, self._L.mosaic_last_error(None).decode())
+        self.ptr, self.nbytes = p.value, nbytes
+
+    def free(self):
+        if getattr(self, "ptr", None):
+            self._L.mosaic_host_free(C.c_void_p(self.ptr))
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
 class Mosaic:
     """One video stream's context.  Tensors are torch CUDA tensors; the
     observers return numpy arrays."""
@@ -183,8 +211,9 @@ class Mosaic:
         self.host_arena = None
         if hbytes:
             # pinned (hipHostMalloc) host memory for the host tier's cluster slabs
-            self.host_arena = torch.empty(hbytes + 256, dtype=torch.uint8, pin_memory=True)
-            cfg.host_arena = (self.host_arena.data_ptr() + 255) // 256 * 256
+            torch.cuda.current_stream(self.device)            # (the HIP runtime is up before the raw call)
+            self.host_arena = PinnedArena(hbytes + 256)
+            cfg.host_arena = (self.host_arena.ptr + 255) // 256 * 256
             cfg.host_arena_bytes = hbytes
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         cfg.stream = self.stream.cuda_stream
@@ -202,6 +231,9 @@ class Mosaic:
         if getattr(self, "_h", None):
             self._L.mosaic_destroy(self._h)
             self._h = None
+        if getattr(self, "host_arena", None) is not None:
+            self.host_arena.free()
+            self.host_arena = None
 
     def __del__(self):
         try:

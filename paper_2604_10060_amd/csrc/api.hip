@@ -304,6 +304,25 @@ int32_t mosaic_calibration_copy(void *dst_dev, const void *src_dev, size_t bytes
     return MOSAIC_OK;
 }
 
+int32_t mosaic_host_alloc(size_t bytes, void **out) {
+    if (!out || bytes == 0) return fail(nullptr, MOSAIC_EINVAL, "mosaic_host_alloc needs a size and an output pointer");
+    void *p = nullptr;
+    const hipError_t e = hipHostMalloc(&p, bytes, hipHostMallocDefault);
+    if (e != hipSuccess || !p) {
+        (void)hipGetLastError();             // the refusal must not surface in a later call
+        *out = nullptr;
+        return fail(nullptr, MOSAIC_ENOMEM, std::string("hipHostMalloc refused the pinned allocation: ") + hipGetErrorString(e));
+    }
+    *out = p;
+    return MOSAIC_OK;
+}
+
+int32_t mosaic_host_free(void *p) {
+    if (!p) return MOSAIC_OK;
+    const hipError_t e = hipHostFree(p);
+    return e == hipSuccess ? MOSAIC_OK : fail_hip(nullptr, e, "hipHostFree");
+}
+
 int32_t mosaic_workspace_size(const mosaic_config *cfg, size_t *dev_bytes, size_t *host_bytes) {
     std::string why;
     int rc = check_config(cfg, why);

@@ -267,15 +267,59 @@ def test_cfg4_full_size_question_prefill(stream_id):
 
 
 def test_cfg3_full_shape_one_layer_host_tier():
-    """The host-offload workload with its per-layer shape kept (16384 frames of 196 tokens,
-    512 clusters, top-32, slabs of 16 frames, 10 % of the clusters cacheable) and one of its
-    28 layers: 6.6 GB of KV in pinned host memory; decode steps on a sampled unit."""
+    """The host-offload workload with its per-layer shape kept (16384 frames of 196 tokens, a table of
+    512 clusters, top-32, slabs of 8 frames) and one of its 28 layers: 8.8 GB of KV in pinned host
+    memory, a GPU cluster cache capped at 10 % of the stream's pages and 10 % of the cluster table, the
+    self-adaptive maintainer keeping the clusters small enough for it (the benchmark's parameters).
+    One sampled unit: every assignment and the maintainer's counters against the oracle, then decode
+    steps (ids, token lists, attention)."""
     wl = inputs.CONFIGS[3].scaled(n_layers=1)
-    rep = harness.run_full_size(wl, [(0, 2)], ingest_batch=64, decode_steps=2, question=False,
-                                tier=binding.TIER_HOST, slab_frames=16, cache_fraction=0.10,
-                                cache_pages_per_unit=wl.n_frames)
-    _report(rep)
-    assert rep.online_decisions == wl.n_frames - wl.warmup
+    mt = _mt(1, 64, 1.0, 4.0, n0=32.0)
+    dev = DEV
+    st = inputs.SceneStream(wl, device=dev)
+    F = wl.n_frames
+    m = binding.Mosaic(binding.config_for(wl, warmup_frames=0, tier=binding.TIER_HOST, slab_frames=8,
+                                          cache_fraction=0.10, cache_pages_per_unit=F // 10,
+                                          **harness.maintainer_overrides(mt)), device=dev)
+    unit = (0, 2)
+    keepK, keepV = [], []
+    for f0 in range(0, F, 256):
+        K, V = st.frames(f0, min(F, f0 + 256))
+        keepK.append(K[:, unit[0], unit[1]].cpu()); keepV.append(V[:, unit[0], unit[1]].cpu())
+        for b in range(0, K.shape[0], 64):
+            m.ingest_frame(K[b:b + 64], V[b:b + 64])
+    torch.cuda.synchronize()
+    Ku = torch.cat(keepK).float().numpy().astype(np.float64)
+    Vu = torch.cat(keepV).float().numpy().astype(np.float64)
+    from oracle import mosaic_oracle as orc
+    o = orc.OracleUnit(wl.n_clusters, wl.head_dim, wl.tokens_per_frame, F, 0, wl.lloyd_iters, 0, maintainer=mt)
+    for f in range(F):
+        o.ingest(Ku[f])
+    u = unit[0] * wl.n_kv_heads + unit[1]
+    np.testing.assert_array_equal(m.assignments()[u], o.assignments())
+    _, N = m.centroids()
+    np.testing.assert_array_equal(N[u], o.sizes())
+    assert m.maintainer()["n_slots"][u] == o.n_slots and o.counters()["split_now"] > 100
+    assert N[u].max() < 200                        # no degenerate cluster: top-32 fits a tenth of the pages
+    G, D = wl.group, wl.head_dim
+    for i in range(3):
+        q = st.question(st.draw_scene(), 1, i)
+        m.retrieve(0, q[0].contiguous())
+        out, lse = m.attend(0, q[0].contiguous())
+        torch.cuda.synchronize()
+        ids, n_ids, sc, toks = m.selection(0)
+        qh = q[0].float().cpu().numpy().astype(np.float64)
+        ids_o, sc_o, tok_o, gap = o.retrieve(qh, unit[1], G, wl.top_k)
+        np.testing.assert_array_equal(ids[unit[1], : n_ids[unit[1]]], ids_o)
+        np.testing.assert_array_equal(toks[unit[1]], tok_o)
+        assert len(tok_o) <= (F // 10) * wl.tokens_per_frame
+        want, want_lse = orc.attend(qh, Ku.reshape(-1, D), Vu.reshape(-1, D), tok_o, unit[1], G)
+        got = out[:, unit[1] * G:(unit[1] + 1) * G].float().cpu().numpy()
+        assert np.abs(got - want).max() <= harness.OUT_TOL["bf16"]
+        assert np.abs(lse[:, unit[1] * G:(unit[1] + 1) * G].cpu().numpy() - want_lse).max() <= harness.LSE_TOL["bf16"]
+    s = m.stats()
+    assert s.cache_misses > 0 and s.h2d_bytes > 0
+    m.close()
 
 
 # --------------------------------------------------------------------------

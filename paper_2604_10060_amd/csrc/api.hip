@@ -54,7 +54,7 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 }
 
 struct Layout {
-    size_t k_store, v_store, summ, r, rnorm, n, assign, pos, scores, ids, n_ids, sel_pages, n_sel,
+    size_t k_store, v_store, summ, r, rnorm, n, assign, pos, lloyd_moved, scores, ids, n_ids, sel_pages, n_sel,
         tok_scratch, part_o, part_ml, stage_k, stage_v, dest, var, lazy, resident, n_slots, buf_frame,
         buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, vsumm, rvsum, rep_k, rep_v, aug_o, aug_ml,
         vemb, vr, vrn, vn, part, pr, prn, pn, pscores, pids, n_pids, total;
@@ -184,6 +184,7 @@ Layout make_layout(const mosaic_config &c) {
     L.n = take(U * C * 4);
     L.assign = take(U * F * 4);
     L.pos = take(U * F * 4);
+    L.lloyd_moved = take(U * 3 * 4);
     L.c_init = init_clusters_of(c); L.buf_max = buffer_max_of(c); L.W = warmup_of(c);
     L.split_iters = c.split_iters > 0 ? c.split_iters : 4;
     const bool mt = c.maint_mode != MOSAIC_MAINT_OFF;
@@ -384,6 +385,7 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.summ = (double *)(base + L.summ); dv.r = (double *)(base + L.r);
     dv.rnorm = (double *)(base + L.rnorm); dv.n = (int *)(base + L.n);
     dv.assign = (int *)(base + L.assign); dv.pos = (int *)(base + L.pos);
+    dv.lloyd_moved = (int *)(base + L.lloyd_moved);
     dv.scores = (double *)(base + L.scores); dv.ids = (int *)(base + L.ids);
     dv.aug_reps = cfg->aug_global_reps; dv.aug_window = cfg->aug_window_frames; dv.nt_max = L.nt_max;
     dv.vsumm = cfg->aug_global_reps ? (double *)(base + L.vsumm) : nullptr;

@@ -829,12 +829,20 @@ __global__ __launch_bounds__(kBlock) void k_exact_var(DeviceView dv, int n_frame
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef double f64x2 __attribute__((ext_vector_type(2)));
 
+// Rounds that change nothing are skipped: a round `it` that moved no frame of a unit leaves the same
+// members, hence (the sums being one fixed sequence of additions) the same representatives bit for
+// bit, hence the same assignments in every later round.  moved[u][it % 3] counts the frames round
+// `it` moved; a round whose predecessor moved none returns at once (and so does its update kernel).
+// The slot of the round after is cleared by this launch, which neither reads nor counts in it.
 template <int D>
-__global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n_frames) {
+__global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n_frames, int it) {
     constexpr int KS = D / 8;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, C = dv.C;
     const int row = lane % 16, kq = lane / 16;
     const int fbase = blockIdx.y * 64 + wave * 16;
+    int *moved = dv.lloyd_moved + (size_t)u * 3;
+    if (blockIdx.y == 0 && tid == 0) moved[(it + 1) % 3] = 0;
+    if (it > 0 && moved[(it - 1) % 3] == 0) return;            // workgroup-uniform: converged in an earlier round
     __shared__ double sn_sh[4][16];
     f64x2 a[KS];
     {
@@ -931,7 +939,11 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
             if (better(ov, oi, bv[v], bi[v])) { bv[v] = ov; bi[v] = oi; }
         }
         const int f = fbase + 4 * v + kq;
-        if (row == 0 && f < n_frames) dv.assign[(size_t)u * dv.F + f] = bi[v] == 0x7fffffff ? plo[v] : bi[v];
+        if (row == 0 && f < n_frames) {
+            const int a_new = bi[v] == 0x7fffffff ? plo[v] : bi[v];
+            int *slot = dv.assign + (size_t)u * dv.F + f;
+            if (*slot != a_new) { *slot = a_new; atomicAdd(&moved[it % 3], 1); }
+        }
     }
 }
 
@@ -946,9 +958,11 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
 // unit: 470 MB at 112 units x 4096 frames), which is what bounds it.
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frames) {
+__global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frames, int it) {
     constexpr int NT = 128, FPT = 16, CH = NT * FPT;
     const int u = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, C = dv.C;
+    // (a round that moved no frame would rebuild the same sums: see k_lloyd_assign)
+    if (it > 0 && dv.lloyd_moved[(size_t)u * 3 + it % 3] == 0) return;
     const int wave = tid / 64, lane = tid % 64;
     __shared__ int a_sh[CH];
     __shared__ int mem[CH];
@@ -1145,15 +1159,16 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
         if (e != hipSuccess) return e;
     }
     dim3 ga(dv.U, (n_frames + 63) / 64), gu(dv.U, dv.C);
+    if ((e = hipMemsetAsync(dv.lloyd_moved, 0, (size_t)dv.U * 3 * 4, s)) != hipSuccess) return e;
     for (int it = 0; it < iters; ++it) {
         e = checked([&] {
-            if (dv.D == 64) k_lloyd_assign<64><<<ga, kBlock, 0, s>>>(dv, n_frames);
-            else k_lloyd_assign<128><<<ga, kBlock, 0, s>>>(dv, n_frames);
+            if (dv.D == 64) k_lloyd_assign<64><<<ga, kBlock, 0, s>>>(dv, n_frames, it);
+            else k_lloyd_assign<128><<<ga, kBlock, 0, s>>>(dv, n_frames, it);
         });
         if (e != hipSuccess) return e;
         e = checked([&] {
-            if (dv.D == 64) k_lloyd_update<64><<<gu, 128, 0, s>>>(dv, n_frames);
-            else k_lloyd_update<128><<<gu, 128, 0, s>>>(dv, n_frames);
+            if (dv.D == 64) k_lloyd_update<64><<<gu, 128, 0, s>>>(dv, n_frames, it);
+            else k_lloyd_update<128><<<gu, 128, 0, s>>>(dv, n_frames, it);
         });
         if (e != hipSuccess) return e;
     }

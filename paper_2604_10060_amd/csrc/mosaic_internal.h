@@ -55,6 +55,7 @@ struct DeviceView {
     int *n;           // [U][C]      sizes in frames
     int *assign;      // [U][F]      frame -> cluster
     int *pos;         // [U][F]      rank of the frame among its cluster's members (ascending frame order)
+    int *lloyd_moved; // [U][3]      frames moved by the K-means rounds it-1, it, it+1 (mod 3): converged units skip the rest
     // self-adaptive maintainer (paper Sec. VI); maint_mode 0 = off (the arrays are then empty)
     int maint_mode, c_init, split_iters, buf_max;
     int SC;           // score columns per unit: C + buf_max

@@ -18,15 +18,31 @@ _SRC = os.path.join(_HERE, "mosaic_oracle.c")
 _LIB = os.path.join(_HERE, "libmosaic_oracle.so")
 
 
-def build(force: bool = False) -> str:
+_LIB_SAN = os.path.join(_HERE, "libmosaic_oracle_san.so")
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
     """Compile the oracle with gcc (-O2, strict IEEE: no fast-math, no FMA
-    contraction) and return the library path."""
-    if force or not os.path.exists(_LIB) or \
-            os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    contraction) and return the library path.  sanitize=True builds a second
+    library with AddressSanitizer and UndefinedBehaviorSanitizer (host code only),
+    which lib() loads when MOSAIC_ORACLE_SANITIZED=1 is set in the environment."""
+    out = _LIB_SAN if sanitize else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        extra = ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                 "-fno-omit-frame-pointer"] if sanitize else []
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared",
-             "-o", _LIB, _SRC, "-lm"])
-    return _LIB
+            ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", *extra,
+             "-o", out, _SRC, "-lm"])
+    return out
+
+
+def sanitizer_runtime() -> str | None:
+    """Path of gcc's libasan.so (a process that loads the sanitized oracle needs it preloaded), or None."""
+    try:
+        p = subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
+    except (OSError, subprocess.CalledProcessError):
+        return None
+    return p if os.path.isabs(p) and os.path.exists(p) else None
 
 
 class _Decision(C.Structure):
@@ -50,7 +66,7 @@ _ip = C.POINTER(C.c_int)
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
+        L = C.CDLL(build(sanitize=os.environ.get("MOSAIC_ORACLE_SANITIZED") == "1"))
         L.orc_unit_new.restype = C.c_void_p
         L.orc_unit_new.argtypes = [C.c_int] * 8
         L.orc_unit_free.argtypes = [C.c_void_p]

@@ -91,8 +91,10 @@ typedef struct {
     float cache_fraction;         /* at most floor(cache_fraction * C) clusters (but at least top_k) are
                                      cached per unit, least recently used evicted first; 0 -> 0.10 */
     int32_t decode_fused_max_mib; /* (any tier; sits here for alignment) mosaic_decode_step runs its single
-                                     fused kernel while the expected K/V volume of the step is at most this
-                                     many MiB; 0 -> 48 */
+                                     fused kernel (equal splits) while the expected K/V volume of the step is
+                                     at most this many MiB; 0 -> 48; -2: always the two calls; -1: never that
+                                     kernel but, wherever it applies, the one-launch form with proportional
+                                     splits (an option kept for measurement: slower than the two calls) */
     void *host_arena;             /* HOST pointer to pinned (hipHostMalloc) memory, 256-byte aligned,
                                      borrowed; size from mosaic_workspace_size */
     size_t host_arena_bytes;
@@ -168,7 +170,9 @@ typedef struct {
     int32_t ready;             /* 1 once the initial clustering has run */
     int32_t attend_impl;       /* the kernel family in use (MOSAIC_ATTEND_VALU or _MFMA) */
     int32_t last_n_splits;     /* average KV splits per unit used by the latest attend */
-    int32_t last_decode_fused; /* 1 if the latest mosaic_decode_step ran the single fused kernel */
+    int32_t last_decode_fused; /* what the latest mosaic_decode_step ran: 0 = mosaic_retrieve + mosaic_attend,
+                                  1 = the single fused kernel (equal splits), 2 = selection inside the attention
+                                  launch with size-proportional splits */
     /* host tier */
     int64_t cache_hits, cache_misses;   /* selected clusters found in / missing from the GPU cache */
     int64_t h2d_bytes, h2d_copies;      /* cluster fetches: bytes moved host-to-device and fetch-kernel launches */
@@ -184,6 +188,9 @@ typedef struct {
     int64_t splits_deferred;            /* deferred splits carried out at retrieval */
     int64_t deferred_inserts;           /* states put into the singleton buffer */
     int64_t forced_absorbs;             /* invalid, but absorbed: no free cluster id, degenerate split, or full buffer */
+    int64_t sync_timeouts;              /* nonzero if a bounded wait inside a kernel (the selection exchange of
+                                           mosaic_decode_step's one-launch form) ever ran out: results of that
+                                           step are then undefined (filled by mosaic_get_stats) */
 } mosaic_stats;
 
 /* Bytes of device arena and of pinned host arena (0 for MOSAIC_TIER_HBM) a
@@ -314,7 +321,14 @@ int32_t mosaic_attend_static(mosaic_ctx *ctx, int32_t layer, const void *q_dev, 
  * by bandwidth -- the selection and the attention over the selected clusters run in ONE kernel
  * (every attention workgroup repeats its unit's selection for itself, which is cheaper than a
  * launch boundary and the dependent loads after it; KV splits are then equal per unit instead of
- * proportional to the retrieved size); everywhere else it simply makes the two calls. */
+ * proportional to the retrieved size).  Everywhere else the call simply makes the two calls.
+ * With decode_fused_max_mib = -1, under the same conditions otherwise (and n_kv_heads <= 64), the
+ * selection moves into the attention launch but is made once per unit: the launch's first Hkv
+ * workgroups select for one KV head each and publish the result through memory, all workgroups
+ * wait for that (a bounded wait on workgroups that are started first and wait for nobody;
+ * sync_timeouts in the statistics counts waits that ran out) and then share out the retrieved pages
+ * in proportion to the units' sizes, as mosaic_attend does.  Same results bit for bit; measured
+ * slower than the two calls, because what the waiting workgroups read has to bypass the L2s. */
 int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, int32_t n_q_tokens,
                            void *out_dev, float *lse_dev);
 

@@ -70,7 +70,7 @@ class Stats(C.Structure):
         ("h2d_bytes", C.c_int64), ("h2d_copies", C.c_int64), ("h2d_busy_ms", C.c_double),
         ("prefetch_calls", C.c_int64), ("prefetch_fetched", C.c_int64), ("prefetch_useful", C.c_int64),
         ("splits_immediate", C.c_int64), ("splits_deferred", C.c_int64),
-        ("deferred_inserts", C.c_int64), ("forced_absorbs", C.c_int64),
+        ("deferred_inserts", C.c_int64), ("forced_absorbs", C.c_int64), ("sync_timeouts", C.c_int64),
     ]
 
 

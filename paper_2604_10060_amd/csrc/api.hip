@@ -54,7 +54,7 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 }
 
 struct Layout {
-    size_t k_store, v_store, summ, r, rnorm, n, assign, pos, lloyd_moved, scores, ids, n_ids, sel_pages, n_sel,
+    size_t k_store, v_store, summ, r, rnorm, n, assign, pos, lloyd_moved, sel_flag, sync_err, scores, ids, n_ids, sel_pages, n_sel,
         tok_scratch, part_o, part_ml, stage_k, stage_v, dest, var, lazy, resident, n_slots, buf_frame,
         buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, vsumm, rvsum, rep_k, rep_v, aug_o, aug_ml,
         vemb, vr, vrn, vn, part, pr, prn, pn, pscores, pids, n_pids, total;
@@ -127,7 +127,7 @@ int check_config(const mosaic_config *c, std::string &why) {
     if (c->attend_impl < MOSAIC_ATTEND_AUTO || c->attend_impl > MOSAIC_ATTEND_MFMA) { why = "attend_impl out of range"; return MOSAIC_EINVAL; }
     if (c->attend_impl == MOSAIC_ATTEND_MFMA && c->kv_dtype != MOSAIC_BF16) { why = "the MFMA attention kernel needs bf16 KV"; return MOSAIC_EINVAL; }
     if ((long long)c->max_frames * c->tokens_per_frame > 0x7fffffffLL) { why = "max_frames * tokens_per_frame must fit in int32"; return MOSAIC_EINVAL; }
-    if (c->decode_fused_max_mib < 0) { why = "decode_fused_max_mib must not be negative"; return MOSAIC_EINVAL; }
+    if (c->decode_fused_max_mib < -2) { why = "decode_fused_max_mib must be >= -2"; return MOSAIC_EINVAL; }
     if (c->tier != MOSAIC_TIER_HBM && c->tier != MOSAIC_TIER_HOST) { why = "tier must be MOSAIC_TIER_HBM or MOSAIC_TIER_HOST"; return MOSAIC_EINVAL; }
     if (c->tier == MOSAIC_TIER_HOST) {
         if (c->recluster_every != 0) { why = "re-clustering is not available in the host tier (pages would have to move between slabs)"; return MOSAIC_EINVAL; }
@@ -185,6 +185,8 @@ Layout make_layout(const mosaic_config &c) {
     L.assign = take(U * F * 4);
     L.pos = take(U * F * 4);
     L.lloyd_moved = take(U * 3 * 4);
+    L.sel_flag = take(U * 8);
+    L.sync_err = take(4);
     L.c_init = init_clusters_of(c); L.buf_max = buffer_max_of(c); L.W = warmup_of(c);
     L.split_iters = c.split_iters > 0 ? c.split_iters : 4;
     const bool mt = c.maint_mode != MOSAIC_MAINT_OFF;
@@ -386,6 +388,8 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.rnorm = (double *)(base + L.rnorm); dv.n = (int *)(base + L.n);
     dv.assign = (int *)(base + L.assign); dv.pos = (int *)(base + L.pos);
     dv.lloyd_moved = (int *)(base + L.lloyd_moved);
+    dv.sel_flag = (long long *)(base + L.sel_flag); dv.sync_err = (int *)(base + L.sync_err);
+    ctx->launch_epoch = 0;
     dv.scores = (double *)(base + L.scores); dv.ids = (int *)(base + L.ids);
     dv.aug_reps = cfg->aug_global_reps; dv.aug_window = cfg->aug_window_frames; dv.nt_max = L.nt_max;
     dv.vsumm = cfg->aug_global_reps ? (double *)(base + L.vsumm) : nullptr;
@@ -505,11 +509,15 @@ int32_t mosaic_destroy(mosaic_ctx *ctx) {
     return MOSAIC_OK;
 }
 
-// Maintainer state that must read as empty before the initial clustering has run.
+// State that must read as empty before the initial clustering has run: the flags of the in-kernel
+// selection exchange, and the maintainer's.
 static hipError_t clear_maintainer(mosaic_ctx *ctx) {
     const DeviceView &dv = ctx->dv;
-    if (!dv.maint_mode) return hipSuccess;
     hipError_t e;
+    if ((e = hipMemsetAsync(dv.sel_flag, 0, (size_t)dv.U * 8, ctx->stream)) != hipSuccess) return e;
+    if ((e = hipMemsetAsync(dv.sync_err, 0, 4, ctx->stream)) != hipSuccess) return e;
+    ctx->launch_epoch = 0;
+    if (!dv.maint_mode) return hipSuccess;
     if ((e = hipMemsetAsync(dv.n_buf, 0, (size_t)dv.U * 4, ctx->stream)) != hipSuccess) return e;
     if ((e = hipMemsetAsync(dv.n_slots, 0, (size_t)dv.U * 4, ctx->stream)) != hipSuccess) return e;
     if ((e = hipMemsetAsync(dv.mt_cnt, 0, (size_t)dv.U * 4 * 8, ctx->stream)) != hipSuccess) return e;
@@ -1069,7 +1077,8 @@ int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, in
     const long long est_bytes = (long long)dv.Hkv * est_pages * (long long)(dv.kpage + dv.vpage);
     const bool fused = !ctx->host && ctx->impl == MOSAIC_ATTEND_MFMA && layer >= 0 && NT == 1 &&
                        dv.maint_mode == MOSAIC_MAINT_OFF && !dv.aug_reps && !dv.aug_window && dv.P == 0 &&
-                       dv.C <= 256 && est_bytes <= ((long long)(ctx->cfg.decode_fused_max_mib > 0 ? ctx->cfg.decode_fused_max_mib : 48) << 20);
+                       dv.C <= 256 && ctx->cfg.decode_fused_max_mib >= 0 &&
+                       est_bytes <= ((long long)(ctx->cfg.decode_fused_max_mib > 0 ? ctx->cfg.decode_fused_max_mib : 48) << 20);
     int S = 0;
     if (fused) {
         S = choose_splits(ctx, dv.Hkv, n_q_tokens, dv.part_entries);
@@ -1078,9 +1087,40 @@ int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, in
     }
     if (!fused || ctx->n_frames / std::max(S, 1) + 2 > 2048 ||
         (long long)dv.Hkv * S > dv.part_entries) {
-        ctx->stats.last_decode_fused = 0;
-        const int rc = mosaic_retrieve(ctx, layer, q_dev, n_q_tokens);
-        return rc != MOSAIC_OK ? rc : mosaic_attend(ctx, layer, q_dev, n_q_tokens, out_dev, lse_dev);
+        // On request (decode_fused_max_mib = -1) the selection moves into the attention launch, whose first
+        // workgroups select and publish, with splits proportional to the retrieved sizes.  Not the
+        // default: what the waiting workgroups read must cross the chip's L2s, and those round trips
+        // cost more than the selection launch they replace (28 launches of ~118 MB: 47 us against 39 us).
+        const bool layer_fused = !ctx->host && ctx->impl == MOSAIC_ATTEND_MFMA && layer >= 0 && NT == 1 &&
+                                 dv.maint_mode == MOSAIC_MAINT_OFF && !dv.aug_reps && !dv.aug_window && dv.P == 0 &&
+                                 dv.C <= 256 && dv.Hkv <= 64 && ctx->cfg.decode_fused_max_mib == -1;
+        if (!layer_fused) {
+            ctx->stats.last_decode_fused = 0;
+            const int rc = mosaic_retrieve(ctx, layer, q_dev, n_q_tokens);
+            return rc != MOSAIC_OK ? rc : mosaic_attend(ctx, layer, q_dev, n_q_tokens, out_dev, lse_dev);
+        }
+        int u0, nu;
+        int rc = check_query_args(ctx, layer, q_dev, n_q_tokens, &u0, &nu);
+        if (rc != MOSAIC_OK) return rc;
+        if (!out_dev) return fail(ctx, MOSAIC_EINVAL, "out_dev is NULL");
+        if (ctx->n_frames < ctx->W) return fail(ctx, MOSAIC_ENOTREADY, "initial clustering has not run yet (fewer than warmup_frames frames ingested)");
+        const int S2 = choose_splits(ctx, nu, n_q_tokens, dv.part_entries);
+        const int B = std::max(nu * S2, nu);
+        hipError_t e;
+        hipEvent_t ev0 = nullptr, ev1 = nullptr;
+        if ((e = take_profile_events(ctx, &ev0, &ev1)) != hipSuccess) return fail_hip(ctx, e, "kernel timing");
+        if (++ctx->launch_epoch == 0x7fffffff) ctx->launch_epoch = 1;      // (flags hold the last ~2^31 launches apart)
+        e = launch_decode_layer(dv, u0, nu, q_dev, n_q_tokens, B, (int)ctx->n_frames, ctx->cfg.score_mode,
+                                ctx->launch_epoch, kv_beyond_caches(ctx), ctx->stream, ev0, ev1);
+        if (e != hipSuccess) return fail_hip(ctx, e, "layer decode launch");
+        e = launch_attend_combine(dv, u0, nu, n_q_tokens, S2, out_dev, lse_dev, ctx->stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "combine launch");
+        ctx->sel_epoch[layer] = ctx->epoch; ctx->sel_tq[layer] = n_q_tokens;
+        ctx->stats.retrieve_calls += 1;
+        ctx->stats.attend_calls += 1;
+        ctx->stats.last_n_splits = S2;
+        ctx->stats.last_decode_fused = 2;
+        return MOSAIC_OK;
     }
     int u0, nu;
     int rc = check_query_args(ctx, layer, q_dev, n_q_tokens, &u0, &nu);
@@ -1294,6 +1334,12 @@ int32_t mosaic_get_stats(mosaic_ctx *ctx, mosaic_stats *stats) {
         ctx->stats.h2d_busy_ms = ht->busy_ms;
         ctx->stats.prefetch_calls = ht->pf_calls; ctx->stats.prefetch_fetched = ht->pf_fetched;
         ctx->stats.prefetch_useful = ht->pf_useful;
+    }
+    {   // bounded in-kernel waits that ran out (never, unless the GPU was shared with other waiting kernels)
+        int err = 0;
+        int rc = d2h(ctx, &err, ctx->dv.sync_err, 4);
+        if (rc != MOSAIC_OK || (rc = sync(ctx)) != MOSAIC_OK) return rc;
+        ctx->stats.sync_timeouts = err;
     }
     if (ctx->dv.maint_mode) {
         const DeviceView &dv = ctx->dv;

@@ -55,6 +55,8 @@ struct DeviceView {
     int *n;           // [U][C]      sizes in frames
     int *assign;      // [U][F]      frame -> cluster
     int *pos;         // [U][F]      rank of the frame among its cluster's members (ascending frame order)
+    long long *sel_flag;   // [U]    (launch number << 32 | retrieved pages) of the unit's last selection published inside a launch (k_decode_layer)
+    int *sync_err;    // [1]         set if a bounded in-kernel wait ever ran out
     int *lloyd_moved; // [U][3]      frames moved by the K-means rounds it-1, it, it+1 (mod 3): converged units skip the rest
     // self-adaptive maintainer (paper Sec. VI); maint_mode 0 = off (the arrays are then empty)
     int maint_mode, c_init, split_iters, buf_max;
@@ -118,6 +120,7 @@ struct Ctx {
     std::vector<long long> sel_epoch; // per layer: epoch at which the selection was made
     std::vector<int> sel_tq;
     long long epoch;     // bumped by ingest and reset
+    int launch_epoch;    // numbers the launches that publish a selection inside the kernel (never 0)
     long long rv_epoch;  // epoch the value representatives were last computed at
     mosaic_stats stats;
     std::string err;
@@ -180,6 +183,12 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
 // uniform: every unit has exactly n_splits splits at slots unit * n_splits + split (fused decode step)
 hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int Tq, int n_splits,
                                  void *out, float *lse, hipStream_t s, bool uniform = false);
+// selection + attention of one decode step of one layer in one launch with size-proportional splits: the
+// first n_units workgroups select for one unit each and publish the result, all workgroups then share
+// out the retrieved pages (one row tile, bf16, C <= 256).  epoch: a number no earlier launch on this
+// context has used.  B = total workgroups (>= n_units)
+hipError_t launch_decode_layer(const DeviceView &dv, int u0, int n_units, const void *q, int Tq, int B, int n_frames,
+                               int score_mode, int epoch, bool stream_kv, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 // selection + attention of one decode step in one launch (one row tile, bf16, C <= 256, uniform splits)
 hipError_t launch_decode_fused(const DeviceView &dv, int u0, int n_units, const void *q, int Tq, int n_splits,
                                int n_frames, int score_mode, bool stream_kv, hipStream_t s, hipEvent_t ev0,
@@ -271,6 +280,13 @@ struct SplitSlot {
     int S;       // number of splits of the unit
     int base;    // first split slot of the unit (partials are indexed by slot)
 };
+
+// Agent-scope (write-through / cache-bypassing) accesses for values that one workgroup publishes and
+// others of the SAME launch read: an ordinary store may sit in the writing XCD's L2 until the kernel ends.
+__device__ __forceinline__ void st_agent(int *p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ int ld_agent(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_agent(long long *p, long long v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ long long ld_agent(const long long *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 template <bool BY_UNIT>
 __device__ __forceinline__ SplitSlot split_slot(const int *n_sel_call, int n_units, int B, int key) {

@@ -972,6 +972,42 @@ def test_decode_step_fused_parity(kw):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("kw", [
+    dict(),                                                          # D = 128, 4 KV heads, G = 7
+    dict(head_dim=64, n_q_heads=8, n_kv_heads=2, tokens_per_frame=50, n_clusters=9, top_k=3),   # ragged pages, G = 4
+    dict(n_q_heads=16, n_kv_heads=1, n_clusters=200, top_k=150, n_frames=420, n_scenes=30),     # G = 16, one unit, C > 128
+    dict(n_layers=3, n_frames=2600, n_scenes=60, n_clusters=40, top_k=6),                       # frame lists beyond one batch
+])
+def test_decode_step_one_launch_with_proportional_splits_parity(kw):
+    """mosaic_decode_step in its one-launch form for bandwidth-bound steps (the launch's first workgroups
+    select and publish, all workgroups then share out the pages in proportion to the units' sizes),
+    forced on small workloads: scores, ids, token lists and attention against the oracle, bitwise equal
+    to mosaic_retrieve + mosaic_attend (the same splits), and no in-kernel wait ever ran out."""
+    wl = _small(name="layer_fused", **kw)
+    rep = harness.run_workload(wl, n_questions=0, decode_steps=3, layer_mode="fused", decode_fused_max_mib=-1)
+    _report(rep)
+    assert [v for (k_, v) in rep.notes if k_ == "decode_step_fused"] == [2] * (3 * wl.n_layers)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    a = _ingest_all(wl, K, V, (16,), decode_fused_max_mib=-1)
+    b = _ingest_all(wl, K, V, (16,), decode_fused_max_mib=-2)
+    for i in range(4):
+        q = st.question(st.draw_scene(), 1, i).to(DEV)
+        for l in range(wl.n_layers):
+            oa, la = a.decode_step(l, q[l].contiguous())
+            ob, lb = b.decode_step(l, q[l].contiguous())
+            torch.cuda.synchronize()
+            assert a.stats().last_decode_fused == 2 and b.stats().last_decode_fused == 0
+            assert torch.equal(oa, ob) and torch.equal(la, lb)
+            sa, sb = a.selection(l), b.selection(l)
+            np.testing.assert_array_equal(sa[0], sb[0]); np.testing.assert_array_equal(sa[2], sb[2])
+            for ta, tb in zip(sa[3], sb[3]):
+                np.testing.assert_array_equal(ta, tb)
+    assert a.stats().sync_timeouts == 0
+    a.close(); b.close()
+
+
+@pytest.mark.gpu
 def test_decode_step_equals_retrieve_then_attend():
     """Same ids, scores and token lists bit for bit; outputs equal up to the merge order of the
     fp32 partials (equal splits per unit instead of proportional ones)."""

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmosaic.so")
 SOURCES = ("api.hip", "host_tier.hip", "ingest_kernels.hip", "visual_kernels.hip",
-           "retrieve_kernels.hip", "attend_kernels.hip", "attend_mfma.hip", "decode_layer.hip")
+           "retrieve_kernels.hip", "attend_kernels.hip", "attend_mfma.hip", "decode_layer.hip", "attend_prefill.hip")
 # Packed-FP32 instructions are switched off for all device code.
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -261,7 +261,8 @@ int choose_splits(const mosaic_ctx *ctx, int n_units, int Tq, long long part_ent
     const DeviceView &dv = ctx->dv;
     const long long NT = ((long long)Tq * dv.G + kRowTile - 1) / kRowTile;
     const bool mfma = ctx->impl == MOSAIC_ATTEND_MFMA;
-    const long long row_blocks = NT == 1 ? 1 : (mfma ? (NT + 4 * kPrefillTiles - 1) / (4 * kPrefillTiles) : NT);
+    constexpr int pw = kPrefillWaves;
+    const long long row_blocks = NT == 1 ? 1 : (mfma ? (NT + pw * kPrefillTiles - 1) / (pw * kPrefillTiles) : NT);
     const long long est_pages = std::max<long long>(1, (ctx->n_frames * dv.k + dv.C - 1) / dv.C);
     const long long est_chunks = est_pages * dv.chunks_per_page;
     long long s;
@@ -272,7 +273,7 @@ int choose_splits(const mosaic_ctx *ctx, int n_units, int Tq, long long part_ent
         // kernel's rate a little but cost more in the combine; measured on config 4),
         // each with at least 8 chunks; a multiple of 8 keeps the workgroups that share
         // a (unit, split) on one XCD (workgroup ids congruent mod 8)
-        s = (512 + n_units * row_blocks - 1) / (n_units * row_blocks);
+        s = (2048 / pw + n_units * row_blocks - 1) / (n_units * row_blocks);
         s = std::min(s, std::max<long long>(1, est_chunks / 8));
         if (s >= 8) s = s / 8 * 8;
     } else {

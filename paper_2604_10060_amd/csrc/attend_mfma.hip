@@ -16,7 +16,6 @@
 //          t0 + 8g + j, j = 0..7 -- exactly the B operand P^T[8g+j][n] of
 // Output:  A = V^T (row slot n = channel 16*db + n, k-slots = tokens t0 + 8g + j),
 //          D = O^T[16*db + 4g + i][n].
-#include <mutex>
 
 #include "mosaic_internal.h"
 #include "attend_mfma_device.h"
@@ -380,224 +379,6 @@ __global__ __launch_bounds__(kBlock) void k_decode_fused(DeviceView dv, int u0, 
     merge_waves_store<D>(dv, acc, m, l, lx, R, (size_t)uc * S + split);
 }
 
-// ---------------------------------------------------------------------------
-// Multi-token questions (MFMA-bound).  A workgroup owns 64 * kPrefillTiles query
-// rows: wave w holds kPrefillTiles row tiles of 16 in registers and all four waves
-// walk the same chunk range, so each 32-token K/V chunk is fetched from memory once
-// per workgroup, staged in LDS (double-buffered; the loads of the next two chunks
-// are in flight, in two register sets, during the current chunk's MFMAs) and read
-// as MFMA operands by every wave.  Two workgroups share a CU, so one's barriers and
-// softmax arithmetic overlap the other's MFMAs.
-// LDS rows are padded (K: +16 B, V: +16 B) and the K rows are stored in MFMA
-// slot order so that the 16-byte operand reads are bank-conflict free.
-// A group is one (unit, split) slot -- split_slot() shares the slots out over the
-// units by retrieved size -- and its n_row_blocks workgroups read the same K/V range.
-// Workgroups go to the 8 XCDs round-robin by id and are dispatched in id order, so
-// the 1-D grid is laid out as id = 8 * (row block + n_row_blocks * (group / 8)) +
-// group % 8: a group's workgroups share one XCD (one L2) and have neighbouring
-// dispatch slots there, which keeps them together in time -- also when the grid
-// exceeds the chip or several streams' kernels interleave -- so the group's K/V is
-// fetched from memory once and found in L2 by the rest.
-// ---------------------------------------------------------------------------
-template <int D, bool AUG>
-__global__ __launch_bounds__(kBlock, 2) void k_attend_prefill_mfma(DeviceView dv, int u0, int n_units,
-                                                                   const unsigned short *q, int Tq,
-                                                                   int NT, int n_groups, int n_row_blocks,
-                                                                   int group_blocks) {
-    constexpr int KK = D / 32, DB = D / 16, RTW = kPrefillTiles;
-    constexpr int KROW = D + 8, VROW = kChunk + 8;       // LDS row strides in elements
-    constexpr int KPIECES = kChunk * D / 8, VPIECES = D * kChunk / 8;   // 16-byte pieces per chunk
-    constexpr int KPT = KPIECES / kBlock, VPT = VPIECES / kBlock;       // pieces per thread
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, g = lane / 16, n = lane % 16;
-    // workgroup id -> (group = (unit, split) slot, row block): see the mapping above
-    if constexpr (AUG) {
-        if ((int)blockIdx.x >= group_blocks) {   // extra workgroups: the global representatives' part (augmentation)
-            const int idx = (int)blockIdx.x - group_blocks;
-            attend_reps_partial<unsigned short, D>(dv, u0, idx / NT, idx % NT, q, Tq);
-            return;
-        }
-    }
-    const int xcd = (int)blockIdx.x % 8, seq = (int)blockIdx.x / 8;
-    const int grp = (seq / n_row_blocks) * 8 + xcd, yb = seq % n_row_blocks;
-    if (grp >= n_groups) return;                   // block-uniform: no barrier reached yet
-    const SplitSlot slot = split_slot<false>(dv.n_sel + u0, n_units, n_groups, grp);
-    if (slot.uc < 0) return;
-    const int uc = slot.uc, u = u0 + uc, split = slot.split, n_splits = slot.S;
-    const int T = dv.T, F = dv.F, cpp = dv.chunks_per_page;
-    const int lc = uc / dv.Hkv, h = u % dv.Hkv;
-    const int tile0 = (yb * 4 + wave) * RTW;
-    // LDS (dynamic: 74 KB at D = 128): two buffers of two 32-token chunks each, K then V
-    extern __shared__ __attribute__((aligned(16))) unsigned short prefill_lds[];
-    typedef unsigned short (*KTile)[kChunk][KROW];      // [buffer * 2 + half][token slot][channel]
-    typedef unsigned short (*VTile)[D][VROW];           // [buffer * 2 + half][channel][token]
-    const KTile k_lds = reinterpret_cast<KTile>(prefill_lds);
-    const VTile v_lds = reinterpret_cast<VTile>(prefill_lds + 4 * kChunk * KROW);
-
-    bf16x8 qf[RTW][KK];
-#pragma unroll
-    for (int r = 0; r < RTW; ++r) load_q<D>(dv, q, lc, h, Tq, (tile0 + r) * kRowTile + n, g, qf[r]);
-
-    const int *sel = dv.sel_pages + (size_t)u * F;
-    const int NC = __builtin_amdgcn_readfirstlane(dv.n_sel[u]) * cpp;
-    const int cps = (NC + n_splits - 1) / n_splits;
-    const int c0 = __builtin_amdgcn_readfirstlane(split * cps);
-    const int c1 = __builtin_amdgcn_readfirstlane(min(NC, c0 + cps));
-    const float sl2 = 1.4426950408889634f / sqrtf((float)D);
-
-    f32x4 acc[RTW][DB], l[RTW];                    // l: row sums, kept by an all-ones MFMA
-    float m[RTW], lx[RTW];
-#pragma unroll
-    for (int r = 0; r < RTW; ++r) {
-        m[r] = -INFINITY; l[r] = f32x4{0.f, 0.f, 0.f, 0.f}; lx[r] = 0.f;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) acc[r][db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    // Chunks are fetched in order.  The fetch cursor (chunk nf = chunk f_cc of the
-    // f_pi-th selected page) advances by increments, page addresses are worked out once
-    // per page, and the id of the page after the current one is read (a wave-uniform
-    // load) a whole page ahead, so no fetch waits on a dependent load or divides.
-    const int cl = c1 - 1, n_pages = NC / cpp;
-    const char *const kbase = dv.k_store + (size_t)u * dv.k_ustride;
-    const char *const vbase = dv.v_store + (size_t)u * dv.v_ustride;
-    int nf = c0, f_pi = c0 / cpp, f_cc = c0 - f_pi * cpp;
-    const unsigned short *f_kp = nullptr, *f_vp = nullptr;
-    auto set_page = [&](int page) {
-        f_kp = reinterpret_cast<const unsigned short *>(kbase + (size_t)page * dv.kpage);
-        f_vp = reinterpret_cast<const unsigned short *>(vbase + (size_t)page * dv.vpage);
-    };
-    int pg_next = 0;
-    if (c0 < c1) {
-        set_page(sel[f_pi]);
-        pg_next = sel[min(f_pi + 1, n_pages - 1)];
-    }
-    int c_cc = f_cc;                                  // compute cursor: chunk inside its page
-    // One chunk's worth of 16-byte pieces per thread (KPT, VPT <= 2), held in named
-    // members so that both register sets stay in VGPRs.
-    static_assert(KPT >= 1 && KPT <= 2 && VPT >= 1 && VPT <= 2, "piece count per thread");
-    struct Regs { u32x4 k0, k1, v0, v1; };
-    Regs ra, rb;
-    auto fetch = [&]() -> Regs {   // global -> registers; past the end re-reads the last chunk
-        const int t0 = f_cc * kChunk;
-        const unsigned short *kp = f_kp, *vp = f_vp + (size_t)f_cc * D * kChunk;
-        auto kpiece = [&](int i) {
-            const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);
-            return *reinterpret_cast<const u32x4 *>(kp + (size_t)min(t0 + t, T - 1) * D + seg * 8);
-        };
-        auto vpiece = [&](int i) {   // chunk block is contiguous
-            return *reinterpret_cast<const u32x4 *>(vp + (size_t)(tid + kBlock * i) * 8);
-        };
-        Regs r;
-        r.k0 = kpiece(0);
-        r.k1 = KPT > 1 ? kpiece(KPT - 1) : r.k0;
-        r.v0 = vpiece(0);
-        r.v1 = VPT > 1 ? vpiece(VPT - 1) : r.v0;
-        if (nf < cl) {                                // wave-uniform
-            ++nf;
-            if (++f_cc == cpp) {
-                f_cc = 0; ++f_pi;
-                set_page(pg_next);
-                pg_next = sel[min(f_pi + 1, n_pages - 1)];
-            }
-        }
-        return r;
-    };
-    auto stage = [&](int buf, const Regs &r) {   // registers -> LDS; buf = buffer * 2 + half
-        auto kput = [&](int i, u32x4 x) {
-            const int p = tid + kBlock * i, t = p / (D / 8), seg = p % (D / 8);
-            const int row = 16 * ((t / 4) % 2) + 4 * (t / 8) + t % 4;   // MFMA slot order
-            *reinterpret_cast<u32x4 *>(&k_lds[buf][row][seg * 8]) = x;
-        };
-        auto vput = [&](int i, u32x4 x) {
-            const int p = tid + kBlock * i, d = p / (kChunk / 8), seg = p % (kChunk / 8);
-            *reinterpret_cast<u32x4 *>(&v_lds[buf][d][seg * 8]) = x;
-        };
-        kput(0, r.k0);
-        if (KPT > 1) kput(1, r.k1);
-        vput(0, r.v0);
-        if (VPT > 1) vput(1, r.v1);
-    };
-    auto compute = [&](int buf) {
-        bf16x8 kf[2 * KK], vf[DB];
-#pragma unroll
-        for (int tau = 0; tau < 2; ++tau)
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk)
-                kf[tau * KK + kk] = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const uint4 *>(&k_lds[buf][16 * tau + n][32 * kk + 8 * g]));
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-            vf[db] = __builtin_bit_cast(
-                bf16x8, *reinterpret_cast<const uint4 *>(&v_lds[buf][16 * db + n][8 * g]));
-        const int n_valid = min(kChunk, T - c_cc * kChunk);
-        c_cc = c_cc + 1 == cpp ? 0 : c_cc + 1;
-        chunk_step_multi<D, RTW, f32x4>(kf, vf, qf, n_valid, g, sl2, acc, m, l, lx);
-    };
-
-    // Pipeline, two chunks (64 tokens) per barrier: the pair (c, c+1) is computed from LDS
-    // buffer b (slots 2b, 2b+1) while the next pair travels global -> the two register sets,
-    // and is stored into the other buffer once the pair is done.  Half as many barriers and
-    // twice the arithmetic between them as with one chunk per barrier; the same 64 tokens of
-    // memory latency hidden.  Fetches past the end re-read the last chunk instead of being
-    // skipped, so the register sets are written unconditionally and stay in registers.
-    if (c0 < c1) {
-        ra = fetch();
-        rb = fetch();
-        stage(0, ra);
-        stage(1, rb);
-        __syncthreads();
-        int c = c0;
-        for (; c + 4 <= c1; c += 4) {
-            ra = fetch();
-            rb = fetch();
-            compute(0);
-            compute(1);
-            stage(2, ra);
-            stage(3, rb);
-            __syncthreads();
-            ra = fetch();
-            rb = fetch();
-            compute(2);
-            compute(3);
-            stage(0, ra);
-            stage(1, rb);
-            __syncthreads();
-        }
-        const int rem = c1 - c;                       // 0..3 chunks left, the first two in buffer 0
-        if (rem > 2) {
-            ra = fetch();
-            compute(0);
-            compute(1);
-            stage(2, ra);
-            __syncthreads();
-            compute(2);
-        } else if (rem > 0) {
-            compute(0);
-            if (rem > 1) compute(1);
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < RTW; ++r) {
-        const int tile = tile0 + r;
-        if (tile >= NT) break;
-        const float lr = l[r][0];
-        float xr = lx[r];                              // this lane's 8 tokens per chunk: add the four lane groups
-        xr += __shfl_xor(xr, 16, 64);
-        xr += __shfl_xor(xr, 32, 64);
-        const size_t entry = (size_t)slot.base * NT + (size_t)tile * n_splits + split;
-        float *po = dv.part_o + (entry * kRowTile + n) * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-            *reinterpret_cast<float4 *>(po + 16 * db + 4 * g) =
-                make_float4(acc[r][db][0], acc[r][db][1], acc[r][db][2], acc[r][db][3]);
-        if (g == 0) {
-            dv.part_ml[entry * kMlRows * kRowTile + n] = m[r];
-            dv.part_ml[entry * kMlRows * kRowTile + kRowTile + n] = lr;
-            dv.part_ml[entry * kMlRows * kRowTile + 2 * kRowTile + n] = xr;
-        }
-    }
-}
-
 } // namespace
 
 hipError_t launch_decode_fused(const DeviceView &dv, int u0, int n_units, const void *q, int Tq, int n_splits,
@@ -632,25 +413,7 @@ hipError_t launch_attend_mfma(const DeviceView &dv, int u0, int n_units, const v
             else stream_kv ? go(k_attend_decode_mfma<128, false, true>) : go(k_attend_decode_mfma<128, false, false>);
         }
     } else {
-        // dynamic LDS of the multi-token kernel: 4 K tiles [32][D + 8] and 4 V tiles [D][40] of bf16
-        const size_t lds = (size_t)(4 * kChunk * (dv.D + 8) + 4 * dv.D * (kChunk + 8)) * 2;
-        static std::once_flag attr_once;          // process-wide, but set exactly once whichever handle comes first
-        std::call_once(attr_once, [] {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<64, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<64, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<128, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attend_prefill_mfma<128, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-        });
-        const int n_groups = n_units * n_splits, rb = (NT + 4 * kPrefillTiles - 1) / (4 * kPrefillTiles);
-        const int gb = (n_groups + 7) / 8 * 8 * rb;
-        const dim3 grid(gb + (dv.aug_reps ? n_units * NT : 0));
-        if (dv.aug_reps) {
-            if (dv.D == 64) launch_timed((k_attend_prefill_mfma<64, true>), grid, block, lds, s, ev0, ev1, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
-            else launch_timed((k_attend_prefill_mfma<128, true>), grid, block, lds, s, ev0, ev1, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
-        } else {
-            if (dv.D == 64) launch_timed((k_attend_prefill_mfma<64, false>), grid, block, lds, s, ev0, ev1, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
-            else launch_timed((k_attend_prefill_mfma<128, false>), grid, block, lds, s, ev0, ev1, dv, u0, n_units, qq, Tq, NT, n_groups, rb, gb);
-        }
+        return launch_attend_prefill(dv, u0, n_units, qq, Tq, n_splits, s, ev0, ev1);
     }
     return hipGetLastError();
 }

@@ -16,6 +16,7 @@ constexpr int kChunk = 32;        // tokens per attention step, always inside on
 constexpr int kMaxSplits = 64;    // KV splits per (unit, row tile), average over the units of a launch
 constexpr int kMaxUnitSplits = 256; // ... and the most one unit can be given when the units retrieve unequal amounts
 constexpr int kPrefillTiles = 2;  // row tiles per wavefront in the multi-tile MFMA kernel
+constexpr int kPrefillWaves = 4;  // wavefronts per workgroup of that kernel (64 * kPrefillTiles * 4 = 128 query rows)
 constexpr int kMlRows = 3;        // rows of 16 floats per attention partial besides O: max, normaliser, exact-weight sum
 
 // Device-side view of one context: plain pointers into the caller's arena.
@@ -175,6 +176,8 @@ hipError_t launch_expand_tok_idx(const DeviceView &dv, int u0, int n_units, hipS
 // n_splits = average splits per unit chosen by the caller (B = n_units * n_splits split
 // workgroups are shared out by split_slot); partial entries needed = B * NT
 // ev0/ev1 (may be null) receive the kernel's own start/stop timestamps
+hipError_t launch_attend_prefill(const DeviceView &dv, int u0, int n_units, const unsigned short *q, int Tq,
+                                 int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 hipError_t launch_attend_valu(const DeviceView &dv, int u0, int n_units, const void *q, int Tq,
                               int n_splits, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1);
 // stream_kv: the decode-shape kernels load K/V with the non-temporal hint (stores far beyond the caches)

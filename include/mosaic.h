@@ -149,6 +149,16 @@ typedef struct {
     int32_t n_partitions;         /* P, 0..64 */
     int32_t visual_dim;           /* Dv, 1..4096 */
     int32_t top_partitions;       /* 1..P; 0 -> max(1, P / 4) */
+    /* Batched matching, overlapped (paper Sec. VII-A: frame encoding is pipelined; the assignment of
+     * frame t depends on frame t-1, its page store does not).  1: the order-dependent part of
+     * mosaic_ingest_frame -- assignment chain, initial clustering, re-clustering -- runs on a stream
+     * the context owns, after the call's page stores (an event), while the caller's stream goes on
+     * with the next call's page stores.  Every mosaic_* call that reads or changes the index first
+     * makes the caller's stream wait for that work, so results are the same bit for bit; work the
+     * caller enqueues on its stream by itself (or a synchronisation of that stream alone) is NOT
+     * ordered after it: call mosaic_ingest_join first.  MOSAIC_TIER_HBM, n_partitions = 0 and calls
+     * of more than one frame only (other calls run wholly on the caller's stream, as with 0). */
+    int32_t ingest_overlap;
 } mosaic_config;
 
 /* maint_mode.  _EAGER: every cluster counts as GPU resident, an invalid cluster is split at once
@@ -242,6 +252,11 @@ int32_t mosaic_reset(mosaic_ctx *ctx);
  * Re-clustering (recluster_every > 0) is not available in the host tier. */
 int32_t mosaic_ingest_frame(mosaic_ctx *ctx, const void *k_dev, const void *v_dev,
                             int32_t n_frames);
+
+/* Makes the context's stream (mosaic_config.stream) wait for the order-dependent part of earlier
+ * mosaic_ingest_frame calls that ingest_overlap = 1 put on the context's own stream.  Enqueues a
+ * wait, does not block the host; no-op when nothing is pending.  Sec. VII-A (pipelined encoding). */
+int32_t mosaic_ingest_join(mosaic_ctx *ctx);
 
 /* Frame Encoding under the nested hierarchy (Sec. V-B; config.n_partitions > 0, where it replaces
  * mosaic_ingest_frame, which then fails with EINVAL -- and vice versa).  k_dev, v_dev, n_frames

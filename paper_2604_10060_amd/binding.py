@@ -27,7 +27,7 @@ EXPORTS = (
     "mosaic_host_alloc", "mosaic_host_free", "mosaic_workspace_size", "mosaic_create", "mosaic_destroy", "mosaic_reset",
     "mosaic_ingest_frame", "mosaic_retrieve", "mosaic_prefetch", "mosaic_attend", "mosaic_attend_static",
     "mosaic_get_assignments", "mosaic_get_centroids", "mosaic_get_summaries", "mosaic_get_maintainer",
-    "mosaic_decode_step", "mosaic_ingest_frame_visual", "mosaic_get_partitions", "mosaic_get_partition_selection",
+    "mosaic_decode_step", "mosaic_ingest_frame_visual", "mosaic_ingest_join", "mosaic_get_partitions", "mosaic_get_partition_selection",
     "mosaic_get_selection", "mosaic_get_stats", "mosaic_get_cache_directory", "mosaic_profile_enable",
     "mosaic_profile_read", "mosaic_calibration_copy", "mosaic_last_error",
 )
@@ -57,6 +57,7 @@ class Config(C.Structure):
         ("aug_global_reps", C.c_int32), ("aug_window_frames", C.c_int32),
         ("prefetch_top_k", C.c_int32), ("n_partitions", C.c_int32),
         ("visual_dim", C.c_int32), ("top_partitions", C.c_int32),
+        ("ingest_overlap", C.c_int32),
     ]
 
 
@@ -96,6 +97,7 @@ def load_library():
     L.mosaic_reset.argtypes = [vp]
     L.mosaic_ingest_frame.argtypes = [vp, vp, vp, i32]
     L.mosaic_ingest_frame_visual.argtypes = [vp, vp, vp, vp, i32]
+    L.mosaic_ingest_join.argtypes = [vp]
     L.mosaic_get_partitions.argtypes = [vp, vp, vp, vp, vp, vp]
     L.mosaic_get_partition_selection.argtypes = [vp, i32, vp, vp, vp]
     L.mosaic_retrieve.argtypes = [vp, i32, vp, i32]
@@ -128,7 +130,8 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
                 slab_frames=0, cache_pages_per_unit=0, cache_fraction=0.0,
                 maint_mode=MAINT_OFF, init_clusters=0, split_iters=0, buffer_max=0,
                 tau_min=0.0, tau_max=0.0, tau_n0=1.0, aug_global_reps=0, aug_window_frames=0,
-                prefetch_top_k=0, n_partitions=0, visual_dim=0, top_partitions=0, decode_fused_max_mib=0) -> Config:
+                prefetch_top_k=0, n_partitions=0, visual_dim=0, top_partitions=0, decode_fused_max_mib=0,
+                ingest_overlap=0) -> Config:
     c = Config()
     c.n_layers, c.n_q_heads, c.n_kv_heads = n_layers, n_q_heads, n_kv_heads
     c.head_dim, c.tokens_per_frame, c.max_frames = head_dim, tokens_per_frame, max_frames
@@ -144,6 +147,7 @@ def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, tokens_per_frame, 
     c.prefetch_top_k = prefetch_top_k
     c.decode_fused_max_mib = decode_fused_max_mib
     c.n_partitions, c.visual_dim, c.top_partitions = n_partitions, visual_dim, top_partitions
+    c.ingest_overlap = ingest_overlap
     return c
 
 
@@ -263,6 +267,10 @@ class Mosaic:
         self._check_tensor(k, shape, "k")
         self._check_tensor(v, shape, "v")
         self._check(self._L.mosaic_ingest_frame(self._h, _ptr(k), _ptr(v), n))
+
+    def ingest_join(self):
+        """ingest_overlap = 1: make the context's stream wait for the ingest work on the library's own stream"""
+        self._check(self._L.mosaic_ingest_join(self._h))
 
     def ingest_frame_visual(self, k, v, e):
         """Nested hierarchy: k, v as for ingest_frame; e: fp32 [n_frames][visual_dim]"""

@@ -128,6 +128,7 @@ int check_config(const mosaic_config *c, std::string &why) {
     if (c->attend_impl == MOSAIC_ATTEND_MFMA && c->kv_dtype != MOSAIC_BF16) { why = "the MFMA attention kernel needs bf16 KV"; return MOSAIC_EINVAL; }
     if ((long long)c->max_frames * c->tokens_per_frame > 0x7fffffffLL) { why = "max_frames * tokens_per_frame must fit in int32"; return MOSAIC_EINVAL; }
     if (c->decode_fused_max_mib < -2) { why = "decode_fused_max_mib must be >= -2"; return MOSAIC_EINVAL; }
+    if (c->ingest_overlap != 0 && c->ingest_overlap != 1) { why = "ingest_overlap must be 0 or 1"; return MOSAIC_EINVAL; }
     if (c->tier != MOSAIC_TIER_HBM && c->tier != MOSAIC_TIER_HOST) { why = "tier must be MOSAIC_TIER_HBM or MOSAIC_TIER_HOST"; return MOSAIC_EINVAL; }
     if (c->tier == MOSAIC_TIER_HOST) {
         if (c->recluster_every != 0) { why = "re-clustering is not available in the host tier (pages would have to move between slabs)"; return MOSAIC_EINVAL; }
@@ -364,6 +365,17 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
         return fail_hip(nullptr, e, "hipGetSymbolAddress(static attention scratch)");
     }
     ctx->stream = (hipStream_t)cfg->stream;
+    ctx->assign_stream = nullptr; ctx->stored = nullptr; ctx->assigned = nullptr; ctx->assign_pending = false;
+    if (cfg->ingest_overlap == 1 && cfg->tier == MOSAIC_TIER_HBM && cfg->n_partitions == 0) {
+        if ((e = hipStreamCreateWithFlags(&ctx->assign_stream, hipStreamNonBlocking)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&ctx->stored, hipEventDisableTiming)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&ctx->assigned, hipEventDisableTiming)) != hipSuccess) {
+            if (ctx->assign_stream) (void)hipStreamDestroy(ctx->assign_stream);
+            if (ctx->stored) (void)hipEventDestroy(ctx->stored);
+            delete ctx;
+            return fail_hip(nullptr, e, "stream / events of the overlapped ingest");
+        }
+    }
     ctx->W = L.W;
     ctx->iters = cfg->lloyd_iters > 0 ? cfg->lloyd_iters : 8;
     ctx->impl = L.impl;
@@ -496,6 +508,12 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
 int32_t mosaic_destroy(mosaic_ctx *ctx) {
     if (!ctx) return MOSAIC_EINVAL;
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->assign_stream) {
+        (void)hipStreamSynchronize(ctx->assign_stream);
+        (void)hipStreamDestroy(ctx->assign_stream);
+        (void)hipEventDestroy(ctx->stored);
+        (void)hipEventDestroy(ctx->assigned);
+    }
     if (HostTier *ht = ctx->host) {
         if (ht->sel_stream) { (void)hipStreamSynchronize(ht->sel_stream); (void)hipStreamDestroy(ht->sel_stream); }
         if (ht->copy_stream) { (void)hipStreamSynchronize(ht->copy_stream); (void)hipStreamDestroy(ht->copy_stream); }
@@ -508,6 +526,21 @@ int32_t mosaic_destroy(mosaic_ctx *ctx) {
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     delete ctx;
     return MOSAIC_OK;
+}
+
+// Overlapped ingest: the caller's stream waits for the order-dependent part that earlier ingest calls
+// left on the context's own stream.  Called by everything that reads or changes the index.
+static int join_ingest(mosaic_ctx *ctx) {
+    if (!ctx->assign_pending) return MOSAIC_OK;
+    const hipError_t e = hipStreamWaitEvent(ctx->stream, ctx->assigned, 0);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent(overlapped ingest)");
+    ctx->assign_pending = false;
+    return MOSAIC_OK;
+}
+
+int32_t mosaic_ingest_join(mosaic_ctx *ctx) {
+    if (!ctx) return MOSAIC_EINVAL;
+    return join_ingest(ctx);
 }
 
 // State that must read as empty before the initial clustering has run: the flags of the in-kernel
@@ -529,6 +562,7 @@ static hipError_t clear_maintainer(mosaic_ctx *ctx) {
 
 int32_t mosaic_reset(mosaic_ctx *ctx) {
     if (!ctx) return MOSAIC_EINVAL;
+    { const int rc = join_ingest(ctx); if (rc != MOSAIC_OK) return rc; }
     ctx->n_frames = 0;
     ctx->epoch += 1;
     if (HostTier *ht = ctx->host) {
@@ -726,6 +760,11 @@ static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, 
     // A single frame of the online phase takes one launch where the assignment kernel that keeps
     // the table in registers applies: its workgroups store the pages and form the summary themselves.
     const bool one_launch = n_frames == 1 && ctx->n_frames >= ctx->W && !dv.maint_mode && dv.C <= 128;
+    // Overlapped ingest: the order-dependent part of a batched call goes to the context's own stream
+    // (it reads nothing of the caller's buffers), so that the next call's page stores run beside it.
+    const bool overlap = ctx->assign_stream != nullptr && n_frames > 1;
+    if (!overlap) { const int rc = join_ingest(ctx); if (rc != MOSAIC_OK) return rc; }
+    const hipStream_t dep = overlap ? ctx->assign_stream : ctx->stream;
     // pages + summaries of the whole batch (independent across frames); the grid's
     // y dimension is limited to 65535 frames per launch
     for (int done = 0; done < n_frames && !one_launch;) {
@@ -742,6 +781,11 @@ static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, 
         }
         done += nb;
     }
+    if (overlap) {
+        if ((e = hipEventRecord(ctx->stored, ctx->stream)) != hipSuccess ||
+            (e = hipStreamWaitEvent(ctx->assign_stream, ctx->stored, 0)) != hipSuccess)
+            return fail_hip(ctx, e, "ordering the assignment after the page stores");
+    }
     // temporally dependent part, in stream order
     long long f = ctx->n_frames;
     const long long end = f + n_frames, W = ctx->W, every = ctx->cfg.recluster_every;
@@ -750,13 +794,13 @@ static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, 
             f = std::min(end, W);
             if (f == W) {
                 if (dv.P > 0) {      // the visual level first: the units' K-means runs inside its partitions
-                    e = launch_visual_lloyd(dv, (int)W, ctx->iters, ctx->stream);
+                    e = launch_visual_lloyd(dv, (int)W, ctx->iters, dep);
                     if (e != hipSuccess) return fail_hip(ctx, e, "visual clustering launch");
                 }
-                e = launch_lloyd(dv, (int)W, ctx->iters, true, ctx->stream);
+                e = launch_lloyd(dv, (int)W, ctx->iters, true, dep);
                 if (e != hipSuccess) return fail_hip(ctx, e, "initial clustering launch");
                 if (dv.P > 0) {
-                    e = launch_partition_reps(dv, (int)W, ctx->stream);
+                    e = launch_partition_reps(dv, (int)W, dep);
                     if (e != hipSuccess) return fail_hip(ctx, e, "partition representatives launch");
                 }
                 ctx->stats.lloyd_runs += 1;
@@ -766,18 +810,23 @@ static int ingest_frames(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, 
         long long seg_end = end;
         if (every > 0) seg_end = std::min(end, (f / every + 1) * every);
         if (dv.P > 0) {
-            e = launch_visual_assign(dv, e_dev + (size_t)(f - ctx->n_frames) * dv.Dv, (int)f, (int)seg_end, ctx->stream);
+            e = launch_visual_assign(dv, e_dev + (size_t)(f - ctx->n_frames) * dv.Dv, (int)f, (int)seg_end, dep);
             if (e != hipSuccess) return fail_hip(ctx, e, "visual assignment launch");
         }
-        e = one_launch ? launch_ingest_one(dv, k_dev, v_dev, (int)f, ctx->stream)
-                       : launch_assign_update(dv, (int)f, (int)seg_end, ctx->stream);
+        e = one_launch ? launch_ingest_one(dv, k_dev, v_dev, (int)f, dep)
+                       : launch_assign_update(dv, (int)f, (int)seg_end, dep);
         if (e != hipSuccess) return fail_hip(ctx, e, "assign_update launch");
         f = seg_end;
         if (every > 0 && f % every == 0) {
-            e = launch_lloyd(dv, (int)f, ctx->iters, false, ctx->stream);
+            e = launch_lloyd(dv, (int)f, ctx->iters, false, dep);
             if (e != hipSuccess) return fail_hip(ctx, e, "re-clustering launch");
             ctx->stats.lloyd_runs += 1;
         }
+    }
+    if (overlap) {
+        if ((e = hipEventRecord(ctx->assigned, ctx->assign_stream)) != hipSuccess)
+            return fail_hip(ctx, e, "marking the end of the assignment");
+        ctx->assign_pending = true;
     }
     ctx->n_frames = end;
     ctx->epoch += 1;
@@ -792,6 +841,7 @@ static int check_query_args(mosaic_ctx *ctx, int32_t layer, const void *q_dev, i
     if (!q_dev) return fail(ctx, MOSAIC_EINVAL, "q_dev is NULL");
     if ((uintptr_t)q_dev % 16) return fail(ctx, MOSAIC_EINVAL, "q_dev must be 16-byte aligned");
     if (layer < -1 || layer >= ctx->dv.L) return fail(ctx, MOSAIC_EINVAL, "layer out of range");
+    { const int rc = join_ingest(ctx); if (rc != MOSAIC_OK) return rc; }       // every query call comes through here
     const int maxq = ctx->cfg.max_q_tokens > 0 ? ctx->cfg.max_q_tokens : 256;
     if (Tq < 1 || Tq > maxq) return fail(ctx, MOSAIC_EINVAL, "n_q_tokens must be in 1..max_q_tokens");
     *u0 = layer < 0 ? 0 : layer * ctx->dv.Hkv;
@@ -1144,12 +1194,14 @@ int32_t mosaic_decode_step(mosaic_ctx *ctx, int32_t layer, const void *q_dev, in
     return MOSAIC_OK;
 }
 
-static int d2h(mosaic_ctx *ctx, void *dst, const void *src, size_t bytes) {
+static int d2h(mosaic_ctx *ctx, void *dst, const void *src, size_t bytes) {     // (observers: after any overlapped ingest)
+    { const int rc = join_ingest(ctx); if (rc != MOSAIC_OK) return rc; }
     hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync D2H");
     return MOSAIC_OK;
 }
 static int sync(mosaic_ctx *ctx) {
+    { const int rc = join_ingest(ctx); if (rc != MOSAIC_OK) return rc; }
     hipError_t e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
     return MOSAIC_OK;

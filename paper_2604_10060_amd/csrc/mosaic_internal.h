@@ -137,6 +137,11 @@ struct Ctx {
     long long *h_cnt;        // ... its counters, [U][4]
     int *h_nbuf, *h_buf_frame, *h_buf_owner;   // ... its singleton buffer, [U] / [U][buf_max]
     int *h_resident;         // residency flags on their way to the device, [U][C]
+    // ingest_overlap: the order-dependent part of batched ingest calls runs here, after `stored`;
+    // `assigned` marks its end and the caller's stream waits for it before anything touches the index
+    hipStream_t assign_stream;
+    hipEvent_t stored, assigned;
+    bool assign_pending;
     // profiling
     bool profile;
     std::vector<hipEvent_t> ev;      // pool of pairs, created by mosaic_profile_enable

@@ -154,6 +154,51 @@ def test_single_frame_calls_equal_batched_ingest_variants(kw, over):
         np.testing.assert_array_equal(a, b)
 
 
+@pytest.mark.parametrize("over", [
+    dict(),
+    dict(maint_mode=binding.MAINT_EAGER, init_clusters=4, tau_min=1.0, tau_max=2.0, tau_n0=8.0, recluster_every=0),
+])
+def test_overlapped_ingest_equals_plain_ingest_bitwise(over):
+    """ingest_overlap = 1 (Sec. VII-A pipelining: the order-dependent part of a batched call on the context's
+    own stream, the next call's page stores beside it) leaves the same state and outputs bit for bit as the
+    plain call order, with queries, observers, single-frame calls and a reset in between."""
+    wl = _small(n_frames=300, recluster_every=over.pop("recluster_every", 64), warmup_frames=24, lloyd_iters=3)
+    st = inputs.SceneStream(wl)
+    K, V = [x.to(DEV) for x in st.frames(0, wl.n_frames)]
+    q = st.question(0, 2, 0).to(DEV)[0].contiguous()
+    pattern = (16, 37, 1, 64, 5, 1, 16)
+    res = []
+    for overlap in (0, 1):
+        m = binding.Mosaic(binding.config_for(wl, ingest_overlap=overlap, **over), device=DEV)
+        seen = []
+        for rounds in range(2):                    # the second round after a reset
+            f = i = 0
+            while f < wl.n_frames:
+                nb = min(pattern[i % len(pattern)], wl.n_frames - f)
+                m.ingest_frame(K[f:f + nb].contiguous(), V[f:f + nb].contiguous())
+                f += nb
+                i += 1
+                if f >= wl.warmup_frames and i % 3 == 0:     # a query between ingest calls
+                    m.retrieve(0, q)
+                    out, lse = m.attend(0, q)
+                    seen.append((out.float().cpu().numpy(), lse.cpu().numpy()))
+                if i % 5 == 0:
+                    seen.append((m.assignments(),))          # an observer between ingest calls
+            if overlap:
+                m.ingest_join()
+            torch.cuda.synchronize()
+            r, n = m.centroids()
+            seen.append((m.assignments(), r, n, m.summaries()))
+            if rounds == 0:
+                m.reset()
+        res.append(seen)
+        m.close()
+    assert len(res[0]) == len(res[1])
+    for a, b in zip(res[0], res[1]):
+        for x, y in zip(a, b):
+            np.testing.assert_array_equal(x, y)
+
+
 def test_reset_and_rerun_is_deterministic():
     wl = _small(n_frames=80, n_clusters=6, top_k=2)
     st = inputs.SceneStream(wl)

@@ -28,8 +28,9 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    # 16 int32 fields; pointer, size_t, pointer; 2 int32, float, int32; pointer, size_t
-    assert C.sizeof(binding.Config) == 16 * 4 + 3 * 8 + 4 * 4 + 2 * 8 + 4 * 4 + 3 * 8 + 2 * 4 + 4 * 4
+    # 16 int32 fields; pointer, size_t, pointer; 2 int32, float, int32; pointer, size_t; 4 int32; 3 doubles;
+    # 2 int32; 4 int32; 1 int32 and 4 bytes of tail padding
+    assert C.sizeof(binding.Config) == 16 * 4 + 3 * 8 + 4 * 4 + 2 * 8 + 4 * 4 + 3 * 8 + 2 * 4 + 4 * 4 + 4 + 4
     assert C.sizeof(binding.Stats) == 5 * 8 + 4 * 4 + 5 * 8 + 3 * 8 + 5 * 8
 
 

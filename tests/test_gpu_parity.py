@@ -79,6 +79,8 @@ def test_shapes_fp32(kw):
     (256, dict(n_frames=128, n_clusters=8, top_k=3)),          # 1792 rows: 7 full 256-row workgroups
     (41, dict(tokens_per_frame=50, n_frames=96)),              # 287 rows: 18 tiles, ragged last workgroup and tile
     (19, dict(n_q_heads=8, n_kv_heads=4, head_dim=64)),        # G = 2, D = 64, 38 rows
+    (64, dict(tokens_per_frame=196, n_frames=64, n_clusters=6, top_k=2)),   # 7 chunks per page, the last with 4 tokens
+    (70, dict(n_q_heads=8, n_kv_heads=4, head_dim=64, tokens_per_frame=40)),   # D = 64, 140 rows (two row blocks), ragged pages
 ])
 def test_long_question_prefill_bf16(tq, kw):
     rep = harness.run_workload(_small(question_tokens=tq, **kw))

@@ -55,6 +55,13 @@ typedef __attribute__((address_space(1))) const void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 typedef const __attribute__((address_space(4))) int *cint_ptr;
 
+// maximum of three floats in one instruction (no NaNs reach it: logits are finite or -inf)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // s_waitcnt that waits until at most n vector-memory loads of this wave are outstanding (and for nothing else)
 template <int N>
 __device__ __forceinline__ void wait_vmem_le() {
@@ -115,10 +122,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void k_attend_prefill_mfm
     const float sl2 = 1.4426950408889634f / sqrtf((float)D);
 
     f32x4 acc[RTW][DB], l[RTW];                    // l: row sums, kept by an all-ones MFMA
-    float m[RTW], lx[RTW];
+    float m[RTW], lx[RTW], bar[RTW];               // bar: a raw logit above it raises the row's reference m
 #pragma unroll
     for (int r = 0; r < RTW; ++r) {
-        m[r] = -INFINITY; l[r] = f32x4{0.f, 0.f, 0.f, 0.f}; lx[r] = 0.f;
+        m[r] = -INFINITY; bar[r] = -INFINITY; l[r] = f32x4{0.f, 0.f, 0.f, 0.f}; lx[r] = 0.f;
 #pragma unroll
         for (int db = 0; db < DB; ++db) acc[r][db] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -277,11 +284,15 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void k_attend_prefill_mfm
             for (int j = 0; j < 8; ++j)
                 if (8 * g + j >= n_valid) s[j / 4][j % 4] = -INFINITY;
         }
-        float cm = fmaxf(fmaxf(s[0][0], s[0][1]), s[0][2]);
-        cm = fmaxf(fmaxf(cm, s[0][3]), s[1][0]);
-        cm = fmaxf(fmaxf(cm, s[1][1]), s[1][2]);
-        cm = fmaxf(cm, s[1][3]) * sl2;
-        if (__builtin_amdgcn_ballot_w64(cm > m[r] + kLazy)) {   // rare, wave-uniform
+        // (three-operand maxima written out: the compiler's own fmaxf chain quiets every MFMA result first,
+        // six more instructions per unit; the raw maximum is compared with the row's bar (m + kLazy) / sl2,
+        // kept up to date by the rare branch, so the common path has no scaling)
+        float cm = max3(s[0][0], s[0][1], s[0][2]);
+        cm = max3(cm, s[0][3], s[1][0]);
+        cm = max3(cm, s[1][1], s[1][2]);
+        cm = max3(cm, s[1][3], s[1][3]);
+        if (__builtin_amdgcn_ballot_w64(cm > bar[r])) {   // rare, wave-uniform
+            cm = cm * sl2;
             cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
             cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
             const float mnew = fmaxf(m[r], cm);
@@ -289,6 +300,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void k_attend_prefill_mfm
             l[r] = l[r] * alpha;
             lx[r] = lx[r] * alpha;
             m[r] = mnew;
+            bar[r] = (mnew + kLazy) / sl2;
 #pragma unroll
             for (int db = 0; db < DB; ++db) acc[r][db] = acc[r][db] * alpha;
         }

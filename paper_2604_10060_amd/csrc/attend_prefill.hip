@@ -23,16 +23,18 @@
 //   A 16-lane group's operand read (16 rows, one piece each) then covers all 64 banks once.
 //
 // What bounds it (D = 128, 256-token questions: 0.25 of the bf16 MFMA peak).  Per 16 x 32 block of
-// logits a wave issues 17 MFMAs (272 cycles of the matrix pipe) and about 48 vector-ALU
-// instructions, 8 of them exp2 (about 230 cycles of the vector pipe).  Measured on this chip
-// with a loop of independent instructions: a wave64 VALU instruction issues every 4 cycles (exp2
-// every 8), an MFMA every 16, and two VALU instructions per MFMA hide completely behind the MFMAs
-// (19 cycles per group against 18 without them), but every further one adds 5-10 cycles, so the
-// two pipes overlap far less than their separate occupancies suggest.  With the softmax removed
-// the kernel takes 107 us instead of 129, without the LDS operand reads 114, without the
-// global -> LDS traffic 103, with nothing but the MFMAs and the row-maximum check 67; the parts
-// add up almost linearly.  The arithmetic per logit (scale-and-shift, exp2, two sums, convert,
-// maximum) is what a 32-bit softmax needs without packed two-element instructions.
+// logits a wave issues 17 MFMAs (272 cycles of the matrix pipe) and about 45 vector-ALU
+// instructions, 8 of them exp2 (about 210 cycles of the vector pipe): scale-and-shift, exp2, two
+// sums (the bf16-rounded one by MFMA, the exact one for the log-sum-exp on the ALU), convert,
+// maximum -- what a 32-bit softmax needs without packed two-element instructions.  A loop of
+// independent instructions with this mix runs at 0.6-0.7 of the MFMA peak on this chip (a wave64
+// VALU instruction issues every 4 cycles, exp2 every 8, an MFMA every 16; two VALU instructions
+// per MFMA hide completely, further ones add 5-10 cycles each), so the mix is not the limit.
+// Taking parts out of the kernel: without the softmax arithmetic 107 us instead of 129, without
+// the LDS operand reads 114, without the global -> LDS traffic 103, with nothing but the MFMAs and
+// the row-maximum check 67 -- the parts add up almost linearly, i.e. they hardly overlap: the
+// chain LDS read -> MFMA -> softmax -> MFMA is dependent, and two wavefronts per SIMD (all that
+// two row tiles of accumulators leave room for) do not cover it.
 //
 // A group is one (unit, split) slot -- split_slot() shares the slots out over the units by
 // retrieved size -- and its n_row_blocks workgroups read the same K/V range.  Workgroups go to

@@ -9,6 +9,7 @@
 // non-packed fp32 rate, so exact-to-rounding decisions cost only table bytes.
 #include <type_traits>
 
+#include <algorithm>
 #include "mosaic_internal.h"
 #include "maintain_device.h"
 
@@ -1055,23 +1056,35 @@ __global__ __launch_bounds__(kBlock) void k_offload(DeviceView dv, int f0) {
 // ---------------------------------------------------------------------------
 // Host tier: cluster fetch.  One launch moves every missing page of a layer's
 // selection from the pinned slabs into the GPU cluster cache: the kernel loads
-// straight from host memory over PCIe (16 bytes per lane, a page per workgroup
-// and operand), which streams at the rate of a large DMA copy and costs one
-// launch instead of one runtime call per slab.
-// grid (max moves per unit, 2, n_units): y = 0 keys, y = 1 values.
+// straight from host memory over PCIe (16 bytes per lane), which streams at the
+// rate of a large DMA copy and costs one launch instead of one runtime call per
+// slab.  grid: a few dozen workgroups that share the (unit, page, keys | values) items.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_fetch(DeviceView dv, int u0) {
-    const int u = u0 + blockIdx.z, i = blockIdx.x;
-    if (i >= dv.n_moves[u]) return;
-    const int hp = dv.moves[((size_t)u * dv.F + i) * 2], cp = dv.moves[((size_t)u * dv.F + i) * 2 + 1];
-    const bool val = blockIdx.y == 1;
-    const size_t bytes = val ? dv.vpage : dv.kpage;
-    const char *src = (val ? dv.host_v : dv.host_k) + (size_t)u * dv.h_ustride +
-                      (size_t)(hp / dv.SFh) * dv.h_bstride + (size_t)(hp % dv.SFh) * bytes;
-    char *dst = (val ? dv.v_store + (size_t)u * dv.v_ustride : dv.k_store + (size_t)u * dv.k_ustride) + (size_t)cp * bytes;
-    const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
-    uint4 *d4 = reinterpret_cast<uint4 *>(dst);
-    for (size_t j = threadIdx.x; j < bytes / 16; j += kBlock) d4[j] = s4[j];
+__global__ __launch_bounds__(kBlock) void k_fetch(DeviceView dv, int u0, int n_units, int max_moves) {
+    // items = (unit, move, keys | values), dealt round-robin to a SMALL fixed number of workgroups: the link
+    // needs ~150 KB in flight, and workgroups parked on PCIe loads would otherwise hold the wave slots and
+    // registers that the attention and selection kernels of the neighbouring layers are waiting for
+    const int n_items = n_units * max_moves * 2;
+    for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+        const int val = it & 1, i = (it >> 1) % max_moves, u = u0 + (it >> 1) / max_moves;
+        if (i >= dv.n_moves[u]) continue;                                   // block-uniform
+        const int hp = dv.moves[((size_t)u * dv.F + i) * 2], cp = dv.moves[((size_t)u * dv.F + i) * 2 + 1];
+        const size_t bytes = val ? dv.vpage : dv.kpage;
+        const char *src = (val ? dv.host_v : dv.host_k) + (size_t)u * dv.h_ustride +
+                          (size_t)(hp / dv.SFh) * dv.h_bstride + (size_t)(hp % dv.SFh) * bytes;
+        char *dst = (val ? dv.v_store + (size_t)u * dv.v_ustride : dv.k_store + (size_t)u * dv.k_ustride) + (size_t)cp * bytes;
+        const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
+        uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+        const size_t n16 = bytes / 16;
+        for (size_t j = threadIdx.x; j < n16; j += 4 * kBlock) {           // four 16-byte loads in flight per thread
+            uint4 x[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) x[q] = s4[min(j + (size_t)q * kBlock, n16 - 1)];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (j + (size_t)q * kBlock < n16) d4[j + (size_t)q * kBlock] = x[q];
+        }
+    }
 }
 
 template <typename F> hipError_t checked(F &&launch) {
@@ -1122,7 +1135,11 @@ hipError_t launch_offload(const DeviceView &dv, int f0, int n, hipStream_t s) {
 
 hipError_t launch_fetch(const DeviceView &dv, int u0, int n_units, int max_moves, hipStream_t s) {
     if (max_moves <= 0) return hipSuccess;
-    return checked([&] { k_fetch<<<dim3(max_moves, 2, n_units), kBlock, 0, s>>>(dv, u0); });
+    // 64 workgroups (measured on config 3: 16 / 32 / 64 / 96 / 128 / 256 / one per page and operand give a warm
+    // decode step of 6.15 / 6.19 / 6.01 / 6.28 / 6.25 / 6.53 / 6.71 ms and 53.4 .. 55.2 GB/s over the link)
+    const long long items = (long long)n_units * max_moves * 2;
+    const int blocks = (int)std::min<long long>(items, 64);
+    return checked([&] { k_fetch<<<blocks, kBlock, 0, s>>>(dv, u0, n_units, max_moves); });
 }
 
 hipError_t launch_assign_update(const DeviceView &dv, int f0, int f1, hipStream_t s) {

@@ -170,7 +170,7 @@ Layout make_layout(const mosaic_config &c) {
                                  ? std::min<long long>(c.cache_pages_per_unit, (long long)F)
                                  : std::min<long long>((long long)(3.0 * share * (double)F) + (long long)k, (long long)F);
         L.PU = (int)std::max<long long>(cp, 1);
-        L.SN = std::max(W, 64);                 // staging ring: the warm-up plus one batch
+        L.SN = std::max(W, 128);                // staging ring: the warm-up, or two batches (one being offloaded, one being staged)
     }
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -178,7 +178,7 @@ Layout make_layout(const mosaic_config &c) {
     L.v_store = take(U * (size_t)L.PU * L.vpage);
     L.stage_k = take(host ? (size_t)L.SN * U * L.kpage : 0);
     L.stage_v = take(host ? (size_t)L.SN * U * L.vpage : 0);
-    L.dest = take(host ? U * (size_t)L.SN * 4 : 0);
+    L.dest = take(host ? 2 * U * (size_t)L.SN * 4 : 0);      // two slab tables, used in turn
     L.summ = take(U * F * D * 8);
     L.r = take(U * C * D * 8);
     L.rnorm = take(U * C * 8);
@@ -242,7 +242,7 @@ Layout make_layout(const mosaic_config &c) {
         L.host_moves = htake(U * F * 2 * 4);   // fetch work lists, read by the fetch kernel
         L.host_nmoves = htake(U * 4);
         L.host_assign = htake(U * (size_t)L.SN * 4);  // assignments of a staged batch on their way back
-        L.host_dest = htake(U * (size_t)L.SN * 4);    // their slab positions on their way to the device
+        L.host_dest = htake(2 * U * (size_t)L.SN * 4); // their slab positions on their way to the device (two tables)
         // maintainer on the host tier: what the host reads back to follow splits, and the residency flags it sends
         L.host_assign_full = htake(mt ? U * F * 4 : 0);
         L.host_cnt = htake(mt ? U * 4 * 8 : 0);
@@ -487,9 +487,13 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
         // two internal streams only: selection (+ value fetches) and key fetches
         if ((e = hipStreamCreateWithFlags(&ht->sel_stream, hipStreamNonBlocking)) != hipSuccess ||
             (e = hipStreamCreateWithFlags(&ht->copy_stream, hipStreamNonBlocking)) != hipSuccess ||
-            (e = hipEventCreateWithFlags(&ht->main_mark, hipEventDisableTiming)) != hipSuccess)
+            (e = hipEventCreateWithFlags(&ht->main_mark, hipEventDisableTiming)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&ht->off_ready, hipEventDisableTiming)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&ht->off_done[0], hipEventDisableTiming)) != hipSuccess ||
+            (e = hipEventCreateWithFlags(&ht->off_done[1], hipEventDisableTiming)) != hipSuccess)
             return bail(MOSAIC_EHIP, std::string("host tier stream/event creation: ") + hipGetErrorString(e));
         ht->ready.resize(dv.L); ht->attend_done.resize(dv.L);
+        ht->follow_dirty.assign(dv.L, 0);
         ht->attend_recorded.assign(dv.L, 0); ht->ready_recorded.assign(dv.L, 0);
         for (int l = 0; l < dv.L; ++l)
             if ((e = hipEventCreateWithFlags(&ht->ready[l], hipEventDisableTiming)) != hipSuccess ||
@@ -518,6 +522,8 @@ int32_t mosaic_destroy(mosaic_ctx *ctx) {
         if (ht->sel_stream) { (void)hipStreamSynchronize(ht->sel_stream); (void)hipStreamDestroy(ht->sel_stream); }
         if (ht->copy_stream) { (void)hipStreamSynchronize(ht->copy_stream); (void)hipStreamDestroy(ht->copy_stream); }
         if (ht->main_mark) (void)hipEventDestroy(ht->main_mark);
+        if (ht->off_ready) (void)hipEventDestroy(ht->off_ready);
+        for (hipEvent_t e : ht->off_done) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : ht->ready) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : ht->attend_done) if (e) (void)hipEventDestroy(e);
         for (hipEvent_t e : ht->busy_ev) (void)hipEventDestroy(e);
@@ -571,6 +577,9 @@ int32_t mosaic_reset(mosaic_ctx *ctx) {
         (void)hipStreamSynchronize(ht->sel_stream);
         (void)hipStreamSynchronize(ht->copy_stream);
         ht->reset();
+        ht->off_used[0] = ht->off_used[1] = false;
+        ht->off_idx = 0;
+        std::fill(ht->follow_dirty.begin(), ht->follow_dirty.end(), 0);
         ht->hits = ht->misses = ht->evictions = ht->h2d_bytes = ht->h2d_copies = 0;
         ht->pf_calls = ht->pf_fetched = ht->pf_useful = 0;
         ht->busy_ms = 0.0;
@@ -649,16 +658,38 @@ static int follow_membership(mosaic_ctx *ctx, int u0, int nu, hipStream_t s) {
 // Host tier: read back the assignments of staged frames f0..f1-1, give every
 // page its slab position, and store the pages into pinned host memory.
 // (ctx->n_frames must already count the frames up to f1.)
+// The staging ring holds frame f in slot f % SN.  Before frames [g0, g1) are staged, the caller's stream waits for
+// every offload still counted that read slots of theirs.
+static int wait_for_ring(mosaic_ctx *ctx, long long g0, long long g1) {
+    HostTier *ht = ctx->host;
+    const long long SN = ctx->dv.SN;
+    for (int p = 0; p < 2; ++p) {
+        if (!ht->off_used[p]) continue;
+        const long long a0 = ht->off_f0[p], a1 = ht->off_f1[p];
+        bool overlap = (a1 - a0) >= SN || (g1 - g0) >= SN;
+        for (long long f = g0; f < g1 && !overlap; ++f) {
+            const long long d = ((f - a0) % SN + SN) % SN;       // slot distance from the offload's first frame
+            overlap = d < a1 - a0;
+        }
+        if (!overlap) continue;
+        const hipError_t e = hipStreamWaitEvent(ctx->stream, ht->off_done[p], 0);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent(offload)");
+        ht->off_used[p] = false;
+    }
+    return MOSAIC_OK;
+}
+
 static int offload_range(mosaic_ctx *ctx, int f0, int f1) {
     const DeviceView &dv = ctx->dv;
     HostTier *ht = ctx->host;
     const int n = f1 - f0;
+    const int p = (int)(ht->off_idx & 1);                 // slab table of this batch
     // both directions go through pinned memory of the host arena: an asynchronous copy to
     // or from pageable memory is only complete (or its source only free) when the runtime
     // says so, which a stream synchronisation does not promise
-    int *a = ctx->h_assign, *dest = ctx->h_dest;
+    int *a = ctx->h_assign, *dest = ctx->h_dest + (size_t)p * dv.U * dv.SN;
     hipError_t e = hipSuccess;
-    // the previous batch's slab table must have left `dest`, and its assignments are final
+    // the batch's assignments are final (and the upload of this table's previous contents, two batches ago, is over)
     if ((e = hipStreamSynchronize(ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
     for (int u = 0; u < dv.U && e == hipSuccess; ++u)
         e = hipMemcpyAsync(a + (size_t)u * n, dv.assign + (size_t)u * dv.F + f0, (size_t)n * 4,
@@ -675,10 +706,28 @@ static int offload_range(mosaic_ctx *ctx, int f0, int f1) {
             dest[(size_t)u * dv.SN + fl] = hp;
             if (c >= 0) ht->join(u, f0 + fl, c);     // (units whose membership moved are rebuilt below)
         }
-    e = hipMemcpyAsync(dv.dest, dest, (size_t)dv.U * dv.SN * 4, hipMemcpyHostToDevice, ctx->stream);
+    // The offload itself goes to the copy stream, behind the table's upload, so that the caller's stream can stage
+    // and assign the next batch meanwhile; the device copy of this table was last read by the offload two batches ago.
+    DeviceView d2 = dv;
+    d2.dest = dv.dest + (size_t)p * dv.U * dv.SN;
+    if (ht->off_used[p]) {
+        if ((e = hipStreamWaitEvent(ctx->stream, ht->off_done[p], 0)) != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent(offload)");
+        ht->off_used[p] = false;
+    }
+    e = hipMemcpyAsync(d2.dest, dest, (size_t)dv.U * dv.SN * 4, hipMemcpyHostToDevice, ctx->stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "slab table upload");
-    if ((e = launch_offload(dv, f0, n, ctx->stream)) != hipSuccess) return fail_hip(ctx, e, "offload launch");
-    if (dv.maint_mode) return follow_membership(ctx, 0, dv.U, ctx->stream);
+    if ((e = hipEventRecord(ht->off_ready, ctx->stream)) != hipSuccess ||
+        (e = hipStreamWaitEvent(ht->copy_stream, ht->off_ready, 0)) != hipSuccess)
+        return fail_hip(ctx, e, "ordering the offload after its slab table");
+    if ((e = launch_offload(d2, f0, n, ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "offload launch");
+    if ((e = hipEventRecord(ht->off_done[p], ht->copy_stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord(offload)");
+    ht->off_used[p] = true; ht->off_f0[p] = f0; ht->off_f1[p] = f1;
+    ht->off_idx += 1;
+    // Membership after splits.  Deferred splits test "C is in GPU memory" against the cache directory at every
+    // insertion batch, so the host follows at once; eager splits never ask, so the host follows when the layer is
+    // next queried (reading every unit's frame map back after every batch was more than half of the ingest time).
+    if (dv.maint_mode == MOSAIC_MAINT_DEFERRED) return follow_membership(ctx, 0, dv.U, ctx->stream);
+    if (dv.maint_mode) std::fill(ht->follow_dirty.begin(), ht->follow_dirty.end(), 1);
     return MOSAIC_OK;
 }
 
@@ -695,6 +744,7 @@ static int ingest_host(mosaic_ctx *ctx, const void *k_dev, const void *v_dev, in
         if ((rc = upload_residency(ctx)) != MOSAIC_OK) return rc;
         // warm-up frames stay in the staging ring (SN >= W); afterwards batches of <= 64
         const int nb = (int)(f < W ? std::min(end, W) - f : std::min<long long>(end - f, 64));
+        if ((rc = wait_for_ring(ctx, f, f + nb)) != MOSAIC_OK) return rc;
         e = launch_store_summary(dv, (const char *)k_dev + done * frame_bytes,
                                  (const char *)v_dev + done * frame_bytes, (int)f, nb, ctx->stream);
         if (e != hipSuccess) return fail_hip(ctx, e, "store_summary launch");
@@ -886,6 +936,11 @@ static int retrieve_host(mosaic_ctx *ctx, int layer, const void *q_dev, int Tq, 
         (e = hipMemcpyAsync(nids, dv.n_ids + u0, (size_t)nu * 4, hipMemcpyDeviceToHost, ht->sel_stream)) != hipSuccess)
         return fail_hip(ctx, e, "selection read-back");
     if ((e = hipStreamSynchronize(ht->sel_stream)) != hipSuccess) return fail_hip(ctx, e, "hipStreamSynchronize");
+    if (ht->follow_dirty[layer]) {           // eager splits since this layer was last queried (all ingest work is over: main_mark)
+        const int rc2 = follow_membership(ctx, u0, nu, ht->sel_stream);
+        if (rc2 != MOSAIC_OK) return rc2;
+        ht->follow_dirty[layer] = 0;
+    }
     // the pinned page-list staging of this layer must not be in flight any more
     if (ht->ready_recorded[layer] && (e = hipEventSynchronize(ht->ready[layer])) != hipSuccess)
         return fail_hip(ctx, e, "hipEventSynchronize");
@@ -1370,6 +1425,12 @@ int32_t mosaic_get_cache_directory(mosaic_ctx *ctx, int32_t *cached_pages) {
     if (!ctx->host) return fail(ctx, MOSAIC_EINVAL, "the cluster cache exists in the host tier only");
     if (!cached_pages) return fail(ctx, MOSAIC_EINVAL, "cached_pages is NULL");
     const DeviceView &dv = ctx->dv;
+    for (int l = 0; l < dv.L; ++l) {         // eager splits the host has not followed yet
+        if (!ctx->host->follow_dirty[l]) continue;
+        const int rc = follow_membership(ctx, l * dv.Hkv, dv.Hkv, ctx->stream);
+        if (rc != MOSAIC_OK) return rc;
+        ctx->host->follow_dirty[l] = 0;
+    }
     for (int u = 0; u < dv.U; ++u) {
         const HostTier::Unit &un = ctx->host->units[u];
         for (int c = 0; c < dv.C; ++c) cached_pages[(size_t)u * dv.C + c] = un.cached[c] > 0 ? un.cached[c] : -1;

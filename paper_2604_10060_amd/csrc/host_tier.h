@@ -50,6 +50,15 @@ struct HostTier {
     hipStream_t sel_stream = nullptr;    // selection kernel + read-back of the ids
     hipStream_t copy_stream = nullptr;   // fetch kernel, page-list upload, `ready` events
     hipEvent_t main_mark = nullptr;                 // marks the caller's stream at each retrieve
+    // ingest: the offload of a staged batch runs on the copy stream while the caller's stream goes on with the
+    // next batch; two slab tables (host and device) used in turn, an event per table for "offload finished",
+    // and the frames each still-counted offload read from the staging ring
+    hipEvent_t off_ready = nullptr, off_done[2] = {nullptr, nullptr};
+    bool off_used[2] = {false, false};
+    long long off_f0[2] = {0, 0}, off_f1[2] = {0, 0};
+    long long off_idx = 0;
+    // eager maintainer: splits since the host last followed a layer's units (followed when the layer is next queried)
+    std::vector<char> follow_dirty;              // [L]
     std::vector<hipEvent_t> ready, attend_done;     // per layer
     std::vector<char> attend_recorded, ready_recorded;
     // timing of the fetch kernels while profiling is on: a fixed pool of event pairs, folded into

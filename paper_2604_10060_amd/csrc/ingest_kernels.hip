@@ -1040,17 +1040,22 @@ __global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frame
 // ---------------------------------------------------------------------------
 // Host tier: store staged pages into their cluster's slab in pinned host memory
 // (device stores over PCIe, 16 bytes per lane, whole pages contiguous).
-// grid (U, n, 2): z = 0 keys, z = 1 values.
+// A few dozen workgroups share the (unit, frame, keys | values) items: the launch
+// runs on the copy stream beside the next batch's staging and assignment, and
+// one workgroup per page would hold the chip while it waits for the link.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_offload(DeviceView dv, int f0) {
-    const int u = blockIdx.x, fl = blockIdx.y, f = f0 + fl;
-    const size_t bytes = blockIdx.z == 0 ? dv.kpage : dv.vpage;
-    const size_t spage = (size_t)(f % dv.SN) * dv.U + u;
-    const int hp = dv.dest[(size_t)u * dv.SN + fl];        // page within the unit's host pool
-    const size_t hoff = (size_t)u * dv.h_ustride + (size_t)(hp / dv.SFh) * dv.h_bstride + (size_t)(hp % dv.SFh) * bytes;
-    const uint4 *src = reinterpret_cast<const uint4 *>((blockIdx.z == 0 ? dv.stage_k : dv.stage_v) + spage * bytes);
-    uint4 *dst = reinterpret_cast<uint4 *>((blockIdx.z == 0 ? dv.host_k : dv.host_v) + hoff);
-    for (size_t i = threadIdx.x; i < bytes / 16; i += kBlock) dst[i] = src[i];
+__global__ __launch_bounds__(kBlock) void k_offload(DeviceView dv, int f0, int n) {
+    const int n_items = dv.U * n * 2;
+    for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+        const int val = it & 1, u = (it >> 1) % dv.U, fl = (it >> 1) / dv.U, f = f0 + fl;
+        const size_t bytes = val ? dv.vpage : dv.kpage;
+        const size_t spage = (size_t)(f % dv.SN) * dv.U + u;
+        const int hp = dv.dest[(size_t)u * dv.SN + fl];        // page within the unit's host pool
+        const size_t hoff = (size_t)u * dv.h_ustride + (size_t)(hp / dv.SFh) * dv.h_bstride + (size_t)(hp % dv.SFh) * bytes;
+        const uint4 *src = reinterpret_cast<const uint4 *>((val ? dv.stage_v : dv.stage_k) + spage * bytes);
+        uint4 *dst = reinterpret_cast<uint4 *>((val ? dv.host_v : dv.host_k) + hoff);
+        for (size_t i = threadIdx.x; i < bytes / 16; i += kBlock) dst[i] = src[i];
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1130,7 +1135,9 @@ hipError_t launch_value_reps(const DeviceView &dv, int n_frames, hipStream_t s) 
 }
 
 hipError_t launch_offload(const DeviceView &dv, int f0, int n, hipStream_t s) {
-    return checked([&] { k_offload<<<dim3(dv.U, n, 2), kBlock, 0, s>>>(dv, f0); });
+    const long long items = (long long)dv.U * n * 2;
+    const int blocks = (int)std::min<long long>(items, 128);
+    return checked([&] { k_offload<<<blocks, kBlock, 0, s>>>(dv, f0, n); });
 }
 
 hipError_t launch_fetch(const DeviceView &dv, int u0, int n_units, int max_moves, hipStream_t s) {

@@ -1136,7 +1136,10 @@ hipError_t launch_value_reps(const DeviceView &dv, int n_frames, hipStream_t s) 
 
 hipError_t launch_offload(const DeviceView &dv, int f0, int n, hipStream_t s) {
     const long long items = (long long)dv.U * n * 2;
-    const int blocks = (int)std::min<long long>(items, 128);
+    // 16 workgroups (posted stores keep the link full; config 3 ingest with 4 / 8 / 16 / 64 / 256 / 1024 workgroups:
+    // 12.5 / 13.9 / 14.0 / 13.2 / 12.7 / 12.6 k frames/s -- the more of them, the more they slow the staging and
+    // assignment kernels that run beside them)
+    const int blocks = (int)std::min<long long>(items, 16);
     return checked([&] { k_offload<<<blocks, kBlock, 0, s>>>(dv, f0, n); });
 }
 

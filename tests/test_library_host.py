@@ -58,6 +58,7 @@ def test_workspace_size_grows_with_the_stream():
     dict(warmup_frames=8), dict(score_mode=2), dict(attend_impl=binding.ATTEND_MFMA),
     dict(max_frames=1 << 30, tokens_per_frame=64), dict(attend_impl=9), dict(tier=2),
     dict(tier=1, recluster_every=16), dict(tier=1, cache_fraction=1.5),
+    dict(ingest_overlap=2), dict(decode_fused_max_mib=-3),
 ])
 def test_bad_configurations_are_rejected(bad):
     with pytest.raises(binding.MosaicError) as e:
@@ -86,4 +87,6 @@ def test_null_arguments_do_not_crash():
     assert lib.mosaic_retrieve(None, 0, None, 1) == binding.EINVAL
     assert lib.mosaic_attend(None, 0, None, 1, None, None) == binding.EINVAL
     assert lib.mosaic_destroy(None) == binding.EINVAL
+    assert lib.mosaic_ingest_join(None) == binding.EINVAL
+    assert lib.mosaic_decode_step(None, 0, None, 1, None, None) == binding.EINVAL
     assert isinstance(lib.mosaic_last_error(None), bytes)

@@ -269,7 +269,8 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
         else if (n_splits <= 128) combine_accumulate<D, 128, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
         else combine_accumulate<D, kMaxUnitSplits, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
     } else {
-        if (n_splits <= 64) combine_accumulate<D, 64, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+        if (n_splits <= 16) combine_accumulate<D, 16, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+        else if (n_splits <= 64) combine_accumulate<D, 64, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
         else combine_accumulate<D, kMaxUnitSplits, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
     }
 #pragma unroll

@@ -844,27 +844,31 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
     int *moved = dv.lloyd_moved + (size_t)u * 3;
     if (blockIdx.y == 0 && tid == 0) moved[(it + 1) % 3] = 0;
     if (it > 0 && moved[(it - 1) % 3] == 0) return;            // workgroup-uniform: converged in an earlier round
-    __shared__ double sn_sh[4][16];
+    // The ranking of a frame's similarities does not need the division by |s| |r_j| per candidate: |s| is the
+    // same positive factor for every j, so the winner is argmax_j dot_j * (1 / |r_j|).  The fp64 matrix
+    // instruction runs on the vector unit's fp64 lanes (counters: no cycle in which both execute), so every
+    // vector instruction of the tile epilogue is time taken from the contraction: the reciprocals are formed
+    // once per workgroup in LDS (0 for a zero representative, as the cosine is 0 there; NaN for an empty
+    // cluster, which then never compares greater), and an all-zero summary gives dot = 0 for every j and the
+    // lowest id, as its cosines (all 0) do.
+    __shared__ double scale_sh[1024];    // the cluster-count limit of a context
     f64x2 a[KS];
     {
         const int f = min(fbase + row, n_frames - 1);
         const double *sp = dv.summ + ((size_t)u * dv.F + f) * D + 2 * kq;
 #pragma unroll
         for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const f64x2 *>(sp + 8 * s);
-        double sq = 0.0;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) sq += a[s].x * a[s].x + a[s].y * a[s].y;
-        sq += __shfl_xor(sq, 16, 64);
-        sq += __shfl_xor(sq, 32, 64);
-        if (kq == 0) sn_sh[wave][row] = sqrt(sq);
+        for (int j = tid; j < C; j += kBlock) {
+            const double rnj = dv.rnorm[(size_t)u * C + j];
+            scale_sh[j] = dv.n[(size_t)u * C + j] > 0 ? (rnj == 0.0 ? 0.0 : 1.0 / rnj) : __builtin_nan("");
+        }
     }
     __syncthreads();
     // the four result rows of this lane: frames fbase + 4v + kq
-    double snv[4], bv[4];
+    double bv[4];
     int plo[4], phi[4], bi[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        snv[v] = sn_sh[wave][4 * v + kq];
         bv[v] = -INFINITY; bi[v] = 0x7fffffff;
         plo[v] = 0; phi[v] = C;
         if (dv.P > 0) {      // nested hierarchy: only the ids of the frame's visual partition are candidates
@@ -873,8 +877,6 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
         }
     }
     const double *r = dv.r + (size_t)u * C * D;
-    const double *rn = dv.rnorm + (size_t)u * C;
-    const int *n = dv.n + (size_t)u * C;
     const int n_tiles = (C + 15) / 16;
     // A tile of 16 representatives is shared by the four wavefronts through LDS (each row is read
     // from L2 once per workgroup); rows are padded by 16 bytes so that the 16 lanes of a k group hit
@@ -897,38 +899,32 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
         }
     };
     fetch_tile(0);
-    int nj = n[min(row, C - 1)];
-    double rnj = rn[min(row, C - 1)];
     stage_tile(0);
     __syncthreads();
     for (int ct = 0; ct < n_tiles; ++ct) {
-        const int ctn = min(ct + 1, n_tiles - 1), jn = min(16 * ctn + row, C - 1);
+        const int ctn = min(ct + 1, n_tiles - 1);
         fetch_tile(ctn);
-        const int nj_next = n[jn];
-        const double rnj_next = rn[jn];
         f64x2 b[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) b[s] = *reinterpret_cast<const f64x2 *>(&b_lds[ct & 1][row][8 * s + 2 * kq]);
-        f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+        // one accumulator chain: back-to-back matrix instructions on the same accumulator sustain 70 TFLOP/s
+        // in a probe of nothing else, two alternating accumulators 66, four 58
+        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].x, b[s].x, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].y, b[s].y, acc1, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].x, b[s].x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].y, b[s].y, acc, 0, 0, 0);
         }
         const int j = 16 * ct + row;
-        if (j < C) {
+        const double scale = j < C ? scale_sh[j] : __builtin_nan("");
+        // a lane meets its candidates in ascending id order, so a strict comparison keeps the lowest id of equals
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if (nj > 0 && j >= plo[v] && j < phi[v]) {
-                    const double dot = acc0[v] + acc1[v];
-                    const double c = (snv[v] == 0.0 || rnj == 0.0) ? 0.0 : dot / (snv[v] * rnj);
-                    if (better(c, j, bv[v], bi[v])) { bv[v] = c; bi[v] = j; }
-                }
-            }
+        for (int v = 0; v < 4; ++v) {
+            const double c = acc[v] * scale;
+            if (c > bv[v] && j >= plo[v] && j < phi[v]) { bv[v] = c; bi[v] = j; }
         }
         stage_tile((ct + 1) & 1);       // the other buffer: last read before the previous barrier
         __syncthreads();
-        nj = nj_next; rnj = rnj_next;
     }
     // best over the 16 columns a lane group covers (lanes 16k .. 16k + 15)
 #pragma unroll
@@ -1006,13 +1002,15 @@ __global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frame
         __syncthreads();
         if (tid < D) {
             // sixteen members' loads in flight at a time (index clamped, loads unconditional), added in order
+            // (thirty-two: slower, 75 against 68 us on average over a pass of config 2)
+            constexpr int NL = 16;
             const double *sb = dv.summ + (size_t)u * dv.F * D + tid;
-            for (int m0 = 0; m0 < filled; m0 += 16) {
-                double v[16];
+            for (int m0 = 0; m0 < filled; m0 += NL) {
+                double v[NL];
 #pragma unroll
-                for (int x = 0; x < 16; ++x) v[x] = sb[(size_t)mem[min(m0 + x, filled - 1)] * D];
+                for (int x = 0; x < NL; ++x) v[x] = sb[(size_t)mem[min(m0 + x, filled - 1)] * D];
 #pragma unroll
-                for (int x = 0; x < 16; ++x)
+                for (int x = 0; x < NL; ++x)
                     if (m0 + x < filled) acc += v[x];
             }
         }

@@ -54,7 +54,7 @@ int fail_hip(mosaic_ctx *ctx, hipError_t e, const char *what) {
 }
 
 struct Layout {
-    size_t k_store, v_store, summ, r, rnorm, n, assign, pos, lloyd_moved, sel_flag, sync_err, scores, ids, n_ids, sel_pages, n_sel,
+    size_t k_store, v_store, summ, r, rnorm, n, assign, pos, lloyd_moved, lloyd_delta, lloyd_ub, lloyd_lb, lloyd_live, sel_flag, sync_err, scores, ids, n_ids, sel_pages, n_sel,
         tok_scratch, part_o, part_ml, stage_k, stage_v, dest, var, lazy, resident, n_slots, buf_frame,
         buf_owner, n_buf, mt_cnt, mt_mem, mt_side, mt_nrm, vsumm, rvsum, rep_k, rep_v, aug_o, aug_ml,
         vemb, vr, vrn, vn, part, pr, prn, pn, pscores, pids, n_pids, total;
@@ -185,7 +185,11 @@ Layout make_layout(const mosaic_config &c) {
     L.n = take(U * C * 4);
     L.assign = take(U * F * 4);
     L.pos = take(U * F * 4);
-    L.lloyd_moved = take(U * 3 * 4);
+    L.lloyd_moved = take(U * 6 * 4 + U * C * 4);      // + the live-row counters and the clusters' changed flags
+    L.lloyd_live = take(U * ((F + 15) / 16) * 4);
+    L.lloyd_delta = take(U * C * 8);
+    L.lloyd_ub = take(U * F * 8);
+    L.lloyd_lb = take(U * F * 8);
     L.sel_flag = take(U * 8);
     L.sync_err = take(4);
     L.c_init = init_clusters_of(c); L.buf_max = buffer_max_of(c); L.W = warmup_of(c);
@@ -400,7 +404,10 @@ int32_t mosaic_create(const mosaic_config *cfg, mosaic_ctx **out) {
     dv.summ = (double *)(base + L.summ); dv.r = (double *)(base + L.r);
     dv.rnorm = (double *)(base + L.rnorm); dv.n = (int *)(base + L.n);
     dv.assign = (int *)(base + L.assign); dv.pos = (int *)(base + L.pos);
-    dv.lloyd_moved = (int *)(base + L.lloyd_moved);
+    dv.lloyd_moved = (int *)(base + L.lloyd_moved); dv.lloyd_changed = dv.lloyd_moved + (size_t)dv.U * 6;
+    dv.lloyd_live = (int *)(base + L.lloyd_live);
+    dv.lloyd_delta = (double *)(base + L.lloyd_delta);
+    dv.lloyd_ub = (double *)(base + L.lloyd_ub); dv.lloyd_lb = (double *)(base + L.lloyd_lb);
     dv.sel_flag = (long long *)(base + L.sel_flag); dv.sync_err = (int *)(base + L.sync_err);
     ctx->launch_epoch = 0;
     dv.scores = (double *)(base + L.scores); dv.ids = (int *)(base + L.ids);

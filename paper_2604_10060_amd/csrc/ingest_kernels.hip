@@ -835,46 +835,117 @@ typedef double f64x2 __attribute__((ext_vector_type(2)));
 // bit, hence the same assignments in every later round.  moved[u][it % 3] counts the frames round
 // `it` moved; a round whose predecessor moved none returns at once (and so does its update kernel).
 // The slot of the round after is cleared by this launch, which neither reads nor counts in it.
+//
+// Frames whose assignment cannot change are skipped as well, by the distance bounds of accelerated
+// K-means (Hamerly, SDM 2010) taken on the unit sphere, where the largest cosine is the smallest chord
+// d(s, r) = |s/|s| - r/|r|| = sqrt(2 - 2 cos): a round that computes a frame's similarities leaves
+// ub = d(own representative) and lb = d(best other candidate); an update that moves representative j by
+// delta_j = d(old r_j, new r_j) can shrink any frame's distance to it by at most delta_j, so after it
+// ub + delta_own still bounds the own distance from above and lb - max_{j != own} delta_j the others from
+// below (triangle inequality).  While ub + 1e-6 < lb the own representative wins by a margin far above
+// the rounding of the similarities (> 5e-13 in the cosine) and the full computation would return the same
+// id: a row of 16 frames (what one wavefront multiplies) whose frames all pass only gets the moved bounds
+// stored (k_lloyd_bounds); any other is recomputed in full and leaves exact bounds again.  Round 0 computes
+// everything.  After the first round a handful of frames per unit keeps moving and a few representatives with
+// them, so most rows pass.  The assignments are the same as without the test, by construction.
+constexpr double kBoundMargin = 1e-6;
+
+// The bound test of a round it >= 1, for all frames of a unit: grid (U, ceil(F/1024)), 256 threads, a lane per
+// frame, sixteen consecutive frames (what one wavefront of k_lloyd_assign multiplies) per 16-lane row.  A row
+// whose frames all pass stores their moved bounds; any other is appended to the unit's list of live rows
+// (order of arrival: every frame's result is independent of it), which k_lloyd_assign then works through
+// four rows per workgroup, so that the few rows still alive fill whole workgroups.
+__global__ __launch_bounds__(kBlock) void k_lloyd_bounds(DeviceView dv, int n_frames, int it) {
+    const int u = blockIdx.x, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, C = dv.C;
+    int *n_live = dv.lloyd_moved + (size_t)dv.U * 3 + (size_t)u * 3;
+    if (blockIdx.y == 0 && tid == 0) n_live[(it + 1) % 3] = 0;
+    if (dv.lloyd_moved[(size_t)u * 3 + (it - 1) % 3] == 0) return;      // converged (as in k_lloyd_assign)
+    __shared__ double top_v[4][2];
+    __shared__ int top_j[4];
+    // largest and second largest movement of a representative in the last update, and whose the largest was
+    const double *delta = dv.lloyd_delta + (size_t)u * C;
+    double d1 = 0.0, d2 = 0.0;
+    int j1 = -1;
+    for (int j = tid; j < C; j += kBlock) {
+        const double dj = delta[j];
+        if (dj > d1) { d2 = d1; d1 = dj; j1 = j; }
+        else if (dj > d2) d2 = dj;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const double o1 = __shfl_xor(d1, o, 64), o2 = __shfl_xor(d2, o, 64);
+        const int oj = __shfl_xor(j1, o, 64);
+        if (o1 > d1) { d2 = fmax(d1, o2); d1 = o1; j1 = oj; }
+        else d2 = fmax(d2, o1);
+    }
+    if (lane == 0) { top_v[wave][0] = d1; top_v[wave][1] = d2; top_j[wave] = j1; }
+    __syncthreads();
+    d1 = top_v[0][0]; d2 = top_v[0][1]; j1 = top_j[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+        const double o1 = top_v[w][0], o2 = top_v[w][1];
+        if (o1 > d1) { d2 = fmax(d1, o2); d1 = o1; j1 = top_j[w]; }
+        else d2 = fmax(d2, o1);
+    }
+    const int fend = min(n_frames, (int)(blockIdx.y + 1) * 1024);
+    for (int f0 = blockIdx.y * 1024 + wave * 64; f0 < fend; f0 += kBlock) {
+        const int f = f0 + lane;
+        bool safe = true;
+        double ubn = 0.0, lbn = 0.0;
+        if (f < n_frames) {
+            const int a_old = dv.assign[(size_t)u * dv.F + f];
+            ubn = dv.lloyd_ub[(size_t)u * dv.F + f] + delta[a_old];
+            lbn = dv.lloyd_lb[(size_t)u * dv.F + f] - (a_old == j1 ? d2 : d1);
+            safe = ubn + kBoundMargin < lbn;
+        }
+        const unsigned long long unsafe = __ballot(!safe);
+        const bool row_live = ((unsafe >> (lane & 48)) & 0xffffull) != 0ull;
+        if (!row_live && f < n_frames) {
+            dv.lloyd_ub[(size_t)u * dv.F + f] = ubn;
+            dv.lloyd_lb[(size_t)u * dv.F + f] = lbn;
+        }
+        // the wavefront's live rows (at most four) take consecutive slots of the list
+        unsigned int rows = 0;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) rows |= (((unsafe >> (16 * g)) & 0xffffull) != 0ull ? 1u : 0u) << g;
+        if (rows) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&n_live[it % 3], __popc(rows));
+            base = __shfl(base, 0, 64);
+            const int g = lane / 16;
+            if ((lane & 15) == 0 && ((rows >> g) & 1u))
+                dv.lloyd_live[(size_t)u * ((dv.F + 15) / 16) + base + __popc(rows & ((1u << g) - 1u))] = f0 / 16 + g;
+        }
+    }
+}
+
+// fp64 max / min as single instructions (the builtins add an instruction per operand that quiets signalling NaNs);
+// only used on values that are never NaN
+__device__ __forceinline__ double max_f64(double a, double b) {
+    double r;
+    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ double min_f64(double a, double b) {
+    double r;
+    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 template <int D>
 __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n_frames, int it) {
     constexpr int KS = D / 8;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, C = dv.C;
     const int row = lane % 16, kq = lane / 16;
-    const int fbase = blockIdx.y * 64 + wave * 16;
     int *moved = dv.lloyd_moved + (size_t)u * 3;
     if (blockIdx.y == 0 && tid == 0) moved[(it + 1) % 3] = 0;
     if (it > 0 && moved[(it - 1) % 3] == 0) return;            // workgroup-uniform: converged in an earlier round
-    // The ranking of a frame's similarities does not need the division by |s| |r_j| per candidate: |s| is the
-    // same positive factor for every j, so the winner is argmax_j dot_j * (1 / |r_j|).  The fp64 matrix
-    // instruction runs on the vector unit's fp64 lanes (counters: no cycle in which both execute), so every
-    // vector instruction of the tile epilogue is time taken from the contraction: the reciprocals are formed
-    // once per workgroup in LDS (0 for a zero representative, as the cosine is 0 there; NaN for an empty
-    // cluster, which then never compares greater), and an all-zero summary gives dot = 0 for every j and the
-    // lowest id, as its cosines (all 0) do.
-    __shared__ double scale_sh[1024];    // the cluster-count limit of a context
-    f64x2 a[KS];
-    {
-        const int f = min(fbase + row, n_frames - 1);
-        const double *sp = dv.summ + ((size_t)u * dv.F + f) * D + 2 * kq;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const f64x2 *>(sp + 8 * s);
-        for (int j = tid; j < C; j += kBlock) {
-            const double rnj = dv.rnorm[(size_t)u * C + j];
-            scale_sh[j] = dv.n[(size_t)u * C + j] > 0 ? (rnj == 0.0 ? 0.0 : 1.0 / rnj) : __builtin_nan("");
-        }
-    }
-    __syncthreads();
-    // the four result rows of this lane: frames fbase + 4v + kq
-    double bv[4];
-    int plo[4], phi[4], bi[4];
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        bv[v] = -INFINITY; bi[v] = 0x7fffffff;
-        plo[v] = 0; phi[v] = C;
-        if (dv.P > 0) {      // nested hierarchy: only the ids of the frame's visual partition are candidates
-            plo[v] = dv.part[min(fbase + 4 * v + kq, n_frames - 1)] * dv.Cs;
-            phi[v] = plo[v] + dv.Cs;
-        }
+    // Round 0: one task per workgroup, wavefront w of workgroup y takes frames 64 y + 16 w ...  Later rounds:
+    // task t = rows 4 t .. 4 t + 3 of the unit's list of live rows, the workgroups of a unit taking tasks in turn.
+    int cnt = 0;
+    if (it > 0) {
+        cnt = dv.lloyd_moved[(size_t)dv.U * 3 + (size_t)u * 3 + it % 3];
+        if ((int)blockIdx.y * 4 >= cnt) return;                // workgroup-uniform
     }
     const double *r = dv.r + (size_t)u * C * D;
     const int n_tiles = (C + 15) / 16;
@@ -898,49 +969,141 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
             *reinterpret_cast<f64x2 *>(&b_lds[buf][trow][2 * seg]) = stg[i];
         }
     };
-    fetch_tile(0);
-    stage_tile(0);
-    __syncthreads();
-    for (int ct = 0; ct < n_tiles; ++ct) {
-        const int ctn = min(ct + 1, n_tiles - 1);
-        fetch_tile(ctn);
-        f64x2 b[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) b[s] = *reinterpret_cast<const f64x2 *>(&b_lds[ct & 1][row][8 * s + 2 * kq]);
-        // one accumulator chain: back-to-back matrix instructions on the same accumulator sustain 70 TFLOP/s
-        // in a probe of nothing else, two alternating accumulators 66, four 58
-        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].x, b[s].x, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].y, b[s].y, acc, 0, 0, 0);
+    // The ranking of a frame's similarities does not need the division by |s| |r_j| per candidate: |s| is the
+    // same positive factor for every j, so the winner is argmax_j dot_j * (1 / |r_j|).  The fp64 matrix
+    // instruction runs on the vector unit's fp64 lanes (counters: no cycle in which both execute), so every
+    // vector instruction of the tile epilogue is time taken from the contraction: per candidate one fused
+    // multiply-add, dot * scale_j + offset_j, with the pair formed once per workgroup in LDS: (1 / |r_j|, 0) for
+    // a candidate, (0, 0) for a zero representative (its cosine is 0), (0, -inf) for an empty cluster and past
+    // the table's end.  An all-zero summary gives 0 for every candidate and so the lowest id, as its cosines
+    // (all 0) do.
+    __shared__ __attribute__((aligned(16))) f64x2 scale_sh[1024 + 16];    // the cluster-count limit of a context, rounded up to tiles
+    __shared__ double sn_sh[4][16];
+    for (int j = tid; j < 16 * n_tiles; j += kBlock) {
+        f64x2 e = {0.0, -INFINITY};
+        if (j < C && dv.n[(size_t)u * C + j] > 0) {
+            const double rnj = dv.rnorm[(size_t)u * C + j];
+            e.x = rnj == 0.0 ? 0.0 : 1.0 / rnj;
+            e.y = 0.0;
         }
-        const int j = 16 * ct + row;
-        const double scale = j < C ? scale_sh[j] : __builtin_nan("");
-        // a lane meets its candidates in ascending id order, so a strict comparison keeps the lowest id of equals
+        scale_sh[j] = e;
+    }
+    const bool nested = dv.P > 0;
+    for (int task = blockIdx.y;; task += gridDim.y) {
+        int fbase = task * 64 + wave * 16;
+        bool live = true;
+        if (it > 0) {
+            if (task * 4 >= cnt) break;                         // workgroup-uniform
+            live = task * 4 + wave < cnt;
+            fbase = live ? dv.lloyd_live[(size_t)u * ((dv.F + 15) / 16) + task * 4 + wave] * 16 : 0;
+        }
+        fetch_tile(0);
+        f64x2 a[KS];
+        if (live) {
+            const int f = min(fbase + row, n_frames - 1);
+            const double *sp = dv.summ + ((size_t)u * dv.F + f) * D + 2 * kq;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const f64x2 *>(sp + 8 * s);
+            double sq = 0.0;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) sq += a[s].x * a[s].x + a[s].y * a[s].y;
+            sq += __shfl_xor(sq, 16, 64);
+            sq += __shfl_xor(sq, 32, 64);
+            if (kq == 0) sn_sh[wave][row] = sqrt(sq);
+        }
+        // the four result rows of this lane: frames fbase + 4v + kq; best and second best similarity (times |s|)
+        double bv[4], sv[4];
+        int plo[4], phi[4], bi[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const double c = acc[v] * scale;
-            if (c > bv[v] && j >= plo[v] && j < phi[v]) { bv[v] = c; bi[v] = j; }
+            bv[v] = -INFINITY; sv[v] = -INFINITY; bi[v] = 0x7fffffff;
+            plo[v] = 0; phi[v] = C;
+            if (nested) {        // nested hierarchy: only the ids of the frame's visual partition are candidates
+                plo[v] = dv.part[min(fbase + 4 * v + kq, n_frames - 1)] * dv.Cs;
+                phi[v] = plo[v] + dv.Cs;
+            }
         }
-        stage_tile((ct + 1) & 1);       // the other buffer: last read before the previous barrier
+        stage_tile(0);
         __syncthreads();
-    }
-    // best over the 16 columns a lane group covers (lanes 16k .. 16k + 15)
+        for (int ct = 0; ct < n_tiles; ++ct) {
+            const int ctn = min(ct + 1, n_tiles - 1);
+            fetch_tile(ctn);
+            if (live) {
+                f64x2 b[KS];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
+                for (int s = 0; s < KS; ++s) b[s] = *reinterpret_cast<const f64x2 *>(&b_lds[ct & 1][row][8 * s + 2 * kq]);
+                const f64x2 sc = scale_sh[16 * ct + row];
+                // one accumulator chain: back-to-back matrix instructions on the same accumulator sustain 70 TFLOP/s
+                // in a probe of nothing else, two alternating accumulators 66, four 58
+                f64x4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int o = 8; o >= 1; o >>= 1) {
-            const double ov = __shfl_xor(bv[v], o, 16);
-            const int oi = __shfl_xor(bi[v], o, 16);
-            if (better(ov, oi, bv[v], bi[v])) { bv[v] = ov; bi[v] = oi; }
+                for (int s = 0; s < KS; ++s) {
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].x, b[s].x, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s].y, b[s].y, acc, 0, 0, 0);
+                }
+                const int j = 16 * ct + row;
+                // A lane meets its candidates in ascending id order, so a strict comparison keeps the lowest id of
+                // equals; the second best is kept for the bounds.
+                if (nested) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        double c = __builtin_fma(acc[v], sc.x, sc.y);
+                        if (j < plo[v] || j >= phi[v]) c = -INFINITY;
+                        bi[v] = c > bv[v] ? j : bi[v];
+                        sv[v] = max_f64(sv[v], min_f64(bv[v], c));
+                        bv[v] = max_f64(bv[v], c);
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const double c = __builtin_fma(acc[v], sc.x, sc.y);
+                        bi[v] = c > bv[v] ? j : bi[v];
+                        sv[v] = max_f64(sv[v], min_f64(bv[v], c));
+                        bv[v] = max_f64(bv[v], c);
+                    }
+                }
+            }
+            stage_tile((ct + 1) & 1);       // the other buffer: last read before the previous barrier
+            __syncthreads();
         }
-        const int f = fbase + 4 * v + kq;
-        if (row == 0 && f < n_frames) {
-            const int a_new = bi[v] == 0x7fffffff ? plo[v] : bi[v];
-            int *slot = dv.assign + (size_t)u * dv.F + f;
-            if (*slot != a_new) { *slot = a_new; atomicAdd(&moved[it % 3], 1); }
+        if (live) {
+            // best and second best over the 16 columns a lane group covers (lanes 16k .. 16k + 15)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+#pragma unroll
+                for (int o = 8; o >= 1; o >>= 1) {
+                    const double ov = __shfl_xor(bv[v], o, 16), os = __shfl_xor(sv[v], o, 16);
+                    const int oi = __shfl_xor(bi[v], o, 16);
+                    if (better(ov, oi, bv[v], bi[v])) { sv[v] = max_f64(bv[v], os); bv[v] = ov; bi[v] = oi; }
+                    else sv[v] = max_f64(sv[v], ov);
+                }
+                const int f = fbase + 4 * v + kq;
+                if (row == 0 && f < n_frames) {
+                    const bool none = bv[v] == -INFINITY;            // no candidate at all: the first id of the range
+                    const int a_new = none ? plo[v] : bi[v];
+                    int *slot = dv.assign + (size_t)u * dv.F + f;
+                    const int a_old = *slot;
+                    if (a_old != a_new) {
+                        *slot = a_new;
+                        atomicAdd(&moved[it % 3], 1);
+                        // both clusters' sums change; every other cluster's update is skipped (round 0 updates all)
+                        dv.lloyd_changed[(size_t)u * C + a_new] = 1;
+                        if (a_old >= 0 && a_old < C) dv.lloyd_changed[(size_t)u * C + a_old] = 1;
+                    }
+                    // chords to the winner and to the best other candidate (a frame without a winner, or an all-zero
+                    // summary, whose cosines are all 0, is never skipped)
+                    const double sn = sn_sh[wave][4 * v + kq];
+                    double ubn = 2.0, lbn = 0.0;
+                    if (!none && sn > 0.0) {
+                        ubn = sqrt(fmax(0.0, 2.0 - 2.0 * (bv[v] / sn)));
+                        lbn = sv[v] == -INFINITY ? INFINITY : sqrt(fmax(0.0, 2.0 - 2.0 * (sv[v] / sn)));
+                    }
+                    dv.lloyd_ub[(size_t)u * dv.F + f] = ubn;
+                    dv.lloyd_lb[(size_t)u * dv.F + f] = lbn;
+                }
+            }
         }
+        if (it == 0) break;
     }
 }
 
@@ -960,11 +1123,21 @@ __global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frame
     const int u = blockIdx.x, j = blockIdx.y, tid = threadIdx.x, C = dv.C;
     // (a round that moved no frame would rebuild the same sums: see k_lloyd_assign)
     if (it > 0 && dv.lloyd_moved[(size_t)u * 3 + it % 3] == 0) return;
+    // A cluster that no frame entered or left in this round (flags set by k_lloyd_assign) has the same
+    // members, so the same sums bit for bit: it is not recomputed, and its representative has not moved.
+    // Round 0 recomputes every cluster (the online running means are not the ordered sums).
+    int *changed = dv.lloyd_changed + (size_t)u * C + j;
+    double *delta = dv.lloyd_delta + (size_t)u * C + j;
+    if (it > 0 && *changed == 0) {                   // workgroup-uniform: the flag is cleared only after the last barrier
+        if (tid == 0) *delta = 0.0;
+        return;
+    }
+    const double norm_old = dv.rnorm[(size_t)u * C + j];
     const int wave = tid / 64, lane = tid % 64;
     __shared__ int a_sh[CH];
     __shared__ int mem[CH];
     __shared__ int wtot[2];
-    __shared__ double nsum_sh[2];
+    __shared__ double nsum_sh[2], dsum_sh[2];
     const int *assign = dv.assign + (size_t)u * dv.F;
     int *pos = dv.pos + (size_t)u * dv.F;
     double acc = 0.0;
@@ -1017,21 +1190,36 @@ __global__ __launch_bounds__(128) void k_lloyd_update(DeviceView dv, int n_frame
         count += filled;
     }
     if (count == 0) {                      // keeps its representative, skipped from now on
-        if (tid == 0) dv.n[(size_t)u * C + j] = 0;
+        if (tid == 0) { dv.n[(size_t)u * C + j] = 0; *delta = 0.0; *changed = 0; }
         return;
     }
-    double sq = 0.0;
+    double sq = 0.0, rv = 0.0, r_old = 0.0;
     if (tid < D) {
-        const double rv = acc / (double)count;
+        r_old = dv.r[((size_t)u * C + j) * D + tid];
+        rv = acc / (double)count;
         dv.r[((size_t)u * C + j) * D + tid] = rv;
         sq = rv * rv;
     }
     sq = wave_sum(sq);
     if (lane == 0) nsum_sh[wave] = sq;
     __syncthreads();
+    // how far the representative moved on the unit sphere (chord between the old and the new direction): what
+    // k_lloyd_assign's bounds are moved by; 2, the largest chord there is, if either is the zero vector
+    const double norm_new = sqrt(nsum_sh[0] + nsum_sh[1]);
+    const bool both = norm_old > 0.0 && norm_new > 0.0;
+    double dd = 0.0;
+    if (tid < D && both) {
+        const double t = r_old / norm_old - rv / norm_new;
+        dd = t * t;
+    }
+    dd = wave_sum(dd);
+    if (lane == 0) dsum_sh[wave] = dd;
+    __syncthreads();
     if (tid == 0) {
-        dv.rnorm[(size_t)u * C + j] = sqrt(nsum_sh[0] + nsum_sh[1]);
+        dv.rnorm[(size_t)u * C + j] = norm_new;
         dv.n[(size_t)u * C + j] = count;
+        *delta = both ? sqrt(dsum_sh[0] + dsum_sh[1]) : 2.0;
+        *changed = 0;
     }
 }
 
@@ -1184,11 +1372,20 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
         if (e != hipSuccess) return e;
     }
     dim3 ga(dv.U, (n_frames + 63) / 64), gu(dv.U, dv.C);
-    if ((e = hipMemsetAsync(dv.lloyd_moved, 0, (size_t)dv.U * 3 * 4, s)) != hipSuccess) return e;
+    // the rounds' moved-frame counters, live-row counters and, behind them, the clusters' changed flags
+    if ((e = hipMemsetAsync(dv.lloyd_moved, 0, ((size_t)dv.U * 6 + (size_t)dv.U * dv.C) * 4, s)) != hipSuccess) return e;
     for (int it = 0; it < iters; ++it) {
+        if (it > 0) {
+            e = checked([&] { k_lloyd_bounds<<<dim3(dv.U, (n_frames + 1023) / 1024), kBlock, 0, s>>>(dv, n_frames, it); });
+            if (e != hipSuccess) return e;
+        }
+        // (later rounds: a workgroup per task of four live rows, the rest of the grid exits at once; fewer
+        // workgroups that take tasks in turn were slower, 80 against 59 us per round: a unit whose rows mostly
+        // stay alive then keeps its few workgroups busy for several tasks)
+        const dim3 gi = ga;
         e = checked([&] {
-            if (dv.D == 64) k_lloyd_assign<64><<<ga, kBlock, 0, s>>>(dv, n_frames, it);
-            else k_lloyd_assign<128><<<ga, kBlock, 0, s>>>(dv, n_frames, it);
+            if (dv.D == 64) k_lloyd_assign<64><<<gi, kBlock, 0, s>>>(dv, n_frames, it);
+            else k_lloyd_assign<128><<<gi, kBlock, 0, s>>>(dv, n_frames, it);
         });
         if (e != hipSuccess) return e;
         e = checked([&] {

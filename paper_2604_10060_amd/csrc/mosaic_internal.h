@@ -58,7 +58,12 @@ struct DeviceView {
     int *pos;         // [U][F]      rank of the frame among its cluster's members (ascending frame order)
     long long *sel_flag;   // [U]    (launch number << 32 | retrieved pages) of the unit's last selection published inside a launch (k_decode_layer)
     int *sync_err;    // [1]         set if a bounded in-kernel wait ever ran out
-    int *lloyd_moved; // [U][3]      frames moved by the K-means rounds it-1, it, it+1 (mod 3): converged units skip the rest
+    int *lloyd_moved; // [U][3]      frames moved by the K-means rounds it-1, it, it+1 (mod 3): converged units skip the rest;
+                      //             behind it [U][3] rows of 16 frames the rounds' bound tests left alive
+    int *lloyd_live;  // [U][ceil(F/16)] those rows (index of the row's first frame / 16), in order of arrival
+    int *lloyd_changed; // [U][C]    1 = a frame entered or left the cluster in the current round (its sums must be rebuilt)
+    double *lloyd_delta; // [U][C]   chord by which the last update moved the representative's direction
+    double *lloyd_ub, *lloyd_lb; // [U][F]  chord bounds of a frame: to its own representative from above, to any other from below
     // self-adaptive maintainer (paper Sec. VI); maint_mode 0 = off (the arrays are then empty)
     int maint_mode, c_init, split_iters, buf_max;
     int SC;           // score columns per unit: C + buf_max

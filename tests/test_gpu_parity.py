@@ -94,6 +94,26 @@ def test_recluster_parity():
     assert rep.lloyd_runs >= 4 * 4      # init + 4 re-clusterings (48..192, 96 etc.), per unit
 
 
+@pytest.mark.parametrize("kw", [
+    # weakly structured keys (a scene every 1-3 frames, noise as large as the scene centres): many frames keep
+    # moving between clusters for all twelve rounds, so rows of frames pass and fail the bound test of the later
+    # rounds side by side
+    dict(n_frames=700, scene_model="rapid", noise=1.0, drift=0.0, n_clusters=24, warmup_frames=48,
+         recluster_every=128, lloyd_iters=12),
+    # more frames than one workgroup of the bound test covers, cluster count not a multiple of the tile
+    dict(n_frames=1200, n_scenes=30, n_clusters=40, warmup_frames=80, recluster_every=400, lloyd_iters=8),
+    # head size 64, clusters that run empty (more clusters than scenes, few frames)
+    dict(n_frames=300, head_dim=64, n_scenes=5, n_clusters=48, warmup_frames=96, recluster_every=100, lloyd_iters=6),
+])
+def test_recluster_rounds_with_skipped_frames_parity(kw):
+    """The K-means rounds after the first skip frames whose assignment cannot change and clusters whose members
+    did not change: assignments, sizes and representatives must still be the oracle's, which does neither."""
+    wl = _small(**kw)
+    rep = harness.run_workload(wl, decode_steps=1)
+    _report(rep)
+    assert rep.lloyd_runs >= 2 * 4
+
+
 def test_low_coherence_stream():
     wl = inputs.cfg4_stream(5).scaled(n_frames=192, n_clusters=16, top_k=5, question_tokens=8)
     rep = harness.run_workload(wl)

@@ -492,11 +492,13 @@ __global__ __launch_bounds__(kBlock) void k_assign_update(DeviceView dv, int f0,
 template <int D, int THREADS, typename E>
 __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int u, int f0, int f1, const E *k_in) {
     constexpr int EPL = D / 16, NG = THREADS / 16, RPG = 8, NW = THREADS / 64, ROWS = NG * RPG;
+    constexpr int CHUNK = 32;                   // frames whose summaries are staged in LDS at a time
     const int tid = threadIdx.x, C = dv.C;
     const int lr = tid % 16, grp = tid / 16, wave = tid / 64, lane = tid % 64;
-    __shared__ double s_sh[2][D];
+    __shared__ __attribute__((aligned(16))) double s_sh[CHUNK][D];
     __shared__ double dot_sh[ROWS], rn_sh[ROWS];
     __shared__ int n_sh[ROWS];
+    __shared__ int a_out[CHUNK], p_out[CHUNK];
     __shared__ double red_v[NW];
     __shared__ int red_i[NW];
     __shared__ double psum_sh[2];
@@ -522,112 +524,143 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
             __shared__ double red[kBlock / (D / 8)][D];
             store_key_page<E, D>(dv, k_in, dv.k_store, u, 0, f0, red, s_sh[0]);      // HBM tier only
         }
-    } else if (tid < D) {
-        s_sh[0][tid] = dv.summ[((size_t)u * dv.F + f0) * D + tid];
     }
     const bool nested = dv.P > 0;
-    __syncthreads();
-    for (int f = f0; f < f1; ++f) {
-        const int cur = (f - f0) & 1;
-        const double *sv = s_sh[cur];
-        // the next frame's summary: issued now, stored into the other buffer at the end
-        double s_next = 0.0;
-        if (tid < D && f + 1 < f1) s_next = dv.summ[((size_t)u * dv.F + f + 1) * D + tid];
-        const int part_f = nested ? dv.part[f] : 0;
-        const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : C;
-        // Dot products of the summary with every row the group holds, unconditionally and
-        // without lane-dependent branches so that the rows' reduction chains interleave (rows
-        // beyond the table or of empty clusters give values nobody reads); the group also
-        // forms |s|^2 from its own share of the channels, the same bits in every group.
-        double sl[EPL];
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) sl[e] = sv[lr * EPL + e];
-        double ssq = 0.0;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) ssq += sl[e] * sl[e];
-        const double sn = sqrt(row16_sum(ssq));
-#pragma unroll
-        for (int i = 0; i < RPG; ++i) {
-            if (NG * i < C) {                                 // block-uniform
-                double p = 0.0;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) p += sl[e] * rr[i][e];
-                p = row16_sum(p);
-                if (lr == 0) dot_sh[grp + NG * i] = p;
-            }
+    // The barriers inside the frame loop order LDS traffic only, and the loop touches no global memory: the
+    // call's summaries are staged in LDS a chunk at a time, the winner's row stays in registers and is written
+    // back once after the last frame, sizes and norms live in LDS, the frames' ids and ranks collect in LDS until
+    // the chunk ends.  A full __syncthreads() waits for every outstanding global access of the wavefront, and so
+    // does any wait the compiler places for a register a load is still to fill: with the next frame's summary
+    // fetched inside the loop and the winner's row written through in every frame, each frame waited once for
+    // that load, issued a moment before, and once for the store's acknowledgement.  The nested hierarchy's
+    // partition representatives and sizes do go through global memory from one frame to the next, so there the
+    // barriers stay full ones.
+    auto frame_barrier = [&]() {
+        if (nested) __syncthreads();          // workgroup-uniform
+        else lds_barrier();
+    };
+    unsigned int dirty = 0;                   // bit i: this group's row i changed in this call
+    for (int c0 = f0; c0 < f1; c0 += CHUNK) {
+        const int nc = min(CHUNK, f1 - c0);
+        if (k_in == nullptr) {
+            const double *src = dv.summ + ((size_t)u * dv.F + c0) * D;
+            for (int i = tid; i < nc * D / 2; i += THREADS)
+                *reinterpret_cast<double2 *>(&s_sh[0][0] + 2 * i) = *reinterpret_cast<const double2 *>(src + 2 * i);
         }
         __syncthreads();
-        // argmax of the cosine over the candidates, ties to the lowest id (THREADS >= C: at
-        // most one candidate per thread)
-        double bv = -INFINITY;
-        int bi = 0x7fffffff;
-        {
-            const int j = lo + tid;
-            if (j < hi && n_sh[j] > 0) {
-                bv = (sn == 0.0 || rn_sh[j] == 0.0) ? 0.0 : dot_sh[j] / (sn * rn_sh[j]);
-                bi = j;
-            }
-        }
-        wave_best(bv, bi);
-        if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
-        // nested hierarchy: the partition's representative follows the same running mean
-        int pn_i = 0;
-        if (nested) {
-            double *prow = dv.pr + ((size_t)u * dv.P + part_f) * D;
-            pn_i = dv.pn[(size_t)u * dv.P + part_f];
-            double psq = 0.0;
-            if (tid < D) {
-                const double pv = ((double)pn_i * prow[tid] + sv[tid]) / ((double)pn_i + 1.0);
-                prow[tid] = pv;
-                psq = pv * pv;
-            }
-            if (wave < 2) {
-                psq = wave_sum(psq);
-                if (lane == 0) psum_sh[wave] = psq;
-            }
-        }
-        __syncthreads();
-        // every thread merges the wavefronts' winners itself (no second barrier for one thread's merge)
-        bv = red_v[0]; bi = red_i[0];
+        for (int fc = 0; fc < nc; ++fc) {
+            const int f = c0 + fc;
+            const double *sv = s_sh[fc];
+            const int part_f = nested ? dv.part[f] : 0;
+            const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : C;
+            // Dot products of the summary with every row the group holds, unconditionally and
+            // without lane-dependent branches so that the rows' reduction chains interleave (rows
+            // beyond the table or of empty clusters give values nobody reads); the group also
+            // forms |s|^2 from its own share of the channels, the same bits in every group.
+            double sl[EPL];
 #pragma unroll
-        for (int w = 1; w < NW; ++w)
-            if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
-        const int a = bi == 0x7fffffff ? lo : bi;
-        const int ai = __builtin_amdgcn_readfirstlane(a / NG);      // workgroup-uniform: a scalar
-        if (grp == a % NG) {                                  // the group that holds row a
-            const int na_i = n_sh[a];
-            const double na = (double)na_i;
-            double sq = 0.0;
+            for (int e = 0; e < EPL; ++e) sl[e] = sv[lr * EPL + e];
+            double ssq = 0.0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) ssq += sl[e] * sl[e];
+            const double sn = sqrt(row16_sum(ssq));
 #pragma unroll
             for (int i = 0; i < RPG; ++i) {
-                if (i == ai) {                                // scalar branch: one pass runs
+                if (NG * i < C) {                                 // block-uniform
+                    double p = 0.0;
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) {
-                        // Eq. 3 with each operation rounded separately (no contraction)
-                        const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, rr[i][e]), sl[e]), na + 1.0);
-                        rr[i][e] = rv;
-                        r[(size_t)a * D + lr * EPL + e] = rv;
-                        sq += rv * rv;
-                    }
+                    for (int e = 0; e < EPL; ++e) p += sl[e] * rr[i][e];
+                    p = row16_sum(p);
+                    if (lr == 0) dot_sh[grp + NG * i] = p;
                 }
             }
-            sq = row16_sum(sq);
-            if (lr == 0) {
-                const double nr = sqrt(sq);
-                rn_sh[a] = nr;
-                dv.rnorm[(size_t)u * C + a] = nr;
-                n_sh[a] = na_i + 1;
-                dv.n[(size_t)u * C + a] = na_i + 1;
-                dv.assign[(size_t)u * dv.F + f] = a;
-                dv.pos[(size_t)u * dv.F + f] = na_i;
+            frame_barrier();
+            // argmax of the cosine over the candidates, ties to the lowest id (THREADS >= C: at
+            // most one candidate per thread)
+            double bv = -INFINITY;
+            int bi = 0x7fffffff;
+            {
+                const int j = lo + tid;
+                if (j < hi && n_sh[j] > 0) {
+                    bv = (sn == 0.0 || rn_sh[j] == 0.0) ? 0.0 : dot_sh[j] / (sn * rn_sh[j]);
+                    bi = j;
+                }
             }
+            wave_best(bv, bi);
+            if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
+            // nested hierarchy: the partition's representative follows the same running mean
+            int pn_i = 0;
+            if (nested) {
+                double *prow = dv.pr + ((size_t)u * dv.P + part_f) * D;
+                pn_i = dv.pn[(size_t)u * dv.P + part_f];
+                double psq = 0.0;
+                if (tid < D) {
+                    const double pv = ((double)pn_i * prow[tid] + sv[tid]) / ((double)pn_i + 1.0);
+                    prow[tid] = pv;
+                    psq = pv * pv;
+                }
+                if (wave < 2) {
+                    psq = wave_sum(psq);
+                    if (lane == 0) psum_sh[wave] = psq;
+                }
+            }
+            frame_barrier();
+            // every thread merges the wavefronts' winners itself (no second barrier for one thread's merge)
+            bv = red_v[0]; bi = red_i[0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w)
+                if (better(red_v[w], red_i[w], bv, bi)) { bv = red_v[w]; bi = red_i[w]; }
+            const int a = bi == 0x7fffffff ? lo : bi;
+            const int ai = __builtin_amdgcn_readfirstlane(a / NG);      // workgroup-uniform: a scalar
+            if (grp == a % NG) {                                  // the group that holds row a
+                const int na_i = n_sh[a];
+                const double na = (double)na_i;
+                double sq = 0.0;
+#pragma unroll
+                for (int i = 0; i < RPG; ++i) {
+                    if (i == ai) {                                // scalar branch: one pass runs
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) {
+                            // Eq. 3 with each operation rounded separately (no contraction)
+                            const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, rr[i][e]), sl[e]), na + 1.0);
+                            rr[i][e] = rv;
+                            sq += rv * rv;
+                        }
+                    }
+                }
+                dirty |= 1u << ai;
+                sq = row16_sum(sq);
+                if (lr == 0) {
+                    rn_sh[a] = sqrt(sq);
+                    n_sh[a] = na_i + 1;
+                    a_out[fc] = a;
+                    p_out[fc] = na_i;
+                }
+            }
+            if (nested && tid == 0) {
+                dv.prn[(size_t)u * dv.P + part_f] = sqrt(D > 64 ? psum_sh[0] + psum_sh[1] : psum_sh[0]);
+                dv.pn[(size_t)u * dv.P + part_f] = pn_i + 1;
+            }
+            frame_barrier();
         }
-        if (nested && tid == 0) {
-            dv.prn[(size_t)u * dv.P + part_f] = sqrt(D > 64 ? psum_sh[0] + psum_sh[1] : psum_sh[0]);
-            dv.pn[(size_t)u * dv.P + part_f] = pn_i + 1;
+        // the chunk's ids and ranks (the barrier that ended its last frame made them visible)
+        if (tid < nc) {
+            dv.assign[(size_t)u * dv.F + c0 + tid] = a_out[tid];
+            dv.pos[(size_t)u * dv.F + c0 + tid] = p_out[tid];
         }
-        if (tid < D) s_sh[cur ^ 1][tid] = s_next;
-        __syncthreads();
+        __syncthreads();                          // before the next chunk overwrites the staged summaries
+    }
+    // write back what changed: rows, then every cluster's size and norm
+#pragma unroll
+    for (int i = 0; i < RPG; ++i) {
+        if ((dirty >> i) & 1u) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) r[(size_t)(grp + NG * i) * D + lr * EPL + e] = rr[i][e];
+        }
+    }
+    for (int j = tid; j < C; j += THREADS) {
+        dv.n[(size_t)u * C + j] = n_sh[j];
+        dv.rnorm[(size_t)u * C + j] = rn_sh[j];
     }
 }
 

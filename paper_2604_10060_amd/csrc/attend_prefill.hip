@@ -227,7 +227,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void k_attend_prefill_mfm
     // the 2 (DIST - 1) younger pairs in flight; then the workgroup meets.
     auto publish = [&]() {
         wait_vmem_le<kPending>();
-        __syncthreads();
+        lds_barrier();          // (a full __syncthreads() would wait for the younger pairs as well)
     };
     auto ldk = [&](int s, bf16x8 (&kf)[2 * KK]) {
         const unsigned char *const kb = prefill_lds + s * KBYTES;

@@ -499,6 +499,7 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
     __shared__ double dot_sh[ROWS], rn_sh[ROWS];
     __shared__ int n_sh[ROWS];
     __shared__ int a_out[CHUNK], p_out[CHUNK];
+    __shared__ int chg_sh[ROWS];                // 1 = the cluster's size and norm changed in this call
     __shared__ double red_v[NW];
     __shared__ int red_i[NW];
     __shared__ double psum_sh[2];
@@ -518,6 +519,7 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
     for (int j = tid; j < ROWS; j += THREADS) {
         n_sh[j] = j < C ? dv.n[(size_t)u * C + j] : 0;
         rn_sh[j] = j < C ? dv.rnorm[(size_t)u * C + j] : 0.0;
+        chg_sh[j] = 0;
     }
     if (k_in != nullptr) {
         if constexpr (THREADS == kBlock) {
@@ -540,6 +542,8 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
         else lds_barrier();
     };
     unsigned int dirty = 0;                   // bit i: this group's row i changed in this call
+    // a one-frame call is all latency: its results go straight to memory, with no collection and no write-back pass
+    const bool single = f1 - f0 == 1;
     for (int c0 = f0; c0 < f1; c0 += CHUNK) {
         const int nc = min(CHUNK, f1 - c0);
         if (k_in == nullptr) {
@@ -624,23 +628,34 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
                             // Eq. 3 with each operation rounded separately (no contraction)
                             const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, rr[i][e]), sl[e]), na + 1.0);
                             rr[i][e] = rv;
+                            if (single) r[(size_t)a * D + lr * EPL + e] = rv;
                             sq += rv * rv;
                         }
                     }
                 }
-                dirty |= 1u << ai;
+                if (!single) dirty |= 1u << ai;
                 sq = row16_sum(sq);
                 if (lr == 0) {
-                    rn_sh[a] = sqrt(sq);
-                    n_sh[a] = na_i + 1;
-                    a_out[fc] = a;
-                    p_out[fc] = na_i;
+                    const double nr = sqrt(sq);
+                    if (single) {
+                        dv.rnorm[(size_t)u * C + a] = nr;
+                        dv.n[(size_t)u * C + a] = na_i + 1;
+                        dv.assign[(size_t)u * dv.F + f] = a;
+                        dv.pos[(size_t)u * dv.F + f] = na_i;
+                    } else {
+                        rn_sh[a] = nr;
+                        n_sh[a] = na_i + 1;
+                        chg_sh[a] = 1;
+                        a_out[fc] = a;
+                        p_out[fc] = na_i;
+                    }
                 }
             }
             if (nested && tid == 0) {
                 dv.prn[(size_t)u * dv.P + part_f] = sqrt(D > 64 ? psum_sh[0] + psum_sh[1] : psum_sh[0]);
                 dv.pn[(size_t)u * dv.P + part_f] = pn_i + 1;
             }
+            if (single) return;                   // workgroup-uniform: nothing follows the only frame
             frame_barrier();
         }
         // the chunk's ids and ranks (the barrier that ended its last frame made them visible)
@@ -650,7 +665,7 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
         }
         __syncthreads();                          // before the next chunk overwrites the staged summaries
     }
-    // write back what changed: rows, then every cluster's size and norm
+    // write back what changed: rows, sizes and norms
 #pragma unroll
     for (int i = 0; i < RPG; ++i) {
         if ((dirty >> i) & 1u) {
@@ -659,8 +674,10 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
         }
     }
     for (int j = tid; j < C; j += THREADS) {
-        dv.n[(size_t)u * C + j] = n_sh[j];
-        dv.rnorm[(size_t)u * C + j] = rn_sh[j];
+        if (chg_sh[j]) {
+            dv.n[(size_t)u * C + j] = n_sh[j];
+            dv.rnorm[(size_t)u * C + j] = rn_sh[j];
+        }
     }
 }
 

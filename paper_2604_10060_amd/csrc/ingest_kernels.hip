@@ -557,27 +557,44 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
             const double *sv = s_sh[fc];
             const int part_f = nested ? dv.part[f] : 0;
             const int lo = nested ? part_f * dv.Cs : 0, hi = nested ? lo + dv.Cs : C;
-            // Dot products of the summary with every row the group holds, unconditionally and
-            // without lane-dependent branches so that the rows' reduction chains interleave (rows
-            // beyond the table or of empty clusters give values nobody reads); the group also
+            // Dot products of the summary with the rows the group holds, four rows at a time written out side by
+            // side: four independent multiply-add chains, then their 16-lane reductions step by step in lockstep,
+            // so that one chain's latency is filled by the other three (a loop over the rows with the block-uniform
+            // test per row kept every row's chain in a basic block of its own: 2100 cycles per frame for 210
+            // instructions).  Rows beyond the table or of empty clusters give values nobody reads.  The group also
             // forms |s|^2 from its own share of the channels, the same bits in every group.
             double sl[EPL];
 #pragma unroll
             for (int e = 0; e < EPL; ++e) sl[e] = sv[lr * EPL + e];
             double ssq = 0.0;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) ssq += sl[e] * sl[e];
-            const double sn = sqrt(row16_sum(ssq));
+            for (int h = 0; h < RPG / 4; ++h) {
+                if (h > 0 && NG * 4 * h >= C) break;                  // block-uniform: passes beyond the table
+                double p[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int i = 0; i < RPG; ++i) {
-                if (NG * i < C) {                                 // block-uniform
-                    double p = 0.0;
+                for (int e = 0; e < EPL; ++e) {
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) p += sl[e] * rr[i][e];
-                    p = row16_sum(p);
-                    if (lr == 0) dot_sh[grp + NG * i] = p;
+                    for (int k = 0; k < 4; ++k) p[k] += sl[e] * rr[4 * h + k][e];
+                    if (h == 0) ssq += sl[e] * sl[e];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) p[k] += dpp_f64<kDppXor8>(p[k]);
+                if (h == 0) ssq += dpp_f64<kDppXor8>(ssq);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) p[k] += dpp_f64<kDppXor7>(p[k]);
+                if (h == 0) ssq += dpp_f64<kDppXor7>(ssq);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) p[k] += dpp_f64<kDppXor3>(p[k]);
+                if (h == 0) ssq += dpp_f64<kDppXor3>(ssq);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) p[k] += dpp_f64<kDppXor1>(p[k]);
+                if (h == 0) ssq += dpp_f64<kDppXor1>(ssq);
+                if (lr == 0) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) dot_sh[grp + NG * (4 * h + k)] = p[k];
                 }
             }
+            const double sn = sqrt(ssq);
             frame_barrier();
             // argmax of the cosine over the candidates, ties to the lowest id (THREADS >= C: at
             // most one candidate per thread)
@@ -619,14 +636,25 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
             if (grp == a % NG) {                                  // the group that holds row a
                 const int na_i = n_sh[a];
                 const double na = (double)na_i;
+                // Eq. 3 with each operation rounded separately (no contraction).  The division by n + 1, the same
+                // divisor for the lane's eight channels: the compiler's division sequence hands a flag from its
+                // scaling step to its last step in VCC, so eight of them run one after the other (1400 cycles).
+                // Instead y = RN(1 / (n + 1)) once, then per channel q = RN(x y) and two residual corrections
+                // q <- RN(q + RN(x - (n + 1) q) y), each residual exact in a fused multiply-add: the first leaves q
+                // within half an ulp and a little of x / (n + 1), and from such a q and a correctly rounded y the
+                // second returns the correctly rounded quotient (Markstein's theorem; n + 1 is a small integer, so
+                // its significand is not all ones, and nothing here is near the ends of the exponent range).
+                const double nb = na + 1.0, ny = __ddiv_rn(1.0, nb);
                 double sq = 0.0;
 #pragma unroll
                 for (int i = 0; i < RPG; ++i) {
                     if (i == ai) {                                // scalar branch: one pass runs
 #pragma unroll
                         for (int e = 0; e < EPL; ++e) {
-                            // Eq. 3 with each operation rounded separately (no contraction)
-                            const double rv = __ddiv_rn(__dadd_rn(__dmul_rn(na, rr[i][e]), sl[e]), na + 1.0);
+                            const double x = __dadd_rn(__dmul_rn(na, rr[i][e]), sl[e]);
+                            double rv = __dmul_rn(x, ny);
+                            rv = __fma_rn(__fma_rn(-nb, rv, x), ny, rv);
+                            rv = __fma_rn(__fma_rn(-nb, rv, x), ny, rv);
                             rr[i][e] = rv;
                             if (single) r[(size_t)a * D + lr * EPL + e] = rv;
                             sq += rv * rv;

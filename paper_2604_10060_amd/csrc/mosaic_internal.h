@@ -246,7 +246,9 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
 // same bits.  About 80 cycles for a double against about 500 with ds_bpermute.
 // ---------------------------------------------------------------------------
 template <int CTRL> __device__ __forceinline__ int dpp_i32(int x) {
-    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, false);
+    // bound_ctrl on: a source lane that is out of range or switched off reads as 0, which is also what the old value 0
+    // would leave, and the compiler need not clear the destination first (two instructions fewer per 64-bit step)
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
 }
 template <int CTRL> __device__ __forceinline__ double dpp_f64(double x) {
     const long long b = __double_as_longlong(x);

@@ -1010,19 +1010,27 @@ __device__ __forceinline__ double min_f64(double a, double b) {
     return r;
 }
 
-template <int D>
-__global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n_frames, int it) {
+// LATER: the instantiation for the rounds after the first.  Their launches are mostly workgroups that find nothing to
+// do and lone tasks that are all latency, so it may use more registers (two wavefronts per SIMD are plenty) to start
+// every independent load at once: both round counters and the wavefront's list entry together, the frames' old ids
+// with the operands, the table built while the operands travel; and its bounds take their roots in fp32.
+template <int D, bool LATER>
+__global__ __launch_bounds__(kBlock, LATER ? 2 : 3) void k_lloyd_assign(DeviceView dv, int n_frames, int it) {
     constexpr int KS = D / 8;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, C = dv.C;
     const int row = lane % 16, kq = lane / 16;
     int *moved = dv.lloyd_moved + (size_t)u * 3;
     if (blockIdx.y == 0 && tid == 0) moved[(it + 1) % 3] = 0;
-    if (it > 0 && moved[(it - 1) % 3] == 0) return;            // workgroup-uniform: converged in an earlier round
     // Round 0: one task per workgroup, wavefront w of workgroup y takes frames 64 y + 16 w ...  Later rounds:
     // task t = rows 4 t .. 4 t + 3 of the unit's list of live rows, the workgroups of a unit taking tasks in turn.
-    int cnt = 0;
-    if (it > 0) {
+    const int n_rows = (dv.F + 15) / 16;
+    const int *live_list = dv.lloyd_live + (size_t)u * n_rows;
+    int cnt = 0, first_row = 0;
+    if constexpr (LATER) {
+        const int moved_before = moved[(it - 1) % 3];
         cnt = dv.lloyd_moved[(size_t)dv.U * 3 + (size_t)u * 3 + it % 3];
+        first_row = live_list[min((int)blockIdx.y * 4 + wave, n_rows - 1)];
+        if (moved_before == 0) return;                         // workgroup-uniform: converged in an earlier round
         if ((int)blockIdx.y * 4 >= cnt) return;                // workgroup-uniform
     }
     const double *r = dv.r + (size_t)u * C * D;
@@ -1057,31 +1065,44 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
     // (all 0) do.
     __shared__ __attribute__((aligned(16))) f64x2 scale_sh[1024 + 16];    // the cluster-count limit of a context, rounded up to tiles
     __shared__ double sn_sh[4][16];
-    for (int j = tid; j < 16 * n_tiles; j += kBlock) {
-        f64x2 e = {0.0, -INFINITY};
-        if (j < C && dv.n[(size_t)u * C + j] > 0) {
-            const double rnj = dv.rnorm[(size_t)u * C + j];
-            e.x = rnj == 0.0 ? 0.0 : 1.0 / rnj;
-            e.y = 0.0;
+    auto build_table = [&]() {
+        for (int j = tid; j < 16 * n_tiles; j += kBlock) {
+            f64x2 e = {0.0, -INFINITY};
+            if (j < C && dv.n[(size_t)u * C + j] > 0) {
+                const double rnj = dv.rnorm[(size_t)u * C + j];
+                e.x = rnj == 0.0 ? 0.0 : 1.0 / rnj;
+                e.y = 0.0;
+            }
+            scale_sh[j] = e;
         }
-        scale_sh[j] = e;
-    }
+    };
+    if constexpr (!LATER) build_table();
     const bool nested = dv.P > 0;
     for (int task = blockIdx.y;; task += gridDim.y) {
         int fbase = task * 64 + wave * 16;
         bool live = true;
-        if (it > 0) {
+        if constexpr (LATER) {
             if (task * 4 >= cnt) break;                         // workgroup-uniform
             live = task * 4 + wave < cnt;
-            fbase = live ? dv.lloyd_live[(size_t)u * ((dv.F + 15) / 16) + task * 4 + wave] * 16 : 0;
+            fbase = !live ? 0 : 16 * (task == (int)blockIdx.y ? first_row : live_list[task * 4 + wave]);
         }
         fetch_tile(0);
         f64x2 a[KS];
+        int a_old[4] = {0, 0, 0, 0};     // LATER: the frames' ids before this round, for the lane that finishes them
         if (live) {
             const int f = min(fbase + row, n_frames - 1);
             const double *sp = dv.summ + ((size_t)u * dv.F + f) * D + 2 * kq;
 #pragma unroll
             for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const f64x2 *>(sp + 8 * s);
+            if constexpr (LATER) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) a_old[v] = dv.assign[(size_t)u * dv.F + min(fbase + 4 * v + kq, n_frames - 1)];
+            }
+        }
+        if constexpr (LATER) {
+            if (task == (int)blockIdx.y) build_table();        // once, while the summaries are on their way
+        }
+        if (live) {
             double sq = 0.0;
 #pragma unroll
             for (int s = 0; s < KS; ++s) sq += a[s].x * a[s].x + a[s].y * a[s].y;
@@ -1160,28 +1181,39 @@ __global__ __launch_bounds__(kBlock, 3) void k_lloyd_assign(DeviceView dv, int n
                     const bool none = bv[v] == -INFINITY;            // no candidate at all: the first id of the range
                     const int a_new = none ? plo[v] : bi[v];
                     int *slot = dv.assign + (size_t)u * dv.F + f;
-                    const int a_old = *slot;
-                    if (a_old != a_new) {
+                    const int a_was = LATER ? a_old[v] : *slot;
+                    if (a_was != a_new) {
                         *slot = a_new;
                         atomicAdd(&moved[it % 3], 1);
                         // both clusters' sums change; every other cluster's update is skipped (round 0 updates all)
                         dv.lloyd_changed[(size_t)u * C + a_new] = 1;
-                        if (a_old >= 0 && a_old < C) dv.lloyd_changed[(size_t)u * C + a_old] = 1;
+                        if (a_was >= 0 && a_was < C) dv.lloyd_changed[(size_t)u * C + a_was] = 1;
                     }
                     // chords to the winner and to the best other candidate (a frame without a winner, or an all-zero
                     // summary, whose cosines are all 0, is never skipped)
                     const double sn = sn_sh[wave][4 * v + kq];
                     double ubn = 2.0, lbn = 0.0;
                     if (!none && sn > 0.0) {
-                        ubn = sqrt(fmax(0.0, 2.0 - 2.0 * (bv[v] / sn)));
-                        lbn = sv[v] == -INFINITY ? INFINITY : sqrt(fmax(0.0, 2.0 - 2.0 * (sv[v] / sn)));
+                        if constexpr (LATER) {
+                            // They only have to bound: roots in fp32 (relative error below 2e-7 with the conversion),
+                            // pushed outwards by 1e-6 relative and 1e-9 absolute; an fp64 root is a dozen instructions
+                            // and, like the fp64 division, keeps a flag in VCC, so a lane's eight ran one after the other.
+                            const double inv = 1.0 / sn;
+                            ubn = (double)sqrtf((float)fmax(0.0, 2.0 - 2.0 * (bv[v] * inv))) * (1.0 + 1e-6) + 1e-9;
+                            lbn = sv[v] == -INFINITY
+                                      ? INFINITY
+                                      : fmax(0.0, (double)sqrtf((float)fmax(0.0, 2.0 - 2.0 * (sv[v] * inv))) * (1.0 - 1e-6) - 1e-9);
+                        } else {
+                            ubn = sqrt(fmax(0.0, 2.0 - 2.0 * (bv[v] / sn)));
+                            lbn = sv[v] == -INFINITY ? INFINITY : sqrt(fmax(0.0, 2.0 - 2.0 * (sv[v] / sn)));
+                        }
                     }
                     dv.lloyd_ub[(size_t)u * dv.F + f] = ubn;
                     dv.lloyd_lb[(size_t)u * dv.F + f] = lbn;
                 }
             }
         }
-        if (it == 0) break;
+        if constexpr (!LATER) break;
     }
 }
 
@@ -1462,8 +1494,13 @@ hipError_t launch_lloyd(const DeviceView &dv, int n_frames, int iters, bool seed
         // stay alive then keeps its few workgroups busy for several tasks)
         const dim3 gi = ga;
         e = checked([&] {
-            if (dv.D == 64) k_lloyd_assign<64><<<gi, kBlock, 0, s>>>(dv, n_frames, it);
-            else k_lloyd_assign<128><<<gi, kBlock, 0, s>>>(dv, n_frames, it);
+            if (it == 0) {
+                if (dv.D == 64) k_lloyd_assign<64, false><<<gi, kBlock, 0, s>>>(dv, n_frames, it);
+                else k_lloyd_assign<128, false><<<gi, kBlock, 0, s>>>(dv, n_frames, it);
+            } else {
+                if (dv.D == 64) k_lloyd_assign<64, true><<<gi, kBlock, 0, s>>>(dv, n_frames, it);
+                else k_lloyd_assign<128, true><<<gi, kBlock, 0, s>>>(dv, n_frames, it);
+            }
         });
         if (e != hipSuccess) return e;
         e = checked([&] {

@@ -53,6 +53,44 @@ __device__ __forceinline__ double wave_sum(double x) { return wave64_sum(x); }
 __device__ __forceinline__ bool better(double v, int i, double bv, int bi) {
     return v > bv || (v == bv && i < bi);
 }
+// fp64 max / min as single instructions (the builtins add an instruction per operand that quiets signalling NaNs);
+// only used on values that are never NaN
+__device__ __forceinline__ double max_f64(double a, double b) {
+    double r;
+    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ double min_f64(double a, double b) {
+    double r;
+    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// Best (value, id) of a wavefront when the ids ascend with the lane (at most one candidate per lane, -inf and
+// 0x7fffffff in lanes without one; no NaN): the largest value by a max butterfly (three instructions per step
+// against a dozen for the (value, id) pair), then the first lane that holds it, which is the lowest id.  Left in
+// every lane.
+__device__ __forceinline__ void wave_best_ascending(double &bv, int &bi) {
+    double m = bv;
+    m = max_f64(m, dpp_f64<kDppXor8>(m));
+    m = max_f64(m, dpp_f64<kDppXor7>(m));
+    m = max_f64(m, dpp_f64<kDppXor3>(m));
+    m = max_f64(m, dpp_f64<kDppXor1>(m));
+    const long long b = __double_as_longlong(m);
+    const int lo = (int)b, hi = (int)(b >> 32);
+    double wm = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int l = __builtin_amdgcn_readlane(lo, 16 * r), h = __builtin_amdgcn_readlane(hi, 16 * r);
+        wm = fmax(wm, __longlong_as_double(((long long)h << 32) | (long long)(unsigned int)l));
+    }
+    const unsigned long long at = __ballot(bv == wm);
+    const int first = __ffsll((long long)at) - 1;                       // some lane holds the maximum
+    const int id = __builtin_amdgcn_readlane(bi, first);
+    bv = wm;
+    bi = wm == -INFINITY ? 0x7fffffff : id;
+}
+
 // Best (value, id) of a wavefront, left in every lane: a butterfly inside each row of 16
 // lanes with data-parallel primitives (the order is total, so every lane of a row ends
 // with the same pair), then the four rows' pairs are read from their first lanes.
@@ -607,7 +645,7 @@ __device__ __forceinline__ void assign_update_reg_run(const DeviceView &dv, int 
                     bi = j;
                 }
             }
-            wave_best(bv, bi);
+            wave_best_ascending(bv, bi);        // (ids ascend with the thread: j = lo + tid)
             if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
             // nested hierarchy: the partition's representative follows the same running mean
             int pn_i = 0;
@@ -995,19 +1033,6 @@ __global__ __launch_bounds__(kBlock) void k_lloyd_bounds(DeviceView dv, int n_fr
                 dv.lloyd_live[(size_t)u * ((dv.F + 15) / 16) + base + __popc(rows & ((1u << g) - 1u))] = f0 / 16 + g;
         }
     }
-}
-
-// fp64 max / min as single instructions (the builtins add an instruction per operand that quiets signalling NaNs);
-// only used on values that are never NaN
-__device__ __forceinline__ double max_f64(double a, double b) {
-    double r;
-    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-__device__ __forceinline__ double min_f64(double a, double b) {
-    double r;
-    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
 }
 
 // LATER: the instantiation for the rounds after the first.  Their launches are mostly workgroups that find nothing to

@@ -129,7 +129,12 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         fa[i] = in ? assign[f] : -1;
         fp[i] = in ? pos[f] : 0;
     }
-    for (int j = tid; j < C; j += BLK) { n_sh[j] = n[j]; rn_sh[j] = rn[j]; cnt_sh[j] = 0; wcnt_sh[j] = 0; }
+    // (C <= 1024 = BLK: one table entry per thread, loaded into registers now and stored to LDS only after every
+    // other load has been issued: a loop here would be a basic block of its own, and its LDS stores would wait for
+    // its loads before the loads below could start)
+    int n_reg = 0;
+    double rn_reg = 0.0;
+    if (tid < C) { n_reg = n[tid]; rn_reg = rn[tid]; }
     if (tid == 0) tk_sh.n_live = 0;
     // local-window augmentation (Sec. V-C): the w most recent frames are listed once, after the
     // clusters; they are the last members of their clusters (ranks ascend with the frame id), so
@@ -163,16 +168,41 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
         if (tid == 0) p_live_sh = 0;
     }
     // mean query over the Tq tokens and the G query heads of this KV head
-    mean_query_partials<E, D>(q, lc, h, Tq, G, Hq, qpart);
-    __syncthreads();
-    if (wa >= 0) atomicAdd(&wcnt_sh[wa], 1);
-    if (tid < D) {
-        double acc = 0.0;
+    const int R = Tq * G;
+    if (R <= 16) {
+        // A decode step or a short question: a thread per channel adds the rows in order, every row's load in flight
+        // at once, beside the loads above: the prologue is one trip to memory.  (The general path below costs a
+        // decode step two trips and a reduction through LDS permutes for seven rows.)
+        if (tid < D) {
+            const E *qb = q + (size_t)lc * Tq * Hq * D + (size_t)h * G * D + tid;
+            E v[16];
 #pragma unroll
-        for (int p = 0; p < BLK / 64; ++p) acc += qpart[p][tid];
-        qbar[tid] = acc / (double)(Tq * G);
+            for (int x = 0; x < 16; ++x) {
+                const int rr = min(x, R - 1), t = rr / G, g = rr - t * G;
+                v[x] = qb[((size_t)t * Hq + g) * D];
+            }
+            double acc = 0.0;
+#pragma unroll
+            for (int x = 0; x < 16; ++x)
+                if (x < R) acc += to_f64<E>(v[x]);
+            qbar[tid] = acc / (double)R;
+        }
+        if (tid < C) { n_sh[tid] = n_reg; rn_sh[tid] = rn_reg; cnt_sh[tid] = 0; wcnt_sh[tid] = 0; }
+        __syncthreads();
+        if (wa >= 0) atomicAdd(&wcnt_sh[wa], 1);         // (read after the scores' barrier at the earliest)
+    } else {
+        if (tid < C) { n_sh[tid] = n_reg; rn_sh[tid] = rn_reg; cnt_sh[tid] = 0; wcnt_sh[tid] = 0; }
+        mean_query_partials<E, D>(q, lc, h, Tq, G, Hq, qpart);
+        __syncthreads();
+        if (wa >= 0) atomicAdd(&wcnt_sh[wa], 1);
+        if (tid < D) {
+            double acc = 0.0;
+#pragma unroll
+            for (int p = 0; p < BLK / 64; ++p) acc += qpart[p][tid];
+            qbar[tid] = acc / (double)R;
+        }
+        __syncthreads();
     }
-    __syncthreads();
     if constexpr (NESTED) {
         const int P = dv.P, top_p = dv.top_p;
         if (row0 < P) {
@@ -219,8 +249,7 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
                 const double nr = rn_sh[j];
                 sc = score_mode == 1 ? p : (nr == 0.0 ? 0.0 : p / nr);
             }
-            sc_sh[j] = sc;
-            dv.scores[(size_t)u * C + j] = sc;
+            sc_sh[j] = sc;        // (goes to dv.scores at the end: a store here would be waited for at the next barrier)
         }
     };
     if constexpr (NESTED) {
@@ -264,8 +293,8 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
     // pruned clusters have n_sh = 0 and take no part
     const int n_live = topk_rank(sc_sh, n_sh, C, k, rank_sh, ids_sh, cnt_sh, off_sh, tk_sh);
     const int n_ids = min(k, n_live);
+    int run = 0;
     if (tid < 64) {      // page offsets of the selected clusters: running sums of their sizes, 64 at a time
-        int run = 0;
         for (int i0 = 0; i0 < n_ids; i0 += 64) {
             const int i = i0 + tid;
             const int sz = i < n_ids ? n_sh[ids_sh[i]] - wcnt_sh[ids_sh[i]] : 0;
@@ -278,14 +307,17 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
             if (i < n_ids) off_sh[i + 1] = run + incl;
             run += __shfl(incl, 63, 64);
         }
-        if (tid == 0) {
-            off_sh[0] = 0;
-            dv.n_ids[u] = n_ids;
-            if (write_pages) dv.n_sel[u] = run + (n_frames - w0);
-        }
+        if (tid == 0) off_sh[0] = 0;
+    }
+    __syncthreads();
+    // Everything this launch leaves in global memory is stored from here on, after the last barrier: a barrier
+    // waits for the acknowledgement of the wavefront's outstanding stores (1-2 us for lines that are not in L2).
+    if (tid == 0) {
+        dv.n_ids[u] = n_ids;
+        if (write_pages) dv.n_sel[u] = run + (n_frames - w0);
     }
     for (int i = tid; i < k; i += BLK) dv.ids[(size_t)u * k + i] = i < n_ids ? ids_sh[i] : -1;
-    __syncthreads();
+    if (tid < C) dv.scores[(size_t)u * C + tid] = sc_sh[tid];
     if (!write_pages) return;     // host tier: the host maps clusters to cache slots
     // page list: clusters in selection order, member frames ascending
     int *sel = dv.sel_pages + (size_t)u * dv.F;

@@ -275,10 +275,19 @@ __global__ __launch_bounds__(kRetrBlock) void k_retrieve(DeviceView dv, int u0, 
                 pv[i] = group16_sum(pv[i]);
             }
         }
-#pragma unroll
-        for (int i = 0; i < RPF; ++i) {
-            const int j = row0 + RPP * i;
-            if (j < C) finish_row(j, pv[i], true);
+        {   // lane i of the group finishes prefetched row i: one pass through the division instead of RPF (the
+            // workgroup's sixteen wavefronts share four SIMDs, so every instruction of a phase counts four times)
+            static_assert(RPF == 2, "the select below is written for two prefetched passes");
+            const int j = row0 + RPP * lr;
+            if (lr < RPF && j < C) {
+                const double p = lr == 0 ? pv[0] : pv[1];
+                double sc = -INFINITY;
+                if (n_sh[j] > 0) {
+                    const double nr = rn_sh[j];
+                    sc = score_mode == 1 ? p : (nr == 0.0 ? 0.0 : p / nr);
+                }
+                sc_sh[j] = sc;
+            }
         }
         for (int j = row0 + RPP * RPF; j < C; j += RPP) {
             const double *rj = r + (size_t)j * D + lr * EPL;

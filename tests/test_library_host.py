@@ -90,3 +90,32 @@ def test_null_arguments_do_not_crash():
     assert lib.mosaic_ingest_join(None) == binding.EINVAL
     assert lib.mosaic_decode_step(None, 0, None, 1, None, None) == binding.EINVAL
     assert isinstance(lib.mosaic_last_error(None), bytes)
+
+
+def test_running_mean_division_scheme_is_correctly_rounded():
+    """Eq. 3's division by n + 1 in the register-table assignment kernel: y = RN(1 / b) once, then per channel
+    q = RN(x y) and two residual corrections q <- RN(q + RN(x - b q) y), each residual exact in a fused
+    multiply-add.  Emulated here with exact rational arithmetic (one rounding per operation, as the hardware's
+    FMA): the result must be the correctly rounded x / b, i.e. what the oracle's plain division returns, also
+    for quotients that lie next to a rounding boundary."""
+    import math
+    import random
+    from fractions import Fraction as Fr
+
+    def fma(a, b, c):
+        return float(Fr(a) * Fr(b) + Fr(c))
+
+    rng = random.Random(7)
+    for t in range(20000):
+        b = float(rng.randint(1, 1 << rng.randint(1, 24)))
+        x = math.ldexp(1.0 + rng.getrandbits(52) / 2.0 ** 52, rng.randint(-60, 60)) * rng.choice((-1, 1))
+        if t % 2 == 0:      # x ~ b * (q +- half an ulp of q)
+            q = math.ldexp(1.0 + rng.getrandbits(52) / 2.0 ** 52, rng.randint(-20, 20))
+            x = float(Fr(q) * Fr(b) + Fr(math.ulp(q)) * Fr(b) * Fr(rng.choice((1, -1)), 2)
+                      * Fr(rng.randint(999999, 1000001), 1000000))
+        want = float(Fr(x) / Fr(b))
+        y = float(Fr(1) / Fr(b))
+        q = x * y
+        q = fma(fma(-b, q, x), y, q)
+        q = fma(fma(-b, q, x), y, q)
+        assert q == want, (x, b, q, want)

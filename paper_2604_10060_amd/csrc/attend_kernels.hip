@@ -152,8 +152,8 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, i
 
 // Weighted sum of one unit's split partials for 32 output channels of one row tile
 // (the per-thread share): log-sum-exp weights into w_sh, row maxima and normalisers
-// into M_sh / L_sh, partial sums into acc.  RMAX = 8 or 16 bounds the valid rows of the
-// tile (a decode step has G <= 8 rows), MAXS the splits handled.  A thread keeps 128
+// into M_sh / L_sh, partial sums into acc.  The workgroup takes rows rbase .. rbase + nr - 1 of the
+// tile; RMAX = 4, 8 or 16 bounds nr, MAXS the splits handled.  A thread keeps 128
 // partial values in registers per pass, i.e. 64 splits of 16 rows or 128 splits of 8
 // rows; MAXS beyond that (a unit that retrieved far more than the others of its launch)
 // takes further passes, each one more memory round trip.
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(kBlock) void k_attend_valu(DeviceView dv, int u0, i
 // Split and row indices are clamped instead of tested, so the loads are unconditional
 // (straight-line code); what a clamped load brings is never used.
 template <int D, int MAXS, int RMAX>
-__device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t e0, int n_splits, int rows, int dg,
+__device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t e0, int n_splits, int rbase, int nr, int dg,
                                                    float (*w_sh)[kRowTile], float (*pm)[kRowTile],
                                                    float (*pl)[kRowTile], float (*px)[kRowTile], float *M_sh,
                                                    float *L_sh, float *X_sh, float (&acc)[kRowTile]) {
@@ -177,7 +177,7 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
             const int s = min(s0 + sg + 8 * i, max(n_splits - 1, 0));
             const float *po = dv.part_o + (e0 + s) * kRowTile * D + dg * 32 + col;
 #pragma unroll
-            for (int r = 0; r < RMAX; ++r) v[i][r] = po[(size_t)min(r, rows - 1) * D];
+            for (int r = 0; r < RMAX; ++r) v[i][r] = po[(size_t)(rbase + min(r, nr - 1)) * D];
         }
     };
     load_pass(0);
@@ -233,7 +233,7 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
             const int s = s0 + sg + 8 * i;
             if (s < n_splits) {
 #pragma unroll
-                for (int r = 0; r < RMAX; ++r) acc[r] += w_sh[s][r] * v[i][r];
+                for (int r = 0; r < RMAX; ++r) acc[r] += w_sh[s][min(rbase + r, kRowTile - 1)] * v[i][r];
             }
         }
     }
@@ -246,10 +246,17 @@ __device__ __forceinline__ void combine_accumulate(const DeviceView &dv, size_t 
 template <typename E, int D>
 __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0, int n_units, int Tq,
                                                            int B, int uniform_S, E *out, float *lse) {
-    const int dg = blockIdx.x, tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc, NT = gridDim.y;
+    // grid.x = (D / 32) * RS: RS workgroups share a tile's rows (a decode step's heaviest unit has up to 256
+    // partials to merge, and the launch lasts as long as that unit's workgroups: with its rows shared by two
+    // workgroups each thread reads half as much, all of it in one pass)
+    constexpr int DG = D / 32;
+    const int dg = blockIdx.x % DG, rs = blockIdx.x / DG, RS = gridDim.x / DG;
+    const int tile = blockIdx.y, uc = blockIdx.z, u = u0 + uc, NT = gridDim.y;
     const int tid = threadIdx.x;
     const int G = dv.G, Hq = dv.Hq, lc = uc / dv.Hkv, h = u % dv.Hkv, R = Tq * G;
     const int rows = min(kRowTile, R - tile * kRowTile);
+    const int rper = (rows + RS - 1) / RS, rbase = rs * rper, nr = min(rper, rows - rbase);
+    if (nr <= 0) return;                         // block-uniform: no barrier reached yet
     // uniform_S > 0: every unit has exactly that many splits (the fused decode step); else the
     // splits were shared out by retrieved size and split_slot() says how
     SplitSlot slot{uc, 0, uniform_S, uc * uniform_S};
@@ -262,27 +269,36 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
     __shared__ float red[8][kRowTile][33];
     const int sg = tid / 32, col = tid % 32;
     float acc[kRowTile];
-    if (rows <= 8) {             // block-uniform choices
-        if (n_splits <= 16) combine_accumulate<D, 16, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
-        else if (n_splits <= 32) combine_accumulate<D, 32, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
-        else if (n_splits <= 64) combine_accumulate<D, 64, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
-        else if (n_splits <= 128) combine_accumulate<D, 128, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
-        else combine_accumulate<D, kMaxUnitSplits, 8>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+#define MOSAIC_COMBINE(MAXS, RMAX) \
+    combine_accumulate<D, MAXS, RMAX>(dv, e0, n_splits, rbase, nr, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc)
+    if (rper <= 4) {             // block-uniform choices
+        if (n_splits <= 32) MOSAIC_COMBINE(32, 4);
+        else if (n_splits <= 64) MOSAIC_COMBINE(64, 4);
+        else if (n_splits <= 128) MOSAIC_COMBINE(128, 4);
+        else MOSAIC_COMBINE(kMaxUnitSplits, 4);
+    } else if (rper <= 8) {
+        if (n_splits <= 16) MOSAIC_COMBINE(16, 8);
+        else if (n_splits <= 32) MOSAIC_COMBINE(32, 8);
+        else if (n_splits <= 64) MOSAIC_COMBINE(64, 8);
+        else if (n_splits <= 128) MOSAIC_COMBINE(128, 8);
+        else MOSAIC_COMBINE(kMaxUnitSplits, 8);
     } else {
-        if (n_splits <= 16) combine_accumulate<D, 16, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
-        else if (n_splits <= 64) combine_accumulate<D, 64, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
-        else combine_accumulate<D, kMaxUnitSplits, 16>(dv, e0, n_splits, rows, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc);
+        if (n_splits <= 16) MOSAIC_COMBINE(16, 16);
+        else if (n_splits <= 64) MOSAIC_COMBINE(64, 16);
+        else MOSAIC_COMBINE(kMaxUnitSplits, 16);
     }
+#undef MOSAIC_COMBINE
 #pragma unroll
     for (int r = 0; r < kRowTile; ++r) red[sg][r][col] = acc[r];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const int r = sg + 8 * j;
-        if (r >= rows) continue;
+        const int rl = sg + 8 * j;                    // row inside this workgroup's share
+        if (rl >= nr) continue;
+        const int r = rbase + rl;
         float o = 0.f;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) o += red[q][r][col];
+        for (int q = 0; q < 8; ++q) o += red[q][rl][col];
         // Lr: normaliser of the output (the weights the value contraction used, bf16-rounded in the
         // MFMA kernels); Xr: the same sum over the unrounded fp32 weights, for the log-sum-exp
         float Lr = L_sh[r], Xr = X_sh[r], Mr = M_sh[r];
@@ -327,7 +343,9 @@ hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int 
     const int us = uniform ? n_splits : 0;
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
     const int B = n_units * n_splits;
-    dim3 grid(dv.D / 32, NT, n_units);
+    // one row tile of more than four rows (a decode step): two workgroups share its rows
+    const int RS = NT == 1 && Tq * dv.G > 4 ? 2 : 1;
+    dim3 grid(dv.D / 32 * RS, NT, n_units);
     if (dv.esize == 4) {
         if (dv.D == 64) k_attend_combine<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, us, (float *)out, lse);
         else k_attend_combine<float, 128><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, us, (float *)out, lse);

@@ -271,7 +271,15 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
     float acc[kRowTile];
 #define MOSAIC_COMBINE(MAXS, RMAX) \
     combine_accumulate<D, MAXS, RMAX>(dv, e0, n_splits, rbase, nr, dg, w_sh, pm, pl, px, M_sh, L_sh, X_sh, acc)
-    if (rper <= 4) {             // block-uniform choices
+    if (rper <= 1) {             // block-uniform choices
+        if (n_splits <= 64) MOSAIC_COMBINE(64, 1);
+        else if (n_splits <= 128) MOSAIC_COMBINE(128, 1);
+        else MOSAIC_COMBINE(kMaxUnitSplits, 1);
+    } else if (rper <= 2) {
+        if (n_splits <= 64) MOSAIC_COMBINE(64, 2);
+        else if (n_splits <= 128) MOSAIC_COMBINE(128, 2);
+        else MOSAIC_COMBINE(kMaxUnitSplits, 2);
+    } else if (rper <= 4) {
         if (n_splits <= 32) MOSAIC_COMBINE(32, 4);
         else if (n_splits <= 64) MOSAIC_COMBINE(64, 4);
         else if (n_splits <= 128) MOSAIC_COMBINE(128, 4);
@@ -343,8 +351,10 @@ hipError_t launch_attend_combine(const DeviceView &dv, int u0, int n_units, int 
     const int us = uniform ? n_splits : 0;
     const int NT = (Tq * dv.G + kRowTile - 1) / kRowTile;
     const int B = n_units * n_splits;
-    // one row tile of more than four rows (a decode step): two workgroups share its rows
-    const int RS = NT == 1 && Tq * dv.G > 4 ? 2 : 1;
+    // One row tile (a decode step) of a few units: up to eight workgroups share a tile's rows, as long as the launch
+    // stays within about two workgroups per CU (per-layer launch of config 2: 1075 -> 1048 / 1033 / 1027 us per step
+    // with 2 / 4 / 8; the all-layers launch, 112 units, is left alone: 542 -> 562 us with 8).
+    const int RS = NT == 1 ? std::max(1, std::min(8, 512 / (n_units * (dv.D / 32)))) : 1;
     dim3 grid(dv.D / 32 * RS, NT, n_units);
     if (dv.esize == 4) {
         if (dv.D == 64) k_attend_combine<float, 64><<<grid, kBlock, 0, s>>>(dv, u0, n_units, Tq, B, us, (float *)out, lse);

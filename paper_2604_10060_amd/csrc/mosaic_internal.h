@@ -312,6 +312,32 @@ __device__ __forceinline__ long long ld_agent(const long long *p) { return __hip
 template <bool BY_UNIT>
 __device__ __forceinline__ SplitSlot split_slot(const int *n_sel_call, int n_units, int B, int key) {
     const int lane = threadIdx.x % 64;
+    if (n_units <= 8) {
+        // A layer's few units (the per-layer decode chain, where this sits at the head of two launches' dependent
+        // chains): sizes, shares and offsets as wave-uniform scalars read from the first lanes, one 32-bit
+        // division per lane where the product fits, no cross-lane scans.  Same shares as the general path below.
+        const int ns = lane < n_units ? n_sel_call[lane] : 0;
+        long long total = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) total += __builtin_amdgcn_readlane(ns, i);
+        int want = 0;
+        if (ns > 0) {
+            const long long prod = (long long)(B - n_units) * ns;      // total >= ns > 0 here
+            want = 1 + (prod < (1ll << 32) && total < (1ll << 32) ? (int)((unsigned int)prod / (unsigned int)total)
+                                                                  : (int)(prod / total));
+            want = min(want, kMaxUnitSplits);
+        }
+        SplitSlot r{-1, 0, 0, 0};
+        int run = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int w = __builtin_amdgcn_readlane(want, i);
+            const bool hit = BY_UNIT ? (i == key) : (key >= run && key < run + w);
+            if (hit && r.uc < 0 && i < n_units) { r.uc = i; r.S = w; r.base = run; r.split = BY_UNIT ? 0 : key - run; }
+            run += w;
+        }
+        return r;
+    }
     long long total = 0;
     for (int i = lane; i < n_units; i += 64) total += n_sel_call[i];
 #pragma unroll

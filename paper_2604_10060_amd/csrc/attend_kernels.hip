@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kBlock) void k_attend_combine(DeviceView dv, int u0
     if (nr <= 0) return;                         // block-uniform: no barrier reached yet
     // uniform_S > 0: every unit has exactly that many splits (the fused decode step); else the
     // splits were shared out by retrieved size and split_slot() says how
-    SplitSlot slot{uc, 0, uniform_S, uc * uniform_S};
+    SplitSlot slot{uc, 0, uniform_S, uc * uniform_S, 0};
     if (uniform_S <= 0) slot = split_slot<true>(dv.n_sel + u0, n_units, B, uc);
     const int n_splits = slot.S;                 // 0 if the unit retrieved nothing
     const size_t e0 = (size_t)slot.base * NT + (size_t)tile * n_splits;

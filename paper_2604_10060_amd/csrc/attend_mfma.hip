@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_attend_decode_mfma(DeviceView dv,
     for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m = -INFINITY, l = 0.f, lx = 0.f;
 
-    const int NC = __builtin_amdgcn_readfirstlane(dv.n_sel[u]) * cpp;
+    const int NC = __builtin_amdgcn_readfirstlane(slot.n) * cpp;
     const int n_my = __builtin_amdgcn_readfirstlane(first < NC ? (NC - first + stride - 1) / stride : 0);
 
     // The page id of a chunk is read (a wave-uniform scalar load) one step before the

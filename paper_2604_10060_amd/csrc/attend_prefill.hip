@@ -117,7 +117,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void k_attend_prefill_mfm
     // the page list was written by an earlier launch and is read-only here: constant address space, so
     // that a wave-uniform read of it is a scalar load
     const cint_ptr sel = (cint_ptr)(dv.sel_pages + (size_t)u * F);
-    const int NC = __builtin_amdgcn_readfirstlane(dv.n_sel[u]) * cpp;
+    const int NC = __builtin_amdgcn_readfirstlane(slot.n) * cpp;
     const int cps = (NC + n_splits - 1) / n_splits;
     const int c0 = __builtin_amdgcn_readfirstlane(split * cps);
     const int c1 = __builtin_amdgcn_readfirstlane(min(NC, c0 + cps));

@@ -294,6 +294,7 @@ struct SplitSlot {
     int split;   // split index within the unit
     int S;       // number of splits of the unit
     int base;    // first split slot of the unit (partials are indexed by slot)
+    int n;       // the unit's retrieved size (n_sel), so that the caller need not load it again
 };
 
 // Agent-scope (write-through / cache-bypassing) accesses for values that one workgroup publishes and
@@ -327,13 +328,16 @@ __device__ __forceinline__ SplitSlot split_slot(const int *n_sel_call, int n_uni
                                                                   : (int)(prod / total));
             want = min(want, kMaxUnitSplits);
         }
-        SplitSlot r{-1, 0, 0, 0};
+        SplitSlot r{-1, 0, 0, 0, 0};
         int run = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int w = __builtin_amdgcn_readlane(want, i);
             const bool hit = BY_UNIT ? (i == key) : (key >= run && key < run + w);
-            if (hit && r.uc < 0 && i < n_units) { r.uc = i; r.S = w; r.base = run; r.split = BY_UNIT ? 0 : key - run; }
+            if (hit && r.uc < 0 && i < n_units) {
+                r.uc = i; r.S = w; r.base = run; r.split = BY_UNIT ? 0 : key - run;
+                r.n = __builtin_amdgcn_readlane(ns, i);
+            }
             run += w;
         }
         return r;
@@ -342,7 +346,7 @@ __device__ __forceinline__ SplitSlot split_slot(const int *n_sel_call, int n_uni
     for (int i = lane; i < n_units; i += 64) total += n_sel_call[i];
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) total += __shfl_xor(total, o, 64);
-    SplitSlot r{-1, 0, 0, 0};
+    SplitSlot r{-1, 0, 0, 0, 0};
     int run = 0;
     for (int i0 = 0; i0 < n_units; i0 += 64) {
         const int i = i0 + lane;
@@ -366,6 +370,7 @@ __device__ __forceinline__ SplitSlot split_slot(const int *n_sel_call, int n_uni
             r.uc = i0 + src;
             r.S = __shfl(want, src, 64);
             r.base = __shfl(excl, src, 64);
+            r.n = __shfl(ns, src, 64);
             r.split = BY_UNIT ? 0 : key - r.base;
         }
         run += __shfl(incl, 63, 64);
